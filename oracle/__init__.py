@@ -1,0 +1,201 @@
+"""CPU oracle for the conv-LIF layer (per-step, TAC, TAC-TP).
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, by the smoke check and by the
+CPU-baseline leg of the benchmark.  The GPU library never imports or calls it.
+
+The arithmetic lives in ``tac_oracle.c`` (plain C, double precision, seven-loop
+convolution, explicit LIF recurrences as in Algorithms 1 and 2 of the paper);
+this module only marshals numpy arrays into it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tac_oracle.c")
+_LIB = os.path.join(_HERE, "libtac_oracle.so")
+
+PER_STEP, TAC, TAC_TP = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile tac_oracle.c with gcc (no fast-math; OpenMP only over the batch loop)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("T", "B", "Cin", "H", "W", "Cout", "kh", "kw", "stride", "pad", "K",
+                 "pool2", "round_a_bf16", "nthreads")] + \
+               [("beta", ctypes.c_double), ("theta", ctypes.c_double)]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(_Desc)
+        vp = ctypes.c_void_p
+        for name in ("oracle_per_step", "oracle_tac", "oracle_tac_tp"):
+            f = getattr(lib, name)
+            f.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
+            f.restype = ctypes.c_int
+        lib.oracle_neurons.argtypes = [dp, ctypes.c_int, vp, vp, vp, vp, ctypes.c_int64, vp, vp, vp, vp]
+        lib.oracle_neurons.restype = ctypes.c_int
+        lib.oracle_conv2d.argtypes = [vp, vp, vp, vp] + [ctypes.c_int] * 10
+        lib.oracle_conv2d.restype = None
+        lib.oracle_round_bf16.argtypes = [ctypes.c_double]
+        lib.oracle_round_bf16.restype = ctypes.c_double
+        lib.oracle_decay_weights.argtypes = [ctypes.c_double, ctypes.c_int, vp]
+        lib.oracle_decay_weights.restype = None
+        lib.oracle_avgpool2.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int]
+        lib.oracle_avgpool2.restype = None
+        lib.oracle_max_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def max_threads() -> int:
+    return int(_load().oracle_max_threads())
+
+
+def round_bf16(x):
+    """Nearest-even rounding to bfloat16, elementwise, returned as float64."""
+    lib = _load()
+    a = np.asarray(x, dtype=np.float64)
+    return np.vectorize(lambda v: lib.oracle_round_bf16(float(v)), otypes=[np.float64])(a)
+
+
+def decay_weights(beta: float, K: int) -> np.ndarray:
+    """w[j] = beta^(K-1-j) (Eq. 2)."""
+    w = np.zeros(K, dtype=np.float64)
+    _load().oracle_decay_weights(float(beta), int(K), _ptr(w))
+    return w
+
+
+def avgpool2(x: np.ndarray) -> np.ndarray:
+    """2x2 mean pool, stride 2, over the last two axes."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    H2, W2 = x.shape[-2:]
+    assert H2 % 2 == 0 and W2 % 2 == 0
+    out = np.zeros(x.shape[:-2] + (H2 // 2, W2 // 2), dtype=np.float64)
+    _load().oracle_avgpool2(_ptr(x), _ptr(out), int(np.prod(x.shape[:-2], dtype=np.int64)), H2 // 2, W2 // 2)
+    return out
+
+
+def conv2d(x: np.ndarray, w: np.ndarray, bias=None, stride: int = 1, pad: int = 1, nthreads: int = 1) -> np.ndarray:
+    """Zero-padded cross-correlation, x[B,Cin,H,W], w[Cout,Cin,kh,kw] -> [B,Cout,Ho,Wo] (float64)."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    B, Cin, H, W = x.shape
+    Cout, Cin2, kh, kw = w.shape
+    assert Cin == Cin2
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float64)
+        assert bias.shape == (Cout,)
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    y = np.zeros((B, Cout, Ho, Wo), dtype=np.float64)
+    _load().oracle_conv2d(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), B, Cin, H, W, Cout, kh, kw, stride, pad, nthreads)
+    return y
+
+
+def _desc(spikes, weight, K, beta, theta, stride, pad, pool2, round_a_bf16, nthreads):
+    T, B, Cin, Hs, Ws = spikes.shape
+    Cout, Cin2, kh, kw = weight.shape
+    if Cin != Cin2:
+        raise ValueError("channel mismatch")
+    if pool2:
+        if Hs % 2 or Ws % 2:
+            raise ValueError("pool2 needs even input size")
+        H, W = Hs // 2, Ws // 2
+    else:
+        H, W = Hs, Ws
+    d = _Desc(T=T, B=B, Cin=Cin, H=H, W=W, Cout=Cout, kh=kh, kw=kw, stride=stride, pad=pad, K=K,
+              pool2=int(bool(pool2)), round_a_bf16=int(bool(round_a_bf16)), nthreads=int(nthreads),
+              beta=float(beta), theta=float(theta))
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    return d, Ho, Wo
+
+
+def conv_lif(spikes, weight, bias=None, *, K=1, beta, theta, mode, stride=1, pad=1, v0=None,
+             pool2=False, round_a_bf16=False, nthreads=1):
+    """One conv-LIF layer over all T input frames.
+
+    spikes uint8 [T,B,Cin,H,W] of 0/1 (unpooled size when pool2); weight [Cout,Cin,kh,kw];
+    mode PER_STEP / TAC / TAC_TP.  Returns (out_spikes uint8 [T_out,B,Cout,Ho,Wo],
+    v_pre float64 same shape (membrane before reset at every LIF step),
+    v_final float64 [B,Cout,Ho,Wo]).
+    """
+    lib = _load()
+    spikes = np.ascontiguousarray(spikes, dtype=np.uint8)
+    if spikes.max(initial=0) > 1:
+        raise ValueError("spikes must be 0/1")
+    weight = np.ascontiguousarray(weight, dtype=np.float64)
+    d, Ho, Wo = _desc(spikes, weight, K, beta, theta, stride, pad, pool2, round_a_bf16, nthreads)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float64)
+    if v0 is not None:
+        v0 = np.ascontiguousarray(v0, dtype=np.float64)
+        assert v0.shape == (d.B, d.Cout, Ho, Wo)
+    T_out = d.T // K if mode == TAC else d.T
+    if mode != PER_STEP and d.T % K:
+        raise ValueError("K must divide T")
+    out_s = np.zeros((T_out, d.B, d.Cout, Ho, Wo), dtype=np.uint8)
+    v_pre = np.zeros((T_out, d.B, d.Cout, Ho, Wo), dtype=np.float64)
+    v_fin = np.zeros((d.B, d.Cout, Ho, Wo), dtype=np.float64)
+    fn = {PER_STEP: lib.oracle_per_step, TAC: lib.oracle_tac, TAC_TP: lib.oracle_tac_tp}[mode]
+    rc = fn(ctypes.byref(d), _ptr(spikes), _ptr(weight), _ptr(bias), _ptr(v0), _ptr(out_s), _ptr(v_pre), _ptr(v_fin))
+    if rc:
+        raise ValueError("oracle rejected the layer description (code %d)" % rc)
+    return out_s, v_pre, v_fin
+
+
+def conv_lif_neurons(spikes, weight, bias=None, *, idx, K=1, beta, theta, mode, stride=1, pad=1,
+                     v0=None, pool2=False, round_a_bf16=False, nthreads=1):
+    """The same layer followed at single output neurons idx[n,4] = (b, co, oy, ox).
+
+    Returns (out_spikes uint8 [T_out,n], v_pre float64 [T_out,n], v_final float64 [n]).
+    """
+    lib = _load()
+    spikes = np.ascontiguousarray(spikes, dtype=np.uint8)
+    weight = np.ascontiguousarray(weight, dtype=np.float64)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    assert idx.ndim == 2 and idx.shape[1] == 4
+    n = idx.shape[0]
+    d, Ho, Wo = _desc(spikes, weight, K, beta, theta, stride, pad, pool2, round_a_bf16, nthreads)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float64)
+    if v0 is not None:
+        v0 = np.ascontiguousarray(v0, dtype=np.float64)
+        assert v0.shape == (n,)
+    if mode != PER_STEP and d.T % K:
+        raise ValueError("K must divide T")
+    T_out = d.T // K if mode == TAC else d.T
+    out_s = np.zeros((T_out, n), dtype=np.uint8)
+    v_pre = np.zeros((T_out, n), dtype=np.float64)
+    v_fin = np.zeros((n,), dtype=np.float64)
+    rc = lib.oracle_neurons(ctypes.byref(d), int(mode), _ptr(spikes), _ptr(weight), _ptr(bias), _ptr(v0),
+                            n, _ptr(idx), _ptr(out_s), _ptr(v_pre), _ptr(v_fin))
+    if rc:
+        raise ValueError("oracle rejected the request (code %d)" % rc)
+    return out_s, v_pre, v_fin

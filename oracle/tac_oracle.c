@@ -1,0 +1,352 @@
+/*
+ * CPU oracle for the conv-LIF layer in its three temporal modes.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT A PRODUCT PATH.  It is a plain, slow,
+ * double-precision restatement of what the paper defines, used only to check
+ * the GPU library and to report a CPU baseline.  It shares no code with the
+ * GPU library and is never called by it.
+ *
+ * What it computes (paper notation: T timesteps, B batch, K group size,
+ * beta membrane decay, theta = V_th threshold, S_t binary input frame,
+ * W conv kernel, A_k aggregate of group k, Y_k = Conv2d(A_k, W), V membrane):
+ *
+ *   per-step  (Sec. 3.1, Eq. 1, with the reset applied as in Algorithms 1/2):
+ *             for every t:  Y = Conv2d(S_t, W);  V <- beta V + Y;
+ *                           S_out = [V >= theta];  V <- V - S_out theta
+ *   TAC       (Definition 1 / Eq. 2 and Algorithm 1):
+ *             for every group k:  A_k = sum_j beta^(K-1-j) S_{kK+j};
+ *                           Y_k = Conv2d(A_k, W);  V <- beta^K V + Y_k;
+ *                           S_out = [V >= theta];  V <- V - S_out theta
+ *   TAC-TP    (Algorithm 2):  same A_k and Y_k, then K LIF steps that all
+ *                           read the same Y_k:  V <- beta V + Y_k; spike; reset
+ *
+ * Conv2d is the deep-learning cross-correlation (no kernel flip) with zero
+ * padding, written as seven nested loops.  A bias, when given, is added once
+ * per convolution.  The spike test is V >= theta.  The reset is the
+ * subtractive one of the algorithms (subtracted immediately, so it decays with
+ * the membrane at the next step).
+ *
+ * Every routine also records the membrane potential BEFORE the reset at each
+ * LIF step, because that is the quantity the threshold looked at.
+ *
+ * Parity status: the per-step, TAC and TAC-TP recurrences, the aggregation
+ * weights, the convolution, the pooling and the bf16 rounding helper are each
+ * pinned by CPU tests (closed forms, a hand-worked example, a library
+ * convolution, exact rational brute force).  The paper's accuracy tables are
+ * parity unpinned: they need datasets and trained weights.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct {
+  int32_t T, B, Cin, H, W;     /* input spikes S[T][B][Cin][H][W], values 0/1            */
+  int32_t Cout, kh, kw;        /* kernel W[Cout][Cin][kh][kw]                            */
+  int32_t stride, pad;
+  int32_t K;                   /* group size (ignored by the per-step routine)           */
+  int32_t pool2;               /* 1: S is [T][B][Cin][2H][2W]; a 2x2 mean pool precedes the layer */
+  int32_t round_a_bf16;        /* 1: round every A_k element to bfloat16 (nearest even)  */
+  int32_t nthreads;            /* OpenMP threads over the batch loop; <=1: serial        */
+  double beta, theta;
+} oracle_desc_t;
+
+int oracle_out_h(const oracle_desc_t* d) { return (d->H + 2 * d->pad - d->kh) / d->stride + 1; }
+int oracle_out_w(const oracle_desc_t* d) { return (d->W + 2 * d->pad - d->kw) / d->stride + 1; }
+
+/* Round a double to the nearest bfloat16 (8 significand bits), ties to even.
+ * Done on the float32 bit pattern: the inputs this is used on (short sums of
+ * powers of beta) are first rounded to float32, as the 16-bit format is
+ * defined as the upper half of a float32. */
+double oracle_round_bf16(double x) {
+  float f = (float)x;
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  if ((u & 0x7f800000u) == 0x7f800000u) return (double)f; /* inf / nan unchanged */
+  uint32_t lsb = (u >> 16) & 1u;
+  u += 0x7fffu + lsb;
+  u &= 0xffff0000u;
+  memcpy(&f, &u, 4);
+  return (double)f;
+}
+
+/* Aggregation weights of Eq. 2: w[j] = beta^(K-1-j); the newest frame has weight 1. */
+void oracle_decay_weights(double beta, int K, double* w) {
+  for (int j = 0; j < K; ++j) {
+    double p = 1.0;
+    for (int e = 0; e < K - 1 - j; ++e) p *= beta;
+    w[j] = p;
+  }
+}
+
+/* 2x2 mean pool with stride 2: X[N][2H][2W] -> P[N][H][W]. */
+void oracle_avgpool2(const double* X, double* P, int64_t N, int H, int W) {
+  for (int64_t n = 0; n < N; ++n)
+    for (int y = 0; y < H; ++y)
+      for (int x = 0; x < W; ++x) {
+        const double* r0 = X + (n * 2 * H + 2 * y) * (int64_t)(2 * W) + 2 * x;
+        const double* r1 = r0 + 2 * W;
+        P[(n * H + y) * (int64_t)W + x] = 0.25 * (r0[0] + r0[1] + r1[0] + r1[1]);
+      }
+}
+
+/* Y[B][Cout][Ho][Wo] = bias + cross-correlation of X[B][Cin][H][W] with
+ * Wt[Cout][Cin][kh][kw], zero padding `pad`, stride `stride`.  Seven loops. */
+void oracle_conv2d(const double* X, const double* Wt, const double* bias, double* Y,
+                   int B, int Cin, int H, int W, int Cout, int kh, int kw,
+                   int stride, int pad, int nthreads) {
+  const int Ho = (H + 2 * pad - kh) / stride + 1;
+  const int Wo = (W + 2 * pad - kw) / stride + 1;
+  (void)nthreads;
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(nthreads > 1 ? nthreads : 1) schedule(static)
+#endif
+  for (int b = 0; b < B; ++b)
+    for (int co = 0; co < Cout; ++co)
+      for (int oy = 0; oy < Ho; ++oy)
+        for (int ox = 0; ox < Wo; ++ox) {
+          double acc = bias ? bias[co] : 0.0;
+          for (int ci = 0; ci < Cin; ++ci)
+            for (int ky = 0; ky < kh; ++ky)
+              for (int kx = 0; kx < kw; ++kx) {
+                const int iy = oy * stride + ky - pad;
+                const int ix = ox * stride + kx - pad;
+                if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
+                acc += Wt[(((int64_t)co * Cin + ci) * kh + ky) * kw + kx] *
+                       X[(((int64_t)b * Cin + ci) * H + iy) * W + ix];
+              }
+          Y[(((int64_t)b * Cout + co) * Ho + oy) * Wo + ox] = acc;
+        }
+}
+
+/* Input frame t as doubles X[B][Cin][H][W] (after the optional 2x2 mean pool). */
+static void load_frame(const oracle_desc_t* d, const uint8_t* S, int t, double* X, double* tmp) {
+  const int64_t n_in = (int64_t)d->B * d->Cin;
+  if (d->pool2) {
+    const int64_t fr = n_in * (2 * d->H) * (int64_t)(2 * d->W);
+    for (int64_t i = 0; i < fr; ++i) tmp[i] = (double)S[(int64_t)t * fr + i];
+    oracle_avgpool2(tmp, X, n_in, d->H, d->W);
+  } else {
+    const int64_t fr = n_in * d->H * (int64_t)d->W;
+    for (int64_t i = 0; i < fr; ++i) X[i] = (double)S[(int64_t)t * fr + i];
+  }
+}
+
+/* Temporal aggregate of group k (Eq. 2): A = sum_j beta^(K-1-j) S_{kK+j}. */
+void oracle_aggregate(const oracle_desc_t* d, const uint8_t* S, int k, double* A, double* X, double* tmp) {
+  const int64_t n = (int64_t)d->B * d->Cin * d->H * d->W;
+  double* w = (double*)malloc(sizeof(double) * (size_t)d->K);
+  oracle_decay_weights(d->beta, d->K, w);
+  for (int64_t i = 0; i < n; ++i) A[i] = 0.0;
+  for (int j = 0; j < d->K; ++j) {
+    load_frame(d, S, k * d->K + j, X, tmp);
+    for (int64_t i = 0; i < n; ++i) A[i] += w[j] * X[i];
+  }
+  if (d->round_a_bf16)
+    for (int64_t i = 0; i < n; ++i) A[i] = oracle_round_bf16(A[i]);
+  free(w);
+}
+
+typedef struct { double *X, *tmp, *A, *Y, *V; int64_t n_out; } scratch_t;
+
+static int scratch_init(const oracle_desc_t* d, const double* v0, scratch_t* s) {
+  const int Ho = oracle_out_h(d), Wo = oracle_out_w(d);
+  const int64_t n_in = (int64_t)d->B * d->Cin * d->H * d->W;
+  s->n_out = (int64_t)d->B * d->Cout * Ho * Wo;
+  s->X = (double*)malloc(sizeof(double) * (size_t)n_in);
+  s->A = (double*)malloc(sizeof(double) * (size_t)n_in);
+  s->tmp = (double*)malloc(sizeof(double) * (size_t)n_in * (d->pool2 ? 4 : 1));
+  s->Y = (double*)malloc(sizeof(double) * (size_t)s->n_out);
+  s->V = (double*)malloc(sizeof(double) * (size_t)s->n_out);
+  if (!s->X || !s->A || !s->tmp || !s->Y || !s->V) return -1;
+  for (int64_t i = 0; i < s->n_out; ++i) s->V[i] = v0 ? v0[i] : 0.0;
+  return 0;
+}
+
+static void scratch_free(scratch_t* s, double* v_final) {
+  if (v_final) memcpy(v_final, s->V, sizeof(double) * (size_t)s->n_out);
+  free(s->X); free(s->A); free(s->tmp); free(s->Y); free(s->V);
+}
+
+static int check_desc(const oracle_desc_t* d, int need_k) {
+  if (d->T < 1 || d->B < 1 || d->Cin < 1 || d->H < 1 || d->W < 1 || d->Cout < 1) return -1;
+  if (d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0) return -1;
+  if (oracle_out_h(d) < 1 || oracle_out_w(d) < 1) return -1;
+  if (need_k && (d->K < 1 || d->T % d->K != 0)) return -2;
+  return 0;
+}
+
+/* Per-timestep layer: T convolutions, T LIF steps.  Written without A_k and
+ * without K so that "K = 1 equals per-step" is a test and not a tautology.
+ *   S      uint8 [T][B][Cin][H][W] (or the unpooled size when pool2)
+ *   Wt     [Cout][Cin][kh][kw], bias [Cout] or NULL, v0 [B][Cout][Ho][Wo] or NULL (zeros)
+ *   out_s  uint8 [T][B][Cout][Ho][Wo]; v_pre (may be NULL) same shape, V before reset
+ *   v_final (may be NULL) [B][Cout][Ho][Wo], V after the last reset            */
+int oracle_per_step(const oracle_desc_t* d, const uint8_t* S, const double* Wt, const double* bias,
+                    const double* v0, uint8_t* out_s, double* v_pre, double* v_final) {
+  int rc = check_desc(d, 0);
+  if (rc) return rc;
+  scratch_t s;
+  if (scratch_init(d, v0, &s)) return -3;
+  for (int t = 0; t < d->T; ++t) {
+    load_frame(d, S, t, s.X, s.tmp);
+    oracle_conv2d(s.X, Wt, bias, s.Y, d->B, d->Cin, d->H, d->W, d->Cout, d->kh, d->kw,
+                  d->stride, d->pad, d->nthreads);
+    for (int64_t i = 0; i < s.n_out; ++i) {
+      double v = d->beta * s.V[i] + s.Y[i];
+      const int fire = v >= d->theta;
+      if (v_pre) v_pre[(int64_t)t * s.n_out + i] = v;
+      out_s[(int64_t)t * s.n_out + i] = (uint8_t)fire;
+      if (fire) v -= d->theta;
+      s.V[i] = v;
+    }
+  }
+  scratch_free(&s, v_final);
+  return 0;
+}
+
+/* TAC (Algorithm 1): one convolution and one LIF step per group of K frames.
+ * out_s / v_pre hold T/K steps. */
+int oracle_tac(const oracle_desc_t* d, const uint8_t* S, const double* Wt, const double* bias,
+               const double* v0, uint8_t* out_s, double* v_pre, double* v_final) {
+  int rc = check_desc(d, 1);
+  if (rc) return rc;
+  scratch_t s;
+  if (scratch_init(d, v0, &s)) return -3;
+  double beta_K = 1.0;
+  for (int e = 0; e < d->K; ++e) beta_K *= d->beta;
+  for (int k = 0; k < d->T / d->K; ++k) {
+    oracle_aggregate(d, S, k, s.A, s.X, s.tmp);
+    oracle_conv2d(s.A, Wt, bias, s.Y, d->B, d->Cin, d->H, d->W, d->Cout, d->kh, d->kw,
+                  d->stride, d->pad, d->nthreads);
+    for (int64_t i = 0; i < s.n_out; ++i) {
+      double v = beta_K * s.V[i] + s.Y[i];
+      const int fire = v >= d->theta;
+      if (v_pre) v_pre[(int64_t)k * s.n_out + i] = v;
+      out_s[(int64_t)k * s.n_out + i] = (uint8_t)fire;
+      if (fire) v -= d->theta;
+      s.V[i] = v;
+    }
+  }
+  scratch_free(&s, v_final);
+  return 0;
+}
+
+/* TAC-TP (Algorithm 2): one convolution per group, then K LIF steps that all
+ * take the same Y_k as input current.  out_s / v_pre hold T steps. */
+int oracle_tac_tp(const oracle_desc_t* d, const uint8_t* S, const double* Wt, const double* bias,
+                  const double* v0, uint8_t* out_s, double* v_pre, double* v_final) {
+  int rc = check_desc(d, 1);
+  if (rc) return rc;
+  scratch_t s;
+  if (scratch_init(d, v0, &s)) return -3;
+  for (int k = 0; k < d->T / d->K; ++k) {
+    oracle_aggregate(d, S, k, s.A, s.X, s.tmp);
+    oracle_conv2d(s.A, Wt, bias, s.Y, d->B, d->Cin, d->H, d->W, d->Cout, d->kh, d->kw,
+                  d->stride, d->pad, d->nthreads);
+    for (int j = 0; j < d->K; ++j) {
+      const int64_t t = (int64_t)k * d->K + j;
+      for (int64_t i = 0; i < s.n_out; ++i) {
+        double v = d->beta * s.V[i] + s.Y[i];
+        const int fire = v >= d->theta;
+        if (v_pre) v_pre[t * s.n_out + i] = v;
+        out_s[t * s.n_out + i] = (uint8_t)fire;
+        if (fire) v -= d->theta;
+        s.V[i] = v;
+      }
+    }
+  }
+  scratch_free(&s, v_final);
+  return 0;
+}
+
+/* ---- the same three recurrences for a list of single output neurons ----
+ *
+ * At full benchmark sizes the whole tensor is too much work for this code, but
+ * one output neuron (b, co, oy, ox) depends only on its own receptive field
+ * over time, so it can be followed alone.  mode: 0 per-step, 1 TAC, 2 TAC-TP.
+ *   idx     int32 [n][4] = (b, co, oy, ox)
+ *   out_s   uint8 [T_out][n];  v_pre [T_out][n] (may be NULL);  v_final [n] (may be NULL)
+ *   v0      [n] initial membrane per listed neuron, or NULL (zeros)             */
+static double input_at(const oracle_desc_t* d, const uint8_t* S, int t, int b, int ci, int iy, int ix) {
+  if (d->pool2) {
+    const int H2 = 2 * d->H, W2 = 2 * d->W;
+    const uint8_t* p = S + ((((int64_t)t * d->B + b) * d->Cin + ci) * H2 + 2 * iy) * (int64_t)W2 + 2 * ix;
+    return 0.25 * ((double)p[0] + (double)p[1] + (double)p[W2] + (double)p[W2 + 1]);
+  }
+  return (double)S[((((int64_t)t * d->B + b) * d->Cin + ci) * d->H + iy) * (int64_t)d->W + ix];
+}
+
+/* Convolution output at one neuron, of the frame t0 (per-step, K1 = 1) or of
+ * the aggregate of the K1 frames t0 .. t0+K1-1. */
+static double conv_at(const oracle_desc_t* d, const uint8_t* S, const double* Wt, const double* bias,
+                      const double* w, int t0, int K1, int b, int co, int oy, int ox) {
+  double acc = bias ? bias[co] : 0.0;
+  for (int ci = 0; ci < d->Cin; ++ci)
+    for (int ky = 0; ky < d->kh; ++ky)
+      for (int kx = 0; kx < d->kw; ++kx) {
+        const int iy = oy * d->stride + ky - d->pad;
+        const int ix = ox * d->stride + kx - d->pad;
+        if (iy < 0 || iy >= d->H || ix < 0 || ix >= d->W) continue;
+        double a = 0.0;
+        for (int j = 0; j < K1; ++j) a += w[j] * input_at(d, S, t0 + j, b, ci, iy, ix);
+        if (d->round_a_bf16) a = oracle_round_bf16(a);
+        acc += Wt[(((int64_t)co * d->Cin + ci) * d->kh + ky) * d->kw + kx] * a;
+      }
+  return acc;
+}
+
+int oracle_neurons(const oracle_desc_t* d, int mode, const uint8_t* S, const double* Wt,
+                   const double* bias, const double* v0, int64_t n, const int32_t* idx,
+                   uint8_t* out_s, double* v_pre, double* v_final) {
+  int rc = check_desc(d, mode != 0);
+  if (rc) return rc;
+  if (mode < 0 || mode > 2) return -4;
+  const int K = mode == 0 ? 1 : d->K;
+  double* w = (double*)malloc(sizeof(double) * (size_t)K);
+  oracle_decay_weights(d->beta, K, w);
+  double beta_K = 1.0;
+  for (int e = 0; e < K; ++e) beta_K *= d->beta;
+  const int Ho = oracle_out_h(d), Wo = oracle_out_w(d);
+  int bad = 0;
+  (void)Ho; (void)Wo;
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(d->nthreads > 1 ? d->nthreads : 1) schedule(dynamic, 16)
+#endif
+  for (int64_t i = 0; i < n; ++i) {
+    const int b = idx[4 * i], co = idx[4 * i + 1], oy = idx[4 * i + 2], ox = idx[4 * i + 3];
+    if (b < 0 || b >= d->B || co < 0 || co >= d->Cout || oy < 0 || oy >= Ho || ox < 0 || ox >= Wo) {
+      bad = 1;
+      continue;
+    }
+    double v = v0 ? v0[i] : 0.0;
+    int64_t step = 0;
+    for (int k = 0; k < d->T / K; ++k) {
+      const double y = conv_at(d, S, Wt, bias, w, k * K, K, b, co, oy, ox);
+      const int nlif = (mode == 2) ? K : 1;
+      const double decay = (mode == 1) ? beta_K : d->beta;
+      for (int j = 0; j < nlif; ++j, ++step) {
+        v = decay * v + y;
+        const int fire = v >= d->theta;
+        if (v_pre) v_pre[step * n + i] = v;
+        out_s[step * n + i] = (uint8_t)fire;
+        if (fire) v -= d->theta;
+      }
+    }
+    if (v_final) v_final[i] = v;
+  }
+  free(w);
+  return bad ? -5 : 0;
+}
+
+int oracle_max_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}

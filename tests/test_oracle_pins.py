@@ -1,0 +1,314 @@
+"""Pins for the CPU oracle: every part of it is checked against something other than itself
+(closed forms, a hand-worked example, a library convolution, exact rational brute force),
+so that a dropped term, a wrong sign or index, or a transposed operand fails a test here.
+CPU only."""
+import itertools
+import json
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import PER_STEP, TAC, TAC_TP
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+# ------------------------------------------------------------------ convolution
+
+def test_conv_box_kernel_is_neighbourhood_sum():
+    # 3x3 all-ones kernel, one channel, zero padding: every output is the sum of the
+    # in-bounds 3x3 neighbourhood (textbook box filter with a zero border).
+    x = _rng(1).integers(0, 5, size=(2, 1, 6, 7)).astype(np.float64)
+    y = oracle.conv2d(x, np.ones((1, 1, 3, 3)), stride=1, pad=1)
+    xp = np.pad(x, ((0, 0), (0, 0), (1, 1), (1, 1)))
+    ref = sum(xp[:, :, dy:dy + 6, dx:dx + 7] for dy in range(3) for dx in range(3))
+    assert np.array_equal(y, ref)
+
+
+def test_conv_delta_kernel_identity_and_subsample():
+    x = _rng(2).standard_normal((2, 3, 8, 10))
+    w = np.zeros((3, 3, 3, 3))
+    for c in range(3):
+        w[c, c, 1, 1] = 1.0
+    assert np.array_equal(oracle.conv2d(x, w, stride=1, pad=1), x)
+    assert np.array_equal(oracle.conv2d(x, w, stride=2, pad=1), x[:, :, ::2, ::2])
+
+
+def test_conv_is_cross_correlation_not_flipped():
+    # a single off-centre tap shifts the image in a known direction
+    x = np.zeros((1, 1, 5, 5)); x[0, 0, 2, 2] = 1.0
+    w = np.zeros((1, 1, 3, 3)); w[0, 0, 0, 2] = 1.0      # tap at ky=0 (up), kx=2 (right)
+    y = oracle.conv2d(x, w, stride=1, pad=1)
+    # y[oy,ox] = x[oy+0-1, ox+2-1]  ->  the impulse appears at oy=3, ox=1
+    assert y[0, 0, 3, 1] == 1.0 and y.sum() == 1.0
+
+
+@pytest.mark.parametrize("stride,pad,kh,kw", [(1, 1, 3, 3), (2, 1, 3, 3), (1, 0, 3, 3), (2, 0, 1, 1), (1, 2, 5, 3)])
+def test_conv_matches_library_routine(stride, pad, kh, kw):
+    r = _rng(3)
+    x = r.standard_normal((3, 4, 9, 11)); w = r.standard_normal((5, 4, kh, kw)); b = r.standard_normal(5)
+    y = oracle.conv2d(x, w, b, stride=stride, pad=pad)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x), torch.from_numpy(w), torch.from_numpy(b),
+                                     stride=stride, padding=pad).numpy()
+    assert y.shape == ref.shape
+    assert np.abs(y - ref).max() < 1e-12
+
+
+def test_conv_linearity_identity():
+    # Sec. 3.2: W * (sum_i a_i X_i) = sum_i a_i (W * X_i)
+    r = _rng(4)
+    xs = r.integers(0, 2, size=(4, 2, 3, 7, 7)).astype(np.float64)
+    al = oracle.decay_weights(0.9, 4)
+    w = r.standard_normal((5, 3, 3, 3))
+    lhs = oracle.conv2d(np.tensordot(al, xs, axes=1), w)
+    rhs = sum(a * oracle.conv2d(x, w) for a, x in zip(al, xs))
+    assert np.abs(lhs - rhs).max() < 1e-12
+
+
+def test_conv_threads_do_not_change_result():
+    r = _rng(5)
+    x = r.standard_normal((4, 3, 6, 6)); w = r.standard_normal((4, 3, 3, 3))
+    assert np.array_equal(oracle.conv2d(x, w, nthreads=1), oracle.conv2d(x, w, nthreads=4))
+
+
+# ------------------------------------------------------------------ helpers
+
+@pytest.mark.parametrize("beta,K", [(0.9, 1), (0.9, 4), (0.5, 8), (0.25, 16)])
+def test_decay_weights_closed_form(beta, K):
+    w = oracle.decay_weights(beta, K)
+    assert w[-1] == 1.0                                      # newest frame has weight one
+    assert abs(w.sum() - (1 - beta ** K) / (1 - beta)) < 1e-13   # geometric sum
+    assert all(abs(w[j] - beta * w[j + 1]) < 1e-15 for j in range(K - 1))  # older = more decayed
+
+
+def test_decay_weights_edge_betas():
+    assert np.array_equal(oracle.decay_weights(0.0, 3), [0.0, 0.0, 1.0])   # 0^0 = 1
+    assert np.array_equal(oracle.decay_weights(1.0, 3), [1.0, 1.0, 1.0])
+
+
+def test_round_bf16_matches_library_cast():
+    r = _rng(6)
+    x = np.concatenate([r.standard_normal(2000) * 3, [0.0, 1.0, 0.9, 1.9, 1 + 2 ** -8, 1 + 3 * 2 ** -8, -1 - 2 ** -8]])
+    x = x.astype(np.float32).astype(np.float64)
+    ref = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(oracle.round_bf16(x), ref)
+    # ties go to the even neighbour
+    assert oracle.round_bf16([1 + 2 ** -8])[0] == 1.0 and oracle.round_bf16([1 + 3 * 2 ** -8])[0] == 1 + 2 ** -6
+
+
+def test_avgpool_matches_library_routine():
+    x = _rng(7).integers(0, 2, size=(3, 2, 8, 6)).astype(np.float64)
+    ref = torch.nn.functional.avg_pool2d(torch.from_numpy(x), 2).numpy()
+    assert np.array_equal(oracle.avgpool2(x), ref)
+
+
+# ------------------------------------------------------------------ recurrences
+
+def test_hand_worked_scalar_example():
+    g = json.load(open(os.path.join(GOLDEN, "scalar_example.json")))
+    s = np.array(g["input"], dtype=np.uint8).reshape(4, 1, 1, 1, 1)
+    w = _rng(8).standard_normal((1, 1, 3, 3)); w[0, 0, 1, 1] = g["centre_tap"]
+    kw = dict(beta=g["beta"], theta=g["theta"])
+    for mode, K, key in [(PER_STEP, 1, "per_step"), (TAC, 2, "tac_K2"), (TAC_TP, 2, "tac_tp_K2")]:
+        out, v_pre, v_fin = oracle.conv_lif(s, w, K=K, mode=mode, **kw)
+        assert out.ravel().tolist() == g[key]["spikes"], key
+        assert v_pre.ravel().tolist() == g[key]["v_pre"], key
+        assert v_fin.ravel().tolist() == [g[key]["v_final"]], key
+
+
+def _tiny(seed, T=8, B=2, Cin=2, H=5, W=6, Cout=3):
+    r = _rng(seed)
+    s = r.integers(0, 2, size=(T, B, Cin, H, W)).astype(np.uint8)
+    w = r.standard_normal((Cout, Cin, 3, 3)) * 0.4
+    return s, w
+
+
+@pytest.mark.parametrize("K", [1, 2, 4, 8])
+def test_tac_without_spikes_equals_per_step_at_group_ends(K):
+    # With the threshold out of reach no reset happens, and unrolling the per-step
+    # recurrence over one group gives beta^K V + W * A_k: TAC's membrane after group k
+    # equals the per-step membrane at the group's last timestep.
+    s, w = _tiny(10)
+    kw = dict(beta=0.9, theta=1e30)
+    _, v_ps, _ = oracle.conv_lif(s, w, mode=PER_STEP, **kw)
+    _, v_tac, _ = oracle.conv_lif(s, w, K=K, mode=TAC, **kw)
+    assert np.abs(v_tac - v_ps[K - 1::K]).max() < 1e-12
+
+
+@pytest.mark.parametrize("K", [2, 4])
+def test_tac_tp_without_spikes_closed_form(K):
+    # No resets: after a group, V = beta^K V0 + Y_k (1 - beta^K) / (1 - beta)
+    s, w = _tiny(11)
+    beta = 0.7
+    r = _rng(12)
+    v0 = r.standard_normal((2, 3, 5, 6))
+    _, v_pre, v_fin = oracle.conv_lif(s, w, K=K, beta=beta, theta=1e30, mode=TAC_TP, v0=v0)
+    al = oracle.decay_weights(beta, K)
+    V = v0.copy()
+    for k in range(8 // K):
+        A = np.tensordot(al, s[k * K:(k + 1) * K].astype(np.float64), axes=1)
+        Y = torch.nn.functional.conv2d(torch.from_numpy(A), torch.from_numpy(w), padding=1).numpy()
+        V = beta ** K * V + Y * (1 - beta ** K) / (1 - beta)
+        assert np.abs(v_pre[(k + 1) * K - 1] - V).max() < 1e-12
+        # every one of the K inner steps saw the same input current Y_k
+        prev = v_pre[k * K - 1] if k else v0
+        for j in range(K):
+            cur = v_pre[k * K + j]
+            assert np.abs((cur - beta * prev) - Y).max() < 1e-12
+            prev = cur
+    assert np.abs(v_fin - V).max() < 1e-12
+
+
+def test_K1_all_modes_bit_identical():
+    s, w = _tiny(13)
+    b = _rng(14).standard_normal(3) * 0.1
+    kw = dict(beta=0.9, theta=1.0, bias=b)
+    a = oracle.conv_lif(s, w, mode=PER_STEP, **kw)
+    for mode in (TAC, TAC_TP):
+        c = oracle.conv_lif(s, w, K=1, mode=mode, **kw)
+        for x, y in zip(a, c):
+            assert np.array_equal(x, y)
+    assert a[0].sum() > 0          # the case does fire
+
+
+def test_output_shapes_collapse_vs_preserve():
+    # App. B: TAC-TP keeps T steps at every layer, TAC gives T/K
+    s, w = _tiny(15)
+    for K in (1, 2, 4, 8):
+        assert oracle.conv_lif(s, w, K=K, beta=0.9, theta=1.0, mode=TAC)[0].shape[0] == 8 // K
+        assert oracle.conv_lif(s, w, K=K, beta=0.9, theta=1.0, mode=TAC_TP)[0].shape[0] == 8
+    with pytest.raises(ValueError):
+        oracle.conv_lif(s, w, K=3, beta=0.9, theta=1.0, mode=TAC)
+
+
+def test_threshold_tie_fires():
+    # integer arithmetic: V reaches theta exactly and must spike (V >= theta)
+    s = np.ones((2, 1, 1, 1, 1), dtype=np.uint8)
+    w = np.zeros((1, 1, 3, 3)); w[0, 0, 1, 1] = 1.0
+    out, v_pre, v_fin = oracle.conv_lif(s, w, beta=1.0, theta=2.0, mode=PER_STEP)
+    assert v_pre.ravel().tolist() == [1.0, 2.0] and out.ravel().tolist() == [0, 1] and v_fin.ravel()[0] == 0.0
+    out, v_pre, _ = oracle.conv_lif(s, w, K=2, beta=1.0, theta=2.0, mode=TAC)
+    assert v_pre.ravel().tolist() == [2.0] and out.ravel().tolist() == [1]
+
+
+def test_reset_is_subtractive_not_to_zero():
+    s = np.ones((1, 1, 1, 1, 1), dtype=np.uint8)
+    w = np.zeros((1, 1, 3, 3)); w[0, 0, 1, 1] = 2.75
+    _, _, v_fin = oracle.conv_lif(s, w, beta=0.5, theta=1.0, mode=PER_STEP)
+    assert v_fin.ravel()[0] == 1.75
+
+
+# ---------------------------------------------- exact brute force on tiny inputs
+
+def _brute(s, w, bias, v0, K, beta, theta, mode, stride, pad, pool2):
+    """Independent scalar re-derivation in exact rational arithmetic, one output neuron at a
+    time, taps gathered in a different order from the oracle's loops."""
+    F = Fraction
+    T, B, Cin, Hs, Ws = s.shape
+    H, W = (Hs // 2, Ws // 2) if pool2 else (Hs, Ws)
+    Cout = w.shape[0]
+    Ho = (H + 2 * pad - 3) // stride + 1
+    Wo = (W + 2 * pad - 3) // stride + 1
+    beta, theta = F(beta), F(theta)
+
+    def pix(t, b, ci, y, x):
+        if not (0 <= y < H and 0 <= x < W):
+            return F(0)
+        if pool2:
+            return F(int(s[t, b, ci, 2 * y:2 * y + 2, 2 * x:2 * x + 2].sum()), 4)
+        return F(int(s[t, b, ci, y, x]))
+
+    Kg = 1 if mode == PER_STEP else K
+    n_lif = Kg if mode == TAC_TP else 1
+    decay = beta ** Kg if mode == TAC else beta
+    T_out = T // Kg * n_lif
+    spikes = np.zeros((T_out, B, Cout, Ho, Wo), dtype=np.uint8)
+    v_pre = np.empty((T_out, B, Cout, Ho, Wo), dtype=object)
+    v_fin = np.empty((B, Cout, Ho, Wo), dtype=object)
+    for b, co, oy, ox in itertools.product(range(B), range(Cout), range(Ho), range(Wo)):
+        V = F(float(v0[b, co, oy, ox])) if v0 is not None else F(0)
+        step = 0
+        for k in range(T // Kg):
+            Y = F(float(bias[co])) if bias is not None else F(0)
+            for kx, ky, ci in itertools.product(range(2, -1, -1), range(3), range(Cin - 1, -1, -1)):
+                a = sum(beta ** (Kg - 1 - j) * pix(k * Kg + j, b, ci, oy * stride + ky - pad, ox * stride + kx - pad)
+                        for j in range(Kg))
+                Y += F(float(w[co, ci, ky, kx])) * a
+            for _ in range(n_lif):
+                V = decay * V + Y
+                v_pre[step, b, co, oy, ox] = V
+                if V >= theta:
+                    spikes[step, b, co, oy, ox] = 1
+                    V -= theta
+                step += 1
+        v_fin[b, co, oy, ox] = V
+    return spikes, v_pre, v_fin
+
+
+@pytest.mark.parametrize("mode,K", [(PER_STEP, 1), (TAC, 2), (TAC, 4), (TAC_TP, 2), (TAC_TP, 4)])
+@pytest.mark.parametrize("stride,pool2", [(1, False), (2, False), (1, True)])
+def test_exact_brute_force(mode, K, stride, pool2):
+    r = _rng(100 + 10 * K + stride + 5 * pool2)
+    T, B, Cin, Cout, H, W = 4, 1, 2, 3, 5, 4
+    shape = (T, B, Cin, 2 * H, 2 * W) if pool2 else (T, B, Cin, H, W)
+    s = r.integers(0, 2, size=shape).astype(np.uint8)
+    # dyadic weights and a dyadic beta keep every intermediate exact in double as well
+    w = r.integers(-8, 9, size=(Cout, Cin, 3, 3)) / 8.0
+    bias = r.integers(-4, 5, size=Cout) / 16.0
+    v0 = r.integers(-8, 9, size=(B, Cout, (H + 2 - 3) // stride + 1, (W + 2 - 3) // stride + 1)) / 8.0
+    beta, theta = 0.75, 1.0
+    got = oracle.conv_lif(s, w, bias, K=K, beta=beta, theta=theta, mode=mode, stride=stride, pad=1, v0=v0, pool2=pool2)
+    ref = _brute(s, w, bias, v0, K, beta, theta, mode, stride, 1, pool2)
+    assert np.array_equal(got[0], ref[0])
+    assert np.array_equal(got[1], ref[1].astype(np.float64))
+    assert np.array_equal(got[2], ref[2].astype(np.float64))
+    assert got[0].sum() > 0
+
+
+@pytest.mark.parametrize("mode,K", [(PER_STEP, 1), (TAC, 4), (TAC_TP, 2)])
+@pytest.mark.parametrize("stride,pool2,round_a", [(1, False, False), (2, False, True), (1, True, True)])
+def test_single_neuron_routine_matches_full_tensor(mode, K, stride, pool2, round_a):
+    r = _rng(200 + K)
+    T, B, Cin, Cout, H, W = 8, 2, 3, 4, 6, 7
+    shape = (T, B, Cin, 2 * H, 2 * W) if pool2 else (T, B, Cin, H, W)
+    s = r.integers(0, 2, size=shape).astype(np.uint8)
+    w = r.standard_normal((Cout, Cin, 3, 3)) * 0.4
+    bias = r.standard_normal(Cout) * 0.1
+    kw = dict(K=K, beta=0.9, theta=1.0, mode=mode, stride=stride, pool2=pool2, round_a_bf16=round_a)
+    full = oracle.conv_lif(s, w, bias, **kw)
+    Ho, Wo = full[2].shape[2:]
+    idx = np.array(list(itertools.product(range(B), range(Cout), range(Ho), range(Wo))), dtype=np.int32)
+    part = oracle.conv_lif_neurons(s, w, bias, idx=idx, nthreads=2, **kw)
+    assert np.array_equal(part[0], full[0].reshape(full[0].shape[0], -1))
+    assert np.abs(part[1] - full[1].reshape(full[1].shape[0], -1)).max() < 1e-12
+    assert np.abs(part[2] - full[2].ravel()).max() < 1e-12
+
+
+def test_bf16_rounded_aggregate_is_what_it_says():
+    # one input pixel, centre tap 1: Y_k is A_k itself, so V_pre of group 0 is round_bf16(A_0)
+    s = np.ones((4, 1, 1, 1, 1), dtype=np.uint8)
+    w = np.zeros((1, 1, 3, 3)); w[0, 0, 1, 1] = 1.0
+    _, v_pre, _ = oracle.conv_lif(s, w, K=4, beta=0.9, theta=1e30, mode=TAC, round_a_bf16=True)
+    exact = 1 + 0.9 + 0.81 + 0.729
+    ref = float(torch.tensor(exact, dtype=torch.float32).to(torch.bfloat16))
+    assert v_pre.ravel()[0] == ref and ref != exact
+
+
+def test_state_carry_splits_time():
+    # the only state is V: one call over T = 8 equals two calls over T = 4 carrying V
+    s, w = _tiny(16)
+    for mode, K in [(PER_STEP, 1), (TAC, 2), (TAC_TP, 4)]:
+        kw = dict(K=K, beta=0.9, theta=1.0, mode=mode)
+        whole = oracle.conv_lif(s, w, **kw)
+        a = oracle.conv_lif(s[:4], w, **kw)
+        b = oracle.conv_lif(s[4:], w, v0=a[2], **kw)
+        assert np.array_equal(np.concatenate([a[0], b[0]]), whole[0])
+        assert np.array_equal(b[2], whole[2])
