@@ -1,0 +1,151 @@
+/*
+ * libtac -- forward pass of one convolutional spiking (conv-LIF) layer on an
+ * AMD MI355X (gfx950), in the three temporal modes of the paper:
+ *
+ *   per-step   T convolutions, T LIF steps                      (Sec. 3.1, Eq. 1)
+ *   TAC        T/K convolutions of the decay-weighted aggregate
+ *              A_k = sum_j beta^(K-1-j) S_{kK+j}, T/K LIF steps  (Def. 1 / Eq. 2, Alg. 1)
+ *   TAC-TP     T/K convolutions of the same A_k, each output fed
+ *              to K LIF steps, T output steps                    (Alg. 2)
+ *
+ * Plain C ABI: every pointer is either a HOST pointer or a DEVICE pointer, as
+ * stated per argument; sizes are plain integers; `stream` is a hipStream_t
+ * passed as void* (NULL = the default stream).  The library allocates no
+ * device memory, keeps no device state between calls, enqueues all work on
+ * `stream` and returns without synchronising.  Every entry point returns an
+ * int status (0 = TAC_OK, negative = error) unless stated otherwise; no
+ * exception or abort crosses the boundary.  All argument validation happens
+ * before anything is launched, so error paths can be exercised on a machine
+ * without a GPU.
+ *
+ * Spike tensors cross the boundary bit-packed:
+ *   logical   S[T][B][C][H][W], values 0/1 (the layout of Alg. 1 / Alg. 2)
+ *   physical  uint32 [T][B][C][H][ceil(W/32)]; pixel x of a row is bit (x % 32)
+ *             of word x / 32; every row is padded to a whole word and the pad
+ *             bits are zero on input and written as zero on output.
+ * The output of one layer is therefore a valid input of the next.
+ */
+#ifndef TAC_H
+#define TAC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Temporal mode. */
+enum { TAC_PER_STEP = 0, TAC_COLLAPSE = 1 /* TAC */, TAC_PRESERVE = 2 /* TAC-TP */ };
+/* Operand precision of the convolution.  Accumulation, membrane, beta and theta
+ * are always fp32.  TAC_BF16: the kernel W and every aggregate A_k are rounded
+ * to bfloat16 (nearest even) before they are multiplied. */
+enum { TAC_FP32 = 0, TAC_BF16 = 1 };
+/* Input format.  TAC_IN_BITS_POOL2: `spikes_packed` holds the UNPOOLED frames
+ * [T][B][Cin][2H][2W]; a 2x2 mean pool (stride 2) is applied while loading, so
+ * the layer sees inputs in {0, 1/4, 1/2, 3/4, 1} of size H x W. */
+enum { TAC_IN_BITS = 0, TAC_IN_BITS_POOL2 = 1 };
+/* Kernel family.  AUTO picks MFMA when the shape qualifies (see
+ * tac_select_kernel), else DIRECT.  Forcing MFMA on a shape it does not
+ * support is TAC_ERR_UNSUPPORTED. */
+enum { TAC_KERNEL_AUTO = 0, TAC_KERNEL_DIRECT = 1, TAC_KERNEL_MFMA = 2 };
+
+enum {
+  TAC_OK = 0,
+  TAC_ERR_NULL = -1,        /* a required pointer is NULL                               */
+  TAC_ERR_BAD_SHAPE = -2,   /* a dimension <= 0, kh/kw != 3, stride not 1 or 2, pad != 1,
+                               or a tensor too large for 32-bit word indexing           */
+  TAC_ERR_BAD_K = -3,       /* K < 1, K > TAC_MAX_K, or K does not divide T
+                               (App. A assumes K | T)                                   */
+  TAC_ERR_BAD_PARAM = -4,   /* beta outside [0,1], theta <= 0 or not finite, bad enum   */
+  TAC_ERR_UNSUPPORTED = -5, /* valid request that the chosen kernel family cannot run   */
+  TAC_ERR_HIP = -6,         /* a HIP call failed; text via tac_last_error()             */
+  TAC_ERR_ALIGN = -7        /* a device pointer is not aligned as documented            */
+};
+
+#define TAC_MAX_K 32
+
+/* One conv-LIF layer.  Plain data; the caller fills every field. */
+typedef struct tac_layer_desc {
+  int32_t T, B, Cin, H, W;   /* logical input S[T][B][Cin][H][W] (H, W after the pool when
+                                in_format = TAC_IN_BITS_POOL2)                            */
+  int32_t Cout, kh, kw;      /* kernel W[Cout][Cin][kh][kw]; kh = kw = 3                  */
+  int32_t stride, pad;       /* stride 1 or 2, pad 1 (zero padding)                       */
+  int32_t K;                 /* group size; TAC_PER_STEP ignores it and uses 1            */
+  int32_t mode;              /* TAC_PER_STEP / TAC_COLLAPSE / TAC_PRESERVE                */
+  int32_t precision;         /* TAC_FP32 / TAC_BF16                                       */
+  int32_t in_format;         /* TAC_IN_BITS / TAC_IN_BITS_POOL2                           */
+  int32_t kernel;            /* TAC_KERNEL_AUTO / _DIRECT / _MFMA                         */
+  float beta;                /* membrane decay, in [0, 1]                                 */
+  float theta;               /* threshold V_th, > 0                                       */
+} tac_layer_desc_t;
+
+/* Output geometry: T_out = T/K for TAC (Alg. 1 returns T/K steps), T for TAC-TP
+ * (Alg. 2, App. B) and per-step; Ho = (H + 2 pad - kh)/stride + 1, same for Wo.
+ * Host only.  Any of the three out-pointers may be NULL. */
+int tac_out_shape(const tac_layer_desc_t* desc, int32_t* T_out, int32_t* Ho, int32_t* Wo);
+
+/* Bytes of a packed spike tensor [T][B][C][H][ceil(W/32)] of uint32.  0 if a dimension is <= 0. */
+size_t tac_packed_bytes(int32_t T, int32_t B, int32_t C, int32_t H, int32_t W);
+
+/* Which kernel family tac_prepare_weights / tac_conv_lif will use for this
+ * layer: TAC_KERNEL_DIRECT or TAC_KERNEL_MFMA, or a negative error.  Host only.
+ * MFMA (bf16 implicit-GEMM on the matrix cores) needs precision = TAC_BF16 and
+ * a shape in its supported set; everything else runs on the DIRECT kernel
+ * (fp32 vector FMAs, any shape). */
+int tac_select_kernel(const tac_layer_desc_t* desc);
+
+/* Size of the prepared-weight buffer for this layer.  0 on an invalid desc. */
+size_t tac_prepared_weight_bytes(const tac_layer_desc_t* desc);
+
+/* Re-lay the kernel W for the chosen kernel family (and round it to bf16 when
+ * precision = TAC_BF16).  Done once per layer, outside the timed path.
+ *   w_oihw      DEVICE, read-only, float32 [Cout][Cin][3][3] (cross-correlation
+ *               taps, as a deep-learning Conv2d stores them)
+ *   w_prepared  DEVICE, written, tac_prepared_weight_bytes(desc) bytes, 16-byte aligned
+ * The prepared buffer is only valid for a desc with the same Cin, Cout,
+ * precision and kernel choice. */
+int tac_prepare_weights(const tac_layer_desc_t* desc, const float* w_oihw, void* w_prepared, void* stream);
+
+/* The layer: for every group k of K frames form A_k (Eq. 2), Y_k = bias +
+ * Conv2d(A_k, W), then the LIF update(s), threshold (spike iff V >= theta) and
+ * subtractive reset of Alg. 1 (TAC), Alg. 2 (TAC-TP) or the per-step layer
+ * (K = 1).  A_k and Y_k never leave the chip.
+ *   spikes_packed      DEVICE, read-only, packed [T][B][Cin][H][ceil(W/32)]
+ *                      (or [T][B][Cin][2H][ceil(2W/32)] with TAC_IN_BITS_POOL2)
+ *   w_prepared         DEVICE, read-only, from tac_prepare_weights
+ *   bias               DEVICE, read-only, float32 [Cout], or NULL for zero.  Added
+ *                      once per convolution (so TAC-TP sees it in each of its K steps)
+ *   v_inout            DEVICE, float32 [B][Cout][Ho][Wo]: membrane after the last
+ *                      reset.  Read at entry as V_0, overwritten at exit, so a long
+ *                      sequence can be fed in chunks of T.  NULL: V_0 = 0 (Alg. 1/2
+ *                      line 1) and the final V is dropped
+ *   out_spikes_packed  DEVICE, written, packed [T_out][B][Cout][Ho][ceil(Wo/32)]
+ *   v_trace            DEVICE, optional debug output, float32 [T_out][B][Cout][Ho][Wo]:
+ *                      membrane BEFORE the reset at every LIF step; NULL in timed runs
+ * Buffers must not overlap.  All pointers need 4-byte alignment. */
+int tac_conv_lif(const tac_layer_desc_t* desc, const uint32_t* spikes_packed, const void* w_prepared,
+                 const float* bias, float* v_inout, uint32_t* out_spikes_packed, float* v_trace,
+                 void* stream);
+
+/* Dense 0/1 bytes <-> packed words, `rows` rows of W pixels each (rows = T*B*C*H).
+ *   dense01  DEVICE uint8 [rows][W]; any non-zero byte packs as 1
+ *   packed   DEVICE uint32 [rows][ceil(W/32)] */
+int tac_pack_spikes(const uint8_t* dense01, uint32_t* packed, int64_t rows, int32_t W, void* stream);
+int tac_unpack_spikes(const uint32_t* packed, uint8_t* dense01, int64_t rows, int32_t W, void* stream);
+
+/* Host-side accounting since the last reset, summed over tac_conv_lif calls of
+ * this process: convolution stages executed (T/K per call; Table 3 counts these
+ * "conv calls" over all layers) and LIF steps (T_out per call). */
+int tac_get_counters(uint64_t* conv_stages, uint64_t* lif_steps);
+int tac_reset_counters(void);
+
+/* Static text for a status code; never NULL. */
+const char* tac_status_string(int status);
+/* Text of the last HIP failure seen by the calling thread ("" if none). */
+const char* tac_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TAC_H */

@@ -1,0 +1,233 @@
+"""Thin ctypes binding over libtac.so: same names as include/tac.h, argument marshalling only.
+
+Every step of the layer (spike loading, aggregation, convolution, LIF, packing) runs inside
+the library's HIP kernels.  PyTorch is used for device memory and the current stream only.
+There is no fallback: if the library has not been built, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libtac.so")
+
+TAC_PER_STEP, TAC_COLLAPSE, TAC_PRESERVE = 0, 1, 2
+TAC_FP32, TAC_BF16 = 0, 1
+TAC_IN_BITS, TAC_IN_BITS_POOL2 = 0, 1
+TAC_KERNEL_AUTO, TAC_KERNEL_DIRECT, TAC_KERNEL_MFMA = 0, 1, 2
+TAC_OK, TAC_ERR_NULL, TAC_ERR_BAD_SHAPE, TAC_ERR_BAD_K = 0, -1, -2, -3
+TAC_ERR_BAD_PARAM, TAC_ERR_UNSUPPORTED, TAC_ERR_HIP, TAC_ERR_ALIGN = -4, -5, -6, -7
+TAC_MAX_K = 32
+
+MODE_NAMES = {TAC_PER_STEP: "per_step", TAC_COLLAPSE: "TAC", TAC_PRESERVE: "TAC_TP"}
+
+EXPORTS = ("tac_out_shape", "tac_packed_bytes", "tac_select_kernel", "tac_prepared_weight_bytes",
+           "tac_prepare_weights", "tac_conv_lif", "tac_pack_spikes", "tac_unpack_spikes",
+           "tac_get_counters", "tac_reset_counters", "tac_status_string", "tac_last_error")
+
+
+class tac_layer_desc_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("T", "B", "Cin", "H", "W", "Cout", "kh", "kw", "stride", "pad", "K",
+                 "mode", "precision", "in_format", "kernel")] + \
+               [("beta", ctypes.c_float), ("theta", ctypes.c_float)]
+
+
+class TacError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("libtac status %d: %s" % (status, text))
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libtac.so (built in-tree by paper_2603_13810_amd/build.py).  Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libtac.so is not built: run `python paper_2603_13810_amd/build.py` "
+                               "(there is no CPU fallback for the HIP path)")
+        L = ctypes.CDLL(LIB_PATH)
+        dp, vp, i32p = ctypes.POINTER(tac_layer_desc_t), ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32)
+        L.tac_out_shape.argtypes = [dp, i32p, i32p, i32p]
+        L.tac_out_shape.restype = ctypes.c_int
+        L.tac_packed_bytes.argtypes = [ctypes.c_int32] * 5
+        L.tac_packed_bytes.restype = ctypes.c_size_t
+        L.tac_select_kernel.argtypes = [dp]
+        L.tac_select_kernel.restype = ctypes.c_int
+        L.tac_prepared_weight_bytes.argtypes = [dp]
+        L.tac_prepared_weight_bytes.restype = ctypes.c_size_t
+        L.tac_prepare_weights.argtypes = [dp, vp, vp, vp]
+        L.tac_prepare_weights.restype = ctypes.c_int
+        L.tac_conv_lif.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
+        L.tac_conv_lif.restype = ctypes.c_int
+        L.tac_pack_spikes.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp]
+        L.tac_pack_spikes.restype = ctypes.c_int
+        L.tac_unpack_spikes.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp]
+        L.tac_unpack_spikes.restype = ctypes.c_int
+        u64p = ctypes.POINTER(ctypes.c_uint64)
+        L.tac_get_counters.argtypes = [u64p, u64p]
+        L.tac_get_counters.restype = ctypes.c_int
+        L.tac_reset_counters.argtypes = []
+        L.tac_reset_counters.restype = ctypes.c_int
+        L.tac_status_string.argtypes = [ctypes.c_int]
+        L.tac_status_string.restype = ctypes.c_char_p
+        L.tac_last_error.argtypes = []
+        L.tac_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def tac_status_string(status: int) -> str:
+    return lib().tac_status_string(int(status)).decode()
+
+
+def tac_last_error() -> str:
+    return lib().tac_last_error().decode()
+
+
+def _check(status: int) -> None:
+    if status != TAC_OK:
+        text = tac_status_string(status)
+        if status == TAC_ERR_HIP:
+            text += " [" + tac_last_error() + "]"
+        raise TacError(status, text)
+
+
+def make_desc(T, B, Cin, H, W, Cout, *, K=1, beta, theta, mode, stride=1, pad=1, kh=3, kw=3,
+              precision=TAC_FP32, in_format=TAC_IN_BITS, kernel=TAC_KERNEL_AUTO) -> tac_layer_desc_t:
+    return tac_layer_desc_t(T=T, B=B, Cin=Cin, H=H, W=W, Cout=Cout, kh=kh, kw=kw, stride=stride, pad=pad,
+                            K=K, mode=mode, precision=precision, in_format=in_format, kernel=kernel,
+                            beta=beta, theta=theta)
+
+
+def tac_out_shape(desc: tac_layer_desc_t) -> Tuple[int, int, int]:
+    t, h, w = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().tac_out_shape(ctypes.byref(desc), ctypes.byref(t), ctypes.byref(h), ctypes.byref(w)))
+    return t.value, h.value, w.value
+
+
+def tac_packed_bytes(T, B, C, H, W) -> int:
+    return int(lib().tac_packed_bytes(T, B, C, H, W))
+
+
+def tac_select_kernel(desc: tac_layer_desc_t) -> int:
+    k = lib().tac_select_kernel(ctypes.byref(desc))
+    if k < 0:
+        _check(k)
+    return k
+
+
+def tac_prepared_weight_bytes(desc: tac_layer_desc_t) -> int:
+    return int(lib().tac_prepared_weight_bytes(ctypes.byref(desc)))
+
+
+def _stream(stream=None):
+    if stream is not None:
+        return ctypes.c_void_p(int(stream))
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_ptr(t, dtype=None, name="tensor"):
+    if t is None:
+        return None
+    import torch
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous device tensor" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("%s must have dtype %s" % (name, dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def tac_prepare_weights(desc, w_oihw, w_prepared=None, stream=None):
+    """w_oihw: float32 device tensor [Cout,Cin,3,3].  Returns the prepared buffer (uint8 device tensor)."""
+    import torch
+    if tuple(w_oihw.shape) != (desc.Cout, desc.Cin, 3, 3):
+        raise ValueError("weight shape does not match the layer description")
+    tac_select_kernel(desc)            # raises on an invalid or unsupported description
+    n = tac_prepared_weight_bytes(desc)
+    if w_prepared is None:
+        w_prepared = torch.empty(n, dtype=torch.uint8, device=w_oihw.device)
+    elif w_prepared.numel() * w_prepared.element_size() < n:
+        raise ValueError("prepared-weight buffer too small")
+    _check(lib().tac_prepare_weights(ctypes.byref(desc), _dev_ptr(w_oihw, torch.float32, "w_oihw"),
+                                     _dev_ptr(w_prepared, None, "w_prepared"), _stream(stream)))
+    return w_prepared
+
+
+def tac_conv_lif(desc, spikes_packed, w_prepared, bias=None, v_inout=None, out_spikes_packed=None,
+                 v_trace=None, stream=None):
+    """One layer call.  Tensors are device tensors; buffer sizes are checked against the
+    description here because the C side only sees raw pointers.  Returns out_spikes_packed
+    (int32 tensor [T_out,B,Cout,Ho,ceil(Wo/32)], allocated if not given)."""
+    import torch
+    T_out, Ho, Wo = tac_out_shape(desc)
+    f = 2 if desc.in_format == TAC_IN_BITS_POOL2 else 1
+    need_in = tac_packed_bytes(desc.T, desc.B, desc.Cin, desc.H * f, desc.W * f)
+    if spikes_packed.numel() * spikes_packed.element_size() != need_in:
+        raise ValueError("spikes_packed has %d bytes, the description needs %d" %
+                         (spikes_packed.numel() * spikes_packed.element_size(), need_in))
+    if w_prepared.numel() * w_prepared.element_size() < tac_prepared_weight_bytes(desc):
+        raise ValueError("prepared-weight buffer too small for this description")
+    if out_spikes_packed is None:
+        out_spikes_packed = torch.empty((T_out, desc.B, desc.Cout, Ho, (Wo + 31) // 32), dtype=torch.int32,
+                                        device=spikes_packed.device)
+    elif out_spikes_packed.numel() * out_spikes_packed.element_size() != tac_packed_bytes(T_out, desc.B, desc.Cout, Ho, Wo):
+        raise ValueError("out_spikes_packed has the wrong size")
+    if bias is not None and tuple(bias.shape) != (desc.Cout,):
+        raise ValueError("bias must be [Cout]")
+    if v_inout is not None and tuple(v_inout.shape) != (desc.B, desc.Cout, Ho, Wo):
+        raise ValueError("v_inout must be [B,Cout,Ho,Wo]")
+    if v_trace is not None and tuple(v_trace.shape) != (T_out, desc.B, desc.Cout, Ho, Wo):
+        raise ValueError("v_trace must be [T_out,B,Cout,Ho,Wo]")
+    _check(lib().tac_conv_lif(ctypes.byref(desc), _dev_ptr(spikes_packed, None, "spikes_packed"),
+                              _dev_ptr(w_prepared, None, "w_prepared"), _dev_ptr(bias, torch.float32, "bias"),
+                              _dev_ptr(v_inout, torch.float32, "v_inout"),
+                              _dev_ptr(out_spikes_packed, None, "out_spikes_packed"),
+                              _dev_ptr(v_trace, torch.float32, "v_trace"), _stream(stream)))
+    return out_spikes_packed
+
+
+def tac_pack_spikes(dense01, packed=None, stream=None):
+    """dense01: uint8 device tensor [..., W] -> int32 device tensor [..., ceil(W/32)]."""
+    import torch
+    W = dense01.shape[-1]
+    rows = dense01.numel() // W
+    if packed is None:
+        packed = torch.empty(tuple(dense01.shape[:-1]) + ((W + 31) // 32,), dtype=torch.int32, device=dense01.device)
+    elif packed.numel() != rows * ((W + 31) // 32) or packed.element_size() != 4:
+        raise ValueError("packed buffer has the wrong size")
+    _check(lib().tac_pack_spikes(_dev_ptr(dense01, torch.uint8, "dense01"), _dev_ptr(packed, None, "packed"),
+                                 rows, W, _stream(stream)))
+    return packed
+
+
+def tac_unpack_spikes(packed, W, dense01=None, stream=None):
+    """packed: int32 device tensor [..., ceil(W/32)] -> uint8 device tensor [..., W]."""
+    import torch
+    Ww = (W + 31) // 32
+    if packed.shape[-1] != Ww:
+        raise ValueError("last dimension of packed must be ceil(W/32)")
+    rows = packed.numel() // Ww
+    if dense01 is None:
+        dense01 = torch.empty(tuple(packed.shape[:-1]) + (W,), dtype=torch.uint8, device=packed.device)
+    elif dense01.numel() != rows * W:
+        raise ValueError("dense buffer has the wrong size")
+    _check(lib().tac_unpack_spikes(_dev_ptr(packed, None, "packed"), _dev_ptr(dense01, torch.uint8, "dense01"),
+                                   rows, W, _stream(stream)))
+    return dense01
+
+
+def tac_get_counters() -> Tuple[int, int]:
+    a, b = ctypes.c_uint64(), ctypes.c_uint64()
+    _check(lib().tac_get_counters(ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
+
+
+def tac_reset_counters() -> None:
+    _check(lib().tac_reset_counters())

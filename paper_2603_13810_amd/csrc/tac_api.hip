@@ -1,0 +1,189 @@
+// Host side of the C ABI: argument validation, kernel-family selection, decay
+// tables, accounting.  No arithmetic of the method runs here except the
+// (K+1)-entry table of powers of beta (Eq. 2 and the beta^K of Alg. 1), which
+// is evaluated in double and rounded once to fp32.
+#include <atomic>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+
+#include "tac_internal.h"
+
+namespace {
+
+thread_local char g_last_error[512] = "";
+std::atomic<uint64_t> g_conv_stages{0}, g_lif_steps{0};
+
+int hip_fail(hipError_t e, const char* where) {
+  std::snprintf(g_last_error, sizeof(g_last_error), "%s: %s", where, hipGetErrorString(e));
+  return TAC_ERR_HIP;
+}
+
+// Shape / parameter checks shared by every entry point.  Returns TAC_OK or the error.
+int validate(const tac_layer_desc_t* d) {
+  if (!d) return TAC_ERR_NULL;
+  if (d->T < 1 || d->B < 1 || d->Cin < 1 || d->H < 1 || d->W < 1 || d->Cout < 1) return TAC_ERR_BAD_SHAPE;
+  if (d->kh != 3 || d->kw != 3 || d->pad != 1) return TAC_ERR_BAD_SHAPE;
+  if (d->stride != 1 && d->stride != 2) return TAC_ERR_BAD_SHAPE;
+  if (d->mode != TAC_PER_STEP && d->mode != TAC_COLLAPSE && d->mode != TAC_PRESERVE) return TAC_ERR_BAD_PARAM;
+  if (d->precision != TAC_FP32 && d->precision != TAC_BF16) return TAC_ERR_BAD_PARAM;
+  if (d->in_format != TAC_IN_BITS && d->in_format != TAC_IN_BITS_POOL2) return TAC_ERR_BAD_PARAM;
+  if (d->kernel != TAC_KERNEL_AUTO && d->kernel != TAC_KERNEL_DIRECT && d->kernel != TAC_KERNEL_MFMA)
+    return TAC_ERR_BAD_PARAM;
+  if (!(d->beta >= 0.0f && d->beta <= 1.0f)) return TAC_ERR_BAD_PARAM;
+  if (!(d->theta > 0.0f) || !std::isfinite(d->theta)) return TAC_ERR_BAD_PARAM;
+  if (d->mode != TAC_PER_STEP) {
+    if (d->K < 1 || d->K > TAC_MAX_K || d->T % d->K != 0) return TAC_ERR_BAD_K;
+  }
+  // kernels index words and membrane elements with 32-bit offsets inside one (t) slab and
+  // 64-bit offsets across slabs; keep each slab below 2^31 elements
+  const int Ho = (d->H + 2 - 3) / d->stride + 1, Wo = (d->W + 2 - 3) / d->stride + 1;
+  const int64_t out_slab = (int64_t)d->B * d->Cout * Ho * Wo;
+  const int f = d->in_format == TAC_IN_BITS_POOL2 ? 2 : 1;
+  const int64_t in_slab = (int64_t)d->B * d->Cin * (d->H * f) * ((d->W * f + 31) / 32);
+  if (out_slab >= (1LL << 31) || in_slab >= (1LL << 31)) return TAC_ERR_BAD_SHAPE;
+  if (d->B > 65535) return TAC_ERR_BAD_SHAPE;
+  return TAC_OK;
+}
+
+int select_kernel(const tac_layer_desc_t* d) {
+  const bool ok = tac::mfma_supported(*d);
+  if (d->kernel == TAC_KERNEL_DIRECT) return TAC_KERNEL_DIRECT;
+  if (d->kernel == TAC_KERNEL_MFMA) return ok ? TAC_KERNEL_MFMA : TAC_ERR_UNSUPPORTED;
+  return ok ? TAC_KERNEL_MFMA : TAC_KERNEL_DIRECT;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tac_out_shape(const tac_layer_desc_t* desc, int32_t* T_out, int32_t* Ho, int32_t* Wo) {
+  const int rc = validate(desc);
+  if (rc) return rc;
+  const int K = desc->mode == TAC_PER_STEP ? 1 : desc->K;
+  if (T_out) *T_out = desc->mode == TAC_COLLAPSE ? desc->T / K : desc->T;
+  if (Ho) *Ho = (desc->H + 2 * desc->pad - desc->kh) / desc->stride + 1;
+  if (Wo) *Wo = (desc->W + 2 * desc->pad - desc->kw) / desc->stride + 1;
+  return TAC_OK;
+}
+
+size_t tac_packed_bytes(int32_t T, int32_t B, int32_t C, int32_t H, int32_t W) {
+  if (T < 1 || B < 1 || C < 1 || H < 1 || W < 1) return 0;
+  return (size_t)T * (size_t)B * (size_t)C * (size_t)H * (size_t)((W + 31) / 32) * 4u;
+}
+
+int tac_select_kernel(const tac_layer_desc_t* desc) {
+  const int rc = validate(desc);
+  if (rc) return rc;
+  return select_kernel(desc);
+}
+
+size_t tac_prepared_weight_bytes(const tac_layer_desc_t* desc) {
+  if (validate(desc)) return 0;
+  const int k = select_kernel(desc);
+  if (k == TAC_KERNEL_MFMA) return tac::mfma_weight_bytes(*desc);
+  if (k == TAC_KERNEL_DIRECT) return tac::direct_weight_bytes(*desc);
+  return 0;
+}
+
+int tac_prepare_weights(const tac_layer_desc_t* desc, const float* w_oihw, void* w_prepared, void* stream) {
+  int rc = validate(desc);
+  if (rc) return rc;
+  if (!w_oihw || !w_prepared) return TAC_ERR_NULL;
+  if (((uintptr_t)w_oihw & 3u) || ((uintptr_t)w_prepared & 15u)) return TAC_ERR_ALIGN;
+  const int k = select_kernel(desc);
+  if (k < 0) return k;
+  hipError_t e = k == TAC_KERNEL_MFMA ? tac::mfma_prepare(*desc, w_oihw, w_prepared, (hipStream_t)stream)
+                                      : tac::direct_prepare(*desc, w_oihw, w_prepared, (hipStream_t)stream);
+  return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_prepare_weights");
+}
+
+int tac_conv_lif(const tac_layer_desc_t* desc, const uint32_t* spikes_packed, const void* w_prepared,
+                 const float* bias, float* v_inout, uint32_t* out_spikes_packed, float* v_trace,
+                 void* stream) {
+  int rc = validate(desc);
+  if (rc) return rc;
+  if (!spikes_packed || !w_prepared || !out_spikes_packed) return TAC_ERR_NULL;
+  if (((uintptr_t)spikes_packed & 3u) || ((uintptr_t)w_prepared & 15u) || ((uintptr_t)bias & 3u) ||
+      ((uintptr_t)v_inout & 3u) || ((uintptr_t)out_spikes_packed & 3u) || ((uintptr_t)v_trace & 3u))
+    return TAC_ERR_ALIGN;
+  const int kern = select_kernel(desc);
+  if (kern < 0) return kern;
+
+  tac::LayerParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.spikes = spikes_packed; p.w = w_prepared; p.bias = bias; p.v_inout = v_inout;
+  p.out = out_spikes_packed; p.v_trace = v_trace;
+  p.T = desc->T; p.B = desc->B; p.Cin = desc->Cin; p.H = desc->H; p.W = desc->W;
+  p.Cout = desc->Cout; p.stride = desc->stride;
+  p.Ho = (desc->H + 2 - 3) / desc->stride + 1;
+  p.Wo = (desc->W + 2 - 3) / desc->stride + 1;
+  p.pool2 = desc->in_format == TAC_IN_BITS_POOL2;
+  p.Hs = p.pool2 ? 2 * desc->H : desc->H;
+  p.Wwi = ((p.pool2 ? 2 * desc->W : desc->W) + 31) / 32;
+  p.Wwo = (p.Wo + 31) / 32;
+  p.K = desc->mode == TAC_PER_STEP ? 1 : desc->K;
+  p.G = desc->T / p.K;
+  p.n_lif = desc->mode == TAC_PRESERVE ? p.K : 1;
+  p.bf16 = desc->precision == TAC_BF16;
+  p.theta = desc->theta;
+  // powers of beta in double from the fp32 beta the caller passed, rounded once
+  const double beta = (double)desc->beta;
+  double pw = 1.0;
+  for (int j = p.K - 1; j >= 0; --j) { p.wj[j] = (float)pw; pw *= beta; }   // wj[j] = beta^(K-1-j)
+  p.decay = desc->mode == TAC_COLLAPSE ? (float)pw /* beta^K */ : desc->beta;
+
+  hipError_t e = kern == TAC_KERNEL_MFMA ? tac::mfma_launch(p, (hipStream_t)stream)
+                                         : tac::direct_launch(p, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "tac_conv_lif");
+  g_conv_stages += (uint64_t)p.G;
+  g_lif_steps += (uint64_t)p.G * (uint64_t)p.n_lif;
+  return TAC_OK;
+}
+
+int tac_pack_spikes(const uint8_t* dense01, uint32_t* packed, int64_t rows, int32_t W, void* stream) {
+  if (!dense01 || !packed) return TAC_ERR_NULL;
+  if (rows < 1 || W < 1) return TAC_ERR_BAD_SHAPE;
+  if ((uintptr_t)packed & 3u) return TAC_ERR_ALIGN;
+  hipError_t e = tac::pack_launch(dense01, packed, rows, W, (hipStream_t)stream);
+  return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_pack_spikes");
+}
+
+int tac_unpack_spikes(const uint32_t* packed, uint8_t* dense01, int64_t rows, int32_t W, void* stream) {
+  if (!dense01 || !packed) return TAC_ERR_NULL;
+  if (rows < 1 || W < 1) return TAC_ERR_BAD_SHAPE;
+  if ((uintptr_t)packed & 3u) return TAC_ERR_ALIGN;
+  hipError_t e = tac::unpack_launch(packed, dense01, rows, W, (hipStream_t)stream);
+  return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_unpack_spikes");
+}
+
+int tac_get_counters(uint64_t* conv_stages, uint64_t* lif_steps) {
+  if (!conv_stages || !lif_steps) return TAC_ERR_NULL;
+  *conv_stages = g_conv_stages.load();
+  *lif_steps = g_lif_steps.load();
+  return TAC_OK;
+}
+
+int tac_reset_counters(void) {
+  g_conv_stages = 0;
+  g_lif_steps = 0;
+  return TAC_OK;
+}
+
+const char* tac_status_string(int status) {
+  switch (status) {
+    case TAC_OK: return "ok";
+    case TAC_ERR_NULL: return "a required pointer is NULL";
+    case TAC_ERR_BAD_SHAPE: return "bad shape (dimension <= 0, kernel not 3x3, stride not 1/2, pad not 1, or tensor too large)";
+    case TAC_ERR_BAD_K: return "bad group size K (K < 1, K > 32, or K does not divide T)";
+    case TAC_ERR_BAD_PARAM: return "bad parameter (beta outside [0,1], theta <= 0 or not finite, or unknown enum value)";
+    case TAC_ERR_UNSUPPORTED: return "the requested kernel family does not support this layer";
+    case TAC_ERR_HIP: return "a HIP call failed (see tac_last_error)";
+    case TAC_ERR_ALIGN: return "a device pointer is not aligned as documented";
+    default: return "unknown status";
+  }
+}
+
+const char* tac_last_error(void) { return g_last_error; }
+
+}  // extern "C"

@@ -1,0 +1,46 @@
+// Internal declarations shared by the host entry points and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "tac.h"
+
+namespace tac {
+
+// Everything a conv-LIF kernel needs, resolved on the host from tac_layer_desc_t.
+struct LayerParams {
+  const uint32_t* spikes;   // packed input
+  const void* w;            // prepared weights
+  const float* bias;        // [Cout] or nullptr
+  float* v_inout;           // [B][Cout][Ho][Wo] or nullptr
+  uint32_t* out;            // packed output
+  float* v_trace;           // [T_out][B][Cout][Ho][Wo] or nullptr
+  int T, B, Cin, H, W;      // H, W: size the convolution sees (after the pool)
+  int Cout, stride, Ho, Wo;
+  int Wwi;                  // words per stored input row (of the unpooled row when pool2)
+  int Hs;                   // stored input rows per channel (2H when pool2)
+  int Wwo;                  // words per output row
+  int K;                    // frames per group (1 for per-step)
+  int G;                    // groups = T / K = convolution stages
+  int n_lif;                // LIF steps per group: K for TAC-TP, else 1
+  int pool2;                // input needs the 2x2 mean pool
+  int bf16;                 // round A_k to bf16
+  float decay;              // membrane decay per LIF step: beta^K for TAC, else beta
+  float theta;
+  float wj[TAC_MAX_K];      // aggregation weights beta^(K-1-j), Eq. 2
+};
+
+// direct (vector-FMA) kernel family: any shape
+size_t direct_weight_bytes(const tac_layer_desc_t& d);
+hipError_t direct_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s);
+hipError_t direct_launch(const LayerParams& p, hipStream_t s);
+
+// MFMA (bf16 implicit-GEMM) kernel family: restricted shapes
+bool mfma_supported(const tac_layer_desc_t& d);
+size_t mfma_weight_bytes(const tac_layer_desc_t& d);
+hipError_t mfma_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s);
+hipError_t mfma_launch(const LayerParams& p, hipStream_t s);
+
+hipError_t pack_launch(const uint8_t* dense, uint32_t* packed, int64_t rows, int W, hipStream_t s);
+hipError_t unpack_launch(const uint32_t* packed, uint8_t* dense, int64_t rows, int W, hipStream_t s);
+
+}  // namespace tac

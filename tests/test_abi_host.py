@@ -1,0 +1,122 @@
+"""Host-side behaviour of the C-ABI library that needs no GPU: it loads, exports every
+symbol the header declares, validates arguments before launching anything, and does the
+shape / size / call-count accounting the paper's tables imply."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_13810_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _desc(**kw):
+    base = dict(T=8, B=2, Cin=3, H=16, W=20, Cout=8, K=2, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE)
+    base.update(kw)
+    return api.make_desc(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "tac.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(tac_[a-z_]+)\s*\(", header))
+    assert declared == set(api.EXPORTS)
+    L = api.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_desc_struct_layout_matches_header():
+    assert ctypes.sizeof(api.tac_layer_desc_t) == 15 * 4 + 2 * 4
+
+
+@pytest.mark.parametrize("mode,K,T_out", [(api.TAC_PER_STEP, 4, 8), (api.TAC_COLLAPSE, 4, 2),
+                                          (api.TAC_PRESERVE, 4, 8), (api.TAC_COLLAPSE, 1, 8)])
+def test_out_shape_collapse_vs_preserve(mode, K, T_out):
+    # Alg. 1 returns T/K steps, Alg. 2 and the per-step layer T steps (App. B)
+    assert api.tac_out_shape(_desc(mode=mode, K=K)) == (T_out, 16, 20)
+    assert api.tac_out_shape(_desc(mode=mode, K=K, stride=2, H=128, W=128))[1:] == (64, 64)
+    assert api.tac_out_shape(_desc(mode=mode, K=K, stride=2, H=5, W=7))[1:] == (3, 4)
+
+
+def test_cascade_of_collapse_layers_divides_T():
+    # App. B: TAC cascades to T / prod K_l, TAC-TP keeps T
+    T = 16
+    for K in (2, 2, 2, 2):
+        T = api.tac_out_shape(_desc(T=T, K=K, mode=api.TAC_COLLAPSE))[0]
+    assert T == 1
+    T = 16
+    for K in (2, 4, 8):
+        T = api.tac_out_shape(_desc(T=T, K=K, mode=api.TAC_PRESERVE))[0]
+    assert T == 16
+
+
+def test_packed_bytes():
+    assert api.tac_packed_bytes(32, 256, 128, 64, 64) == 512 * 1024 * 1024
+    assert api.tac_packed_bytes(4, 4, 1, 28, 28) == 4 * 4 * 28 * 4
+    assert api.tac_packed_bytes(1, 1, 1, 1, 33) == 8
+    assert api.tac_packed_bytes(0, 1, 1, 1, 1) == 0
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(T=0), api.TAC_ERR_BAD_SHAPE), (dict(Cout=-1), api.TAC_ERR_BAD_SHAPE),
+    (dict(kh=5), api.TAC_ERR_BAD_SHAPE), (dict(stride=3), api.TAC_ERR_BAD_SHAPE), (dict(pad=0), api.TAC_ERR_BAD_SHAPE),
+    (dict(K=3), api.TAC_ERR_BAD_K), (dict(K=0), api.TAC_ERR_BAD_K), (dict(T=64, K=64), api.TAC_ERR_BAD_K),
+    (dict(beta=1.5), api.TAC_ERR_BAD_PARAM), (dict(beta=float("nan")), api.TAC_ERR_BAD_PARAM),
+    (dict(theta=0.0), api.TAC_ERR_BAD_PARAM), (dict(theta=float("inf")), api.TAC_ERR_BAD_PARAM),
+    (dict(mode=7), api.TAC_ERR_BAD_PARAM), (dict(precision=3), api.TAC_ERR_BAD_PARAM),
+    (dict(in_format=2), api.TAC_ERR_BAD_PARAM), (dict(kernel=9), api.TAC_ERR_BAD_PARAM),
+    (dict(B=70000), api.TAC_ERR_BAD_SHAPE),
+])
+def test_invalid_descriptions_are_rejected_before_any_launch(kw, status):
+    L = api.lib()
+    d = _desc(**kw)
+    assert L.tac_out_shape(ctypes.byref(d), None, None, None) == status
+    assert L.tac_select_kernel(ctypes.byref(d)) == status
+    assert L.tac_prepared_weight_bytes(ctypes.byref(d)) == 0
+    fake = ctypes.c_void_p(0x1000)
+    assert L.tac_conv_lif(ctypes.byref(d), fake, fake, None, None, fake, None, None) == status
+    assert L.tac_prepare_weights(ctypes.byref(d), fake, fake, None) == status
+    assert api.tac_status_string(status) not in ("ok", "unknown status")
+
+
+def test_per_step_ignores_K():
+    d = _desc(mode=api.TAC_PER_STEP, K=3)
+    assert api.tac_out_shape(d)[0] == 8
+
+
+def test_null_and_alignment_errors():
+    L = api.lib()
+    d = _desc()
+    fake, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1002)
+    assert L.tac_out_shape(None, None, None, None) == api.TAC_ERR_NULL
+    assert L.tac_conv_lif(ctypes.byref(d), None, fake, None, None, fake, None, None) == api.TAC_ERR_NULL
+    assert L.tac_conv_lif(ctypes.byref(d), fake, None, None, None, fake, None, None) == api.TAC_ERR_NULL
+    assert L.tac_conv_lif(ctypes.byref(d), fake, fake, None, None, None, None, None) == api.TAC_ERR_NULL
+    assert L.tac_conv_lif(ctypes.byref(d), odd, fake, None, None, fake, None, None) == api.TAC_ERR_ALIGN
+    assert L.tac_conv_lif(ctypes.byref(d), fake, fake, None, odd, fake, None, None) == api.TAC_ERR_ALIGN
+    assert L.tac_prepare_weights(ctypes.byref(d), None, fake, None) == api.TAC_ERR_NULL
+    assert L.tac_prepare_weights(ctypes.byref(d), fake, ctypes.c_void_p(0x1004), None) == api.TAC_ERR_ALIGN
+    assert L.tac_pack_spikes(None, fake, 1, 1, None) == api.TAC_ERR_NULL
+    assert L.tac_pack_spikes(fake, fake, 0, 1, None) == api.TAC_ERR_BAD_SHAPE
+    assert L.tac_unpack_spikes(fake, fake, 1, 0, None) == api.TAC_ERR_BAD_SHAPE
+    assert L.tac_get_counters(None, None) == api.TAC_ERR_NULL
+
+
+def test_kernel_selection():
+    # fp32 always runs on the vector-FMA kernel; forcing the matrix-core kernel on it is an error
+    d = _desc(precision=api.TAC_FP32)
+    assert api.tac_select_kernel(d) == api.TAC_KERNEL_DIRECT
+    d.kernel = api.TAC_KERNEL_MFMA
+    assert api.lib().tac_select_kernel(ctypes.byref(d)) == api.TAC_ERR_UNSUPPORTED
+    d = _desc(precision=api.TAC_BF16, kernel=api.TAC_KERNEL_DIRECT)
+    assert api.tac_select_kernel(d) == api.TAC_KERNEL_DIRECT
+    assert api.tac_prepared_weight_bytes(d) == 8 * 3 * 9 * 4
+
+
+def test_status_strings():
+    assert api.tac_status_string(0) == "ok"
+    assert api.tac_status_string(-99) == "unknown status"
+    assert api.tac_last_error() == ""
