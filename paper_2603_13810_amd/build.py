@@ -22,7 +22,7 @@ def hipcc() -> str:
 def build(verbose: bool = True) -> str:
     """Compile every HIP source for gfx950 and link the shared library.  Always recompiles."""
     objs = []
-    flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
+    flags = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-I", INCLUDE, "-I", CSRC,
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
              "-Wall", "-Wno-unused-command-line-argument"]
     procs = []

@@ -1,8 +1,408 @@
-// MFMA kernel family (bf16 implicit GEMM) -- placeholder until the kernel lands.
+// MFMA kernel family: the conv-LIF layer as a bf16 implicit GEMM on the matrix cores,
+// membrane-stationary over time.
+//
+// GEMM view of one convolution stage (Alg. 1 / Alg. 2, "Y_k <- Conv2d(A_k, W)"):
+//     Y^T[cout][pixel] = sum over (tap, cin) of  W[cout][cin][tap] * A_k[cin][pixel + tap]
+// The kernel W is the MFMA A-operand (rows = cout) and the aggregated frame is the
+// B-operand (columns = pixels), so one v_mfma_f32_32x32x16_bf16 result holds 32 cout x 32
+// x-consecutive pixels with the pixels along the lanes: a wave ballot of "V >= theta" is
+// then directly two packed output words.
+//
+// One workgroup = 8 wavefronts owns a tile of 4 output rows x 64 pixels x 128 output
+// channels of one sample for the WHOLE call: its membrane V (fp32) never leaves the
+// registers between the first and the last timestep.  Wave w handles output row (w & 3) and
+// the 64-channel half (w >> 2): 2 x 2 MFMA tiles, 64 accumulator + 64 membrane registers.
+//
+// Per group of K frames and per chunk of 16 input channels:
+//   loader   wave-uniform 64-bit row masks (one packed input row = 64 pixels) come in
+//            through scalar loads; "lane x gets bit x" is a v_cndmask on the mask, so the
+//            decay-weighted aggregate A_k (Eq. 2) costs two vector ops per frame per 64
+//            pixels; it is rounded once to bf16 and written to LDS as [k-half][row][x][8 cin]
+//            (zero columns left and right are the padding), never to HBM;
+//   weights  the chunk's 9 taps x 128 cout x 16 cin, pre-arranged in MFMA operand order, are
+//            copied global -> LDS one chunk ahead;
+//   MFMA     9 taps x 4 MFMAs per wave, operands read from LDS as conflict-free 16-byte
+//            fragments; im2col is only the (ky, kx) offset in the fragment address.
+// After the last chunk: LIF epilogue on the accumulators (one step for TAC / per-step, K
+// steps with the same Y_k for TAC-TP), ballot, packed stores.
+#include <type_traits>
+
 #include "tac_internal.h"
+
 namespace tac {
-bool mfma_supported(const tac_layer_desc_t&) { return false; }
-size_t mfma_weight_bytes(const tac_layer_desc_t&) { return 0; }
-hipError_t mfma_prepare(const tac_layer_desc_t&, const float*, void*, hipStream_t) { return hipErrorNotSupported; }
-hipError_t mfma_launch(const LayerParams&, hipStream_t) { return hipErrorNotSupported; }
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef const __attribute__((address_space(4))) uint64_t* const_u64_ptr;
+
+constexpr int kThreads = 256;
+constexpr int kRows = 4;                       // output rows per tile
+constexpr int kInRows = kRows + 2;             // with the 3x3 halo
+constexpr int kW = 64;                         // row width handled by this kernel
+constexpr int kXP = kW + 2;                    // padded row in LDS
+constexpr int kCoutTile = 128;
+constexpr int kChunk = 16;                     // input channels per MFMA k-step
+constexpr int kAHalf = kInRows * kXP * 16;     // bytes: one k-half plane [row][xp][8 bf16]
+constexpr int kABuf = 2 * kAHalf;
+constexpr int kWTap = (kCoutTile / 32) * 64 * 16;   // bytes of one tap: [mc][lane][8 bf16]
+constexpr int kWBuf = 9 * kWTap;
+constexpr int kWUnits = kWBuf / 16;            // 16-byte units per chunk of weights
+constexpr int kWLoads = (kWUnits + kThreads - 1) / kThreads;
+constexpr int kLdsA = 0;
+constexpr int kLdsW = 2 * kABuf;
+constexpr int kLdsBias = kLdsW + 2 * kWBuf;
+constexpr int kLdsBytes = kLdsBias + kCoutTile * 4;
+
+struct MfmaParams {
+  const uint32_t* __restrict__ spikes;
+  const uint8_t* __restrict__ w;       // prepared: [cout_tile][chunk][tap][mc][lane][8] bf16
+  const float* __restrict__ bias;
+  float* __restrict__ v_inout;
+  uint32_t* __restrict__ out;
+  float* __restrict__ v_trace;
+  int B, Cin, H, Cout, K, G, n_lif, row_tiles;
+  float decay, theta;
+  float wj[TAC_MAX_K];
+};
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  f32x2 f = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // v_cvt_pk_bf16_f32, nearest even
+}
+
+template <int LANE>
+__device__ __forceinline__ uint32_t write_lane(uint32_t old, uint32_t sval) {
+  // vdst[LANE] = sval (wave-uniform); other lanes keep `old`.  The s_nop covers the two wait
+  // states this chip needs between a vector instruction that wrote the SGPR (a compare, or a
+  // spill reload) and a vector instruction that reads it: the assembler text is opaque to the
+  // compiler's hazard pass.
+  uint32_t r;
+  asm volatile("s_nop 1\n\tv_writelane_b32 %0, %1, %2" : "=v"(r) : "s"(sval), "n"(LANE), "0"(old));
+  return r;
+}
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+// One LIF step on a wave's 2 x 2 MFMA tiles: V <- decay V + Y, spike iff V >= theta,
+// subtractive reset.  The 64 ballots of the step are gathered, one 32-bit half per lane,
+// into two store registers: lane L = (r << 2) | (hi << 1) | np of word[mc] holds the packed
+// word of cout 32 mc + 8 (r/4) + 4 hi + r%4, x-block np.
+template <bool TRACE>
+__device__ __forceinline__ void lif_step(float (&V)[4][2][16], const f32x16 (&acc)[4][2], float decay, float theta,
+                                         uint32_t (&word)[4], float* __restrict__ trace_wave, size_t plane, uint32_t lane_bytes) {
+  static_for<0, 4>([&](auto mc_) {
+    constexpr int mc = decltype(mc_)::value;
+    static_for<0, 2>([&](auto np_) {
+      constexpr int np = decltype(np_)::value;
+      static_for<0, 16>([&](auto r_) {
+        constexpr int r = decltype(r_)::value;
+        const float v = fmaf(decay, V[mc][np][r], acc[mc][np][r]);
+        const bool fire = v >= theta;
+        const uint64_t m = __builtin_amdgcn_ballot_w64(fire);
+        word[mc] = write_lane<(r << 2) | np>(word[mc], (uint32_t)m);
+        word[mc] = write_lane<(r << 2) | 2 | np>(word[mc], (uint32_t)(m >> 32));
+        V[mc][np][r] = fire ? v - theta : v;
+        if constexpr (TRACE)
+          *reinterpret_cast<float*>(reinterpret_cast<char*>(trace_wave) + ((size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane + np * 32) * 4 + lane_bytes) = v;
+        if constexpr ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // keep only a few ballots alive
+      });
+    });
+  });
+}
+
+// Aggregate one loader item: 4 input channels x one input row (64 pixels) x K frames,
+// and write the 4 bf16 values of lane x to the LDS tile of the NEXT chunk.
+template <int KT>
+__device__ __forceinline__ void load_item(const MfmaParams& p, uint8_t* a_next, int item, int lane,
+                                          int b, int g, int c, int y0) {
+  const int r = item >> 2, q = item & 3;
+  const int iy = y0 - 1 + r;
+  const int K = KT > 0 ? KT : p.K;
+  float val[4] = {0.f, 0.f, 0.f, 0.f};
+  if (iy >= 0 && iy < p.H) {                                   // wave-uniform; outside = zero padding
+    const_u64_ptr sp = (const_u64_ptr)(p.spikes);
+    const size_t chan_stride = (size_t)p.H;                    // in 64-bit rows
+    const size_t t_stride = (size_t)p.B * p.Cin * chan_stride;
+    const size_t base = ((size_t)(g * K) * p.B + b) * p.Cin * chan_stride +
+                        (size_t)(c * kChunk + q * 4) * chan_stride + iy;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float a = 0.f;
+      if (KT > 0) {
+#pragma unroll
+        for (int j = 0; j < KT; ++j) {
+          const uint64_t m = sp[base + j * t_stride + e * chan_stride];
+          a += __builtin_amdgcn_inverse_ballot_w64(m) ? p.wj[j] : 0.f;
+        }
+      } else {
+        for (int j = 0; j < K; ++j) {
+          const uint64_t m = sp[base + j * t_stride + e * chan_stride];
+          a += __builtin_amdgcn_inverse_ballot_w64(m) ? p.wj[j] : 0.f;
+        }
+      }
+      val[e] = a;
+    }
+  }
+  uint2 pk = make_uint2(pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3]));
+  *reinterpret_cast<uint2*>(a_next + (q >> 1) * kAHalf + (r * kXP + lane + 1) * 16 + (q & 1) * 8) = pk;
+}
+
+template <int KT>
+__global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int row = wave;                        // output row of this wave inside the tile
+  const int b = blockIdx.z;
+  const int co_tile = blockIdx.y;
+  const int y0 = blockIdx.x * kRows;
+  const int y = y0 + row;
+  const bool row_ok = y < p.H;                 // wave-uniform
+  const int NC = p.Cin / kChunk;
+  const int n = lane & 31, h = lane >> 5;
+  const int Ho = p.H;
+  const int co_wave = co_tile * kCoutTile;
+
+  // zero padding columns of both A buffers (never written again)
+  if (tid < 2 * 2 * kInRows * 2) {
+    const int col = tid & 1, rr = (tid >> 1) % kInRows, hh = (tid >> 1) / kInRows % 2, bb = (tid >> 1) / (2 * kInRows);
+    *reinterpret_cast<u32x4*>(lds + kLdsA + bb * kABuf + hh * kAHalf + (rr * kXP + col * (kXP - 1)) * 16) = u32x4{0, 0, 0, 0};
+  }
+  if (tid < kCoutTile)
+    reinterpret_cast<float*>(lds + kLdsBias)[tid] = p.bias ? p.bias[co_tile * kCoutTile + tid] : 0.f;
+
+  // membrane, MFMA result layout: register r of tile (mc, np), lane -> cout = 32 mc + 8 (r/4) + 4 h + r%4, x = 32 np + n
+  float V[4][2][16];
+  f32x16 acc[4][2];
+  const size_t plane = (size_t)Ho * kW;                               // elements per (b, cout)
+  // wave-uniform base of this wave's 64 channels at row y; the lane adds 4 h channels + n
+  const size_t v_wave = ((size_t)b * p.Cout + co_wave) * plane + (size_t)y * kW;
+  uint32_t v_lane = (uint32_t)(4 * h * plane + n) * 4u;               // bytes
+  if (p.v_inout && row_ok) {
+    const char* vb = reinterpret_cast<const char*>(p.v_inout + v_wave);
+    static_for<0, 4>([&](auto mc_) { static_for<0, 2>([&](auto np_) { static_for<0, 16>([&](auto r_) {
+      constexpr int mc = decltype(mc_)::value, np = decltype(np_)::value, r = decltype(r_)::value;
+      V[mc][np][r] = *reinterpret_cast<const float*>(vb + ((size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane + np * 32) * 4 + v_lane);
+    }); }); });
+  } else {
+#pragma unroll
+    for (int mc = 0; mc < 4; ++mc)
+#pragma unroll
+      for (int np = 0; np < 2; ++np)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) V[mc][np][r] = 0.f;
+  }
+
+  const uint8_t* wsrc = p.w + (size_t)co_tile * NC * kWBuf;
+
+  // ---- prologue: chunk 0 of group 0 into buffer 0
+  {
+    for (int i = 0; i < 6; ++i) load_item<KT>(p, lds + kLdsA, wave + 4 * i, lane, b, 0, 0, y0);
+#pragma unroll
+    for (int i = 0; i < kWLoads; ++i) {
+      const int u = tid + i * kThreads;
+      if (u < kWUnits)
+        *reinterpret_cast<u32x4*>(lds + kLdsW + u * 16) = *reinterpret_cast<const u32x4*>(wsrc + (size_t)u * 16);
+    }
+  }
+  __syncthreads();
+
+  // per-lane byte offsets of the fragments
+  const int a_frag_off = h * kAHalf + (row * kXP + n) * 16;          // + (ky*kXP + kx + 32 np)*16
+  const int w_frag_off = lane * 16;                                  // + tap*kWTap + mc*1024
+  // per-lane output word offset for the packed store: lane L = (r << 2) | (hi << 1) | np
+  const int st_r = lane >> 2, st_hi = (lane >> 1) & 1, st_np = lane & 1;
+  const int st_co = 8 * (st_r >> 2) + 4 * st_hi + (st_r & 3);         // + 32 mc
+  const size_t out_plane = (size_t)Ho * 2;                            // words per (step, b, cout)
+  const size_t out_lane = ((size_t)b * p.Cout + co_wave + st_co) * out_plane + (size_t)y * 2 + st_np;
+  const size_t out_step = (size_t)p.B * p.Cout * out_plane;
+
+  const int total = p.G * NC;
+  int s = 0;
+  for (int g = 0; g < p.G; ++g) {
+#pragma unroll
+    for (int mc = 0; mc < 4; ++mc)
+#pragma unroll
+      for (int np = 0; np < 2; ++np)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mc][np][r] = 0.f;
+
+    for (int c = 0; c < NC; ++c, ++s) {
+      const int cur = s & 1;
+      const uint8_t* a_cur = lds + kLdsA + cur * kABuf;
+      const uint8_t* w_cur = lds + kLdsW + cur * kWBuf;
+      uint8_t* a_next = lds + kLdsA + (cur ^ 1) * kABuf;
+      uint8_t* w_next = lds + kLdsW + (cur ^ 1) * kWBuf;
+      const bool has_next = s + 1 < total;
+      int gn = g, cn = c + 1;
+      if (cn == NC) { cn = 0; gn = g + 1; }
+
+      // weights of the next chunk: global -> registers now, registers -> LDS after the MFMAs
+      u32x4 wreg[kWLoads];
+      if (has_next) {
+        const uint8_t* wn = wsrc + (size_t)cn * kWBuf;
+#pragma unroll
+        for (int i = 0; i < kWLoads; ++i) {
+          const int u = tid + i * kThreads;
+          if (u < kWUnits) wreg[i] = *reinterpret_cast<const u32x4*>(wn + (size_t)u * 16);
+        }
+      }
+
+      // software pipeline over the 9 taps: fragments of tap+1 are fetched while tap multiplies
+      bf16x8 wf[2][4], af[2][2];
+      auto fetch = [&](int tap, int slot) {
+        const int ky = tap / 3, kx = tap % 3;
+#pragma unroll
+        for (int mc = 0; mc < 4; ++mc)
+          wf[slot][mc] = *reinterpret_cast<const bf16x8*>(w_cur + tap * kWTap + mc * 1024 + w_frag_off);
+#pragma unroll
+        for (int np = 0; np < 2; ++np)
+          af[slot][np] = *reinterpret_cast<const bf16x8*>(a_cur + a_frag_off + (ky * kXP + kx + 32 * np) * 16);
+      };
+      fetch(0, 0);
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        const int slot = tap & 1;
+        if (tap < 8) fetch(tap + 1, slot ^ 1);
+#pragma unroll
+        for (int mc = 0; mc < 4; ++mc)
+#pragma unroll
+          for (int np = 0; np < 2; ++np)
+            acc[mc][np] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][mc], af[slot][np], acc[mc][np], 0, 0, 0);
+        if (has_next && tap < 6) load_item<KT>(p, a_next, wave + 4 * tap, lane, b, gn, cn, y0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+
+      if (has_next) {
+#pragma unroll
+        for (int i = 0; i < kWLoads; ++i) {
+          const int u = tid + i * kThreads;
+          if (u < kWUnits) *reinterpret_cast<u32x4*>(w_next + u * 16) = wreg[i];
+        }
+      }
+      __syncthreads();
+    }
+
+    // ---- LIF epilogue on Y_k = acc + bias
+    const float* bias_lds = reinterpret_cast<const float*>(lds + kLdsBias);
+    if (p.bias) {
+#pragma unroll
+      for (int mc = 0; mc < 4; ++mc)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float bv = bias_lds[mc * 32 + 8 * (r >> 2) + 4 * h + (r & 3)];
+          acc[mc][0][r] += bv;
+          acc[mc][1][r] += bv;
+        }
+    }
+    for (int j = 0; j < p.n_lif; ++j) {
+      const size_t step = (size_t)g * p.n_lif + j;
+      uint32_t word[4] = {0u, 0u, 0u, 0u};
+      if (p.v_trace && row_ok) {
+        float* tl = p.v_trace + step * ((size_t)p.B * p.Cout * plane) + v_wave;
+        size_t plane_l = plane;
+        asm volatile("" : "+s"(plane_l));       // keep the trace addresses out of the loop preheader
+        lif_step<true>(V, acc, p.decay, p.theta, word, tl, plane_l, v_lane);
+      } else {
+        lif_step<false>(V, acc, p.decay, p.theta, word, nullptr, plane, v_lane);
+      }
+      if (row_ok) {
+#pragma unroll
+        for (int mc = 0; mc < 4; ++mc) p.out[step * out_step + out_lane + mc * 32 * out_plane] = word[mc];
+      }
+    }
+  }
+
+  if (p.v_inout && row_ok) {
+    size_t plane_l = plane;                   // opaque copy: the 128 addresses below are formed here,
+    asm volatile("" : "+s"(plane_l));         // not before the time loop (they would not fit in registers)
+    char* vb = reinterpret_cast<char*>(p.v_inout + v_wave);
+    static_for<0, 4>([&](auto mc_) { static_for<0, 2>([&](auto np_) { static_for<0, 16>([&](auto r_) {
+      constexpr int mc = decltype(mc_)::value, np = decltype(np_)::value, r = decltype(r_)::value;
+      *reinterpret_cast<float*>(vb + ((size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane_l + np * 32) * 4 + v_lane) = V[mc][np][r];
+    }); }); });
+  }
+}
+
+// OIHW fp32 -> [cout_tile][chunk][tap][mc][lane][8] bf16, the order the MFMA A-operand
+// fragments are read in: lane l of block mc holds cout 32 mc + l%32, cin 8 (l/32) .. +7.
+__global__ void mfma_prepare_kernel(const float* __restrict__ w, uint32_t* __restrict__ out, int Cin, int Cout) {
+  const int NC = Cin / kChunk;
+  const int total = (Cout / kCoutTile) * NC * 9 * 4 * 64 * 4;      // one thread per bf16 pair
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  int t = i;
+  const int e2 = t & 3; t >>= 2;
+  const int l = t & 63; t >>= 6;
+  const int mc = t & 3; t >>= 2;
+  const int tap = t % 9; t /= 9;
+  const int c = t % NC;
+  const int ct = t / NC;
+  const int co = ct * kCoutTile + mc * 32 + (l & 31);
+  const int ci = c * kChunk + (l >> 5) * 8 + e2 * 2;
+  const float a = w[((size_t)co * Cin + ci) * 9 + tap];
+  const float bb = w[((size_t)co * Cin + ci + 1) * 9 + tap];
+  out[i] = pack_bf16(a, bb);
+}
+
+template <int KT>
+hipError_t launch_kt(const MfmaParams& mp, dim3 grid, hipStream_t s) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_w64_kernel<KT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(mfma_w64_kernel<KT>, grid, dim3(kThreads), kLdsBytes, s, mp);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool mfma_supported(const tac_layer_desc_t& d) {
+  return d.precision == TAC_BF16 && d.in_format == TAC_IN_BITS && d.stride == 1 && d.W == kW &&
+         d.Cin % kChunk == 0 && d.Cout % kCoutTile == 0;
+}
+
+size_t mfma_weight_bytes(const tac_layer_desc_t& d) { return (size_t)d.Cout * d.Cin * 9 * 2; }
+
+hipError_t mfma_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s) {
+  const int total = d.Cout * d.Cin * 9 / 2;
+  hipLaunchKernelGGL(mfma_prepare_kernel, dim3((total + 255) / 256), dim3(256), 0, s, w_oihw,
+                     static_cast<uint32_t*>(w_prepared), d.Cin, d.Cout);
+  return hipGetLastError();
+}
+
+hipError_t mfma_launch(const LayerParams& p, hipStream_t s) {
+  MfmaParams mp;
+  mp.spikes = p.spikes; mp.w = static_cast<const uint8_t*>(p.w); mp.bias = p.bias; mp.v_inout = p.v_inout;
+  mp.out = p.out; mp.v_trace = p.v_trace;
+  mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.Cout = p.Cout; mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif;
+  mp.row_tiles = (p.H + kRows - 1) / kRows;
+  mp.decay = p.decay; mp.theta = p.theta;
+  for (int j = 0; j < TAC_MAX_K; ++j) mp.wj[j] = p.wj[j];
+  const dim3 grid(mp.row_tiles, p.Cout / kCoutTile, p.B);
+  switch (p.K) {
+    case 1: return launch_kt<1>(mp, grid, s);
+    case 2: return launch_kt<2>(mp, grid, s);
+    case 4: return launch_kt<4>(mp, grid, s);
+    case 8: return launch_kt<8>(mp, grid, s);
+    case 16: return launch_kt<16>(mp, grid, s);
+    default: return launch_kt<0>(mp, grid, s);
+  }
+}
+
 }  // namespace tac

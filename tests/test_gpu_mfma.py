@@ -1,0 +1,72 @@
+"""GPU parity of the bf16 MFMA implicit-GEMM kernel family against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_13810_amd import api, synth
+
+from gpu_util import check_layer, run_gpu, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+MODES = [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 2), (api.TAC_COLLAPSE, 4), (api.TAC_PRESERVE, 2),
+         (api.TAC_PRESERVE, 4), (api.TAC_COLLAPSE, 8), (api.TAC_PRESERVE, 16), (api.TAC_COLLAPSE, 3)]
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+@pytest.mark.parametrize("mode,K", MODES)
+def test_w64_tiles_and_ragged_rows(mode, K):
+    # 10 rows = two full 4-row tiles and a ragged one; 32 input channels = two k-chunks
+    r = _rng(100 + K)
+    T = 48 if K in (16, 3) else 8
+    s = (r.random((T, 2, 32, 10, 64)) < 0.15).astype(np.uint8)
+    w = synth.kaiming_normal(11, 128, 32)
+    bias = (r.standard_normal(128) * 0.1).astype(np.float32)
+    v0 = (r.standard_normal((2, 128, 10, 64)) * 0.3).astype(np.float32)
+    par, g, ref = check_layer(s, w, K=K, beta=0.9, theta=1.0, mode=mode, precision=api.TAC_BF16,
+                              bias=bias, v0=v0, expect_kernel=api.TAC_KERNEL_MFMA)
+    assert ref[0].sum() > 0
+    print("mfma", api.MODE_NAMES[mode], K, par, "| vs unrounded oracle:", par.plain)
+
+
+def test_two_cout_tiles_no_bias_no_state():
+    r = _rng(7)
+    s = (r.random((4, 1, 16, 4, 64)) < 0.2).astype(np.uint8)
+    w = synth.kaiming_normal(12, 256, 16)
+    par, g, ref = check_layer(s, w, K=2, beta=0.5, theta=1.0, mode=api.TAC_PRESERVE, precision=api.TAC_BF16,
+                              expect_kernel=api.TAC_KERNEL_MFMA)
+    g2 = run_gpu(s, w, K=2, beta=0.5, theta=1.0, mode=api.TAC_PRESERVE, precision=api.TAC_BF16, trace=False)
+    assert np.array_equal(g["packed"], g2["packed"])
+
+
+def test_mfma_matches_direct_kernel_on_same_operands():
+    # both kernel families round W and A_k to bf16 the same way; their spikes should agree
+    # except at near-threshold neurons (different fp32 summation order)
+    r = _rng(8)
+    s = (r.random((8, 1, 64, 8, 64)) < 0.1).astype(np.uint8)
+    w = synth.kaiming_normal(13, 128, 64)
+    kw = dict(K=4, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, precision=api.TAC_BF16)
+    a = run_gpu(s, w, kernel=api.TAC_KERNEL_MFMA, **kw)
+    b = run_gpu(s, w, kernel=api.TAC_KERNEL_DIRECT, **kw)
+    assert a["kernel"] == api.TAC_KERNEL_MFMA and b["kernel"] == api.TAC_KERNEL_DIRECT
+    assert np.abs(a["v_trace"][0] - b["v_trace"][0]).max() < 1e-4
+    assert (a["spikes"] != b["spikes"]).mean() < 1e-3
+
+
+def test_state_carry_and_K1_equivalence():
+    r = _rng(9)
+    s = (r.random((8, 1, 16, 8, 64)) < 0.2).astype(np.uint8)
+    w = synth.kaiming_normal(14, 128, 16)
+    kw = dict(beta=0.9, theta=1.0, precision=api.TAC_BF16)
+    ps = run_gpu(s, w, K=1, mode=api.TAC_PER_STEP, **kw)
+    for mode in (api.TAC_COLLAPSE, api.TAC_PRESERVE):
+        k1 = run_gpu(s, w, K=1, mode=mode, **kw)
+        assert np.array_equal(ps["packed"], k1["packed"]) and np.array_equal(ps["v_trace"], k1["v_trace"])
+    whole = run_gpu(s, w, K=2, mode=api.TAC_PRESERVE, **kw)
+    a = run_gpu(s[:4], w, K=2, mode=api.TAC_PRESERVE, **kw)
+    b = run_gpu(s[4:], w, K=2, mode=api.TAC_PRESERVE, v0=a["v_final"], **kw)
+    assert np.array_equal(np.concatenate([a["packed"], b["packed"]]), whole["packed"])
+    assert np.array_equal(b["v_final"], whole["v_final"])
