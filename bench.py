@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the conv-LIF layer (per-step / TAC / TAC-TP) on one MI355X.
+
+A "step" is one call of tac_conv_lif over the whole synthetic input of the workload
+(all T frames of all B samples, inputs already resident in HBM): spike loading, aggregation,
+convolution, LIF and packed output.  Prints ONE JSON line:
+
+  metric   spike-frames/s of the layer = B * T / latency (T is always the input T)
+  value    for the headline mode (default TAC, K = 4) on the roofline workload (cfg5)
+  roofline executed convolution FLOPs (2 B Ho Wo Cout Cin 9 T/K, the T/K stages the method
+           needs) / average kernel duration (HIP events on the launch stream) against the
+           dense bf16 MFMA peak
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
+  config.table  latency and speed-up over the per-step mode of the same kernel for every
+           mode and K of the workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3       # MI355X fp32 vector
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg3", "cfg5"])
+    ap.add_argument("--mode", default="TAC", choices=["per_step", "TAC", "TAC_TP"])
+    ap.add_argument("--K", type=int, default=4)
+    ap.add_argument("--rate", type=float, default=None, help="firing rate of the Bernoulli input (cfg5)")
+    ap.add_argument("--no-table", action="store_true", help="time only the headline mode")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--batch", type=int, default=None, help="override the batch size (debugging only)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2603_13810_amd import api, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    wl = synth.WORKLOADS[args.workload]
+    L = wl.layers[0]
+    B = args.batch or wl.B
+    T = wl.T
+    rate = args.rate if args.rate is not None else wl.rate
+    MODE = {"per_step": api.TAC_PER_STEP, "TAC": api.TAC_COLLAPSE, "TAC_TP": api.TAC_PRESERVE}
+
+    # ---- synthetic input, resident in HBM, packed by the library's own packer
+    Ww = (wl.W + 31) // 32
+    spikes = torch.empty((T, B, wl.C, wl.H, Ww), dtype=torch.int32, device=dev)
+    keep = {}                                    # dense frames of sample 0 for the CPU baseline
+    if wl.spikes == "bernoulli":
+        dense0 = np.empty((T, min(B, 2), wl.C, wl.H, wl.W), dtype=np.uint8)
+        for t in range(T):
+            fr = synth.bernoulli_device(wl.seed + t, B, wl.C, wl.H, wl.W, rate, dev)
+            api.tac_pack_spikes(fr, spikes[t])
+            dense0[t] = fr[:dense0.shape[1]].cpu().numpy()
+            del fr
+        keep["dense"] = dense0
+    else:
+        dense = wl.make_spikes(B=B)
+        for t in range(T):
+            api.tac_pack_spikes(torch.from_numpy(dense[t]).to(dev), spikes[t])
+        keep["dense"] = dense[:, :2]
+    w32 = wl.make_weights(0)
+    w_dev = torch.from_numpy(w32).to(dev)
+    torch.cuda.synchronize()
+
+    def make(mode, K):
+        d = api.make_desc(T, B, L.Cin, wl.H, wl.W, L.Cout, K=K, beta=wl.beta, theta=wl.theta, mode=mode,
+                          stride=L.stride, precision=api.TAC_BF16)
+        wp = api.tac_prepare_weights(d, w_dev)
+        T_out, Ho, Wo = api.tac_out_shape(d)
+        out = torch.empty((T_out, B, L.Cout, Ho, (Wo + 31) // 32), dtype=torch.int32, device=dev)
+        return d, wp, out, (T_out, Ho, Wo)
+
+    def time_mode(mode, K, steps, warmup):
+        d, wp, out, (T_out, Ho, Wo) = make(mode, K)
+        for _ in range(warmup):
+            api.tac_conv_lif(d, spikes, wp, None, None, out)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        t0 = time.perf_counter()
+        for a, b in evs:
+            a.record()
+            api.tac_conv_lif(d, spikes, wp, None, None, out)
+            b.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        kern_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        Kg = 1 if mode == api.TAC_PER_STEP else K
+        flops = 2.0 * B * Ho * Wo * L.Cout * L.Cin * 9 * (T // Kg)
+        fired = None
+        return dict(mode=api.MODE_NAMES[mode], K=Kg, ms=wall_ms, kernel_ms=kern_ms, flops=flops,
+                    kernel=("mfma" if api.tac_select_kernel(d) == api.TAC_KERNEL_MFMA else "direct"),
+                    frames_per_s=B * T / (wall_ms * 1e-3), tflops=flops / (kern_ms * 1e-3) / 1e12,
+                    out_bytes=out.numel() * 4)
+
+    head = time_mode(MODE[args.mode], args.K, args.steps, args.warmup)
+    table = []
+    if not args.no_table:
+        base = time_mode(api.TAC_PER_STEP, 1, max(3, args.steps // 4), 2)
+        table.append(dict(mode="per_step", K=1, ms=round(base["kernel_ms"], 4), speedup=1.0,
+                          tflops=round(base["tflops"], 1)))
+        for K in wl.Ks:
+            if K == 1:
+                continue
+            for mode in (api.TAC_COLLAPSE, api.TAC_PRESERVE):
+                r = time_mode(mode, K, max(3, args.steps // 4), 2)
+                table.append(dict(mode=r["mode"], K=K, ms=round(r["kernel_ms"], 4),
+                                  speedup=round(base["kernel_ms"] / r["kernel_ms"], 3), tflops=round(r["tflops"], 1)))
+
+    is_mfma = head["kernel"] == "mfma"
+    peak = PEAK_BF16_TFLOPS if is_mfma else PEAK_FP32_TFLOPS
+    roofline = dict(bound="mfma" if is_mfma else "alu", achieved=round(head["tflops"], 2), peak=peak,
+                    unit="TFLOP/s", frac=round(head["tflops"] / peak, 4), traffic=None,
+                    kernel_ms=round(head["kernel_ms"], 4),
+                    algorithmic_bytes=int(spikes.numel() * 4 + head["out_bytes"]))
+
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        from oracle import PER_STEP, TAC, TAC_TP
+        omode = {"per_step": PER_STEP, "TAC": TAC, "TAC_TP": TAC_TP}[args.mode]
+        Kc = 1 if args.mode == "per_step" else args.K
+        Tc = T
+        sl = keep["dense"][:Tc]
+        nth = oracle.max_threads()
+        t0 = time.perf_counter()
+        oracle.conv_lif(sl, w32.astype(np.float64), K=Kc, beta=wl.beta, theta=wl.theta, mode=omode,
+                        stride=L.stride, nthreads=nth)
+        dt = time.perf_counter() - t0
+        cpu = dict(value=round(sl.shape[0] * sl.shape[1] / dt, 3), unit="spike-frames/s", cores=nth, kind="oracle",
+                   sample="%d samples x %d frames of %s, mode %s K=%d, %.1f s wall" % (sl.shape[1], Tc, wl.name, args.mode, Kc, dt))
+
+    line = {
+        "metric": "spike-frames/s per conv-LIF layer",
+        "value": round(head["frames_per_s"], 1),
+        "unit": "spike-frames/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(head["ms"], 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: conv-LIF 3x3 %d->%d, %dx%d, stride %d, B=%d, T=%d, Bernoulli rate %s, beta=%.2f"
+                               % (wl.name, L.Cin, L.Cout, wl.H, wl.W, L.stride, B, T, rate, wl.beta),
+                   "mode": args.mode, "K": head["K"], "kernel": head["kernel"],
+                   "paper_context": "TAC training speed-ups 13.8x (Apple M3 Max) and 11.0x (NVIDIA V100), other hardware",
+                   "table": table},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -103,7 +103,7 @@ void oracle_conv2d(const double* X, const double* Wt, const double* bias, double
   const int Wo = (W + 2 * pad - kw) / stride + 1;
   (void)nthreads;
 #ifdef _OPENMP
-#pragma omp parallel for num_threads(nthreads > 1 ? nthreads : 1) schedule(static)
+#pragma omp parallel for collapse(2) num_threads(nthreads > 1 ? nthreads : 1) schedule(static)
 #endif
   for (int b = 0; b < B; ++b)
     for (int co = 0; co < Cout; ++co)

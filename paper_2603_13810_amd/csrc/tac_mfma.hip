@@ -8,23 +8,31 @@
 // x-consecutive pixels with the pixels along the lanes: a wave ballot of "V >= theta" is
 // then directly two packed output words.
 //
-// One workgroup = 8 wavefronts owns a tile of 4 output rows x 64 pixels x 128 output
-// channels of one sample for the WHOLE call: its membrane V (fp32) never leaves the
-// registers between the first and the last timestep.  Wave w handles output row (w & 3) and
-// the 64-channel half (w >> 2): 2 x 2 MFMA tiles, 64 accumulator + 64 membrane registers.
+// One workgroup = 4 wavefronts (one per SIMD, 512 registers each) owns a tile of 4 output
+// rows x 64 pixels x 128 output channels of one sample for the WHOLE call: its membrane V
+// (fp32) never leaves the registers between the first and the last timestep.  Wave w handles
+// output row w: 4 x 2 MFMA tiles, 128 accumulator + 128 membrane registers.
 //
-// Per group of K frames and per chunk of 16 input channels:
-//   loader   wave-uniform 64-bit row masks (one packed input row = 64 pixels) come in
-//            through scalar loads; "lane x gets bit x" is a v_cndmask on the mask, so the
-//            decay-weighted aggregate A_k (Eq. 2) costs two vector ops per frame per 64
-//            pixels; it is rounded once to bf16 and written to LDS as [k-half][row][x][8 cin]
-//            (zero columns left and right are the padding), never to HBM;
+// Per group of K frames and per chunk of 16 input channels, everything one chunk ahead of
+// the MFMAs that consume it:
+//   staging  the chunk's packed input words (16 cin x 6 haloed rows x 2 words x K frames)
+//            are copied global -> LDS, rows outside the image as zero words;
+//   loader   lane x reads the word that holds its pixel (a two-address broadcast LDS read,
+//            all K frames of it at once), extracts its bit and accumulates the decay weight
+//            as a 24-bit fixed-point integer, one v_bfe + one v_mad per frame; the aggregate
+//            A_k (Eq. 2) is converted once, rounded to bf16 and written to LDS as
+//            [k-half][row][x][8 cin] with zero columns left and right as the padding; it is
+//            never written to HBM;
 //   weights  the chunk's 9 taps x 128 cout x 16 cin, pre-arranged in MFMA operand order, are
-//            copied global -> LDS one chunk ahead;
-//   MFMA     9 taps x 4 MFMAs per wave, operands read from LDS as conflict-free 16-byte
+//            copied global -> LDS;
+//   MFMA     9 taps x 8 MFMAs per wave, operands read from LDS as conflict-free 16-byte
 //            fragments; im2col is only the (ky, kx) offset in the fragment address.
 // After the last chunk: LIF epilogue on the accumulators (one step for TAC / per-step, K
 // steps with the same Y_k for TAC-TP), ballot, packed stores.
+//
+// Fixed point: the aggregate is formed as A' = sum_j bit_j * round(beta^(K-1-j) 2^23), an
+// integer below 2^28, and the prepared weights carry the factor 2^-23 (a power of two, so
+// the bf16 rounding of both operands is unchanged and the products are the same).
 #include <type_traits>
 
 #include "tac_internal.h"
@@ -38,36 +46,42 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef const __attribute__((address_space(4))) uint64_t* const_u64_ptr;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kThreads = 256;
-constexpr int kRows = 4;                       // output rows per tile
+constexpr int kRows = 4;                       // output rows per tile = waves per workgroup
 constexpr int kInRows = kRows + 2;             // with the 3x3 halo
 constexpr int kW = 64;                         // row width handled by this kernel
 constexpr int kXP = kW + 2;                    // padded row in LDS
 constexpr int kCoutTile = 128;
+constexpr int kMC = kCoutTile / 32;            // MFMA row blocks per wave
 constexpr int kChunk = 16;                     // input channels per MFMA k-step
 constexpr int kAHalf = kInRows * kXP * 16;     // bytes: one k-half plane [row][xp][8 bf16]
 constexpr int kABuf = 2 * kAHalf;
-constexpr int kWTap = (kCoutTile / 32) * 64 * 16;   // bytes of one tap: [mc][lane][8 bf16]
+constexpr int kWTap = kMC * 64 * 16;           // bytes of one tap: [mc][lane][8 bf16]
 constexpr int kWBuf = 9 * kWTap;
 constexpr int kWUnits = kWBuf / 16;            // 16-byte units per chunk of weights
 constexpr int kWLoads = (kWUnits + kThreads - 1) / kThreads;
+constexpr int kWordsPerFrame = kChunk * kInRows * 2;   // staged dwords per chunk and frame
+constexpr int kFixShift = 23;                  // fixed-point scale of the aggregation weights
 constexpr int kLdsA = 0;
-constexpr int kLdsW = 2 * kABuf;
+constexpr int kLdsW = kLdsA + 2 * kABuf;
 constexpr int kLdsBias = kLdsW + 2 * kWBuf;
-constexpr int kLdsBytes = kLdsBias + kCoutTile * 4;
+constexpr int kLdsWords = kLdsBias + kCoutTile * 4;     // two staging buffers follow
+
+__host__ __device__ constexpr int words_buf_bytes(int K) { return kWordsPerFrame * K * 4; }
+__host__ __device__ constexpr int lds_bytes(int K) { return kLdsWords + 2 * words_buf_bytes(K); }
 
 struct MfmaParams {
   const uint32_t* __restrict__ spikes;
-  const uint8_t* __restrict__ w;       // prepared: [cout_tile][chunk][tap][mc][lane][8] bf16
+  const uint8_t* __restrict__ w;       // prepared: [cout_tile][chunk][tap][mc][lane][8] bf16, scaled 2^-23
   const float* __restrict__ bias;
   float* __restrict__ v_inout;
   uint32_t* __restrict__ out;
   float* __restrict__ v_trace;
   int B, Cin, H, Cout, K, G, n_lif, row_tiles;
   float decay, theta;
-  float wj[TAC_MAX_K];
+  uint32_t wq[TAC_MAX_K];              // round(beta^(K-1-j) * 2^23)
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -94,14 +108,15 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// One LIF step on a wave's 2 x 2 MFMA tiles: V <- decay V + Y, spike iff V >= theta,
-// subtractive reset.  The 64 ballots of the step are gathered, one 32-bit half per lane,
-// into two store registers: lane L = (r << 2) | (hi << 1) | np of word[mc] holds the packed
-// word of cout 32 mc + 8 (r/4) + 4 hi + r%4, x-block np.
+// One LIF step on a wave's 4 x 2 MFMA tiles: V <- decay V + Y, spike iff V >= theta,
+// subtractive reset.  The ballots of the step are gathered, one 32-bit half per lane, into
+// one store register per 32-channel block: lane L = (r << 2) | (hi << 1) | np of word[mc]
+// holds the packed word of cout 32 mc + 8 (r/4) + 4 hi + r%4, x-block np.
 template <bool TRACE>
-__device__ __forceinline__ void lif_step(float (&V)[4][2][16], const f32x16 (&acc)[4][2], float decay, float theta,
-                                         uint32_t (&word)[4], float* __restrict__ trace_wave, size_t plane, uint32_t lane_bytes) {
-  static_for<0, 4>([&](auto mc_) {
+__device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&acc)[kMC][2], float decay, float theta,
+                                         uint32_t (&word)[kMC], float* __restrict__ trace_wave, size_t plane,
+                                         uint32_t lane_bytes) {
+  static_for<0, kMC>([&](auto mc_) {
     constexpr int mc = decltype(mc_)::value;
     static_for<0, 2>([&](auto np_) {
       constexpr int np = decltype(np_)::value;
@@ -114,57 +129,98 @@ __device__ __forceinline__ void lif_step(float (&V)[4][2][16], const f32x16 (&ac
         word[mc] = write_lane<(r << 2) | 2 | np>(word[mc], (uint32_t)(m >> 32));
         V[mc][np][r] = fire ? v - theta : v;
         if constexpr (TRACE)
-          *reinterpret_cast<float*>(reinterpret_cast<char*>(trace_wave) + ((size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane + np * 32) * 4 + lane_bytes) = v;
+          *reinterpret_cast<float*>(reinterpret_cast<char*>(trace_wave) +
+                                    ((size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane + np * 32) * 4 + lane_bytes) = v;
         if constexpr ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // keep only a few ballots alive
       });
     });
   });
 }
 
-// Aggregate one loader item: 4 input channels x one input row (64 pixels) x K frames,
-// and write the 4 bf16 values of lane x to the LDS tile of the NEXT chunk.
-template <int KT>
-__device__ __forceinline__ void load_item(const MfmaParams& p, uint8_t* a_next, int item, int lane,
-                                          int b, int g, int c, int y0) {
-  const int r = item >> 2, q = item & 3;
-  const int iy = y0 - 1 + r;
-  const int K = KT > 0 ? KT : p.K;
-  float val[4] = {0.f, 0.f, 0.f, 0.f};
-  if (iy >= 0 && iy < p.H) {                                   // wave-uniform; outside = zero padding
-    const_u64_ptr sp = (const_u64_ptr)(p.spikes);
-    const size_t chan_stride = (size_t)p.H;                    // in 64-bit rows
-    const size_t t_stride = (size_t)p.B * p.Cin * chan_stride;
-    const size_t base = ((size_t)(g * K) * p.B + b) * p.Cin * chan_stride +
-                        (size_t)(c * kChunk + q * 4) * chan_stride + iy;
+// ---- staging of packed input words ------------------------------------------------------
+// Flat staging index i in [0, 192 K): i = (j * 16 + cin) * 12 + row * 2 + half, so that
+// consecutive threads read consecutive dwords of one (frame, channel) plane.  In LDS the
+// K frames of one (cin, row, half) are adjacent: index ((cin * 6 + row) * 2 + half) * K + j.
+template <int NL>
+__device__ __forceinline__ void stage_load(uint32_t (&wd)[NL], const MfmaParams& p, int K, int tid, int b, int g,
+                                           int c, int y0) {
+  const int n = kWordsPerFrame * K;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      float a = 0.f;
-      if (KT > 0) {
+  for (int l = 0; l < NL; ++l) {
+    const int i = tid + l * kThreads;
+    uint32_t v = 0;
+    if (i < n) {
+      const int j = i / kWordsPerFrame;
+      const int rem = i - j * kWordsPerFrame;
+      const int cin = rem / (kInRows * 2);
+      const int rh = rem - cin * (kInRows * 2);
+      const int iy = y0 - 1 + (rh >> 1);
+      if (iy >= 0 && iy < p.H)
+        v = p.spikes[((((size_t)(g * K + j) * p.B + b) * p.Cin + c * kChunk + cin) * p.H + iy) * 2 + (rh & 1)];
+    }
+    wd[l] = v;
+  }
+}
+
+template <int NL>
+__device__ __forceinline__ void stage_store(const uint32_t (&wd)[NL], uint8_t* words_buf, int K, int tid) {
+  const int n = kWordsPerFrame * K;
 #pragma unroll
-        for (int j = 0; j < KT; ++j) {
-          const uint64_t m = sp[base + j * t_stride + e * chan_stride];
-          a += __builtin_amdgcn_inverse_ballot_w64(m) ? p.wj[j] : 0.f;
-        }
-      } else {
-        for (int j = 0; j < K; ++j) {
-          const uint64_t m = sp[base + j * t_stride + e * chan_stride];
-          a += __builtin_amdgcn_inverse_ballot_w64(m) ? p.wj[j] : 0.f;
-        }
-      }
-      val[e] = a;
+  for (int l = 0; l < NL; ++l) {
+    const int i = tid + l * kThreads;
+    if (i < n) {
+      const int j = i / kWordsPerFrame;
+      const int rem = i - j * kWordsPerFrame;            // (cin * 6 + row) * 2 + half
+      reinterpret_cast<uint32_t*>(words_buf)[rem * K + j] = wd[l];
     }
   }
-  uint2 pk = make_uint2(pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3]));
-  *reinterpret_cast<uint2*>(a_next + (q >> 1) * kAHalf + (r * kXP + lane + 1) * 16 + (q & 1) * 8) = pk;
+}
+
+// Aggregate input row r of the wave's 4 channels (cin quad q) for lane x and write the
+// 4 bf16 values into the A tile under construction.
+template <int KT>
+__device__ __forceinline__ void expand_row(const MfmaParams& p, const uint8_t* words_buf, uint8_t* a_next, int K,
+                                           int lane, int q, int r) {
+  const uint32_t* wb = reinterpret_cast<const uint32_t*>(words_buf);
+  const uint32_t bitpos = lane & 31;
+  float val[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const uint32_t* src = wb + ((((q * 4 + e) * kInRows + r) * 2 + (lane >> 5)) * K);
+    uint32_t acc = 0;
+    if constexpr (KT >= 4) {
+#pragma unroll
+      for (int j4 = 0; j4 < KT / 4; ++j4) {
+        const u32x4 w4 = *reinterpret_cast<const u32x4*>(src + 4 * j4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc = __umul24(__builtin_amdgcn_ubfe(w4[j], bitpos, 1), p.wq[4 * j4 + j]) + acc;
+      }
+    } else if constexpr (KT == 2) {
+      const u32x2 w2 = *reinterpret_cast<const u32x2*>(src);
+      acc = __umul24(__builtin_amdgcn_ubfe(w2[0], bitpos, 1), p.wq[0]) + acc;
+      acc = __umul24(__builtin_amdgcn_ubfe(w2[1], bitpos, 1), p.wq[1]) + acc;
+    } else if constexpr (KT == 1) {
+      acc = __builtin_amdgcn_ubfe(src[0], bitpos, 1) << kFixShift;
+    } else {
+      for (int j = 0; j < K; ++j) acc = __umul24(__builtin_amdgcn_ubfe(src[j], bitpos, 1), p.wq[j]) + acc;
+    }
+    val[e] = (float)acc;
+  }
+  u32x2 pk = {pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])};
+  *reinterpret_cast<u32x2*>(a_next + (q >> 1) * kAHalf + (r * kXP + lane + 1) * 16 + (q & 1) * 8) = pk;
 }
 
 template <int KT>
 __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  constexpr int NL = KT > 0 ? (kWordsPerFrame * KT + kThreads - 1) / kThreads
+                            : (kWordsPerFrame * TAC_MAX_K + kThreads - 1) / kThreads;
+  const int K = KT > 0 ? KT : p.K;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int row = wave;                        // output row of this wave inside the tile
+  const int q = wave;                          // and the cin quad it aggregates in every chunk
   const int b = blockIdx.z;
   const int co_tile = blockIdx.y;
   const int y0 = blockIdx.x * kRows;
@@ -174,6 +230,9 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
   const int n = lane & 31, h = lane >> 5;
   const int Ho = p.H;
   const int co_wave = co_tile * kCoutTile;
+  const int total = p.G * NC;
+  uint8_t* const words0 = lds + kLdsWords;
+  const int words_bytes = kWordsPerFrame * K * 4;
 
   // zero padding columns of both A buffers (never written again)
   if (tid < 2 * 2 * kInRows * 2) {
@@ -184,21 +243,21 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
     reinterpret_cast<float*>(lds + kLdsBias)[tid] = p.bias ? p.bias[co_tile * kCoutTile + tid] : 0.f;
 
   // membrane, MFMA result layout: register r of tile (mc, np), lane -> cout = 32 mc + 8 (r/4) + 4 h + r%4, x = 32 np + n
-  float V[4][2][16];
-  f32x16 acc[4][2];
+  float V[kMC][2][16];
+  f32x16 acc[kMC][2];
   const size_t plane = (size_t)Ho * kW;                               // elements per (b, cout)
-  // wave-uniform base of this wave's 64 channels at row y; the lane adds 4 h channels + n
+  // wave-uniform base of this wave's channels at row y; the lane adds 4 h channels + n
   const size_t v_wave = ((size_t)b * p.Cout + co_wave) * plane + (size_t)y * kW;
-  uint32_t v_lane = (uint32_t)(4 * h * plane + n) * 4u;               // bytes
+  const uint32_t v_lane = (uint32_t)(4 * h * plane + n) * 4u;         // bytes
   if (p.v_inout && row_ok) {
     const char* vb = reinterpret_cast<const char*>(p.v_inout + v_wave);
-    static_for<0, 4>([&](auto mc_) { static_for<0, 2>([&](auto np_) { static_for<0, 16>([&](auto r_) {
+    static_for<0, kMC>([&](auto mc_) { static_for<0, 2>([&](auto np_) { static_for<0, 16>([&](auto r_) {
       constexpr int mc = decltype(mc_)::value, np = decltype(np_)::value, r = decltype(r_)::value;
       V[mc][np][r] = *reinterpret_cast<const float*>(vb + ((size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane + np * 32) * 4 + v_lane);
     }); }); });
   } else {
 #pragma unroll
-    for (int mc = 0; mc < 4; ++mc)
+    for (int mc = 0; mc < kMC; ++mc)
 #pragma unroll
       for (int np = 0; np < 2; ++np)
 #pragma unroll
@@ -206,10 +265,23 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
   }
 
   const uint8_t* wsrc = p.w + (size_t)co_tile * NC * kWBuf;
+  auto chunk_of = [&](int sx, int& gx, int& cx) {
+    sx = min(sx, total - 1);                    // past the end: harmless repeat of the last chunk
+    gx = sx / NC;
+    cx = sx - gx * NC;
+  };
 
-  // ---- prologue: chunk 0 of group 0 into buffer 0
+  // ---- prologue: A tile and weights of chunk 0, staged words of chunk 1
   {
-    for (int i = 0; i < 6; ++i) load_item<KT>(p, lds + kLdsA, wave + 4 * i, lane, b, 0, 0, y0);
+    uint32_t wd[NL];
+    stage_load<NL>(wd, p, K, tid, b, 0, 0, y0);
+    stage_store<NL>(wd, words0, K, tid);
+    __syncthreads();
+    for (int r = 0; r < kInRows; ++r) expand_row<KT>(p, words0, lds + kLdsA, K, lane, q, r);
+    int g1, c1;
+    chunk_of(1, g1, c1);
+    stage_load<NL>(wd, p, K, tid, b, g1, c1, y0);
+    stage_store<NL>(wd, words0 + words_bytes, K, tid);
 #pragma unroll
     for (int i = 0; i < kWLoads; ++i) {
       const int u = tid + i * kThreads;
@@ -229,11 +301,10 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
   const size_t out_lane = ((size_t)b * p.Cout + co_wave + st_co) * out_plane + (size_t)y * 2 + st_np;
   const size_t out_step = (size_t)p.B * p.Cout * out_plane;
 
-  const int total = p.G * NC;
   int s = 0;
   for (int g = 0; g < p.G; ++g) {
 #pragma unroll
-    for (int mc = 0; mc < 4; ++mc)
+    for (int mc = 0; mc < kMC; ++mc)
 #pragma unroll
       for (int np = 0; np < 2; ++np)
 #pragma unroll
@@ -245,27 +316,31 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
       const uint8_t* w_cur = lds + kLdsW + cur * kWBuf;
       uint8_t* a_next = lds + kLdsA + (cur ^ 1) * kABuf;
       uint8_t* w_next = lds + kLdsW + (cur ^ 1) * kWBuf;
-      const bool has_next = s + 1 < total;
-      int gn = g, cn = c + 1;
-      if (cn == NC) { cn = 0; gn = g + 1; }
+      const uint8_t* words_next = words0 + (cur ^ 1) * words_bytes;   // words of chunk s+1 (read now)
+      uint8_t* words_nn = words0 + cur * words_bytes;                 // words of chunk s+2 (written at the end)
+      int gn, cn, gnn, cnn;
+      chunk_of(s + 1, gn, cn);
+      chunk_of(s + 2, gnn, cnn);
 
-      // weights of the next chunk: global -> registers now, registers -> LDS after the MFMAs
+      // global -> registers now, registers -> LDS after the MFMAs: weights of chunk s+1, words of chunk s+2
       u32x4 wreg[kWLoads];
-      if (has_next) {
+      uint32_t wd[NL];
+      {
         const uint8_t* wn = wsrc + (size_t)cn * kWBuf;
 #pragma unroll
         for (int i = 0; i < kWLoads; ++i) {
           const int u = tid + i * kThreads;
           if (u < kWUnits) wreg[i] = *reinterpret_cast<const u32x4*>(wn + (size_t)u * 16);
         }
+        stage_load<NL>(wd, p, K, tid, b, gnn, cnn, y0);
       }
 
       // software pipeline over the 9 taps: fragments of tap+1 are fetched while tap multiplies
-      bf16x8 wf[2][4], af[2][2];
+      bf16x8 wf[2][kMC], af[2][2];
       auto fetch = [&](int tap, int slot) {
         const int ky = tap / 3, kx = tap % 3;
 #pragma unroll
-        for (int mc = 0; mc < 4; ++mc)
+        for (int mc = 0; mc < kMC; ++mc)
           wf[slot][mc] = *reinterpret_cast<const bf16x8*>(w_cur + tap * kWTap + mc * 1024 + w_frag_off);
 #pragma unroll
         for (int np = 0; np < 2; ++np)
@@ -277,21 +352,20 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
         const int slot = tap & 1;
         if (tap < 8) fetch(tap + 1, slot ^ 1);
 #pragma unroll
-        for (int mc = 0; mc < 4; ++mc)
+        for (int mc = 0; mc < kMC; ++mc)
 #pragma unroll
           for (int np = 0; np < 2; ++np)
             acc[mc][np] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][mc], af[slot][np], acc[mc][np], 0, 0, 0);
-        if (has_next && tap < 6) load_item<KT>(p, a_next, wave + 4 * tap, lane, b, gn, cn, y0);
+        if (tap < kInRows) expand_row<KT>(p, words_next, a_next, K, lane, q, tap);
         __builtin_amdgcn_sched_barrier(0);
       }
 
-      if (has_next) {
 #pragma unroll
-        for (int i = 0; i < kWLoads; ++i) {
-          const int u = tid + i * kThreads;
-          if (u < kWUnits) *reinterpret_cast<u32x4*>(w_next + u * 16) = wreg[i];
-        }
+      for (int i = 0; i < kWLoads; ++i) {
+        const int u = tid + i * kThreads;
+        if (u < kWUnits) *reinterpret_cast<u32x4*>(w_next + u * 16) = wreg[i];
       }
+      stage_store<NL>(wd, words_nn, K, tid);
       __syncthreads();
     }
 
@@ -299,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
     const float* bias_lds = reinterpret_cast<const float*>(lds + kLdsBias);
     if (p.bias) {
 #pragma unroll
-      for (int mc = 0; mc < 4; ++mc)
+      for (int mc = 0; mc < kMC; ++mc)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const float bv = bias_lds[mc * 32 + 8 * (r >> 2) + 4 * h + (r & 3)];
@@ -309,7 +383,9 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
     }
     for (int j = 0; j < p.n_lif; ++j) {
       const size_t step = (size_t)g * p.n_lif + j;
-      uint32_t word[4] = {0u, 0u, 0u, 0u};
+      uint32_t word[kMC];
+#pragma unroll
+      for (int mc = 0; mc < kMC; ++mc) word[mc] = 0u;
       if (p.v_trace && row_ok) {
         float* tl = p.v_trace + step * ((size_t)p.B * p.Cout * plane) + v_wave;
         size_t plane_l = plane;
@@ -320,7 +396,7 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
       }
       if (row_ok) {
 #pragma unroll
-        for (int mc = 0; mc < 4; ++mc) p.out[step * out_step + out_lane + mc * 32 * out_plane] = word[mc];
+        for (int mc = 0; mc < kMC; ++mc) p.out[step * out_step + out_lane + mc * 32 * out_plane] = word[mc];
       }
     }
   }
@@ -329,44 +405,47 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
     size_t plane_l = plane;                   // opaque copy: the 128 addresses below are formed here,
     asm volatile("" : "+s"(plane_l));         // not before the time loop (they would not fit in registers)
     char* vb = reinterpret_cast<char*>(p.v_inout + v_wave);
-    static_for<0, 4>([&](auto mc_) { static_for<0, 2>([&](auto np_) { static_for<0, 16>([&](auto r_) {
+    static_for<0, kMC>([&](auto mc_) { static_for<0, 2>([&](auto np_) { static_for<0, 16>([&](auto r_) {
       constexpr int mc = decltype(mc_)::value, np = decltype(np_)::value, r = decltype(r_)::value;
       *reinterpret_cast<float*>(vb + ((size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane_l + np * 32) * 4 + v_lane) = V[mc][np][r];
     }); }); });
   }
 }
 
-// OIHW fp32 -> [cout_tile][chunk][tap][mc][lane][8] bf16, the order the MFMA A-operand
-// fragments are read in: lane l of block mc holds cout 32 mc + l%32, cin 8 (l/32) .. +7.
+// OIHW fp32 -> [cout_tile][chunk][tap][mc][lane][8] bf16 (times 2^-23, see the header), the
+// order the MFMA A-operand fragments are read in: lane l of block mc holds
+// cout 32 mc + l%32, cin 8 (l/32) .. +7.
 __global__ void mfma_prepare_kernel(const float* __restrict__ w, uint32_t* __restrict__ out, int Cin, int Cout) {
   const int NC = Cin / kChunk;
-  const int total = (Cout / kCoutTile) * NC * 9 * 4 * 64 * 4;      // one thread per bf16 pair
+  const int total = (Cout / kCoutTile) * NC * 9 * kMC * 64 * 4;      // one thread per bf16 pair
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
   int t = i;
   const int e2 = t & 3; t >>= 2;
   const int l = t & 63; t >>= 6;
-  const int mc = t & 3; t >>= 2;
+  const int mc = t % kMC; t /= kMC;
   const int tap = t % 9; t /= 9;
   const int c = t % NC;
   const int ct = t / NC;
   const int co = ct * kCoutTile + mc * 32 + (l & 31);
   const int ci = c * kChunk + (l >> 5) * 8 + e2 * 2;
-  const float a = w[((size_t)co * Cin + ci) * 9 + tap];
-  const float bb = w[((size_t)co * Cin + ci + 1) * 9 + tap];
+  const float scale = 1.0f / (float)(1u << kFixShift);
+  const float a = w[((size_t)co * Cin + ci) * 9 + tap] * scale;
+  const float bb = w[((size_t)co * Cin + ci + 1) * 9 + tap] * scale;
   out[i] = pack_bf16(a, bb);
 }
 
 template <int KT>
 hipError_t launch_kt(const MfmaParams& mp, dim3 grid, hipStream_t s) {
+  const int lds = lds_bytes(KT > 0 ? KT : TAC_MAX_K);
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_w64_kernel<KT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(mfma_w64_kernel<KT>, grid, dim3(kThreads), kLdsBytes, s, mp);
+  hipLaunchKernelGGL(mfma_w64_kernel<KT>, grid, dim3(kThreads), lds, s, mp);
   return hipGetLastError();
 }
 
@@ -393,7 +472,11 @@ hipError_t mfma_launch(const LayerParams& p, hipStream_t s) {
   mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.Cout = p.Cout; mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif;
   mp.row_tiles = (p.H + kRows - 1) / kRows;
   mp.decay = p.decay; mp.theta = p.theta;
-  for (int j = 0; j < TAC_MAX_K; ++j) mp.wj[j] = p.wj[j];
+  for (int j = 0; j < TAC_MAX_K; ++j) {
+    // beta^(K-1-j) in 24-bit fixed point, from the fp32 table the host already rounded
+    const double q = (double)p.wj[j] * (double)(1u << kFixShift);
+    mp.wq[j] = j < p.K ? (uint32_t)(q + 0.5) : 0u;
+  }
   const dim3 grid(mp.row_tiles, p.Cout / kCoutTile, p.B);
   switch (p.K) {
     case 1: return launch_kt<1>(mp, grid, s);
