@@ -141,68 +141,99 @@ __device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&
 // Flat staging index i in [0, 192 K): i = (j * 16 + cin) * 12 + row * 2 + half, so that
 // consecutive threads read consecutive dwords of one (frame, channel) plane.  In LDS the
 // K frames of one (cin, row, half) are adjacent: index ((cin * 6 + row) * 2 + half) * K + j.
+// A thread's share of a chunk is the same in every chunk, so its global dword offsets
+// (relative to the chunk's first frame and channel) and LDS indices are computed once.
 template <int NL>
-__device__ __forceinline__ void stage_load(uint32_t (&wd)[NL], const MfmaParams& p, int K, int tid, int b, int g,
-                                           int c, int y0) {
+struct StagePlan {
+  uint32_t goff[NL];     // dword offset from the chunk base; 0xffffffff = nothing to load (zero word)
+  uint32_t lidx[NL];     // dword index in the LDS staging buffer; 0xffffffff = no store
+};
+
+template <int NL>
+__device__ __forceinline__ void stage_plan(StagePlan<NL>& sp, const MfmaParams& p, int K, int tid, int y0) {
   const int n = kWordsPerFrame * K;
 #pragma unroll
   for (int l = 0; l < NL; ++l) {
     const int i = tid + l * kThreads;
-    uint32_t v = 0;
+    sp.goff[l] = 0xffffffffu;
+    sp.lidx[l] = 0xffffffffu;
     if (i < n) {
       const int j = i / kWordsPerFrame;
-      const int rem = i - j * kWordsPerFrame;
+      const int rem = i - j * kWordsPerFrame;              // (cin * 6 + row) * 2 + half
       const int cin = rem / (kInRows * 2);
       const int rh = rem - cin * (kInRows * 2);
       const int iy = y0 - 1 + (rh >> 1);
+      sp.lidx[l] = (uint32_t)(rem * K + j);
       if (iy >= 0 && iy < p.H)
-        v = p.spikes[((((size_t)(g * K + j) * p.B + b) * p.Cin + c * kChunk + cin) * p.H + iy) * 2 + (rh & 1)];
+        sp.goff[l] = (uint32_t)((((size_t)j * p.B * p.Cin + cin) * p.H + iy) * 2 + (rh & 1));
     }
-    wd[l] = v;
   }
 }
 
 template <int NL>
-__device__ __forceinline__ void stage_store(const uint32_t (&wd)[NL], uint8_t* words_buf, int K, int tid) {
-  const int n = kWordsPerFrame * K;
+__device__ __forceinline__ void stage_load(uint32_t (&wd)[NL], const StagePlan<NL>& sp, const MfmaParams& p, int K,
+                                           int b, int g, int c) {
+  // wave-uniform base of (first frame of group g, sample b, first channel of chunk c)
+  const uint32_t* base = p.spikes + (((size_t)(g * K) * p.B + b) * p.Cin + c * kChunk) * p.H * 2;
 #pragma unroll
-  for (int l = 0; l < NL; ++l) {
-    const int i = tid + l * kThreads;
-    if (i < n) {
-      const int j = i / kWordsPerFrame;
-      const int rem = i - j * kWordsPerFrame;            // (cin * 6 + row) * 2 + half
-      reinterpret_cast<uint32_t*>(words_buf)[rem * K + j] = wd[l];
-    }
-  }
+  for (int l = 0; l < NL; ++l) wd[l] = sp.goff[l] != 0xffffffffu ? base[sp.goff[l]] : 0u;
 }
 
-// Aggregate input row r of the wave's 4 channels (cin quad q) for lane x and write the
-// 4 bf16 values into the A tile under construction.
+template <int NL>
+__device__ __forceinline__ void stage_store(const uint32_t (&wd)[NL], const StagePlan<NL>& sp, uint8_t* words_buf) {
+#pragma unroll
+  for (int l = 0; l < NL; ++l)
+    if (sp.lidx[l] != 0xffffffffu) reinterpret_cast<uint32_t*>(words_buf)[sp.lidx[l]] = wd[l];
+}
+
+// The loader works in two halves one filter tap apart, so that the LDS latency of the word
+// reads hides behind the MFMAs of a tap: read_words fetches, for lane x, the K staged words
+// (one per frame) that hold pixel x of input row r for each of the wave's 4 channels (cin
+// quad q); expand_words turns them into the 4 bf16 aggregates and writes them into the A
+// tile under construction.
 template <int KT>
-__device__ __forceinline__ void expand_row(const MfmaParams& p, const uint8_t* words_buf, uint8_t* a_next, int K,
-                                           int lane, int q, int r) {
+struct RowWords {
+  static constexpr int N = KT > 0 ? KT : 1;
+  uint32_t w[4][N];
+};
+
+template <int KT>
+__device__ __forceinline__ void read_words(RowWords<KT>& rw, const uint8_t* words_buf, int lane, int q, int r) {
+  static_assert(KT > 0, "compile-time K only");
   const uint32_t* wb = reinterpret_cast<const uint32_t*>(words_buf);
-  const uint32_t bitpos = lane & 31;
-  float val[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    const uint32_t* src = wb + ((((q * 4 + e) * kInRows + r) * 2 + (lane >> 5)) * K);
-    uint32_t acc = 0;
+    const uint32_t* src = wb + ((((q * 4 + e) * kInRows + r) * 2 + (lane >> 5)) * KT);
     if constexpr (KT >= 4) {
 #pragma unroll
       for (int j4 = 0; j4 < KT / 4; ++j4) {
         const u32x4 w4 = *reinterpret_cast<const u32x4*>(src + 4 * j4);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc = __umul24(__builtin_amdgcn_ubfe(w4[j], bitpos, 1), p.wq[4 * j4 + j]) + acc;
+        for (int j = 0; j < 4; ++j) rw.w[e][4 * j4 + j] = w4[j];
       }
     } else if constexpr (KT == 2) {
       const u32x2 w2 = *reinterpret_cast<const u32x2*>(src);
-      acc = __umul24(__builtin_amdgcn_ubfe(w2[0], bitpos, 1), p.wq[0]) + acc;
-      acc = __umul24(__builtin_amdgcn_ubfe(w2[1], bitpos, 1), p.wq[1]) + acc;
-    } else if constexpr (KT == 1) {
-      acc = __builtin_amdgcn_ubfe(src[0], bitpos, 1) << kFixShift;
+      rw.w[e][0] = w2[0];
+      rw.w[e][1] = w2[1];
     } else {
-      for (int j = 0; j < K; ++j) acc = __umul24(__builtin_amdgcn_ubfe(src[j], bitpos, 1), p.wq[j]) + acc;
+      rw.w[e][0] = src[0];
+    }
+  }
+}
+
+template <int KT>
+__device__ __forceinline__ void expand_words(const RowWords<KT>& rw, const MfmaParams& p, uint8_t* a_next, int lane,
+                                             int q, int r) {
+  const uint32_t bitpos = lane & 31;
+  float val[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    uint32_t acc = 0;
+    if constexpr (KT == 1) {
+      acc = __builtin_amdgcn_ubfe(rw.w[e][0], bitpos, 1) << kFixShift;
+    } else {
+#pragma unroll
+      for (int j = 0; j < KT; ++j) acc = __umul24(__builtin_amdgcn_ubfe(rw.w[e][j], bitpos, 1), p.wq[j]) + acc;
     }
     val[e] = (float)acc;
   }
@@ -210,11 +241,49 @@ __device__ __forceinline__ void expand_row(const MfmaParams& p, const uint8_t* w
   *reinterpret_cast<u32x2*>(a_next + (q >> 1) * kAHalf + (r * kXP + lane + 1) * 16 + (q & 1) * 8) = pk;
 }
 
+// Unpipelined form (prologue, and the run-time-K kernel).
+template <int KT>
+__device__ __forceinline__ void expand_row(const MfmaParams& p, const uint8_t* words_buf, uint8_t* a_next, int K,
+                                           int lane, int q, int r) {
+  if constexpr (KT > 0) {
+    RowWords<KT> rw;
+    read_words<KT>(rw, words_buf, lane, q, r);
+    expand_words<KT>(rw, p, a_next, lane, q, r);
+  } else {
+    const uint32_t* wb = reinterpret_cast<const uint32_t*>(words_buf);
+    const uint32_t bitpos = lane & 31;
+    float val[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t* src = wb + ((((q * 4 + e) * kInRows + r) * 2 + (lane >> 5)) * K);
+      uint32_t acc = 0;
+      for (int j = 0; j < K; ++j) acc = __umul24(__builtin_amdgcn_ubfe(src[j], bitpos, 1), p.wq[j]) + acc;
+      val[e] = (float)acc;
+    }
+    u32x2 pk = {pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])};
+    *reinterpret_cast<u32x2*>(a_next + (q >> 1) * kAHalf + (r * kXP + lane + 1) * 16 + (q & 1) * 8) = pk;
+  }
+}
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
+
+// Workgroup barrier that orders LDS traffic only: the compiler waits for this wave's LDS
+// accesses and for its direct-to-LDS loads, but leaves ordinary global loads in flight.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 template <int KT>
 __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   constexpr int NL = KT > 0 ? (kWordsPerFrame * KT + kThreads - 1) / kThreads
                             : (kWordsPerFrame * TAC_MAX_K + kThreads - 1) / kThreads;
+  // depth of the register pipeline of staged words: loads are issued D chunks before the
+  // words are written to LDS (they come from HBM)
+  constexpr int D = KT == 0 ? 1 : (KT >= 16 ? 2 : 3);
   const int K = KT > 0 ? KT : p.K;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -270,23 +339,41 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
     gx = sx / NC;
     cx = sx - gx * NC;
   };
+  // weights of chunk cx: global -> LDS without passing through registers; each wave moves
+  // 9 of the 36 one-KiB blocks, lane l its 16 bytes of the block
+  const uint32_t w_lane_off = (uint32_t)lane * 16u;
+  auto weights_to_lds = [&](int cx, uint8_t* w_dst) {
+    const uint8_t* src = wsrc + (size_t)cx * kWBuf;
+#pragma unroll
+    for (int i = 0; i < kWBuf / 1024 / kRows; ++i) {
+      const int blk = wave + kRows * i;
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (uint32_t)(blk * 1024) + w_lane_off),
+                                       (lds_void_ptr)(w_dst + blk * 1024), 16, 0, 0);
+    }
+  };
 
-  // ---- prologue: A tile and weights of chunk 0, staged words of chunk 1
+  StagePlan<NL> plan;
+  stage_plan<NL>(plan, p, K, tid, y0);
+  uint32_t wd[D][NL];                           // staged words in flight; wd[0] is written to LDS next
+
+  // ---- prologue: A tile of chunk 0, weights of chunks 0 and 1, staged words of chunk 1,
+  //      words of chunks 2 .. 1+D in registers
   {
-    uint32_t wd[NL];
-    stage_load<NL>(wd, p, K, tid, b, 0, 0, y0);
-    stage_store<NL>(wd, words0, K, tid);
+    weights_to_lds(0, lds + kLdsW);
+    int gx, cx;
+    chunk_of(1, gx, cx);
+    weights_to_lds(cx, lds + kLdsW + kWBuf);
+    uint32_t w0[NL];
+    stage_load<NL>(w0, plan, p, K, b, 0, 0);
+    stage_store<NL>(w0, plan, words0);
+    stage_load<NL>(w0, plan, p, K, b, gx, cx);
+    stage_store<NL>(w0, plan, words0 + words_bytes);
     __syncthreads();
     for (int r = 0; r < kInRows; ++r) expand_row<KT>(p, words0, lds + kLdsA, K, lane, q, r);
-    int g1, c1;
-    chunk_of(1, g1, c1);
-    stage_load<NL>(wd, p, K, tid, b, g1, c1, y0);
-    stage_store<NL>(wd, words0 + words_bytes, K, tid);
 #pragma unroll
-    for (int i = 0; i < kWLoads; ++i) {
-      const int u = tid + i * kThreads;
-      if (u < kWUnits)
-        *reinterpret_cast<u32x4*>(lds + kLdsW + u * 16) = *reinterpret_cast<const u32x4*>(wsrc + (size_t)u * 16);
+    for (int d = 0; d < D; ++d) {
+      chunk_of(2 + d, gx, cx);
+      stage_load<NL>(wd[d], plan, p, K, b, gx, cx);
     }
   }
   __syncthreads();
@@ -301,6 +388,93 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
   const size_t out_lane = ((size_t)b * p.Cout + co_wave + st_co) * out_plane + (size_t)y * 2 + st_np;
   const size_t out_step = (size_t)p.B * p.Cout * out_plane;
 
+  // MFMA operand fragments, two slots: tap t multiplies slot t & 1 while slot (t+1) & 1 is
+  // being fetched; tap 8 fetches the next chunk's tap-0 fragments into slot 1, which the next
+  // chunk starts by moving to slot 0
+  bf16x8 wf[2][kMC], af[2][2];
+  auto fetch = [&](const uint8_t* a_buf, const uint8_t* w_buf, int tap, int slot) {
+    const int ky = tap / 3, kx = tap % 3;
+#pragma unroll
+    for (int mc = 0; mc < kMC; ++mc)
+      wf[slot][mc] = *reinterpret_cast<const bf16x8*>(w_buf + tap * kWTap + mc * 1024 + w_frag_off);
+#pragma unroll
+    for (int np = 0; np < 2; ++np)
+      af[slot][np] = *reinterpret_cast<const bf16x8*>(a_buf + a_frag_off + (ky * kXP + kx + 32 * np) * 16);
+  };
+  fetch(lds + kLdsA, lds + kLdsW, 0, 1);
+
+  // One chunk of 16 input channels: 9 taps of MFMAs on buffers PAR, while the A tile of the
+  // next chunk is built in buffers PAR^1.  The workgroup barrier sits between tap 7 and tap 8:
+  // by then every read of the PAR buffers has returned (tap 8's fragments are fetched during
+  // tap 7) and every write to the PAR^1 buffers is done, so tap 8 already fetches the first
+  // fragments of the next chunk and refills the PAR weight buffer for the chunk after it.
+  auto chunk_iteration = [&](int s) {
+    const int PAR = s & 1;
+    const uint8_t* a_cur = lds + kLdsA + PAR * kABuf;
+    const uint8_t* w_cur = lds + kLdsW + PAR * kWBuf;
+    uint8_t* a_next = lds + kLdsA + (PAR ^ 1) * kABuf;
+    uint8_t* w_next = lds + kLdsW + (PAR ^ 1) * kWBuf;
+    const uint8_t* words_next = words0 + (PAR ^ 1) * words_bytes;    // words of chunk s+1 (read now)
+    uint8_t* words_nn = words0 + PAR * words_bytes;                  // words of chunk s+2 (written at tap 7)
+    RowWords<KT> rw;
+#pragma unroll
+    for (int mc = 0; mc < kMC; ++mc) wf[0][mc] = wf[1][mc];
+#pragma unroll
+    for (int np = 0; np < 2; ++np) af[0][np] = af[1][np];
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      const int slot = tap & 1;
+      if (tap == 8) {
+        // after the barrier: refill this chunk's weight buffer for chunk s+2, request the
+        // staged words of chunk s+2+D
+        int gx, cx;
+        chunk_of(s + 2, gx, cx);
+        weights_to_lds(cx, const_cast<uint8_t*>(w_cur));
+        __builtin_amdgcn_sched_barrier(0);
+        chunk_of(s + 2 + D, gx, cx);
+        stage_load<NL>(wd[D - 1], plan, p, K, b, gx, cx);
+        fetch(a_next, w_next, 0, slot ^ 1);
+      } else {
+        fetch(a_cur, w_cur, tap + 1, slot ^ 1);
+      }
+#pragma unroll
+      for (int mc = 0; mc < kMC; ++mc)
+#pragma unroll
+        for (int np = 0; np < 2; ++np)
+          acc[mc][np] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][mc], af[slot][np], acc[mc][np], 0, 0, 0);
+      if constexpr (KT > 0) {
+        // input row r: words requested during tap r, expanded during tap r + 1
+        if (tap >= 1 && tap <= kInRows) expand_words<KT>(rw, p, a_next, lane, q, tap - 1);
+        if (tap < kInRows) read_words<KT>(rw, words_next, lane, q, tap);
+      } else {
+        if (tap < kInRows) expand_row<KT>(p, words_next, a_next, K, lane, q, tap);
+      }
+      if (tap == 7) {
+        stage_store<NL>(wd[0], plan, words_nn);
+#pragma unroll
+        for (int d = 0; d + 1 < D; ++d)
+#pragma unroll
+          for (int l = 0; l < NL; ++l) wd[d][l] = wd[d + 1][l];
+      }
+      if constexpr (KT > 0) {
+        // issue order inside the tap: one MFMA, then a few LDS reads and vector ops that run
+        // while the matrix pipe is busy, eight times over
+        constexpr int kValuPerMfma = KT <= 2 ? 3 : (KT == 4 ? 5 : (KT == 8 ? 10 : 18));
+#pragma unroll
+        for (int i = 0; i < 2 * kMC; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (tap == 7) {
+        lds_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+
   int s = 0;
   for (int g = 0; g < p.G; ++g) {
 #pragma unroll
@@ -311,62 +485,7 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
         for (int r = 0; r < 16; ++r) acc[mc][np][r] = 0.f;
 
     for (int c = 0; c < NC; ++c, ++s) {
-      const int cur = s & 1;
-      const uint8_t* a_cur = lds + kLdsA + cur * kABuf;
-      const uint8_t* w_cur = lds + kLdsW + cur * kWBuf;
-      uint8_t* a_next = lds + kLdsA + (cur ^ 1) * kABuf;
-      uint8_t* w_next = lds + kLdsW + (cur ^ 1) * kWBuf;
-      const uint8_t* words_next = words0 + (cur ^ 1) * words_bytes;   // words of chunk s+1 (read now)
-      uint8_t* words_nn = words0 + cur * words_bytes;                 // words of chunk s+2 (written at the end)
-      int gn, cn, gnn, cnn;
-      chunk_of(s + 1, gn, cn);
-      chunk_of(s + 2, gnn, cnn);
-
-      // global -> registers now, registers -> LDS after the MFMAs: weights of chunk s+1, words of chunk s+2
-      u32x4 wreg[kWLoads];
-      uint32_t wd[NL];
-      {
-        const uint8_t* wn = wsrc + (size_t)cn * kWBuf;
-#pragma unroll
-        for (int i = 0; i < kWLoads; ++i) {
-          const int u = tid + i * kThreads;
-          if (u < kWUnits) wreg[i] = *reinterpret_cast<const u32x4*>(wn + (size_t)u * 16);
-        }
-        stage_load<NL>(wd, p, K, tid, b, gnn, cnn, y0);
-      }
-
-      // software pipeline over the 9 taps: fragments of tap+1 are fetched while tap multiplies
-      bf16x8 wf[2][kMC], af[2][2];
-      auto fetch = [&](int tap, int slot) {
-        const int ky = tap / 3, kx = tap % 3;
-#pragma unroll
-        for (int mc = 0; mc < kMC; ++mc)
-          wf[slot][mc] = *reinterpret_cast<const bf16x8*>(w_cur + tap * kWTap + mc * 1024 + w_frag_off);
-#pragma unroll
-        for (int np = 0; np < 2; ++np)
-          af[slot][np] = *reinterpret_cast<const bf16x8*>(a_cur + a_frag_off + (ky * kXP + kx + 32 * np) * 16);
-      };
-      fetch(0, 0);
-#pragma unroll
-      for (int tap = 0; tap < 9; ++tap) {
-        const int slot = tap & 1;
-        if (tap < 8) fetch(tap + 1, slot ^ 1);
-#pragma unroll
-        for (int mc = 0; mc < kMC; ++mc)
-#pragma unroll
-          for (int np = 0; np < 2; ++np)
-            acc[mc][np] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][mc], af[slot][np], acc[mc][np], 0, 0, 0);
-        if (tap < kInRows) expand_row<KT>(p, words_next, a_next, K, lane, q, tap);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-
-#pragma unroll
-      for (int i = 0; i < kWLoads; ++i) {
-        const int u = tid + i * kThreads;
-        if (u < kWUnits) *reinterpret_cast<u32x4*>(w_next + u * 16) = wreg[i];
-      }
-      stage_store<NL>(wd, words_nn, K, tid);
-      __syncthreads();
+      chunk_iteration(s);
     }
 
     // ---- LIF epilogue on Y_k = acc + bias
@@ -400,6 +519,7 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
       }
     }
   }
+  __syncthreads();                            // drains the last direct-to-LDS loads before the waves end
 
   if (p.v_inout && row_ok) {
     size_t plane_l = plane;                   // opaque copy: the 128 addresses below are formed here,
