@@ -145,17 +145,19 @@ __device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&
 // (relative to the chunk's first frame and channel) and LDS indices are computed once.
 template <int NL>
 struct StagePlan {
-  uint32_t goff[NL];     // dword offset from the chunk base; 0xffffffff = nothing to load (zero word)
-  uint32_t lidx[NL];     // dword index in the LDS staging buffer; 0xffffffff = no store
+  uint32_t goff[NL];     // dword offset from the chunk base (always a valid address)
+  uint32_t lidx[NL];     // dword index in the LDS staging buffer; 0xffffffff = this thread has no word l
+  uint32_t keep;         // bit l set: the word is inside the image; clear: store a zero word (padding row)
 };
 
 template <int NL>
 __device__ __forceinline__ void stage_plan(StagePlan<NL>& sp, const MfmaParams& p, int K, int tid, int y0) {
   const int n = kWordsPerFrame * K;
+  sp.keep = 0;
 #pragma unroll
   for (int l = 0; l < NL; ++l) {
     const int i = tid + l * kThreads;
-    sp.goff[l] = 0xffffffffu;
+    sp.goff[l] = 0;
     sp.lidx[l] = 0xffffffffu;
     if (i < n) {
       const int j = i / kWordsPerFrame;
@@ -163,27 +165,30 @@ __device__ __forceinline__ void stage_plan(StagePlan<NL>& sp, const MfmaParams& 
       const int cin = rem / (kInRows * 2);
       const int rh = rem - cin * (kInRows * 2);
       const int iy = y0 - 1 + (rh >> 1);
+      const int iyc = min(max(iy, 0), p.H - 1);
       sp.lidx[l] = (uint32_t)(rem * K + j);
-      if (iy >= 0 && iy < p.H)
-        sp.goff[l] = (uint32_t)((((size_t)j * p.B * p.Cin + cin) * p.H + iy) * 2 + (rh & 1));
+      sp.goff[l] = (uint32_t)((((size_t)j * p.B * p.Cin + cin) * p.H + iyc) * 2 + (rh & 1));
+      if (iy == iyc) sp.keep |= 1u << l;
     }
   }
 }
 
+// Unconditional loads (no lane masking, no register initialisation in front of them).
 template <int NL>
 __device__ __forceinline__ void stage_load(uint32_t (&wd)[NL], const StagePlan<NL>& sp, const MfmaParams& p, int K,
                                            int b, int g, int c) {
   // wave-uniform base of (first frame of group g, sample b, first channel of chunk c)
   const uint32_t* base = p.spikes + (((size_t)(g * K) * p.B + b) * p.Cin + c * kChunk) * p.H * 2;
 #pragma unroll
-  for (int l = 0; l < NL; ++l) wd[l] = sp.goff[l] != 0xffffffffu ? base[sp.goff[l]] : 0u;
+  for (int l = 0; l < NL; ++l) wd[l] = base[sp.goff[l]];
 }
 
 template <int NL>
 __device__ __forceinline__ void stage_store(const uint32_t (&wd)[NL], const StagePlan<NL>& sp, uint8_t* words_buf) {
 #pragma unroll
   for (int l = 0; l < NL; ++l)
-    if (sp.lidx[l] != 0xffffffffu) reinterpret_cast<uint32_t*>(words_buf)[sp.lidx[l]] = wd[l];
+    if (sp.lidx[l] != 0xffffffffu)
+      reinterpret_cast<uint32_t*>(words_buf)[sp.lidx[l]] = (sp.keep >> l) & 1u ? wd[l] : 0u;
 }
 
 // The loader works in two halves one filter tap apart, so that the LDS latency of the word
@@ -283,7 +288,7 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
                             : (kWordsPerFrame * TAC_MAX_K + kThreads - 1) / kThreads;
   // depth of the register pipeline of staged words: loads are issued D chunks before the
   // words are written to LDS (they come from HBM)
-  constexpr int D = KT == 0 ? 1 : (KT >= 16 ? 2 : 3);
+  constexpr int D = 1;
   const int K = KT > 0 ? KT : p.K;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
