@@ -89,14 +89,16 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // v_cvt_pk_bf16_f32, nearest even
 }
 
-template <int LANE>
-__device__ __forceinline__ uint32_t write_lane(uint32_t old, uint32_t sval) {
-  // vdst[LANE] = sval (wave-uniform); other lanes keep `old`.  The s_nop covers the two wait
-  // states this chip needs between a vector instruction that wrote the SGPR (a compare, or a
-  // spill reload) and a vector instruction that reads it: the assembler text is opaque to the
-  // compiler's hazard pass.
+template <int LANE_LO, int LANE_HI>
+__device__ __forceinline__ uint32_t write_lanes(uint32_t old, uint64_t ballot) {
+  // vdst[LANE_LO] = low half, vdst[LANE_HI] = high half of a wave-uniform 64-bit ballot; other
+  // lanes keep `old`.  The s_nop covers the two wait states this chip needs between a vector
+  // instruction that wrote the SGPR pair (the compare, or a spill reload) and a vector
+  // instruction that reads it: the assembler text is opaque to the compiler's hazard pass.
   uint32_t r;
-  asm volatile("s_nop 1\n\tv_writelane_b32 %0, %1, %2" : "=v"(r) : "s"(sval), "n"(LANE), "0"(old));
+  asm volatile("s_nop 1\n\tv_writelane_b32 %0, %1, %3\n\tv_writelane_b32 %0, %2, %4"
+               : "=v"(r)
+               : "s"((uint32_t)ballot), "s"((uint32_t)(ballot >> 32)), "n"(LANE_LO), "n"(LANE_HI), "0"(old));
   return r;
 }
 
@@ -125,8 +127,7 @@ __device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&
         const float v = fmaf(decay, V[mc][np][r], acc[mc][np][r]);
         const bool fire = v >= theta;
         const uint64_t m = __builtin_amdgcn_ballot_w64(fire);
-        word[mc] = write_lane<(r << 2) | np>(word[mc], (uint32_t)m);
-        word[mc] = write_lane<(r << 2) | 2 | np>(word[mc], (uint32_t)(m >> 32));
+        word[mc] = write_lanes<(r << 2) | np, (r << 2) | 2 | np>(word[mc], m);
         V[mc][np][r] = fire ? v - theta : v;
         if constexpr (TRACE)
           *reinterpret_cast<float*>(reinterpret_cast<char*>(trace_wave) +
