@@ -122,17 +122,29 @@ __device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&
     constexpr int mc = decltype(mc_)::value;
     static_for<0, 2>([&](auto np_) {
       constexpr int np = decltype(np_)::value;
-      static_for<0, 16>([&](auto r_) {
-        constexpr int r = decltype(r_)::value;
-        const float v = fmaf(decay, V[mc][np][r], acc[mc][np][r]);
-        const bool fire = v >= theta;
-        const uint64_t m = __builtin_amdgcn_ballot_w64(fire);
-        word[mc] = write_lanes<(r << 2) | np, (r << 2) | 2 | np>(word[mc], m);
-        V[mc][np][r] = fire ? v - theta : v;
-        if constexpr (TRACE)
-          *reinterpret_cast<float*>(reinterpret_cast<char*>(trace_wave) +
-                                    ((size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane + np * 32) * 4 + lane_bytes) = v;
-        if constexpr ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // keep only a few ballots alive
+      // four registers at a time: all four membranes and compares first, then the four ballot
+      // hand-overs, then the four resets, so that no instruction waits on the one before it
+      static_for<0, 4>([&](auto r4_) {
+        constexpr int r0 = decltype(r4_)::value * 4;
+        float v[4];
+        uint64_t m[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = fmaf(decay, V[mc][np][r0 + i], acc[mc][np][r0 + i]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) m[i] = __builtin_amdgcn_ballot_w64(v[i] >= theta);
+        word[mc] = write_lanes<((r0 + 0) << 2) | np, ((r0 + 0) << 2) | 2 | np>(word[mc], m[0]);
+        word[mc] = write_lanes<((r0 + 1) << 2) | np, ((r0 + 1) << 2) | 2 | np>(word[mc], m[1]);
+        word[mc] = write_lanes<((r0 + 2) << 2) | np, ((r0 + 2) << 2) | 2 | np>(word[mc], m[2]);
+        word[mc] = write_lanes<((r0 + 3) << 2) | np, ((r0 + 3) << 2) | 2 | np>(word[mc], m[3]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          V[mc][np][r0 + i] = __builtin_amdgcn_inverse_ballot_w64(m[i]) ? v[i] - theta : v[i];
+          if constexpr (TRACE)
+            *reinterpret_cast<float*>(reinterpret_cast<char*>(trace_wave) +
+                                      ((size_t)(mc * 32 + 8 * ((r0 + i) >> 2) + ((r0 + i) & 3)) * plane + np * 32) * 4 +
+                                      lane_bytes) = v[i];
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep only a few ballots alive
       });
     });
   });
