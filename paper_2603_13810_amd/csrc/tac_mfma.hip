@@ -62,6 +62,7 @@ constexpr int kWTap = kMC * 64 * 16;           // bytes of one tap: [mc][lane][8
 constexpr int kWBuf = 9 * kWTap;
 constexpr int kWUnits = kWBuf / 16;            // 16-byte units per chunk of weights
 constexpr int kWLoads = (kWUnits + kThreads - 1) / kThreads;
+constexpr int kWBlocks = kWBuf / 1024 / kRows;     // one-KiB weight blocks each wave copies per chunk
 constexpr int kWordsPerFrame = kChunk * kInRows * 2;   // staged dwords per chunk and frame
 constexpr int kFixShift = 23;                  // fixed-point scale of the aggregation weights
 constexpr int kLdsA = 0;
@@ -189,11 +190,12 @@ __device__ __forceinline__ void stage_plan(StagePlan<NL>& sp, const MfmaParams& 
 // Unconditional loads (no lane masking, no register initialisation in front of them).
 template <int NL>
 __device__ __forceinline__ void stage_load(uint32_t (&wd)[NL], const StagePlan<NL>& sp, const MfmaParams& p, int K,
-                                           int b, int g, int c) {
+                                           int b, int g, int c, int l0 = 0, int l1 = NL) {
   // wave-uniform base of (first frame of group g, sample b, first channel of chunk c)
   const uint32_t* base = p.spikes + (((size_t)(g * K) * p.B + b) * p.Cin + c * kChunk) * p.H * 2;
 #pragma unroll
-  for (int l = 0; l < NL; ++l) wd[l] = base[sp.goff[l]];
+  for (int l = 0; l < NL; ++l)
+    if (l >= l0 && l < l1) wd[l] = base[sp.goff[l]];
 }
 
 template <int NL>
@@ -360,10 +362,10 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
   // weights of chunk cx: global -> LDS without passing through registers; each wave moves
   // 9 of the 36 one-KiB blocks, lane l its 16 bytes of the block
   const uint32_t w_lane_off = (uint32_t)lane * 16u;
-  auto weights_to_lds = [&](int cx, uint8_t* w_dst) {
+  auto weights_to_lds = [&](int cx, uint8_t* w_dst, int i0, int i1) {
     const uint8_t* src = wsrc + (size_t)cx * kWBuf;
 #pragma unroll
-    for (int i = 0; i < kWBuf / 1024 / kRows; ++i) {
+    for (int i = i0; i < i1; ++i) {
       const int blk = wave + kRows * i;
       __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (uint32_t)(blk * 1024) + w_lane_off),
                                        (lds_void_ptr)(w_dst + blk * 1024), 16, 0, 0);
@@ -377,10 +379,10 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
   // ---- prologue: A tile of chunk 0, weights of chunks 0 and 1, staged words of chunk 1,
   //      words of chunks 2 .. 1+D in registers
   {
-    weights_to_lds(0, lds + kLdsW);
+    weights_to_lds(0, lds + kLdsW, 0, kWBlocks);
     int gx, cx;
     chunk_of(1, gx, cx);
-    weights_to_lds(cx, lds + kLdsW + kWBuf);
+    weights_to_lds(cx, lds + kLdsW + kWBuf, 0, kWBlocks);
     uint32_t w0[NL];
     stage_load<NL>(w0, plan, p, K, b, 0, 0);
     stage_store<NL>(w0, plan, words0);
@@ -442,17 +444,30 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) {
       const int slot = tap & 1;
+      // Global loads are dealt out over the taps, a few per tap, so that the wave never
+      // stalls on a full memory-instruction queue.  The weight buffer of this chunk is free
+      // after the barrier: tap 8 starts refilling it for chunk s+2 (blocks 0,1) and taps 0..5
+      // of the next chunk finish that (blocks 2..8).  Staged words likewise: slot 0 at tap 8
+      // (for chunk s+3), slots 1..5 at taps 0..4 (for chunk s+2, written to LDS at tap 7).
+      constexpr int kLPT = (NL + 5) / 6;        // staged words requested per slot
       if (tap == 8) {
-        // after the barrier: refill this chunk's weight buffer for chunk s+2, request the
-        // staged words of chunk s+2+D
         int gx, cx;
         chunk_of(s + 2, gx, cx);
-        weights_to_lds(cx, const_cast<uint8_t*>(w_cur));
+        weights_to_lds(cx, const_cast<uint8_t*>(w_cur), 0, 2);
         __builtin_amdgcn_sched_barrier(0);
-        chunk_of(s + 2 + D, gx, cx);
-        stage_load<NL>(wd[D - 1], plan, p, K, b, gx, cx);
+        chunk_of(s + 3, gx, cx);
+        stage_load<NL>(wd[0], plan, p, K, b, gx, cx, 0, kLPT);
         fetch(a_next, w_next, 0, slot ^ 1);
       } else {
+        if (tap <= 5) {
+          int gx, cx;
+          chunk_of(s + 1, gx, cx);
+          weights_to_lds(cx, w_next, tap == 0 ? 2 : 3 + tap, tap == 0 ? 4 : 4 + tap);
+          if (tap <= 4) {
+            chunk_of(s + 2, gx, cx);
+            stage_load<NL>(wd[0], plan, p, K, b, gx, cx, (tap + 1) * kLPT, (tap + 2) * kLPT);
+          }
+        }
         fetch(a_cur, w_cur, tap + 1, slot ^ 1);
       }
 #pragma unroll
