@@ -310,9 +310,19 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int row = wave;                        // output row of this wave inside the tile
   const int q = wave;                          // and the cin quad it aggregates in every chunk
-  const int b = blockIdx.z;
-  const int co_tile = blockIdx.y;
-  const int y0 = blockIdx.x * kRows;
+  // Workgroups are handed to the 8 XCDs round-robin.  Tiles are numbered row tile fastest,
+  // then cout tile, then sample, and XCD x takes the x-th eighth of that list: row tiles
+  // that are neighbours in the image then run at about the same time under the same L2, which
+  // sees their shared halo rows once and merges their partial output lines.
+  int tile = blockIdx.x;
+  {
+    const int n_tiles = gridDim.x;
+    if ((n_tiles & 7) == 0) tile = (tile & 7) * (n_tiles >> 3) + (tile >> 3);
+  }
+  const int n_co_tiles = p.Cout / kCoutTile;
+  const int y0 = (tile % p.row_tiles) * kRows;
+  const int co_tile = (tile / p.row_tiles) % n_co_tiles;
+  const int b = tile / (p.row_tiles * n_co_tiles);
   const int y = y0 + row;
   const bool row_ok = y < p.H;                 // wave-uniform
   const int NC = p.Cin / kChunk;
@@ -630,7 +640,7 @@ hipError_t mfma_launch(const LayerParams& p, hipStream_t s) {
     const double q = (double)p.wj[j] * (double)(1u << kFixShift);
     mp.wq[j] = j < p.K ? (uint32_t)(q + 0.5) : 0u;
   }
-  const dim3 grid(mp.row_tiles, p.Cout / kCoutTile, p.B);
+  const dim3 grid(mp.row_tiles * (p.Cout / kCoutTile) * p.B);
   switch (p.K) {
     case 1: return launch_kt<1>(mp, grid, s);
     case 2: return launch_kt<2>(mp, grid, s);
