@@ -2,31 +2,35 @@
 // membrane-stationary over time.
 //
 // GEMM view of one convolution stage (Alg. 1 / Alg. 2, "Y_k <- Conv2d(A_k, W)"):
-//     Y^T[cout][pixel] = sum over (tap, cin) of  W[cout][cin][tap] * A_k[cin][pixel + tap]
+//     Y^T[cout][pixel] = sum over (tap, cin) of  W[cout][cin][tap] * A_k[cin][pixel * stride + tap]
 // The kernel W is the MFMA A-operand (rows = cout) and the aggregated frame is the
 // B-operand (columns = pixels), so one v_mfma_f32_32x32x16_bf16 result holds 32 cout x 32
-// x-consecutive pixels with the pixels along the lanes: a wave ballot of "V >= theta" is
-// then directly two packed output words.
+// consecutive output pixels with the pixels along the lanes: a wave ballot of "V >= theta"
+// is then directly packed output words.
 //
-// One workgroup = 4 wavefronts (one per SIMD, 512 registers each) owns a tile of 4 output
-// rows x 64 pixels x 128 output channels of one sample for the WHOLE call: its membrane V
-// (fp32) never leaves the registers between the first and the last timestep.  Wave w handles
-// output row w: 4 x 2 MFMA tiles, 128 accumulator + 128 membrane registers.
+// One workgroup = 4 wavefronts (one per SIMD, 512 registers each) owns a tile of 256 output
+// pixels x 128 output channels of one sample for the WHOLE call: its membrane V (fp32) never
+// leaves the registers between the first and the last timestep.  A wave handles 64 output
+// pixels (two 32-pixel MFMA column blocks) x 128 channels: 4 x 2 MFMA tiles, 128 accumulator +
+// 128 membrane registers.  The geometry <WIN, S> (input width 32 or 64, stride 1 or 2) decides
+// how the 64 pixels of a wave fold into output rows: one row of 64, two rows of 32, or four
+// rows of 16.
 //
 // Per group of K frames and per chunk of 16 input channels, everything one chunk ahead of
 // the MFMAs that consume it:
-//   staging  the chunk's packed input words (16 cin x 6 haloed rows x 2 words x K frames)
-//            are copied global -> LDS, rows outside the image as zero words;
-//   loader   lane x reads the word that holds its pixel (a two-address broadcast LDS read,
-//            all K frames of it at once), extracts its bit and accumulates the decay weight
-//            as a 24-bit fixed-point integer, one v_bfe + one v_mad per frame; the aggregate
-//            A_k (Eq. 2) is converted once, rounded to bf16 and written to LDS as
-//            [k-half][row][x][8 cin] with zero columns left and right as the padding; it is
-//            never written to HBM;
+//   staging  the chunk's packed input words (16 cin x haloed rows x K frames) are copied
+//            global -> registers -> LDS, rows outside the image as zero words;
+//   loader   a lane reads the word that holds its input pixel (a two-address broadcast LDS
+//            read, all K frames of it at once), extracts its bit and accumulates the decay
+//            weight as a 24-bit fixed-point integer, one v_bfe + one v_mad per frame; the
+//            aggregate A_k (Eq. 2) is converted once, rounded to bf16 and written to LDS as
+//            [k-half][row][column][8 cin] with zero columns left and right as the padding
+//            (for stride 2 the even and the odd columns are stored apart, so that a fragment
+//            read is contiguous again); it is never written to HBM;
 //   weights  the chunk's 9 taps x 128 cout x 16 cin, pre-arranged in MFMA operand order, are
-//            copied global -> LDS;
-//   MFMA     9 taps x 8 MFMAs per wave, operands read from LDS as conflict-free 16-byte
-//            fragments; im2col is only the (ky, kx) offset in the fragment address.
+//            copied global -> LDS without passing through registers;
+//   MFMA     9 taps x 8 MFMAs per wave, operands read from LDS as 16-byte fragments; im2col
+//            is only the (ky, kx) offset in the fragment address.
 // After the last chunk: LIF epilogue on the accumulators (one step for TAC / per-step, K
 // steps with the same Y_k for TAC-TP), ballot, packed stores.
 //
@@ -47,31 +51,48 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
 
 constexpr int kThreads = 256;
-constexpr int kRows = 4;                       // output rows per tile = waves per workgroup
-constexpr int kInRows = kRows + 2;             // with the 3x3 halo
-constexpr int kW = 64;                         // row width handled by this kernel
-constexpr int kXP = kW + 2;                    // padded row in LDS
+constexpr int kWaves = 4;
 constexpr int kCoutTile = 128;
 constexpr int kMC = kCoutTile / 32;            // MFMA row blocks per wave
 constexpr int kChunk = 16;                     // input channels per MFMA k-step
-constexpr int kAHalf = kInRows * kXP * 16;     // bytes: one k-half plane [row][xp][8 bf16]
-constexpr int kABuf = 2 * kAHalf;
 constexpr int kWTap = kMC * 64 * 16;           // bytes of one tap: [mc][lane][8 bf16]
 constexpr int kWBuf = 9 * kWTap;
-constexpr int kWUnits = kWBuf / 16;            // 16-byte units per chunk of weights
-constexpr int kWLoads = (kWUnits + kThreads - 1) / kThreads;
-constexpr int kWBlocks = kWBuf / 1024 / kRows;     // one-KiB weight blocks each wave copies per chunk
-constexpr int kWordsPerFrame = kChunk * kInRows * 2;   // staged dwords per chunk and frame
+constexpr int kWBlocks = kWBuf / 1024 / kWaves;     // one-KiB weight blocks each wave copies per chunk
 constexpr int kFixShift = 23;                  // fixed-point scale of the aggregation weights
-constexpr int kLdsA = 0;
-constexpr int kLdsW = kLdsA + 2 * kABuf;
-constexpr int kLdsBias = kLdsW + 2 * kWBuf;
-constexpr int kLdsWords = kLdsBias + kCoutTile * 4;     // two staging buffers follow
+constexpr int kLdsLimit = 160 * 1024;          // LDS of one compute unit
 
-__host__ __device__ constexpr int words_buf_bytes(int K) { return kWordsPerFrame * K * 4; }
-__host__ __device__ constexpr int lds_bytes(int K) { return kLdsWords + 2 * words_buf_bytes(K); }
+// Compile-time geometry of a tile: input width WIN (32 or 64 pixels = 1 or 2 words), stride S.
+template <int WIN, int S>
+struct Geo {
+  static constexpr int kWo = WIN / S;                        // output width: 64, 32 or 16
+  static constexpr int kWaveRows = 64 / kWo;                 // output rows per wave
+  static constexpr int kTileRows = kWaves * kWaveRows;       // output rows per workgroup
+  static constexpr int kInRows = (kTileRows - 1) * S + 3;    // input rows with the 3x3 halo
+  static constexpr int kWW = WIN / 32;                       // words per input row
+  static constexpr int kRowWords = kInRows * kWW;            // staged words per channel and frame
+  static constexpr int kSteps = (kRowWords + 1) / 2;         // loader steps of 64 input pixels each
+  static constexpr bool kOddTail = (kRowWords & 1) != 0;     // the last step has only 32 pixels
+  static constexpr int kXP = WIN + 2;                        // padded row, in pixels
+  static constexpr int kXH = kXP / 2;                        // stride 2: columns per parity
+  static constexpr int kAHalf = kInRows * kXP * 16;          // bytes: one k-half plane
+  static constexpr int kABuf = 2 * kAHalf;
+  static constexpr int kWordsPerFrame = kChunk * kRowWords;  // staged dwords per chunk and frame
+  static constexpr int kOutWords = (kWo + 31) / 32;          // packed words per output row
+  static constexpr int kLdsA = 0;
+  static constexpr int kLdsW = kLdsA + 2 * kABuf;
+  static constexpr int kLdsBias = kLdsW + 2 * kWBuf;
+  static constexpr int kLdsWords = kLdsBias + kCoutTile * 4; // two staging buffers follow
+  static constexpr int lds_bytes(int K) { return kLdsWords + 2 * kWordsPerFrame * K * 4; }
+  // LDS column (in 16-byte units) of padded pixel xp
+  __host__ __device__ static constexpr int col(int xp) { return S == 1 ? xp : (xp & 1) * kXH + (xp >> 1); }
+  // the loader pipeline has kSteps + 1 slots (slot i requests step i and expands step i-1),
+  // spread over the 8 filter taps in front of the workgroup barrier
+  static constexpr int kSlotsPerTap = (kSteps + 1 + 7) / 8;
+};
 
 struct MfmaParams {
   const uint32_t* __restrict__ spikes;
@@ -80,7 +101,7 @@ struct MfmaParams {
   float* __restrict__ v_inout;
   uint32_t* __restrict__ out;
   float* __restrict__ v_trace;
-  int B, Cin, H, Cout, K, G, n_lif, row_tiles;
+  int B, Cin, H, Ho, Cout, K, G, n_lif, row_tiles;
   float decay, theta;
   uint32_t wq[TAC_MAX_K];              // round(beta^(K-1-j) * 2^23)
 };
@@ -90,16 +111,16 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // v_cvt_pk_bf16_f32, nearest even
 }
 
-template <int LANE_LO, int LANE_HI>
-__device__ __forceinline__ uint32_t write_lanes(uint32_t old, uint64_t ballot) {
-  // vdst[LANE_LO] = low half, vdst[LANE_HI] = high half of a wave-uniform 64-bit ballot; other
-  // lanes keep `old`.  The s_nop covers the two wait states this chip needs between a vector
-  // instruction that wrote the SGPR pair (the compare, or a spill reload) and a vector
-  // instruction that reads it: the assembler text is opaque to the compiler's hazard pass.
+// vdst[LANE_A] = a, vdst[LANE_B] = b for wave-uniform a, b; other lanes keep `old`.  The s_nop
+// covers the two wait states this chip needs between a vector instruction that wrote the SGPR
+// (the compare, or a spill reload) and a vector instruction that reads it: the assembler text
+// is opaque to the compiler's hazard pass.
+template <int LANE_A, int LANE_B>
+__device__ __forceinline__ uint32_t write_lanes(uint32_t old, uint32_t a, uint32_t b) {
   uint32_t r;
   asm volatile("s_nop 1\n\tv_writelane_b32 %0, %1, %3\n\tv_writelane_b32 %0, %2, %4"
                : "=v"(r)
-               : "s"((uint32_t)ballot), "s"((uint32_t)(ballot >> 32)), "n"(LANE_LO), "n"(LANE_HI), "0"(old));
+               : "s"(a), "s"(b), "n"(LANE_A), "n"(LANE_B), "0"(old));
   return r;
 }
 
@@ -111,14 +132,45 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// Per-lane constants of the epilogue: where the lane's two pixels (np = 0, 1) sit.
+struct LaneGeom {
+  uint32_t v_off[2];     // byte offset of (4 h channels, local row, column) in the wave's membrane block
+  float theta[2];        // the threshold, or +inf where the pixel's output row is outside the image
+  bool ok[2];            // the pixel's output row is inside the image
+};
+
+// Computed afresh wherever it is needed (from an opaque copy of the lane id), so that it does
+// not occupy registers across the MFMA loop.
+template <class G>
+__device__ __forceinline__ LaneGeom lane_geom(int lane, int oy_wave, int Ho, size_t plane, float theta) {
+  asm volatile("" : "+v"(lane));
+  LaneGeom lg;
+  const int n = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int np = 0; np < 2; ++np) {
+    const int pix = np * 32 + n;
+    // one row per wave: the row test below is wave-uniform and the threshold stays scalar
+    const int lr = G::kWaveRows == 1 ? 0 : pix / G::kWo, ox = G::kWaveRows == 1 ? pix : pix % G::kWo;
+    lg.v_off[np] = (uint32_t)((4 * h * plane + (size_t)lr * G::kWo + ox) * 4);
+    lg.ok[np] = oy_wave + lr < Ho;
+    lg.theta[np] = lg.ok[np] ? theta : __builtin_inff();
+  }
+  return lg;
+}
+
 // One LIF step on a wave's 4 x 2 MFMA tiles: V <- decay V + Y, spike iff V >= theta,
-// subtractive reset.  The ballots of the step are gathered, one 32-bit half per lane, into
-// one store register per 32-channel block: lane L = (r << 2) | (hi << 1) | np of word[mc]
-// holds the packed word of cout 32 mc + 8 (r/4) + 4 hi + r%4, x-block np.
-template <bool TRACE>
+// subtractive reset.  Register r of tile (mc, np) on lane (n, h) is channel
+// 32 mc + 8 (r/4) + 4 h + r%4 at the wave's pixel 32 np + n.  The ballot of a register is two
+// 32-bit halves (h = 0, 1), each the packed spikes of 32 consecutive output pixels of one
+// channel; they are handed, one per lane, to the store registers word[mc][..]:
+//   output width 64 or 32: lane (r << 2) | (h << 1) | np of word[mc][0] holds pixel block np;
+//   output width 16:       a half is two rows of 16 pixels; lane
+//                          ((r & 7) << 3) | (h << 2) | (np << 1) | sub of word[mc][r >> 3] holds
+//                          row 2 np + sub.
+template <int WO, bool TRACE>
 __device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&acc)[kMC][2], float decay, float theta,
-                                         uint32_t (&word)[kMC], float* __restrict__ trace_wave, size_t plane,
-                                         uint32_t lane_bytes) {
+                                         const LaneGeom& lg, uint32_t (&word)[kMC][2], float* __restrict__ trace_wave,
+                                         size_t plane) {
   static_for<0, kMC>([&](auto mc_) {
     constexpr int mc = decltype(mc_)::value;
     static_for<0, 2>([&](auto np_) {
@@ -132,18 +184,28 @@ __device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] = fmaf(decay, V[mc][np][r0 + i], acc[mc][np][r0 + i]);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) m[i] = __builtin_amdgcn_ballot_w64(v[i] >= theta);
-        word[mc] = write_lanes<((r0 + 0) << 2) | np, ((r0 + 0) << 2) | 2 | np>(word[mc], m[0]);
-        word[mc] = write_lanes<((r0 + 1) << 2) | np, ((r0 + 1) << 2) | 2 | np>(word[mc], m[1]);
-        word[mc] = write_lanes<((r0 + 2) << 2) | np, ((r0 + 2) << 2) | 2 | np>(word[mc], m[2]);
-        word[mc] = write_lanes<((r0 + 3) << 2) | np, ((r0 + 3) << 2) | 2 | np>(word[mc], m[3]);
+        for (int i = 0; i < 4; ++i) m[i] = __builtin_amdgcn_ballot_w64(v[i] >= lg.theta[np]);
+        static_for<0, 4>([&](auto i_) {
+          constexpr int i = decltype(i_)::value;
+          constexpr int r = r0 + i;
+          const uint32_t lo = (uint32_t)m[i], hi = (uint32_t)(m[i] >> 32);
+          if constexpr (WO >= 32) {
+            word[mc][0] = write_lanes<(r << 2) | np, (r << 2) | 2 | np>(word[mc][0], lo, hi);
+          } else {
+            constexpr int base = ((r & 7) << 3) | (np << 1);
+            word[mc][r >> 3] = write_lanes<base, base | 1>(word[mc][r >> 3], lo & 0xffffu, lo >> 16);
+            word[mc][r >> 3] = write_lanes<base | 4, base | 5>(word[mc][r >> 3], hi & 0xffffu, hi >> 16);
+          }
+        });
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           V[mc][np][r0 + i] = __builtin_amdgcn_inverse_ballot_w64(m[i]) ? v[i] - theta : v[i];
-          if constexpr (TRACE)
-            *reinterpret_cast<float*>(reinterpret_cast<char*>(trace_wave) +
-                                      ((size_t)(mc * 32 + 8 * ((r0 + i) >> 2) + ((r0 + i) & 3)) * plane + np * 32) * 4 +
-                                      lane_bytes) = v[i];
+          if constexpr (TRACE) {
+            if (lg.ok[np])
+              *reinterpret_cast<float*>(reinterpret_cast<char*>(trace_wave) +
+                                        (size_t)(mc * 32 + 8 * ((r0 + i) >> 2) + ((r0 + i) & 3)) * plane * 4 +
+                                        lg.v_off[np]) = v[i];
+          }
         }
         __builtin_amdgcn_sched_barrier(0);   // keep only a few ballots alive
       });
@@ -152,11 +214,12 @@ __device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&
 }
 
 // ---- staging of packed input words ------------------------------------------------------
-// Flat staging index i in [0, 192 K): i = (j * 16 + cin) * 12 + row * 2 + half, so that
-// consecutive threads read consecutive dwords of one (frame, channel) plane.  In LDS the
-// K frames of one (cin, row, half) are adjacent: index ((cin * 6 + row) * 2 + half) * K + j.
-// A thread's share of a chunk is the same in every chunk, so its global dword offsets
-// (relative to the chunk's first frame and channel) and LDS indices are computed once.
+// Flat staging index i in [0, F K) with F = 16 * rows * words-per-row:
+// i = j * F + (cin * rows + row) * wpr + word, so that consecutive threads read consecutive
+// dwords of one (frame, channel) plane.  In LDS the K frames of one (cin, row, word) are
+// adjacent: index ((cin * rows + row) * wpr + word) * K + j.  A thread's share of a chunk is
+// the same in every chunk, so its global dword offsets (relative to the chunk's first frame and
+// channel) and LDS indices are computed once.
 template <int NL>
 struct StagePlan {
   uint32_t goff[NL];     // dword offset from the chunk base (always a valid address)
@@ -164,9 +227,9 @@ struct StagePlan {
   uint32_t keep;         // bit l set: the word is inside the image; clear: store a zero word (padding row)
 };
 
-template <int NL>
-__device__ __forceinline__ void stage_plan(StagePlan<NL>& sp, const MfmaParams& p, int K, int tid, int y0) {
-  const int n = kWordsPerFrame * K;
+template <class G, int NL>
+__device__ __forceinline__ void stage_plan(StagePlan<NL>& sp, const MfmaParams& p, int K, int tid, int iy0) {
+  const int n = G::kWordsPerFrame * K;
   sp.keep = 0;
 #pragma unroll
   for (int l = 0; l < NL; ++l) {
@@ -174,25 +237,26 @@ __device__ __forceinline__ void stage_plan(StagePlan<NL>& sp, const MfmaParams& 
     sp.goff[l] = 0;
     sp.lidx[l] = 0xffffffffu;
     if (i < n) {
-      const int j = i / kWordsPerFrame;
-      const int rem = i - j * kWordsPerFrame;              // (cin * 6 + row) * 2 + half
-      const int cin = rem / (kInRows * 2);
-      const int rh = rem - cin * (kInRows * 2);
-      const int iy = y0 - 1 + (rh >> 1);
+      const int j = i / G::kWordsPerFrame;
+      const int rem = i - j * G::kWordsPerFrame;           // (cin * rows + row) * wpr + word
+      const int cin = rem / G::kRowWords;
+      const int rw = rem - cin * G::kRowWords;
+      const int row = rw / G::kWW, word = rw - row * G::kWW;
+      const int iy = iy0 + row;
       const int iyc = min(max(iy, 0), p.H - 1);
       sp.lidx[l] = (uint32_t)(rem * K + j);
-      sp.goff[l] = (uint32_t)((((size_t)j * p.B * p.Cin + cin) * p.H + iyc) * 2 + (rh & 1));
+      sp.goff[l] = (uint32_t)((((size_t)j * p.B * p.Cin + cin) * p.H + iyc) * G::kWW + word);
       if (iy == iyc) sp.keep |= 1u << l;
     }
   }
 }
 
 // Unconditional loads (no lane masking, no register initialisation in front of them).
-template <int NL>
+template <class G, int NL>
 __device__ __forceinline__ void stage_load(uint32_t (&wd)[NL], const StagePlan<NL>& sp, const MfmaParams& p, int K,
                                            int b, int g, int c, int l0 = 0, int l1 = NL) {
   // wave-uniform base of (first frame of group g, sample b, first channel of chunk c)
-  const uint32_t* base = p.spikes + (((size_t)(g * K) * p.B + b) * p.Cin + c * kChunk) * p.H * 2;
+  const uint32_t* base = p.spikes + (((size_t)(g * K) * p.B + b) * p.Cin + c * kChunk) * p.H * G::kWW;
 #pragma unroll
   for (int l = 0; l < NL; ++l)
     if (l >= l0 && l < l1) wd[l] = base[sp.goff[l]];
@@ -206,24 +270,51 @@ __device__ __forceinline__ void stage_store(const uint32_t (&wd)[NL], const Stag
       reinterpret_cast<uint32_t*>(words_buf)[sp.lidx[l]] = (sp.keep >> l) & 1u ? wd[l] : 0u;
 }
 
-// The loader works in two halves one filter tap apart, so that the LDS latency of the word
-// reads hides behind the MFMAs of a tap: read_words fetches, for lane x, the K staged words
-// (one per frame) that hold pixel x of input row r for each of the wave's 4 channels (cin
-// quad q); expand_words turns them into the 4 bf16 aggregates and writes them into the A
-// tile under construction.
+// The loader works in steps of 64 input pixels (one row of 64, or two rows of 32) and in two
+// halves one pipeline slot apart, so that the LDS latency of the word reads hides behind the
+// MFMAs: read_words fetches, for the lane's pixel, the K staged words (one per frame) for each
+// of the wave's 4 channels (cin quad q); expand_words turns them into the 4 bf16 aggregates
+// and writes them into the A tile under construction.
 template <int KT>
 struct RowWords {
   static constexpr int N = KT > 0 ? KT : 1;
   uint32_t w[4][N];
 };
 
-template <int KT>
-__device__ __forceinline__ void read_words(RowWords<KT>& rw, const uint8_t* words_buf, int lane, int q, int r) {
+// index of the lane's word within a channel's [row][word] block at loader step `step`; in an
+// odd last step the upper 32 lanes have no pixel and re-read the lower lanes' word
+template <class G>
+__device__ __forceinline__ int lane_word(int lane, int step) {
+  return step * 2 + ((G::kOddTail && step == G::kSteps - 1) ? 0 : (lane >> 5));
+}
+
+// byte offset in a k-half plane of the A tile of the lane's pixel at loader step `step`
+template <class G>
+__device__ __forceinline__ int a_write_off(int lane, int step) {
+  if constexpr (G::kWW == 2)
+    return (step * G::kXP + G::col(lane + 1)) * 16;
+  else
+    return ((step * 2 + (lane >> 5)) * G::kXP + G::col((lane & 31) + 1)) * 16;
+}
+
+template <class G>
+__device__ __forceinline__ void a_write(uint8_t* a_next, int lane, int q, int step, const float (&val)[4]) {
+  const u32x2 pk = {pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])};
+  u32x2* dst = reinterpret_cast<u32x2*>(a_next + (q >> 1) * G::kAHalf + a_write_off<G>(lane, step) + (q & 1) * 8);
+  if (G::kOddTail && step == G::kSteps - 1) {
+    if (lane < 32) *dst = pk;
+  } else {
+    *dst = pk;
+  }
+}
+
+template <class G, int KT>
+__device__ __forceinline__ void read_words(RowWords<KT>& rw, const uint8_t* words_buf, int lane, int q, int step) {
   static_assert(KT > 0, "compile-time K only");
   const uint32_t* wb = reinterpret_cast<const uint32_t*>(words_buf);
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    const uint32_t* src = wb + ((((q * 4 + e) * kInRows + r) * 2 + (lane >> 5)) * KT);
+    const uint32_t* src = wb + (((q * 4 + e) * G::kRowWords + lane_word<G>(lane, step)) * KT);
     if constexpr (KT >= 4) {
 #pragma unroll
       for (int j4 = 0; j4 < KT / 4; ++j4) {
@@ -241,9 +332,9 @@ __device__ __forceinline__ void read_words(RowWords<KT>& rw, const uint8_t* word
   }
 }
 
-template <int KT>
+template <class G, int KT>
 __device__ __forceinline__ void expand_words(const RowWords<KT>& rw, const MfmaParams& p, uint8_t* a_next, int lane,
-                                             int q, int r) {
+                                             int q, int step) {
   const uint32_t bitpos = lane & 31;
   float val[4];
 #pragma unroll
@@ -257,36 +348,31 @@ __device__ __forceinline__ void expand_words(const RowWords<KT>& rw, const MfmaP
     }
     val[e] = (float)acc;
   }
-  u32x2 pk = {pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])};
-  *reinterpret_cast<u32x2*>(a_next + (q >> 1) * kAHalf + (r * kXP + lane + 1) * 16 + (q & 1) * 8) = pk;
+  a_write<G>(a_next, lane, q, step, val);
 }
 
 // Unpipelined form (prologue, and the run-time-K kernel).
-template <int KT>
-__device__ __forceinline__ void expand_row(const MfmaParams& p, const uint8_t* words_buf, uint8_t* a_next, int K,
-                                           int lane, int q, int r) {
+template <class G, int KT>
+__device__ __forceinline__ void expand_step(const MfmaParams& p, const uint8_t* words_buf, uint8_t* a_next, int K,
+                                            int lane, int q, int step) {
   if constexpr (KT > 0) {
     RowWords<KT> rw;
-    read_words<KT>(rw, words_buf, lane, q, r);
-    expand_words<KT>(rw, p, a_next, lane, q, r);
+    read_words<G, KT>(rw, words_buf, lane, q, step);
+    expand_words<G, KT>(rw, p, a_next, lane, q, step);
   } else {
     const uint32_t* wb = reinterpret_cast<const uint32_t*>(words_buf);
     const uint32_t bitpos = lane & 31;
     float val[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const uint32_t* src = wb + ((((q * 4 + e) * kInRows + r) * 2 + (lane >> 5)) * K);
+      const uint32_t* src = wb + (((q * 4 + e) * G::kRowWords + lane_word<G>(lane, step)) * K);
       uint32_t acc = 0;
       for (int j = 0; j < K; ++j) acc = __umul24(__builtin_amdgcn_ubfe(src[j], bitpos, 1), p.wq[j]) + acc;
       val[e] = (float)acc;
     }
-    u32x2 pk = {pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])};
-    *reinterpret_cast<u32x2*>(a_next + (q >> 1) * kAHalf + (r * kXP + lane + 1) * 16 + (q & 1) * 8) = pk;
+    a_write<G>(a_next, lane, q, step, val);
   }
 }
-
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-typedef const __attribute__((address_space(1))) void* global_void_ptr;
 
 // Workgroup barrier that orders LDS traffic only: the compiler waits for this wave's LDS
 // accesses and for its direct-to-LDS loads, but leaves ordinary global loads in flight.
@@ -296,20 +382,19 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int KT>
-__global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) {
+// TRACE: also write the pre-reset membrane of every LIF step (a kernel of its own, so that the
+// stores and their addresses do not weigh on the register allocation of the plain one).
+template <int KT, int WIN, int S, bool TRACE>
+__global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
+  using G = Geo<WIN, S>;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-  constexpr int NL = KT > 0 ? (kWordsPerFrame * KT + kThreads - 1) / kThreads
-                            : (kWordsPerFrame * TAC_MAX_K + kThreads - 1) / kThreads;
-  // depth of the register pipeline of staged words: loads are issued D chunks before the
-  // words are written to LDS (they come from HBM)
-  constexpr int D = 1;
+  constexpr int KMAX = KT > 0 ? KT : TAC_MAX_K;
+  constexpr int NL = (G::kWordsPerFrame * KMAX + kThreads - 1) / kThreads;
   const int K = KT > 0 ? KT : p.K;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int row = wave;                        // output row of this wave inside the tile
-  const int q = wave;                          // and the cin quad it aggregates in every chunk
+  const int q = wave;                          // the cin quad this wave aggregates in every chunk
   // Workgroups are handed to the 8 XCDs round-robin.  Tiles are numbered row tile fastest,
   // then cout tile, then sample, and XCD x takes the x-th eighth of that list: row tiles
   // that are neighbours in the image then run at about the same time under the same L2, which
@@ -320,47 +405,61 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
     if ((n_tiles & 7) == 0) tile = (tile & 7) * (n_tiles >> 3) + (tile >> 3);
   }
   const int n_co_tiles = p.Cout / kCoutTile;
-  const int y0 = (tile % p.row_tiles) * kRows;
+  const int y0 = (tile % p.row_tiles) * G::kTileRows;          // first output row of the tile
   const int co_tile = (tile / p.row_tiles) % n_co_tiles;
   const int b = tile / (p.row_tiles * n_co_tiles);
-  const int y = y0 + row;
-  const bool row_ok = y < p.H;                 // wave-uniform
   const int NC = p.Cin / kChunk;
   const int n = lane & 31, h = lane >> 5;
-  const int Ho = p.H;
+  const int Ho = p.Ho;
   const int co_wave = co_tile * kCoutTile;
   const int total = p.G * NC;
-  uint8_t* const words0 = lds + kLdsWords;
-  const int words_bytes = kWordsPerFrame * K * 4;
+  uint8_t* const words0 = lds + G::kLdsWords;
+  const int words_bytes = G::kWordsPerFrame * K * 4;
+  const int oy_wave = y0 + wave * G::kWaveRows;                // first output row of this wave
 
-  // zero padding columns of both A buffers (never written again)
-  if (tid < 2 * 2 * kInRows * 2) {
-    const int col = tid & 1, rr = (tid >> 1) % kInRows, hh = (tid >> 1) / kInRows % 2, bb = (tid >> 1) / (2 * kInRows);
-    *reinterpret_cast<u32x4*>(lds + kLdsA + bb * kABuf + hh * kAHalf + (rr * kXP + col * (kXP - 1)) * 16) = u32x4{0, 0, 0, 0};
+  // zero padding columns (left of pixel 0, right of the last pixel) of both A buffers; they
+  // are never written again
+  for (int i = tid; i < 2 * 2 * G::kInRows * 2; i += kThreads) {
+    const int side = i & 1, rr = (i >> 1) % G::kInRows, hh = (i >> 1) / G::kInRows % 2, bb = (i >> 1) / (2 * G::kInRows);
+    const int c = side ? G::col(WIN + 1) : G::col(0);
+    *reinterpret_cast<u32x4*>(lds + G::kLdsA + bb * G::kABuf + hh * G::kAHalf + (rr * G::kXP + c) * 16) = u32x4{0, 0, 0, 0};
   }
   if (tid < kCoutTile)
-    reinterpret_cast<float*>(lds + kLdsBias)[tid] = p.bias ? p.bias[co_tile * kCoutTile + tid] : 0.f;
+    reinterpret_cast<float*>(lds + G::kLdsBias)[tid] = p.bias ? p.bias[co_tile * kCoutTile + tid] : 0.f;
 
-  // membrane, MFMA result layout: register r of tile (mc, np), lane -> cout = 32 mc + 8 (r/4) + 4 h + r%4, x = 32 np + n
+  // the lane's two pixels (np = 0, 1): local output row, column, validity
+  const size_t plane = (size_t)Ho * G::kWo;                    // elements per (b, cout)
+  int a_frag_off[2];                                           // byte offset of the lane's B fragments, tap (0, 0)
+#pragma unroll
+  for (int np = 0; np < 2; ++np) {
+    const int pix = np * 32 + n;
+    const int lr = pix / G::kWo, ox = pix % G::kWo;
+    a_frag_off[np] = h * G::kAHalf + (((wave * G::kWaveRows + lr) * S) * G::kXP + G::col(ox * S)) * 16;
+  }
+  // wave-uniform element offset of (sample, first channel of the tile, first row of the wave)
+  const size_t v_wave = ((size_t)b * p.Cout + co_wave) * plane + (size_t)oy_wave * G::kWo;
+
+  // membrane, MFMA result layout: register r of tile (mc, np), lane -> cout = 32 mc + 8 (r/4) + 4 h + r%4
   float V[kMC][2][16];
   f32x16 acc[kMC][2];
-  const size_t plane = (size_t)Ho * kW;                               // elements per (b, cout)
-  // wave-uniform base of this wave's channels at row y; the lane adds 4 h channels + n
-  const size_t v_wave = ((size_t)b * p.Cout + co_wave) * plane + (size_t)y * kW;
-  const uint32_t v_lane = (uint32_t)(4 * h * plane + n) * 4u;         // bytes
-  if (p.v_inout && row_ok) {
+#pragma unroll
+  for (int mc = 0; mc < kMC; ++mc)
+#pragma unroll
+    for (int np = 0; np < 2; ++np)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) V[mc][np][r] = 0.f;
+  if (p.v_inout) {
+    const LaneGeom lg = lane_geom<G>(lane, oy_wave, Ho, plane, p.theta);
     const char* vb = reinterpret_cast<const char*>(p.v_inout + v_wave);
-    static_for<0, kMC>([&](auto mc_) { static_for<0, 2>([&](auto np_) { static_for<0, 16>([&](auto r_) {
-      constexpr int mc = decltype(mc_)::value, np = decltype(np_)::value, r = decltype(r_)::value;
-      V[mc][np][r] = *reinterpret_cast<const float*>(vb + ((size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane + np * 32) * 4 + v_lane);
-    }); }); });
-  } else {
-#pragma unroll
-    for (int mc = 0; mc < kMC; ++mc)
-#pragma unroll
-      for (int np = 0; np < 2; ++np)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) V[mc][np][r] = 0.f;
+    static_for<0, 2>([&](auto np_) {
+      constexpr int np = decltype(np_)::value;
+      if (lg.ok[np]) {
+        static_for<0, kMC>([&](auto mc_) { static_for<0, 16>([&](auto r_) {
+          constexpr int mc = decltype(mc_)::value, r = decltype(r_)::value;
+          V[mc][np][r] = *reinterpret_cast<const float*>(vb + (size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane * 4 + lg.v_off[np]);
+        }); });
+      }
+    });
   }
 
   const uint8_t* wsrc = p.w + (size_t)co_tile * NC * kWBuf;
@@ -376,47 +475,35 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
     const uint8_t* src = wsrc + (size_t)cx * kWBuf;
 #pragma unroll
     for (int i = i0; i < i1; ++i) {
-      const int blk = wave + kRows * i;
+      const int blk = wave + kWaves * i;
       __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (uint32_t)(blk * 1024) + w_lane_off),
                                        (lds_void_ptr)(w_dst + blk * 1024), 16, 0, 0);
     }
   };
 
   StagePlan<NL> plan;
-  stage_plan<NL>(plan, p, K, tid, y0);
-  uint32_t wd[D][NL];                           // staged words in flight; wd[0] is written to LDS next
+  stage_plan<G, NL>(plan, p, K, tid, y0 * S - 1);
+  uint32_t wd[NL];                              // staged words in flight
 
   // ---- prologue: A tile of chunk 0, weights of chunks 0 and 1, staged words of chunk 1,
-  //      words of chunks 2 .. 1+D in registers
+  //      words of chunk 2 in registers
   {
-    weights_to_lds(0, lds + kLdsW, 0, kWBlocks);
+    weights_to_lds(0, lds + G::kLdsW, 0, kWBlocks);
     int gx, cx;
     chunk_of(1, gx, cx);
-    weights_to_lds(cx, lds + kLdsW + kWBuf, 0, kWBlocks);
-    uint32_t w0[NL];
-    stage_load<NL>(w0, plan, p, K, b, 0, 0);
-    stage_store<NL>(w0, plan, words0);
-    stage_load<NL>(w0, plan, p, K, b, gx, cx);
-    stage_store<NL>(w0, plan, words0 + words_bytes);
+    weights_to_lds(cx, lds + G::kLdsW + kWBuf, 0, kWBlocks);
+    stage_load<G, NL>(wd, plan, p, K, b, 0, 0);
+    stage_store<NL>(wd, plan, words0);
+    stage_load<G, NL>(wd, plan, p, K, b, gx, cx);
+    stage_store<NL>(wd, plan, words0 + words_bytes);
     __syncthreads();
-    for (int r = 0; r < kInRows; ++r) expand_row<KT>(p, words0, lds + kLdsA, K, lane, q, r);
-#pragma unroll
-    for (int d = 0; d < D; ++d) {
-      chunk_of(2 + d, gx, cx);
-      stage_load<NL>(wd[d], plan, p, K, b, gx, cx);
-    }
+    for (int st = 0; st < G::kSteps; ++st) expand_step<G, KT>(p, words0, lds + G::kLdsA, K, lane, q, st);
+    chunk_of(2, gx, cx);
+    stage_load<G, NL>(wd, plan, p, K, b, gx, cx);
   }
   __syncthreads();
 
-  // per-lane byte offsets of the fragments
-  const int a_frag_off = h * kAHalf + (row * kXP + n) * 16;          // + (ky*kXP + kx + 32 np)*16
   const int w_frag_off = lane * 16;                                  // + tap*kWTap + mc*1024
-  // per-lane output word offset for the packed store: lane L = (r << 2) | (hi << 1) | np
-  const int st_r = lane >> 2, st_hi = (lane >> 1) & 1, st_np = lane & 1;
-  const int st_co = 8 * (st_r >> 2) + 4 * st_hi + (st_r & 3);         // + 32 mc
-  const size_t out_plane = (size_t)Ho * 2;                            // words per (step, b, cout)
-  const size_t out_lane = ((size_t)b * p.Cout + co_wave + st_co) * out_plane + (size_t)y * 2 + st_np;
-  const size_t out_step = (size_t)p.B * p.Cout * out_plane;
 
   // MFMA operand fragments, two slots: tap t multiplies slot t & 1 while slot (t+1) & 1 is
   // being fetched; tap 8 fetches the next chunk's tap-0 fragments into slot 1, which the next
@@ -424,26 +511,28 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
   bf16x8 wf[2][kMC], af[2][2];
   auto fetch = [&](const uint8_t* a_buf, const uint8_t* w_buf, int tap, int slot) {
     const int ky = tap / 3, kx = tap % 3;
+    const int tap_off = (ky * G::kXP + G::col(kx)) * 16;            // col(ox S + kx) = col(ox S) + col(kx)
 #pragma unroll
     for (int mc = 0; mc < kMC; ++mc)
       wf[slot][mc] = *reinterpret_cast<const bf16x8*>(w_buf + tap * kWTap + mc * 1024 + w_frag_off);
 #pragma unroll
     for (int np = 0; np < 2; ++np)
-      af[slot][np] = *reinterpret_cast<const bf16x8*>(a_buf + a_frag_off + (ky * kXP + kx + 32 * np) * 16);
+      af[slot][np] = *reinterpret_cast<const bf16x8*>(a_buf + a_frag_off[np] + tap_off);
   };
-  fetch(lds + kLdsA, lds + kLdsW, 0, 1);
+  fetch(lds + G::kLdsA, lds + G::kLdsW, 0, 1);
 
   // One chunk of 16 input channels: 9 taps of MFMAs on buffers PAR, while the A tile of the
   // next chunk is built in buffers PAR^1.  The workgroup barrier sits between tap 7 and tap 8:
   // by then every read of the PAR buffers has returned (tap 8's fragments are fetched during
   // tap 7) and every write to the PAR^1 buffers is done, so tap 8 already fetches the first
-  // fragments of the next chunk and refills the PAR weight buffer for the chunk after it.
+  // fragments of the next chunk and starts refilling the PAR weight buffer.
+  static_assert(8 * G::kSlotsPerTap >= G::kSteps + 1, "the loader must be done before the barrier");
   auto chunk_iteration = [&](int s) {
     const int PAR = s & 1;
-    const uint8_t* a_cur = lds + kLdsA + PAR * kABuf;
-    const uint8_t* w_cur = lds + kLdsW + PAR * kWBuf;
-    uint8_t* a_next = lds + kLdsA + (PAR ^ 1) * kABuf;
-    uint8_t* w_next = lds + kLdsW + (PAR ^ 1) * kWBuf;
+    const uint8_t* a_cur = lds + G::kLdsA + PAR * G::kABuf;
+    const uint8_t* w_cur = lds + G::kLdsW + PAR * kWBuf;
+    uint8_t* a_next = lds + G::kLdsA + (PAR ^ 1) * G::kABuf;
+    uint8_t* w_next = lds + G::kLdsW + (PAR ^ 1) * kWBuf;
     const uint8_t* words_next = words0 + (PAR ^ 1) * words_bytes;    // words of chunk s+1 (read now)
     uint8_t* words_nn = words0 + PAR * words_bytes;                  // words of chunk s+2 (written at tap 7)
     RowWords<KT> rw;
@@ -457,16 +546,16 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
       // Global loads are dealt out over the taps, a few per tap, so that the wave never
       // stalls on a full memory-instruction queue.  The weight buffer of this chunk is free
       // after the barrier: tap 8 starts refilling it for chunk s+2 (blocks 0,1) and taps 0..5
-      // of the next chunk finish that (blocks 2..8).  Staged words likewise: slot 0 at tap 8
-      // (for chunk s+3), slots 1..5 at taps 0..4 (for chunk s+2, written to LDS at tap 7).
-      constexpr int kLPT = (NL + 5) / 6;        // staged words requested per slot
+      // of the next chunk finish that (blocks 2..8).  Staged words likewise: part 0 at tap 8
+      // (for chunk s+3), parts 1..5 at taps 0..4 (for chunk s+2, written to LDS at tap 7).
+      constexpr int kLPT = (NL + 5) / 6;        // staged words requested per part
       if (tap == 8) {
         int gx, cx;
         chunk_of(s + 2, gx, cx);
         weights_to_lds(cx, const_cast<uint8_t*>(w_cur), 0, 2);
         __builtin_amdgcn_sched_barrier(0);
         chunk_of(s + 3, gx, cx);
-        stage_load<NL>(wd[0], plan, p, K, b, gx, cx, 0, kLPT);
+        stage_load<G, NL>(wd, plan, p, K, b, gx, cx, 0, kLPT);
         fetch(a_next, w_next, 0, slot ^ 1);
       } else {
         if (tap <= 5) {
@@ -475,7 +564,7 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
           weights_to_lds(cx, w_next, tap == 0 ? 2 : 3 + tap, tap == 0 ? 4 : 4 + tap);
           if (tap <= 4) {
             chunk_of(s + 2, gx, cx);
-            stage_load<NL>(wd[0], plan, p, K, b, gx, cx, (tap + 1) * kLPT, (tap + 2) * kLPT);
+            stage_load<G, NL>(wd, plan, p, K, b, gx, cx, (tap + 1) * kLPT, (tap + 2) * kLPT);
           }
         }
         fetch(a_cur, w_cur, tap + 1, slot ^ 1);
@@ -485,28 +574,26 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
 #pragma unroll
         for (int np = 0; np < 2; ++np)
           acc[mc][np] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][mc], af[slot][np], acc[mc][np], 0, 0, 0);
-      if constexpr (KT > 0) {
-        // input row r: words requested during tap r, expanded during tap r + 1
-        if (tap >= 1 && tap <= kInRows) expand_words<KT>(rw, p, a_next, lane, q, tap - 1);
-        if (tap < kInRows) read_words<KT>(rw, words_next, lane, q, tap);
-      } else {
-        if (tap < kInRows) expand_row<KT>(p, words_next, a_next, K, lane, q, tap);
-      }
-      if (tap == 7) {
-        stage_store<NL>(wd[0], plan, words_nn);
+      // loader: pipeline slot i expands step i-1, then requests the words of step i
 #pragma unroll
-        for (int d = 0; d + 1 < D; ++d)
-#pragma unroll
-          for (int l = 0; l < NL; ++l) wd[d][l] = wd[d + 1][l];
+      for (int i = tap * G::kSlotsPerTap; i < (tap + 1) * G::kSlotsPerTap; ++i) {
+        if constexpr (KT > 0) {
+          if (i >= 1 && i <= G::kSteps) expand_words<G, KT>(rw, p, a_next, lane, q, i - 1);
+          if (i < G::kSteps) read_words<G, KT>(rw, words_next, lane, q, i);
+        } else {
+          if (i < G::kSteps) expand_step<G, KT>(p, words_next, a_next, K, lane, q, i);
+        }
       }
+      if (tap == 7) stage_store<NL>(wd, plan, words_nn);
       if constexpr (KT > 0) {
         // issue order inside the tap: one MFMA, then a few LDS reads and vector ops that run
         // while the matrix pipe is busy, eight times over
-        constexpr int kValuPerMfma = KT <= 2 ? 3 : (KT == 4 ? 5 : (KT == 8 ? 10 : 18));
+        constexpr int kValuPerMfma = (KT <= 2 ? 3 : (KT == 4 ? 5 : (KT == 8 ? 10 : 18))) * G::kSlotsPerTap;
+        constexpr int kDsPerMfma = G::kSlotsPerTap == 1 ? 2 : 3;
 #pragma unroll
         for (int i = 0; i < 2 * kMC; ++i) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, kDsPerMfma, 0);
           __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);
         }
       }
@@ -518,8 +605,33 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
     }
   };
 
+  // Packed stores (lane order: see lif_step).  The lane's word of 32-channel block mc sits at
+  // out_wave + mc * 32 * out_plane + out_off, with out_wave wave-uniform and out_off a small
+  // per-lane offset, the only part kept in a vector register across the time loop.
+  constexpr int kStoreRegs = G::kWo >= 32 ? 1 : 2;
+  const uint32_t out_plane = (uint32_t)(Ho * G::kOutWords);           // words per (step, b, cout)
+  const size_t out_step = (size_t)p.B * p.Cout * out_plane;
+  uint32_t* const out_wave = p.out + ((size_t)b * p.Cout + co_wave) * out_plane + (size_t)oy_wave * G::kOutWords;
+  uint32_t out_off;                                                   // in words; store register 1: + 16 out_plane
+  int out_row;                                                        // the lane's row within the wave
+  if constexpr (G::kWo >= 32) {
+    const int r = lane >> 2, hi = (lane >> 1) & 1;
+    out_row = G::kWo == 64 ? 0 : (lane & 1);
+    out_off = (uint32_t)(8 * (r >> 2) + 4 * hi + (r & 3)) * out_plane + (G::kWo == 64 ? (lane & 1) : out_row);
+  } else {
+    const int r = lane >> 3, hi = (lane >> 2) & 1;
+    out_row = lane & 3;
+    out_off = (uint32_t)(8 * (r >> 2) + 4 * hi + (r & 3)) * out_plane + out_row;
+  }
+  const bool out_ok = oy_wave + out_row < Ho;
+
   int s = 0;
   for (int g = 0; g < p.G; ++g) {
+    // Nothing may be in flight when the chunk loop is entered: a load still pending here (a
+    // register reloaded after the epilogue, say) would otherwise be waited for inside the loop,
+    // at its first use, in every iteration, and that wait would also cover the loads the loop
+    // itself keeps in flight.
+    __builtin_amdgcn_s_waitcnt(0x0f70);         // vmcnt(0), other counters untouched
 #pragma unroll
     for (int mc = 0; mc < kMC; ++mc)
 #pragma unroll
@@ -527,12 +639,10 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mc][np][r] = 0.f;
 
-    for (int c = 0; c < NC; ++c, ++s) {
-      chunk_iteration(s);
-    }
+    for (int c = 0; c < NC; ++c, ++s) chunk_iteration(s);
 
     // ---- LIF epilogue on Y_k = acc + bias
-    const float* bias_lds = reinterpret_cast<const float*>(lds + kLdsBias);
+    const float* bias_lds = reinterpret_cast<const float*>(lds + G::kLdsBias);
     if (p.bias) {
 #pragma unroll
       for (int mc = 0; mc < kMC; ++mc)
@@ -543,35 +653,46 @@ __global__ __launch_bounds__(kThreads) void mfma_w64_kernel(const MfmaParams p) 
           acc[mc][1][r] += bv;
         }
     }
+    // epilogue geometry, recomputed per group: nothing of it lives across the MFMA loop
+    const LaneGeom lg = lane_geom<G>(lane, oy_wave, Ho, plane, p.theta);
     for (int j = 0; j < p.n_lif; ++j) {
       const size_t step = (size_t)g * p.n_lif + j;
-      uint32_t word[kMC];
+      uint32_t word[kMC][2];
 #pragma unroll
-      for (int mc = 0; mc < kMC; ++mc) word[mc] = 0u;
-      if (p.v_trace && row_ok) {
+      for (int mc = 0; mc < kMC; ++mc) word[mc][0] = word[mc][1] = 0u;
+      if constexpr (TRACE) {
         float* tl = p.v_trace + step * ((size_t)p.B * p.Cout * plane) + v_wave;
         size_t plane_l = plane;
         asm volatile("" : "+s"(plane_l));       // keep the trace addresses out of the loop preheader
-        lif_step<true>(V, acc, p.decay, p.theta, word, tl, plane_l, v_lane);
+        lif_step<G::kWo, true>(V, acc, p.decay, p.theta, lg, word, tl, plane_l);
       } else {
-        lif_step<false>(V, acc, p.decay, p.theta, word, nullptr, plane, v_lane);
+        lif_step<G::kWo, false>(V, acc, p.decay, p.theta, lg, word, nullptr, plane);
       }
-      if (row_ok) {
+      if (out_ok) {
+        uint32_t* const o = out_wave + step * out_step;
 #pragma unroll
-        for (int mc = 0; mc < kMC; ++mc) p.out[step * out_step + out_lane + mc * 32 * out_plane] = word[mc];
+        for (int sr = 0; sr < kStoreRegs; ++sr)
+#pragma unroll
+          for (int mc = 0; mc < kMC; ++mc) o[(uint32_t)(mc * 32 + sr * 16) * out_plane + out_off] = word[mc][sr];
       }
     }
   }
   __syncthreads();                            // drains the last direct-to-LDS loads before the waves end
 
-  if (p.v_inout && row_ok) {
+  if (p.v_inout) {
     size_t plane_l = plane;                   // opaque copy: the 128 addresses below are formed here,
     asm volatile("" : "+s"(plane_l));         // not before the time loop (they would not fit in registers)
+    const LaneGeom lg = lane_geom<G>(lane, oy_wave, Ho, plane_l, p.theta);
     char* vb = reinterpret_cast<char*>(p.v_inout + v_wave);
-    static_for<0, kMC>([&](auto mc_) { static_for<0, 2>([&](auto np_) { static_for<0, 16>([&](auto r_) {
-      constexpr int mc = decltype(mc_)::value, np = decltype(np_)::value, r = decltype(r_)::value;
-      *reinterpret_cast<float*>(vb + ((size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane_l + np * 32) * 4 + v_lane) = V[mc][np][r];
-    }); }); });
+    static_for<0, 2>([&](auto np_) {
+      constexpr int np = decltype(np_)::value;
+      if (lg.ok[np]) {
+        static_for<0, kMC>([&](auto mc_) { static_for<0, 16>([&](auto r_) {
+          constexpr int mc = decltype(mc_)::value, r = decltype(r_)::value;
+          *reinterpret_cast<float*>(vb + (size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane_l * 4 + lg.v_off[np]) = V[mc][np][r];
+        }); });
+      }
+    });
   }
 }
 
@@ -598,25 +719,70 @@ __global__ void mfma_prepare_kernel(const float* __restrict__ w, uint32_t* __res
   out[i] = pack_bf16(a, bb);
 }
 
-template <int KT>
-hipError_t launch_kt(const MfmaParams& mp, dim3 grid, hipStream_t s) {
-  const int lds = lds_bytes(KT > 0 ? KT : TAC_MAX_K);
+template <int KT, int WIN, int S, bool TRACE>
+hipError_t launch_traced(const MfmaParams& mp, hipStream_t s) {
+  using G = Geo<WIN, S>;
+  constexpr int lds = G::lds_bytes(KT > 0 ? KT : TAC_MAX_K);
+  static_assert(lds <= kLdsLimit, "tile does not fit the LDS");
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_w64_kernel<KT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<KT, WIN, S, TRACE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(mfma_w64_kernel<KT>, grid, dim3(kThreads), lds, s, mp);
+  MfmaParams q = mp;
+  q.row_tiles = (mp.Ho + G::kTileRows - 1) / G::kTileRows;
+  const dim3 grid(q.row_tiles * (mp.Cout / kCoutTile) * mp.B);
+  hipLaunchKernelGGL((mfma_kernel<KT, WIN, S, TRACE>), grid, dim3(kThreads), lds, s, q);
   return hipGetLastError();
 }
+
+template <int KT, int WIN, int S>
+hipError_t launch_one(const MfmaParams& mp, hipStream_t s) {
+  return mp.v_trace ? launch_traced<KT, WIN, S, true>(mp, s) : launch_traced<KT, WIN, S, false>(mp, s);
+}
+
+// Largest K a geometry has LDS room for (the stride-2 tiles hold 17 or 33 input rows).
+template <int WIN, int S>
+constexpr int max_k() {
+  int k = 0;
+  while (k < TAC_MAX_K && Geo<WIN, S>::lds_bytes(k + 1) <= kLdsLimit) ++k;
+  return k;
+}
+
+template <int WIN, int S>
+hipError_t launch_geo(const MfmaParams& mp, hipStream_t s) {
+  constexpr int kMaxK = max_k<WIN, S>();
+  if (mp.K > kMaxK) return hipErrorInvalidValue;
+  switch (mp.K) {
+    case 1: return launch_one<1, WIN, S>(mp, s);
+    case 2: return launch_one<2, WIN, S>(mp, s);
+    case 4: return launch_one<4, WIN, S>(mp, s);
+    default: break;
+  }
+  if constexpr (kMaxK == TAC_MAX_K) {
+    switch (mp.K) {
+      case 8: return launch_one<8, WIN, S>(mp, s);
+      case 16: return launch_one<16, WIN, S>(mp, s);
+      default: return launch_one<0, WIN, S>(mp, s);
+    }
+  }
+  return hipErrorInvalidValue;
+}
+
+static_assert(max_k<64, 1>() == TAC_MAX_K && max_k<32, 1>() == TAC_MAX_K, "stride 1 takes every K");
+static_assert(max_k<64, 2>() >= 4 && max_k<32, 2>() >= 4, "stride 2 takes K up to 4");
 
 }  // namespace
 
 bool mfma_supported(const tac_layer_desc_t& d) {
-  return d.precision == TAC_BF16 && d.in_format == TAC_IN_BITS && d.stride == 1 && d.W == kW &&
-         d.Cin % kChunk == 0 && d.Cout % kCoutTile == 0;
+  if (d.precision != TAC_BF16 || d.in_format != TAC_IN_BITS) return false;
+  if (d.Cin % kChunk != 0 || d.Cout % kCoutTile != 0) return false;
+  if (d.W != 64 && d.W != 32) return false;
+  if (d.stride == 1) return true;
+  const int K = d.mode == TAC_PER_STEP ? 1 : d.K;
+  return d.stride == 2 && (K == 1 || K == 2 || K == 4);     // LDS room of the stride-2 tiles
 }
 
 size_t mfma_weight_bytes(const tac_layer_desc_t& d) { return (size_t)d.Cout * d.Cin * 9 * 2; }
@@ -632,23 +798,19 @@ hipError_t mfma_launch(const LayerParams& p, hipStream_t s) {
   MfmaParams mp;
   mp.spikes = p.spikes; mp.w = static_cast<const uint8_t*>(p.w); mp.bias = p.bias; mp.v_inout = p.v_inout;
   mp.out = p.out; mp.v_trace = p.v_trace;
-  mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.Cout = p.Cout; mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif;
-  mp.row_tiles = (p.H + kRows - 1) / kRows;
+  mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.Ho = p.Ho; mp.Cout = p.Cout; mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif;
+  mp.row_tiles = 0;
   mp.decay = p.decay; mp.theta = p.theta;
   for (int j = 0; j < TAC_MAX_K; ++j) {
     // beta^(K-1-j) in 24-bit fixed point, from the fp32 table the host already rounded
     const double q = (double)p.wj[j] * (double)(1u << kFixShift);
     mp.wq[j] = j < p.K ? (uint32_t)(q + 0.5) : 0u;
   }
-  const dim3 grid(mp.row_tiles * (p.Cout / kCoutTile) * p.B);
-  switch (p.K) {
-    case 1: return launch_kt<1>(mp, grid, s);
-    case 2: return launch_kt<2>(mp, grid, s);
-    case 4: return launch_kt<4>(mp, grid, s);
-    case 8: return launch_kt<8>(mp, grid, s);
-    case 16: return launch_kt<16>(mp, grid, s);
-    default: return launch_kt<0>(mp, grid, s);
-  }
+  if (p.W == 64 && p.stride == 1) return launch_geo<64, 1>(mp, s);
+  if (p.W == 32 && p.stride == 1) return launch_geo<32, 1>(mp, s);
+  if (p.W == 64 && p.stride == 2) return launch_geo<64, 2>(mp, s);
+  if (p.W == 32 && p.stride == 2) return launch_geo<32, 2>(mp, s);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace tac

@@ -70,3 +70,44 @@ def test_state_carry_and_K1_equivalence():
     b = run_gpu(s[4:], w, K=2, mode=api.TAC_PRESERVE, v0=a["v_final"], **kw)
     assert np.array_equal(np.concatenate([a["packed"], b["packed"]]), whole["packed"])
     assert np.array_equal(b["v_final"], whole["v_final"])
+
+
+# (input width, stride, input rows): the rows give at least one full tile and a ragged one
+# (tiles are 8 output rows for output width 32, 16 rows for output width 16), odd and even
+GEOMETRIES = [(32, 1, 11), (64, 2, 21), (64, 2, 18), (32, 2, 35), (32, 2, 38)]
+GEO_MODES = [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 2), (api.TAC_PRESERVE, 4), (api.TAC_COLLAPSE, 4)]
+
+
+@pytest.mark.parametrize("W,stride,H", GEOMETRIES)
+@pytest.mark.parametrize("mode,K", GEO_MODES)
+def test_other_geometries(W, stride, H, mode, K):
+    # width 32 and stride 2: a wave's 64 pixels fold into 2 or 4 output rows
+    r = _rng(1000 + 10 * W + stride + H + K)
+    s = (r.random((8, 2, 32, H, W)) < 0.15).astype(np.uint8)
+    w = synth.kaiming_normal(21, 128, 32)
+    bias = (r.standard_normal(128) * 0.1).astype(np.float32)
+    Ho, Wo = (H - 1) // stride + 1, W // stride
+    v0 = (r.standard_normal((2, 128, Ho, Wo)) * 0.3).astype(np.float32)
+    par, g, ref = check_layer(s, w, K=K, beta=0.9, theta=1.0, mode=mode, stride=stride, precision=api.TAC_BF16,
+                              bias=bias, v0=v0, expect_kernel=api.TAC_KERNEL_MFMA)
+    assert ref[0].sum() > 0
+    print("mfma W=%d stride=%d H=%d" % (W, stride, H), api.MODE_NAMES[mode], K, par)
+
+
+@pytest.mark.parametrize("K", [8, 16, 5])
+def test_width_32_larger_K(K):
+    r = _rng(1200 + K)
+    s = (r.random((80 if K == 5 else 32, 1, 16, 9, 32)) < 0.1).astype(np.uint8)
+    w = synth.kaiming_normal(22, 256, 16)
+    check_layer(s, w, K=K, beta=0.9, theta=1.0, mode=api.TAC_PRESERVE, precision=api.TAC_BF16,
+                expect_kernel=api.TAC_KERNEL_MFMA)
+
+
+def test_stride_2_large_K_takes_the_direct_kernel():
+    # the stride-2 tiles have LDS room for 4 frames; larger groups run on the direct kernel
+    d = api.make_desc(16, 1, 16, 16, 64, 128, K=8, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, stride=2,
+                      precision=api.TAC_BF16)
+    assert api.tac_select_kernel(d) == api.TAC_KERNEL_DIRECT
+    d = api.make_desc(16, 1, 16, 16, 64, 128, K=4, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, stride=2,
+                      precision=api.TAC_BF16)
+    assert api.tac_select_kernel(d) == api.TAC_KERNEL_MFMA
