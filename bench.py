@@ -10,7 +10,13 @@ convolution, LIF and packed output.  Prints ONE JSON line:
   roofline executed convolution FLOPs (2 B Ho Wo Cout Cin 9 T/K, the T/K stages the method
            needs) / average kernel duration (HIP events on the launch stream) against the
            dense bf16 MFMA peak
+           traffic = HBM bytes of one launch from rocprofv3 counters (null when the kernel
+           source has changed since they were taken)
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
+  config.aggregation_stage_GBps  packed input bytes / kernel duration: the rate at which the
+           fused loader consumes spikes from HBM (it is not a separate pass)
+  config.launch_per_group_ms  the headline mode as T/K launches of one group each, the membrane
+           carried through v_inout, against ms_per_step for the single fused launch
   config.table  latency and speed-up over the per-step mode of the same kernel for every
            mode and K of the workload
 """
@@ -29,6 +35,28 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3       # MI355X fp32 vector
+
+# HBM traffic of one launch of the headline kernel (cfg5, TAC, K = 4), from two rocprofv3 --pmc
+# runs (FETCH_SIZE, then WRITE_SIZE; summary and scale factors under profiles/).  The figures
+# belong to one version of the kernel source: they are reported only while its hash matches.
+TRAFFIC = {
+    "kernel_source_sha256": "",
+    "workload": ("cfg5", "TAC", 4),
+    "fetch_bytes": 0,
+    "write_bytes": 0,
+}
+
+
+def measured_traffic(workload, mode, K):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2603_13810_amd", "csrc", "tac_mfma.hip")
+    try:
+        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    if sha != TRAFFIC["kernel_source_sha256"] or TRAFFIC["workload"] != (workload, mode, K):
+        return None
+    return TRAFFIC["fetch_bytes"] + TRAFFIC["write_bytes"]
 
 
 def parse():
@@ -117,7 +145,35 @@ def main():
                     frames_per_s=B * T / (wall_ms * 1e-3), tflops=flops / (kern_ms * 1e-3) / 1e12,
                     out_bytes=out.numel() * 4)
 
+    def time_per_group(mode, K, steps, warmup):
+        """The same layer as one launch per group of K frames, the membrane carried through v_inout."""
+        G = T // K
+        d = api.make_desc(K, B, L.Cin, wl.H, wl.W, L.Cout, K=K, beta=wl.beta, theta=wl.theta, mode=mode,
+                          stride=L.stride, precision=api.TAC_BF16)
+        wp = api.tac_prepare_weights(d, w_dev)
+        T_out, Ho, Wo = api.tac_out_shape(d)
+        out = torch.empty((G * T_out, B, L.Cout, Ho, (Wo + 31) // 32), dtype=torch.int32, device=dev)
+        v = torch.zeros((B, L.Cout, Ho, Wo), dtype=torch.float32, device=dev)
+
+        def once():
+            v.zero_()
+            for g in range(G):
+                api.tac_conv_lif(d, spikes[g * K:(g + 1) * K], wp, None, v, out[g * T_out:(g + 1) * T_out])
+        for _ in range(warmup):
+            once()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            once()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / steps
+
     head = time_mode(MODE[args.mode], args.K, args.steps, args.warmup)
+    per_group_ms = None
+    if not args.no_table and args.mode != "per_step":
+        per_group_ms = time_per_group(MODE[args.mode], args.K, max(3, args.steps // 4), 2)
     table = []
     if not args.no_table:
         base = time_mode(api.TAC_PER_STEP, 1, max(3, args.steps // 4), 2)
@@ -134,7 +190,8 @@ def main():
     is_mfma = head["kernel"] == "mfma"
     peak = PEAK_BF16_TFLOPS if is_mfma else PEAK_FP32_TFLOPS
     roofline = dict(bound="mfma" if is_mfma else "alu", achieved=round(head["tflops"], 2), peak=peak,
-                    unit="TFLOP/s", frac=round(head["tflops"] / peak, 4), traffic=None,
+                    unit="TFLOP/s", frac=round(head["tflops"] / peak, 4),
+                    traffic=measured_traffic(wl.name, args.mode, head["K"]) if B == wl.B else None,
                     kernel_ms=round(head["kernel_ms"], 4),
                     algorithmic_bytes=int(spikes.numel() * 4 + head["out_bytes"]))
 
@@ -165,6 +222,8 @@ def main():
         "config": {"workload": "%s: conv-LIF 3x3 %d->%d, %dx%d, stride %d, B=%d, T=%d, Bernoulli rate %s, beta=%.2f"
                                % (wl.name, L.Cin, L.Cout, wl.H, wl.W, L.stride, B, T, rate, wl.beta),
                    "mode": args.mode, "K": head["K"], "kernel": head["kernel"],
+                   "aggregation_stage_GBps": round(spikes.numel() * 4 / (head["kernel_ms"] * 1e-3) / 1e9, 1),
+                   "launch_per_group_ms": None if per_group_ms is None else round(per_group_ms, 4),
                    "paper_context": "TAC training speed-ups 13.8x (Apple M3 Max) and 11.0x (NVIDIA V100), other hardware",
                    "table": table},
         "roofline": roofline,

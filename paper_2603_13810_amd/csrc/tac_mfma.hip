@@ -216,10 +216,11 @@ __device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&
 // ---- staging of packed input words ------------------------------------------------------
 // Flat staging index i in [0, F K) with F = 16 * rows * words-per-row:
 // i = j * F + (cin * rows + row) * wpr + word, so that consecutive threads read consecutive
-// dwords of one (frame, channel) plane.  In LDS the K frames of one (cin, row, word) are
-// adjacent: index ((cin * rows + row) * wpr + word) * K + j.  A thread's share of a chunk is
-// the same in every chunk, so its global dword offsets (relative to the chunk's first frame and
-// channel) and LDS indices are computed once.
+// dwords of one (frame, channel) plane.  In LDS the order is [row word][cin][frame], index
+// ((row * wpr + word) * 16 + cin) * K + j: the K frames of the four channels a loader lane
+// aggregates are 4 K adjacent dwords.  A thread's share of a chunk is the same in every chunk,
+// so its global dword offsets (relative to the chunk's first frame and channel) and LDS indices
+// are computed once.
 template <int NL>
 struct StagePlan {
   uint32_t goff[NL];     // dword offset from the chunk base (always a valid address)
@@ -244,19 +245,18 @@ __device__ __forceinline__ void stage_plan(StagePlan<NL>& sp, const MfmaParams& 
       const int row = rw / G::kWW, word = rw - row * G::kWW;
       const int iy = iy0 + row;
       const int iyc = min(max(iy, 0), p.H - 1);
-      sp.lidx[l] = (uint32_t)(rem * K + j);
+      sp.lidx[l] = (uint32_t)((rw * kChunk + cin) * K + j);
       sp.goff[l] = (uint32_t)((((size_t)j * p.B * p.Cin + cin) * p.H + iyc) * G::kWW + word);
       if (iy == iyc) sp.keep |= 1u << l;
     }
   }
 }
 
-// Unconditional loads (no lane masking, no register initialisation in front of them).
-template <class G, int NL>
-__device__ __forceinline__ void stage_load(uint32_t (&wd)[NL], const StagePlan<NL>& sp, const MfmaParams& p, int K,
-                                           int b, int g, int c, int l0 = 0, int l1 = NL) {
-  // wave-uniform base of (first frame of group g, sample b, first channel of chunk c)
-  const uint32_t* base = p.spikes + (((size_t)(g * K) * p.B + b) * p.Cin + c * kChunk) * p.H * G::kWW;
+// Unconditional loads (no lane masking, no register initialisation in front of them).  `base`
+// is the wave-uniform address of (first frame of the group, sample, first channel of the chunk).
+template <int NL>
+__device__ __forceinline__ void stage_load(uint32_t (&wd)[NL], const StagePlan<NL>& sp, const uint32_t* base,
+                                           int l0 = 0, int l1 = NL) {
 #pragma unroll
   for (int l = 0; l < NL; ++l)
     if (l >= l0 && l < l1) wd[l] = base[sp.goff[l]];
@@ -297,9 +297,38 @@ __device__ __forceinline__ int a_write_off(int lane, int step) {
     return ((step * 2 + (lane >> 5)) * G::kXP + G::col((lane & 31) + 1)) * 16;
 }
 
+template <class G, int KT>
+__device__ __forceinline__ void read_words(RowWords<KT>& rw, const uint8_t* words_buf, int lane, int q, int step) {
+  static_assert(KT > 0, "compile-time K only");
+  // the lane's 4 channels x KT frames: 4 KT consecutive dwords
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(words_buf) + (lane_word<G>(lane, step) * kChunk + q * 4) * KT;
+  if constexpr (KT >= 4) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int j4 = 0; j4 < KT / 4; ++j4) {
+        const u32x4 w4 = *reinterpret_cast<const u32x4*>(src + e * KT + 4 * j4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) rw.w[e][4 * j4 + j] = w4[j];
+      }
+  } else if constexpr (KT == 2) {
+#pragma unroll
+    for (int e2 = 0; e2 < 2; ++e2) {
+      const u32x4 w4 = *reinterpret_cast<const u32x4*>(src + 4 * e2);
+      rw.w[2 * e2][0] = w4[0];
+      rw.w[2 * e2][1] = w4[1];
+      rw.w[2 * e2 + 1][0] = w4[2];
+      rw.w[2 * e2 + 1][1] = w4[3];
+    }
+  } else {
+    const u32x4 w4 = *reinterpret_cast<const u32x4*>(src);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) rw.w[e][0] = w4[e];
+  }
+}
+
 template <class G>
-__device__ __forceinline__ void a_write(uint8_t* a_next, int lane, int q, int step, const float (&val)[4]) {
-  const u32x2 pk = {pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])};
+__device__ __forceinline__ void a_write_packed(uint8_t* a_next, int lane, int q, int step, u32x2 pk) {
   u32x2* dst = reinterpret_cast<u32x2*>(a_next + (q >> 1) * G::kAHalf + a_write_off<G>(lane, step) + (q & 1) * 8);
   if (G::kOddTail && step == G::kSteps - 1) {
     if (lane < 32) *dst = pk;
@@ -308,47 +337,38 @@ __device__ __forceinline__ void a_write(uint8_t* a_next, int lane, int q, int st
   }
 }
 
-template <class G, int KT>
-__device__ __forceinline__ void read_words(RowWords<KT>& rw, const uint8_t* words_buf, int lane, int q, int step) {
-  static_assert(KT > 0, "compile-time K only");
-  const uint32_t* wb = reinterpret_cast<const uint32_t*>(words_buf);
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const uint32_t* src = wb + (((q * 4 + e) * G::kRowWords + lane_word<G>(lane, step)) * KT);
-    if constexpr (KT >= 4) {
-#pragma unroll
-      for (int j4 = 0; j4 < KT / 4; ++j4) {
-        const u32x4 w4 = *reinterpret_cast<const u32x4*>(src + 4 * j4);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) rw.w[e][4 * j4 + j] = w4[j];
-      }
-    } else if constexpr (KT == 2) {
-      const u32x2 w2 = *reinterpret_cast<const u32x2*>(src);
-      rw.w[e][0] = w2[0];
-      rw.w[e][1] = w2[1];
-    } else {
-      rw.w[e][0] = src[0];
-    }
-  }
+template <class G>
+__device__ __forceinline__ void a_write(uint8_t* a_next, int lane, int q, int step, const float (&val)[4]) {
+  a_write_packed<G>(a_next, lane, q, step, u32x2{pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])});
 }
 
 template <class G, int KT>
 __device__ __forceinline__ void expand_words(const RowWords<KT>& rw, const MfmaParams& p, uint8_t* a_next, int lane,
                                              int q, int step) {
   const uint32_t bitpos = lane & 31;
-  float val[4];
+  if constexpr (KT == 1) {
+    // one frame: the aggregate is the bit itself, 2^23 in the fixed-point scale, whose bf16
+    // pattern is 0x4b00; two channels per multiplication
+    static_assert(kFixShift == 23, "0x4b00 is bf16(2^23)");
+    u32x2 pk;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    uint32_t acc = 0;
-    if constexpr (KT == 1) {
-      acc = __builtin_amdgcn_ubfe(rw.w[e][0], bitpos, 1) << kFixShift;
-    } else {
+    for (int e2 = 0; e2 < 2; ++e2) {
+      const uint32_t b0 = __builtin_amdgcn_ubfe(rw.w[2 * e2][0], bitpos, 1);
+      const uint32_t b1 = __builtin_amdgcn_ubfe(rw.w[2 * e2 + 1][0], bitpos, 1);
+      pk[e2] = __umul24((b1 << 16) | b0, 0x4b00u);
+    }
+    a_write_packed<G>(a_next, lane, q, step, pk);
+  } else {
+    float val[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      uint32_t acc = 0;
 #pragma unroll
       for (int j = 0; j < KT; ++j) acc = __umul24(__builtin_amdgcn_ubfe(rw.w[e][j], bitpos, 1), p.wq[j]) + acc;
+      val[e] = (float)acc;
     }
-    val[e] = (float)acc;
+    a_write<G>(a_next, lane, q, step, val);
   }
-  a_write<G>(a_next, lane, q, step, val);
 }
 
 // Unpipelined form (prologue, and the run-time-K kernel).
@@ -365,7 +385,7 @@ __device__ __forceinline__ void expand_step(const MfmaParams& p, const uint8_t* 
     float val[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const uint32_t* src = wb + (((q * 4 + e) * G::kRowWords + lane_word<G>(lane, step)) * K);
+      const uint32_t* src = wb + ((lane_word<G>(lane, step) * kChunk + q * 4 + e) * K);
       uint32_t acc = 0;
       for (int j = 0; j < K; ++j) acc = __umul24(__builtin_amdgcn_ubfe(src[j], bitpos, 1), p.wq[j]) + acc;
       val[e] = (float)acc;
@@ -462,24 +482,50 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     });
   }
 
-  const uint8_t* wsrc = p.w + (size_t)co_tile * NC * kWBuf;
-  auto chunk_of = [&](int sx, int& gx, int& cx) {
-    sx = min(sx, total - 1);                    // past the end: harmless repeat of the last chunk
-    gx = sx / NC;
-    cx = sx - gx * NC;
+  // Position in the sequence of chunks (group-major), with the addresses that go with it: the
+  // packed words of (first frame of the group, this sample, first channel of the chunk) and the
+  // chunk's prepared weights.  Advanced by additions only; past the last chunk it stays there
+  // (the loads that run ahead of the MFMAs then repeat the last chunk, harmlessly).
+  struct Cursor {
+    const uint32_t* spk;
+    const uint8_t* w;
+    int c, left;             // chunk within the group; chunks after this one
   };
-  // weights of chunk cx: global -> LDS without passing through registers; each wave moves
-  // 9 of the 36 one-KiB blocks, lane l its 16 bytes of the block
-  const uint32_t w_lane_off = (uint32_t)lane * 16u;
-  auto weights_to_lds = [&](int cx, uint8_t* w_dst, int i0, int i1) {
-    const uint8_t* src = wsrc + (size_t)cx * kWBuf;
-#pragma unroll
-    for (int i = i0; i < i1; ++i) {
-      const int blk = wave + kWaves * i;
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (uint32_t)(blk * 1024) + w_lane_off),
-                                       (lds_void_ptr)(w_dst + blk * 1024), 16, 0, 0);
+  const size_t spk_chunk = (size_t)kChunk * p.H * G::kWW;                      // dwords
+  const size_t spk_wrap = (size_t)K * p.B * p.Cin * p.H * G::kWW - (size_t)NC * spk_chunk;
+  auto advance = [&](Cursor& cu) {
+    if (cu.left > 0) {
+      --cu.left;
+      ++cu.c;
+      cu.spk += spk_chunk;
+      cu.w += kWBuf;
+      if (cu.c == NC) {
+        cu.c = 0;
+        cu.spk += spk_wrap;
+        cu.w -= (size_t)NC * kWBuf;
+      }
     }
   };
+  // weights of a chunk: global -> LDS without passing through registers.  Each wave moves 9
+  // consecutive one-KiB blocks of the 36, lane l its 16 bytes of a block; four blocks share one
+  // address (global and LDS) and differ in the instruction's immediate offset.
+  const uint32_t w_lane_off = (uint32_t)(wave * (kWBlocks * 1024)) + (uint32_t)lane * 16u;
+  auto weights_to_lds = [&](const uint8_t* src, uint8_t* w_dst, auto i0_, auto i1_) {
+    static_for<decltype(i0_)::value, decltype(i1_)::value>([&](auto i_) {
+      constexpr int i = decltype(i_)::value;
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (i / 4) * 4096 + w_lane_off),
+                                       (lds_void_ptr)(w_dst + wave * (kWBlocks * 1024) + (i / 4) * 4096), 16,
+                                       (i % 4) * 1024, 0);
+    });
+  };
+  constexpr std::integral_constant<int, 0> c0;
+  constexpr std::integral_constant<int, 2> c2;
+  constexpr std::integral_constant<int, 4> c4;
+  constexpr std::integral_constant<int, 5> c5;
+  constexpr std::integral_constant<int, 6> c6;
+  constexpr std::integral_constant<int, 7> c7;
+  constexpr std::integral_constant<int, 8> c8;
+  constexpr std::integral_constant<int, 9> c9;
 
   StagePlan<NL> plan;
   stage_plan<G, NL>(plan, p, K, tid, y0 * S - 1);
@@ -487,19 +533,30 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
 
   // ---- prologue: A tile of chunk 0, weights of chunks 0 and 1, staged words of chunk 1,
   //      words of chunk 2 in registers
+  Cursor cur;                                   // chunk s + 3 while chunk s is multiplied
+  const uint8_t* w_n1;                          // weights of chunk s + 1
+  const uint8_t* w_n2;                          // weights and words of chunk s + 2
+  const uint32_t* spk_n2;
   {
-    weights_to_lds(0, lds + G::kLdsW, 0, kWBlocks);
-    int gx, cx;
-    chunk_of(1, gx, cx);
-    weights_to_lds(cx, lds + G::kLdsW + kWBuf, 0, kWBlocks);
-    stage_load<G, NL>(wd, plan, p, K, b, 0, 0);
+    cur.spk = p.spikes + ((size_t)b * p.Cin) * p.H * G::kWW;
+    cur.w = p.w + (size_t)co_tile * NC * kWBuf;
+    cur.c = 0;
+    cur.left = total - 1;
+    weights_to_lds(cur.w, lds + G::kLdsW, c0, c9);
+    stage_load<NL>(wd, plan, cur.spk);
     stage_store<NL>(wd, plan, words0);
-    stage_load<G, NL>(wd, plan, p, K, b, gx, cx);
+    advance(cur);                               // chunk 1
+    w_n1 = cur.w;
+    weights_to_lds(cur.w, lds + G::kLdsW + kWBuf, c0, c9);
+    stage_load<NL>(wd, plan, cur.spk);
     stage_store<NL>(wd, plan, words0 + words_bytes);
     __syncthreads();
     for (int st = 0; st < G::kSteps; ++st) expand_step<G, KT>(p, words0, lds + G::kLdsA, K, lane, q, st);
-    chunk_of(2, gx, cx);
-    stage_load<G, NL>(wd, plan, p, K, b, gx, cx);
+    advance(cur);                               // chunk 2
+    w_n2 = cur.w;
+    spk_n2 = cur.spk;
+    stage_load<NL>(wd, plan, cur.spk);
+    advance(cur);                               // chunk 3
   }
   __syncthreads();
 
@@ -550,22 +607,21 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
       // (for chunk s+3), parts 1..5 at taps 0..4 (for chunk s+2, written to LDS at tap 7).
       constexpr int kLPT = (NL + 5) / 6;        // staged words requested per part
       if (tap == 8) {
-        int gx, cx;
-        chunk_of(s + 2, gx, cx);
-        weights_to_lds(cx, const_cast<uint8_t*>(w_cur), 0, 2);
+        weights_to_lds(w_n2, const_cast<uint8_t*>(w_cur), c0, c2);
         __builtin_amdgcn_sched_barrier(0);
-        chunk_of(s + 3, gx, cx);
-        stage_load<G, NL>(wd, plan, p, K, b, gx, cx, 0, kLPT);
+        stage_load<NL>(wd, plan, cur.spk, 0, kLPT);
         fetch(a_next, w_next, 0, slot ^ 1);
       } else {
         if (tap <= 5) {
-          int gx, cx;
-          chunk_of(s + 1, gx, cx);
-          weights_to_lds(cx, w_next, tap == 0 ? 2 : 3 + tap, tap == 0 ? 4 : 4 + tap);
-          if (tap <= 4) {
-            chunk_of(s + 2, gx, cx);
-            stage_load<G, NL>(wd, plan, p, K, b, gx, cx, (tap + 1) * kLPT, (tap + 2) * kLPT);
+          switch (tap) {
+            case 0: weights_to_lds(w_n1, w_next, c2, c4); break;
+            case 1: weights_to_lds(w_n1, w_next, c4, c5); break;
+            case 2: weights_to_lds(w_n1, w_next, c5, c6); break;
+            case 3: weights_to_lds(w_n1, w_next, c6, c7); break;
+            case 4: weights_to_lds(w_n1, w_next, c7, c8); break;
+            default: weights_to_lds(w_n1, w_next, c8, c9); break;
           }
+          if (tap <= 4) stage_load<NL>(wd, plan, spk_n2, (tap + 1) * kLPT, (tap + 2) * kLPT);
         }
         fetch(a_cur, w_cur, tap + 1, slot ^ 1);
       }
@@ -603,6 +659,10 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+    w_n1 = w_n2;
+    w_n2 = cur.w;
+    spk_n2 = cur.spk;
+    advance(cur);
   };
 
   // Packed stores (lane order: see lif_step).  The lane's word of 32-channel block mc sits at
