@@ -111,16 +111,23 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // v_cvt_pk_bf16_f32, nearest even
 }
 
-// vdst[LANE_A] = a, vdst[LANE_B] = b for wave-uniform a, b; other lanes keep `old`.  The s_nop
-// covers the two wait states this chip needs between a vector instruction that wrote the SGPR
-// (the compare, or a spill reload) and a vector instruction that reads it: the assembler text
-// is opaque to the compiler's hazard pass.
-template <int LANE_A, int LANE_B>
-__device__ __forceinline__ uint32_t write_lanes(uint32_t old, uint32_t a, uint32_t b) {
+// vdst[lane L0 + i * STEP + (j ? HALF : 0)] = x[i][j] for the wave-uniform values x[4][2]; other
+// lanes keep `old`.  The s_nop covers the two wait states this chip needs between a vector
+// instruction that wrote an SGPR (the compare, or a spill reload) and a vector instruction that
+// reads it: the assembler text is opaque to the compiler's hazard pass.
+template <int L0, int STEP, int HALF>
+__device__ __forceinline__ uint32_t write_lanes(uint32_t old, const uint32_t (&x)[4][2]) {
   uint32_t r;
-  asm volatile("s_nop 1\n\tv_writelane_b32 %0, %1, %3\n\tv_writelane_b32 %0, %2, %4"
-               : "=v"(r)
-               : "s"(a), "s"(b), "n"(LANE_A), "n"(LANE_B), "0"(old));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_writelane_b32 %0, %1, %9\n\tv_writelane_b32 %0, %2, %10\n\t"
+      "v_writelane_b32 %0, %3, %11\n\tv_writelane_b32 %0, %4, %12\n\t"
+      "v_writelane_b32 %0, %5, %13\n\tv_writelane_b32 %0, %6, %14\n\t"
+      "v_writelane_b32 %0, %7, %15\n\tv_writelane_b32 %0, %8, %16"
+      : "=v"(r)
+      : "s"(x[0][0]), "s"(x[0][1]), "s"(x[1][0]), "s"(x[1][1]), "s"(x[2][0]), "s"(x[2][1]), "s"(x[3][0]),
+        "s"(x[3][1]), "n"(L0), "n"(L0 + HALF), "n"(L0 + STEP), "n"(L0 + STEP + HALF), "n"(L0 + 2 * STEP),
+        "n"(L0 + 2 * STEP + HALF), "n"(L0 + 3 * STEP), "n"(L0 + 3 * STEP + HALF), "0"(old));
   return r;
 }
 
@@ -185,18 +192,35 @@ __device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&
         for (int i = 0; i < 4; ++i) v[i] = fmaf(decay, V[mc][np][r0 + i], acc[mc][np][r0 + i]);
 #pragma unroll
         for (int i = 0; i < 4; ++i) m[i] = __builtin_amdgcn_ballot_w64(v[i] >= lg.theta[np]);
-        static_for<0, 4>([&](auto i_) {
-          constexpr int i = decltype(i_)::value;
-          constexpr int r = r0 + i;
-          const uint32_t lo = (uint32_t)m[i], hi = (uint32_t)(m[i] >> 32);
-          if constexpr (WO >= 32) {
-            word[mc][0] = write_lanes<(r << 2) | np, (r << 2) | 2 | np>(word[mc][0], lo, hi);
-          } else {
-            constexpr int base = ((r & 7) << 3) | (np << 1);
-            word[mc][r >> 3] = write_lanes<base, base | 1>(word[mc][r >> 3], lo & 0xffffu, lo >> 16);
-            word[mc][r >> 3] = write_lanes<base | 4, base | 5>(word[mc][r >> 3], hi & 0xffffu, hi >> 16);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (WO >= 32) {
+          // registers r0 .. r0+3: lanes (r << 2) | np (low half) and (r << 2) | 2 | np (high half)
+          uint32_t x[4][2];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            x[i][0] = (uint32_t)m[i];
+            x[i][1] = (uint32_t)(m[i] >> 32);
           }
-        });
+          word[mc][0] = write_lanes<(r0 << 2) | np, 4, 2>(word[mc][0], x);
+        } else {
+          // a ballot half is two rows of 16 pixels: lanes base | sub (low half), base | 4 | sub (high)
+          constexpr int base = ((r0 & 7) << 3) | (np << 1);
+          uint32_t x[4][2];
+#pragma unroll
+          for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const uint32_t lo = (uint32_t)m[i], hi = (uint32_t)(m[i] >> 32);
+              x[i][0] = sub ? lo >> 16 : lo & 0xffffu;
+              x[i][1] = sub ? hi >> 16 : hi & 0xffffu;
+            }
+            if (sub == 0)
+              word[mc][r0 >> 3] = write_lanes<base, 8, 4>(word[mc][r0 >> 3], x);
+            else
+              word[mc][r0 >> 3] = write_lanes<base | 1, 8, 4>(word[mc][r0 >> 3], x);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           V[mc][np][r0 + i] = __builtin_amdgcn_inverse_ballot_w64(m[i]) ? v[i] - theta : v[i];
@@ -207,6 +231,10 @@ __device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&
                                         lg.v_off[np]) = v[i];
           }
         }
+        // the new membranes count as used here: otherwise the compiler moves the resets behind
+        // the whole step and keeps all 128 ballots alive until then (in spilled scalar registers)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(V[mc][np][r0 + i]));
         __builtin_amdgcn_sched_barrier(0);   // keep only a few ballots alive
       });
     });
