@@ -65,6 +65,11 @@ constexpr int kWBlocks = kWBuf / 1024 / kWaves;     // one-KiB weight blocks eac
 constexpr int kFixShift = 23;                  // fixed-point scale of the aggregation weights
 constexpr int kLdsLimit = 160 * 1024;          // LDS of one compute unit
 
+// Aggregate table: entry t = the aggregate (Eq. 2) of a pixel whose frames have the bits of t,
+// in the 2^23 fixed-point scale.  K <= 8: 2^K bf16 patterns.  K = 16: two tables of 256
+// integers (frames 0..7, frames 8..15) that are added before the one rounding to bf16.
+__host__ __device__ constexpr int lut_bytes(int K) { return K == 16 ? 2048 : (K >= 2 && K <= 8 ? ((2 << K) + 15) / 16 * 16 : 0); }
+
 // Compile-time geometry of a tile: input width WIN (32 or 64 pixels = 1 or 2 words), stride S.
 template <int WIN, int S>
 struct Geo {
@@ -85,13 +90,13 @@ struct Geo {
   static constexpr int kLdsA = 0;
   static constexpr int kLdsW = kLdsA + 2 * kABuf;
   static constexpr int kLdsBias = kLdsW + 2 * kWBuf;
-  static constexpr int kLdsWords = kLdsBias + kCoutTile * 4; // two staging buffers follow
-  static constexpr int lds_bytes(int K) { return kLdsWords + 2 * kWordsPerFrame * K * 4; }
+  static constexpr int kLdsLut = kLdsBias + kCoutTile * 4;   // aggregate table, then two staging buffers
+  static constexpr int lds_bytes(int K) { return kLdsLut + lut_bytes(K) + 2 * kWordsPerFrame * K * 4; }
   // LDS column (in 16-byte units) of padded pixel xp
   __host__ __device__ static constexpr int col(int xp) { return S == 1 ? xp : (xp & 1) * kXH + (xp >> 1); }
-  // the loader pipeline has kSteps + 1 slots (slot i requests step i and expands step i-1),
-  // spread over the 8 filter taps in front of the workgroup barrier
-  static constexpr int kSlotsPerTap = (kSteps + 1 + 7) / 8;
+  // the loader pipeline has kSteps + 2 slots (slot i reads the words of step i, looks up step
+  // i-1 and writes step i-2), spread over the 8 filter taps in front of the workgroup barrier
+  static constexpr int kSlotsPerTap = (kSteps + 2 + 7) / 8;
 };
 
 struct MfmaParams {
@@ -242,71 +247,135 @@ __device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&
 }
 
 // ---- staging of packed input words ------------------------------------------------------
-// Flat staging index i in [0, F K) with F = 16 * rows * words-per-row:
-// i = j * F + (cin * rows + row) * wpr + word, so that consecutive threads read consecutive
-// dwords of one (frame, channel) plane.  In LDS the order is [row word][cin][frame], index
-// ((row * wpr + word) * 16 + cin) * K + j: the K frames of the four channels a loader lane
-// aggregates are 4 K adjacent dwords.  A thread's share of a chunk is the same in every chunk,
-// so its global dword offsets (relative to the chunk's first frame and channel) and LDS indices
-// are computed once.
-template <int NL>
+// A staging group is the K words (one per frame) of one (channel, input row, word of the row);
+// a thread owns the same groups in every chunk, so its global offsets and LDS addresses are
+// computed once.  Consecutive threads take consecutive words of a channel plane (coalesced
+// loads).  Before the words go to LDS, the thread that holds a group turns its K x 32 bit
+// matrix (frame j, pixel p) into K "class words": class word c holds the pixels p = c (mod K),
+// pixel p as the K-bit field [bit j = frame j] at bit position p - c.  A loader lane then gets
+// all K bits of its pixel with one bit-field extract, and the aggregate from a table.  K = 16
+// is staged as two such halves of 8 frames.  In LDS the order is [row word][class word][cin].
+template <int NG>
 struct StagePlan {
-  uint32_t goff[NL];     // dword offset from the chunk base (always a valid address)
-  uint32_t lidx[NL];     // dword index in the LDS staging buffer; 0xffffffff = this thread has no word l
-  uint32_t keep;         // bit l set: the word is inside the image; clear: store a zero word (padding row)
+  uint32_t goff[NG];     // dword offset of the group's frame-0 word from the chunk base (always valid)
+  uint32_t lofs[NG];     // byte offset of the group's first word in the staging buffer; 0xffffffff = no group
+  uint32_t keep;         // bit l set: the input row is inside the image; clear: store zero words (padding row)
 };
 
-template <class G, int NL>
-__device__ __forceinline__ void stage_plan(StagePlan<NL>& sp, const MfmaParams& p, int K, int tid, int iy0) {
-  const int n = G::kWordsPerFrame * K;
+template <class G, int NG>
+__device__ __forceinline__ void stage_plan(StagePlan<NG>& sp, const MfmaParams& p, int K, int tid, int iy0) {
   sp.keep = 0;
 #pragma unroll
-  for (int l = 0; l < NL; ++l) {
-    const int i = tid + l * kThreads;
+  for (int l = 0; l < NG; ++l) {
+    const int g = tid + l * kThreads;
     sp.goff[l] = 0;
-    sp.lidx[l] = 0xffffffffu;
-    if (i < n) {
-      const int j = i / G::kWordsPerFrame;
-      const int rem = i - j * G::kWordsPerFrame;           // (cin * rows + row) * wpr + word
-      const int cin = rem / G::kRowWords;
-      const int rw = rem - cin * G::kRowWords;
+    sp.lofs[l] = 0xffffffffu;
+    if (g < G::kWordsPerFrame) {
+      const int cin = g / G::kRowWords;
+      const int rw = g - cin * G::kRowWords;                // row * wpr + word
       const int row = rw / G::kWW, word = rw - row * G::kWW;
       const int iy = iy0 + row;
       const int iyc = min(max(iy, 0), p.H - 1);
-      sp.lidx[l] = (uint32_t)((rw * kChunk + cin) * K + j);
-      sp.goff[l] = (uint32_t)((((size_t)j * p.B * p.Cin + cin) * p.H + iyc) * G::kWW + word);
+      sp.lofs[l] = (uint32_t)((rw * K * kChunk + cin) * 4);
+      sp.goff[l] = (uint32_t)((cin * p.H + iyc) * G::kWW + word);
       if (iy == iyc) sp.keep |= 1u << l;
     }
   }
 }
 
 // Unconditional loads (no lane masking, no register initialisation in front of them).  `base`
-// is the wave-uniform address of (first frame of the group, sample, first channel of the chunk).
-template <int NL>
-__device__ __forceinline__ void stage_load(uint32_t (&wd)[NL], const StagePlan<NL>& sp, const uint32_t* base,
-                                           int l0 = 0, int l1 = NL) {
+// is the wave-uniform address of (first frame of the group of frames, sample, first channel of
+// the chunk), fstride the distance between frames in dwords.  Loads f0 <= l * KM + j < f1 only.
+template <int KM, int NG>
+__device__ __forceinline__ void stage_load(uint32_t (&wd)[NG][KM], const StagePlan<NG>& sp, const uint32_t* base,
+                                           uint32_t fstride, int K, int f0 = 0, int f1 = NG * KM) {
 #pragma unroll
-  for (int l = 0; l < NL; ++l)
-    if (l >= l0 && l < l1) wd[l] = base[sp.goff[l]];
+  for (int l = 0; l < NG; ++l)
+#pragma unroll
+    for (int j = 0; j < KM; ++j) {
+      const int f = l * KM + j;
+      if (f >= f0 && f < f1 && j < K) wd[l][j] = (base + (size_t)j * fstride)[sp.goff[l]];
+    }
 }
 
-template <int NL>
-__device__ __forceinline__ void stage_store(const uint32_t (&wd)[NL], const StagePlan<NL>& sp, uint8_t* words_buf) {
+// (a & m) | (b & ~m): one v_bfi_b32
+__device__ __forceinline__ uint32_t bfi(uint32_t m, uint32_t a, uint32_t b) { return (a & m) | (b & ~m); }
+
+// K frame words -> K class words, in place (K a power of two up to 8).  Recursion: the two
+// halves of the frames give class words with K/2-bit fields; class c of the result takes the
+// even fields of both (low half of the new field from the first half of the frames), class
+// c + K/2 the odd ones.
+template <int K>
+__device__ __forceinline__ void frames_to_fields(uint32_t* w) {
+  if constexpr (K >= 2) {
+    frames_to_fields<K / 2>(w);
+    frames_to_fields<K / 2>(w + K / 2);
+    constexpr uint32_t m = K == 2 ? 0x55555555u : (K == 4 ? 0x33333333u : 0x0f0f0f0fu);
 #pragma unroll
-  for (int l = 0; l < NL; ++l)
-    if (sp.lidx[l] != 0xffffffffu)
-      reinterpret_cast<uint32_t*>(words_buf)[sp.lidx[l]] = (sp.keep >> l) & 1u ? wd[l] : 0u;
+    for (int c = 0; c < K / 2; ++c) {
+      const uint32_t lo = w[c], hi = w[c + K / 2];
+      w[c] = bfi(m, lo, hi << (K / 2));
+      w[c + K / 2] = bfi(m, lo >> (K / 2), hi);
+    }
+  }
 }
 
-// The loader works in steps of 64 input pixels (one row of 64, or two rows of 32) and in two
-// halves one pipeline slot apart, so that the LDS latency of the word reads hides behind the
-// MFMAs: read_words fetches, for the lane's pixel, the K staged words (one per frame) for each
-// of the wave's 4 channels (cin quad q); expand_words turns them into the 4 bf16 aggregates
-// and writes them into the A tile under construction.
+template <int KT, int KM, int NG>
+__device__ __forceinline__ void stage_store(const uint32_t (&wd)[NG][KM], const StagePlan<NG>& sp, uint8_t* words_buf,
+                                            int K) {
+#pragma unroll
+  for (int l = 0; l < NG; ++l)
+    if (sp.lofs[l] != 0xffffffffu) {
+      uint8_t* dst = words_buf + sp.lofs[l];
+      const bool keep = (sp.keep >> l) & 1u;
+      if constexpr (KT > 0) {
+        uint32_t w[KT];
+#pragma unroll
+        for (int j = 0; j < KT; ++j) w[j] = keep ? wd[l][j] : 0u;
+        if constexpr (KT == 16) {
+          frames_to_fields<8>(w);
+          frames_to_fields<8>(w + 8);
+        } else {
+          frames_to_fields<KT>(w);
+        }
+#pragma unroll
+        for (int m = 0; m < KT; ++m) *reinterpret_cast<uint32_t*>(dst + m * (kChunk * 4)) = w[m];
+      } else {
+        for (int j = 0; j < K; ++j) *reinterpret_cast<uint32_t*>(dst + j * (kChunk * 4)) = keep ? wd[l][j] : 0u;
+      }
+    }
+}
+
 template <int KT>
-struct RowWords {
-  static constexpr int N = KT > 0 ? KT : 1;
-  uint32_t w[4][N];
+__device__ __forceinline__ void lut_fill(uint8_t* lut, const MfmaParams& p, int tid) {
+  if constexpr (KT >= 2 && KT <= 8) {
+    for (int t = tid; t < (1 << KT); t += kThreads) {
+      uint32_t acc = 0;
+#pragma unroll
+      for (int j = 0; j < KT; ++j) acc += ((t >> j) & 1) * p.wq[j];
+      reinterpret_cast<uint16_t*>(lut)[t] = (uint16_t)pack_bf16((float)acc, 0.f);
+    }
+  } else if constexpr (KT == 16) {
+    for (int t = tid; t < 512; t += kThreads) {
+      uint32_t acc = 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc += ((t >> j) & 1) * p.wq[(t >> 8) * 8 + j];
+      reinterpret_cast<uint32_t*>(lut)[t] = acc;
+    }
+  }
+}
+
+// The loader works in steps of 64 input pixels (one row of 64, or two rows of 32) and in three
+// stages one pipeline slot apart, so that the LDS latencies hide behind the MFMAs: read_words
+// fetches the class words of the lane's pixel for the wave's 4 channels (cin quad q), one
+// 16-byte read; lookup extracts the pixel's K-bit field from each and requests the table
+// entries; write_a packs the 4 bf16 aggregates and writes them into the A tile under
+// construction.
+template <int KT>
+struct StepRegs {
+  u32x4 cw;              // class words (K = 16: frames 0..7)
+  u32x4 cw_hi;           // K = 16: frames 8..15
+  uint32_t lv[KT == 16 ? 8 : 4];   // table entries
 };
 
 // index of the lane's word within a channel's [row][word] block at loader step `step`; in an
@@ -326,32 +395,32 @@ __device__ __forceinline__ int a_write_off(int lane, int step) {
 }
 
 template <class G, int KT>
-__device__ __forceinline__ void read_words(RowWords<KT>& rw, const uint8_t* words_buf, int lane, int q, int step) {
+__device__ __forceinline__ void read_words(StepRegs<KT>& sr, const uint8_t* words_buf, int lane, int q, int step) {
   static_assert(KT > 0, "compile-time K only");
-  // the lane's 4 channels x KT frames: 4 KT consecutive dwords
-  const uint32_t* src = reinterpret_cast<const uint32_t*>(words_buf) + (lane_word<G>(lane, step) * kChunk + q * 4) * KT;
-  if constexpr (KT >= 4) {
+  const int lw = lane_word<G>(lane, step);
+  if constexpr (KT == 16) {
+    const uint8_t* src = words_buf + (((lw * 16 + (lane & 7)) * kChunk + q * 4) * 4);
+    sr.cw = *reinterpret_cast<const u32x4*>(src);
+    sr.cw_hi = *reinterpret_cast<const u32x4*>(src + 8 * kChunk * 4);
+  } else {
+    sr.cw = *reinterpret_cast<const u32x4*>(words_buf + (((lw * KT + (lane & (KT - 1))) * kChunk + q * 4) * 4));
+  }
+}
+
+template <int KT>
+__device__ __forceinline__ void lookup(StepRegs<KT>& sr, const uint8_t* lut, int lane) {
+  if constexpr (KT >= 2 && KT <= 8) {
+    const uint32_t pos = lane & 31 & ~(KT - 1);
 #pragma unroll
     for (int e = 0; e < 4; ++e)
+      sr.lv[e] = reinterpret_cast<const uint16_t*>(lut)[__builtin_amdgcn_ubfe(sr.cw[e], pos, KT)];
+  } else if constexpr (KT == 16) {
+    const uint32_t pos = lane & 31 & ~7;
 #pragma unroll
-      for (int j4 = 0; j4 < KT / 4; ++j4) {
-        const u32x4 w4 = *reinterpret_cast<const u32x4*>(src + e * KT + 4 * j4);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) rw.w[e][4 * j4 + j] = w4[j];
-      }
-  } else if constexpr (KT == 2) {
-#pragma unroll
-    for (int e2 = 0; e2 < 2; ++e2) {
-      const u32x4 w4 = *reinterpret_cast<const u32x4*>(src + 4 * e2);
-      rw.w[2 * e2][0] = w4[0];
-      rw.w[2 * e2][1] = w4[1];
-      rw.w[2 * e2 + 1][0] = w4[2];
-      rw.w[2 * e2 + 1][1] = w4[3];
+    for (int e = 0; e < 4; ++e) {
+      sr.lv[e] = reinterpret_cast<const uint32_t*>(lut)[__builtin_amdgcn_ubfe(sr.cw[e], pos, 8)];
+      sr.lv[4 + e] = reinterpret_cast<const uint32_t*>(lut)[256 + __builtin_amdgcn_ubfe(sr.cw_hi[e], pos, 8)];
     }
-  } else {
-    const u32x4 w4 = *reinterpret_cast<const u32x4*>(src);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) rw.w[e][0] = w4[e];
   }
 }
 
@@ -365,60 +434,51 @@ __device__ __forceinline__ void a_write_packed(uint8_t* a_next, int lane, int q,
   }
 }
 
-template <class G>
-__device__ __forceinline__ void a_write(uint8_t* a_next, int lane, int q, int step, const float (&val)[4]) {
-  a_write_packed<G>(a_next, lane, q, step, u32x2{pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])});
-}
-
 template <class G, int KT>
-__device__ __forceinline__ void expand_words(const RowWords<KT>& rw, const MfmaParams& p, uint8_t* a_next, int lane,
-                                             int q, int step) {
-  const uint32_t bitpos = lane & 31;
+__device__ __forceinline__ void write_a(const StepRegs<KT>& sr, uint8_t* a_next, int lane, int q, int step) {
+  u32x2 pk;
   if constexpr (KT == 1) {
     // one frame: the aggregate is the bit itself, 2^23 in the fixed-point scale, whose bf16
     // pattern is 0x4b00; two channels per multiplication
     static_assert(kFixShift == 23, "0x4b00 is bf16(2^23)");
-    u32x2 pk;
+    const uint32_t bitpos = lane & 31;
 #pragma unroll
     for (int e2 = 0; e2 < 2; ++e2) {
-      const uint32_t b0 = __builtin_amdgcn_ubfe(rw.w[2 * e2][0], bitpos, 1);
-      const uint32_t b1 = __builtin_amdgcn_ubfe(rw.w[2 * e2 + 1][0], bitpos, 1);
+      const uint32_t b0 = __builtin_amdgcn_ubfe(sr.cw[2 * e2], bitpos, 1);
+      const uint32_t b1 = __builtin_amdgcn_ubfe(sr.cw[2 * e2 + 1], bitpos, 1);
       pk[e2] = __umul24((b1 << 16) | b0, 0x4b00u);
     }
-    a_write_packed<G>(a_next, lane, q, step, pk);
+  } else if constexpr (KT == 16) {
+    pk[0] = pack_bf16((float)(sr.lv[0] + sr.lv[4]), (float)(sr.lv[1] + sr.lv[5]));
+    pk[1] = pack_bf16((float)(sr.lv[2] + sr.lv[6]), (float)(sr.lv[3] + sr.lv[7]));
   } else {
-    float val[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      uint32_t acc = 0;
-#pragma unroll
-      for (int j = 0; j < KT; ++j) acc = __umul24(__builtin_amdgcn_ubfe(rw.w[e][j], bitpos, 1), p.wq[j]) + acc;
-      val[e] = (float)acc;
-    }
-    a_write<G>(a_next, lane, q, step, val);
+    pk[0] = (sr.lv[1] << 16) | sr.lv[0];
+    pk[1] = (sr.lv[3] << 16) | sr.lv[2];
   }
+  a_write_packed<G>(a_next, lane, q, step, pk);
 }
 
-// Unpipelined form (prologue, and the run-time-K kernel).
+// Unpipelined form (prologue, and the run-time-K kernel, which reads the frames' words as
+// they are and adds the weights bit by bit).
 template <class G, int KT>
-__device__ __forceinline__ void expand_step(const MfmaParams& p, const uint8_t* words_buf, uint8_t* a_next, int K,
-                                            int lane, int q, int step) {
+__device__ __forceinline__ void expand_step(const MfmaParams& p, const uint8_t* words_buf, const uint8_t* lut,
+                                            uint8_t* a_next, int K, int lane, int q, int step) {
   if constexpr (KT > 0) {
-    RowWords<KT> rw;
-    read_words<G, KT>(rw, words_buf, lane, q, step);
-    expand_words<G, KT>(rw, p, a_next, lane, q, step);
+    StepRegs<KT> sr;
+    read_words<G, KT>(sr, words_buf, lane, q, step);
+    lookup<KT>(sr, lut, lane);
+    write_a<G, KT>(sr, a_next, lane, q, step);
   } else {
-    const uint32_t* wb = reinterpret_cast<const uint32_t*>(words_buf);
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(words_buf) + (lane_word<G>(lane, step) * K * kChunk + q * 4);
     const uint32_t bitpos = lane & 31;
-    float val[4];
+    uint32_t acc[4] = {0, 0, 0, 0};
+    for (int j = 0; j < K; ++j) {
+      const u32x4 w4 = *reinterpret_cast<const u32x4*>(src + j * kChunk);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const uint32_t* src = wb + ((lane_word<G>(lane, step) * kChunk + q * 4 + e) * K);
-      uint32_t acc = 0;
-      for (int j = 0; j < K; ++j) acc = __umul24(__builtin_amdgcn_ubfe(src[j], bitpos, 1), p.wq[j]) + acc;
-      val[e] = (float)acc;
+      for (int e = 0; e < 4; ++e) acc[e] = __umul24(__builtin_amdgcn_ubfe(w4[e], bitpos, 1), p.wq[j]) + acc[e];
     }
-    a_write<G>(a_next, lane, q, step, val);
+    a_write_packed<G>(a_next, lane, q, step,
+                      u32x2{pack_bf16((float)acc[0], (float)acc[1]), pack_bf16((float)acc[2], (float)acc[3])});
   }
 }
 
@@ -437,7 +497,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   using G = Geo<WIN, S>;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   constexpr int KMAX = KT > 0 ? KT : TAC_MAX_K;
-  constexpr int NL = (G::kWordsPerFrame * KMAX + kThreads - 1) / kThreads;
+  constexpr int NG = (G::kWordsPerFrame + kThreads - 1) / kThreads;     // staging groups per thread
   const int K = KT > 0 ? KT : p.K;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -461,7 +521,8 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   const int Ho = p.Ho;
   const int co_wave = co_tile * kCoutTile;
   const int total = p.G * NC;
-  uint8_t* const words0 = lds + G::kLdsWords;
+  uint8_t* const lut = lds + G::kLdsLut;
+  uint8_t* const words0 = lut + lut_bytes(KT);
   const int words_bytes = G::kWordsPerFrame * K * 4;
   const int oy_wave = y0 + wave * G::kWaveRows;                // first output row of this wave
 
@@ -555,9 +616,11 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   constexpr std::integral_constant<int, 8> c8;
   constexpr std::integral_constant<int, 9> c9;
 
-  StagePlan<NL> plan;
-  stage_plan<G, NL>(plan, p, K, tid, y0 * S - 1);
-  uint32_t wd[NL];                              // staged words in flight
+  StagePlan<NG> plan;
+  stage_plan<G, NG>(plan, p, K, tid, y0 * S - 1);
+  uint32_t wd[NG][KMAX];                        // staged words in flight
+  const uint32_t fstride = (uint32_t)(p.B * p.Cin * p.H * G::kWW);   // dwords between frames
+  lut_fill<KT>(lut, p, tid);
 
   // ---- prologue: A tile of chunk 0, weights of chunks 0 and 1, staged words of chunk 1,
   //      words of chunk 2 in registers
@@ -571,19 +634,19 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     cur.c = 0;
     cur.left = total - 1;
     weights_to_lds(cur.w, lds + G::kLdsW, c0, c9);
-    stage_load<NL>(wd, plan, cur.spk);
-    stage_store<NL>(wd, plan, words0);
+    stage_load<KMAX, NG>(wd, plan, cur.spk, fstride, K);
+    stage_store<KT, KMAX, NG>(wd, plan, words0, K);
     advance(cur);                               // chunk 1
     w_n1 = cur.w;
     weights_to_lds(cur.w, lds + G::kLdsW + kWBuf, c0, c9);
-    stage_load<NL>(wd, plan, cur.spk);
-    stage_store<NL>(wd, plan, words0 + words_bytes);
+    stage_load<KMAX, NG>(wd, plan, cur.spk, fstride, K);
+    stage_store<KT, KMAX, NG>(wd, plan, words0 + words_bytes, K);
     __syncthreads();
-    for (int st = 0; st < G::kSteps; ++st) expand_step<G, KT>(p, words0, lds + G::kLdsA, K, lane, q, st);
+    for (int st = 0; st < G::kSteps; ++st) expand_step<G, KT>(p, words0, lut, lds + G::kLdsA, K, lane, q, st);
     advance(cur);                               // chunk 2
     w_n2 = cur.w;
     spk_n2 = cur.spk;
-    stage_load<NL>(wd, plan, cur.spk);
+    stage_load<KMAX, NG>(wd, plan, cur.spk, fstride, K);
     advance(cur);                               // chunk 3
   }
   __syncthreads();
@@ -611,7 +674,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   // by then every read of the PAR buffers has returned (tap 8's fragments are fetched during
   // tap 7) and every write to the PAR^1 buffers is done, so tap 8 already fetches the first
   // fragments of the next chunk and starts refilling the PAR weight buffer.
-  static_assert(8 * G::kSlotsPerTap >= G::kSteps + 1, "the loader must be done before the barrier");
+  static_assert(8 * G::kSlotsPerTap >= G::kSteps + 2, "the loader must be done before the barrier");
   auto chunk_iteration = [&](int s) {
     const int PAR = s & 1;
     const uint8_t* a_cur = lds + G::kLdsA + PAR * G::kABuf;
@@ -620,7 +683,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     uint8_t* w_next = lds + G::kLdsW + (PAR ^ 1) * kWBuf;
     const uint8_t* words_next = words0 + (PAR ^ 1) * words_bytes;    // words of chunk s+1 (read now)
     uint8_t* words_nn = words0 + PAR * words_bytes;                  // words of chunk s+2 (written at tap 7)
-    RowWords<KT> rw;
+    StepRegs<KT> sr;
 #pragma unroll
     for (int mc = 0; mc < kMC; ++mc) wf[0][mc] = wf[1][mc];
 #pragma unroll
@@ -633,11 +696,11 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
       // after the barrier: tap 8 starts refilling it for chunk s+2 (blocks 0,1) and taps 0..5
       // of the next chunk finish that (blocks 2..8).  Staged words likewise: part 0 at tap 8
       // (for chunk s+3), parts 1..5 at taps 0..4 (for chunk s+2, written to LDS at tap 7).
-      constexpr int kLPT = (NL + 5) / 6;        // staged words requested per part
+      constexpr int kLPT = (NG * KMAX + 5) / 6;  // staged words requested per part
       if (tap == 8) {
         weights_to_lds(w_n2, const_cast<uint8_t*>(w_cur), c0, c2);
         __builtin_amdgcn_sched_barrier(0);
-        stage_load<NL>(wd, plan, cur.spk, 0, kLPT);
+        stage_load<KMAX, NG>(wd, plan, cur.spk, fstride, K, 0, kLPT);
         fetch(a_next, w_next, 0, slot ^ 1);
       } else {
         if (tap <= 5) {
@@ -649,7 +712,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
             case 4: weights_to_lds(w_n1, w_next, c7, c8); break;
             default: weights_to_lds(w_n1, w_next, c8, c9); break;
           }
-          if (tap <= 4) stage_load<NL>(wd, plan, spk_n2, (tap + 1) * kLPT, (tap + 2) * kLPT);
+          if (tap <= 4) stage_load<KMAX, NG>(wd, plan, spk_n2, fstride, K, (tap + 1) * kLPT, (tap + 2) * kLPT);
         }
         fetch(a_cur, w_cur, tap + 1, slot ^ 1);
       }
@@ -658,22 +721,25 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
 #pragma unroll
         for (int np = 0; np < 2; ++np)
           acc[mc][np] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][mc], af[slot][np], acc[mc][np], 0, 0, 0);
-      // loader: pipeline slot i expands step i-1, then requests the words of step i
+      // loader: pipeline slot i writes step i-2, looks up step i-1 and reads the words of step i
+      // (one frame: no table, the write follows the read by one slot)
 #pragma unroll
       for (int i = tap * G::kSlotsPerTap; i < (tap + 1) * G::kSlotsPerTap; ++i) {
         if constexpr (KT > 0) {
-          if (i >= 1 && i <= G::kSteps) expand_words<G, KT>(rw, p, a_next, lane, q, i - 1);
-          if (i < G::kSteps) read_words<G, KT>(rw, words_next, lane, q, i);
+          constexpr int kD = KT == 1 ? 1 : 2;
+          if (i >= kD && i - kD < G::kSteps) write_a<G, KT>(sr, a_next, lane, q, i - kD);
+          if (kD == 2 && i >= 1 && i - 1 < G::kSteps) lookup<KT>(sr, lut, lane);
+          if (i < G::kSteps) read_words<G, KT>(sr, words_next, lane, q, i);
         } else {
-          if (i < G::kSteps) expand_step<G, KT>(p, words_next, a_next, K, lane, q, i);
+          if (i < G::kSteps) expand_step<G, KT>(p, words_next, lut, a_next, K, lane, q, i);
         }
       }
-      if (tap == 7) stage_store<NL>(wd, plan, words_nn);
+      if (tap == 7) stage_store<KT, KMAX, NG>(wd, plan, words_nn, K);
       if constexpr (KT > 0) {
         // issue order inside the tap: one MFMA, then a few LDS reads and vector ops that run
         // while the matrix pipe is busy, eight times over
-        constexpr int kValuPerMfma = (KT <= 2 ? 3 : (KT == 4 ? 5 : (KT == 8 ? 10 : 18))) * G::kSlotsPerTap;
-        constexpr int kDsPerMfma = G::kSlotsPerTap == 1 ? 2 : 3;
+        constexpr int kValuPerMfma = (KT == 16 ? 4 : 2) * G::kSlotsPerTap;
+        constexpr int kDsPerMfma = (G::kSlotsPerTap == 1 && KT != 16) ? 2 : 3;
 #pragma unroll
         for (int i = 0; i < 2 * kMC; ++i) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
