@@ -49,8 +49,8 @@ int validate(const tac_layer_desc_t* d) {
 int select_kernel(const tac_layer_desc_t* d) {
   const bool ok = tac::mfma_supported(*d);
   if (d->kernel == TAC_KERNEL_DIRECT) return TAC_KERNEL_DIRECT;
-  if (d->kernel == TAC_KERNEL_MFMA) return ok ? TAC_KERNEL_MFMA : TAC_ERR_UNSUPPORTED;
-  return ok ? TAC_KERNEL_MFMA : TAC_KERNEL_DIRECT;
+  if (d->kernel == TAC_KERNEL_MFMA) return ok ? (int)TAC_KERNEL_MFMA : (int)TAC_ERR_UNSUPPORTED;
+  return ok ? (int)TAC_KERNEL_MFMA : (int)TAC_KERNEL_DIRECT;
 }
 
 }  // namespace
