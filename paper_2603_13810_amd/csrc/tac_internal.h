@@ -39,6 +39,11 @@ bool mfma_supported(const tac_layer_desc_t& d);
 size_t mfma_weight_bytes(const tac_layer_desc_t& d);
 hipError_t mfma_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s);
 hipError_t mfma_launch(const LayerParams& p, hipStream_t s);
+// its member for short contractions (Cin * 9 <= 32)
+bool mfma_small_supported(const tac_layer_desc_t& d);
+size_t mfma_small_weight_bytes(const tac_layer_desc_t& d);
+hipError_t mfma_small_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s);
+hipError_t mfma_small_launch(const LayerParams& p, hipStream_t s);
 
 hipError_t pack_launch(const uint8_t* dense, uint32_t* packed, int64_t rows, int W, hipStream_t s);
 hipError_t unpack_launch(const uint32_t* packed, uint8_t* dense, int64_t rows, int W, hipStream_t s);

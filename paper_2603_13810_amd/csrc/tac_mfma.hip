@@ -37,22 +37,11 @@
 // Fixed point: the aggregate is formed as A' = sum_j bit_j * round(beta^(K-1-j) 2^23), an
 // integer below 2^28, and the prepared weights carry the factor 2^-23 (a power of two, so
 // the bf16 rounding of both operands is unchanged and the products are the same).
-#include <type_traits>
-
-#include "tac_internal.h"
+#include "tac_mfma_common.h"
 
 namespace tac {
 
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-typedef const __attribute__((address_space(1))) void* global_void_ptr;
 
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
@@ -62,7 +51,6 @@ constexpr int kChunk = 16;                     // input channels per MFMA k-step
 constexpr int kWTap = kMC * 64 * 16;           // bytes of one tap: [mc][lane][8 bf16]
 constexpr int kWBuf = 9 * kWTap;
 constexpr int kWBlocks = kWBuf / 1024 / kWaves;     // one-KiB weight blocks each wave copies per chunk
-constexpr int kFixShift = 23;                  // fixed-point scale of the aggregation weights
 constexpr int kLdsLimit = 160 * 1024;          // LDS of one compute unit
 
 // Aggregate table: entry t = the aggregate (Eq. 2) of a pixel whose frames have the bits of t,
@@ -99,58 +87,6 @@ struct Geo {
   static constexpr int kSlotsPerTap = (kSteps + 2 + 7) / 8;
 };
 
-struct MfmaParams {
-  const uint32_t* __restrict__ spikes;
-  const uint8_t* __restrict__ w;       // prepared: [cout_tile][chunk][tap][mc][lane][8] bf16, scaled 2^-23
-  const float* __restrict__ bias;
-  float* __restrict__ v_inout;
-  uint32_t* __restrict__ out;
-  float* __restrict__ v_trace;
-  int B, Cin, H, Ho, Cout, K, G, n_lif, row_tiles;
-  float decay, theta;
-  uint32_t wq[TAC_MAX_K];              // round(beta^(K-1-j) * 2^23)
-};
-
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  f32x2 f = {a, b};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // v_cvt_pk_bf16_f32, nearest even
-}
-
-// vdst[lane L0 + i * STEP + (j ? HALF : 0)] = x[i][j] for the wave-uniform values x[4][2]; other
-// lanes keep `old`.  The s_nop covers the two wait states this chip needs between a vector
-// instruction that wrote an SGPR (the compare, or a spill reload) and a vector instruction that
-// reads it: the assembler text is opaque to the compiler's hazard pass.
-template <int L0, int STEP, int HALF>
-__device__ __forceinline__ uint32_t write_lanes(uint32_t old, const uint32_t (&x)[4][2]) {
-  uint32_t r;
-  asm volatile(
-      "s_nop 1\n\t"
-      "v_writelane_b32 %0, %1, %9\n\tv_writelane_b32 %0, %2, %10\n\t"
-      "v_writelane_b32 %0, %3, %11\n\tv_writelane_b32 %0, %4, %12\n\t"
-      "v_writelane_b32 %0, %5, %13\n\tv_writelane_b32 %0, %6, %14\n\t"
-      "v_writelane_b32 %0, %7, %15\n\tv_writelane_b32 %0, %8, %16"
-      : "=v"(r)
-      : "s"(x[0][0]), "s"(x[0][1]), "s"(x[1][0]), "s"(x[1][1]), "s"(x[2][0]), "s"(x[2][1]), "s"(x[3][0]),
-        "s"(x[3][1]), "n"(L0), "n"(L0 + HALF), "n"(L0 + STEP), "n"(L0 + STEP + HALF), "n"(L0 + 2 * STEP),
-        "n"(L0 + 2 * STEP + HALF), "n"(L0 + 3 * STEP), "n"(L0 + 3 * STEP + HALF), "0"(old));
-  return r;
-}
-
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<I + 1, N>(f);
-  }
-}
-
-// Per-lane constants of the epilogue: where the lane's two pixels (np = 0, 1) sit.
-struct LaneGeom {
-  uint32_t v_off[2];     // byte offset of (4 h channels, local row, column) in the wave's membrane block
-  float theta[2];        // the threshold, or +inf where the pixel's output row is outside the image
-  bool ok[2];            // the pixel's output row is inside the image
-};
-
 // Computed afresh wherever it is needed (from an opaque copy of the lane id), so that it does
 // not occupy registers across the MFMA loop.
 template <class G>
@@ -167,83 +103,8 @@ __device__ __forceinline__ LaneGeom lane_geom(int lane, int oy_wave, int Ho, siz
     lg.ok[np] = oy_wave + lr < Ho;
     lg.theta[np] = lg.ok[np] ? theta : __builtin_inff();
   }
+  lg.co_lim = 1 << 30;
   return lg;
-}
-
-// One LIF step on a wave's 4 x 2 MFMA tiles: V <- decay V + Y, spike iff V >= theta,
-// subtractive reset.  Register r of tile (mc, np) on lane (n, h) is channel
-// 32 mc + 8 (r/4) + 4 h + r%4 at the wave's pixel 32 np + n.  The ballot of a register is two
-// 32-bit halves (h = 0, 1), each the packed spikes of 32 consecutive output pixels of one
-// channel; they are handed, one per lane, to the store registers word[mc][..]:
-//   output width 64 or 32: lane (r << 2) | (h << 1) | np of word[mc][0] holds pixel block np;
-//   output width 16:       a half is two rows of 16 pixels; lane
-//                          ((r & 7) << 3) | (h << 2) | (np << 1) | sub of word[mc][r >> 3] holds
-//                          row 2 np + sub.
-template <int WO, bool TRACE>
-__device__ __forceinline__ void lif_step(float (&V)[kMC][2][16], const f32x16 (&acc)[kMC][2], float decay, float theta,
-                                         const LaneGeom& lg, uint32_t (&word)[kMC][2], float* __restrict__ trace_wave,
-                                         size_t plane) {
-  static_for<0, kMC>([&](auto mc_) {
-    constexpr int mc = decltype(mc_)::value;
-    static_for<0, 2>([&](auto np_) {
-      constexpr int np = decltype(np_)::value;
-      // four registers at a time: all four membranes and compares first, then the four ballot
-      // hand-overs, then the four resets, so that no instruction waits on the one before it
-      static_for<0, 4>([&](auto r4_) {
-        constexpr int r0 = decltype(r4_)::value * 4;
-        float v[4];
-        uint64_t m[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = fmaf(decay, V[mc][np][r0 + i], acc[mc][np][r0 + i]);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) m[i] = __builtin_amdgcn_ballot_w64(v[i] >= lg.theta[np]);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (WO >= 32) {
-          // registers r0 .. r0+3: lanes (r << 2) | np (low half) and (r << 2) | 2 | np (high half)
-          uint32_t x[4][2];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            x[i][0] = (uint32_t)m[i];
-            x[i][1] = (uint32_t)(m[i] >> 32);
-          }
-          word[mc][0] = write_lanes<(r0 << 2) | np, 4, 2>(word[mc][0], x);
-        } else {
-          // a ballot half is two rows of 16 pixels: lanes base | sub (low half), base | 4 | sub (high)
-          constexpr int base = ((r0 & 7) << 3) | (np << 1);
-          uint32_t x[4][2];
-#pragma unroll
-          for (int sub = 0; sub < 2; ++sub) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const uint32_t lo = (uint32_t)m[i], hi = (uint32_t)(m[i] >> 32);
-              x[i][0] = sub ? lo >> 16 : lo & 0xffffu;
-              x[i][1] = sub ? hi >> 16 : hi & 0xffffu;
-            }
-            if (sub == 0)
-              word[mc][r0 >> 3] = write_lanes<base, 8, 4>(word[mc][r0 >> 3], x);
-            else
-              word[mc][r0 >> 3] = write_lanes<base | 1, 8, 4>(word[mc][r0 >> 3], x);
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          V[mc][np][r0 + i] = __builtin_amdgcn_inverse_ballot_w64(m[i]) ? v[i] - theta : v[i];
-          if constexpr (TRACE) {
-            if (lg.ok[np])
-              *reinterpret_cast<float*>(reinterpret_cast<char*>(trace_wave) +
-                                        (size_t)(mc * 32 + 8 * ((r0 + i) >> 2) + ((r0 + i) & 3)) * plane * 4 +
-                                        lg.v_off[np]) = v[i];
-          }
-        }
-        // the new membranes count as used here: otherwise the compiler moves the resets behind
-        // the whole step and keeps all 128 ballots alive until then (in spilled scalar registers)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(V[mc][np][r0 + i]));
-        __builtin_amdgcn_sched_barrier(0);   // keep only a few ballots alive
-      });
-    });
-  });
 }
 
 // ---- staging of packed input words ------------------------------------------------------
@@ -818,9 +679,9 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
         float* tl = p.v_trace + step * ((size_t)p.B * p.Cout * plane) + v_wave;
         size_t plane_l = plane;
         asm volatile("" : "+s"(plane_l));       // keep the trace addresses out of the loop preheader
-        lif_step<G::kWo, true>(V, acc, p.decay, p.theta, lg, word, tl, plane_l);
+        lif_step<kMC, G::kWo, true>(V, acc, p.decay, p.theta, lg, word, tl, plane_l);
       } else {
-        lif_step<G::kWo, false>(V, acc, p.decay, p.theta, lg, word, nullptr, plane);
+        lif_step<kMC, G::kWo, false>(V, acc, p.decay, p.theta, lg, word, nullptr, plane);
       }
       if (out_ok) {
         uint32_t* const o = out_wave + step * out_step;
@@ -930,7 +791,7 @@ static_assert(max_k<64, 2>() >= 4 && max_k<32, 2>() >= 4, "stride 2 takes K up t
 
 }  // namespace
 
-bool mfma_supported(const tac_layer_desc_t& d) {
+static bool large_supported(const tac_layer_desc_t& d) {
   if (d.precision != TAC_BF16 || d.in_format != TAC_IN_BITS) return false;
   if (d.Cin % kChunk != 0 || d.Cout % kCoutTile != 0) return false;
   if (d.W != 64 && d.W != 32) return false;
@@ -939,9 +800,14 @@ bool mfma_supported(const tac_layer_desc_t& d) {
   return d.stride == 2 && (K == 1 || K == 2 || K == 4);     // LDS room of the stride-2 tiles
 }
 
-size_t mfma_weight_bytes(const tac_layer_desc_t& d) { return (size_t)d.Cout * d.Cin * 9 * 2; }
+bool mfma_supported(const tac_layer_desc_t& d) { return large_supported(d) || mfma_small_supported(d); }
+
+size_t mfma_weight_bytes(const tac_layer_desc_t& d) {
+  return large_supported(d) ? (size_t)d.Cout * d.Cin * 9 * 2 : mfma_small_weight_bytes(d);
+}
 
 hipError_t mfma_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s) {
+  if (!large_supported(d)) return mfma_small_prepare(d, w_oihw, w_prepared, s);
   const int total = d.Cout * d.Cin * 9 / 2;
   hipLaunchKernelGGL(mfma_prepare_kernel, dim3((total + 255) / 256), dim3(256), 0, s, w_oihw,
                      static_cast<uint32_t*>(w_prepared), d.Cin, d.Cout);
@@ -949,10 +815,12 @@ hipError_t mfma_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_
 }
 
 hipError_t mfma_launch(const LayerParams& p, hipStream_t s) {
+  if (p.Cin % kChunk != 0) return mfma_small_launch(p, s);       // the short-contraction kernel
   MfmaParams mp;
   mp.spikes = p.spikes; mp.w = static_cast<const uint8_t*>(p.w); mp.bias = p.bias; mp.v_inout = p.v_inout;
   mp.out = p.out; mp.v_trace = p.v_trace;
-  mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.Ho = p.Ho; mp.Cout = p.Cout; mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif;
+  mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.W = p.W; mp.Ho = p.Ho; mp.Wo = p.Wo; mp.Cout = p.Cout; mp.stride = p.stride;
+  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif;
   mp.row_tiles = 0;
   mp.decay = p.decay; mp.theta = p.theta;
   for (int j = 0; j < TAC_MAX_K; ++j) {

@@ -36,7 +36,9 @@ def test_cfg2_two_layer_rate_coded(K, precision):
     w1, w2 = wl.make_weights(0), wl.make_weights(1)
     kw = dict(beta=wl.beta, theta=wl.theta, precision=precision, plain_stats=False)
     # layer 1: TAC with group size K, 28x28, 1 -> 32
-    p1, g1, r1 = check_layer(s, w1, K=K, mode=api.TAC_COLLAPSE, expect_kernel=api.TAC_KERNEL_DIRECT, **kw)
+    # bf16: the short-contraction MFMA kernel; fp32: the vector-FMA kernel
+    first = api.TAC_KERNEL_MFMA if precision == api.TAC_BF16 else api.TAC_KERNEL_DIRECT
+    p1, g1, r1 = check_layer(s, w1, K=K, mode=api.TAC_COLLAPSE, expect_kernel=first, **kw)
     assert r1[0].shape == (wl.T // K, B, 32, 28, 28) and r1[0].sum() > 0
     # layer 2 on the collapsed sequence: 2x2 mean pool while loading, 32 -> 64 at 14x14, K2 = 1
     p2, g2, r2 = check_layer(r1[0], w2, K=1, mode=api.TAC_COLLAPSE, pool2=True, **kw)
@@ -59,7 +61,8 @@ def test_cfg3_event_camera_layer(mode, K):
     s = wl.make_spikes(B=4)
     assert 0.02 < s.mean() < 0.05                      # sparse background plus the moving patch
     w = wl.make_weights(0)
-    par, g, r = check_layer(s, w, K=K, mode=mode, stride=2, beta=wl.beta, theta=wl.theta, precision=api.TAC_BF16)
+    par, g, r = check_layer(s, w, K=K, mode=mode, stride=2, beta=wl.beta, theta=wl.theta, precision=api.TAC_BF16,
+                            expect_kernel=api.TAC_KERNEL_MFMA)
     assert g["spikes"].shape[-2:] == (64, 64) and r[0].sum() > 0
     print("cfg3", api.MODE_NAMES[mode], K, par, "| vs unrounded oracle:", par.plain)
 

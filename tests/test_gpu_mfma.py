@@ -111,3 +111,50 @@ def test_stride_2_large_K_takes_the_direct_kernel():
     d = api.make_desc(16, 1, 16, 16, 64, 128, K=4, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, stride=2,
                       precision=api.TAC_BF16)
     assert api.tac_select_kernel(d) == api.TAC_KERNEL_MFMA
+
+
+# ---- the short-contraction member of the family (Cin = 1 or 2: first layers)
+# (Cin, Cout, H, W, stride): ragged rows and widths, one and two 32-channel blocks, partial blocks
+SMALL_SHAPES = [(1, 8, 28, 28, 1), (1, 32, 13, 28, 1), (2, 64, 22, 128, 2), (2, 40, 9, 64, 1), (1, 64, 11, 50, 2),
+                (2, 24, 7, 33, 1), (2, 64, 6, 127, 2)]
+SMALL_MODES = [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 2), (api.TAC_PRESERVE, 4), (api.TAC_COLLAPSE, 3)]
+
+
+@pytest.mark.parametrize("shape", SMALL_SHAPES)
+@pytest.mark.parametrize("mode,K", SMALL_MODES)
+def test_short_contraction_kernel(shape, mode, K):
+    Cin, Cout, H, W, stride = shape
+    r = _rng(2000 + Cin + Cout + H + W + stride + K)
+    s = (r.random((12, 2, Cin, H, W)) < 0.3).astype(np.uint8)
+    w = synth.kaiming_normal(31, Cout, Cin)
+    bias = (r.standard_normal(Cout) * 0.1).astype(np.float32)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    v0 = (r.standard_normal((2, Cout, Ho, Wo)) * 0.3).astype(np.float32)
+    par, g, ref = check_layer(s, w, K=K, beta=0.9, theta=1.0, mode=mode, stride=stride, precision=api.TAC_BF16,
+                              bias=bias, v0=v0, expect_kernel=api.TAC_KERNEL_MFMA)
+    assert ref[0].sum() > 0
+    print("short contraction", shape, api.MODE_NAMES[mode], K, par)
+
+
+def test_short_contraction_limits():
+    mk = lambda **kw: api.make_desc(8, 1, kw.pop("Cin", 2), 16, kw.pop("W", 128), kw.pop("Cout", 64), K=kw.pop("K", 2), beta=0.9,
+                                    theta=1.0, mode=api.TAC_COLLAPSE, stride=kw.pop("stride", 2), precision=api.TAC_BF16)
+    assert api.tac_select_kernel(mk()) == api.TAC_KERNEL_MFMA
+    assert api.tac_select_kernel(mk(stride=1)) == api.TAC_KERNEL_DIRECT          # 128 output pixels per row
+    assert api.tac_select_kernel(mk(Cout=96)) == api.TAC_KERNEL_DIRECT           # more than two channel blocks
+    assert api.tac_select_kernel(mk(Cin=3)) == api.TAC_KERNEL_DIRECT
+    assert api.tac_select_kernel(mk(W=160, stride=2)) == api.TAC_KERNEL_DIRECT
+
+
+def test_short_contraction_state_carry_and_no_trace():
+    r = _rng(77)
+    s = (r.random((8, 1, 2, 12, 96)) < 0.2).astype(np.uint8)
+    w = synth.kaiming_normal(32, 48, 2)
+    kw = dict(beta=0.5, theta=1.0, stride=2, precision=api.TAC_BF16)
+    whole = run_gpu(s, w, K=2, mode=api.TAC_PRESERVE, **kw)
+    plain = run_gpu(s, w, K=2, mode=api.TAC_PRESERVE, trace=False, **kw)
+    assert whole["kernel"] == api.TAC_KERNEL_MFMA and np.array_equal(whole["packed"], plain["packed"])
+    a = run_gpu(s[:4], w, K=2, mode=api.TAC_PRESERVE, **kw)
+    b = run_gpu(s[4:], w, K=2, mode=api.TAC_PRESERVE, v0=a["v_final"], **kw)
+    assert np.array_equal(np.concatenate([a["packed"], b["packed"]]), whole["packed"])
+    assert np.array_equal(b["v_final"], whole["v_final"])
