@@ -50,7 +50,8 @@ __global__ __launch_bounds__(kThreads) void direct_kernel(const LayerParams p, c
   const bool valid = q < nq && ox < p.Wo;
   if (!valid) { oy = oy0; ox = 0; }                  // keeps LDS reads in range; results masked
 
-  const float* __restrict__ wgt = static_cast<const float*>(p.w);
+  const float* __restrict__ wgt = static_cast<const float*>(p.w);   // [Cin][9][Cout padded to 32]
+  const int cout_pad = (p.Cout + 31) & ~31;
   const size_t plane = (size_t)p.Ho * p.Wo;
   const size_t out_slab = (size_t)p.B * p.Cout * plane;   // elements per output step
 
@@ -115,11 +116,10 @@ __global__ __launch_bounds__(kThreads) void direct_kernel(const LayerParams p, c
 #pragma unroll
           for (int kx = 0; kx < 3; ++kx) {
             const float a = at[ky * Wp + kx];
+            // the CB weights of this (cin, tap) are consecutive: a few wide scalar loads
+            const float* wt = wgt + ((size_t)(c0 + ci) * 9 + ky * 3 + kx) * cout_pad + co0;
 #pragma unroll
-            for (int c = 0; c < CB; ++c) {
-              const int co = min(co0 + c, p.Cout - 1);
-              acc[c] = fmaf(wgt[((size_t)co * p.Cin + (c0 + ci)) * 9 + ky * 3 + kx], a, acc[c]);
-            }
+            for (int c = 0; c < CB; ++c) acc[c] = fmaf(wt[c], a, acc[c]);
           }
       }
     }
@@ -151,20 +151,29 @@ __global__ __launch_bounds__(kThreads) void direct_kernel(const LayerParams p, c
   }
 }
 
-__global__ void direct_prepare_kernel(const float* __restrict__ w, float* __restrict__ out, int n, int bf16) {
+// OIHW -> [Cin][tap][Cout padded to a multiple of 32] (zeros in the padding), so that the weights
+// of consecutive output channels for one (cin, tap) are consecutive; values rounded to bf16 when
+// the layer asks for that precision.
+__global__ void direct_prepare_kernel(const float* __restrict__ w, float* __restrict__ out, int Cin, int Cout,
+                                      int cout_pad, int bf16) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) out[i] = bf16 ? round_bf16(w[i]) : w[i];
+  if (i >= Cin * 9 * cout_pad) return;
+  const int co = i % cout_pad;
+  const int ct = i / cout_pad;                 // cin * 9 + tap
+  const int ci = ct / 9, tap = ct - ci * 9;
+  float v = co < Cout ? w[((size_t)co * Cin + ci) * 9 + tap] : 0.f;
+  out[i] = bf16 ? round_bf16(v) : v;
 }
 
 }  // namespace
 
-size_t direct_weight_bytes(const tac_layer_desc_t& d) { return (size_t)d.Cout * d.Cin * 9 * sizeof(float); }
+size_t direct_weight_bytes(const tac_layer_desc_t& d) { return (size_t)d.Cin * 9 * ((d.Cout + 31) & ~31) * sizeof(float); }
 
 hipError_t direct_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s) {
-  // same [Cout][Cin][3][3] order; values rounded to bf16 when the layer asks for that precision
-  const int n = d.Cout * d.Cin * 9;
+  const int cout_pad = (d.Cout + 31) & ~31;
+  const int n = d.Cin * 9 * cout_pad;
   hipLaunchKernelGGL(direct_prepare_kernel, dim3((n + 255) / 256), dim3(256), 0, s, w_oihw,
-                     static_cast<float*>(w_prepared), n, d.precision == TAC_BF16 ? 1 : 0);
+                     static_cast<float*>(w_prepared), d.Cin, d.Cout, cout_pad, d.precision == TAC_BF16 ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -113,7 +113,7 @@ def test_kernel_selection():
     assert api.lib().tac_select_kernel(ctypes.byref(d)) == api.TAC_ERR_UNSUPPORTED
     d = _desc(precision=api.TAC_BF16, kernel=api.TAC_KERNEL_DIRECT)
     assert api.tac_select_kernel(d) == api.TAC_KERNEL_DIRECT
-    assert api.tac_prepared_weight_bytes(d) == 8 * 3 * 9 * 4
+    assert api.tac_prepared_weight_bytes(d) == 3 * 9 * 32 * 4        # [Cin][tap][Cout padded to 32] fp32
 
 
 def test_status_strings():
