@@ -35,15 +35,15 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3       # MI355X fp32 vector
-CPU_SAMPLES = 24               # samples of the batch the CPU oracle is timed on (10-30 s of CPU work on cfg5)
+CPU_SAMPLES = 40               # samples of the batch the CPU oracle is timed on (10-30 s of CPU work on cfg5)
 
 # HBM traffic of one launch of the headline kernel (cfg5, TAC, K = 4), from two rocprofv3 --pmc
 # runs (FETCH_SIZE, then WRITE_SIZE; summary and scale factors under profiles/).  The figures
 # belong to one version of the kernel source: they are reported only while its hash matches.
 TRAFFIC = {
-    "kernel_source_sha256": "692f46ea66b9ed5617782c2054091a38da265c8296a62f30528985870f065298",
+    "kernel_source_sha256": "abb2a6e0a658b7be743f789564e0ce0765ab2286924e0a332476b23ed519403c",
     "workload": ("cfg5", "TAC", 4),
-    "fetch_bytes": 538546506,
+    "fetch_bytes": 538545372,
     "write_bytes": 134217728,
 }
 
@@ -63,8 +63,8 @@ def measured_traffic(workload, mode, K):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=15)
     ap.add_argument("--workload", default="cfg5", choices=["cfg3", "cfg5"])
     ap.add_argument("--mode", default="TAC", choices=["per_step", "TAC", "TAC_TP"])
     ap.add_argument("--K", type=int, default=4)
