@@ -64,6 +64,10 @@ def _load():
         lib.oracle_decay_weights.restype = None
         lib.oracle_avgpool2.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int]
         lib.oracle_avgpool2.restype = None
+        lib.oracle_maxpool2.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int]
+        lib.oracle_maxpool2.restype = None
+        lib.oracle_fold_batchnorm.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_double, ctypes.c_int, ctypes.c_int, vp, vp]
+        lib.oracle_fold_batchnorm.restype = None
         lib.oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -101,6 +105,32 @@ def avgpool2(x: np.ndarray) -> np.ndarray:
     return out
 
 
+def maxpool2(x: np.ndarray) -> np.ndarray:
+    """2x2 max pool, stride 2, over the last two axes (Sec. 5.1: MaxPool(2) after each LIF layer)."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    H2, W2 = x.shape[-2:]
+    assert H2 % 2 == 0 and W2 % 2 == 0
+    out = np.zeros(x.shape[:-2] + (H2 // 2, W2 // 2), dtype=np.float64)
+    _load().oracle_maxpool2(_ptr(x), _ptr(out), int(np.prod(x.shape[:-2], dtype=np.int64)), H2 // 2, W2 // 2)
+    return out
+
+
+def fold_batchnorm(w, bias, gamma, beta_bn, mean, var, eps=1e-5):
+    """Inference batch norm after the convolution folded into (weights, bias) (Sec. 5.1:
+    Conv -> BN -> LIF).  Returns (w_folded [Cout,Cin,kh,kw], bias_folded [Cout]) in float64."""
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    Cout = w.shape[0]
+    arrs = [None if bias is None else np.ascontiguousarray(bias, dtype=np.float64)]
+    arrs += [np.ascontiguousarray(a, dtype=np.float64) for a in (gamma, beta_bn, mean, var)]
+    for a in arrs:
+        assert a is None or a.shape == (Cout,)
+    w_out = np.zeros_like(w)
+    b_out = np.zeros(Cout, dtype=np.float64)
+    _load().oracle_fold_batchnorm(_ptr(w), _ptr(arrs[0]), _ptr(arrs[1]), _ptr(arrs[2]), _ptr(arrs[3]), _ptr(arrs[4]),
+                                  float(eps), Cout, int(w.size // Cout), _ptr(w_out), _ptr(b_out))
+    return w_out, b_out
+
+
 def conv2d(x: np.ndarray, w: np.ndarray, bias=None, stride: int = 1, pad: int = 1, nthreads: int = 1) -> np.ndarray:
     """Zero-padded cross-correlation, x[B,Cin,H,W], w[Cout,Cin,kh,kw] -> [B,Cout,Ho,Wo] (float64)."""
     x = np.ascontiguousarray(x, dtype=np.float64)
@@ -130,7 +160,7 @@ def _desc(spikes, weight, K, beta, theta, stride, pad, pool2, round_a_bf16, nthr
     else:
         H, W = Hs, Ws
     d = _Desc(T=T, B=B, Cin=Cin, H=H, W=W, Cout=Cout, kh=kh, kw=kw, stride=stride, pad=pad, K=K,
-              pool2=int(bool(pool2)), round_a_bf16=int(bool(round_a_bf16)), nthreads=int(nthreads),
+              pool2=(2 if pool2 in (2, "max") else int(bool(pool2))), round_a_bf16=int(bool(round_a_bf16)), nthreads=int(nthreads),
               beta=float(beta), theta=float(theta))
     Ho = (H + 2 * pad - kh) // stride + 1
     Wo = (W + 2 * pad - kw) // stride + 1

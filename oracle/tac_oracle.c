@@ -49,7 +49,7 @@ typedef struct {
   int32_t Cout, kh, kw;        /* kernel W[Cout][Cin][kh][kw]                            */
   int32_t stride, pad;
   int32_t K;                   /* group size (ignored by the per-step routine)           */
-  int32_t pool2;               /* 1: S is [T][B][Cin][2H][2W]; a 2x2 mean pool precedes the layer */
+  int32_t pool2;               /* S is [T][B][Cin][2H][2W] and a 2x2 pool precedes the layer: 1 mean, 2 max */
   int32_t round_a_bf16;        /* 1: round every A_k element to bfloat16 (nearest even)  */
   int32_t nthreads;            /* OpenMP threads over the batch loop; <=1: serial        */
   double beta, theta;
@@ -94,6 +94,37 @@ void oracle_avgpool2(const double* X, double* P, int64_t N, int H, int W) {
       }
 }
 
+/* 2x2 max pool with stride 2 (the MaxPool(2) that follows every LIF layer of the event-data
+ * network, Sec. 5.1): X[N][2H][2W] -> P[N][H][W].  On 0/1 spikes the maximum is the logical OR. */
+void oracle_maxpool2(const double* X, double* P, int64_t N, int H, int W) {
+  for (int64_t n = 0; n < N; ++n)
+    for (int y = 0; y < H; ++y)
+      for (int x = 0; x < W; ++x) {
+        const double* r0 = X + (n * 2 * H + 2 * y) * (int64_t)(2 * W) + 2 * x;
+        const double* r1 = r0 + 2 * W;
+        double m = r0[0];
+        if (r0[1] > m) m = r0[1];
+        if (r1[0] > m) m = r1[0];
+        if (r1[1] > m) m = r1[1];
+        P[(n * H + y) * (int64_t)W + x] = m;
+      }
+}
+
+/* Inference-time batch normalisation after a convolution (Conv -> BN -> LIF, Sec. 5.1) folded
+ * into the convolution: BN(y)[co] = g[co] (y - mean[co]) / sqrt(var[co] + eps) + b[co] with
+ * y = bias[co] + W[co] * x  equals  bias'[co] + W'[co] * x  with
+ * W'[co] = W[co] g[co] / sqrt(var[co] + eps),  bias' = (bias - mean) g / sqrt(var + eps) + b.
+ * per = Cin * kh * kw weights per output channel; bias may be NULL (zeros). */
+void oracle_fold_batchnorm(const double* Wt, const double* bias, const double* g, const double* b,
+                           const double* mean, const double* var, double eps, int Cout, int per,
+                           double* W_out, double* bias_out) {
+  for (int co = 0; co < Cout; ++co) {
+    const double sc = g[co] / sqrt(var[co] + eps);
+    for (int i = 0; i < per; ++i) W_out[(int64_t)co * per + i] = Wt[(int64_t)co * per + i] * sc;
+    bias_out[co] = ((bias ? bias[co] : 0.0) - mean[co]) * sc + b[co];
+  }
+}
+
 /* Y[B][Cout][Ho][Wo] = bias + cross-correlation of X[B][Cin][H][W] with
  * Wt[Cout][Cin][kh][kw], zero padding `pad`, stride `stride`.  Seven loops. */
 void oracle_conv2d(const double* X, const double* Wt, const double* bias, double* Y,
@@ -123,13 +154,14 @@ void oracle_conv2d(const double* X, const double* Wt, const double* bias, double
         }
 }
 
-/* Input frame t as doubles X[B][Cin][H][W] (after the optional 2x2 mean pool). */
+/* Input frame t as doubles X[B][Cin][H][W] (after the optional 2x2 pool). */
 static void load_frame(const oracle_desc_t* d, const uint8_t* S, int t, double* X, double* tmp) {
   const int64_t n_in = (int64_t)d->B * d->Cin;
   if (d->pool2) {
     const int64_t fr = n_in * (2 * d->H) * (int64_t)(2 * d->W);
     for (int64_t i = 0; i < fr; ++i) tmp[i] = (double)S[(int64_t)t * fr + i];
-    oracle_avgpool2(tmp, X, n_in, d->H, d->W);
+    if (d->pool2 == 2) oracle_maxpool2(tmp, X, n_in, d->H, d->W);
+    else oracle_avgpool2(tmp, X, n_in, d->H, d->W);
   } else {
     const int64_t fr = n_in * d->H * (int64_t)d->W;
     for (int64_t i = 0; i < fr; ++i) X[i] = (double)S[(int64_t)t * fr + i];
@@ -276,6 +308,7 @@ static double input_at(const oracle_desc_t* d, const uint8_t* S, int t, int b, i
   if (d->pool2) {
     const int H2 = 2 * d->H, W2 = 2 * d->W;
     const uint8_t* p = S + ((((int64_t)t * d->B + b) * d->Cin + ci) * H2 + 2 * iy) * (int64_t)W2 + 2 * ix;
+    if (d->pool2 == 2) return (p[0] | p[1] | p[W2] | p[W2 + 1]) ? 1.0 : 0.0;
     return 0.25 * ((double)p[0] + (double)p[1] + (double)p[W2] + (double)p[W2 + 1]);
   }
   return (double)S[((((int64_t)t * d->B + b) * d->Cin + ci) * d->H + iy) * (int64_t)d->W + ix];

@@ -110,6 +110,55 @@ def test_avgpool_matches_library_routine():
     assert np.array_equal(oracle.avgpool2(x), ref)
 
 
+def test_maxpool_matches_library_routine_and_is_the_or_of_bits():
+    x = _rng(8).integers(0, 2, size=(3, 2, 8, 6)).astype(np.float64)
+    ref = torch.nn.functional.max_pool2d(torch.from_numpy(x), 2).numpy()
+    got = oracle.maxpool2(x)
+    assert np.array_equal(got, ref)
+    b = x.astype(np.uint8)
+    assert np.array_equal(got, (b[..., 0::2, 0::2] | b[..., 0::2, 1::2] | b[..., 1::2, 0::2] | b[..., 1::2, 1::2]))
+    # not the mean pool
+    assert not np.array_equal(got, oracle.avgpool2(x))
+
+
+def test_maxpool_on_load_equals_pooling_first():
+    # a layer fed "unpooled spikes + max pool" is the layer fed the pooled spikes
+    r = _rng(9)
+    s = r.integers(0, 2, size=(4, 2, 3, 8, 12)).astype(np.uint8)
+    w = r.standard_normal((4, 3, 3, 3)) * 0.5
+    pooled = oracle.maxpool2(s).astype(np.uint8)
+    for mode in (PER_STEP, TAC, TAC_TP):
+        a = oracle.conv_lif(s, w, K=2, beta=0.9, theta=1.0, mode=mode, pool2="max")
+        b = oracle.conv_lif(pooled, w, K=2, beta=0.9, theta=1.0, mode=mode)
+        assert all(np.array_equal(x, y) for x, y in zip(a, b)) and a[0].sum() > 0
+    Ho, Wo = a[2].shape[2:]
+    idx = np.array(list(itertools.product(range(2), range(4), range(Ho), range(Wo))), dtype=np.int32)
+    part = oracle.conv_lif_neurons(s, w, idx=idx, K=2, beta=0.9, theta=1.0, mode=TAC_TP, pool2="max")
+    assert np.array_equal(part[0], a[0].reshape(a[0].shape[0], -1))
+
+
+def test_batchnorm_fold_equals_batchnorm_after_conv():
+    # Conv -> BN (inference statistics) == conv with folded weights and bias, against the library's batch_norm
+    r = _rng(10)
+    x = r.standard_normal((2, 3, 6, 5))
+    w = r.standard_normal((4, 3, 3, 3)) * 0.3
+    bias = r.standard_normal(4) * 0.2
+    g, b = r.uniform(0.5, 1.5, 4), r.standard_normal(4) * 0.1
+    mean, var = r.standard_normal(4) * 0.3, r.uniform(0.2, 2.0, 4)
+    wf, bf = oracle.fold_batchnorm(w, bias, g, b, mean, var, eps=1e-5)
+    y = torch.from_numpy(oracle.conv2d(x, w, bias))
+    ref = torch.nn.functional.batch_norm(y, torch.from_numpy(mean), torch.from_numpy(var), torch.from_numpy(g),
+                                         torch.from_numpy(b), training=False, eps=1e-5).numpy()
+    assert np.abs(oracle.conv2d(x, wf, bf) - ref).max() < 1e-12
+    # identity statistics leave the layer unchanged; no bias is a zero bias
+    w1, b1 = oracle.fold_batchnorm(w, None, np.ones(4), np.zeros(4), np.zeros(4), np.ones(4), eps=0.0)
+    assert np.array_equal(w1, w) and np.array_equal(b1, np.zeros(4))
+    # a wrong sign of the mean, or var used without the square root, would show here
+    w2, b2 = oracle.fold_batchnorm(w, bias, g, b, mean, 4.0 * np.ones(4), eps=0.0)
+    assert np.allclose(w2, w * (g / 2.0)[:, None, None, None], rtol=0, atol=1e-15)
+    assert np.allclose(b2, (bias - mean) * g / 2.0 + b, rtol=0, atol=1e-15)
+
+
 # ------------------------------------------------------------------ recurrences
 
 def test_hand_worked_scalar_example():
@@ -222,6 +271,8 @@ def _brute(s, w, bias, v0, K, beta, theta, mode, stride, pad, pool2):
     def pix(t, b, ci, y, x):
         if not (0 <= y < H and 0 <= x < W):
             return F(0)
+        if pool2 == "max":
+            return F(int(s[t, b, ci, 2 * y:2 * y + 2, 2 * x:2 * x + 2].max()))
         if pool2:
             return F(int(s[t, b, ci, 2 * y:2 * y + 2, 2 * x:2 * x + 2].sum()), 4)
         return F(int(s[t, b, ci, y, x]))
@@ -254,9 +305,9 @@ def _brute(s, w, bias, v0, K, beta, theta, mode, stride, pad, pool2):
 
 
 @pytest.mark.parametrize("mode,K", [(PER_STEP, 1), (TAC, 2), (TAC, 4), (TAC_TP, 2), (TAC_TP, 4)])
-@pytest.mark.parametrize("stride,pool2", [(1, False), (2, False), (1, True)])
+@pytest.mark.parametrize("stride,pool2", [(1, False), (2, False), (1, True), (1, "max")])
 def test_exact_brute_force(mode, K, stride, pool2):
-    r = _rng(100 + 10 * K + stride + 5 * pool2)
+    r = _rng(100 + 10 * K + stride + 5 * bool(pool2))
     T, B, Cin, Cout, H, W = 4, 1, 2, 3, 5, 4
     shape = (T, B, Cin, 2 * H, 2 * W) if pool2 else (T, B, Cin, H, W)
     s = r.integers(0, 2, size=shape).astype(np.uint8)
