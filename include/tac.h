@@ -43,8 +43,11 @@ enum { TAC_PER_STEP = 0, TAC_COLLAPSE = 1 /* TAC */, TAC_PRESERVE = 2 /* TAC-TP 
 enum { TAC_FP32 = 0, TAC_BF16 = 1 };
 /* Input format.  TAC_IN_BITS_POOL2: `spikes_packed` holds the UNPOOLED frames
  * [T][B][Cin][2H][2W]; a 2x2 mean pool (stride 2) is applied while loading, so
- * the layer sees inputs in {0, 1/4, 1/2, 3/4, 1} of size H x W. */
-enum { TAC_IN_BITS = 0, TAC_IN_BITS_POOL2 = 1 };
+ * the layer sees inputs in {0, 1/4, 1/2, 3/4, 1} of size H x W (the Pool(2) between the two
+ * convolutions of the rate-coded network, Sec. 5.1).  TAC_IN_BITS_MAXPOOL2: the same buffer
+ * convention with a 2x2 max pool, i.e. the OR of the four bits (the MaxPool(2) that follows
+ * every LIF layer of the event-data network, Sec. 5.1): the layer sees bits again. */
+enum { TAC_IN_BITS = 0, TAC_IN_BITS_POOL2 = 1, TAC_IN_BITS_MAXPOOL2 = 2 };
 /* Kernel family.  AUTO picks MFMA when the shape qualifies (see
  * tac_select_kernel), else DIRECT.  Forcing MFMA on a shape it does not
  * support is TAC_ERR_UNSUPPORTED. */
@@ -68,13 +71,13 @@ enum {
 /* One conv-LIF layer.  Plain data; the caller fills every field. */
 typedef struct tac_layer_desc {
   int32_t T, B, Cin, H, W;   /* logical input S[T][B][Cin][H][W] (H, W after the pool when
-                                in_format = TAC_IN_BITS_POOL2)                            */
+                                in_format = TAC_IN_BITS_[MAX]POOL2)                            */
   int32_t Cout, kh, kw;      /* kernel W[Cout][Cin][kh][kw]; kh = kw = 3                  */
   int32_t stride, pad;       /* stride 1 or 2, pad 1 (zero padding)                       */
   int32_t K;                 /* group size; TAC_PER_STEP ignores it and uses 1            */
   int32_t mode;              /* TAC_PER_STEP / TAC_COLLAPSE / TAC_PRESERVE                */
   int32_t precision;         /* TAC_FP32 / TAC_BF16                                       */
-  int32_t in_format;         /* TAC_IN_BITS / TAC_IN_BITS_POOL2                           */
+  int32_t in_format;         /* TAC_IN_BITS / TAC_IN_BITS_POOL2 / TAC_IN_BITS_MAXPOOL2    */
   int32_t kernel;            /* TAC_KERNEL_AUTO / _DIRECT / _MFMA                         */
   float beta;                /* membrane decay, in [0, 1]                                 */
   float theta;               /* threshold V_th, > 0                                       */
@@ -112,7 +115,7 @@ int tac_prepare_weights(const tac_layer_desc_t* desc, const float* w_oihw, void*
  * subtractive reset of Alg. 1 (TAC), Alg. 2 (TAC-TP) or the per-step layer
  * (K = 1).  A_k and Y_k never leave the chip.
  *   spikes_packed      DEVICE, read-only, packed [T][B][Cin][H][ceil(W/32)]
- *                      (or [T][B][Cin][2H][ceil(2W/32)] with TAC_IN_BITS_POOL2)
+ *                      (or [T][B][Cin][2H][ceil(2W/32)] with TAC_IN_BITS_[MAX]POOL2)
  *   w_prepared         DEVICE, read-only, from tac_prepare_weights
  *   bias               DEVICE, read-only, float32 [Cout], or NULL for zero.  Added
  *                      once per convolution (so TAC-TP sees it in each of its K steps)
@@ -131,6 +134,20 @@ int tac_conv_lif(const tac_layer_desc_t* desc, const uint32_t* spikes_packed, co
 /* Dense 0/1 bytes <-> packed words, `rows` rows of W pixels each (rows = T*B*C*H).
  *   dense01  DEVICE uint8 [rows][W]; any non-zero byte packs as 1
  *   packed   DEVICE uint32 [rows][ceil(W/32)] */
+/* Inference-time batch normalisation after the convolution (the Conv -> BN -> LIF blocks of
+ * Sec. 5.1) folded into the layer's weights and bias:
+ *   w_out[co] = w[co] * gamma[co] / sqrt(var[co] + eps)
+ *   bias_out[co] = (bias[co] - mean[co]) * gamma[co] / sqrt(var[co] + eps) + beta_bn[co]
+ * so that tac_conv_lif on (w_out, bias_out) is Conv -> BN -> LIF.  All pointers DEVICE, fp32:
+ *   w_oihw [Cout][per_cout] (per_cout = Cin*kh*kw), read;  bias [Cout] or NULL (zeros), read;
+ *   gamma, beta_bn, mean, var [Cout], read;  w_out [Cout][per_cout], bias_out [Cout], written
+ *   (w_out may be w_oihw, bias_out may be bias: in place).  Enqueued on `stream`, no synchronisation.
+ * Errors: TAC_ERR_NULL, TAC_ERR_BAD_SHAPE (Cout or per_cout <= 0), TAC_ERR_BAD_PARAM (eps < 0 or
+ * not finite), TAC_ERR_HIP. */
+int tac_fold_batchnorm(const float* w_oihw, const float* bias, const float* gamma, const float* beta_bn,
+                       const float* mean, const float* var, float eps, int32_t Cout, int32_t per_cout,
+                       float* w_out, float* bias_out, void* stream);
+
 int tac_pack_spikes(const uint8_t* dense01, uint32_t* packed, int64_t rows, int32_t W, void* stream);
 int tac_unpack_spikes(const uint32_t* packed, uint8_t* dense01, int64_t rows, int32_t W, void* stream);
 

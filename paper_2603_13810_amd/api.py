@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libtac.so")
 
 TAC_PER_STEP, TAC_COLLAPSE, TAC_PRESERVE = 0, 1, 2
 TAC_FP32, TAC_BF16 = 0, 1
-TAC_IN_BITS, TAC_IN_BITS_POOL2 = 0, 1
+TAC_IN_BITS, TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2 = 0, 1, 2
 TAC_KERNEL_AUTO, TAC_KERNEL_DIRECT, TAC_KERNEL_MFMA = 0, 1, 2
 TAC_OK, TAC_ERR_NULL, TAC_ERR_BAD_SHAPE, TAC_ERR_BAD_K = 0, -1, -2, -3
 TAC_ERR_BAD_PARAM, TAC_ERR_UNSUPPORTED, TAC_ERR_HIP, TAC_ERR_ALIGN = -4, -5, -6, -7
@@ -24,7 +24,7 @@ TAC_MAX_K = 32
 MODE_NAMES = {TAC_PER_STEP: "per_step", TAC_COLLAPSE: "TAC", TAC_PRESERVE: "TAC_TP"}
 
 EXPORTS = ("tac_out_shape", "tac_packed_bytes", "tac_select_kernel", "tac_prepared_weight_bytes",
-           "tac_prepare_weights", "tac_conv_lif", "tac_pack_spikes", "tac_unpack_spikes",
+           "tac_prepare_weights", "tac_conv_lif", "tac_pack_spikes", "tac_unpack_spikes", "tac_fold_batchnorm",
            "tac_get_counters", "tac_reset_counters", "tac_status_string", "tac_last_error")
 
 
@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.tac_pack_spikes.restype = ctypes.c_int
         L.tac_unpack_spikes.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp]
         L.tac_unpack_spikes.restype = ctypes.c_int
+        L.tac_fold_batchnorm.argtypes = [vp] * 6 + [ctypes.c_float, ctypes.c_int32, ctypes.c_int32, vp, vp, vp]
+        L.tac_fold_batchnorm.restype = ctypes.c_int
         u64p = ctypes.POINTER(ctypes.c_uint64)
         L.tac_get_counters.argtypes = [u64p, u64p]
         L.tac_get_counters.restype = ctypes.c_int
@@ -167,7 +169,7 @@ def tac_conv_lif(desc, spikes_packed, w_prepared, bias=None, v_inout=None, out_s
     (int32 tensor [T_out,B,Cout,Ho,ceil(Wo/32)], allocated if not given)."""
     import torch
     T_out, Ho, Wo = tac_out_shape(desc)
-    f = 2 if desc.in_format == TAC_IN_BITS_POOL2 else 1
+    f = 1 if desc.in_format == TAC_IN_BITS else 2
     need_in = tac_packed_bytes(desc.T, desc.B, desc.Cin, desc.H * f, desc.W * f)
     if spikes_packed.numel() * spikes_packed.element_size() != need_in:
         raise ValueError("spikes_packed has %d bytes, the description needs %d" %
@@ -221,6 +223,28 @@ def tac_unpack_spikes(packed, W, dense01=None, stream=None):
     _check(lib().tac_unpack_spikes(_dev_ptr(packed, None, "packed"), _dev_ptr(dense01, torch.uint8, "dense01"),
                                    rows, W, _stream(stream)))
     return dense01
+
+
+def tac_fold_batchnorm(w_oihw, bias, gamma, beta_bn, mean, var, eps=1e-5, stream=None):
+    """Folds an inference batch norm that follows the convolution into (weights, bias).
+    Device fp32 tensors: w_oihw [Cout,Cin,kh,kw], bias [Cout] or None, gamma/beta_bn/mean/var [Cout].
+    Returns new device tensors (w_folded, bias_folded)."""
+    import torch
+    Cout = w_oihw.shape[0]
+    for t in (gamma, beta_bn, mean, var):
+        if tuple(t.shape) != (Cout,):
+            raise ValueError("batch-norm vectors must be [Cout]")
+    if bias is not None and tuple(bias.shape) != (Cout,):
+        raise ValueError("bias must be [Cout]")
+    w_out = torch.empty_like(w_oihw)
+    b_out = torch.empty((Cout,), dtype=torch.float32, device=w_oihw.device)
+    f32 = torch.float32
+    _check(lib().tac_fold_batchnorm(_dev_ptr(w_oihw, f32, "w_oihw"), _dev_ptr(bias, f32, "bias"),
+                                    _dev_ptr(gamma, f32, "gamma"), _dev_ptr(beta_bn, f32, "beta_bn"),
+                                    _dev_ptr(mean, f32, "mean"), _dev_ptr(var, f32, "var"), float(eps), Cout,
+                                    w_oihw.numel() // Cout, _dev_ptr(w_out, f32, "w_out"), _dev_ptr(b_out, f32, "bias_out"),
+                                    _stream(stream)))
+    return w_out, b_out
 
 
 def tac_get_counters() -> Tuple[int, int]:

@@ -27,7 +27,8 @@ int validate(const tac_layer_desc_t* d) {
   if (d->stride != 1 && d->stride != 2) return TAC_ERR_BAD_SHAPE;
   if (d->mode != TAC_PER_STEP && d->mode != TAC_COLLAPSE && d->mode != TAC_PRESERVE) return TAC_ERR_BAD_PARAM;
   if (d->precision != TAC_FP32 && d->precision != TAC_BF16) return TAC_ERR_BAD_PARAM;
-  if (d->in_format != TAC_IN_BITS && d->in_format != TAC_IN_BITS_POOL2) return TAC_ERR_BAD_PARAM;
+  if (d->in_format != TAC_IN_BITS && d->in_format != TAC_IN_BITS_POOL2 && d->in_format != TAC_IN_BITS_MAXPOOL2)
+    return TAC_ERR_BAD_PARAM;
   if (d->kernel != TAC_KERNEL_AUTO && d->kernel != TAC_KERNEL_DIRECT && d->kernel != TAC_KERNEL_MFMA)
     return TAC_ERR_BAD_PARAM;
   if (!(d->beta >= 0.0f && d->beta <= 1.0f)) return TAC_ERR_BAD_PARAM;
@@ -39,7 +40,7 @@ int validate(const tac_layer_desc_t* d) {
   // 64-bit offsets across slabs; keep each slab below 2^31 elements
   const int Ho = (d->H + 2 - 3) / d->stride + 1, Wo = (d->W + 2 - 3) / d->stride + 1;
   const int64_t out_slab = (int64_t)d->B * d->Cout * Ho * Wo;
-  const int f = d->in_format == TAC_IN_BITS_POOL2 ? 2 : 1;
+  const int f = d->in_format == TAC_IN_BITS ? 1 : 2;
   const int64_t in_slab = (int64_t)d->B * d->Cin * (d->H * f) * ((d->W * f + 31) / 32);
   if (out_slab >= (1LL << 31) || in_slab >= (1LL << 31)) return TAC_ERR_BAD_SHAPE;
   if (d->B > 65535) return TAC_ERR_BAD_SHAPE;
@@ -118,7 +119,7 @@ int tac_conv_lif(const tac_layer_desc_t* desc, const uint32_t* spikes_packed, co
   p.Cout = desc->Cout; p.stride = desc->stride;
   p.Ho = (desc->H + 2 - 3) / desc->stride + 1;
   p.Wo = (desc->W + 2 - 3) / desc->stride + 1;
-  p.pool2 = desc->in_format == TAC_IN_BITS_POOL2;
+  p.pool2 = desc->in_format == TAC_IN_BITS_POOL2 ? 1 : (desc->in_format == TAC_IN_BITS_MAXPOOL2 ? 2 : 0);
   p.Hs = p.pool2 ? 2 * desc->H : desc->H;
   p.Wwi = ((p.pool2 ? 2 * desc->W : desc->W) + 31) / 32;
   p.Wwo = (p.Wo + 31) / 32;
@@ -155,6 +156,17 @@ int tac_unpack_spikes(const uint32_t* packed, uint8_t* dense01, int64_t rows, in
   if ((uintptr_t)packed & 3u) return TAC_ERR_ALIGN;
   hipError_t e = tac::unpack_launch(packed, dense01, rows, W, (hipStream_t)stream);
   return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_unpack_spikes");
+}
+
+int tac_fold_batchnorm(const float* w_oihw, const float* bias, const float* gamma, const float* beta_bn,
+                       const float* mean, const float* var, float eps, int32_t Cout, int32_t per_cout,
+                       float* w_out, float* bias_out, void* stream) {
+  if (!w_oihw || !gamma || !beta_bn || !mean || !var || !w_out || !bias_out) return TAC_ERR_NULL;
+  if (Cout < 1 || per_cout < 1) return TAC_ERR_BAD_SHAPE;
+  if (!(eps >= 0.0f) || !std::isfinite(eps)) return TAC_ERR_BAD_PARAM;
+  hipError_t e = tac::fold_bn_launch(w_oihw, bias, gamma, beta_bn, mean, var, eps, Cout, per_cout, w_out, bias_out,
+                                     (hipStream_t)stream);
+  return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_fold_batchnorm");
 }
 
 int tac_get_counters(uint64_t* conv_stages, uint64_t* lif_steps) {

@@ -6,8 +6,8 @@
 // (Alg. 1 / Alg. 2 loop body):
 //   1. loader:  the haloed input rows of a chunk of input channels are read as packed
 //               words and the decay-weighted aggregate A_k (Eq. 2) is formed as floats
-//               directly in LDS (never in HBM); with the 2x2 mean pool the four bits of
-//               a block are counted first;
+//               directly in LDS (never in HBM); with a 2x2 pool on load the four bits of
+//               a block are counted (mean) or OR-ed (max) first;
 //   2. conv:    every lane accumulates Y_k for its pixel and CB channels from LDS, the
 //               kernel taps arriving as wave-uniform scalars;
 //   3. LIF:     V <- decay V + Y_k, spike iff V >= theta, subtractive reset; once for TAC
@@ -99,8 +99,12 @@ __global__ __launch_bounds__(kThreads) void direct_kernel(const LayerParams p, c
             const size_t off = (size_t)(2 * iy) * p.Wwi + (xs >> 5);
             for (int j = 0; j < p.K; ++j) {
               const uint32_t w0 = src[j * t_stride + off], w1 = src[j * t_stride + off + p.Wwi];
-              const int cnt = __popc((w0 >> (xs & 31)) & 3u) + __popc((w1 >> (xs & 31)) & 3u);
-              a += (0.25f * (float)cnt) * p.wj[j];
+              if (p.pool2 == 2) {                     // max pool of bits = OR
+                a += (((w0 | w1) >> (xs & 31)) & 3u) ? p.wj[j] : 0.0f;
+              } else {
+                const int cnt = __popc((w0 >> (xs & 31)) & 3u) + __popc((w1 >> (xs & 31)) & 3u);
+                a += (0.25f * (float)cnt) * p.wj[j];
+              }
             }
           }
           if (p.bf16) a = round_bf16(a);

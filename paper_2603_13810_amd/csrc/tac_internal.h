@@ -22,7 +22,7 @@ struct LayerParams {
   int K;                    // frames per group (1 for per-step)
   int G;                    // groups = T / K = convolution stages
   int n_lif;                // LIF steps per group: K for TAC-TP, else 1
-  int pool2;                // input needs the 2x2 mean pool
+  int pool2;                // input is unpooled: 1 = 2x2 mean pool while loading, 2 = 2x2 max pool
   int bf16;                 // round A_k to bf16
   float decay;              // membrane decay per LIF step: beta^K for TAC, else beta
   float theta;
@@ -46,6 +46,8 @@ hipError_t mfma_small_prepare(const tac_layer_desc_t& d, const float* w_oihw, vo
 hipError_t mfma_small_launch(const LayerParams& p, hipStream_t s);
 
 hipError_t pack_launch(const uint8_t* dense, uint32_t* packed, int64_t rows, int W, hipStream_t s);
+hipError_t fold_bn_launch(const float* w, const float* bias, const float* gamma, const float* beta_bn, const float* mean,
+                          const float* var, float eps, int Cout, int per, float* w_out, float* bias_out, hipStream_t s);
 hipError_t unpack_launch(const uint32_t* packed, uint8_t* dense, int64_t rows, int W, hipStream_t s);
 
 }  // namespace tac

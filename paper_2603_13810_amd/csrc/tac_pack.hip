@@ -55,4 +55,24 @@ hipError_t unpack_launch(const uint32_t* packed, uint8_t* dense, int64_t rows, i
   return hipGetLastError();
 }
 
+// Batch norm (inference statistics) folded into weights and bias: one workgroup per output
+// channel; the scale is formed in double from the fp32 statistics and rounded once.
+__global__ void fold_bn_kernel(const float* __restrict__ w, const float* __restrict__ bias, const float* __restrict__ gamma,
+                               const float* __restrict__ beta_bn, const float* __restrict__ mean,
+                               const float* __restrict__ var, float eps, int per, float* w_out, float* bias_out) {
+  const int co = blockIdx.x;
+  const double sc = (double)gamma[co] / sqrt((double)var[co] + (double)eps);
+  for (int i = threadIdx.x; i < per; i += blockDim.x)
+    w_out[(size_t)co * per + i] = (float)((double)w[(size_t)co * per + i] * sc);
+  if (threadIdx.x == 0)
+    bias_out[co] = (float)((((bias ? (double)bias[co] : 0.0) - (double)mean[co]) * sc) + (double)beta_bn[co]);
+}
+
+hipError_t fold_bn_launch(const float* w, const float* bias, const float* gamma, const float* beta_bn, const float* mean,
+                          const float* var, float eps, int Cout, int per, float* w_out, float* bias_out, hipStream_t s) {
+  hipLaunchKernelGGL(fold_bn_kernel, dim3(Cout), dim3(256), 0, s, w, bias, gamma, beta_bn, mean, var, eps, per, w_out,
+                     bias_out);
+  return hipGetLastError();
+}
+
 }  // namespace tac

@@ -24,7 +24,7 @@ def run_gpu(spikes, w32, *, K, beta, theta, mode, stride=1, bias=None, v0=None, 
     Cout = w32.shape[0]
     desc = api.make_desc(T, B, Cin, H, W, Cout, K=K, beta=beta, theta=theta, mode=mode, stride=stride,
                          precision=precision, kernel=kernel,
-                         in_format=api.TAC_IN_BITS_POOL2 if pool2 else api.TAC_IN_BITS)
+                         in_format=(api.TAC_IN_BITS_MAXPOOL2 if pool2 == "max" else api.TAC_IN_BITS_POOL2) if pool2 else api.TAC_IN_BITS)
     T_out, Ho, Wo = api.tac_out_shape(desc)
     sp = torch.from_numpy(np_pack(spikes)).to(dev)
     wp = api.tac_prepare_weights(desc, torch.from_numpy(np.ascontiguousarray(w32, dtype=np.float32)).to(dev))

@@ -147,3 +147,41 @@ def test_conv_call_counts_five_layers():
             x = api.tac_conv_lif(d, x, wp)
         torch.cuda.synchronize()
         assert api.tac_get_counters() == (expect, 80)
+
+
+@pytest.mark.parametrize("mode,K", [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 2), (api.TAC_PRESERVE, 4)])
+@pytest.mark.parametrize("precision", [api.TAC_FP32, api.TAC_BF16])
+def test_max_pool_on_load(mode, K, precision):
+    # the previous layer's spikes arrive unpooled; MaxPool(2) = OR of the 2x2 bits while loading
+    r = np.random.Generator(np.random.PCG64(31 + K))
+    s = (r.random((8, 2, 6, 2 * 9, 2 * 20)) < 0.15).astype(np.uint8)
+    w = synth.kaiming_normal(41, 16, 6)
+    par, g, ref = check_layer(s, w, K=K, beta=0.9, theta=1.0, mode=mode, pool2="max", precision=precision,
+                              kernel=api.TAC_KERNEL_DIRECT)
+    assert ref[0].sum() > 0 and g["spikes"].shape[-2:] == (9, 20)
+    # and it is not the mean pool
+    gm = run_gpu(s, w, K=K, beta=0.9, theta=1.0, mode=mode, pool2=True, precision=precision, kernel=api.TAC_KERNEL_DIRECT)
+    assert (gm["spikes"] != g["spikes"]).any()
+
+
+def test_fold_batchnorm_on_device():
+    import oracle
+    r = np.random.Generator(np.random.PCG64(51))
+    w = (r.standard_normal((24, 5, 3, 3)) * 0.3).astype(np.float32)
+    bias = (r.standard_normal(24) * 0.2).astype(np.float32)
+    g, b = r.uniform(0.5, 1.5, 24).astype(np.float32), (r.standard_normal(24) * 0.1).astype(np.float32)
+    mean, var = (r.standard_normal(24) * 0.3).astype(np.float32), r.uniform(0.2, 2.0, 24).astype(np.float32)
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(a).to(dev)
+    for bb in (bias, None):
+        wf, bf = api.tac_fold_batchnorm(t(w), None if bb is None else t(bb), t(g), t(b), t(mean), t(var), eps=1e-5)
+        rw, rb = oracle.fold_batchnorm(w, bb, g, b, mean, var, eps=float(np.float32(1e-5)))
+        assert np.abs(wf.cpu().numpy() - rw).max() <= 1e-7 * np.abs(rw).max() + 1e-12
+        assert np.abs(bf.cpu().numpy() - rb).max() <= 1e-6
+    # folded layer = BN after the convolution, checked on the membrane trace of a spiking layer
+    s = (r.random((4, 1, 5, 8, 32)) < 0.3).astype(np.uint8)
+    wf, bf = api.tac_fold_batchnorm(t(w), t(bias), t(g), t(b), t(mean), t(var), eps=1e-5)
+    rw, rb = oracle.fold_batchnorm(w, bias, g, b, mean, var, eps=float(np.float32(1e-5)))
+    gpu = run_gpu(s, wf.cpu().numpy(), K=2, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, bias=bf.cpu().numpy())
+    ref = oracle.conv_lif(s, rw, rb, K=2, beta=0.9, theta=1.0, mode=oracle.TAC)
+    assert np.abs(gpu["v_trace"] - ref[1]).max() < 1e-4
