@@ -126,7 +126,8 @@ int tac_prepare_weights(const tac_layer_desc_t* desc, const float* w_oihw, void*
  *   out_spikes_packed  DEVICE, written, packed [T_out][B][Cout][Ho][ceil(Wo/32)]
  *   v_trace            DEVICE, optional debug output, float32 [T_out][B][Cout][Ho][Wo]:
  *                      membrane BEFORE the reset at every LIF step; NULL in timed runs
- * Buffers must not overlap.  All pointers need 4-byte alignment. */
+ * Buffers must not overlap.  All pointers need 4-byte alignment (spikes_packed 8-byte with
+ * TAC_IN_BITS_MAXPOOL2 on the MFMA kernel; w_prepared 16-byte), else TAC_ERR_ALIGN. */
 int tac_conv_lif(const tac_layer_desc_t* desc, const uint32_t* spikes_packed, const void* w_prepared,
                  const float* bias, float* v_inout, uint32_t* out_spikes_packed, float* v_trace,
                  void* stream);

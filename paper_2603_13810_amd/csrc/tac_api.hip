@@ -110,6 +110,9 @@ int tac_conv_lif(const tac_layer_desc_t* desc, const uint32_t* spikes_packed, co
     return TAC_ERR_ALIGN;
   const int kern = select_kernel(desc);
   if (kern < 0) return kern;
+  // the MFMA kernel reads the unpooled rows two words at a time
+  if (kern == TAC_KERNEL_MFMA && desc->in_format == TAC_IN_BITS_MAXPOOL2 && ((uintptr_t)spikes_packed & 7u))
+    return TAC_ERR_ALIGN;
 
   tac::LayerParams p;
   std::memset(&p, 0, sizeof(p));

@@ -123,7 +123,7 @@ struct StagePlan {
   uint32_t keep;         // bit l set: the input row is inside the image; clear: store zero words (padding row)
 };
 
-template <class G, int NG>
+template <class G, int NG, bool MP>
 __device__ __forceinline__ void stage_plan(StagePlan<NG>& sp, const MfmaParams& p, int K, int tid, int iy0) {
   sp.keep = 0;
 #pragma unroll
@@ -138,7 +138,10 @@ __device__ __forceinline__ void stage_plan(StagePlan<NG>& sp, const MfmaParams& 
       const int iy = iy0 + row;
       const int iyc = min(max(iy, 0), p.H - 1);
       sp.lofs[l] = (uint32_t)((rw * K * kChunk + cin) * 4);
-      sp.goff[l] = (uint32_t)((cin * p.H + iyc) * G::kWW + word);
+      // max pool on load: the stored image has twice the rows and words; the group starts at its
+      // upper left word
+      sp.goff[l] = MP ? (uint32_t)((cin * 2 * p.H + 2 * iyc) * (2 * G::kWW) + 2 * word)
+                      : (uint32_t)((cin * p.H + iyc) * G::kWW + word);
       if (iy == iyc) sp.keep |= 1u << l;
     }
   }
@@ -147,16 +150,39 @@ __device__ __forceinline__ void stage_plan(StagePlan<NG>& sp, const MfmaParams& 
 // Unconditional loads (no lane masking, no register initialisation in front of them).  `base`
 // is the wave-uniform address of (first frame of the group of frames, sample, first channel of
 // the chunk), fstride the distance between frames in dwords.  Loads f0 <= l * KM + j < f1 only.
-template <int KM, int NG>
-__device__ __forceinline__ void stage_load(uint32_t (&wd)[NG][KM], const StagePlan<NG>& sp, const uint32_t* base,
-                                           uint32_t fstride, int K, int f0 = 0, int f1 = NG * KM) {
+template <int KM, int NG, bool MP, int WW>
+__device__ __forceinline__ void stage_load(uint32_t (&wd)[NG][KM * (MP ? 4 : 1)], const StagePlan<NG>& sp,
+                                           const uint32_t* base, uint32_t fstride, int K, int f0 = 0, int f1 = NG * KM) {
 #pragma unroll
   for (int l = 0; l < NG; ++l)
 #pragma unroll
     for (int j = 0; j < KM; ++j) {
       const int f = l * KM + j;
-      if (f >= f0 && f < f1 && j < K) wd[l][j] = (base + (size_t)j * fstride)[sp.goff[l]];
+      if (f >= f0 && f < f1 && j < K) {
+        const uint32_t* src = base + (size_t)j * fstride + sp.goff[l];
+        if constexpr (MP) {
+          // the 2 x 2 words (two stored rows, 64 stored pixels) behind one word of pooled pixels
+          const u32x2 r0 = *reinterpret_cast<const u32x2*>(src);
+          const u32x2 r1 = *reinterpret_cast<const u32x2*>(src + 2 * WW);
+          wd[l][4 * j + 0] = r0[0];
+          wd[l][4 * j + 1] = r0[1];
+          wd[l][4 * j + 2] = r1[0];
+          wd[l][4 * j + 3] = r1[1];
+        } else {
+          wd[l][j] = *src;
+        }
+      }
     }
+}
+
+// 2 x 2 max pool of bits: OR of the two rows, OR of horizontal neighbours, even bits gathered
+// into the low half; 64 stored pixels (a, b = the OR-ed rows' two words) -> 32 pooled pixels.
+__device__ __forceinline__ uint32_t pool_pairs(uint32_t v) {
+  v = (v | (v >> 1)) & 0x55555555u;
+  v = (v | (v >> 1)) & 0x33333333u;
+  v = (v | (v >> 2)) & 0x0f0f0f0fu;
+  v = (v | (v >> 4)) & 0x00ff00ffu;
+  return (v | (v >> 8)) & 0x0000ffffu;
 }
 
 // (a & m) | (b & ~m): one v_bfi_b32
@@ -181,9 +207,9 @@ __device__ __forceinline__ void frames_to_fields(uint32_t* w) {
   }
 }
 
-template <int KT, int KM, int NG>
-__device__ __forceinline__ void stage_store(const uint32_t (&wd)[NG][KM], const StagePlan<NG>& sp, uint8_t* words_buf,
-                                            int K) {
+template <int KT, int KM, int NG, bool MP>
+__device__ __forceinline__ void stage_store(const uint32_t (&wd)[NG][KM * (MP ? 4 : 1)], const StagePlan<NG>& sp,
+                                            uint8_t* words_buf, int K) {
 #pragma unroll
   for (int l = 0; l < NG; ++l)
     if (sp.lofs[l] != 0xffffffffu) {
@@ -192,7 +218,13 @@ __device__ __forceinline__ void stage_store(const uint32_t (&wd)[NG][KM], const 
       if constexpr (KT > 0) {
         uint32_t w[KT];
 #pragma unroll
-        for (int j = 0; j < KT; ++j) w[j] = keep ? wd[l][j] : 0u;
+        for (int j = 0; j < KT; ++j) {
+          if constexpr (MP)
+            w[j] = keep ? pool_pairs(wd[l][4 * j] | wd[l][4 * j + 2]) | (pool_pairs(wd[l][4 * j + 1] | wd[l][4 * j + 3]) << 16)
+                        : 0u;
+          else
+            w[j] = keep ? wd[l][j] : 0u;
+        }
         if constexpr (KT == 16) {
           frames_to_fields<8>(w);
           frames_to_fields<8>(w + 8);
@@ -202,6 +234,7 @@ __device__ __forceinline__ void stage_store(const uint32_t (&wd)[NG][KM], const 
 #pragma unroll
         for (int m = 0; m < KT; ++m) *reinterpret_cast<uint32_t*>(dst + m * (kChunk * 4)) = w[m];
       } else {
+        static_assert(KT > 0 || !MP, "max pool on load: compile-time K only");
         for (int j = 0; j < K; ++j) *reinterpret_cast<uint32_t*>(dst + j * (kChunk * 4)) = keep ? wd[l][j] : 0u;
       }
     }
@@ -353,7 +386,9 @@ __device__ __forceinline__ void lds_barrier() {
 
 // TRACE: also write the pre-reset membrane of every LIF step (a kernel of its own, so that the
 // stores and their addresses do not weigh on the register allocation of the plain one).
-template <int KT, int WIN, int S, bool TRACE>
+// MP: the input buffer holds the unpooled spikes of the layer before and a 2 x 2 max pool is
+// applied while staging (the staged words are pooled bits; everything after them is unchanged).
+template <int KT, int WIN, int S, bool TRACE, bool MP>
 __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   using G = Geo<WIN, S>;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -441,8 +476,9 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     const uint8_t* w;
     int c, left;             // chunk within the group; chunks after this one
   };
-  const size_t spk_chunk = (size_t)kChunk * p.H * G::kWW;                      // dwords
-  const size_t spk_wrap = (size_t)K * p.B * p.Cin * p.H * G::kWW - (size_t)NC * spk_chunk;
+  const size_t in_plane = (size_t)p.H * G::kWW * (MP ? 4 : 1);                 // stored dwords per (frame, sample, cin)
+  const size_t spk_chunk = (size_t)kChunk * in_plane;
+  const size_t spk_wrap = (size_t)K * p.B * p.Cin * in_plane - (size_t)NC * spk_chunk;
   auto advance = [&](Cursor& cu) {
     if (cu.left > 0) {
       --cu.left;
@@ -478,9 +514,9 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   constexpr std::integral_constant<int, 9> c9;
 
   StagePlan<NG> plan;
-  stage_plan<G, NG>(plan, p, K, tid, y0 * S - 1);
-  uint32_t wd[NG][KMAX];                        // staged words in flight
-  const uint32_t fstride = (uint32_t)(p.B * p.Cin * p.H * G::kWW);   // dwords between frames
+  stage_plan<G, NG, MP>(plan, p, K, tid, y0 * S - 1);
+  uint32_t wd[NG][KMAX * (MP ? 4 : 1)];         // staged words in flight
+  const uint32_t fstride = (uint32_t)((size_t)p.B * p.Cin * in_plane);         // dwords between frames
   lut_fill<KT>(lut, p, tid);
 
   // ---- prologue: A tile of chunk 0, weights of chunks 0 and 1, staged words of chunk 1,
@@ -490,24 +526,24 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   const uint8_t* w_n2;                          // weights and words of chunk s + 2
   const uint32_t* spk_n2;
   {
-    cur.spk = p.spikes + ((size_t)b * p.Cin) * p.H * G::kWW;
+    cur.spk = p.spikes + ((size_t)b * p.Cin) * in_plane;
     cur.w = p.w + (size_t)co_tile * NC * kWBuf;
     cur.c = 0;
     cur.left = total - 1;
     weights_to_lds(cur.w, lds + G::kLdsW, c0, c9);
-    stage_load<KMAX, NG>(wd, plan, cur.spk, fstride, K);
-    stage_store<KT, KMAX, NG>(wd, plan, words0, K);
+    stage_load<KMAX, NG, MP, G::kWW>(wd, plan, cur.spk, fstride, K);
+    stage_store<KT, KMAX, NG, MP>(wd, plan, words0, K);
     advance(cur);                               // chunk 1
     w_n1 = cur.w;
     weights_to_lds(cur.w, lds + G::kLdsW + kWBuf, c0, c9);
-    stage_load<KMAX, NG>(wd, plan, cur.spk, fstride, K);
-    stage_store<KT, KMAX, NG>(wd, plan, words0 + words_bytes, K);
+    stage_load<KMAX, NG, MP, G::kWW>(wd, plan, cur.spk, fstride, K);
+    stage_store<KT, KMAX, NG, MP>(wd, plan, words0 + words_bytes, K);
     __syncthreads();
     for (int st = 0; st < G::kSteps; ++st) expand_step<G, KT>(p, words0, lut, lds + G::kLdsA, K, lane, q, st);
     advance(cur);                               // chunk 2
     w_n2 = cur.w;
     spk_n2 = cur.spk;
-    stage_load<KMAX, NG>(wd, plan, cur.spk, fstride, K);
+    stage_load<KMAX, NG, MP, G::kWW>(wd, plan, cur.spk, fstride, K);
     advance(cur);                               // chunk 3
   }
   __syncthreads();
@@ -561,7 +597,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
       if (tap == 8) {
         weights_to_lds(w_n2, const_cast<uint8_t*>(w_cur), c0, c2);
         __builtin_amdgcn_sched_barrier(0);
-        stage_load<KMAX, NG>(wd, plan, cur.spk, fstride, K, 0, kLPT);
+        stage_load<KMAX, NG, MP, G::kWW>(wd, plan, cur.spk, fstride, K, 0, kLPT);
         fetch(a_next, w_next, 0, slot ^ 1);
       } else {
         if (tap <= 5) {
@@ -573,7 +609,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
             case 4: weights_to_lds(w_n1, w_next, c7, c8); break;
             default: weights_to_lds(w_n1, w_next, c8, c9); break;
           }
-          if (tap <= 4) stage_load<KMAX, NG>(wd, plan, spk_n2, fstride, K, (tap + 1) * kLPT, (tap + 2) * kLPT);
+          if (tap <= 4) stage_load<KMAX, NG, MP, G::kWW>(wd, plan, spk_n2, fstride, K, (tap + 1) * kLPT, (tap + 2) * kLPT);
         }
         fetch(a_cur, w_cur, tap + 1, slot ^ 1);
       }
@@ -595,7 +631,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
           if (i < G::kSteps) expand_step<G, KT>(p, words_next, lut, a_next, K, lane, q, i);
         }
       }
-      if (tap == 7) stage_store<KT, KMAX, NG>(wd, plan, words_nn, K);
+      if (tap == 7) stage_store<KT, KMAX, NG, MP>(wd, plan, words_nn, K);
       if constexpr (KT > 0) {
         // issue order inside the tap: one MFMA, then a few LDS reads and vector ops that run
         // while the matrix pipe is busy, eight times over
@@ -734,14 +770,14 @@ __global__ void mfma_prepare_kernel(const float* __restrict__ w, uint32_t* __res
   out[i] = pack_bf16(a, bb);
 }
 
-template <int KT, int WIN, int S, bool TRACE>
+template <int KT, int WIN, int S, bool TRACE, bool MP>
 hipError_t launch_traced(const MfmaParams& mp, hipStream_t s) {
   using G = Geo<WIN, S>;
   constexpr int lds = G::lds_bytes(KT > 0 ? KT : TAC_MAX_K);
   static_assert(lds <= kLdsLimit, "tile does not fit the LDS");
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<KT, WIN, S, TRACE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<KT, WIN, S, TRACE, MP>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_done = true;
@@ -749,13 +785,17 @@ hipError_t launch_traced(const MfmaParams& mp, hipStream_t s) {
   MfmaParams q = mp;
   q.row_tiles = (mp.Ho + G::kTileRows - 1) / G::kTileRows;
   const dim3 grid(q.row_tiles * (mp.Cout / kCoutTile) * mp.B);
-  hipLaunchKernelGGL((mfma_kernel<KT, WIN, S, TRACE>), grid, dim3(kThreads), lds, s, q);
+  hipLaunchKernelGGL((mfma_kernel<KT, WIN, S, TRACE, MP>), grid, dim3(kThreads), lds, s, q);
   return hipGetLastError();
 }
 
 template <int KT, int WIN, int S>
 hipError_t launch_one(const MfmaParams& mp, hipStream_t s) {
-  return mp.v_trace ? launch_traced<KT, WIN, S, true>(mp, s) : launch_traced<KT, WIN, S, false>(mp, s);
+  if constexpr (S == 1 && KT >= 1 && KT <= 4) {
+    if (mp.maxpool) return mp.v_trace ? launch_traced<KT, WIN, S, true, true>(mp, s) : launch_traced<KT, WIN, S, false, true>(mp, s);
+  }
+  if (mp.maxpool) return hipErrorInvalidValue;
+  return mp.v_trace ? launch_traced<KT, WIN, S, true, false>(mp, s) : launch_traced<KT, WIN, S, false, false>(mp, s);
 }
 
 // Largest K a geometry has LDS room for (the stride-2 tiles hold 17 or 33 input rows).
@@ -792,7 +832,11 @@ static_assert(max_k<64, 2>() >= 4 && max_k<32, 2>() >= 4, "stride 2 takes K up t
 }  // namespace
 
 static bool large_supported(const tac_layer_desc_t& d) {
-  if (d.precision != TAC_BF16 || d.in_format != TAC_IN_BITS) return false;
+  if (d.precision != TAC_BF16 || d.in_format == TAC_IN_BITS_POOL2) return false;
+  if (d.in_format == TAC_IN_BITS_MAXPOOL2) {   // max pool on load: stride 1, groups of 1, 2 or 4 frames
+    const int Kp = d.mode == TAC_PER_STEP ? 1 : d.K;
+    if (d.stride != 1 || !(Kp == 1 || Kp == 2 || Kp == 4)) return false;
+  }
   if (d.Cin % kChunk != 0 || d.Cout % kCoutTile != 0) return false;
   if (d.W != 64 && d.W != 32) return false;
   if (d.stride == 1) return true;
@@ -820,7 +864,7 @@ hipError_t mfma_launch(const LayerParams& p, hipStream_t s) {
   mp.spikes = p.spikes; mp.w = static_cast<const uint8_t*>(p.w); mp.bias = p.bias; mp.v_inout = p.v_inout;
   mp.out = p.out; mp.v_trace = p.v_trace;
   mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.W = p.W; mp.Ho = p.Ho; mp.Wo = p.Wo; mp.Cout = p.Cout; mp.stride = p.stride;
-  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif;
+  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.maxpool = p.pool2 == 2;
   mp.row_tiles = 0;
   mp.decay = p.decay; mp.theta = p.theta;
   for (int j = 0; j < TAC_MAX_K; ++j) {

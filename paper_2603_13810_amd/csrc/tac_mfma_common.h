@@ -27,7 +27,7 @@ struct MfmaParams {
   float* __restrict__ v_inout;
   uint32_t* __restrict__ out;
   float* __restrict__ v_trace;
-  int B, Cin, H, W, Ho, Wo, Cout, stride, K, G, n_lif, row_tiles;
+  int B, Cin, H, W, Ho, Wo, Cout, stride, K, G, n_lif, row_tiles, maxpool;
   float decay, theta;
   uint32_t wq[TAC_MAX_K];              // round(beta^(K-1-j) * 2^23)
 };

@@ -306,7 +306,7 @@ hipError_t mfma_small_launch(const LayerParams& p, hipStream_t s) {
   mp.spikes = p.spikes; mp.w = static_cast<const uint8_t*>(p.w); mp.bias = p.bias; mp.v_inout = p.v_inout;
   mp.out = p.out; mp.v_trace = p.v_trace;
   mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.W = p.W; mp.Ho = p.Ho; mp.Wo = p.Wo; mp.Cout = p.Cout; mp.stride = p.stride;
-  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.row_tiles = 0;
+  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.row_tiles = 0; mp.maxpool = 0;
   mp.decay = p.decay; mp.theta = p.theta;
   for (int j = 0; j < TAC_MAX_K; ++j) {
     const double q = (double)p.wj[j] * (double)(1u << kFixShift);

@@ -158,3 +158,57 @@ def test_short_contraction_state_carry_and_no_trace():
     b = run_gpu(s[4:], w, K=2, mode=api.TAC_PRESERVE, v0=a["v_final"], **kw)
     assert np.array_equal(np.concatenate([a["packed"], b["packed"]]), whole["packed"])
     assert np.array_equal(b["v_final"], whole["v_final"])
+
+
+# ---- max pool on load (the MaxPool(2) between the blocks of the event-data network)
+
+@pytest.mark.parametrize("W,H", [(64, 10), (32, 19)])
+@pytest.mark.parametrize("mode,K", [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 2), (api.TAC_PRESERVE, 4), (api.TAC_COLLAPSE, 4)])
+def test_max_pool_on_load_mfma(W, H, mode, K):
+    r = _rng(3000 + W + H + K)
+    s = (r.random((8, 2, 32, 2 * H, 2 * W)) < 0.06).astype(np.uint8)          # unpooled spikes of the layer before
+    w = synth.kaiming_normal(51, 128, 32)
+    bias = (r.standard_normal(128) * 0.1).astype(np.float32)
+    par, g, ref = check_layer(s, w, K=K, beta=0.9, theta=1.0, mode=mode, pool2="max", precision=api.TAC_BF16, bias=bias,
+                              expect_kernel=api.TAC_KERNEL_MFMA)
+    assert ref[0].sum() > 0 and g["spikes"].shape[-2:] == (H, W)
+    d = run_gpu(s, w, K=K, beta=0.9, theta=1.0, mode=mode, pool2="max", precision=api.TAC_BF16, bias=bias,
+                kernel=api.TAC_KERNEL_DIRECT, trace=False)
+    assert (d["spikes"] != g["spikes"]).mean() < 1e-3                           # the two kernel families agree
+    print("max pool on load W=%d H=%d" % (W, H), api.MODE_NAMES[mode], K, par)
+
+
+def test_max_pool_on_load_limits():
+    mk = lambda **kw: api.make_desc(8, 1, 32, 16, 64, 128, K=kw.pop("K", 2), beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE,
+                                    stride=kw.pop("stride", 1), precision=api.TAC_BF16, in_format=api.TAC_IN_BITS_MAXPOOL2)
+    assert api.tac_select_kernel(mk()) == api.TAC_KERNEL_MFMA
+    assert api.tac_select_kernel(mk(K=8)) == api.TAC_KERNEL_DIRECT
+    assert api.tac_select_kernel(mk(stride=2)) == api.TAC_KERNEL_DIRECT
+
+
+def test_conv_bn_lif_maxpool_blocks_stay_packed():
+    # three blocks Conv -> BN -> LIF -> MaxPool(2) of the event-data network shape (Sec. 5.1) at a
+    # reduced width: batch norm folded on the device, every inter-layer tensor packed bits, the pool
+    # applied by the next layer's loader; teacher-forced against the oracle layer by layer
+    import oracle
+    r = _rng(3100)
+    dev = torch.device("cuda:0")
+    x = (r.random((4, 1, 2, 64, 128)) < 0.1).astype(np.uint8)
+    chans = [(2, 32), (32, 128), (128, 128)]
+    fmt = [False, "max", "max"]
+    for li, (ci, co) in enumerate(chans):
+        w = synth.kaiming_normal(60 + li, co, ci) * np.float32(2.0)
+        g_, b_ = r.uniform(0.8, 1.2, co).astype(np.float32), (r.standard_normal(co) * 0.05).astype(np.float32)
+        mean, var = (r.standard_normal(co) * 0.05).astype(np.float32), r.uniform(0.8, 1.2, co).astype(np.float32)
+        t = lambda a: torch.from_numpy(a).to(dev)
+        wf, bf = api.tac_fold_batchnorm(t(w), None, t(g_), t(b_), t(mean), t(var), eps=1e-5)
+        rw, rb = oracle.fold_batchnorm(w, None, g_, b_, mean, var, eps=float(np.float32(1e-5)))
+        assert np.abs(wf.cpu().numpy() - rw).max() < 1e-6
+        # both sides take the device's folded fp32 weights from here on
+        wq, bq = wf.cpu().numpy(), bf.cpu().numpy()
+        par, g, ref = check_layer(x, wq, K=2, beta=0.5, theta=1.0, mode=api.TAC_PRESERVE, pool2=fmt[li], bias=bq,
+                                  precision=api.TAC_BF16, plain_stats=False)
+        assert ref[0].mean() > 0.002, "layer %d is silent" % (li + 1)
+        print("block %d %s: %s rate %.3f" % (li + 1, "mfma" if g["kernel"] == api.TAC_KERNEL_MFMA else "direct", par, ref[0].mean()))
+        x = ref[0]                                                               # unpooled spikes, pooled by the next loader
+    assert x.shape == (4, 1, 128, 16, 32)
