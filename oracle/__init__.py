@@ -36,7 +36,7 @@ def build(force: bool = False) -> str:
 class _Desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("T", "B", "Cin", "H", "W", "Cout", "kh", "kw", "stride", "pad", "K",
-                 "pool2", "round_a_bf16", "nthreads")] + \
+                 "pool2", "round_a_bf16", "nthreads", "dense")] + \
                [("beta", ctypes.c_double), ("theta", ctypes.c_double)]
 
 
@@ -148,6 +148,14 @@ def conv2d(x: np.ndarray, w: np.ndarray, bias=None, stride: int = 1, pad: int = 
     return y
 
 
+def _as_input(spikes):
+    """uint8 0/1 spikes stay bytes; anything real-valued is handed over as float64 frames."""
+    spikes = np.asarray(spikes)
+    if np.issubdtype(spikes.dtype, np.floating):
+        return np.ascontiguousarray(spikes, dtype=np.float64)
+    return np.ascontiguousarray(spikes, dtype=np.uint8)
+
+
 def _desc(spikes, weight, K, beta, theta, stride, pad, pool2, round_a_bf16, nthreads):
     T, B, Cin, Hs, Ws = spikes.shape
     Cout, Cin2, kh, kw = weight.shape
@@ -161,7 +169,7 @@ def _desc(spikes, weight, K, beta, theta, stride, pad, pool2, round_a_bf16, nthr
         H, W = Hs, Ws
     d = _Desc(T=T, B=B, Cin=Cin, H=H, W=W, Cout=Cout, kh=kh, kw=kw, stride=stride, pad=pad, K=K,
               pool2=(2 if pool2 in (2, "max") else int(bool(pool2))), round_a_bf16=int(bool(round_a_bf16)), nthreads=int(nthreads),
-              beta=float(beta), theta=float(theta))
+              dense=int(spikes.dtype == np.float64), beta=float(beta), theta=float(theta))
     Ho = (H + 2 * pad - kh) // stride + 1
     Wo = (W + 2 * pad - kw) // stride + 1
     return d, Ho, Wo
@@ -177,7 +185,7 @@ def conv_lif(spikes, weight, bias=None, *, K=1, beta, theta, mode, stride=1, pad
     v_final float64 [B,Cout,Ho,Wo]).
     """
     lib = _load()
-    spikes = np.ascontiguousarray(spikes, dtype=np.uint8)
+    spikes = _as_input(spikes)
     if spikes.max(initial=0) > 1:
         raise ValueError("spikes must be 0/1")
     weight = np.ascontiguousarray(weight, dtype=np.float64)
@@ -207,7 +215,7 @@ def conv_lif_neurons(spikes, weight, bias=None, *, idx, K=1, beta, theta, mode, 
     Returns (out_spikes uint8 [T_out,n], v_pre float64 [T_out,n], v_final float64 [n]).
     """
     lib = _load()
-    spikes = np.ascontiguousarray(spikes, dtype=np.uint8)
+    spikes = _as_input(spikes)
     weight = np.ascontiguousarray(weight, dtype=np.float64)
     idx = np.ascontiguousarray(idx, dtype=np.int32)
     assert idx.ndim == 2 and idx.shape[1] == 4

@@ -52,6 +52,8 @@ typedef struct {
   int32_t pool2;               /* S is [T][B][Cin][2H][2W] and a 2x2 pool precedes the layer: 1 mean, 2 max */
   int32_t round_a_bf16;        /* 1: round every A_k element to bfloat16 (nearest even)  */
   int32_t nthreads;            /* OpenMP threads over the batch loop; <=1: serial        */
+  int32_t dense;               /* 1: S points to doubles (real-valued frames, e.g. the continuous-valued
+                                * first layer of Sec. 4.2), not to uint8 spikes            */
   double beta, theta;
 } oracle_desc_t;
 
@@ -155,16 +157,20 @@ void oracle_conv2d(const double* X, const double* Wt, const double* bias, double
 }
 
 /* Input frame t as doubles X[B][Cin][H][W] (after the optional 2x2 pool). */
+static double in_value(const oracle_desc_t* d, const uint8_t* S, int64_t i) {
+  return d->dense ? ((const double*)S)[i] : (double)S[i];
+}
+
 static void load_frame(const oracle_desc_t* d, const uint8_t* S, int t, double* X, double* tmp) {
   const int64_t n_in = (int64_t)d->B * d->Cin;
   if (d->pool2) {
     const int64_t fr = n_in * (2 * d->H) * (int64_t)(2 * d->W);
-    for (int64_t i = 0; i < fr; ++i) tmp[i] = (double)S[(int64_t)t * fr + i];
+    for (int64_t i = 0; i < fr; ++i) tmp[i] = in_value(d, S, (int64_t)t * fr + i);
     if (d->pool2 == 2) oracle_maxpool2(tmp, X, n_in, d->H, d->W);
     else oracle_avgpool2(tmp, X, n_in, d->H, d->W);
   } else {
     const int64_t fr = n_in * d->H * (int64_t)d->W;
-    for (int64_t i = 0; i < fr; ++i) X[i] = (double)S[(int64_t)t * fr + i];
+    for (int64_t i = 0; i < fr; ++i) X[i] = in_value(d, S, (int64_t)t * fr + i);
   }
 }
 
@@ -307,11 +313,19 @@ int oracle_tac_tp(const oracle_desc_t* d, const uint8_t* S, const double* Wt, co
 static double input_at(const oracle_desc_t* d, const uint8_t* S, int t, int b, int ci, int iy, int ix) {
   if (d->pool2) {
     const int H2 = 2 * d->H, W2 = 2 * d->W;
-    const uint8_t* p = S + ((((int64_t)t * d->B + b) * d->Cin + ci) * H2 + 2 * iy) * (int64_t)W2 + 2 * ix;
-    if (d->pool2 == 2) return (p[0] | p[1] | p[W2] | p[W2 + 1]) ? 1.0 : 0.0;
-    return 0.25 * ((double)p[0] + (double)p[1] + (double)p[W2] + (double)p[W2 + 1]);
+    const int64_t i = ((((int64_t)t * d->B + b) * d->Cin + ci) * H2 + 2 * iy) * (int64_t)W2 + 2 * ix;
+    const double p00 = in_value(d, S, i), p01 = in_value(d, S, i + 1);
+    const double p10 = in_value(d, S, i + W2), p11 = in_value(d, S, i + W2 + 1);
+    if (d->pool2 == 2) {
+      double m = p00;
+      if (p01 > m) m = p01;
+      if (p10 > m) m = p10;
+      if (p11 > m) m = p11;
+      return m;
+    }
+    return 0.25 * (p00 + p01 + p10 + p11);
   }
-  return (double)S[((((int64_t)t * d->B + b) * d->Cin + ci) * d->H + iy) * (int64_t)d->W + ix];
+  return in_value(d, S, ((((int64_t)t * d->B + b) * d->Cin + ci) * d->H + iy) * (int64_t)d->W + ix);
 }
 
 /* Convolution output at one neuron, of the frame t0 (per-step, K1 = 1) or of

@@ -272,10 +272,10 @@ def _brute(s, w, bias, v0, K, beta, theta, mode, stride, pad, pool2):
         if not (0 <= y < H and 0 <= x < W):
             return F(0)
         if pool2 == "max":
-            return F(int(s[t, b, ci, 2 * y:2 * y + 2, 2 * x:2 * x + 2].max()))
+            return F(float(s[t, b, ci, 2 * y:2 * y + 2, 2 * x:2 * x + 2].max()))
         if pool2:
-            return F(int(s[t, b, ci, 2 * y:2 * y + 2, 2 * x:2 * x + 2].sum()), 4)
-        return F(int(s[t, b, ci, y, x]))
+            return sum(F(float(v)) for v in s[t, b, ci, 2 * y:2 * y + 2, 2 * x:2 * x + 2].ravel()) / 4
+        return F(float(s[t, b, ci, y, x]))
 
     Kg = 1 if mode == PER_STEP else K
     n_lif = Kg if mode == TAC_TP else 1
@@ -322,6 +322,42 @@ def test_exact_brute_force(mode, K, stride, pool2):
     assert np.array_equal(got[1], ref[1].astype(np.float64))
     assert np.array_equal(got[2], ref[2].astype(np.float64))
     assert got[0].sum() > 0
+
+
+@pytest.mark.parametrize("mode,K", [(PER_STEP, 1), (TAC, 2), (TAC_TP, 4)])
+@pytest.mark.parametrize("stride,pool2", [(1, False), (2, False), (1, True)])
+def test_exact_brute_force_real_valued_frames(mode, K, stride, pool2):
+    # real-valued input frames (the continuous-valued first layer, Sec. 4.2), dyadic so that doubles are exact
+    r = _rng(150 + 10 * K + stride + 5 * bool(pool2))
+    T, B, Cin, Cout, H, W = 4, 1, 2, 3, 4, 5
+    shape = (T, B, Cin, 2 * H, 2 * W) if pool2 else (T, B, Cin, H, W)
+    s = r.integers(0, 9, size=shape) / 8.0
+    w = r.integers(-8, 9, size=(Cout, Cin, 3, 3)) / 8.0
+    bias = r.integers(-4, 5, size=Cout) / 16.0
+    got = oracle.conv_lif(s, w, bias, K=K, beta=0.75, theta=1.0, mode=mode, stride=stride, pad=1, pool2=pool2)
+    ref = _brute(s, w, bias, None, K, 0.75, 1.0, mode, stride, 1, pool2)
+    assert np.array_equal(got[0], ref[0]) and got[0].sum() > 0
+    assert np.array_equal(got[1], ref[1].astype(np.float64))
+    assert np.array_equal(got[2], ref[2].astype(np.float64))
+    Ho, Wo = got[2].shape[2:]
+    idx = np.array(list(itertools.product(range(B), range(Cout), range(Ho), range(Wo))), dtype=np.int32)
+    part = oracle.conv_lif_neurons(s, w, bias, idx=idx, K=K, beta=0.75, theta=1.0, mode=mode, stride=stride, pool2=pool2)
+    assert np.array_equal(part[0], got[0].reshape(got[0].shape[0], -1))
+    assert np.array_equal(part[1], got[1].reshape(got[1].shape[0], -1))
+
+
+def test_real_valued_frames_reduce_to_spikes_and_scale_with_the_weights():
+    r = _rng(160)
+    s = r.integers(0, 2, size=(4, 2, 2, 6, 7)).astype(np.uint8)
+    w = r.integers(-8, 9, size=(3, 2, 3, 3)) / 8.0
+    kw = dict(K=2, beta=0.5, theta=1.0, mode=TAC_TP)
+    a = oracle.conv_lif(s, w, **kw)
+    b = oracle.conv_lif(s.astype(np.float64), w, **kw)            # 0/1 frames given as reals: the same layer
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    c = oracle.conv_lif(s * 0.25, w * 4.0, **kw)                  # x/4 with 4 W: the same input current (exact, dyadic)
+    assert all(np.array_equal(x, y) for x, y in zip(a, c))
+    d = oracle.conv_lif(s * 0.25, w, **kw)                        # and a different one without the compensation
+    assert not np.array_equal(a[1], d[1])
 
 
 @pytest.mark.parametrize("mode,K", [(PER_STEP, 1), (TAC, 4), (TAC_TP, 2)])
