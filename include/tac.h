@@ -41,13 +41,16 @@ enum { TAC_PER_STEP = 0, TAC_COLLAPSE = 1 /* TAC */, TAC_PRESERVE = 2 /* TAC-TP 
  * are always fp32.  TAC_BF16: the kernel W and every aggregate A_k are rounded
  * to bfloat16 (nearest even) before they are multiplied. */
 enum { TAC_FP32 = 0, TAC_BF16 = 1 };
-/* Input format.  TAC_IN_BITS_POOL2: `spikes_packed` holds the UNPOOLED frames
+/* Input format.  TAC_IN_BITS: `input` holds packed spikes.  TAC_IN_BITS_POOL2: it holds the UNPOOLED frames
  * [T][B][Cin][2H][2W]; a 2x2 mean pool (stride 2) is applied while loading, so
  * the layer sees inputs in {0, 1/4, 1/2, 3/4, 1} of size H x W (the Pool(2) between the two
  * convolutions of the rate-coded network, Sec. 5.1).  TAC_IN_BITS_MAXPOOL2: the same buffer
  * convention with a 2x2 max pool, i.e. the OR of the four bits (the MaxPool(2) that follows
- * every LIF layer of the event-data network, Sec. 5.1): the layer sees bits again. */
-enum { TAC_IN_BITS = 0, TAC_IN_BITS_POOL2 = 1, TAC_IN_BITS_MAXPOOL2 = 2 };
+ * every LIF layer of the event-data network, Sec. 5.1): the layer sees bits again.
+ * TAC_IN_F32: real-valued frames, `input` is float32 [T][B][Cin][H][W] (the continuous-valued
+ * first layer of Sec. 4.2, e.g. normalised event counts); aggregation, convolution and LIF are
+ * the same, the aggregate A_k is a weighted sum of real frames. */
+enum { TAC_IN_BITS = 0, TAC_IN_BITS_POOL2 = 1, TAC_IN_BITS_MAXPOOL2 = 2, TAC_IN_F32 = 3 };
 /* Kernel family.  AUTO picks MFMA when the shape qualifies (see
  * tac_select_kernel), else DIRECT.  Forcing MFMA on a shape it does not
  * support is TAC_ERR_UNSUPPORTED. */
@@ -77,7 +80,7 @@ typedef struct tac_layer_desc {
   int32_t K;                 /* group size; TAC_PER_STEP ignores it and uses 1            */
   int32_t mode;              /* TAC_PER_STEP / TAC_COLLAPSE / TAC_PRESERVE                */
   int32_t precision;         /* TAC_FP32 / TAC_BF16                                       */
-  int32_t in_format;         /* TAC_IN_BITS / TAC_IN_BITS_POOL2 / TAC_IN_BITS_MAXPOOL2    */
+  int32_t in_format;         /* TAC_IN_BITS / _POOL2 / _MAXPOOL2 / TAC_IN_F32             */
   int32_t kernel;            /* TAC_KERNEL_AUTO / _DIRECT / _MFMA                         */
   float beta;                /* membrane decay, in [0, 1]                                 */
   float theta;               /* threshold V_th, > 0                                       */
@@ -114,8 +117,9 @@ int tac_prepare_weights(const tac_layer_desc_t* desc, const float* w_oihw, void*
  * Conv2d(A_k, W), then the LIF update(s), threshold (spike iff V >= theta) and
  * subtractive reset of Alg. 1 (TAC), Alg. 2 (TAC-TP) or the per-step layer
  * (K = 1).  A_k and Y_k never leave the chip.
- *   spikes_packed      DEVICE, read-only, packed [T][B][Cin][H][ceil(W/32)]
- *                      (or [T][B][Cin][2H][ceil(2W/32)] with TAC_IN_BITS_[MAX]POOL2)
+ *   input              DEVICE, read-only, packed uint32 [T][B][Cin][H][ceil(W/32)]
+ *                      (or [T][B][Cin][2H][ceil(2W/32)] with TAC_IN_BITS_[MAX]POOL2, or float32
+ *                      [T][B][Cin][H][W] with TAC_IN_F32)
  *   w_prepared         DEVICE, read-only, from tac_prepare_weights
  *   bias               DEVICE, read-only, float32 [Cout], or NULL for zero.  Added
  *                      once per convolution (so TAC-TP sees it in each of its K steps)
@@ -126,9 +130,9 @@ int tac_prepare_weights(const tac_layer_desc_t* desc, const float* w_oihw, void*
  *   out_spikes_packed  DEVICE, written, packed [T_out][B][Cout][Ho][ceil(Wo/32)]
  *   v_trace            DEVICE, optional debug output, float32 [T_out][B][Cout][Ho][Wo]:
  *                      membrane BEFORE the reset at every LIF step; NULL in timed runs
- * Buffers must not overlap.  All pointers need 4-byte alignment (spikes_packed 8-byte with
+ * Buffers must not overlap.  All pointers need 4-byte alignment (input 8-byte with
  * TAC_IN_BITS_MAXPOOL2 on the MFMA kernel; w_prepared 16-byte), else TAC_ERR_ALIGN. */
-int tac_conv_lif(const tac_layer_desc_t* desc, const uint32_t* spikes_packed, const void* w_prepared,
+int tac_conv_lif(const tac_layer_desc_t* desc, const void* input, const void* w_prepared,
                  const float* bias, float* v_inout, uint32_t* out_spikes_packed, float* v_trace,
                  void* stream);
 

@@ -232,6 +232,10 @@ int oracle_per_step(const oracle_desc_t* d, const uint8_t* S, const double* Wt, 
   if (scratch_init(d, v0, &s)) return -3;
   for (int t = 0; t < d->T; ++t) {
     load_frame(d, S, t, s.X, s.tmp);
+    if (d->round_a_bf16) {        /* the convolution input of this loop is the frame itself (A_k with K = 1) */
+      const int64_t n_in = (int64_t)d->B * d->Cin * d->H * d->W;
+      for (int64_t i = 0; i < n_in; ++i) s.X[i] = oracle_round_bf16(s.X[i]);
+    }
     oracle_conv2d(s.X, Wt, bias, s.Y, d->B, d->Cin, d->H, d->W, d->Cout, d->kh, d->kw,
                   d->stride, d->pad, d->nthreads);
     for (int64_t i = 0; i < s.n_out; ++i) {

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libtac.so")
 
 TAC_PER_STEP, TAC_COLLAPSE, TAC_PRESERVE = 0, 1, 2
 TAC_FP32, TAC_BF16 = 0, 1
-TAC_IN_BITS, TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2 = 0, 1, 2
+TAC_IN_BITS, TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2, TAC_IN_F32 = 0, 1, 2, 3
 TAC_KERNEL_AUTO, TAC_KERNEL_DIRECT, TAC_KERNEL_MFMA = 0, 1, 2
 TAC_OK, TAC_ERR_NULL, TAC_ERR_BAD_SHAPE, TAC_ERR_BAD_K = 0, -1, -2, -3
 TAC_ERR_BAD_PARAM, TAC_ERR_UNSUPPORTED, TAC_ERR_HIP, TAC_ERR_ALIGN = -4, -5, -6, -7
@@ -169,8 +169,13 @@ def tac_conv_lif(desc, spikes_packed, w_prepared, bias=None, v_inout=None, out_s
     (int32 tensor [T_out,B,Cout,Ho,ceil(Wo/32)], allocated if not given)."""
     import torch
     T_out, Ho, Wo = tac_out_shape(desc)
-    f = 1 if desc.in_format == TAC_IN_BITS else 2
-    need_in = tac_packed_bytes(desc.T, desc.B, desc.Cin, desc.H * f, desc.W * f)
+    f = 2 if desc.in_format in (TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2) else 1
+    if desc.in_format == TAC_IN_F32:
+        need_in = desc.T * desc.B * desc.Cin * desc.H * desc.W * 4
+        if spikes_packed.dtype != torch.float32:
+            raise ValueError("TAC_IN_F32 needs a float32 input tensor")
+    else:
+        need_in = tac_packed_bytes(desc.T, desc.B, desc.Cin, desc.H * f, desc.W * f)
     if spikes_packed.numel() * spikes_packed.element_size() != need_in:
         raise ValueError("spikes_packed has %d bytes, the description needs %d" %
                          (spikes_packed.numel() * spikes_packed.element_size(), need_in))

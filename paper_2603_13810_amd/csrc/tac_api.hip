@@ -27,8 +27,7 @@ int validate(const tac_layer_desc_t* d) {
   if (d->stride != 1 && d->stride != 2) return TAC_ERR_BAD_SHAPE;
   if (d->mode != TAC_PER_STEP && d->mode != TAC_COLLAPSE && d->mode != TAC_PRESERVE) return TAC_ERR_BAD_PARAM;
   if (d->precision != TAC_FP32 && d->precision != TAC_BF16) return TAC_ERR_BAD_PARAM;
-  if (d->in_format != TAC_IN_BITS && d->in_format != TAC_IN_BITS_POOL2 && d->in_format != TAC_IN_BITS_MAXPOOL2)
-    return TAC_ERR_BAD_PARAM;
+  if (d->in_format < TAC_IN_BITS || d->in_format > TAC_IN_F32) return TAC_ERR_BAD_PARAM;
   if (d->kernel != TAC_KERNEL_AUTO && d->kernel != TAC_KERNEL_DIRECT && d->kernel != TAC_KERNEL_MFMA)
     return TAC_ERR_BAD_PARAM;
   if (!(d->beta >= 0.0f && d->beta <= 1.0f)) return TAC_ERR_BAD_PARAM;
@@ -40,8 +39,9 @@ int validate(const tac_layer_desc_t* d) {
   // 64-bit offsets across slabs; keep each slab below 2^31 elements
   const int Ho = (d->H + 2 - 3) / d->stride + 1, Wo = (d->W + 2 - 3) / d->stride + 1;
   const int64_t out_slab = (int64_t)d->B * d->Cout * Ho * Wo;
-  const int f = d->in_format == TAC_IN_BITS ? 1 : 2;
-  const int64_t in_slab = (int64_t)d->B * d->Cin * (d->H * f) * ((d->W * f + 31) / 32);
+  const int f = (d->in_format == TAC_IN_BITS_POOL2 || d->in_format == TAC_IN_BITS_MAXPOOL2) ? 2 : 1;
+  const int64_t in_slab = d->in_format == TAC_IN_F32 ? (int64_t)d->B * d->Cin * d->H * d->W
+                                                      : (int64_t)d->B * d->Cin * (d->H * f) * ((d->W * f + 31) / 32);
   if (out_slab >= (1LL << 31) || in_slab >= (1LL << 31)) return TAC_ERR_BAD_SHAPE;
   if (d->B > 65535) return TAC_ERR_BAD_SHAPE;
   return TAC_OK;
@@ -99,11 +99,12 @@ int tac_prepare_weights(const tac_layer_desc_t* desc, const float* w_oihw, void*
   return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_prepare_weights");
 }
 
-int tac_conv_lif(const tac_layer_desc_t* desc, const uint32_t* spikes_packed, const void* w_prepared,
+int tac_conv_lif(const tac_layer_desc_t* desc, const void* input, const void* w_prepared,
                  const float* bias, float* v_inout, uint32_t* out_spikes_packed, float* v_trace,
                  void* stream) {
   int rc = validate(desc);
   if (rc) return rc;
+  const uint32_t* spikes_packed = static_cast<const uint32_t*>(input);     // float32 frames with TAC_IN_F32
   if (!spikes_packed || !w_prepared || !out_spikes_packed) return TAC_ERR_NULL;
   if (((uintptr_t)spikes_packed & 3u) || ((uintptr_t)w_prepared & 15u) || ((uintptr_t)bias & 3u) ||
       ((uintptr_t)v_inout & 3u) || ((uintptr_t)out_spikes_packed & 3u) || ((uintptr_t)v_trace & 3u))
@@ -123,6 +124,7 @@ int tac_conv_lif(const tac_layer_desc_t* desc, const uint32_t* spikes_packed, co
   p.Ho = (desc->H + 2 - 3) / desc->stride + 1;
   p.Wo = (desc->W + 2 - 3) / desc->stride + 1;
   p.pool2 = desc->in_format == TAC_IN_BITS_POOL2 ? 1 : (desc->in_format == TAC_IN_BITS_MAXPOOL2 ? 2 : 0);
+  p.dense = desc->in_format == TAC_IN_F32;
   p.Hs = p.pool2 ? 2 * desc->H : desc->H;
   p.Wwi = ((p.pool2 ? 2 * desc->W : desc->W) + 31) / 32;
   p.Wwo = (p.Wo + 31) / 32;
@@ -134,7 +136,7 @@ int tac_conv_lif(const tac_layer_desc_t* desc, const uint32_t* spikes_packed, co
   // powers of beta in double from the fp32 beta the caller passed, rounded once
   const double beta = (double)desc->beta;
   double pw = 1.0;
-  for (int j = p.K - 1; j >= 0; --j) { p.wj[j] = (float)pw; pw *= beta; }   // wj[j] = beta^(K-1-j)
+  for (int j = p.K - 1; j >= 0; --j) { p.wj[j] = (float)pw; p.wjd[j] = pw; pw *= beta; }   // wj[j] = beta^(K-1-j)
   p.decay = desc->mode == TAC_COLLAPSE ? (float)pw /* beta^K */ : desc->beta;
 
   hipError_t e = kern == TAC_KERNEL_MFMA ? tac::mfma_launch(p, (hipStream_t)stream)

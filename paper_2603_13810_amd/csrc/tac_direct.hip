@@ -88,7 +88,16 @@ __global__ __launch_bounds__(kThreads) void direct_kernel(const LayerParams p, c
           const uint32_t* src = p.spikes + ((size_t)(g * p.K) * p.B + b) * p.Cin * in_chan +
                                 (size_t)(c0 + ci) * in_chan;
           const size_t t_stride = (size_t)p.B * p.Cin * in_chan;
-          if (!p.pool2) {
+          if (p.dense) {
+            // real-valued frames: the weighted sum in double, products and sums rounded one by one,
+            // then once to fp32 (and to bf16 below when asked)
+            const float* xs = reinterpret_cast<const float*>(p.spikes) +
+                              (((size_t)(g * p.K) * p.B + b) * p.Cin + (c0 + ci)) * ((size_t)p.H * p.W) + (size_t)iy * p.W + x;
+            const size_t ts = (size_t)p.B * p.Cin * p.H * p.W;
+            double ad = 0.0;
+            for (int j = 0; j < p.K; ++j) ad = __dadd_rn(ad, __dmul_rn(p.wjd[j], (double)xs[j * ts]));
+            a = (float)ad;
+          } else if (!p.pool2) {
             const size_t off = (size_t)iy * p.Wwi + (x >> 5);
             for (int j = 0; j < p.K; ++j) {
               const uint32_t wd = src[j * t_stride + off];

@@ -23,10 +23,12 @@ struct LayerParams {
   int G;                    // groups = T / K = convolution stages
   int n_lif;                // LIF steps per group: K for TAC-TP, else 1
   int pool2;                // input is unpooled: 1 = 2x2 mean pool while loading, 2 = 2x2 max pool
+  int dense;                // input is float32 frames [T][B][Cin][H][W], not packed bits
   int bf16;                 // round A_k to bf16
   float decay;              // membrane decay per LIF step: beta^K for TAC, else beta
   float theta;
   float wj[TAC_MAX_K];      // aggregation weights beta^(K-1-j), Eq. 2
+  double wjd[TAC_MAX_K];    // the same before the rounding to fp32 (used with real-valued input frames)
 };
 
 // direct (vector-FMA) kernel family: any shape

@@ -832,7 +832,7 @@ static_assert(max_k<64, 2>() >= 4 && max_k<32, 2>() >= 4, "stride 2 takes K up t
 }  // namespace
 
 static bool large_supported(const tac_layer_desc_t& d) {
-  if (d.precision != TAC_BF16 || d.in_format == TAC_IN_BITS_POOL2) return false;
+  if (d.precision != TAC_BF16 || d.in_format == TAC_IN_BITS_POOL2 || d.in_format == TAC_IN_F32) return false;
   if (d.in_format == TAC_IN_BITS_MAXPOOL2) {   // max pool on load: stride 1, groups of 1, 2 or 4 frames
     const int Kp = d.mode == TAC_PER_STEP ? 1 : d.K;
     if (d.stride != 1 || !(Kp == 1 || Kp == 2 || Kp == 4)) return false;
@@ -864,7 +864,7 @@ hipError_t mfma_launch(const LayerParams& p, hipStream_t s) {
   mp.spikes = p.spikes; mp.w = static_cast<const uint8_t*>(p.w); mp.bias = p.bias; mp.v_inout = p.v_inout;
   mp.out = p.out; mp.v_trace = p.v_trace;
   mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.W = p.W; mp.Ho = p.Ho; mp.Wo = p.Wo; mp.Cout = p.Cout; mp.stride = p.stride;
-  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.maxpool = p.pool2 == 2;
+  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.maxpool = p.pool2 == 2; mp.dense = 0;
   mp.row_tiles = 0;
   mp.decay = p.decay; mp.theta = p.theta;
   for (int j = 0; j < TAC_MAX_K; ++j) {

@@ -30,6 +30,8 @@ struct MfmaParams {
   int B, Cin, H, W, Ho, Wo, Cout, stride, K, G, n_lif, row_tiles, maxpool;
   float decay, theta;
   uint32_t wq[TAC_MAX_K];              // round(beta^(K-1-j) * 2^23)
+  int dense;                           // short-contraction kernel: the input is float32 frames
+  double wjd[TAC_MAX_K];               // beta^(K-1-j) in double, for real-valued frames
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {

@@ -14,6 +14,8 @@
 //   2. every thread forms its share of the aggregate A_k (Eq. 2) from those words, in the same
 //      24-bit fixed point as the large kernel, rounds once to bf16 and writes the tile
 //      [cin][row][x + 1] (columns 0 and W + 1 stay zero: the padding);
+//      (real-valued input frames, the continuous-valued first layer of Sec. 4.2, skip step 1:
+//      the threads sum their elements' K values straight from global memory, in double);
 //   3. gather, 2 x NMC x 2 MFMAs, bias, LIF steps (1, or K for TAC-TP), ballot, packed stores.
 #include "tac_mfma_common.h"
 
@@ -47,7 +49,7 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(const MfmaParams p
   // LDS: raw words [cin][row][word][frame], aggregate tile bf16 [cin][row][WP] followed by one
   // zero element (the target of the contraction slots beyond 9 * Cin), bias
   uint32_t* const words = reinterpret_cast<uint32_t*>(lds);
-  const int n_words = CIN * kRowsIn * WW * K;
+  const int n_words = p.dense ? 0 : CIN * kRowsIn * WW * K;   // real-valued frames are not staged
   uint16_t* const a_tile = reinterpret_cast<uint16_t*>(lds + ((n_words * 4 + 15) & ~15));
   const int n_a = CIN * kRowsIn * WP;
   float* const bias_lds = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(a_tile) + (((n_a + 1) * 2 + 15) & ~15));
@@ -136,6 +138,25 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(const MfmaParams p
       agg[l] = (uint32_t)(cr * WW + (x >> 5)) | ((uint32_t)(x & 31) << 12) | ((uint32_t)(cr * WP + x + 1) << 17);
     }
   }
+  // real-valued frames: element offset of (cin, input row, x) from the group's first frame of this
+  // sample; rows outside the image keep the offset of a valid row and are masked
+  uint32_t doff[kSmallWordRegs];
+  uint32_t dkeep = 0;
+  if (p.dense) {
+#pragma unroll
+    for (int l = 0; l < kSmallWordRegs; ++l) {
+      const int e = tid + l * kSmallThreads;
+      doff[l] = 0;
+      if (e < CIN * kRowsIn * p.W) {
+        const int cr = e / p.W, x = e - cr * p.W;
+        const int cin = cr / kRowsIn, row = cr - cin * kRowsIn;
+        const int iy = iy0 + row;
+        const int iyc = min(max(iy, 0), p.H - 1);
+        doff[l] = (uint32_t)((cin * p.H + iyc) * p.W + x);
+        if (iy == iyc) dkeep |= 1u << l;
+      }
+    }
+  }
   uint32_t wd[kSmallWordRegs];
   auto load_words = [&](int g) {
     const uint32_t* base = p.spikes + (((size_t)g * K) * p.B + b) * CIN * in_chan;
@@ -168,16 +189,35 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(const MfmaParams p
     }
     if (g + 1 < p.G) load_words(g + 1);
     __syncthreads();
-    // ---- 2. aggregate (Eq. 2), fixed point, one rounding to bf16
+    // ---- 2. aggregate (Eq. 2), one rounding to bf16
+    if (p.dense) {
+      // real-valued frames: weighted sum in double (products and sums rounded one by one), then
+      // fp32, then bf16; all of a thread's elements advance together so that their loads overlap
+      const float* base = reinterpret_cast<const float*>(p.spikes) + (((size_t)g * K) * p.B + b) * CIN * ((size_t)p.H * p.W);
+      const size_t ts = (size_t)p.B * CIN * p.H * p.W;
+      double ad[kSmallWordRegs];
 #pragma unroll
-    for (int l = 0; l < kSmallWordRegs; ++l)
-      if (agg[l] != 0xffffffffu) {
-        const uint32_t* src = words + (agg[l] & 0xfffu) * K;
-        const uint32_t bit = (agg[l] >> 12) & 31u;
-        uint32_t acc = 0;
-        for (int j = 0; j < K; ++j) acc = __umul24(__builtin_amdgcn_ubfe(src[j], bit, 1), p.wq[j]) + acc;
-        a_tile[agg[l] >> 17] = (uint16_t)pack_bf16((float)acc * (1.0f / (float)(1u << kFixShift)), 0.f);
+      for (int l = 0; l < kSmallWordRegs; ++l) ad[l] = 0.0;
+      for (int j = 0; j < K; ++j) {
+        const double wj = p.wjd[j];
+#pragma unroll
+        for (int l = 0; l < kSmallWordRegs; ++l)
+          if (agg[l] != 0xffffffffu) ad[l] = __dadd_rn(ad[l], __dmul_rn(wj, (double)base[j * ts + doff[l]]));
       }
+#pragma unroll
+      for (int l = 0; l < kSmallWordRegs; ++l)
+        if (agg[l] != 0xffffffffu) a_tile[agg[l] >> 17] = (dkeep >> l) & 1u ? (uint16_t)pack_bf16((float)ad[l], 0.f) : (uint16_t)0;
+    } else {
+#pragma unroll
+      for (int l = 0; l < kSmallWordRegs; ++l)
+        if (agg[l] != 0xffffffffu) {
+          const uint32_t* src = words + (agg[l] & 0xfffu) * K;
+          const uint32_t bit = (agg[l] >> 12) & 31u;
+          uint32_t acc = 0;
+          for (int j = 0; j < K; ++j) acc = __umul24(__builtin_amdgcn_ubfe(src[j], bit, 1), p.wq[j]) + acc;
+          a_tile[agg[l] >> 17] = (uint16_t)pack_bf16((float)acc * (1.0f / (float)(1u << kFixShift)), 0.f);
+        }
+    }
     __syncthreads();
     // ---- 3. gather the filter windows, multiply
     f32x16 acc[NMC][2];
@@ -282,12 +322,13 @@ hipError_t small_launch_n(const MfmaParams& mp, hipStream_t s) {
 }  // namespace
 
 bool mfma_small_supported(const tac_layer_desc_t& d) {
-  if (d.precision != TAC_BF16 || d.in_format != TAC_IN_BITS) return false;
+  if (d.precision != TAC_BF16 || (d.in_format != TAC_IN_BITS && d.in_format != TAC_IN_F32)) return false;
   if (d.Cin < 1 || d.Cin > 2 || d.Cout > 64) return false;
   if (d.W > kSmallMaxW || (d.W + 2 - 3) / d.stride + 1 > kSmallMaxWo) return false;
   const int K = d.mode == TAC_PER_STEP ? 1 : d.K;
   // staged words of one group: 256 threads x kSmallWordRegs registers
   const int rows = (kSmallRows - 1) * d.stride + 3;
+  if (d.in_format == TAC_IN_F32) return true;
   return d.Cin * rows * ((d.W + 31) / 32) * K <= kSmallThreads * kSmallWordRegs;
 }
 
@@ -306,7 +347,8 @@ hipError_t mfma_small_launch(const LayerParams& p, hipStream_t s) {
   mp.spikes = p.spikes; mp.w = static_cast<const uint8_t*>(p.w); mp.bias = p.bias; mp.v_inout = p.v_inout;
   mp.out = p.out; mp.v_trace = p.v_trace;
   mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.W = p.W; mp.Ho = p.Ho; mp.Wo = p.Wo; mp.Cout = p.Cout; mp.stride = p.stride;
-  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.row_tiles = 0; mp.maxpool = 0;
+  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.row_tiles = 0; mp.maxpool = 0; mp.dense = p.dense;
+  for (int j = 0; j < TAC_MAX_K; ++j) mp.wjd[j] = p.wjd[j];
   mp.decay = p.decay; mp.theta = p.theta;
   for (int j = 0; j < TAC_MAX_K; ++j) {
     const double q = (double)p.wj[j] * (double)(1u << kFixShift);

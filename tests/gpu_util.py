@@ -17,16 +17,19 @@ def bf16_round_np(w32: np.ndarray) -> np.ndarray:
 
 def run_gpu(spikes, w32, *, K, beta, theta, mode, stride=1, bias=None, v0=None, pool2=False,
             precision=api.TAC_FP32, kernel=api.TAC_KERNEL_AUTO, trace=True):
-    """spikes uint8 [T,B,Cin,Hs,Ws] host array.  Returns dict with unpacked spikes, v_trace, v_final, kernel id."""
+    """spikes uint8 [T,B,Cin,Hs,Ws] host array (float32: real-valued frames, TAC_IN_F32).
+    Returns dict with unpacked spikes, v_trace, v_final, kernel id."""
     dev = torch.device("cuda:0")
+    dense = np.issubdtype(np.asarray(spikes).dtype, np.floating)
     T, B, Cin, Hs, Ws = spikes.shape
     H, W = (Hs // 2, Ws // 2) if pool2 else (Hs, Ws)
     Cout = w32.shape[0]
     desc = api.make_desc(T, B, Cin, H, W, Cout, K=K, beta=beta, theta=theta, mode=mode, stride=stride,
                          precision=precision, kernel=kernel,
-                         in_format=(api.TAC_IN_BITS_MAXPOOL2 if pool2 == "max" else api.TAC_IN_BITS_POOL2) if pool2 else api.TAC_IN_BITS)
+                         in_format=api.TAC_IN_F32 if dense else
+                         (api.TAC_IN_BITS_MAXPOOL2 if pool2 == "max" else api.TAC_IN_BITS_POOL2) if pool2 else api.TAC_IN_BITS)
     T_out, Ho, Wo = api.tac_out_shape(desc)
-    sp = torch.from_numpy(np_pack(spikes)).to(dev)
+    sp = torch.from_numpy(np.ascontiguousarray(spikes, dtype=np.float32) if dense else np_pack(spikes)).to(dev)
     wp = api.tac_prepare_weights(desc, torch.from_numpy(np.ascontiguousarray(w32, dtype=np.float32)).to(dev))
     bias_d = None if bias is None else torch.from_numpy(np.asarray(bias, dtype=np.float32)).to(dev)
     v = None

@@ -67,7 +67,7 @@ def test_packed_bytes():
     (dict(beta=1.5), api.TAC_ERR_BAD_PARAM), (dict(beta=float("nan")), api.TAC_ERR_BAD_PARAM),
     (dict(theta=0.0), api.TAC_ERR_BAD_PARAM), (dict(theta=float("inf")), api.TAC_ERR_BAD_PARAM),
     (dict(mode=7), api.TAC_ERR_BAD_PARAM), (dict(precision=3), api.TAC_ERR_BAD_PARAM),
-    (dict(in_format=3), api.TAC_ERR_BAD_PARAM), (dict(kernel=9), api.TAC_ERR_BAD_PARAM),
+    (dict(in_format=4), api.TAC_ERR_BAD_PARAM), (dict(kernel=9), api.TAC_ERR_BAD_PARAM),
     (dict(B=70000), api.TAC_ERR_BAD_SHAPE),
 ])
 def test_invalid_descriptions_are_rejected_before_any_launch(kw, status):

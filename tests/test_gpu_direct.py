@@ -185,3 +185,19 @@ def test_fold_batchnorm_on_device():
     gpu = run_gpu(s, wf.cpu().numpy(), K=2, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, bias=bf.cpu().numpy())
     ref = oracle.conv_lif(s, rw, rb, K=2, beta=0.9, theta=1.0, mode=oracle.TAC)
     assert np.abs(gpu["v_trace"] - ref[1]).max() < 1e-4
+
+
+@pytest.mark.parametrize("mode,K", [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 4), (api.TAC_PRESERVE, 2)])
+@pytest.mark.parametrize("precision", [api.TAC_FP32, api.TAC_BF16])
+def test_real_valued_input_frames(mode, K, precision):
+    # the continuous-valued first layer: float32 frames instead of packed spikes
+    r = np.random.Generator(np.random.PCG64(61 + K))
+    x = (r.random((8, 2, 3, 11, 37)) * (r.random((8, 2, 3, 11, 37)) < 0.4)).astype(np.float32)
+    w = synth.kaiming_normal(42, 16, 3) * np.float32(1.5)
+    par, g, ref = check_layer(x, w, K=K, beta=0.9, theta=1.0, mode=mode, precision=precision, kernel=api.TAC_KERNEL_DIRECT)
+    assert ref[0].sum() > 0
+    # frames of zeros and ones given as reals are the spike layer
+    s = (r.random((8, 2, 3, 11, 37)) < 0.3).astype(np.uint8)
+    a = run_gpu(s, w, K=K, beta=0.9, theta=1.0, mode=mode, precision=precision, kernel=api.TAC_KERNEL_DIRECT)
+    b = run_gpu(s.astype(np.float32), w, K=K, beta=0.9, theta=1.0, mode=mode, precision=precision, kernel=api.TAC_KERNEL_DIRECT)
+    assert np.array_equal(a["packed"], b["packed"]) and np.abs(a["v_trace"] - b["v_trace"]).max() < 1e-5

@@ -212,3 +212,20 @@ def test_conv_bn_lif_maxpool_blocks_stay_packed():
         print("block %d %s: %s rate %.3f" % (li + 1, "mfma" if g["kernel"] == api.TAC_KERNEL_MFMA else "direct", par, ref[0].mean()))
         x = ref[0]                                                               # unpooled spikes, pooled by the next loader
     assert x.shape == (4, 1, 128, 16, 32)
+
+
+# ---- real-valued input frames (the continuous-valued first layer, Sec. 4.2)
+
+@pytest.mark.parametrize("shape", [(2, 64, 22, 128, 2), (1, 32, 13, 28, 1), (2, 40, 9, 64, 1)])
+@pytest.mark.parametrize("mode,K", [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 2), (api.TAC_PRESERVE, 4), (api.TAC_COLLAPSE, 3)])
+def test_real_valued_frames_short_contraction_kernel(shape, mode, K):
+    Cin, Cout, H, W, stride = shape
+    r = _rng(4000 + Cin + Cout + H + W + K)
+    # normalised event counts: mostly zero, some values in (0, 1]
+    x = (r.random((12, 2, Cin, H, W)) * (r.random((12, 2, Cin, H, W)) < 0.3)).astype(np.float32)
+    w = synth.kaiming_normal(71, Cout, Cin) * np.float32(1.5)
+    bias = (r.standard_normal(Cout) * 0.1).astype(np.float32)
+    par, g, ref = check_layer(x, w, K=K, beta=0.9, theta=1.0, mode=mode, stride=stride, precision=api.TAC_BF16, bias=bias,
+                              expect_kernel=api.TAC_KERNEL_MFMA)
+    assert ref[0].sum() > 0
+    print("real-valued frames", shape, api.MODE_NAMES[mode], K, par)

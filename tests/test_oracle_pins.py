@@ -346,6 +346,20 @@ def test_exact_brute_force_real_valued_frames(mode, K, stride, pool2):
     assert np.array_equal(part[1], got[1].reshape(got[1].shape[0], -1))
 
 
+def test_bf16_rounding_of_real_valued_frames_is_the_same_in_all_three_loops():
+    # with K = 1 the aggregate is the frame itself: the per-step loop must round it like the other two
+    r = _rng(170)
+    x = r.random((4, 1, 2, 5, 6))
+    w = r.standard_normal((3, 2, 3, 3)) * 0.5
+    outs = [oracle.conv_lif(x, w, K=1, beta=0.9, theta=1.0, mode=m, round_a_bf16=True) for m in (PER_STEP, TAC, TAC_TP)]
+    for o in outs[1:]:
+        assert all(np.array_equal(a, b) for a, b in zip(outs[0], o))
+    plain = oracle.conv_lif(x, w, K=1, beta=0.9, theta=1.0, mode=PER_STEP)
+    assert not np.array_equal(plain[1], outs[0][1])
+    ref = oracle.conv_lif(oracle.round_bf16(x), w, K=1, beta=0.9, theta=1.0, mode=PER_STEP)
+    assert np.array_equal(ref[1], outs[0][1])
+
+
 def test_real_valued_frames_reduce_to_spikes_and_scale_with_the_weights():
     r = _rng(160)
     s = r.integers(0, 2, size=(4, 2, 2, 6, 7)).astype(np.uint8)
