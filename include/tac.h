@@ -96,9 +96,12 @@ size_t tac_packed_bytes(int32_t T, int32_t B, int32_t C, int32_t H, int32_t W);
 
 /* Which kernel family tac_prepare_weights / tac_conv_lif will use for this
  * layer: TAC_KERNEL_DIRECT or TAC_KERNEL_MFMA, or a negative error.  Host only.
- * MFMA (bf16 implicit-GEMM on the matrix cores) needs precision = TAC_BF16 and
- * a shape in its supported set; everything else runs on the DIRECT kernel
- * (fp32 vector FMAs, any shape). */
+ * MFMA (bf16 implicit GEMM on the matrix cores) needs precision = TAC_BF16 and one of
+ *   - Cin a multiple of 16, Cout a multiple of 128, W = 32 or 64, packed-bit input (as it is or
+ *     with the max pool on load; stride 2 and the max pool only for groups of 1, 2 or 4 frames);
+ *   - Cin = 1 or 2, Cout <= 64, W <= 128 and at most 64 output pixels per row, packed-bit or
+ *     float32 input (first layers);
+ * everything else runs on the DIRECT kernel (fp32 vector FMAs, any shape, every input format). */
 int tac_select_kernel(const tac_layer_desc_t* desc);
 
 /* Size of the prepared-weight buffer for this layer.  0 on an invalid desc. */

@@ -18,15 +18,18 @@
 //
 // Per group of K frames and per chunk of 16 input channels, everything one chunk ahead of
 // the MFMAs that consume it:
-//   staging  the chunk's packed input words (16 cin x haloed rows x K frames) are copied
-//            global -> registers -> LDS, rows outside the image as zero words;
-//   loader   a lane reads the word that holds its input pixel (a two-address broadcast LDS
-//            read, all K frames of it at once), extracts its bit and accumulates the decay
-//            weight as a 24-bit fixed-point integer, one v_bfe + one v_mad per frame; the
-//            aggregate A_k (Eq. 2) is converted once, rounded to bf16 and written to LDS as
-//            [k-half][row][column][8 cin] with zero columns left and right as the padding
-//            (for stride 2 the even and the odd columns are stored apart, so that a fragment
-//            read is contiguous again); it is never written to HBM;
+//   staging  the chunk's packed input words (16 cin x haloed rows x K frames) go global ->
+//            registers -> LDS, rows outside the image as zero words; on the way the thread that
+//            holds the K frame words of one (cin, row, word) transposes them into per-pixel
+//            K-bit fields ("class words", see stage_store), optionally after a 2 x 2 max pool;
+//   loader   a lane reads the class words that hold its input pixel for 4 channels (one
+//            16-byte LDS read), extracts the pixel's K frame bits with one v_bfe and reads the
+//            aggregate A_k (Eq. 2), already rounded to bf16, from a 2^K-entry table in LDS
+//            (K = 16: two 8-bit tables, added before the rounding; one frame: the bit itself;
+//            other K: bit by bit); A_k goes to LDS as [k-half][row][column][8 cin] with zero
+//            columns left and right as the padding (for stride 2 the even and the odd columns
+//            are stored apart, so that a fragment read is contiguous again); it is never
+//            written to HBM;
 //   weights  the chunk's 9 taps x 128 cout x 16 cin, pre-arranged in MFMA operand order, are
 //            copied global -> LDS without passing through registers;
 //   MFMA     9 taps x 8 MFMAs per wave, operands read from LDS as 16-byte fragments; im2col
@@ -34,9 +37,10 @@
 // After the last chunk: LIF epilogue on the accumulators (one step for TAC / per-step, K
 // steps with the same Y_k for TAC-TP), ballot, packed stores.
 //
-// Fixed point: the aggregate is formed as A' = sum_j bit_j * round(beta^(K-1-j) 2^23), an
-// integer below 2^28, and the prepared weights carry the factor 2^-23 (a power of two, so
-// the bf16 rounding of both operands is unchanged and the products are the same).
+// Fixed point: the aggregate (table entry) is A' = sum_j bit_j * round(beta^(K-1-j) 2^23), an
+// integer below 2^28, converted once to fp32 and rounded to bf16, and the prepared weights carry
+// the factor 2^-23 (a power of two, so the bf16 rounding of both operands is unchanged and the
+// products are the same).
 #include "tac_mfma_common.h"
 
 namespace tac {
