@@ -29,8 +29,10 @@ constexpr int kSmallMaxW = 128;                // input width limit (4 words per
 constexpr int kSmallMaxWo = 64;                // output width limit (2 MFMA column blocks)
 constexpr int kSmallWordRegs = 9;              // >= Cin * rows * 4 words * K / 256 for Cin 2, 9 rows, K 32
 
-template <int CIN, int S, int NMC, bool TRACE>
-__global__ __launch_bounds__(kSmallThreads) void small_kernel(const MfmaParams p) {
+// DENSE: real-valued input frames.  Two waves per SIMD are asked for (256 registers each): the
+// gather and the LIF step of one wave then overlap the other's.
+template <int CIN, int S, int NMC, bool TRACE, bool DENSE>
+__global__ __launch_bounds__(kSmallThreads, TRACE ? 1 : 2) void small_kernel(const MfmaParams p) {
   constexpr int kRowsIn = (kSmallRows - 1) * S + 3;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -49,7 +51,7 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(const MfmaParams p
   // LDS: raw words [cin][row][word][frame], aggregate tile bf16 [cin][row][WP] followed by one
   // zero element (the target of the contraction slots beyond 9 * Cin), bias
   uint32_t* const words = reinterpret_cast<uint32_t*>(lds);
-  const int n_words = p.dense ? 0 : CIN * kRowsIn * WW * K;   // real-valued frames are not staged
+  const int n_words = DENSE ? 0 : CIN * kRowsIn * WW * K;     // real-valued frames are not staged
   uint16_t* const a_tile = reinterpret_cast<uint16_t*>(lds + ((n_words * 4 + 15) & ~15));
   const int n_a = CIN * kRowsIn * WP;
   float* const bias_lds = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(a_tile) + (((n_a + 1) * 2 + 15) & ~15));
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(const MfmaParams p
   // sample; rows outside the image keep the offset of a valid row and are masked
   uint32_t doff[kSmallWordRegs];
   uint32_t dkeep = 0;
-  if (p.dense) {
+  if constexpr (DENSE) {
 #pragma unroll
     for (int l = 0; l < kSmallWordRegs; ++l) {
       const int e = tid + l * kSmallThreads;
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(const MfmaParams p
     for (int l = 0; l < kSmallWordRegs; ++l)
       if (tid + l * kSmallThreads < n_words) wd[l] = base[goff[l]];
   };
-  load_words(0);
+  if constexpr (!DENSE) load_words(0);
 
   // packed stores: lane (r << 2) | (hi << 1) | np of word[mc][0] holds channel
   // 32 mc + 8 (r / 4) + 4 hi + r % 4, word np of the row
@@ -187,10 +189,10 @@ __global__ __launch_bounds__(kSmallThreads) void small_kernel(const MfmaParams p
         words[rem * K + j] = (keep >> l) & 1u ? wd[l] : 0u;
       }
     }
-    if (g + 1 < p.G) load_words(g + 1);
+    if (!DENSE && g + 1 < p.G) load_words(g + 1);
     __syncthreads();
     // ---- 2. aggregate (Eq. 2), one rounding to bf16
-    if (p.dense) {
+    if constexpr (DENSE) {
       // real-valued frames: weighted sum in double (products and sums rounded one by one), then
       // fp32, then bf16; all of a thread's elements advance together so that their loads overlap
       const float* base = reinterpret_cast<const float*>(p.spikes) + (((size_t)g * K) * p.B + b) * CIN * ((size_t)p.H * p.W);
@@ -307,10 +309,17 @@ template <int CIN, int S, int NMC>
 hipError_t small_launch_t(const MfmaParams& mp, hipStream_t s) {
   const dim3 grid(((mp.Ho + kSmallRows - 1) / kSmallRows) * mp.B);
   const size_t lds = small_lds_bytes(CIN, S, mp.W, mp.K, NMC);
-  if (mp.v_trace)
-    hipLaunchKernelGGL((small_kernel<CIN, S, NMC, true>), grid, dim3(kSmallThreads), lds, s, mp);
-  else
-    hipLaunchKernelGGL((small_kernel<CIN, S, NMC, false>), grid, dim3(kSmallThreads), lds, s, mp);
+  if (mp.dense) {
+    if (mp.v_trace)
+      hipLaunchKernelGGL((small_kernel<CIN, S, NMC, true, true>), grid, dim3(kSmallThreads), lds, s, mp);
+    else
+      hipLaunchKernelGGL((small_kernel<CIN, S, NMC, false, true>), grid, dim3(kSmallThreads), lds, s, mp);
+  } else {
+    if (mp.v_trace)
+      hipLaunchKernelGGL((small_kernel<CIN, S, NMC, true, false>), grid, dim3(kSmallThreads), lds, s, mp);
+    else
+      hipLaunchKernelGGL((small_kernel<CIN, S, NMC, false, false>), grid, dim3(kSmallThreads), lds, s, mp);
+  }
   return hipGetLastError();
 }
 
