@@ -65,7 +65,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=15)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg3", "cfg5"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--mode", default="TAC", choices=["per_step", "TAC", "TAC_TP"])
     ap.add_argument("--K", type=int, default=4)
     ap.add_argument("--rate", type=float, default=None, help="firing rate of the Bernoulli input (cfg5)")
@@ -89,6 +89,8 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     wl = synth.WORKLOADS[args.workload]
+    if len(wl.layers) > 1:
+        return bench_stack(args, wl, dev)
     L = wl.layers[0]
     B = args.batch or wl.B
     T = wl.T
@@ -231,6 +233,114 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
+
+
+def bench_stack(args, wl, dev):
+    """Multi-layer workloads (cfg2, cfg4): one step = all layers of the stack over the whole input,
+    every inter-layer tensor packed bits in HBM, each layer fed the spikes the layer before wrote."""
+    import torch
+    from paper_2603_13810_amd import api
+    MODE = {"per_step": api.TAC_PER_STEP, "TAC": api.TAC_COLLAPSE, "TAC_TP": api.TAC_PRESERVE}
+    mode = MODE[args.mode]
+    B, T0 = args.batch or wl.B, wl.T
+    dense = wl.make_spikes(B=B)
+    x0 = torch.empty((T0, B, wl.C, wl.H, (wl.W + 31) // 32), dtype=torch.int32, device=dev)
+    for t in range(T0):
+        api.tac_pack_spikes(torch.from_numpy(dense[t]).to(dev), x0[t])
+    layers, T, H, W, flops = [], T0, wl.H, wl.W, 0.0
+    for li, L in enumerate(wl.layers):
+        if L.pool2_in:
+            H, W = H // 2, W // 2
+        K = args.K if (mode != api.TAC_PER_STEP and T % args.K == 0) else 1
+        d = api.make_desc(T, B, L.Cin, H, W, L.Cout, K=K, beta=wl.beta, theta=wl.theta, mode=mode, stride=L.stride,
+                          precision=api.TAC_BF16,
+                          in_format=api.TAC_IN_BITS_POOL2 if L.pool2_in else api.TAC_IN_BITS)
+        w32 = wl.make_weights(li)
+        wp = api.tac_prepare_weights(d, torch.from_numpy(w32).to(dev))
+        T_out, Ho, Wo = api.tac_out_shape(d)
+        out = torch.empty((T_out, B, L.Cout, Ho, (Wo + 31) // 32), dtype=torch.int32, device=dev)
+        Kg = 1 if mode == api.TAC_PER_STEP else K
+        fl = 2.0 * B * Ho * Wo * L.Cout * L.Cin * 9 * (T // Kg)
+        layers.append(dict(desc=d, wp=wp, out=out, w32=w32, K=K, flops=fl, stride=L.stride, pool2=L.pool2_in,
+                           kernel="mfma" if api.tac_select_kernel(d) == api.TAC_KERNEL_MFMA else "direct",
+                           shape="%d->%d %dx%d s%d T%d" % (L.Cin, L.Cout, H, W, L.stride, T)))
+        flops += fl
+        T, H, W = T_out, Ho, Wo
+
+    def step():
+        x = x0
+        for l in layers:
+            api.tac_conv_lif(l["desc"], x, l["wp"], None, None, l["out"])
+            x = l["out"]
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, b in evs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+    per_layer = []
+    x = x0
+    for l in layers:                                # each layer alone, same inputs
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            api.tac_conv_lif(l["desc"], x, l["wp"], None, None, l["out"])
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / 5
+        per_layer.append(dict(layer=l["shape"], kernel=l["kernel"], K=l["K"], ms=round(ms, 4),
+                              tflops=round(l["flops"] / (ms * 1e-3) / 1e12, 1),
+                              out_rate=round(float(_bit_rate(l["out"])), 4)))
+        x = l["out"]
+    dom = max(per_layer, key=lambda r: r["ms"])
+    dom_peak = PEAK_BF16_TFLOPS if dom["kernel"] == "mfma" else PEAK_FP32_TFLOPS
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        omode = {"per_step": oracle.PER_STEP, "TAC": oracle.TAC, "TAC_TP": oracle.TAC_TP}[args.mode]
+        n_s = min(B, 16) if wl.name == "cfg4" else B
+        xs = dense[:, :n_s]
+        nth = oracle.max_threads()
+        t0 = time.perf_counter()
+        for l in layers:
+            o = oracle.conv_lif(xs, l["w32"].astype(np.float64), K=l["K"], beta=wl.beta, theta=wl.theta, mode=omode,
+                                stride=l["stride"], pool2=l["pool2"], nthreads=nth)
+            xs = o[0]
+        dt = time.perf_counter() - t0
+        cpu = dict(value=round(n_s * T0 / dt, 3), unit="spike-frames/s", cores=nth, kind="oracle",
+                   sample="%d sample(s) x %d frames through all %d layers of %s, mode %s K=%d, %.1f s wall" %
+                          (n_s, T0, len(layers), wl.name, args.mode, args.K, dt))
+    line = {
+        "metric": "spike-frames/s through the layer stack", "value": round(B * T0 / (wall_ms * 1e-3), 1),
+        "unit": "spike-frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %d conv-LIF layers, B=%d, T=%d, beta=%.2f" % (wl.name, len(layers), B, T0, wl.beta),
+                   "mode": args.mode, "K": args.K, "layers": per_layer},
+        # the layer that takes longest decides which roof the stack is held against
+        "roofline": dict(bound="mfma" if dom["kernel"] == "mfma" else "alu",
+                         achieved=round(flops / (kern_ms * 1e-3) / 1e12, 2), peak=dom_peak, unit="TFLOP/s",
+                         frac=round(flops / (kern_ms * 1e-3) / 1e12 / dom_peak, 4), traffic=None,
+                         kernel_ms=round(kern_ms, 4), dominant_layer=dom["layer"]),
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+def _bit_rate(packed):
+    """Fraction of set bits in a packed tensor (pad bits are zero, so slightly below the firing rate)."""
+    import torch
+    x = packed.view(torch.uint8).to(torch.int16)
+    cnt = torch.zeros((), dtype=torch.int64, device=packed.device)
+    for sft in range(8):
+        cnt += ((x >> sft) & 1).sum()
+    return cnt.item() / (packed.numel() * 32)
 
 
 if __name__ == "__main__":
