@@ -81,9 +81,10 @@ struct Geo {
   static constexpr int kOutWords = (kWo + 31) / 32;          // packed words per output row
   static constexpr int kLdsA = 0;
   static constexpr int kLdsW = kLdsA + 2 * kABuf;
-  static constexpr int kLdsBias = kLdsW + 2 * kWBuf;
-  static constexpr int kLdsLut = kLdsBias + kCoutTile * 4;   // aggregate table, then two staging buffers
-  static constexpr int lds_bytes(int K) { return kLdsLut + lut_bytes(K) + 2 * kWordsPerFrame * K * 4; }
+  // two weight buffers of 9 taps x MC blocks of one KiB, bias, aggregate table, two staging buffers
+  __host__ __device__ static constexpr int lds_bias(int MC) { return kLdsW + 2 * 9 * MC * 1024; }
+  __host__ __device__ static constexpr int lds_lut(int MC) { return lds_bias(MC) + kCoutTile * 4; }
+  static constexpr int lds_bytes(int K, int MC = kMC) { return lds_lut(MC) + lut_bytes(K) + 2 * kWordsPerFrame * K * 4; }
   // LDS column (in 16-byte units) of padded pixel xp
   __host__ __device__ static constexpr int col(int xp) { return S == 1 ? xp : (xp & 1) * kXH + (xp >> 1); }
   // the loader pipeline has kSteps + 2 slots (slot i reads the words of step i, looks up step
@@ -392,9 +393,16 @@ __device__ __forceinline__ void lds_barrier() {
 // stores and their addresses do not weigh on the register allocation of the plain one).
 // MP: the input buffer holds the unpooled spikes of the layer before and a 2 x 2 max pool is
 // applied while staging (the staged words are pooled bits; everything after them is unchanged).
-template <int KT, int WIN, int S, bool TRACE, bool MP>
+template <int KT, int WIN, int S, bool TRACE, bool MP, int MC>
 __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   using G = Geo<WIN, S>;
+  // MC = 32-channel blocks per workgroup and wave: 4 (128 output channels), or 2 (64) for layers
+  // whose grid would otherwise leave compute units idle.  The prepared weights are laid out
+  // for 128-channel tiles either way; a 64-channel workgroup copies its half of each tap.
+  constexpr int kCT = MC * 32;                 // output channels per workgroup
+  constexpr int kWTapL = MC * 1024;            // bytes of one tap in LDS
+  constexpr int kWBufL = 9 * kWTapL;           // one weight buffer in LDS
+  constexpr int kLdsBias = G::lds_bias(MC), kLdsLut = G::lds_lut(MC);
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   constexpr int KMAX = KT > 0 ? KT : TAC_MAX_K;
   constexpr int NG = (G::kWordsPerFrame + kThreads - 1) / kThreads;     // staging groups per thread
@@ -412,16 +420,16 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     const int n_tiles = gridDim.x;
     if ((n_tiles & 7) == 0) tile = (tile & 7) * (n_tiles >> 3) + (tile >> 3);
   }
-  const int n_co_tiles = p.Cout / kCoutTile;
+  const int n_co_tiles = p.Cout / kCT;
   const int y0 = (tile % p.row_tiles) * G::kTileRows;          // first output row of the tile
   const int co_tile = (tile / p.row_tiles) % n_co_tiles;
   const int b = tile / (p.row_tiles * n_co_tiles);
   const int NC = p.Cin / kChunk;
   const int n = lane & 31, h = lane >> 5;
   const int Ho = p.Ho;
-  const int co_wave = co_tile * kCoutTile;
+  const int co_wave = co_tile * kCT;
   const int total = p.G * NC;
-  uint8_t* const lut = lds + G::kLdsLut;
+  uint8_t* const lut = lds + kLdsLut;
   uint8_t* const words0 = lut + lut_bytes(KT);
   const int words_bytes = G::kWordsPerFrame * K * 4;
   const int oy_wave = y0 + wave * G::kWaveRows;                // first output row of this wave
@@ -433,8 +441,8 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     const int c = side ? G::col(WIN + 1) : G::col(0);
     *reinterpret_cast<u32x4*>(lds + G::kLdsA + bb * G::kABuf + hh * G::kAHalf + (rr * G::kXP + c) * 16) = u32x4{0, 0, 0, 0};
   }
-  if (tid < kCoutTile)
-    reinterpret_cast<float*>(lds + G::kLdsBias)[tid] = p.bias ? p.bias[co_tile * kCoutTile + tid] : 0.f;
+  if (tid < kCT)
+    reinterpret_cast<float*>(lds + kLdsBias)[tid] = p.bias ? p.bias[co_tile * kCT + tid] : 0.f;
 
   // the lane's two pixels (np = 0, 1): local output row, column, validity
   const size_t plane = (size_t)Ho * G::kWo;                    // elements per (b, cout)
@@ -449,10 +457,10 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   const size_t v_wave = ((size_t)b * p.Cout + co_wave) * plane + (size_t)oy_wave * G::kWo;
 
   // membrane, MFMA result layout: register r of tile (mc, np), lane -> cout = 32 mc + 8 (r/4) + 4 h + r%4
-  float V[kMC][2][16];
-  f32x16 acc[kMC][2];
+  float V[MC][2][16];
+  f32x16 acc[MC][2];
 #pragma unroll
-  for (int mc = 0; mc < kMC; ++mc)
+  for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
     for (int np = 0; np < 2; ++np)
 #pragma unroll
@@ -463,7 +471,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     static_for<0, 2>([&](auto np_) {
       constexpr int np = decltype(np_)::value;
       if (lg.ok[np]) {
-        static_for<0, kMC>([&](auto mc_) { static_for<0, 16>([&](auto r_) {
+        static_for<0, MC>([&](auto mc_) { static_for<0, 16>([&](auto r_) {
           constexpr int mc = decltype(mc_)::value, r = decltype(r_)::value;
           V[mc][np][r] = *reinterpret_cast<const float*>(vb + (size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane * 4 + lg.v_off[np]);
         }); });
@@ -496,16 +504,27 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
       }
     }
   };
-  // weights of a chunk: global -> LDS without passing through registers.  Each wave moves 9
-  // consecutive one-KiB blocks of the 36, lane l its 16 bytes of a block; four blocks share one
-  // address (global and LDS) and differ in the instruction's immediate offset.
-  const uint32_t w_lane_off = (uint32_t)(wave * (kWBlocks * 1024)) + (uint32_t)lane * 16u;
+  // weights of a chunk: global -> LDS without passing through registers, lane l its 16 bytes of
+  // a one-KiB block (tap, 32-channel block).  128-channel tile: wave w moves the 9 consecutive
+  // blocks from 9 w on, four blocks share one address (global and LDS) and differ in the
+  // instruction's immediate offset.  64-channel tile: the tile's two blocks of every tap sit 4 KiB
+  // apart in global memory; wave w moves blocks w, w + 4, .. of the 18 (tap i / 2, block i % 2).
+  const uint32_t w_lane_off = (MC == 4 ? (uint32_t)(wave * (kWBlocks * 1024)) : 0u) + (uint32_t)lane * 16u;
+  const uint32_t w_half_off = (uint32_t)(co_tile & 1) * 2048u;       // MC == 2: which half of the 128-channel tile
   auto weights_to_lds = [&](const uint8_t* src, uint8_t* w_dst, auto i0_, auto i1_) {
     static_for<decltype(i0_)::value, decltype(i1_)::value>([&](auto i_) {
       constexpr int i = decltype(i_)::value;
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (i / 4) * 4096 + w_lane_off),
-                                       (lds_void_ptr)(w_dst + wave * (kWBlocks * 1024) + (i / 4) * 4096), 16,
-                                       (i % 4) * 1024, 0);
+      if constexpr (MC == 4) {
+        __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (i / 4) * 4096 + w_lane_off),
+                                         (lds_void_ptr)(w_dst + wave * (kWBlocks * 1024) + (i / 4) * 4096), 16,
+                                         (i % 4) * 1024, 0);
+      } else if constexpr (i < 5) {
+        const int blk = wave + 4 * i;              // 0 .. 17 (the fifth round only for waves 0 and 1)
+        if (i < 4 || wave < 2)
+          __builtin_amdgcn_global_load_lds(
+              (global_void_ptr)(src + (uint32_t)((blk >> 1) * 4096 + (blk & 1) * 1024) + w_half_off + w_lane_off),
+              (lds_void_ptr)(w_dst + blk * 1024), 16, 0, 0);
+      }
     });
   };
   constexpr std::integral_constant<int, 0> c0;
@@ -531,7 +550,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   const uint32_t* spk_n2;
   {
     cur.spk = p.spikes + ((size_t)b * p.Cin) * in_plane;
-    cur.w = p.w + (size_t)co_tile * NC * kWBuf;
+    cur.w = p.w + (size_t)(MC == 4 ? co_tile : co_tile >> 1) * NC * kWBuf;     // the 128-channel tile's weights
     cur.c = 0;
     cur.left = total - 1;
     weights_to_lds(cur.w, lds + G::kLdsW, c0, c9);
@@ -539,7 +558,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     stage_store<KT, KMAX, NG, MP>(wd, plan, words0, K);
     advance(cur);                               // chunk 1
     w_n1 = cur.w;
-    weights_to_lds(cur.w, lds + G::kLdsW + kWBuf, c0, c9);
+    weights_to_lds(cur.w, lds + G::kLdsW + kWBufL, c0, c9);
     stage_load<KMAX, NG, MP, G::kWW>(wd, plan, cur.spk, fstride, K);
     stage_store<KT, KMAX, NG, MP>(wd, plan, words0 + words_bytes, K);
     __syncthreads();
@@ -557,13 +576,13 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   // MFMA operand fragments, two slots: tap t multiplies slot t & 1 while slot (t+1) & 1 is
   // being fetched; tap 8 fetches the next chunk's tap-0 fragments into slot 1, which the next
   // chunk starts by moving to slot 0
-  bf16x8 wf[2][kMC], af[2][2];
+  bf16x8 wf[2][MC], af[2][2];
   auto fetch = [&](const uint8_t* a_buf, const uint8_t* w_buf, int tap, int slot) {
     const int ky = tap / 3, kx = tap % 3;
     const int tap_off = (ky * G::kXP + G::col(kx)) * 16;            // col(ox S + kx) = col(ox S) + col(kx)
 #pragma unroll
-    for (int mc = 0; mc < kMC; ++mc)
-      wf[slot][mc] = *reinterpret_cast<const bf16x8*>(w_buf + tap * kWTap + mc * 1024 + w_frag_off);
+    for (int mc = 0; mc < MC; ++mc)
+      wf[slot][mc] = *reinterpret_cast<const bf16x8*>(w_buf + tap * kWTapL + mc * 1024 + w_frag_off);
 #pragma unroll
     for (int np = 0; np < 2; ++np)
       af[slot][np] = *reinterpret_cast<const bf16x8*>(a_buf + a_frag_off[np] + tap_off);
@@ -579,14 +598,14 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   auto chunk_iteration = [&](int s) {
     const int PAR = s & 1;
     const uint8_t* a_cur = lds + G::kLdsA + PAR * G::kABuf;
-    const uint8_t* w_cur = lds + G::kLdsW + PAR * kWBuf;
+    const uint8_t* w_cur = lds + G::kLdsW + PAR * kWBufL;
     uint8_t* a_next = lds + G::kLdsA + (PAR ^ 1) * G::kABuf;
-    uint8_t* w_next = lds + G::kLdsW + (PAR ^ 1) * kWBuf;
+    uint8_t* w_next = lds + G::kLdsW + (PAR ^ 1) * kWBufL;
     const uint8_t* words_next = words0 + (PAR ^ 1) * words_bytes;    // words of chunk s+1 (read now)
     uint8_t* words_nn = words0 + PAR * words_bytes;                  // words of chunk s+2 (written at tap 7)
     StepRegs<KT> sr;
 #pragma unroll
-    for (int mc = 0; mc < kMC; ++mc) wf[0][mc] = wf[1][mc];
+    for (int mc = 0; mc < MC; ++mc) wf[0][mc] = wf[1][mc];
 #pragma unroll
     for (int np = 0; np < 2; ++np) af[0][np] = af[1][np];
 #pragma unroll
@@ -618,7 +637,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
         fetch(a_cur, w_cur, tap + 1, slot ^ 1);
       }
 #pragma unroll
-      for (int mc = 0; mc < kMC; ++mc)
+      for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
         for (int np = 0; np < 2; ++np)
           acc[mc][np] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][mc], af[slot][np], acc[mc][np], 0, 0, 0);
@@ -642,7 +661,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
         constexpr int kValuPerMfma = (KT == 16 ? 4 : 2) * G::kSlotsPerTap;
         constexpr int kDsPerMfma = (G::kSlotsPerTap == 1 && KT != 16) ? 2 : 3;
 #pragma unroll
-        for (int i = 0; i < 2 * kMC; ++i) {
+        for (int i = 0; i < 2 * MC; ++i) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
           __builtin_amdgcn_sched_group_barrier(0x100, kDsPerMfma, 0);
           __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);
@@ -688,7 +707,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     // itself keeps in flight.
     __builtin_amdgcn_s_waitcnt(0x0f70);         // vmcnt(0), other counters untouched
 #pragma unroll
-    for (int mc = 0; mc < kMC; ++mc)
+    for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
       for (int np = 0; np < 2; ++np)
 #pragma unroll
@@ -697,10 +716,10 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     for (int c = 0; c < NC; ++c, ++s) chunk_iteration(s);
 
     // ---- LIF epilogue on Y_k = acc + bias
-    const float* bias_lds = reinterpret_cast<const float*>(lds + G::kLdsBias);
+    const float* bias_lds = reinterpret_cast<const float*>(lds + kLdsBias);
     if (p.bias) {
 #pragma unroll
-      for (int mc = 0; mc < kMC; ++mc)
+      for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const float bv = bias_lds[mc * 32 + 8 * (r >> 2) + 4 * h + (r & 3)];
@@ -712,23 +731,23 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     const LaneGeom lg = lane_geom<G>(lane, oy_wave, Ho, plane, p.theta);
     for (int j = 0; j < p.n_lif; ++j) {
       const size_t step = (size_t)g * p.n_lif + j;
-      uint32_t word[kMC][2];
+      uint32_t word[MC][2];
 #pragma unroll
-      for (int mc = 0; mc < kMC; ++mc) word[mc][0] = word[mc][1] = 0u;
+      for (int mc = 0; mc < MC; ++mc) word[mc][0] = word[mc][1] = 0u;
       if constexpr (TRACE) {
         float* tl = p.v_trace + step * ((size_t)p.B * p.Cout * plane) + v_wave;
         size_t plane_l = plane;
         asm volatile("" : "+s"(plane_l));       // keep the trace addresses out of the loop preheader
-        lif_step<kMC, G::kWo, true>(V, acc, p.decay, p.theta, lg, word, tl, plane_l);
+        lif_step<MC, G::kWo, true>(V, acc, p.decay, p.theta, lg, word, tl, plane_l);
       } else {
-        lif_step<kMC, G::kWo, false>(V, acc, p.decay, p.theta, lg, word, nullptr, plane);
+        lif_step<MC, G::kWo, false>(V, acc, p.decay, p.theta, lg, word, nullptr, plane);
       }
       if (out_ok) {
         uint32_t* const o = out_wave + step * out_step;
 #pragma unroll
         for (int sr = 0; sr < kStoreRegs; ++sr)
 #pragma unroll
-          for (int mc = 0; mc < kMC; ++mc) o[(uint32_t)(mc * 32 + sr * 16) * out_plane + out_off] = word[mc][sr];
+          for (int mc = 0; mc < MC; ++mc) o[(uint32_t)(mc * 32 + sr * 16) * out_plane + out_off] = word[mc][sr];
       }
     }
   }
@@ -742,7 +761,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     static_for<0, 2>([&](auto np_) {
       constexpr int np = decltype(np_)::value;
       if (lg.ok[np]) {
-        static_for<0, kMC>([&](auto mc_) { static_for<0, 16>([&](auto r_) {
+        static_for<0, MC>([&](auto mc_) { static_for<0, 16>([&](auto r_) {
           constexpr int mc = decltype(mc_)::value, r = decltype(r_)::value;
           *reinterpret_cast<float*>(vb + (size_t)(mc * 32 + 8 * (r >> 2) + (r & 3)) * plane_l * 4 + lg.v_off[np]) = V[mc][np][r];
         }); });
@@ -774,23 +793,35 @@ __global__ void mfma_prepare_kernel(const float* __restrict__ w, uint32_t* __res
   out[i] = pack_bf16(a, bb);
 }
 
-template <int KT, int WIN, int S, bool TRACE, bool MP>
-hipError_t launch_traced(const MfmaParams& mp, hipStream_t s) {
+template <int KT, int WIN, int S, bool TRACE, bool MP, int MC>
+hipError_t launch_tile(const MfmaParams& mp, hipStream_t s) {
   using G = Geo<WIN, S>;
-  constexpr int lds = G::lds_bytes(KT > 0 ? KT : TAC_MAX_K);
+  constexpr int lds = G::lds_bytes(KT > 0 ? KT : TAC_MAX_K, MC);
   static_assert(lds <= kLdsLimit, "tile does not fit the LDS");
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<KT, WIN, S, TRACE, MP>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<KT, WIN, S, TRACE, MP, MC>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   MfmaParams q = mp;
   q.row_tiles = (mp.Ho + G::kTileRows - 1) / G::kTileRows;
-  const dim3 grid(q.row_tiles * (mp.Cout / kCoutTile) * mp.B);
-  hipLaunchKernelGGL((mfma_kernel<KT, WIN, S, TRACE, MP>), grid, dim3(kThreads), lds, s, q);
+  const dim3 grid(q.row_tiles * (mp.Cout / (MC * 32)) * mp.B);
+  hipLaunchKernelGGL((mfma_kernel<KT, WIN, S, TRACE, MP, MC>), grid, dim3(kThreads), lds, s, q);
   return hipGetLastError();
+}
+
+// 64-channel tiles when 128-channel tiles would give fewer workgroups than the chip has compute
+// units (small batches, deep layers); not combined with the max pool on load.
+constexpr int kComputeUnits = 256;
+template <int KT, int WIN, int S, bool TRACE, bool MP>
+hipError_t launch_traced(const MfmaParams& mp, hipStream_t s) {
+  if constexpr (!MP) {
+    const int row_tiles = (mp.Ho + Geo<WIN, S>::kTileRows - 1) / Geo<WIN, S>::kTileRows;
+    if ((long long)row_tiles * (mp.Cout / kCoutTile) * mp.B < kComputeUnits) return launch_tile<KT, WIN, S, TRACE, MP, 2>(mp, s);
+  }
+  return launch_tile<KT, WIN, S, TRACE, MP, 4>(mp, s);
 }
 
 template <int KT, int WIN, int S>

@@ -6,6 +6,7 @@ import torch
 from paper_2603_13810_amd import api, synth
 
 from gpu_util import check_layer, run_gpu, run_oracle
+from parity_util import compare
 
 pytestmark = pytest.mark.gpu
 
@@ -229,3 +230,28 @@ def test_real_valued_frames_short_contraction_kernel(shape, mode, K):
                               expect_kernel=api.TAC_KERNEL_MFMA)
     assert ref[0].sum() > 0
     print("real-valued frames", shape, api.MODE_NAMES[mode], K, par)
+
+
+# ---- tile choice: 64 output channels per workgroup on small grids, 128 on grids that fill the chip
+
+@pytest.mark.parametrize("W,stride,H,reps", [(64, 1, 10, 48), (32, 1, 11, 72), (64, 2, 21, 72), (32, 2, 35, 136)])
+@pytest.mark.parametrize("mode,K", [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 4), (api.TAC_PRESERVE, 2)])
+def test_full_grid_uses_128_channel_tiles(W, stride, H, reps, mode, K):
+    # the other tests have a handful of workgroups and get 64-channel tiles; here the same two
+    # samples are repeated until the 128-channel grid has at least 256 workgroups
+    r = _rng(5000 + W + stride + H + K)
+    s = (r.random((8, 2, 32, H, W)) < 0.15).astype(np.uint8)
+    w = synth.kaiming_normal(81, 128, 32)
+    bias = (r.standard_normal(128) * 0.1).astype(np.float32)
+    kw = dict(K=K, beta=0.9, theta=1.0, mode=mode, stride=stride, bias=bias)
+    small = run_gpu(s, w, precision=api.TAC_BF16, **kw)           # 64-channel tiles
+    ref = run_oracle(s, w, quantised=True, **kw)
+    par = compare(ref[0], ref[1], small["spikes"], small["v_trace"], 1.0, 1e-3)
+    assert par.ok, par
+    big = run_gpu(np.tile(s, (1, reps, 1, 1, 1)), w, precision=api.TAC_BF16, **kw)        # 128-channel tiles
+    rows = {64: 4, 32: 8, 16: 16}[W // stride]
+    assert (-(-small["spikes"].shape[-2] // rows)) * 2 * reps >= 256
+    for i in range(0, 2 * reps, 2):
+        # same operands, same summation order within a tile: the two tile sizes agree bit for bit
+        assert np.array_equal(big["packed"][:, i:i + 2], small["packed"]), i
+    assert np.array_equal(big["v_trace"][:, :2], small["v_trace"])
