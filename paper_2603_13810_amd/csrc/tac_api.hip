@@ -125,6 +125,7 @@ int tac_conv_lif(const tac_layer_desc_t* desc, const void* input, const void* w_
   p.Wo = (desc->W + 2 - 3) / desc->stride + 1;
   p.pool2 = desc->in_format == TAC_IN_BITS_POOL2 ? 1 : (desc->in_format == TAC_IN_BITS_MAXPOOL2 ? 2 : 0);
   p.dense = desc->in_format == TAC_IN_F32;
+  p.mfma_kind = kern == TAC_KERNEL_MFMA ? tac::mfma_kind(*desc) : 0;
   p.Hs = p.pool2 ? 2 * desc->H : desc->H;
   p.Wwi = ((p.pool2 ? 2 * desc->W : desc->W) + 31) / 32;
   p.Wwo = (p.Wo + 31) / 32;

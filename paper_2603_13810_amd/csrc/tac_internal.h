@@ -23,6 +23,7 @@ struct LayerParams {
   int G;                    // groups = T / K = convolution stages
   int n_lif;                // LIF steps per group: K for TAC-TP, else 1
   int pool2;                // input is unpooled: 1 = 2x2 mean pool while loading, 2 = 2x2 max pool
+  int mfma_kind;            // which MFMA kernel (see mfma_kind), 0 for the direct kernel
   int dense;                // input is float32 frames [T][B][Cin][H][W], not packed bits
   int bf16;                 // round A_k to bf16
   float decay;              // membrane decay per LIF step: beta^K for TAC, else beta
@@ -41,6 +42,13 @@ bool mfma_supported(const tac_layer_desc_t& d);
 size_t mfma_weight_bytes(const tac_layer_desc_t& d);
 hipError_t mfma_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s);
 hipError_t mfma_launch(const LayerParams& p, hipStream_t s);
+// its member for the shapes in between (Cin a multiple of 8 up to 64, widths up to 128, any pool on load)
+bool mfma_mid_supported(const tac_layer_desc_t& d);
+size_t mfma_mid_weight_bytes(const tac_layer_desc_t& d);
+hipError_t mfma_mid_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s);
+hipError_t mfma_mid_launch(const LayerParams& p, hipStream_t s);
+// which member takes a layer: 0 none, 1 large, 2 short contraction, 3 in between
+int mfma_kind(const tac_layer_desc_t& d);
 // its member for short contractions (Cin * 9 <= 32)
 bool mfma_small_supported(const tac_layer_desc_t& d);
 size_t mfma_small_weight_bytes(const tac_layer_desc_t& d);

@@ -879,14 +879,24 @@ static bool large_supported(const tac_layer_desc_t& d) {
   return d.stride == 2 && (K == 1 || K == 2 || K == 4);     // LDS room of the stride-2 tiles
 }
 
-bool mfma_supported(const tac_layer_desc_t& d) { return large_supported(d) || mfma_small_supported(d); }
+int mfma_kind(const tac_layer_desc_t& d) {
+  if (large_supported(d)) return 1;
+  if (mfma_small_supported(d)) return 2;
+  if (mfma_mid_supported(d)) return 3;
+  return 0;
+}
+
+bool mfma_supported(const tac_layer_desc_t& d) { return mfma_kind(d) != 0; }
 
 size_t mfma_weight_bytes(const tac_layer_desc_t& d) {
-  return large_supported(d) ? (size_t)d.Cout * d.Cin * 9 * 2 : mfma_small_weight_bytes(d);
+  const int kind = mfma_kind(d);
+  return kind == 1 ? (size_t)d.Cout * d.Cin * 9 * 2 : (kind == 2 ? mfma_small_weight_bytes(d) : mfma_mid_weight_bytes(d));
 }
 
 hipError_t mfma_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s) {
-  if (!large_supported(d)) return mfma_small_prepare(d, w_oihw, w_prepared, s);
+  const int kind = mfma_kind(d);
+  if (kind == 2) return mfma_small_prepare(d, w_oihw, w_prepared, s);
+  if (kind == 3) return mfma_mid_prepare(d, w_oihw, w_prepared, s);
   const int total = d.Cout * d.Cin * 9 / 2;
   hipLaunchKernelGGL(mfma_prepare_kernel, dim3((total + 255) / 256), dim3(256), 0, s, w_oihw,
                      static_cast<uint32_t*>(w_prepared), d.Cin, d.Cout);
@@ -894,7 +904,8 @@ hipError_t mfma_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_
 }
 
 hipError_t mfma_launch(const LayerParams& p, hipStream_t s) {
-  if (p.Cin % kChunk != 0) return mfma_small_launch(p, s);       // the short-contraction kernel
+  if (p.mfma_kind == 2) return mfma_small_launch(p, s);
+  if (p.mfma_kind == 3) return mfma_mid_launch(p, s);
   MfmaParams mp;
   mp.spikes = p.spikes; mp.w = static_cast<const uint8_t*>(p.w); mp.bias = p.bias; mp.v_inout = p.v_inout;
   mp.out = p.out; mp.v_trace = p.v_trace;

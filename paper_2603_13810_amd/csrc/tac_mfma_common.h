@@ -31,6 +31,7 @@ struct MfmaParams {
   float decay, theta;
   uint32_t wq[TAC_MAX_K];              // round(beta^(K-1-j) * 2^23)
   int dense;                           // short-contraction kernel: the input is float32 frames
+  int pool;                            // mid kernel: 2 x 2 pool on load, 1 mean, 2 max
   double wjd[TAC_MAX_K];               // beta^(K-1-j) in double, for real-valued frames
 };
 

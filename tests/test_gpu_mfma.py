@@ -104,14 +104,17 @@ def test_width_32_larger_K(K):
                 expect_kernel=api.TAC_KERNEL_MFMA)
 
 
-def test_stride_2_large_K_takes_the_direct_kernel():
-    # the stride-2 tiles have LDS room for 4 frames; larger groups run on the direct kernel
-    d = api.make_desc(16, 1, 16, 16, 64, 128, K=8, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, stride=2,
+def test_stride_2_large_K_leaves_the_large_kernel():
+    # the stride-2 tiles of the large kernel have LDS room for 4 frames; larger groups go to the
+    # kernel for the shapes in between (still on the matrix cores) and stay correct
+    r = _rng(1300)
+    s = (r.random((16, 1, 16, 12, 64)) < 0.2).astype(np.uint8)
+    w = synth.kaiming_normal(23, 128, 16)
+    check_layer(s, w, K=8, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, stride=2, precision=api.TAC_BF16,
+                expect_kernel=api.TAC_KERNEL_MFMA)
+    d = api.make_desc(16, 1, 128, 16, 64, 128, K=8, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, stride=2,
                       precision=api.TAC_BF16)
-    assert api.tac_select_kernel(d) == api.TAC_KERNEL_DIRECT
-    d = api.make_desc(16, 1, 16, 16, 64, 128, K=4, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, stride=2,
-                      precision=api.TAC_BF16)
-    assert api.tac_select_kernel(d) == api.TAC_KERNEL_MFMA
+    assert api.tac_select_kernel(d) == api.TAC_KERNEL_DIRECT      # 128 input channels: neither of them
 
 
 # ---- the short-contraction member of the family (Cin = 1 or 2: first layers)
@@ -183,8 +186,9 @@ def test_max_pool_on_load_limits():
     mk = lambda **kw: api.make_desc(8, 1, 32, 16, 64, 128, K=kw.pop("K", 2), beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE,
                                     stride=kw.pop("stride", 1), precision=api.TAC_BF16, in_format=api.TAC_IN_BITS_MAXPOOL2)
     assert api.tac_select_kernel(mk()) == api.TAC_KERNEL_MFMA
-    assert api.tac_select_kernel(mk(K=8)) == api.TAC_KERNEL_DIRECT
-    assert api.tac_select_kernel(mk(stride=2)) == api.TAC_KERNEL_DIRECT
+    # 32 input channels: the kernel for the shapes in between takes what the large one does not
+    assert api.tac_select_kernel(mk(K=8)) == api.TAC_KERNEL_MFMA
+    assert api.tac_select_kernel(mk(stride=2)) == api.TAC_KERNEL_MFMA
 
 
 def test_conv_bn_lif_maxpool_blocks_stay_packed():
@@ -255,3 +259,27 @@ def test_full_grid_uses_128_channel_tiles(W, stride, H, reps, mode, K):
         # same operands, same summation order within a tile: the two tile sizes agree bit for bit
         assert np.array_equal(big["packed"][:, i:i + 2], small["packed"]), i
     assert np.array_equal(big["v_trace"][:, :2], small["v_trace"])
+
+
+# ---- the kernel for the shapes in between (Cin a multiple of 8 up to 64, any pool on load)
+# (Cin, Cout, H, W, stride, pool)
+MID_SHAPES = [(32, 64, 14, 14, 1, True), (8, 32, 9, 50, 1, False), (16, 96, 11, 64, 2, False), (64, 24, 7, 20, 1, "max"),
+              (24, 64, 10, 128, 2, False), (40, 160, 6, 33, 1, True)]
+MID_MODES = [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 2), (api.TAC_PRESERVE, 4), (api.TAC_COLLAPSE, 3), (api.TAC_PRESERVE, 8)]
+
+
+@pytest.mark.parametrize("shape", MID_SHAPES)
+@pytest.mark.parametrize("mode,K", MID_MODES)
+def test_in_between_kernel(shape, mode, K):
+    Cin, Cout, H, W, stride, pool = shape
+    r = _rng(6000 + Cin + Cout + H + W + stride + K)
+    f = 2 if pool else 1
+    s = (r.random((24, 2, Cin, f * H, f * W)) < 0.12).astype(np.uint8)
+    w = synth.kaiming_normal(91, Cout, Cin) * np.float32(1.5)
+    bias = (r.standard_normal(Cout) * 0.1).astype(np.float32)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    v0 = (r.standard_normal((2, Cout, Ho, Wo)) * 0.3).astype(np.float32)
+    par, g, ref = check_layer(s, w, K=K, beta=0.9, theta=1.0, mode=mode, stride=stride, pool2=pool, precision=api.TAC_BF16,
+                              bias=bias, v0=v0, expect_kernel=api.TAC_KERNEL_MFMA, plain_stats=False)
+    assert ref[0].sum() > 0
+    print("in-between kernel", shape, api.MODE_NAMES[mode], K, par)
