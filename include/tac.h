@@ -101,7 +101,7 @@ size_t tac_packed_bytes(int32_t T, int32_t B, int32_t C, int32_t H, int32_t W);
  *     with the max pool on load; stride 2 and the max pool only for groups of 1, 2 or 4 frames);
  *   - Cin = 1 or 2, Cout <= 64, W <= 128 and at most 64 output pixels per row, packed-bit or
  *     float32 input (first layers);
- *   - Cin a multiple of 8 up to 64, W <= 128 and at most 64 output pixels per row, packed-bit input
+ *   - Cin a multiple of 8 up to 128 (tile of weights and aggregate tile within the LDS), W <= 128 and at most 64 output pixels per row, packed-bit input
  *     as it is or with either pool on load;
  * everything else runs on the DIRECT kernel (fp32 vector FMAs, any shape, every input format). */
 int tac_select_kernel(const tac_layer_desc_t* desc);

@@ -1,4 +1,4 @@
-// MFMA kernel for the layers in between: input channels a multiple of 8 up to 64, any width up
+// MFMA kernel for the layers in between: input channels a multiple of 8 up to 128, any width up
 // to 128 with at most 64 output pixels per row, any input format made of bits (as they are, or
 // through the 2 x 2 mean or max pool on load), output channels in tiles of 32 or 64.  It takes the
 // shapes the large kernel does not (widths other than 32 / 64, fewer than 128 output channels,
@@ -24,7 +24,7 @@ namespace {
 
 constexpr int kMidThreads = 256;
 constexpr int kMidRows = 4;                    // output rows per workgroup = waves
-constexpr int kMidMaxW = 128, kMidMaxWo = 64, kMidMaxCin = 64;
+constexpr int kMidMaxW = 128, kMidMaxWo = 64, kMidMaxCin = 128;
 constexpr int kMidLdsLimit = 150 * 1024;
 
 struct MidLayout {
@@ -243,7 +243,10 @@ __global__ void mid_prepare_kernel(const float* __restrict__ w, uint32_t* __rest
   out[i] = pack_bf16(v[0], v[1]);
 }
 
-int mid_nmc(int Cout) { return Cout <= 32 ? 1 : 2; }
+// 64-channel tiles when the tile's weights and the aggregate tile fit the LDS together, else 32
+int mid_nmc(int Cin, int S, int W, int Cout) {
+  return (Cout > 32 && mid_layout(Cin, S, W, 2).total <= kMidLdsLimit) ? 2 : 1;
+}
 
 template <int S, int NMC>
 hipError_t mid_launch_t(const MfmaParams& mp, hipStream_t s) {
@@ -266,17 +269,17 @@ bool mfma_mid_supported(const tac_layer_desc_t& d) {
   if (d.precision != TAC_BF16 || d.in_format == TAC_IN_F32) return false;
   if (d.Cin % 8 != 0 || d.Cin > kMidMaxCin) return false;
   if (d.W > kMidMaxW || (d.W + 2 - 3) / d.stride + 1 > kMidMaxWo) return false;
-  return mid_layout(d.Cin, d.stride, d.W, mid_nmc(d.Cout)).total <= kMidLdsLimit;
+  return mid_layout(d.Cin, d.stride, d.W, mid_nmc(d.Cin, d.stride, d.W, d.Cout)).total <= kMidLdsLimit;
 }
 
 size_t mfma_mid_weight_bytes(const tac_layer_desc_t& d) {
-  const int nmc = mid_nmc(d.Cout);
+  const int nmc = mid_nmc(d.Cin, d.stride, d.W, d.Cout);
   const int tiles = (d.Cout + nmc * 32 - 1) / (nmc * 32);
   return (size_t)tiles * mid_layout(d.Cin, d.stride, d.W, nmc).w_bytes;
 }
 
 hipError_t mfma_mid_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s) {
-  const int nmc = mid_nmc(d.Cout);
+  const int nmc = mid_nmc(d.Cin, d.stride, d.W, d.Cout);
   const int nks = (9 * d.Cin + 15) / 16;
   const int tiles = (d.Cout + nmc * 32 - 1) / (nmc * 32);
   const int total = tiles * nks * nmc * 64 * 4;
@@ -297,7 +300,7 @@ hipError_t mfma_mid_launch(const LayerParams& p, hipStream_t s) {
     mp.wq[j] = j < p.K ? (uint32_t)(q + 0.5) : 0u;
     mp.wjd[j] = p.wjd[j];
   }
-  const int nmc = mid_nmc(p.Cout);
+  const int nmc = mid_nmc(p.Cin, p.stride, p.W, p.Cout);
   if (p.stride == 1) return nmc == 1 ? mid_launch_t<1, 1>(mp, s) : mid_launch_t<1, 2>(mp, s);
   return nmc == 1 ? mid_launch_t<2, 1>(mp, s) : mid_launch_t<2, 2>(mp, s);
 }

@@ -112,9 +112,9 @@ def test_stride_2_large_K_leaves_the_large_kernel():
     w = synth.kaiming_normal(23, 128, 16)
     check_layer(s, w, K=8, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, stride=2, precision=api.TAC_BF16,
                 expect_kernel=api.TAC_KERNEL_MFMA)
-    d = api.make_desc(16, 1, 128, 16, 64, 128, K=8, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, stride=2,
+    d = api.make_desc(16, 1, 256, 16, 64, 128, K=8, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, stride=2,
                       precision=api.TAC_BF16)
-    assert api.tac_select_kernel(d) == api.TAC_KERNEL_DIRECT      # 128 input channels: neither of them
+    assert api.tac_select_kernel(d) == api.TAC_KERNEL_DIRECT      # 256 input channels: neither of them
 
 
 # ---- the short-contraction member of the family (Cin = 1 or 2: first layers)
@@ -264,7 +264,7 @@ def test_full_grid_uses_128_channel_tiles(W, stride, H, reps, mode, K):
 # ---- the kernel for the shapes in between (Cin a multiple of 8 up to 64, any pool on load)
 # (Cin, Cout, H, W, stride, pool)
 MID_SHAPES = [(32, 64, 14, 14, 1, True), (8, 32, 9, 50, 1, False), (16, 96, 11, 64, 2, False), (64, 24, 7, 20, 1, "max"),
-              (24, 64, 10, 128, 2, False), (40, 160, 6, 33, 1, True)]
+              (24, 64, 10, 128, 2, False), (40, 160, 6, 33, 1, True), (128, 128, 16, 16, 1, "max"), (128, 64, 8, 8, 1, False)]
 MID_MODES = [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 2), (api.TAC_PRESERVE, 4), (api.TAC_COLLAPSE, 3), (api.TAC_PRESERVE, 8)]
 
 
