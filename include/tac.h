@@ -99,10 +99,9 @@ size_t tac_packed_bytes(int32_t T, int32_t B, int32_t C, int32_t H, int32_t W);
  * MFMA (bf16 implicit GEMM on the matrix cores) needs precision = TAC_BF16 and one of
  *   - Cin a multiple of 16, Cout a multiple of 128, W = 32 or 64, packed-bit input (as it is or
  *     with the max pool on load; stride 2 and the max pool only for groups of 1, 2 or 4 frames);
- *   - Cin = 1 or 2, Cout <= 64, W <= 128 and at most 64 output pixels per row, packed-bit or
- *     float32 input (first layers);
- *   - Cin a multiple of 8 up to 128 (tile of weights and aggregate tile within the LDS), W <= 128 and at most 64 output pixels per row, packed-bit input
- *     as it is or with either pool on load;
+ *   - Cin = 1 or 2, any Cout, W <= 128, packed-bit or float32 input (first layers);
+ *   - Cin a multiple of 8 up to 128 (tile of weights and aggregate tile within the LDS), W <= 128
+ *     and at most 64 output pixels per row, packed-bit input as it is or with either pool on load;
  * everything else runs on the DIRECT kernel (fp32 vector FMAs, any shape, every input format). */
 int tac_select_kernel(const tac_layer_desc_t* desc);
 

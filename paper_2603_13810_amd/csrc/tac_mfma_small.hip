@@ -7,8 +7,9 @@
 // from a small aggregate tile in LDS and feeds them as the B operand.  The weights (at most
 // 64 cout x 32) stay in registers for the whole call, the membrane V too.
 //
-// One workgroup = 4 wavefronts = 4 output rows of one sample, a wave owns one output row of
-// up to 64 pixels x up to 64 output channels (NMC x 2 MFMA tiles).  Per group of K frames:
+// One workgroup = 4 wavefronts = 4 output rows of one sample (2 rows when a row has more than 64
+// pixels) x a tile of up to 64 output channels; a wave owns 64 pixels of one output row x the
+// tile's channels (NMC x 2 MFMA tiles).  Per group of K frames:
 //   1. the packed words of the 3 S + 3 haloed input rows, K frames, Cin channels go
 //      global -> registers (requested one group ahead) -> LDS, rows outside the image as zeros;
 //   2. every thread forms its share of the aggregate A_k (Eq. 2) from those words, in the same
@@ -26,22 +27,30 @@ namespace {
 constexpr int kSmallThreads = 256;
 constexpr int kSmallRows = 4;                  // output rows per workgroup = waves
 constexpr int kSmallMaxW = 128;                // input width limit (4 words per row)
-constexpr int kSmallMaxWo = 64;                // output width limit (2 MFMA column blocks)
+constexpr int kSmallMaxWo = 128;               // output width limit (two waves of 2 MFMA column blocks)
 constexpr int kSmallWordRegs = 9;              // >= Cin * rows * 4 words * K / 256 for Cin 2, 9 rows, K 32
 
 // DENSE: real-valued input frames.  Two waves per SIMD are asked for (256 registers each): the
 // gather and the LIF step of one wave then overlap the other's.
-template <int CIN, int S, int NMC, bool TRACE, bool DENSE>
+// SEG: 64-pixel segments per output row (1: rows up to 64 pixels, 4 rows per workgroup; 2: rows up
+// to 128 pixels, 2 rows per workgroup, two waves side by side).
+template <int CIN, int S, int NMC, bool TRACE, bool DENSE, int SEG>
 __global__ __launch_bounds__(kSmallThreads, TRACE ? 1 : 2) void small_kernel(const MfmaParams p) {
-  constexpr int kRowsIn = (kSmallRows - 1) * S + 3;
+  constexpr int kRows = kSmallRows / SEG;        // output rows per workgroup
+  constexpr int kRowsIn = (kRows - 1) * S + 3;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, h = lane >> 5;
-  const int row_tiles = (p.Ho + kSmallRows - 1) / kSmallRows;
-  const int b = blockIdx.x / row_tiles;
-  const int y0 = (blockIdx.x - b * row_tiles) * kSmallRows;
-  const int oy = y0 + wave;
+  const int row_tiles = (p.Ho + kRows - 1) / kRows;
+  const int co_tiles = (p.Cout + NMC * 32 - 1) / (NMC * 32);
+  int bt = blockIdx.x;
+  const int y0 = (bt % row_tiles) * kRows; bt /= row_tiles;
+  const int co_tile = bt % co_tiles;
+  const int b = bt / co_tiles;
+  const int co0 = co_tile * (NMC * 32);          // first output channel of the workgroup's tile
+  const int wrow = wave / SEG, seg = wave % SEG; // the wave's row in the tile and its 64-pixel segment
+  const int oy = y0 + wrow;
   const int iy0 = y0 * S - 1;
   const int K = p.K;
   const int WW = (p.W + 31) >> 5;              // words per input row
@@ -57,7 +66,7 @@ __global__ __launch_bounds__(kSmallThreads, TRACE ? 1 : 2) void small_kernel(con
   float* const bias_lds = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(a_tile) + (((n_a + 1) * 2 + 15) & ~15));
 
   for (int i = tid; i <= n_a; i += kSmallThreads) a_tile[i] = 0;       // padding columns and the zero element
-  if (tid < NMC * 32) bias_lds[tid] = (p.bias && tid < p.Cout) ? p.bias[tid] : 0.f;
+  if (tid < NMC * 32) bias_lds[tid] = (p.bias && co0 + tid < p.Cout) ? p.bias[co0 + tid] : 0.f;
 
   // weights: [mc][k-step][lane][8] bf16, the MFMA A-operand fragments, kept in registers
   bf16x8 wf[NMC][2];
@@ -65,7 +74,7 @@ __global__ __launch_bounds__(kSmallThreads, TRACE ? 1 : 2) void small_kernel(con
   for (int mc = 0; mc < NMC; ++mc)
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
-      wf[mc][ks] = *reinterpret_cast<const bf16x8*>(p.w + ((mc * 2 + ks) * 64 + lane) * 16);
+      wf[mc][ks] = *reinterpret_cast<const bf16x8*>(p.w + (((co_tile * NMC + mc) * 2 + ks) * 64 + lane) * 16);
 
   // the lane's contraction slots kk = 16 ks + 8 h + i  ->  (tap, cin) = (kk / CIN, kk % CIN):
   // byte offset of that element of the filter window relative to the window's first element
@@ -85,14 +94,14 @@ __global__ __launch_bounds__(kSmallThreads, TRACE ? 1 : 2) void small_kernel(con
   const size_t plane = (size_t)p.Ho * p.Wo;
 #pragma unroll
   for (int np = 0; np < 2; ++np) {
-    const int ox = 32 * np + n;
+    const int ox = 64 * seg + 32 * np + n;
     lg.ok[np] = oy < p.Ho && ox < p.Wo;
     lg.theta[np] = lg.ok[np] ? p.theta : __builtin_inff();
     lg.v_off[np] = (uint32_t)((4 * h * plane + ox) * 4);
-    pix_base[np] = (uint32_t)(((wave * S) * WP + (lg.ok[np] ? ox : 0) * S) * 2);
+    pix_base[np] = (uint32_t)(((wrow * S) * WP + (lg.ok[np] ? ox : 0) * S) * 2);
   }
-  lg.co_lim = p.Cout - 4 * h;
-  const size_t v_wave = (size_t)b * p.Cout * plane + (size_t)oy * p.Wo;
+  lg.co_lim = p.Cout - co0 - 4 * h;
+  const size_t v_wave = ((size_t)b * p.Cout + co0) * plane + (size_t)oy * p.Wo;
 
   float V[NMC][2][16];
 #pragma unroll
@@ -173,8 +182,8 @@ __global__ __launch_bounds__(kSmallThreads, TRACE ? 1 : 2) void small_kernel(con
   const int st_r = lane >> 2, st_hi = (lane >> 1) & 1, st_np = lane & 1;
   const int st_co = 8 * (st_r >> 2) + 4 * st_hi + (st_r & 3);
   const size_t out_plane = (size_t)p.Ho * Wwo;
-  const size_t out_lane = ((size_t)b * p.Cout + st_co) * out_plane + (size_t)oy * Wwo + st_np;
-  const bool out_ok = oy < p.Ho && st_np < Wwo;
+  const size_t out_lane = ((size_t)b * p.Cout + co0 + st_co) * out_plane + (size_t)oy * Wwo + 2 * seg + st_np;
+  const bool out_ok = oy < p.Ho && 2 * seg + st_np < Wwo;
   const size_t out_step = (size_t)p.B * p.Cout * out_plane;
 
   for (int g = 0; g < p.G; ++g) {
@@ -261,7 +270,7 @@ __global__ __launch_bounds__(kSmallThreads, TRACE ? 1 : 2) void small_kernel(con
       if (out_ok) {
 #pragma unroll
         for (int mc = 0; mc < NMC; ++mc)
-          if (mc * 32 + st_co < p.Cout) p.out[step * out_step + out_lane + (size_t)mc * 32 * out_plane] = word[mc][0];
+          if (co0 + mc * 32 + st_co < p.Cout) p.out[step * out_step + out_lane + (size_t)mc * 32 * out_plane] = word[mc][0];
       }
     }
   }
@@ -281,7 +290,7 @@ __global__ __launch_bounds__(kSmallThreads, TRACE ? 1 : 2) void small_kernel(con
   }
 }
 
-// OIHW fp32 -> [mc][k-step][lane][8] bf16: lane l of block mc holds cout 32 mc + l % 32 and the
+// OIHW fp32 -> [32-cout block][k-step][lane][8] bf16: lane l of block mc holds cout 32 mc + l % 32 and the
 // contraction slots kk = 16 ks + 8 (l / 32) + i, slot kk = (tap kk / Cin, cin kk % Cin); slots
 // beyond 9 Cin and channels beyond Cout are zero.
 __global__ void small_prepare_kernel(const float* __restrict__ w, uint32_t* __restrict__ out, int Cin, int Cout, int nmc) {
@@ -298,53 +307,60 @@ __global__ void small_prepare_kernel(const float* __restrict__ w, uint32_t* __re
   out[i] = pack_bf16(v[0], v[1]);
 }
 
-size_t small_lds_bytes(int Cin, int S, int W, int K, int nmc) {
-  const int rows = (kSmallRows - 1) * S + 3, WW = (W + 31) / 32;
+size_t small_lds_bytes(int Cin, int S, int W, int K, int nmc, int seg) {
+  const int rows = (kSmallRows / seg - 1) * S + 3, WW = (W + 31) / 32;
   const size_t words = ((size_t)Cin * rows * WW * K * 4 + 15) & ~(size_t)15;
   const size_t a = (((size_t)Cin * rows * (W + 2) + 1) * 2 + 15) & ~(size_t)15;
   return words + a + (size_t)nmc * 32 * 4;
 }
 
-template <int CIN, int S, int NMC>
+template <int CIN, int S, int NMC, int SEG>
 hipError_t small_launch_t(const MfmaParams& mp, hipStream_t s) {
-  const dim3 grid(((mp.Ho + kSmallRows - 1) / kSmallRows) * mp.B);
-  const size_t lds = small_lds_bytes(CIN, S, mp.W, mp.K, NMC);
+  const int co_tiles = (mp.Cout + NMC * 32 - 1) / (NMC * 32);
+  const dim3 grid(((mp.Ho + kSmallRows / SEG - 1) / (kSmallRows / SEG)) * co_tiles * mp.B);
+  const size_t lds = small_lds_bytes(CIN, S, mp.W, mp.K, NMC, SEG);
   if (mp.dense) {
     if (mp.v_trace)
-      hipLaunchKernelGGL((small_kernel<CIN, S, NMC, true, true>), grid, dim3(kSmallThreads), lds, s, mp);
+      hipLaunchKernelGGL((small_kernel<CIN, S, NMC, true, true, SEG>), grid, dim3(kSmallThreads), lds, s, mp);
     else
-      hipLaunchKernelGGL((small_kernel<CIN, S, NMC, false, true>), grid, dim3(kSmallThreads), lds, s, mp);
+      hipLaunchKernelGGL((small_kernel<CIN, S, NMC, false, true, SEG>), grid, dim3(kSmallThreads), lds, s, mp);
   } else {
     if (mp.v_trace)
-      hipLaunchKernelGGL((small_kernel<CIN, S, NMC, true, false>), grid, dim3(kSmallThreads), lds, s, mp);
+      hipLaunchKernelGGL((small_kernel<CIN, S, NMC, true, false, SEG>), grid, dim3(kSmallThreads), lds, s, mp);
     else
-      hipLaunchKernelGGL((small_kernel<CIN, S, NMC, false, false>), grid, dim3(kSmallThreads), lds, s, mp);
+      hipLaunchKernelGGL((small_kernel<CIN, S, NMC, false, false, SEG>), grid, dim3(kSmallThreads), lds, s, mp);
   }
   return hipGetLastError();
 }
 
 template <int CIN, int S>
 hipError_t small_launch_n(const MfmaParams& mp, hipStream_t s) {
-  return mp.Cout <= 32 ? small_launch_t<CIN, S, 1>(mp, s) : small_launch_t<CIN, S, 2>(mp, s);
+  if (mp.Wo > 64) return mp.Cout <= 32 ? small_launch_t<CIN, S, 1, 2>(mp, s) : small_launch_t<CIN, S, 2, 2>(mp, s);
+  return mp.Cout <= 32 ? small_launch_t<CIN, S, 1, 1>(mp, s) : small_launch_t<CIN, S, 2, 1>(mp, s);
 }
 
 }  // namespace
 
 bool mfma_small_supported(const tac_layer_desc_t& d) {
   if (d.precision != TAC_BF16 || (d.in_format != TAC_IN_BITS && d.in_format != TAC_IN_F32)) return false;
-  if (d.Cin < 1 || d.Cin > 2 || d.Cout > 64) return false;
+  if (d.Cin < 1 || d.Cin > 2) return false;
   if (d.W > kSmallMaxW || (d.W + 2 - 3) / d.stride + 1 > kSmallMaxWo) return false;
   const int K = d.mode == TAC_PER_STEP ? 1 : d.K;
   // staged words of one group: 256 threads x kSmallWordRegs registers
-  const int rows = (kSmallRows - 1) * d.stride + 3;
+  const int Wo = (d.W + 2 - 3) / d.stride + 1;
+  const int rows = (kSmallRows / (Wo > 64 ? 2 : 1) - 1) * d.stride + 3;
   if (d.in_format == TAC_IN_F32) return true;
   return d.Cin * rows * ((d.W + 31) / 32) * K <= kSmallThreads * kSmallWordRegs;
 }
 
-size_t mfma_small_weight_bytes(const tac_layer_desc_t& d) { return (size_t)((d.Cout + 31) / 32) * 2 * 64 * 16; }
+size_t mfma_small_weight_bytes(const tac_layer_desc_t& d) {
+  const int nmc = d.Cout <= 32 ? 1 : 2;                        // blocks per tile; whole tiles are stored
+  return (size_t)((d.Cout + nmc * 32 - 1) / (nmc * 32)) * nmc * 2 * 64 * 16;
+}
 
 hipError_t mfma_small_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s) {
-  const int nmc = (d.Cout + 31) / 32;
+  const int per = d.Cout <= 32 ? 1 : 2;
+  const int nmc = (d.Cout + per * 32 - 1) / (per * 32) * per;   // 32-channel blocks, whole tiles
   const int total = nmc * 2 * 64 * 4;
   hipLaunchKernelGGL(small_prepare_kernel, dim3((total + 255) / 256), dim3(256), 0, s, w_oihw,
                      static_cast<uint32_t*>(w_prepared), d.Cin, d.Cout, nmc);

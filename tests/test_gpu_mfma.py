@@ -118,9 +118,11 @@ def test_stride_2_large_K_leaves_the_large_kernel():
 
 
 # ---- the short-contraction member of the family (Cin = 1 or 2: first layers)
-# (Cin, Cout, H, W, stride): ragged rows and widths, one and two 32-channel blocks, partial blocks
+# (Cin, Cout, H, W, stride): ragged rows and widths, one and two 32-channel blocks, partial blocks, several
+# channel tiles (Cout > 64), output rows of more than 64 pixels (two waves per row, odd row counts)
 SMALL_SHAPES = [(1, 8, 28, 28, 1), (1, 32, 13, 28, 1), (2, 64, 22, 128, 2), (2, 40, 9, 64, 1), (1, 64, 11, 50, 2),
-                (2, 24, 7, 33, 1), (2, 64, 6, 127, 2)]
+                (2, 24, 7, 33, 1), (2, 64, 6, 127, 2), (2, 128, 9, 128, 1), (2, 96, 7, 100, 1), (1, 160, 5, 70, 2),
+                (1, 16, 6, 65, 1)]
 SMALL_MODES = [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 2), (api.TAC_PRESERVE, 4), (api.TAC_COLLAPSE, 3)]
 
 
@@ -144,8 +146,8 @@ def test_short_contraction_limits():
     mk = lambda **kw: api.make_desc(8, 1, kw.pop("Cin", 2), 16, kw.pop("W", 128), kw.pop("Cout", 64), K=kw.pop("K", 2), beta=0.9,
                                     theta=1.0, mode=api.TAC_COLLAPSE, stride=kw.pop("stride", 2), precision=api.TAC_BF16)
     assert api.tac_select_kernel(mk()) == api.TAC_KERNEL_MFMA
-    assert api.tac_select_kernel(mk(stride=1)) == api.TAC_KERNEL_DIRECT          # 128 output pixels per row
-    assert api.tac_select_kernel(mk(Cout=96)) == api.TAC_KERNEL_DIRECT           # more than two channel blocks
+    assert api.tac_select_kernel(mk(stride=1)) == api.TAC_KERNEL_MFMA            # 128 output pixels per row
+    assert api.tac_select_kernel(mk(Cout=96)) == api.TAC_KERNEL_MFMA             # more than one channel tile
     assert api.tac_select_kernel(mk(Cin=3)) == api.TAC_KERNEL_DIRECT
     assert api.tac_select_kernel(mk(W=160, stride=2)) == api.TAC_KERNEL_DIRECT
 
@@ -221,7 +223,7 @@ def test_conv_bn_lif_maxpool_blocks_stay_packed():
 
 # ---- real-valued input frames (the continuous-valued first layer, Sec. 4.2)
 
-@pytest.mark.parametrize("shape", [(2, 64, 22, 128, 2), (1, 32, 13, 28, 1), (2, 40, 9, 64, 1)])
+@pytest.mark.parametrize("shape", [(2, 64, 22, 128, 2), (1, 32, 13, 28, 1), (2, 40, 9, 64, 1), (2, 128, 6, 128, 1)])
 @pytest.mark.parametrize("mode,K", [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 2), (api.TAC_PRESERVE, 4), (api.TAC_COLLAPSE, 3)])
 def test_real_valued_frames_short_contraction_kernel(shape, mode, K):
     Cin, Cout, H, W, stride = shape
