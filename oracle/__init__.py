@@ -195,9 +195,7 @@ def conv_lif(spikes, weight, bias=None, *, K=1, beta, theta, mode, stride=1, pad
     if v0 is not None:
         v0 = np.ascontiguousarray(v0, dtype=np.float64)
         assert v0.shape == (d.B, d.Cout, Ho, Wo)
-    T_out = d.T // K if mode == TAC else d.T
-    if mode != PER_STEP and d.T % K:
-        raise ValueError("K must divide T")
+    T_out = -(-d.T // K) if mode == TAC else d.T       # a shorter last group when K does not divide T
     out_s = np.zeros((T_out, d.B, d.Cout, Ho, Wo), dtype=np.uint8)
     v_pre = np.zeros((T_out, d.B, d.Cout, Ho, Wo), dtype=np.float64)
     v_fin = np.zeros((d.B, d.Cout, Ho, Wo), dtype=np.float64)
@@ -226,9 +224,7 @@ def conv_lif_neurons(spikes, weight, bias=None, *, idx, K=1, beta, theta, mode, 
     if v0 is not None:
         v0 = np.ascontiguousarray(v0, dtype=np.float64)
         assert v0.shape == (n,)
-    if mode != PER_STEP and d.T % K:
-        raise ValueError("K must divide T")
-    T_out = d.T // K if mode == TAC else d.T
+    T_out = -(-d.T // K) if mode == TAC else d.T
     out_s = np.zeros((T_out, n), dtype=np.uint8)
     v_pre = np.zeros((T_out, n), dtype=np.float64)
     v_fin = np.zeros((n,), dtype=np.float64)

@@ -174,13 +174,26 @@ static void load_frame(const oracle_desc_t* d, const uint8_t* S, int t, double* 
   }
 }
 
-/* Temporal aggregate of group k (Eq. 2): A = sum_j beta^(K-1-j) S_{kK+j}. */
+/* Frames in group k.  Appendix A assumes that K divides T.  When it does not, the frames that
+ * are left over form a last, shorter group of Kg = T - kK frames, and Eq. 2 and Alg. 1 / 2 are
+ * applied to it with Kg in the place of K (weights beta^(Kg-1-j), decay beta^Kg, Kg LIF steps
+ * in TAC-TP): the unrolled per-step recurrence over those Kg frames, as for every other group. */
+static int group_frames(const oracle_desc_t* d, int k) {
+  const int left = d->T - k * d->K;
+  return left < d->K ? left : d->K;
+}
+
+static int n_groups(const oracle_desc_t* d) { return (d->T + d->K - 1) / d->K; }
+
+/* Temporal aggregate of group k (Eq. 2): A = sum_j beta^(Kg-1-j) S_{kK+j}, Kg = K except in a
+ * shorter last group. */
 void oracle_aggregate(const oracle_desc_t* d, const uint8_t* S, int k, double* A, double* X, double* tmp) {
   const int64_t n = (int64_t)d->B * d->Cin * d->H * d->W;
-  double* w = (double*)malloc(sizeof(double) * (size_t)d->K);
-  oracle_decay_weights(d->beta, d->K, w);
+  const int Kg = group_frames(d, k);
+  double* w = (double*)malloc(sizeof(double) * (size_t)Kg);
+  oracle_decay_weights(d->beta, Kg, w);
   for (int64_t i = 0; i < n; ++i) A[i] = 0.0;
-  for (int j = 0; j < d->K; ++j) {
+  for (int j = 0; j < Kg; ++j) {
     load_frame(d, S, k * d->K + j, X, tmp);
     for (int64_t i = 0; i < n; ++i) A[i] += w[j] * X[i];
   }
@@ -214,7 +227,7 @@ static int check_desc(const oracle_desc_t* d, int need_k) {
   if (d->T < 1 || d->B < 1 || d->Cin < 1 || d->H < 1 || d->W < 1 || d->Cout < 1) return -1;
   if (d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0) return -1;
   if (oracle_out_h(d) < 1 || oracle_out_w(d) < 1) return -1;
-  if (need_k && (d->K < 1 || d->T % d->K != 0)) return -2;
+  if (need_k && d->K < 1) return -2;
   return 0;
 }
 
@@ -252,16 +265,16 @@ int oracle_per_step(const oracle_desc_t* d, const uint8_t* S, const double* Wt, 
 }
 
 /* TAC (Algorithm 1): one convolution and one LIF step per group of K frames.
- * out_s / v_pre hold T/K steps. */
+ * out_s / v_pre hold ceil(T/K) steps. */
 int oracle_tac(const oracle_desc_t* d, const uint8_t* S, const double* Wt, const double* bias,
                const double* v0, uint8_t* out_s, double* v_pre, double* v_final) {
   int rc = check_desc(d, 1);
   if (rc) return rc;
   scratch_t s;
   if (scratch_init(d, v0, &s)) return -3;
-  double beta_K = 1.0;
-  for (int e = 0; e < d->K; ++e) beta_K *= d->beta;
-  for (int k = 0; k < d->T / d->K; ++k) {
+  for (int k = 0; k < n_groups(d); ++k) {
+    double beta_K = 1.0;
+    for (int e = 0; e < group_frames(d, k); ++e) beta_K *= d->beta;
     oracle_aggregate(d, S, k, s.A, s.X, s.tmp);
     oracle_conv2d(s.A, Wt, bias, s.Y, d->B, d->Cin, d->H, d->W, d->Cout, d->kh, d->kw,
                   d->stride, d->pad, d->nthreads);
@@ -286,11 +299,11 @@ int oracle_tac_tp(const oracle_desc_t* d, const uint8_t* S, const double* Wt, co
   if (rc) return rc;
   scratch_t s;
   if (scratch_init(d, v0, &s)) return -3;
-  for (int k = 0; k < d->T / d->K; ++k) {
+  for (int k = 0; k < n_groups(d); ++k) {
     oracle_aggregate(d, S, k, s.A, s.X, s.tmp);
     oracle_conv2d(s.A, Wt, bias, s.Y, d->B, d->Cin, d->H, d->W, d->Cout, d->kh, d->kw,
                   d->stride, d->pad, d->nthreads);
-    for (int j = 0; j < d->K; ++j) {
+    for (int j = 0; j < group_frames(d, k); ++j) {
       const int64_t t = (int64_t)k * d->K + j;
       for (int64_t i = 0; i < s.n_out; ++i) {
         double v = d->beta * s.V[i] + s.Y[i];
@@ -358,10 +371,12 @@ int oracle_neurons(const oracle_desc_t* d, int mode, const uint8_t* S, const dou
   if (rc) return rc;
   if (mode < 0 || mode > 2) return -4;
   const int K = mode == 0 ? 1 : d->K;
+  const int G = (d->T + K - 1) / K;
+  const int K_last = d->T - (G - 1) * K;         /* frames of the last group (K when K divides T) */
   double* w = (double*)malloc(sizeof(double) * (size_t)K);
+  double* w_last = (double*)malloc(sizeof(double) * (size_t)K_last);
   oracle_decay_weights(d->beta, K, w);
-  double beta_K = 1.0;
-  for (int e = 0; e < K; ++e) beta_K *= d->beta;
+  oracle_decay_weights(d->beta, K_last, w_last);
   const int Ho = oracle_out_h(d), Wo = oracle_out_w(d);
   int bad = 0;
   (void)Ho; (void)Wo;
@@ -376,10 +391,15 @@ int oracle_neurons(const oracle_desc_t* d, int mode, const uint8_t* S, const dou
     }
     double v = v0 ? v0[i] : 0.0;
     int64_t step = 0;
-    for (int k = 0; k < d->T / K; ++k) {
-      const double y = conv_at(d, S, Wt, bias, w, k * K, K, b, co, oy, ox);
-      const int nlif = (mode == 2) ? K : 1;
-      const double decay = (mode == 1) ? beta_K : d->beta;
+    for (int k = 0; k < G; ++k) {
+      const int Kg = k == G - 1 ? K_last : K;
+      const double y = conv_at(d, S, Wt, bias, k == G - 1 ? w_last : w, k * K, Kg, b, co, oy, ox);
+      const int nlif = (mode == 2) ? Kg : 1;
+      double decay = d->beta;
+      if (mode == 1) {
+        decay = 1.0;
+        for (int e = 0; e < Kg; ++e) decay *= d->beta;
+      }
       for (int j = 0; j < nlif; ++j, ++step) {
         v = decay * v + y;
         const int fire = v >= d->theta;
@@ -391,6 +411,7 @@ int oracle_neurons(const oracle_desc_t* d, int mode, const uint8_t* S, const dou
     if (v_final) v_final[i] = v;
   }
   free(w);
+  free(w_last);
   return bad ? -5 : 0;
 }
 

@@ -173,6 +173,75 @@ def test_hand_worked_scalar_example():
         assert v_fin.ravel().tolist() == [g[key]["v_final"]], key
 
 
+def test_hand_worked_scalar_example_with_a_shorter_last_group():
+    g = json.load(open(os.path.join(GOLDEN, "ragged_scalar_example.json")))
+    s = np.array(g["input"], dtype=np.uint8).reshape(5, 1, 1, 1, 1)
+    w = _rng(9).standard_normal((1, 1, 3, 3)); w[0, 0, 1, 1] = g["centre_tap"]
+    kw = dict(beta=g["beta"], theta=g["theta"])
+    for mode, K, key in [(TAC, 2, "tac_K2"), (TAC_TP, 2, "tac_tp_K2"), (TAC, 4, "tac_K4"), (TAC, 3, "tac_K3")]:
+        out, v_pre, v_fin = oracle.conv_lif(s, w, K=K, mode=mode, **kw)
+        assert out.ravel().tolist() == g[key]["spikes"], key
+        assert v_pre.ravel().tolist() == g[key]["v_pre"], key
+        assert v_fin.ravel().tolist() == [g[key]["v_final"]], key
+        idx = np.zeros((1, 4), dtype=np.int32)
+        n = oracle.conv_lif_neurons(s, w, idx=idx, K=K, mode=mode, **kw)
+        assert n[0].ravel().tolist() == g[key]["spikes"] and n[1].ravel().tolist() == g[key]["v_pre"], key
+
+
+@pytest.mark.parametrize("T,K", [(7, 2), (7, 4), (5, 3), (9, 8), (3, 5)])
+def test_shorter_last_group_without_spikes_equals_per_step(T, K):
+    # threshold out of reach: by linearity (Sec. 4.2) the membrane after the last group, whatever
+    # its length, is the per-step membrane after T frames; a wrong weight or decay in the short
+    # group breaks this
+    s, w = _tiny(40 + T + K, T=T)
+    kw = dict(beta=0.9, theta=1e30)
+    v_ps = oracle.conv_lif(s, w, mode=PER_STEP, **kw)[2]
+    for mode in (TAC, TAC_TP):
+        if mode == TAC:
+            assert np.allclose(oracle.conv_lif(s, w, K=K, mode=TAC, **kw)[2], v_ps, rtol=1e-12, atol=1e-12)
+    # TAC-TP feeds the aggregate K' times; with one frame per group it is the per-step layer again
+    a = oracle.conv_lif(s, w, K=1, mode=TAC_TP, beta=0.9, theta=1.0)
+    b = oracle.conv_lif(s, w, mode=PER_STEP, beta=0.9, theta=1.0)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+@pytest.mark.parametrize("mode", [TAC, TAC_TP])
+@pytest.mark.parametrize("T,K", [(7, 2), (7, 4), (11, 4), (5, 3)])
+def test_shorter_last_group_is_a_call_of_its_own_with_the_state_carried(mode, T, K):
+    # the run over T frames = the run over the whole groups, then a run over the T mod K frames
+    # left with K' = T mod K and the membrane carried over
+    s, w = _tiny(60 + T + K, T=T)
+    kw = dict(beta=0.8, theta=1.0, mode=mode)
+    whole = oracle.conv_lif(s, w, K=K, **kw)
+    Tm = T - T % K
+    head = oracle.conv_lif(s[:Tm], w, K=K, **kw)
+    tail = oracle.conv_lif(s[Tm:], w, K=T % K, v0=head[2], **kw)
+    assert np.array_equal(whole[0], np.concatenate([head[0], tail[0]]))
+    assert np.array_equal(whole[1], np.concatenate([head[1], tail[1]]))
+    assert np.array_equal(whole[2], tail[2])
+    assert whole[0].sum() > 0 and tail[0].sum() > 0
+
+
+def test_group_longer_than_the_sequence_is_one_group_of_T_frames():
+    s, w = _tiny(71, T=3)
+    for mode in (TAC, TAC_TP):
+        a = oracle.conv_lif(s, w, K=8, beta=0.9, theta=1.0, mode=mode)
+        b = oracle.conv_lif(s, w, K=3, beta=0.9, theta=1.0, mode=mode)
+        assert all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+def test_neurons_follow_the_full_layer_with_a_shorter_last_group():
+    s, w = _tiny(72, T=7)
+    r = _rng(73)
+    idx = np.stack([r.integers(0, 2, 20), r.integers(0, 3, 20), r.integers(0, 5, 20), r.integers(0, 6, 20)], axis=1).astype(np.int32)
+    for mode, K in [(TAC, 4), (TAC_TP, 4), (TAC, 2), (TAC_TP, 3)]:
+        full = oracle.conv_lif(s, w, K=K, beta=0.9, theta=1.0, mode=mode)
+        n = oracle.conv_lif_neurons(s, w, idx=idx, K=K, beta=0.9, theta=1.0, mode=mode)
+        sel = (slice(None), idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3])
+        assert np.array_equal(n[0], full[0][sel]) and np.allclose(n[1], full[1][sel], rtol=0, atol=1e-12)
+        assert np.allclose(n[2], full[2][sel[1:]], rtol=0, atol=1e-12)
+
+
 def _tiny(seed, T=8, B=2, Cin=2, H=5, W=6, Cout=3):
     r = _rng(seed)
     s = r.integers(0, 2, size=(T, B, Cin, H, W)).astype(np.uint8)
@@ -234,8 +303,9 @@ def test_output_shapes_collapse_vs_preserve():
     for K in (1, 2, 4, 8):
         assert oracle.conv_lif(s, w, K=K, beta=0.9, theta=1.0, mode=TAC)[0].shape[0] == 8 // K
         assert oracle.conv_lif(s, w, K=K, beta=0.9, theta=1.0, mode=TAC_TP)[0].shape[0] == 8
-    with pytest.raises(ValueError):
-        oracle.conv_lif(s, w, K=3, beta=0.9, theta=1.0, mode=TAC)
+    # K does not divide T: the frames left over form one more, shorter group
+    assert oracle.conv_lif(s, w, K=3, beta=0.9, theta=1.0, mode=TAC)[0].shape[0] == 3
+    assert oracle.conv_lif(s, w, K=3, beta=0.9, theta=1.0, mode=TAC_TP)[0].shape[0] == 8
 
 
 def test_threshold_tie_fires():
@@ -277,21 +347,23 @@ def _brute(s, w, bias, v0, K, beta, theta, mode, stride, pad, pool2):
             return sum(F(float(v)) for v in s[t, b, ci, 2 * y:2 * y + 2, 2 * x:2 * x + 2].ravel()) / 4
         return F(float(s[t, b, ci, y, x]))
 
-    Kg = 1 if mode == PER_STEP else K
-    n_lif = Kg if mode == TAC_TP else 1
-    decay = beta ** Kg if mode == TAC else beta
-    T_out = T // Kg * n_lif
+    K = 1 if mode == PER_STEP else K
+    T_out = T if mode != TAC else -(-T // K)
     spikes = np.zeros((T_out, B, Cout, Ho, Wo), dtype=np.uint8)
     v_pre = np.empty((T_out, B, Cout, Ho, Wo), dtype=object)
     v_fin = np.empty((B, Cout, Ho, Wo), dtype=object)
     for b, co, oy, ox in itertools.product(range(B), range(Cout), range(Ho), range(Wo)):
         V = F(float(v0[b, co, oy, ox])) if v0 is not None else F(0)
         step = 0
-        for k in range(T // Kg):
+        for t0 in range(0, T, K):
+            Kg = min(K, T - t0)                  # the group's frames: t0 .. t0 + Kg - 1 (fewer than K only at the end)
+            n_lif = Kg if mode == TAC_TP else 1
+            decay = beta ** Kg if mode == TAC else beta
             Y = F(float(bias[co])) if bias is not None else F(0)
             for kx, ky, ci in itertools.product(range(2, -1, -1), range(3), range(Cin - 1, -1, -1)):
-                a = sum(beta ** (Kg - 1 - j) * pix(k * Kg + j, b, ci, oy * stride + ky - pad, ox * stride + kx - pad)
-                        for j in range(Kg))
+                # weight of a frame: beta to the number of frames after it in the group
+                a = sum(beta ** (t0 + Kg - 1 - t) * pix(t, b, ci, oy * stride + ky - pad, ox * stride + kx - pad)
+                        for t in range(t0, t0 + Kg))
                 Y += F(float(w[co, ci, ky, kx])) * a
             for _ in range(n_lif):
                 V = decay * V + Y
@@ -304,7 +376,7 @@ def _brute(s, w, bias, v0, K, beta, theta, mode, stride, pad, pool2):
     return spikes, v_pre, v_fin
 
 
-@pytest.mark.parametrize("mode,K", [(PER_STEP, 1), (TAC, 2), (TAC, 4), (TAC_TP, 2), (TAC_TP, 4)])
+@pytest.mark.parametrize("mode,K", [(PER_STEP, 1), (TAC, 2), (TAC, 4), (TAC_TP, 2), (TAC_TP, 4), (TAC, 3), (TAC_TP, 3)])
 @pytest.mark.parametrize("stride,pool2", [(1, False), (2, False), (1, True), (1, "max")])
 def test_exact_brute_force(mode, K, stride, pool2):
     r = _rng(100 + 10 * K + stride + 5 * bool(pool2))
