@@ -61,12 +61,12 @@ enum {
   TAC_ERR_NULL = -1,        /* a required pointer is NULL                               */
   TAC_ERR_BAD_SHAPE = -2,   /* a dimension <= 0, kh/kw != 3, stride not 1 or 2, pad != 1,
                                or a tensor too large for 32-bit word indexing           */
-  TAC_ERR_BAD_K = -3,       /* K < 1, K > TAC_MAX_K, or K does not divide T
-                               (App. A assumes K | T)                                   */
+  TAC_ERR_BAD_K = -3,       /* K < 1 or K > TAC_MAX_K                                    */
   TAC_ERR_BAD_PARAM = -4,   /* beta outside [0,1], theta <= 0 or not finite, bad enum   */
   TAC_ERR_UNSUPPORTED = -5, /* valid request that the chosen kernel family cannot run   */
   TAC_ERR_HIP = -6,         /* a HIP call failed; text via tac_last_error()             */
-  TAC_ERR_ALIGN = -7        /* a device pointer is not aligned as documented            */
+  TAC_ERR_ALIGN = -7,       /* a device pointer is not aligned as documented            */
+  TAC_ERR_NEED_STATE = -8   /* K does not divide T and v_inout is NULL (see tac_conv_lif) */
 };
 
 #define TAC_MAX_K 32
@@ -77,7 +77,8 @@ typedef struct tac_layer_desc {
                                 in_format = TAC_IN_BITS_[MAX]POOL2)                            */
   int32_t Cout, kh, kw;      /* kernel W[Cout][Cin][kh][kw]; kh = kw = 3                  */
   int32_t stride, pad;       /* stride 1 or 2, pad 1 (zero padding)                       */
-  int32_t K;                 /* group size; TAC_PER_STEP ignores it and uses 1            */
+  int32_t K;                 /* group size; TAC_PER_STEP ignores it and uses 1.  K need not
+                                divide T (see tac_conv_lif); K > T works as K = T          */
   int32_t mode;              /* TAC_PER_STEP / TAC_COLLAPSE / TAC_PRESERVE                */
   int32_t precision;         /* TAC_FP32 / TAC_BF16                                       */
   int32_t in_format;         /* TAC_IN_BITS / _POOL2 / _MAXPOOL2 / TAC_IN_F32             */
@@ -86,7 +87,7 @@ typedef struct tac_layer_desc {
   float theta;               /* threshold V_th, > 0                                       */
 } tac_layer_desc_t;
 
-/* Output geometry: T_out = T/K for TAC (Alg. 1 returns T/K steps), T for TAC-TP
+/* Output geometry: T_out = ceil(T/K) for TAC (Alg. 1 returns T/K steps), T for TAC-TP
  * (Alg. 2, App. B) and per-step; Ho = (H + 2 pad - kh)/stride + 1, same for Wo.
  * Host only.  Any of the three out-pointers may be NULL. */
 int tac_out_shape(const tac_layer_desc_t* desc, int32_t* T_out, int32_t* Ho, int32_t* Wo);
@@ -121,6 +122,11 @@ int tac_prepare_weights(const tac_layer_desc_t* desc, const float* w_oihw, void*
  * Conv2d(A_k, W), then the LIF update(s), threshold (spike iff V >= theta) and
  * subtractive reset of Alg. 1 (TAC), Alg. 2 (TAC-TP) or the per-step layer
  * (K = 1).  A_k and Y_k never leave the chip.
+ * K need not divide T (App. A assumes it does; Sec. 5 uses T = 25 with K = 4, 8, 16): the
+ * K' = T mod K frames left over form a last group treated like every other with K' in the place
+ * of K (weights beta^(K'-1-j), decay beta^K', K' LIF steps in TAC-TP).  That group is a second
+ * launch and the membrane passes from the first to it through v_inout, which must then be
+ * given: TAC_ERR_NEED_STATE otherwise.
  *   input              DEVICE, read-only, packed uint32 [T][B][Cin][H][ceil(W/32)]
  *                      (or [T][B][Cin][2H][ceil(2W/32)] with TAC_IN_BITS_[MAX]POOL2, or float32
  *                      [T][B][Cin][H][W] with TAC_IN_F32)

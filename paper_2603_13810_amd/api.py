@@ -18,7 +18,7 @@ TAC_FP32, TAC_BF16 = 0, 1
 TAC_IN_BITS, TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2, TAC_IN_F32 = 0, 1, 2, 3
 TAC_KERNEL_AUTO, TAC_KERNEL_DIRECT, TAC_KERNEL_MFMA = 0, 1, 2
 TAC_OK, TAC_ERR_NULL, TAC_ERR_BAD_SHAPE, TAC_ERR_BAD_K = 0, -1, -2, -3
-TAC_ERR_BAD_PARAM, TAC_ERR_UNSUPPORTED, TAC_ERR_HIP, TAC_ERR_ALIGN = -4, -5, -6, -7
+TAC_ERR_BAD_PARAM, TAC_ERR_UNSUPPORTED, TAC_ERR_HIP, TAC_ERR_ALIGN, TAC_ERR_NEED_STATE = -4, -5, -6, -7, -8
 TAC_MAX_K = 32
 
 MODE_NAMES = {TAC_PER_STEP: "per_step", TAC_COLLAPSE: "TAC", TAC_PRESERVE: "TAC_TP"}

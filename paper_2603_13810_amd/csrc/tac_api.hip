@@ -33,7 +33,7 @@ int validate(const tac_layer_desc_t* d) {
   if (!(d->beta >= 0.0f && d->beta <= 1.0f)) return TAC_ERR_BAD_PARAM;
   if (!(d->theta > 0.0f) || !std::isfinite(d->theta)) return TAC_ERR_BAD_PARAM;
   if (d->mode != TAC_PER_STEP) {
-    if (d->K < 1 || d->K > TAC_MAX_K || d->T % d->K != 0) return TAC_ERR_BAD_K;
+    if (d->K < 1 || d->K > TAC_MAX_K) return TAC_ERR_BAD_K;
   }
   // kernels index words and membrane elements with 32-bit offsets inside one (t) slab and
   // 64-bit offsets across slabs; keep each slab below 2^31 elements
@@ -44,6 +44,17 @@ int validate(const tac_layer_desc_t* d) {
                                                       : (int64_t)d->B * d->Cin * (d->H * f) * ((d->W * f + 31) / 32);
   if (out_slab >= (1LL << 31) || in_slab >= (1LL << 31)) return TAC_ERR_BAD_SHAPE;
   if (d->B > 65535) return TAC_ERR_BAD_SHAPE;
+  return TAC_OK;
+}
+
+// Checks the description and copies it with the group size the kernels will work with: 1 for the
+// per-step layer, T when the sequence is shorter than one group (a single group of T frames).
+int effective(const tac_layer_desc_t* d, tac_layer_desc_t* e) {
+  const int rc = validate(d);
+  if (rc) return rc;
+  *e = *d;
+  if (e->mode == TAC_PER_STEP) e->K = 1;
+  else if (e->K > e->T) e->K = e->T;
   return TAC_OK;
 }
 
@@ -59,10 +70,10 @@ int select_kernel(const tac_layer_desc_t* d) {
 extern "C" {
 
 int tac_out_shape(const tac_layer_desc_t* desc, int32_t* T_out, int32_t* Ho, int32_t* Wo) {
-  const int rc = validate(desc);
+  tac_layer_desc_t eff;
+  const int rc = effective(desc, &eff);
   if (rc) return rc;
-  const int K = desc->mode == TAC_PER_STEP ? 1 : desc->K;
-  if (T_out) *T_out = desc->mode == TAC_COLLAPSE ? desc->T / K : desc->T;
+  if (T_out) *T_out = desc->mode == TAC_COLLAPSE ? (desc->T + eff.K - 1) / eff.K : desc->T;
   if (Ho) *Ho = (desc->H + 2 * desc->pad - desc->kh) / desc->stride + 1;
   if (Wo) *Wo = (desc->W + 2 * desc->pad - desc->kw) / desc->stride + 1;
   return TAC_OK;
@@ -73,23 +84,28 @@ size_t tac_packed_bytes(int32_t T, int32_t B, int32_t C, int32_t H, int32_t W) {
   return (size_t)T * (size_t)B * (size_t)C * (size_t)H * (size_t)((W + 31) / 32) * 4u;
 }
 
-int tac_select_kernel(const tac_layer_desc_t* desc) {
-  const int rc = validate(desc);
+int tac_select_kernel(const tac_layer_desc_t* d) {
+  tac_layer_desc_t eff;
+  const int rc = effective(d, &eff);
   if (rc) return rc;
-  return select_kernel(desc);
+  return select_kernel(&eff);
 }
 
-size_t tac_prepared_weight_bytes(const tac_layer_desc_t* desc) {
-  if (validate(desc)) return 0;
+size_t tac_prepared_weight_bytes(const tac_layer_desc_t* d) {
+  tac_layer_desc_t eff;
+  if (effective(d, &eff)) return 0;
+  const tac_layer_desc_t* desc = &eff;
   const int k = select_kernel(desc);
   if (k == TAC_KERNEL_MFMA) return tac::mfma_weight_bytes(*desc);
   if (k == TAC_KERNEL_DIRECT) return tac::direct_weight_bytes(*desc);
   return 0;
 }
 
-int tac_prepare_weights(const tac_layer_desc_t* desc, const float* w_oihw, void* w_prepared, void* stream) {
-  int rc = validate(desc);
+int tac_prepare_weights(const tac_layer_desc_t* d, const float* w_oihw, void* w_prepared, void* stream) {
+  tac_layer_desc_t eff;
+  int rc = effective(d, &eff);
   if (rc) return rc;
+  const tac_layer_desc_t* desc = &eff;
   if (!w_oihw || !w_prepared) return TAC_ERR_NULL;
   if (((uintptr_t)w_oihw & 3u) || ((uintptr_t)w_prepared & 15u)) return TAC_ERR_ALIGN;
   const int k = select_kernel(desc);
@@ -99,11 +115,13 @@ int tac_prepare_weights(const tac_layer_desc_t* desc, const float* w_oihw, void*
   return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_prepare_weights");
 }
 
-int tac_conv_lif(const tac_layer_desc_t* desc, const void* input, const void* w_prepared,
+int tac_conv_lif(const tac_layer_desc_t* d, const void* input, const void* w_prepared,
                  const float* bias, float* v_inout, uint32_t* out_spikes_packed, float* v_trace,
                  void* stream) {
-  int rc = validate(desc);
+  tac_layer_desc_t eff;
+  int rc = effective(d, &eff);
   if (rc) return rc;
+  const tac_layer_desc_t* desc = &eff;
   const uint32_t* spikes_packed = static_cast<const uint32_t*>(input);     // float32 frames with TAC_IN_F32
   if (!spikes_packed || !w_prepared || !out_spikes_packed) return TAC_ERR_NULL;
   if (((uintptr_t)spikes_packed & 3u) || ((uintptr_t)w_prepared & 15u) || ((uintptr_t)bias & 3u) ||
@@ -129,8 +147,10 @@ int tac_conv_lif(const tac_layer_desc_t* desc, const void* input, const void* w_
   p.Hs = p.pool2 ? 2 * desc->H : desc->H;
   p.Wwi = ((p.pool2 ? 2 * desc->W : desc->W) + 31) / 32;
   p.Wwo = (p.Wo + 31) / 32;
-  p.K = desc->mode == TAC_PER_STEP ? 1 : desc->K;
-  p.G = desc->T / p.K;
+  p.K = desc->K;
+  p.G = desc->T / p.K;                           // whole groups; at least one
+  const int K_last = desc->T % p.K;              // frames left over for a shorter last group
+  if (K_last && !v_inout) return TAC_ERR_NEED_STATE;
   p.n_lif = desc->mode == TAC_PRESERVE ? p.K : 1;
   p.bf16 = desc->precision == TAC_BF16;
   p.theta = desc->theta;
@@ -145,6 +165,30 @@ int tac_conv_lif(const tac_layer_desc_t* desc, const void* input, const void* w_
   if (e != hipSuccess) return hip_fail(e, "tac_conv_lif");
   g_conv_stages += (uint64_t)p.G;
   g_lif_steps += (uint64_t)p.G * (uint64_t)p.n_lif;
+  if (K_last) {
+    // The K_last frames left over are one more group with K_last in the place of K: weights
+    // beta^(K_last-1-j), decay beta^K_last, K_last LIF steps in TAC-TP.  It runs as a second
+    // launch of the same kernel on the last K frames of the sequence with the weights of the
+    // first K - K_last of them set to zero (the remaining ones are then exactly
+    // beta^(K_last-1-j)), the membrane handed over in v_inout by the stream's order.
+    tac::LayerParams q = p;
+    const int skip = p.K - K_last;
+    for (int j = 0; j < skip; ++j) { q.wj[j] = 0.0f; q.wjd[j] = 0.0; }
+    const size_t in_slab = (size_t)p.B * p.Cin * p.Hs * (p.dense ? (size_t)p.W : (size_t)p.Wwi);   // 4-byte elements per frame
+    const size_t out_slab = (size_t)p.B * p.Cout * p.Ho * p.Wwo;
+    const size_t v_slab = (size_t)p.B * p.Cout * p.Ho * p.Wo;
+    const size_t steps = (size_t)p.G * p.n_lif;  // LIF steps of the whole groups
+    q.spikes = p.spikes + (size_t)(desc->T - p.K) * in_slab;
+    q.out = p.out + steps * out_slab;
+    q.v_trace = p.v_trace ? p.v_trace + steps * v_slab : nullptr;
+    q.G = 1;
+    q.n_lif = desc->mode == TAC_PRESERVE ? K_last : 1;
+    q.decay = desc->mode == TAC_COLLAPSE ? (float)p.wjd[p.K - 1 - K_last] /* beta^K_last */ : desc->beta;
+    e = kern == TAC_KERNEL_MFMA ? tac::mfma_launch(q, (hipStream_t)stream) : tac::direct_launch(q, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "tac_conv_lif (last group)");
+    g_conv_stages += 1;
+    g_lif_steps += (uint64_t)q.n_lif;
+  }
   return TAC_OK;
 }
 
@@ -193,7 +237,8 @@ const char* tac_status_string(int status) {
     case TAC_OK: return "ok";
     case TAC_ERR_NULL: return "a required pointer is NULL";
     case TAC_ERR_BAD_SHAPE: return "bad shape (dimension <= 0, kernel not 3x3, stride not 1/2, pad not 1, or tensor too large)";
-    case TAC_ERR_BAD_K: return "bad group size K (K < 1, K > 32, or K does not divide T)";
+    case TAC_ERR_BAD_K: return "bad group size K (K < 1 or K > 32)";
+    case TAC_ERR_NEED_STATE: return "T is not a multiple of K: the shorter last group is a launch of its own and needs v_inout to carry the membrane";
     case TAC_ERR_BAD_PARAM: return "bad parameter (beta outside [0,1], theta <= 0 or not finite, or unknown enum value)";
     case TAC_ERR_UNSUPPORTED: return "the requested kernel family does not support this layer";
     case TAC_ERR_HIP: return "a HIP call failed (see tac_last_error)";

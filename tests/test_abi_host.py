@@ -63,7 +63,7 @@ def test_packed_bytes():
 @pytest.mark.parametrize("kw,status", [
     (dict(T=0), api.TAC_ERR_BAD_SHAPE), (dict(Cout=-1), api.TAC_ERR_BAD_SHAPE),
     (dict(kh=5), api.TAC_ERR_BAD_SHAPE), (dict(stride=3), api.TAC_ERR_BAD_SHAPE), (dict(pad=0), api.TAC_ERR_BAD_SHAPE),
-    (dict(K=3), api.TAC_ERR_BAD_K), (dict(K=0), api.TAC_ERR_BAD_K), (dict(T=64, K=64), api.TAC_ERR_BAD_K),
+    (dict(K=33), api.TAC_ERR_BAD_K), (dict(K=0), api.TAC_ERR_BAD_K), (dict(T=64, K=64), api.TAC_ERR_BAD_K),
     (dict(beta=1.5), api.TAC_ERR_BAD_PARAM), (dict(beta=float("nan")), api.TAC_ERR_BAD_PARAM),
     (dict(theta=0.0), api.TAC_ERR_BAD_PARAM), (dict(theta=float("inf")), api.TAC_ERR_BAD_PARAM),
     (dict(mode=7), api.TAC_ERR_BAD_PARAM), (dict(precision=3), api.TAC_ERR_BAD_PARAM),
@@ -80,6 +80,24 @@ def test_invalid_descriptions_are_rejected_before_any_launch(kw, status):
     assert L.tac_conv_lif(ctypes.byref(d), fake, fake, None, None, fake, None, None) == status
     assert L.tac_prepare_weights(ctypes.byref(d), fake, fake, None) == status
     assert api.tac_status_string(status) not in ("ok", "unknown status")
+
+
+def test_sequence_length_need_not_be_a_multiple_of_K():
+    # the frames left over form one more, shorter group: ceil(T/K) output steps for TAC, T for TAC-TP
+    assert api.tac_out_shape(_desc(T=8, K=3, mode=api.TAC_COLLAPSE))[0] == 3
+    assert api.tac_out_shape(_desc(T=8, K=3, mode=api.TAC_PRESERVE))[0] == 8
+    assert api.tac_out_shape(_desc(T=25, K=16, mode=api.TAC_COLLAPSE))[0] == 2
+    # a group longer than the sequence is one group of T frames
+    assert api.tac_out_shape(_desc(T=3, K=8, mode=api.TAC_COLLAPSE))[0] == 1
+    for f in (api.tac_select_kernel, api.tac_prepared_weight_bytes):
+        assert f(_desc(T=3, K=8, mode=api.TAC_COLLAPSE)) == f(_desc(T=3, K=3, mode=api.TAC_COLLAPSE))
+    # the short group is a second launch and takes the membrane from v_inout: refused without it,
+    # before anything is launched
+    L = api.lib()
+    fake = ctypes.c_void_p(0x1000)
+    d = _desc(T=8, K=3, mode=api.TAC_COLLAPSE)
+    assert L.tac_conv_lif(ctypes.byref(d), fake, fake, None, None, fake, None, None) == api.TAC_ERR_NEED_STATE
+    assert api.tac_status_string(api.TAC_ERR_NEED_STATE) not in ("ok", "unknown status")
 
 
 def test_per_step_ignores_K():
