@@ -267,11 +267,10 @@ def bench_stack(args, wl, dev):
         flops += fl
         T, H, W = T_out, Ho, Wo
 
-    def step():
-        x = x0
-        for l in layers:
-            api.tac_conv_lif(l["desc"], x, l["wp"], None, None, l["out"])
-            x = l["out"]
+    stack, _ = api.make_stack([dict(desc=l["desc"], w_prepared=l["wp"], out_spikes_packed=l["out"]) for l in layers])
+
+    def step():                                     # one call: every layer enqueued in order
+        api.tac_stack_forward(stack, x0)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

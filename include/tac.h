@@ -163,6 +163,32 @@ int tac_fold_batchnorm(const float* w_oihw, const float* bias, const float* gamm
                        const float* mean, const float* var, float eps, int32_t Cout, int32_t per_cout,
                        float* w_out, float* bias_out, void* stream);
 
+/* A stack of conv-LIF layers, each with its own mode and group size (App. B: TAC layers cascade,
+ * T -> T / K_1 -> T / (K_1 K_2) ...; TAC-TP layers keep T; Sec. 5.1's networks mix both with
+ * pooling between the layers).  Layer l reads what layer l-1 wrote, still packed.  Plain data;
+ * the caller owns every buffer. */
+typedef struct tac_stack_layer {
+  tac_layer_desc_t desc;        /* T, B, Cin, H, W must continue layer l-1 (see tac_stack_check) */
+  const void* w_prepared;       /* DEVICE, from tac_prepare_weights(&desc, ...)                  */
+  const float* bias;            /* DEVICE [Cout] or NULL                                         */
+  float* v_inout;               /* DEVICE [B][Cout][Ho][Wo] or NULL, as in tac_conv_lif          */
+  uint32_t* out_spikes_packed;  /* DEVICE, written: this layer's output, the next layer's input  */
+  float* v_trace;               /* DEVICE or NULL, as in tac_conv_lif                            */
+} tac_stack_layer_t;
+
+/* Host only: every description valid, and for l >= 1: B equal, Cin = Cout of layer l-1,
+ * T = T_out of layer l-1, packed-bit input, and (H, W) = layer l-1's (Ho, Wo), or half of them
+ * (both even) with TAC_IN_BITS_POOL2 / _MAXPOOL2.  TAC_OK, the failing layer's validation
+ * error, or TAC_ERR_BAD_SHAPE with *bad_layer (may be NULL) = index of the layer that does not
+ * continue the one before. */
+int tac_stack_check(const tac_stack_layer_t* layers, int32_t n_layers, int32_t* bad_layer);
+
+/* Runs tac_stack_check, then enqueues the n layers on `stream` in order (layer 0 reads `input`,
+ * DEVICE, in layer 0's in_format).  No synchronisation, no allocation, no memset: the call can be
+ * recorded into a HIP graph by capturing `stream`.  Errors as tac_stack_check and tac_conv_lif;
+ * layers before a failing one have been enqueued. */
+int tac_stack_forward(const tac_stack_layer_t* layers, int32_t n_layers, const void* input, void* stream);
+
 int tac_pack_spikes(const uint8_t* dense01, uint32_t* packed, int64_t rows, int32_t W, void* stream);
 int tac_unpack_spikes(const uint32_t* packed, uint8_t* dense01, int64_t rows, int32_t W, void* stream);
 

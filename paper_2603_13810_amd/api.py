@@ -25,7 +25,8 @@ MODE_NAMES = {TAC_PER_STEP: "per_step", TAC_COLLAPSE: "TAC", TAC_PRESERVE: "TAC_
 
 EXPORTS = ("tac_out_shape", "tac_packed_bytes", "tac_select_kernel", "tac_prepared_weight_bytes",
            "tac_prepare_weights", "tac_conv_lif", "tac_pack_spikes", "tac_unpack_spikes", "tac_fold_batchnorm",
-           "tac_get_counters", "tac_reset_counters", "tac_status_string", "tac_last_error")
+           "tac_stack_check", "tac_stack_forward", "tac_get_counters", "tac_reset_counters", "tac_status_string",
+           "tac_last_error")
 
 
 class tac_layer_desc_t(ctypes.Structure):
@@ -74,6 +75,10 @@ def lib() -> ctypes.CDLL:
         u64p = ctypes.POINTER(ctypes.c_uint64)
         L.tac_get_counters.argtypes = [u64p, u64p]
         L.tac_get_counters.restype = ctypes.c_int
+        L.tac_stack_check.argtypes = [vp, ctypes.c_int32, i32p]
+        L.tac_stack_check.restype = ctypes.c_int
+        L.tac_stack_forward.argtypes = [vp, ctypes.c_int32, vp, vp]
+        L.tac_stack_forward.restype = ctypes.c_int
         L.tac_reset_counters.argtypes = []
         L.tac_reset_counters.restype = ctypes.c_int
         L.tac_status_string.argtypes = [ctypes.c_int]
@@ -198,6 +203,63 @@ def tac_conv_lif(desc, spikes_packed, w_prepared, bias=None, v_inout=None, out_s
                               _dev_ptr(out_spikes_packed, None, "out_spikes_packed"),
                               _dev_ptr(v_trace, torch.float32, "v_trace"), _stream(stream)))
     return out_spikes_packed
+
+
+class tac_stack_layer_t(ctypes.Structure):
+    _fields_ = [("desc", tac_layer_desc_t), ("w_prepared", ctypes.c_void_p), ("bias", ctypes.c_void_p),
+                ("v_inout", ctypes.c_void_p), ("out_spikes_packed", ctypes.c_void_p), ("v_trace", ctypes.c_void_p)]
+
+
+def make_stack(layers):
+    """layers: list of dicts with desc, w_prepared and optionally bias, v_inout, out_spikes_packed, v_trace
+    (device tensors; missing outputs are allocated).  Returns (ctypes array, list of output tensors); the
+    list of dicts must stay alive as long as the array is used, it owns the tensors."""
+    import torch
+    arr = (tac_stack_layer_t * len(layers))()
+    outs = []
+    for i, L in enumerate(layers):
+        desc = L["desc"]
+        T_out, Ho, Wo = tac_out_shape(desc)
+        if L.get("out_spikes_packed") is None:
+            L["out_spikes_packed"] = torch.empty((T_out, desc.B, desc.Cout, Ho, (Wo + 31) // 32), dtype=torch.int32,
+                                                 device=L["w_prepared"].device)
+        elif L["out_spikes_packed"].numel() * L["out_spikes_packed"].element_size() != tac_packed_bytes(T_out, desc.B, desc.Cout, Ho, Wo):
+            raise ValueError("layer %d: out_spikes_packed has the wrong size" % i)
+        if L["w_prepared"].numel() * L["w_prepared"].element_size() < tac_prepared_weight_bytes(desc):
+            raise ValueError("layer %d: prepared-weight buffer too small for this description" % i)
+        if L.get("bias") is not None and tuple(L["bias"].shape) != (desc.Cout,):
+            raise ValueError("layer %d: bias must be [Cout]" % i)
+        if L.get("v_inout") is not None and tuple(L["v_inout"].shape) != (desc.B, desc.Cout, Ho, Wo):
+            raise ValueError("layer %d: v_inout must be [B,Cout,Ho,Wo]" % i)
+        if L.get("v_trace") is not None and tuple(L["v_trace"].shape) != (T_out, desc.B, desc.Cout, Ho, Wo):
+            raise ValueError("layer %d: v_trace must be [T_out,B,Cout,Ho,Wo]" % i)
+        arr[i].desc = desc
+        val = lambda p: None if p is None else p.value
+        arr[i].w_prepared = val(_dev_ptr(L["w_prepared"], None, "w_prepared"))
+        arr[i].bias = val(_dev_ptr(L.get("bias"), torch.float32, "bias"))
+        arr[i].v_inout = val(_dev_ptr(L.get("v_inout"), torch.float32, "v_inout"))
+        arr[i].out_spikes_packed = val(_dev_ptr(L["out_spikes_packed"], None, "out_spikes_packed"))
+        arr[i].v_trace = val(_dev_ptr(L.get("v_trace"), torch.float32, "v_trace"))
+        outs.append(L["out_spikes_packed"])
+    return arr, outs
+
+
+def tac_stack_check(stack) -> Tuple[int, int]:
+    """(status, index of the layer that does not continue the one before, or -1)."""
+    bad = ctypes.c_int32(-1)
+    rc = lib().tac_stack_check(stack, len(stack), ctypes.byref(bad))
+    return rc, bad.value
+
+
+def tac_stack_forward(stack, input, stream=None) -> None:
+    """Enqueues every layer of a stack built by make_stack; layer 0 reads `input` (device tensor)."""
+    d0 = stack[0].desc
+    f = 2 if d0.in_format in (TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2) else 1
+    need = (d0.T * d0.B * d0.Cin * d0.H * d0.W * 4 if d0.in_format == TAC_IN_F32
+            else tac_packed_bytes(d0.T, d0.B, d0.Cin, d0.H * f, d0.W * f))
+    if input.numel() * input.element_size() != need:
+        raise ValueError("input has %d bytes, layer 0 needs %d" % (input.numel() * input.element_size(), need))
+    _check(lib().tac_stack_forward(stack, len(stack), _dev_ptr(input, None, "input"), _stream(stream)))
 
 
 def tac_pack_spikes(dense01, packed=None, stream=None):

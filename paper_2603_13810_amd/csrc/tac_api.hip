@@ -192,6 +192,45 @@ int tac_conv_lif(const tac_layer_desc_t* d, const void* input, const void* w_pre
   return TAC_OK;
 }
 
+int tac_stack_check(const tac_stack_layer_t* layers, int32_t n_layers, int32_t* bad_layer) {
+  if (!layers) return TAC_ERR_NULL;
+  if (n_layers < 1) return TAC_ERR_BAD_SHAPE;
+  if (bad_layer) *bad_layer = -1;
+  int32_t T = 0, Ho = 0, Wo = 0;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const tac_layer_desc_t& d = layers[l].desc;
+    if (l > 0) {
+      const tac_layer_desc_t& prev = layers[l - 1].desc;
+      const bool pooled = d.in_format == TAC_IN_BITS_POOL2 || d.in_format == TAC_IN_BITS_MAXPOOL2;
+      bool ok = d.in_format != TAC_IN_F32 && d.B == prev.B && d.Cin == prev.Cout && d.T == T;
+      if (pooled) ok = ok && Ho % 2 == 0 && Wo % 2 == 0 && d.H == Ho / 2 && d.W == Wo / 2;
+      else ok = ok && d.H == Ho && d.W == Wo;
+      if (!ok) {
+        if (bad_layer) *bad_layer = l;
+        return TAC_ERR_BAD_SHAPE;
+      }
+    }
+    const int rc = tac_out_shape(&d, &T, &Ho, &Wo);
+    if (rc) {
+      if (bad_layer) *bad_layer = l;
+      return rc;
+    }
+  }
+  return TAC_OK;
+}
+
+int tac_stack_forward(const tac_stack_layer_t* layers, int32_t n_layers, const void* input, void* stream) {
+  int rc = tac_stack_check(layers, n_layers, nullptr);
+  if (rc) return rc;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const tac_stack_layer_t& L = layers[l];
+    rc = tac_conv_lif(&L.desc, l == 0 ? input : layers[l - 1].out_spikes_packed, L.w_prepared, L.bias, L.v_inout,
+                      L.out_spikes_packed, L.v_trace, stream);
+    if (rc) return rc;
+  }
+  return TAC_OK;
+}
+
 int tac_pack_spikes(const uint8_t* dense01, uint32_t* packed, int64_t rows, int32_t W, void* stream) {
   if (!dense01 || !packed) return TAC_ERR_NULL;
   if (rows < 1 || W < 1) return TAC_ERR_BAD_SHAPE;

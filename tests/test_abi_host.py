@@ -138,3 +138,39 @@ def test_status_strings():
     assert api.tac_status_string(0) == "ok"
     assert api.tac_status_string(-99) == "unknown status"
     assert api.tac_last_error() == ""
+
+
+def _stack(descs):
+    arr = (api.tac_stack_layer_t * len(descs))()
+    for i, d in enumerate(descs):
+        arr[i].desc = d
+        arr[i].w_prepared = 0x1000
+        arr[i].out_spikes_packed = 0x2000
+    return arr
+
+
+def test_stack_check_follows_shapes_steps_and_pools_from_layer_to_layer():
+    mk = lambda T, Cin, H, W, Cout, **kw: api.make_desc(T, 2, Cin, H, W, Cout, beta=0.9, theta=1.0, **kw)
+    C, P, S = api.TAC_COLLAPSE, api.TAC_PRESERVE, api.TAC_PER_STEP
+    good = [mk(25, 2, 64, 64, 16, K=4, mode=C, stride=2),                               # 25 -> 7 steps, 32 x 32
+            mk(7, 16, 16, 16, 32, K=2, mode=P, in_format=api.TAC_IN_BITS_MAXPOOL2),     # pooled to 16 x 16, 7 steps
+            mk(7, 32, 16, 16, 8, K=4, mode=C),                                          # 7 -> 2 steps
+            mk(2, 8, 8, 8, 8, mode=S, in_format=api.TAC_IN_BITS_POOL2)]
+    assert api.tac_stack_check(_stack(good)) == (api.TAC_OK, -1)
+    assert api.tac_stack_check(_stack(good[:1])) == (api.TAC_OK, -1)
+    for layer, change in [(1, dict(T=6)), (1, dict(Cin=8)), (1, dict(H=32)), (2, dict(T=4)), (3, dict(W=16)), (2, dict(B=3)),
+                          (1, dict(in_format=api.TAC_IN_F32))]:
+        bad = [api.tac_layer_desc_t.from_buffer_copy(d) for d in good]
+        for k, v in change.items():
+            setattr(bad[layer], k, v)
+        assert api.tac_stack_check(_stack(bad)) == (api.TAC_ERR_BAD_SHAPE, layer), (layer, change)
+    bad = [api.tac_layer_desc_t.from_buffer_copy(d) for d in good]
+    bad[2].K = 0
+    assert api.tac_stack_check(_stack(bad)) == (api.TAC_ERR_BAD_K, 2)
+    # an odd size cannot be pooled
+    odd = [mk(4, 2, 14, 14, 4, K=2, mode=P, stride=2), mk(4, 4, 3, 3, 4, mode=S, in_format=api.TAC_IN_BITS_POOL2)]
+    assert api.tac_stack_check(_stack(odd)) == (api.TAC_ERR_BAD_SHAPE, 1)
+    L = api.lib()
+    assert L.tac_stack_check(None, 1, None) == api.TAC_ERR_NULL
+    assert L.tac_stack_check(_stack(good), 0, None) == api.TAC_ERR_BAD_SHAPE
+    assert L.tac_stack_forward(None, 1, None, None) == api.TAC_ERR_NULL
