@@ -193,7 +193,7 @@ int tac_pack_spikes(const uint8_t* dense01, uint32_t* packed, int64_t rows, int3
 int tac_unpack_spikes(const uint32_t* packed, uint8_t* dense01, int64_t rows, int32_t W, void* stream);
 
 /* Host-side accounting since the last reset, summed over tac_conv_lif calls of
- * this process: convolution stages executed (T/K per call; Table 3 counts these
+ * this process: convolution stages executed (ceil(T/K) per call; Table 3 counts these
  * "conv calls" over all layers) and LIF steps (T_out per call). */
 int tac_get_counters(uint64_t* conv_stages, uint64_t* lif_steps);
 int tac_reset_counters(void);

@@ -20,6 +20,7 @@ _SRC = os.path.join(_HERE, "tac_oracle.c")
 _LIB = os.path.join(_HERE, "libtac_oracle.so")
 
 PER_STEP, TAC, TAC_TP = 0, 1, 2
+FAST_SIGMOID, ARCTAN = 0, 1      # surrogate gradients (Sec. 5.1, Training)
 
 
 def build(force: bool = False) -> str:
@@ -68,6 +69,8 @@ def _load():
         lib.oracle_maxpool2.restype = None
         lib.oracle_fold_batchnorm.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_double, ctypes.c_int, ctypes.c_int, vp, vp]
         lib.oracle_fold_batchnorm.restype = None
+        lib.oracle_backward.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.oracle_backward.restype = ctypes.c_int
         lib.oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -233,3 +236,32 @@ def conv_lif_neurons(spikes, weight, bias=None, *, idx, K=1, beta, theta, mode, 
     if rc:
         raise ValueError("oracle rejected the request (code %d)" % rc)
     return out_s, v_pre, v_fin
+
+
+def conv_lif_backward(spikes, weight, v_pre, g_out, *, K=1, beta, theta, mode, stride=1, pad=1,
+                      surrogate=FAST_SIGMOID, alpha=25.0, detach_reset=False, want_input_grad=True):
+    """Backward pass of one conv-LIF layer with a surrogate gradient (Sec. 5.1, Training).
+
+    spikes as in conv_lif (no pooled input); v_pre [T_out,B,Cout,Ho,Wo] is the membrane before the
+    reset that conv_lif returned; g_out, same shape, is dL/d(output spikes).  Returns a dict with
+    dY [G,B,Cout,Ho,Wo] (dL/dY_k), dW [Cout,Cin,kh,kw], dbias [Cout] and g_in [T,B,Cin,H,W]
+    (dL/d(input frames); None when not wanted)."""
+    lib = _load()
+    spikes = _as_input(spikes)
+    weight = np.ascontiguousarray(weight, dtype=np.float64)
+    d, Ho, Wo = _desc(spikes, weight, K, beta, theta, stride, pad, False, False, 1)
+    Kg = 1 if mode == PER_STEP else K
+    G = -(-d.T // Kg)
+    T_out = d.T if mode != TAC else G
+    v_pre = np.ascontiguousarray(v_pre, dtype=np.float64)
+    g_out = np.ascontiguousarray(g_out, dtype=np.float64)
+    assert v_pre.shape == (T_out, d.B, d.Cout, Ho, Wo) and g_out.shape == v_pre.shape
+    dY = np.zeros((G, d.B, d.Cout, Ho, Wo))
+    dW = np.zeros(weight.shape)
+    dbias = np.zeros(d.Cout)
+    g_in = np.zeros(spikes.shape) if want_input_grad else None
+    rc = lib.oracle_backward(ctypes.byref(d), int(mode), int(surrogate), float(alpha), int(bool(detach_reset)),
+                             _ptr(spikes), _ptr(weight), _ptr(v_pre), _ptr(g_out), _ptr(dY), _ptr(dW), _ptr(dbias), _ptr(g_in))
+    if rc:
+        raise ValueError("oracle rejected the request (code %d)" % rc)
+    return dict(dY=dY, dW=dW, dbias=dbias, g_in=g_in)

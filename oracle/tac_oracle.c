@@ -35,6 +35,8 @@
  * convolution, exact rational brute force).  The paper's accuracy tables are
  * parity unpinned: they need datasets and trained weights.
  */
+#define _USE_MATH_DEFINES
+#define _GNU_SOURCE
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -413,6 +415,114 @@ int oracle_neurons(const oracle_desc_t* d, int mode, const uint8_t* S, const dou
   free(w);
   free(w_last);
   return bad ? -5 : 0;
+}
+
+/* ---- backward pass with a surrogate gradient (Sec. 5.1 "Training", App. C) ----
+ *
+ * The paper trains with backpropagation through time and names its surrogates (fast sigmoid with
+ * alpha = 25, arctan with alpha = 2) and "detach reset" without printing formulas; the forms taken
+ * here are the published ones those names refer to, in x = V - theta:
+ *   kind 0, fast sigmoid:  ds/dV := 1 / (1 + alpha |x|)^2
+ *   kind 1, arctan:        ds/dV := (alpha / 2) / (1 + (pi alpha x / 2)^2)
+ * The forward pass is the one above.  Number the LIF steps n = 0 .. N-1 (one per group for
+ * per-step and TAC, one per frame for TAC-TP), step n in group k(n) with decay d_n (beta^Kg for
+ * TAC, beta otherwise):  V_n = d_n V'_{n-1} + Y_k(n),  s_n = [V_n >= theta],  V'_n = V_n - theta s_n.
+ * Given g_n = dL/ds_n for a loss that depends on the output spikes only, backwards in n with
+ * c = dL/dV'_n (zero after the last step):
+ *   dL/dV_n = g_n ds/dV + c (1 - theta ds/dV)      (detach reset: the factor of c is 1)
+ *   dL/dY_k(n) += dL/dV_n;      c <- d_n dL/dV_n
+ * and from dY_k = dL/dY_k the gradients of Y_k = bias + Conv2d(A_k, W), A_k = sum_j w_j S_{kK+j}:
+ *   dbias[co] = sum dY_k;   dW[co][ci][ky][kx] = sum dY_k[b][co][y][x] A_k[b][ci][y s + ky - p][x s + kx - p];
+ *   dA_k[b][ci][iy][ix] = sum over (co, ky, kx, y, x with y s + ky - p = iy, x s + kx - p = ix) dY_k W;
+ *   dL/dS_{kK+j} = w_j dA_k.
+ *   v_pre [N][n_out]   membrane before the reset at every LIF step (the forward pass returns it)
+ *   g_out [N][n_out]   dL/ds
+ *   dY    [G][n_out]   out;  dW [Cout][Cin][kh][kw] out;  dbias [Cout] out or NULL;
+ *   g_in  [T][B][Cin][H][W] out or NULL.   mode: 0 per-step, 1 TAC, 2 TAC-TP.  No pooled input. */
+static double surrogate(int kind, double alpha, double x) {
+  if (kind == 0) {
+    const double t = 1.0 + alpha * fabs(x);
+    return 1.0 / (t * t);
+  }
+  const double t = 0.5 * M_PI * alpha * x;
+  return 0.5 * alpha / (1.0 + t * t);
+}
+
+int oracle_backward(const oracle_desc_t* d0, int mode, int kind, double alpha, int detach_reset,
+                    const uint8_t* S, const double* Wt, const double* v_pre, const double* g_out,
+                    double* dY, double* dW, double* dbias, double* g_in) {
+  oracle_desc_t dd = *d0;
+  if (mode == 0) dd.K = 1;
+  const oracle_desc_t* d = &dd;
+  int rc = check_desc(d, 1);
+  if (rc) return rc;
+  if (mode < 0 || mode > 2 || kind < 0 || kind > 1 || d->pool2) return -4;
+  const int Ho = oracle_out_h(d), Wo = oracle_out_w(d);
+  const int64_t n_out = (int64_t)d->B * d->Cout * Ho * Wo;
+  const int64_t n_in = (int64_t)d->B * d->Cin * d->H * d->W;
+  const int G = n_groups(d);
+  /* 1. the LIF recurrence backwards */
+  for (int64_t i = 0; i < (int64_t)G * n_out; ++i) dY[i] = 0.0;
+  for (int64_t i = 0; i < n_out; ++i) {
+    double c = 0.0;
+    int64_t n = (mode == 2) ? d->T : G;                 /* LIF steps */
+    for (int k = G - 1; k >= 0; --k) {
+      const int Kg = group_frames(d, k);
+      const int nlif = (mode == 2) ? Kg : 1;
+      double decay = d->beta;
+      if (mode == 1) {
+        decay = 1.0;
+        for (int e = 0; e < Kg; ++e) decay *= d->beta;
+      }
+      for (int j = nlif - 1; j >= 0; --j) {
+        --n;
+        const double sg = surrogate(kind, alpha, v_pre[n * n_out + i] - d->theta);
+        const double gv = g_out[n * n_out + i] * sg + c * (detach_reset ? 1.0 : 1.0 - d->theta * sg);
+        dY[(int64_t)k * n_out + i] += gv;
+        c = decay * gv;
+      }
+    }
+  }
+  /* 2. gradients of the convolution, group by group */
+  double* A = (double*)malloc(sizeof(double) * (size_t)n_in);
+  double* X = (double*)malloc(sizeof(double) * (size_t)n_in);
+  double* dA = (double*)malloc(sizeof(double) * (size_t)n_in);
+  if (!A || !X || !dA) return -3;
+  const int64_t n_w = (int64_t)d->Cout * d->Cin * d->kh * d->kw;
+  for (int64_t i = 0; i < n_w; ++i) dW[i] = 0.0;
+  if (dbias) for (int co = 0; co < d->Cout; ++co) dbias[co] = 0.0;
+  for (int k = 0; k < G; ++k) {
+    const double* dy = dY + (int64_t)k * n_out;
+    oracle_aggregate(d, S, k, A, X, X);
+    for (int64_t i = 0; i < n_in; ++i) dA[i] = 0.0;
+    for (int b = 0; b < d->B; ++b)
+      for (int co = 0; co < d->Cout; ++co)
+        for (int y = 0; y < Ho; ++y)
+          for (int x = 0; x < Wo; ++x) {
+            const double g = dy[(((int64_t)b * d->Cout + co) * Ho + y) * Wo + x];
+            if (dbias) dbias[co] += g;
+            for (int ci = 0; ci < d->Cin; ++ci)
+              for (int ky = 0; ky < d->kh; ++ky)
+                for (int kx = 0; kx < d->kw; ++kx) {
+                  const int iy = y * d->stride + ky - d->pad, ix = x * d->stride + kx - d->pad;
+                  if (iy < 0 || iy >= d->H || ix < 0 || ix >= d->W) continue;
+                  const int64_t wi = (((int64_t)co * d->Cin + ci) * d->kh + ky) * d->kw + kx;
+                  const int64_t ii = (((int64_t)b * d->Cin + ci) * d->H + iy) * d->W + ix;
+                  dW[wi] += g * A[ii];
+                  dA[ii] += g * Wt[wi];
+                }
+          }
+    if (g_in) {
+      const int Kg = group_frames(d, k);
+      double* w = (double*)malloc(sizeof(double) * (size_t)Kg);
+      oracle_decay_weights(d->beta, Kg, w);
+      for (int j = 0; j < Kg; ++j)
+        for (int64_t i = 0; i < n_in; ++i) g_in[((int64_t)k * d->K + j) * n_in + i] = w[j] * dA[i];
+      free(w);
+    }
+  }
+  free(A); free(X); free(dA);
+  return 0;
 }
 
 int oracle_max_threads(void) {
