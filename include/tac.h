@@ -189,6 +189,44 @@ int tac_stack_check(const tac_stack_layer_t* layers, int32_t n_layers, int32_t* 
  * layers before a failing one have been enqueued. */
 int tac_stack_forward(const tac_stack_layer_t* layers, int32_t n_layers, const void* input, void* stream);
 
+/* Backward pass of one layer for training with backpropagation through time and a surrogate
+ * gradient (Sec. 5.1 "Training"; App. C lists surrogate, alpha and "detach reset" per dataset).
+ * The step function's derivative is replaced, in x = V - theta, by
+ *   TAC_SG_FAST_SIGMOID  1 / (1 + alpha |x|)^2            (alpha = 25 in the rate-coded runs)
+ *   TAC_SG_ARCTAN        (alpha / 2) / (1 + (pi alpha x / 2)^2)   (alpha = 2 in the event-data runs)
+ * With the LIF steps numbered n (one per group for per-step and TAC, one per frame for TAC-TP),
+ * V_n = d_n V'_{n-1} + Y_k(n), s_n = [V_n >= theta], V'_n = V_n - theta s_n, the pass runs backwards
+ * with c = dL/dV'_n (zero after the last step):
+ *   dL/dV_n = dL/ds_n ds/dV + c (1 - theta ds/dV)   (detach_reset != 0: + c),   c <- d_n dL/dV_n,
+ *   dL/dY_k = sum of dL/dV_n over the steps of group k,
+ * then dbias = sum dY_k, dW = sum_k dY_k (x) A_k, dL/dS_{kK+j} = beta^(Kg-1-j) ConvTranspose(dY_k, W):
+ * one pair of convolution gradients per group, T/K instead of T (the call-count reduction of
+ * Sec. 4 applies to the backward pass as well).  fp32 arithmetic whatever desc->precision says
+ * (the rounding of a bf16 forward pass is passed straight through). */
+enum { TAC_SG_FAST_SIGMOID = 0, TAC_SG_ARCTAN = 1 };
+typedef struct tac_backward_desc {
+  int32_t surrogate;      /* TAC_SG_FAST_SIGMOID / TAC_SG_ARCTAN                                */
+  int32_t detach_reset;   /* != 0: no gradient through the spike in the reset term              */
+  float alpha;            /* surrogate sharpness, > 0                                           */
+} tac_backward_desc_t;
+
+/*   input      DEVICE, read-only: the packed frames the forward pass read (TAC_IN_BITS only)
+ *   w_oihw     DEVICE, read-only, float32 [Cout][Cin][3][3] (the plain weights, not the prepared ones)
+ *   v_trace    DEVICE, read-only, float32 [T_out][B][Cout][Ho][Wo]: what the forward pass wrote
+ *   grad_out   DEVICE, read-only, float32 [T_out][B][Cout][Ho][Wo]: dL/d(output spikes)
+ *   grad_y     DEVICE, written, float32 [G][B][Cout][Ho][Wo], G = ceil(T/K) (T for per-step): dL/dY_k
+ *   grad_w     DEVICE, written (not accumulated), float32 [Cout][Cin][3][3]
+ *   grad_bias  DEVICE, written, float32 [Cout], or NULL
+ *   grad_in    DEVICE, written, float32 [T][B][Cin][H][W]: dL/d(input frames), the grad_out of the
+ *              layer before; NULL for a first layer (skips that stage)
+ * Enqueued on `stream`; nothing is allocated or synchronised; sums over pixels use float atomics,
+ * so the last bits of grad_w and grad_bias depend on the order of arrival.
+ * Errors: as tac_conv_lif; TAC_ERR_UNSUPPORTED for other input formats than TAC_IN_BITS, W > 1024 or
+ * more than 65535 (group, sample) pairs; TAC_ERR_BAD_PARAM for a bad surrogate or alpha <= 0. */
+int tac_conv_lif_backward(const tac_layer_desc_t* desc, const tac_backward_desc_t* bwd, const void* input,
+                          const float* w_oihw, const float* v_trace, const float* grad_out, float* grad_y,
+                          float* grad_w, float* grad_bias, float* grad_in, void* stream);
+
 int tac_pack_spikes(const uint8_t* dense01, uint32_t* packed, int64_t rows, int32_t W, void* stream);
 int tac_unpack_spikes(const uint32_t* packed, uint8_t* dense01, int64_t rows, int32_t W, void* stream);
 

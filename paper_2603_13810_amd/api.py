@@ -25,7 +25,7 @@ MODE_NAMES = {TAC_PER_STEP: "per_step", TAC_COLLAPSE: "TAC", TAC_PRESERVE: "TAC_
 
 EXPORTS = ("tac_out_shape", "tac_packed_bytes", "tac_select_kernel", "tac_prepared_weight_bytes",
            "tac_prepare_weights", "tac_conv_lif", "tac_pack_spikes", "tac_unpack_spikes", "tac_fold_batchnorm",
-           "tac_stack_check", "tac_stack_forward", "tac_get_counters", "tac_reset_counters", "tac_status_string",
+           "tac_stack_check", "tac_stack_forward", "tac_conv_lif_backward", "tac_get_counters", "tac_reset_counters", "tac_status_string",
            "tac_last_error")
 
 
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
         L.tac_stack_check.restype = ctypes.c_int
         L.tac_stack_forward.argtypes = [vp, ctypes.c_int32, vp, vp]
         L.tac_stack_forward.restype = ctypes.c_int
+        L.tac_conv_lif_backward.argtypes = [dp, ctypes.POINTER(tac_backward_desc_t)] + [vp] * 9
+        L.tac_conv_lif_backward.restype = ctypes.c_int
         L.tac_reset_counters.argtypes = []
         L.tac_reset_counters.restype = ctypes.c_int
         L.tac_status_string.argtypes = [ctypes.c_int]
@@ -203,6 +205,40 @@ def tac_conv_lif(desc, spikes_packed, w_prepared, bias=None, v_inout=None, out_s
                               _dev_ptr(out_spikes_packed, None, "out_spikes_packed"),
                               _dev_ptr(v_trace, torch.float32, "v_trace"), _stream(stream)))
     return out_spikes_packed
+
+
+TAC_SG_FAST_SIGMOID, TAC_SG_ARCTAN = 0, 1
+
+
+class tac_backward_desc_t(ctypes.Structure):
+    _fields_ = [("surrogate", ctypes.c_int32), ("detach_reset", ctypes.c_int32), ("alpha", ctypes.c_float)]
+
+
+def tac_conv_lif_backward(desc, spikes_packed, w_oihw, v_trace, grad_out, *, surrogate=TAC_SG_FAST_SIGMOID, alpha=25.0,
+                          detach_reset=False, want_input_grad=True, stream=None):
+    """Backward pass of one layer.  Device tensors; returns dict(grad_y, grad_w, grad_bias, grad_in)."""
+    import torch
+    T_out, Ho, Wo = tac_out_shape(desc)
+    K = 1 if desc.mode == TAC_PER_STEP else min(desc.K, desc.T)
+    G = -(-desc.T // K)
+    dev = spikes_packed.device
+    if spikes_packed.numel() * spikes_packed.element_size() != tac_packed_bytes(desc.T, desc.B, desc.Cin, desc.H, desc.W):
+        raise ValueError("spikes_packed does not match the description")
+    if tuple(w_oihw.shape) != (desc.Cout, desc.Cin, 3, 3):
+        raise ValueError("w_oihw must be [Cout,Cin,3,3]")
+    for name, t in (("v_trace", v_trace), ("grad_out", grad_out)):
+        if tuple(t.shape) != (T_out, desc.B, desc.Cout, Ho, Wo):
+            raise ValueError("%s must be [T_out,B,Cout,Ho,Wo]" % name)
+    grad_y = torch.empty((G, desc.B, desc.Cout, Ho, Wo), dtype=torch.float32, device=dev)
+    grad_w = torch.empty((desc.Cout, desc.Cin, 3, 3), dtype=torch.float32, device=dev)
+    grad_bias = torch.empty((desc.Cout,), dtype=torch.float32, device=dev)
+    grad_in = torch.empty((desc.T, desc.B, desc.Cin, desc.H, desc.W), dtype=torch.float32, device=dev) if want_input_grad else None
+    bwd = tac_backward_desc_t(surrogate=surrogate, detach_reset=int(bool(detach_reset)), alpha=alpha)
+    _check(lib().tac_conv_lif_backward(ctypes.byref(desc), ctypes.byref(bwd), _dev_ptr(spikes_packed, None, "spikes_packed"),
+                                       _dev_ptr(w_oihw, torch.float32, "w_oihw"), _dev_ptr(v_trace, torch.float32, "v_trace"),
+                                       _dev_ptr(grad_out, torch.float32, "grad_out"), _dev_ptr(grad_y), _dev_ptr(grad_w),
+                                       _dev_ptr(grad_bias), _dev_ptr(grad_in), _stream(stream)))
+    return dict(grad_y=grad_y, grad_w=grad_w, grad_bias=grad_bias, grad_in=grad_in)
 
 
 class tac_stack_layer_t(ctypes.Structure):

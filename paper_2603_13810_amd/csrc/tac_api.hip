@@ -231,6 +231,47 @@ int tac_stack_forward(const tac_stack_layer_t* layers, int32_t n_layers, const v
   return TAC_OK;
 }
 
+int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* bwd, const void* input,
+                          const float* w_oihw, const float* v_trace, const float* grad_out, float* grad_y,
+                          float* grad_w, float* grad_bias, float* grad_in, void* stream) {
+  tac_layer_desc_t eff;
+  int rc = effective(d, &eff);
+  if (rc) return rc;
+  if (!bwd || !input || !w_oihw || !v_trace || !grad_out || !grad_y || !grad_w) return TAC_ERR_NULL;
+  if (bwd->surrogate != TAC_SG_FAST_SIGMOID && bwd->surrogate != TAC_SG_ARCTAN) return TAC_ERR_BAD_PARAM;
+  if (!(bwd->alpha > 0.0f) || !std::isfinite(bwd->alpha)) return TAC_ERR_BAD_PARAM;
+  if (((uintptr_t)input | (uintptr_t)w_oihw | (uintptr_t)v_trace | (uintptr_t)grad_out | (uintptr_t)grad_y |
+       (uintptr_t)grad_w | (uintptr_t)grad_bias | (uintptr_t)grad_in) & 3u)
+    return TAC_ERR_ALIGN;
+  if (eff.in_format != TAC_IN_BITS || eff.W > 1024) return TAC_ERR_UNSUPPORTED;
+
+  tac::BackwardParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.spikes = static_cast<const uint32_t*>(input); p.w = w_oihw; p.v_trace = v_trace; p.grad_out = grad_out;
+  p.grad_y = grad_y; p.grad_w = grad_w; p.grad_bias = grad_bias; p.grad_in = grad_in;
+  p.T = eff.T; p.B = eff.B; p.Cin = eff.Cin; p.H = eff.H; p.W = eff.W; p.Cout = eff.Cout; p.stride = eff.stride;
+  p.Ho = (eff.H + 2 - 3) / eff.stride + 1;
+  p.Wo = (eff.W + 2 - 3) / eff.stride + 1;
+  p.Wwi = (eff.W + 31) / 32;
+  p.K = eff.K;
+  p.K_last = eff.T % eff.K;
+  p.G = (eff.T + eff.K - 1) / eff.K;
+  if ((long long)p.G * p.B > 65535) return TAC_ERR_UNSUPPORTED;
+  p.n_steps = eff.mode == TAC_COLLAPSE ? p.G : eff.T;
+  p.mode = eff.mode; p.surrogate = bwd->surrogate; p.detach_reset = bwd->detach_reset != 0;
+  p.beta = eff.beta; p.theta = eff.theta; p.alpha = bwd->alpha;
+  // powers of beta in double from the fp32 beta, rounded once (as in the forward pass)
+  const double beta = (double)eff.beta;
+  double pw = 1.0;
+  for (int j = p.K - 1; j >= 0; --j) { p.wj[j] = (float)pw; pw *= beta; }
+  p.decay_full = (float)pw;
+  pw = 1.0;
+  for (int j = p.K_last - 1; j >= 0; --j) { p.wj_last[j] = (float)pw; pw *= beta; }
+  p.decay_last = (float)pw;
+  hipError_t e = tac::backward_launch(p, (hipStream_t)stream);
+  return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_conv_lif_backward");
+}
+
 int tac_pack_spikes(const uint8_t* dense01, uint32_t* packed, int64_t rows, int32_t W, void* stream) {
   if (!dense01 || !packed) return TAC_ERR_NULL;
   if (rows < 1 || W < 1) return TAC_ERR_BAD_SHAPE;

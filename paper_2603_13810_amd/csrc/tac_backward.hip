@@ -1,0 +1,231 @@
+// Backward pass of the conv-LIF layer with a surrogate gradient (Sec. 5.1 "Training", App. C):
+// the LIF recurrence backwards in time, then the two gradients of Y_k = bias + Conv2d(A_k, W).
+// fp32 vector arithmetic, any shape; one convolution-gradient stage per group of K frames, like
+// the forward pass (T/K stages for TAC and TAC-TP, T for the per-step layer).
+//
+//   lif_backward_kernel  dL/dY_k from dL/ds and the membranes the forward pass recorded
+//   wgrad_kernel         dW, dbias: A_k rebuilt from the packed frames, strip by strip, in LDS
+//   dgrad_kernel         dL/dS_{kK+j} = beta^(Kg-1-j) * (dY_k convolved back through W)
+#include "tac_internal.h"
+
+namespace tac {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kCoTile = 8;        // output channels per wgrad workgroup
+constexpr int kStripRows = 8;     // output rows per wgrad strip
+constexpr int kCiTile = 4;        // input channels per dgrad thread
+
+// ds/dV in x = V - theta
+__device__ __forceinline__ float surrogate(int kind, float alpha, float x) {
+  if (kind == TAC_SG_FAST_SIGMOID) {
+    const float t = 1.0f + alpha * fabsf(x);
+    return 1.0f / (t * t);
+  }
+  const float t = 1.5707963267948966f * alpha * x;
+  return 0.5f * alpha / (1.0f + t * t);
+}
+
+__device__ __forceinline__ int group_frames(const BackwardParams& p, int k) {
+  return (k == p.G - 1 && p.K_last) ? p.K_last : p.K;
+}
+
+// One thread per output neuron; groups and their LIF steps backwards, c = dL/dV' carried.
+__global__ __launch_bounds__(kThreads) void lif_backward_kernel(const BackwardParams p) {
+  const size_t n_out = (size_t)p.B * p.Cout * p.Ho * p.Wo;
+  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= n_out) return;
+  float c = 0.0f;
+  size_t n = (size_t)p.n_steps;
+  for (int k = p.G - 1; k >= 0; --k) {
+    const int Kg = group_frames(p, k);
+    const int nlif = p.mode == TAC_PRESERVE ? Kg : 1;
+    const float decay = p.mode == TAC_COLLAPSE ? (Kg == p.K ? p.decay_full : p.decay_last) : p.beta;
+    float acc = 0.0f;
+    for (int j = nlif - 1; j >= 0; --j) {
+      --n;
+      const float sg = surrogate(p.surrogate, p.alpha, p.v_trace[n * n_out + i] - p.theta);
+      const float gv = p.grad_out[n * n_out + i] * sg + c * (p.detach_reset ? 1.0f : 1.0f - p.theta * sg);
+      acc += gv;
+      c = decay * gv;
+    }
+    p.grad_y[(size_t)k * n_out + i] = acc;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void zero_kernel(float* __restrict__ a, size_t n) {
+  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < n) a[i] = 0.0f;
+}
+
+// A_k at (frame group k, sample b, channel ci, iy, ix), zero outside the image (Eq. 2)
+__device__ __forceinline__ float aggregate_at(const BackwardParams& p, int k, int Kg, int b, int ci, int iy, int ix) {
+  if (iy < 0 || iy >= p.H || ix < 0 || ix >= p.W) return 0.0f;
+  const float* wj = Kg == p.K ? p.wj : p.wj_last;
+  const size_t fstride = (size_t)p.B * p.Cin * p.H * p.Wwi;
+  const uint32_t* src = p.spikes + ((size_t)k * p.K * p.B + b) * p.Cin * p.H * p.Wwi + ((size_t)ci * p.H + iy) * p.Wwi + (ix >> 5);
+  float a = 0.0f;
+  for (int j = 0; j < Kg; ++j) a += ((src[j * fstride] >> (ix & 31)) & 1u) ? wj[j] : 0.0f;
+  return a;
+}
+
+// Workgroup = (tile of kCoTile output channels, input channel ci, slice of the (group, sample,
+// row strip) list).  Per strip the aggregate rows it touches are rebuilt in LDS (with the zero
+// border), then every thread takes output pixels of the strip: 9 aggregates x kCoTile gradients.
+// Partial sums are reduced over the workgroup and added to dW (and to dbias by the ci = 0
+// workgroups) with float atomics; both arrays are cleared by zero_kernel before.
+__global__ __launch_bounds__(kThreads) void wgrad_kernel(const BackwardParams p, int n_strips, int n_split) {
+  extern __shared__ float a_strip[];             // [(kStripRows - 1) * stride + 3][W + 2]
+  __shared__ float red[kThreads / 64][kCoTile * 9 + kCoTile];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int co0 = blockIdx.x * kCoTile, ci = blockIdx.y;
+  const int WP = p.W + 2;
+  const int rows_in = (kStripRows - 1) * p.stride + 3;
+  const size_t plane = (size_t)p.Ho * p.Wo;
+  float acc[kCoTile][9], accb[kCoTile];
+#pragma unroll
+  for (int c = 0; c < kCoTile; ++c) {
+    accb[c] = 0.0f;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) acc[c][t] = 0.0f;
+  }
+  const int items = p.G * p.B * n_strips;
+  for (int it = blockIdx.z; it < items; it += n_split) {
+    const int strip = it % n_strips, kb = it / n_strips;
+    const int b = kb % p.B, k = kb / p.B;
+    const int Kg = group_frames(p, k);
+    const int y0 = strip * kStripRows;
+    __syncthreads();                             // the strip before has been consumed
+    for (int e = tid; e < rows_in * WP; e += kThreads) {
+      const int r = e / WP, xx = e - r * WP;
+      a_strip[e] = aggregate_at(p, k, Kg, b, ci, y0 * p.stride - 1 + r, xx - 1);
+    }
+    __syncthreads();
+    const int rows = min(kStripRows, p.Ho - y0);
+    const float* dy = p.grad_y + ((size_t)k * p.B + b) * p.Cout * plane + (size_t)y0 * p.Wo;
+    for (int px = tid; px < rows * p.Wo; px += kThreads) {
+      const int yl = px / p.Wo, x = px - yl * p.Wo;
+      float a[9];
+#pragma unroll
+      for (int t = 0; t < 9; ++t) a[t] = a_strip[(yl * p.stride + t / 3) * WP + x * p.stride + t % 3];
+#pragma unroll
+      for (int c = 0; c < kCoTile; ++c) {
+        const float g = co0 + c < p.Cout ? dy[(size_t)(co0 + c) * plane + px] : 0.0f;
+        accb[c] += g;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) acc[c][t] = fmaf(g, a[t], acc[c][t]);
+      }
+    }
+  }
+  // reduction: lanes of a wave by shuffles, the four waves through LDS, then one atomic per sum
+#pragma unroll
+  for (int c = 0; c < kCoTile; ++c) {
+#pragma unroll
+    for (int t = 0; t < 10; ++t) {
+      float v = t < 9 ? acc[c][t] : accb[c];
+      for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+      if (lane == 0) red[wave][t < 9 ? c * 9 + t : kCoTile * 9 + c] = v;
+    }
+  }
+  __syncthreads();
+  if (tid < kCoTile * 9 + kCoTile) {
+    float v = 0.0f;
+    for (int w = 0; w < kThreads / 64; ++w) v += red[w][tid];
+    if (tid < kCoTile * 9) {
+      const int c = tid / 9, t = tid - c * 9;
+      if (co0 + c < p.Cout) atomicAdd(p.grad_w + ((size_t)(co0 + c) * p.Cin + ci) * 9 + t, v);
+    } else if (ci == 0 && p.grad_bias) {
+      const int c = tid - kCoTile * 9;
+      if (co0 + c < p.Cout) atomicAdd(p.grad_bias + co0 + c, v);
+    }
+  }
+}
+
+// Thread = one input pixel (iy, ix) of (group k, sample b), kCiTile input channels: sums
+// dY_k[co][y][x] W[co][ci][ky][kx] over the outputs (y, x) whose window covers the pixel, then
+// writes the gradient of each of the group's frames, dA scaled by the frame's weight.
+__global__ __launch_bounds__(kThreads) void dgrad_kernel(const BackwardParams p) {
+  const int ci0 = blockIdx.y * kCiTile;
+  const int b = blockIdx.z % p.B, k = blockIdx.z / p.B;
+  const int px = blockIdx.x * kThreads + threadIdx.x;
+  if (px >= p.H * p.W) return;
+  const int iy = px / p.W, ix = px - iy * p.W;
+  const size_t plane = (size_t)p.Ho * p.Wo;
+  // the outputs that see this pixel through tap (ky, kx): y = (iy + 1 - ky) / stride when that divides
+  int off[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    const int ny = iy + 1 - t / 3, nx = ix + 1 - t % 3;
+    const bool ok = ny >= 0 && nx >= 0 && ny % p.stride == 0 && nx % p.stride == 0 && ny / p.stride < p.Ho && nx / p.stride < p.Wo;
+    off[t] = ok ? (ny / p.stride) * p.Wo + nx / p.stride : -1;
+  }
+  float dA[kCiTile];
+#pragma unroll
+  for (int c = 0; c < kCiTile; ++c) dA[c] = 0.0f;
+  const float* dy = p.grad_y + ((size_t)k * p.B + b) * p.Cout * plane;
+  for (int co = 0; co < p.Cout; ++co) {
+    float g[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) g[t] = off[t] >= 0 ? dy[(size_t)co * plane + off[t]] : 0.0f;
+#pragma unroll
+    for (int c = 0; c < kCiTile; ++c) {
+      if (ci0 + c < p.Cin) {
+        const float* w = p.w + ((size_t)co * p.Cin + ci0 + c) * 9;     // uniform over the workgroup
+#pragma unroll
+        for (int t = 0; t < 9; ++t) dA[c] = fmaf(g[t], w[t], dA[c]);
+      }
+    }
+  }
+  const int Kg = group_frames(p, k);
+  const float* wj = Kg == p.K ? p.wj : p.wj_last;
+  const size_t in_plane = (size_t)p.H * p.W;
+  for (int j = 0; j < Kg; ++j)
+#pragma unroll
+    for (int c = 0; c < kCiTile; ++c)
+      if (ci0 + c < p.Cin)
+        p.grad_in[(((size_t)(k * p.K + j) * p.B + b) * p.Cin + ci0 + c) * in_plane + px] = wj[j] * dA[c];
+}
+
+}  // namespace
+
+size_t backward_wgrad_lds_bytes(int W, int stride) { return (size_t)((kStripRows - 1) * stride + 3) * (W + 2) * sizeof(float); }
+
+hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
+  const size_t n_out = (size_t)p.B * p.Cout * p.Ho * p.Wo;
+  hipLaunchKernelGGL(lif_backward_kernel, dim3((unsigned)((n_out + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  const size_t n_w = (size_t)p.Cout * p.Cin * 9;
+  hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((n_w + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, p.grad_w, n_w);
+  if (p.grad_bias)
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((p.Cout + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, p.grad_bias,
+                       (size_t)p.Cout);
+  const int co_tiles = (p.Cout + kCoTile - 1) / kCoTile;
+  const int n_strips = (p.Ho + kStripRows - 1) / kStripRows;
+  const long long items = (long long)p.G * p.B * n_strips;
+  long long split = (4096 + (long long)co_tiles * p.Cin - 1) / ((long long)co_tiles * p.Cin);   // about 4096 workgroups
+  if (split > items) split = items;
+  if (split > 65535) split = 65535;
+  if (split < 1) split = 1;
+  const size_t lds = backward_wgrad_lds_bytes(p.W, p.stride);
+  static bool attr_done = false;
+  if (!attr_done) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(wgrad_kernel, dim3(co_tiles, p.Cin, (unsigned)split), dim3(kThreads), lds, s, p, n_strips, (int)split);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  if (p.grad_in) {
+    const dim3 grid((p.H * p.W + kThreads - 1) / kThreads, (p.Cin + kCiTile - 1) / kCiTile, p.G * p.B);
+    hipLaunchKernelGGL(dgrad_kernel, grid, dim3(kThreads), 0, s, p);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace tac

@@ -55,6 +55,27 @@ size_t mfma_small_weight_bytes(const tac_layer_desc_t& d);
 hipError_t mfma_small_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s);
 hipError_t mfma_small_launch(const LayerParams& p, hipStream_t s);
 
+// The backward pass (surrogate-gradient BPTT of one layer), resolved on the host.
+struct BackwardParams {
+  const uint32_t* spikes;   // packed input frames of the forward pass
+  const float* w;           // [Cout][Cin][3][3], as given to tac_prepare_weights
+  const float* v_trace;     // [n_steps][B][Cout][Ho][Wo] membrane before the reset, from the forward pass
+  const float* grad_out;    // [n_steps][B][Cout][Ho][Wo] dL/d(output spikes)
+  float* grad_y;            // [G][B][Cout][Ho][Wo] dL/dY_k, written
+  float* grad_w;            // [Cout][Cin][3][3], written
+  float* grad_bias;         // [Cout] or nullptr
+  float* grad_in;           // [T][B][Cin][H][W] or nullptr
+  int T, B, Cin, H, W, Cout, stride, Ho, Wo, Wwi;
+  int K, K_last, G;         // frames per group, frames of a shorter last group (0: none), groups
+  int n_steps;              // LIF steps = output steps of the forward pass
+  int mode, surrogate, detach_reset;
+  float beta, theta, alpha;
+  float decay_full, decay_last;          // beta^K, beta^K_last (TAC)
+  float wj[TAC_MAX_K], wj_last[TAC_MAX_K];   // beta^(Kg-1-j) for a whole group and for the shorter last one
+};
+hipError_t backward_launch(const BackwardParams& p, hipStream_t s);
+size_t backward_wgrad_lds_bytes(int W, int stride);
+
 hipError_t pack_launch(const uint8_t* dense, uint32_t* packed, int64_t rows, int W, hipStream_t s);
 hipError_t fold_bn_launch(const float* w, const float* bias, const float* gamma, const float* beta_bn, const float* mean,
                           const float* var, float eps, int Cout, int per, float* w_out, float* bias_out, hipStream_t s);

@@ -174,3 +174,22 @@ def test_stack_check_follows_shapes_steps_and_pools_from_layer_to_layer():
     assert L.tac_stack_check(None, 1, None) == api.TAC_ERR_NULL
     assert L.tac_stack_check(_stack(good), 0, None) == api.TAC_ERR_BAD_SHAPE
     assert L.tac_stack_forward(None, 1, None, None) == api.TAC_ERR_NULL
+
+
+def test_backward_rejects_bad_requests_before_any_launch():
+    L = api.lib()
+    d = _desc()
+    fake, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1002)
+    ok = api.tac_backward_desc_t(surrogate=api.TAC_SG_ARCTAN, detach_reset=1, alpha=2.0)
+    call = lambda desc, bwd, *ptrs: L.tac_conv_lif_backward(ctypes.byref(desc), bwd if bwd is None else ctypes.byref(bwd), *ptrs, None)
+    nine = [fake] * 9
+    assert call(d, None, *nine) == api.TAC_ERR_NULL
+    for i in range(6):                           # input, weights, membranes, grad_out, grad_y, grad_w are required
+        ptrs = list(nine); ptrs[i] = None
+        assert call(d, ok, *ptrs) == api.TAC_ERR_NULL, i
+    ptrs = list(nine); ptrs[5] = odd
+    assert call(d, ok, *ptrs) == api.TAC_ERR_ALIGN
+    assert call(d, api.tac_backward_desc_t(surrogate=2, detach_reset=0, alpha=2.0), *nine) == api.TAC_ERR_BAD_PARAM
+    assert call(d, api.tac_backward_desc_t(surrogate=0, detach_reset=0, alpha=0.0), *nine) == api.TAC_ERR_BAD_PARAM
+    assert call(_desc(in_format=api.TAC_IN_BITS_MAXPOOL2), ok, *nine) == api.TAC_ERR_UNSUPPORTED
+    assert call(_desc(K=0), ok, *nine) == api.TAC_ERR_BAD_K

@@ -1,0 +1,86 @@
+"""Backward pass (surrogate-gradient BPTT of one conv-LIF layer, Sec. 5.1 "Training") through the C ABI against the
+oracle: same inputs on both sides, the oracle on its own membranes in double, the library on the fp32 membranes its
+forward pass recorded."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_13810_amd import api, synth
+from gpu_util import ORACLE_MODE
+from parity_util import np_pack
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = 1e-4          # relative to the largest magnitude of the tensor: fp32 sums of up to ~1e5 terms, atomics in any order
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def _close(name, got, ref):
+    scale = max(np.abs(ref).max(), 1e-30)
+    err = np.abs(got - ref).max() / scale
+    assert err <= TOL, "%s: max error %.3g of the largest magnitude %.3g" % (name, err, scale)
+    return err
+
+
+# (Cin, Cout, H, W, stride)
+SHAPES = [(3, 5, 7, 9, 1), (16, 24, 12, 33, 2), (2, 8, 20, 100, 1), (8, 16, 17, 40, 2)]
+# (mode, K, T): whole groups, shorter last groups, a group longer than the sequence
+TIMES = [(api.TAC_PER_STEP, 1, 5), (api.TAC_COLLAPSE, 2, 6), (api.TAC_COLLAPSE, 4, 7), (api.TAC_PRESERVE, 2, 6),
+         (api.TAC_PRESERVE, 4, 10), (api.TAC_COLLAPSE, 8, 3)]
+SURR = [(api.TAC_SG_FAST_SIGMOID, 25.0, False), (api.TAC_SG_ARCTAN, 2.0, True)]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("mode,K,T", TIMES)
+@pytest.mark.parametrize("surrogate,alpha,detach", SURR)
+def test_backward_against_the_oracle(shape, mode, K, T, surrogate, alpha, detach):
+    Cin, Cout, H, W, stride = shape
+    B = 3
+    r = _rng(1200 + Cin + Cout + H + W + K + T)
+    s = (r.random((T, B, Cin, H, W)) < 0.3).astype(np.uint8)
+    w = synth.kaiming_normal(41, Cout, Cin) * np.float32(1.5)
+    bias = (r.standard_normal(Cout) * 0.1).astype(np.float32)
+    beta, theta = 0.9, 1.0
+    desc = api.make_desc(T, B, Cin, H, W, Cout, K=K, beta=beta, theta=theta, mode=mode, stride=stride)
+    T_out, Ho, Wo = api.tac_out_shape(desc)
+    g_out = r.standard_normal((T_out, B, Cout, Ho, Wo)).astype(np.float32)
+    # forward on the GPU, recording the membranes
+    sp = torch.from_numpy(np_pack(s)).to(DEV)
+    wd = torch.from_numpy(w).to(DEV)
+    v = torch.zeros((B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    vt = torch.empty((T_out, B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    api.tac_conv_lif(desc, sp, api.tac_prepare_weights(desc, wd), torch.from_numpy(bias).to(DEV), v, None, vt)
+    got = api.tac_conv_lif_backward(desc, sp, wd, vt, torch.from_numpy(g_out).to(DEV), surrogate=surrogate, alpha=alpha,
+                                    detach_reset=detach)
+    torch.cuda.synchronize()
+    # the oracle, forward and backward, on the same host inputs
+    kw = dict(K=K, beta=float(np.float32(beta)), theta=theta, mode=ORACLE_MODE[mode], stride=stride)
+    out, v_pre, _ = oracle.conv_lif(s, w.astype(np.float64), bias.astype(np.float64), **kw)
+    ref = oracle.conv_lif_backward(s, w.astype(np.float64), v_pre, g_out.astype(np.float64), surrogate=surrogate, alpha=alpha,
+                                   detach_reset=detach, **kw)
+    assert out.sum() > 0
+    errs = [_close("dL/dY", got["grad_y"].cpu().numpy(), ref["dY"]), _close("dW", got["grad_w"].cpu().numpy(), ref["dW"]),
+            _close("dbias", got["grad_bias"].cpu().numpy(), ref["dbias"]), _close("dL/dS", got["grad_in"].cpu().numpy(), ref["g_in"])]
+    print("backward", shape, api.MODE_NAMES[mode], "K=%d T=%d" % (K, T), "max errors dY %.1e dW %.1e dbias %.1e dS %.1e" % tuple(errs))
+
+
+def test_backward_first_layer_skips_the_input_gradient_and_is_repeatable_up_to_rounding():
+    r = _rng(1300)
+    s = (r.random((8, 2, 2, 16, 48)) < 0.3).astype(np.uint8)
+    w = synth.kaiming_normal(42, 12, 2)
+    desc = api.make_desc(8, 2, 2, 16, 48, 12, K=4, beta=0.5, theta=1.0, mode=api.TAC_PRESERVE, stride=2)
+    T_out, Ho, Wo = api.tac_out_shape(desc)
+    sp, wd = torch.from_numpy(np_pack(s)).to(DEV), torch.from_numpy(w).to(DEV)
+    vt = torch.empty((T_out, 2, 12, Ho, Wo), dtype=torch.float32, device=DEV)
+    api.tac_conv_lif(desc, sp, api.tac_prepare_weights(desc, wd), None, None, None, vt)
+    g = torch.from_numpy(r.standard_normal((T_out, 2, 12, Ho, Wo)).astype(np.float32)).to(DEV)
+    a = api.tac_conv_lif_backward(desc, sp, wd, vt, g, surrogate=api.TAC_SG_ARCTAN, alpha=2.0, detach_reset=True, want_input_grad=False)
+    b = api.tac_conv_lif_backward(desc, sp, wd, vt, g, surrogate=api.TAC_SG_ARCTAN, alpha=2.0, detach_reset=True, want_input_grad=False)
+    torch.cuda.synchronize()
+    assert a["grad_in"] is None
+    assert torch.equal(a["grad_y"], b["grad_y"])
+    assert torch.allclose(a["grad_w"], b["grad_w"], rtol=1e-4, atol=1e-5 * float(a["grad_w"].abs().max()))
