@@ -72,6 +72,8 @@ def parse():
     ap.add_argument("--no-table", action="store_true", help="time only the headline mode")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size (debugging only)")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time the backward pass (surrogate-gradient BPTT) of the per-step layer and of the headline mode")
     return ap.parse_args()
 
 
@@ -190,6 +192,34 @@ def main():
                 table.append(dict(mode=r["mode"], K=K, ms=round(r["kernel_ms"], 4),
                                   speedup=round(base["kernel_ms"] / r["kernel_ms"], 3), tflops=round(r["tflops"], 1)))
 
+    backward = None
+    if args.backward:
+        def time_backward(mode, K):
+            d, wp, out, (T_out, Ho, Wo) = make(mode, K)
+            v = torch.zeros((B, L.Cout, Ho, Wo), dtype=torch.float32, device=dev)
+            vt = torch.empty((T_out, B, L.Cout, Ho, Wo), dtype=torch.float32, device=dev)
+            api.tac_conv_lif(d, spikes, wp, None, v, out, vt)          # the forward pass records the membranes
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(wl.seed)
+            g_out = torch.randn(vt.shape, device=dev, generator=gen)
+            res = api.tac_conv_lif_backward(d, spikes, w_dev, vt, g_out, surrogate=api.TAC_SG_FAST_SIGMOID, alpha=25.0)
+            torch.cuda.synchronize()
+            del res
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            res = api.tac_conv_lif_backward(d, spikes, w_dev, vt, g_out, surrogate=api.TAC_SG_FAST_SIGMOID, alpha=25.0)
+            b.record()
+            torch.cuda.synchronize()
+            Kg = 1 if mode == api.TAC_PER_STEP else K
+            fl = 2 * 2.0 * B * Ho * Wo * L.Cout * L.Cin * 9 * (T // Kg)      # weight and input gradients
+            return dict(mode=api.MODE_NAMES[mode], K=Kg, ms=round(a.elapsed_time(b), 3), conv_gradient_stages=T // Kg,
+                        tflops=round(fl / (a.elapsed_time(b) * 1e-3) / 1e12, 2))
+        backward = [time_backward(api.TAC_PER_STEP, 1)]
+        if args.mode != "per_step":
+            backward.append(time_backward(MODE[args.mode], args.K))
+        for r in backward:
+            r["speedup"] = round(backward[0]["ms"] / r["ms"], 3)
+
     is_mfma = head["kernel"] == "mfma"
     peak = PEAK_BF16_TFLOPS if is_mfma else PEAK_FP32_TFLOPS
     roofline = dict(bound="mfma" if is_mfma else "alu", achieved=round(head["tflops"], 2), peak=peak,
@@ -228,7 +258,7 @@ def main():
                    "aggregation_stage_GBps": round(spikes.numel() * 4 / (head["kernel_ms"] * 1e-3) / 1e9, 1),
                    "launch_per_group_ms": None if per_group_ms is None else round(per_group_ms, 4),
                    "paper_context": "TAC training speed-ups 13.8x (Apple M3 Max) and 11.0x (NVIDIA V100), other hardware",
-                   "table": table},
+                   "table": table, "backward": backward},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
