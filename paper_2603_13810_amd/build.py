@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libtac.so")
-SOURCES = ["tac_api.hip", "tac_pack.hip", "tac_direct.hip", "tac_mfma.hip", "tac_mfma_small.hip", "tac_mfma_mid.hip", "tac_backward.hip"]
+SOURCES = ["tac_api.hip", "tac_pack.hip", "tac_direct.hip", "tac_mfma.hip", "tac_mfma_small.hip", "tac_mfma_mid.hip", "tac_backward.hip", "tac_backward_mfma.hip"]
 
 
 def hipcc() -> str:

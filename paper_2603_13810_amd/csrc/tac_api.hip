@@ -259,6 +259,7 @@ int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* 
   if ((long long)p.G * p.B > 65535) return TAC_ERR_UNSUPPORTED;
   p.n_steps = eff.mode == TAC_COLLAPSE ? p.G : eff.T;
   p.mode = eff.mode; p.surrogate = bwd->surrogate; p.detach_reset = bwd->detach_reset != 0;
+  p.bf16 = eff.precision == TAC_BF16;
   p.beta = eff.beta; p.theta = eff.theta; p.alpha = bwd->alpha;
   // powers of beta in double from the fp32 beta, rounded once (as in the forward pass)
   const double beta = (double)eff.beta;

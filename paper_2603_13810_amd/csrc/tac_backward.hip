@@ -202,6 +202,10 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
   if (p.grad_bias)
     hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((p.Cout + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, p.grad_bias,
                        (size_t)p.Cout);
+  if (p.bf16 && backward_wgrad_mfma_supported(p)) {
+    e = backward_wgrad_mfma_launch(p, s);
+    if (e != hipSuccess) return e;
+  } else {
   const int co_tiles = (p.Cout + kCoTile - 1) / kCoTile;
   const int n_strips = (p.Ho + kStripRows - 1) / kStripRows;
   const long long items = (long long)p.G * p.B * n_strips;
@@ -219,6 +223,7 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
   hipLaunchKernelGGL(wgrad_kernel, dim3(co_tiles, p.Cin, (unsigned)split), dim3(kThreads), lds, s, p, n_strips, (int)split);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
+  }
 
   if (p.grad_in) {
     const dim3 grid((p.H * p.W + kThreads - 1) / kThreads, (p.Cin + kCiTile - 1) / kCiTile, p.G * p.B);

@@ -69,12 +69,15 @@ struct BackwardParams {
   int K, K_last, G;         // frames per group, frames of a shorter last group (0: none), groups
   int n_steps;              // LIF steps = output steps of the forward pass
   int mode, surrogate, detach_reset;
+  int bf16;                 // bf16 operands on the matrix cores where the shape allows
   float beta, theta, alpha;
   float decay_full, decay_last;          // beta^K, beta^K_last (TAC)
   float wj[TAC_MAX_K], wj_last[TAC_MAX_K];   // beta^(Kg-1-j) for a whole group and for the shorter last one
 };
 hipError_t backward_launch(const BackwardParams& p, hipStream_t s);
 size_t backward_wgrad_lds_bytes(int W, int stride);
+bool backward_wgrad_mfma_supported(const BackwardParams& p);
+hipError_t backward_wgrad_mfma_launch(const BackwardParams& p, hipStream_t s);
 
 hipError_t pack_launch(const uint8_t* dense, uint32_t* packed, int64_t rows, int W, hipStream_t s);
 hipError_t fold_bn_launch(const float* w, const float* bias, const float* gamma, const float* beta_bn, const float* mean,

@@ -84,3 +84,48 @@ def test_backward_first_layer_skips_the_input_gradient_and_is_repeatable_up_to_r
     assert a["grad_in"] is None
     assert torch.equal(a["grad_y"], b["grad_y"])
     assert torch.allclose(a["grad_w"], b["grad_w"], rtol=1e-4, atol=1e-5 * float(a["grad_w"].abs().max()))
+
+
+# weight gradients on the matrix cores (bf16 layers; Cin a multiple of 32, Cout of 128, width 16/32/64/128, stride 1)
+# (Cin, Cout, H, W)
+MFMA_SHAPES = [(32, 128, 12, 32), (64, 128, 9, 64), (32, 256, 20, 16), (32, 128, 5, 128)]
+TOL_BF16 = 2e-2     # the bar of the bf16 path; dY and A_k enter the matrix cores rounded to bf16
+
+
+@pytest.mark.parametrize("shape", MFMA_SHAPES)
+@pytest.mark.parametrize("mode,K,T", [(api.TAC_PER_STEP, 1, 4), (api.TAC_COLLAPSE, 4, 8), (api.TAC_COLLAPSE, 4, 7), (api.TAC_PRESERVE, 2, 6),
+                                      (api.TAC_COLLAPSE, 16, 16)])
+def test_backward_bf16_layer_weight_gradient_on_the_matrix_cores(shape, mode, K, T):
+    from gpu_util import bf16_round_np
+    Cin, Cout, H, W = shape
+    B = 3
+    r = _rng(1400 + Cin + Cout + H + W + K + T)
+    s = (r.random((T, B, Cin, H, W)) < 0.15).astype(np.uint8)
+    w = synth.kaiming_normal(43, Cout, Cin) * np.float32(1.5)
+    bias = (r.standard_normal(Cout) * 0.1).astype(np.float32)
+    beta, theta = 0.9, 1.0
+    desc = api.make_desc(T, B, Cin, H, W, Cout, K=K, beta=beta, theta=theta, mode=mode, precision=api.TAC_BF16)
+    T_out, Ho, Wo = api.tac_out_shape(desc)
+    g_out = r.standard_normal((T_out, B, Cout, Ho, Wo)).astype(np.float32)
+    sp, wd = torch.from_numpy(np_pack(s)).to(DEV), torch.from_numpy(w).to(DEV)
+    v = torch.zeros((B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    vt = torch.empty((T_out, B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    api.tac_conv_lif(desc, sp, api.tac_prepare_weights(desc, wd), torch.from_numpy(bias).to(DEV), v, None, vt)
+    got = api.tac_conv_lif_backward(desc, sp, wd, vt, torch.from_numpy(g_out).to(DEV), surrogate=api.TAC_SG_ARCTAN, alpha=2.0,
+                                    detach_reset=True)
+    torch.cuda.synchronize()
+    # oracle: the bf16 forward pass (W and A_k rounded), then the backward pass with the rounded A_k in dW and the
+    # unrounded W in dL/dS (the library's input-gradient kernel is fp32)
+    kw = dict(K=K, beta=float(np.float32(beta)), theta=theta, mode=ORACLE_MODE[mode])
+    out, v_pre, _ = oracle.conv_lif(s, bf16_round_np(w).astype(np.float64), bias.astype(np.float64), round_a_bf16=True, **kw)
+    ref = oracle.conv_lif_backward(s, w.astype(np.float64), v_pre, g_out.astype(np.float64), surrogate=oracle.ARCTAN, alpha=2.0,
+                                   detach_reset=True, round_a_bf16=True, **kw)
+    assert out.sum() > 0
+
+    def err(name, a, b, tol):
+        e = np.abs(a - b).max() / np.abs(b).max()
+        assert e <= tol, "%s: %.3g" % (name, e)
+        return e
+    e = [err("dL/dY", got["grad_y"].cpu().numpy(), ref["dY"], 1e-3), err("dW", got["grad_w"].cpu().numpy(), ref["dW"], TOL_BF16),
+         err("dbias", got["grad_bias"].cpu().numpy(), ref["dbias"], 1e-3), err("dL/dS", got["grad_in"].cpu().numpy(), ref["g_in"], 1e-3)]
+    print("backward bf16", shape, api.MODE_NAMES[mode], "K=%d T=%d" % (K, T), "errors dY %.1e dW %.1e dbias %.1e dS %.1e" % tuple(e))
