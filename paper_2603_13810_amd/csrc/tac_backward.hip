@@ -225,7 +225,9 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
   if (e != hipSuccess) return e;
   }
 
-  if (p.grad_in) {
+  if (p.grad_in && p.bf16 && backward_dgrad_mfma_supported(p)) {
+    e = backward_dgrad_mfma_launch(p, s);
+  } else if (p.grad_in) {
     const dim3 grid((p.H * p.W + kThreads - 1) / kThreads, (p.Cin + kCiTile - 1) / kCiTile, p.G * p.B);
     hipLaunchKernelGGL(dgrad_kernel, grid, dim3(kThreads), 0, s, p);
     e = hipGetLastError();

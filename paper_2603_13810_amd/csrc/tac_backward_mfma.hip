@@ -136,7 +136,139 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(const BackwardPara
   }
 }
 
+// Input gradient on the matrix cores (stride 1):
+//   dA_k[b][ci][iy][ix] = sum over co, ky, kx of W[co][ci][ky][kx] * dY_k[b][co][iy + 1 - ky][ix + 1 - kx],
+//   dL/dS_{kK+j} = beta^(Kg-1-j) dA_k.
+// Same orientation as the forward kernels, D[32 ci x 32 px] += W^T[32 ci x 16 co] . dY[16 co x 32 px],
+// 32 consecutive x of one row per MFMA.  Workgroup = 32 input channels x a slice of the (group,
+// sample, row strip) list; its weights (all output channels, 9 taps) are turned into MFMA
+// fragments in LDS once, the dY rows of a strip (with a zero border) go to LDS as bf16
+// [co / 8][row][column][8 co], 64 output channels at a time; a wave owns NBW blocks of 32 pixels.
+// XS = W / 32; R = rows per strip; NBW = R * XS / 4.
+template <int XS, int R, int NBW>
+__global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardParams p, int n_strips, int n_split) {
+  static_assert(R * XS == 4 * NBW, "the strip's pixel blocks are dealt out evenly over the four waves");
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  constexpr int W = XS * 32, WP = W + 2, RI = R + 2;
+  constexpr int kTileBytes = 8 * RI * WP * 16;          // 64 output channels of dY
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 31, h = lane >> 5;
+  const int ci0 = blockIdx.x * 32;
+  const int n_steps16 = p.Cout >> 4;                     // contraction steps of 16 output channels
+  uint8_t* const wl = lds + kTileBytes;                  // weight fragments [tap][step][lane][8]
+  const size_t plane = (size_t)p.Ho * p.Wo;              // = H * W (stride 1)
+
+  // weight fragments: lane (n, h) of (tap, step) holds W[16 step + 8 h + i][ci0 + n][tap], i = 0..7
+  for (int e = tid; e < 9 * n_steps16 * 64; e += kThreads) {
+    const int l = e & 63, st = (e >> 6) % n_steps16, tap = (e >> 6) / n_steps16;
+    const float* src = p.w + ((size_t)(16 * st + 8 * (l >> 5)) * p.Cin + ci0 + (l & 31)) * 9 + tap;
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = src[(size_t)i * p.Cin * 9];
+    *reinterpret_cast<u32x4*>(wl + e * 16) = u32x4{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
+  }
+  // zero border columns of the dY tile (never written again)
+  for (int e = tid; e < 8 * RI * 2; e += kThreads) {
+    const int side = e & 1, orow = e >> 1;
+    *reinterpret_cast<u32x4*>(lds + (orow * WP + (side ? W + 1 : 0)) * 16) = u32x4{0, 0, 0, 0};
+  }
+
+  const int items = p.G * p.B * n_strips;
+  for (int it = blockIdx.z; it < items; it += n_split) {
+    const int strip = it % n_strips, kb = it / n_strips;
+    const int b = kb % p.B, k = kb / p.B;
+    const int y0 = strip * R;
+    f32x16 acc[NBW];
+#pragma unroll
+    for (int q = 0; q < NBW; ++q)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[q][r] = 0.0f;
+    for (int c0 = 0; c0 < p.Cout; c0 += 64) {
+      __syncthreads();                                   // the tile before has been read (and the weights are there)
+      // ---- dY rows y0 - 1 .. y0 + R of 64 output channels: a thread per (8 channels, row, 4 pixels)
+      const float* dy = p.grad_y + (((size_t)k * p.B + b) * p.Cout + c0) * plane;
+      for (int e = tid; e < 8 * RI * (W / 4); e += kThreads) {
+        const int x4 = e % (W / 4), orow = e / (W / 4);
+        const int r = orow % RI, o = orow / RI;
+        const int y = y0 - 1 + r;
+        f32x4 g[8];
+        if (y >= 0 && y < p.Ho) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) g[i] = *reinterpret_cast<const f32x4*>(dy + (size_t)(8 * o + i) * plane + (size_t)y * W + 4 * x4);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) g[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          *reinterpret_cast<u32x4*>(lds + ((o * RI + r) * WP + 4 * x4 + q + 1) * 16) =
+              u32x4{pack_bf16(g[0][q], g[1][q]), pack_bf16(g[2][q], g[3][q]), pack_bf16(g[4][q], g[5][q]), pack_bf16(g[6][q], g[7][q])};
+      }
+      __syncthreads();
+      // ---- MFMAs: 9 taps x 4 steps of 16 channels x the wave's pixel blocks
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        const int ky = tap / 3, kx = tap % 3;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+          const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wl + ((tap * n_steps16 + (c0 >> 4) + st) * 64 + lane) * 16);
+#pragma unroll
+          for (int q = 0; q < NBW; ++q) {
+            const int nb = wave * NBW + q, yl = nb / XS, x0 = (nb % XS) * 32;
+            const bf16x8 df = *reinterpret_cast<const bf16x8*>(
+                lds + (((2 * st + h) * RI + yl + 2 - ky) * WP + x0 + n + 2 - kx) * 16);
+            acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, df, acc[q], 0, 0, 0);
+          }
+        }
+      }
+    }
+    // ---- dL/dS of the group's frames: register r on lane (n, h) is channel ci0 + 8 (r / 4) + 4 h + r % 4, pixel n of the block
+    const int Kg = group_frames(p, k);
+    const float* wj = Kg == p.K ? p.wj : p.wj_last;
+#pragma unroll
+    for (int q = 0; q < NBW; ++q) {
+      const int nb = wave * NBW + q, iy = y0 + nb / XS, ix = (nb % XS) * 32 + n;
+      if (iy < p.H) {
+        for (int j = 0; j < Kg; ++j) {
+          float* dst = p.grad_in + (((size_t)(k * p.K + j) * p.B + b) * p.Cin + ci0) * plane + (size_t)iy * W + ix;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) dst[(size_t)(8 * (r >> 2) + 4 * h + (r & 3)) * plane] = wj[j] * acc[q][r];
+        }
+      }
+    }
+  }
+}
+
 }  // namespace
+
+bool backward_dgrad_mfma_supported(const BackwardParams& p) {
+  return p.stride == 1 && (p.W == 32 || p.W == 64 || p.W == 128) && p.Cin % 32 == 0 && p.Cout % 64 == 0 && p.Cout <= 128 &&
+         ((uintptr_t)p.grad_y & 15u) == 0;
+}
+
+hipError_t backward_dgrad_mfma_launch(const BackwardParams& p, hipStream_t s) {
+  const int R = p.W == 32 ? 12 : (p.W == 64 ? 6 : 2);
+  const int n_strips = (p.H + R - 1) / R;
+  const size_t lds = (size_t)8 * (R + 2) * (p.W + 2) * 16 + (size_t)9 * (p.Cout / 16) * 1024;
+  const int ci_blocks = p.Cin / 32;
+  const long long items = (long long)p.G * p.B * n_strips;
+  long long split = (256 + ci_blocks - 1) / ci_blocks;
+  if (split > items) split = items;
+  if (split > 65535) split = 65535;
+  if (split < 1) split = 1;
+  auto launch = [&](auto kern) -> hipError_t {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(ci_blocks, 1, (unsigned)split), dim3(kThreads), lds, s, p, n_strips, (int)split);
+    return hipGetLastError();
+  };
+  switch (p.W) {
+    case 32: return launch(&dgrad_mfma_kernel<1, 12, 3>);
+    case 64: return launch(&dgrad_mfma_kernel<2, 6, 3>);
+    default: return launch(&dgrad_mfma_kernel<4, 2, 2>);
+  }
+}
 
 bool backward_wgrad_mfma_supported(const BackwardParams& p) {
   return p.stride == 1 && (p.W == 16 || p.W == 32 || p.W == 64 || p.W == 128) && p.Cin % 32 == 0 && p.Cout % 128 == 0 &&

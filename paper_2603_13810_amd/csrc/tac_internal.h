@@ -78,6 +78,8 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s);
 size_t backward_wgrad_lds_bytes(int W, int stride);
 bool backward_wgrad_mfma_supported(const BackwardParams& p);
 hipError_t backward_wgrad_mfma_launch(const BackwardParams& p, hipStream_t s);
+bool backward_dgrad_mfma_supported(const BackwardParams& p);
+hipError_t backward_dgrad_mfma_launch(const BackwardParams& p, hipStream_t s);
 
 hipError_t pack_launch(const uint8_t* dense, uint32_t* packed, int64_t rows, int W, hipStream_t s);
 hipError_t fold_bn_launch(const float* w, const float* bias, const float* gamma, const float* beta_bn, const float* mean,
