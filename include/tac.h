@@ -201,8 +201,12 @@ int tac_stack_forward(const tac_stack_layer_t* layers, int32_t n_layers, const v
  *   dL/dY_k = sum of dL/dV_n over the steps of group k,
  * then dbias = sum dY_k, dW = sum_k dY_k (x) A_k, dL/dS_{kK+j} = beta^(Kg-1-j) ConvTranspose(dY_k, W):
  * one pair of convolution gradients per group, T/K instead of T (the call-count reduction of
- * Sec. 4 applies to the backward pass as well).  fp32 arithmetic whatever desc->precision says
- * (the rounding of a bf16 forward pass is passed straight through). */
+ * Sec. 4 applies to the backward pass as well).  With desc->precision = TAC_BF16 the two
+ * convolution gradients run on the matrix cores where the shape allows (stride 1; Cin a multiple of
+ * 32; width 16, 32, 64 or 128 and Cout a multiple of 128 for dW; width 32, 64 or 128 and Cout = 64
+ * or 128 for dL/dS; grad_y 16-byte aligned): dY_k, A_k and W enter them rounded to bfloat16, sums
+ * are fp32.  Everything else, and TAC_FP32, is fp32 vector arithmetic.  The rounding inside a bf16
+ * forward pass is differentiated as if it were not there. */
 enum { TAC_SG_FAST_SIGMOID = 0, TAC_SG_ARCTAN = 1 };
 typedef struct tac_backward_desc {
   int32_t surrogate;      /* TAC_SG_FAST_SIGMOID / TAC_SG_ARCTAN                                */
