@@ -26,7 +26,7 @@ __device__ __forceinline__ int group_frames(const BackwardParams& p, int k) {
 
 // XS = W / 16: MFMA steps per output row.
 template <int XS>
-__global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(const BackwardParams p, int R, int n_strips, int n_split) {
+__global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(const BackwardParams p, int R, int n_strips, int n_split) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -66,37 +66,44 @@ __global__ __launch_bounds__(kThreads) void wgrad_mfma_kernel(const BackwardPara
     };
     request_row(0);
     __syncthreads();                                     // the fragments of the strip before have been read
-    // ---- aggregates of 32 channels x (R + 2) rows, a thread per (channel, row, block of 8 pixels):
-    //      ten values x = 8 xb - 1 .. 8 xb + 8, written as three blocks of eight (kx = 0, 1, 2)
+    // ---- aggregates of 32 channels x (R + 2) rows, a thread per (channel, row, word of 32 pixels): the
+    //      34 sums x = 32 wi - 1 .. 32 wi + 32 in 2^-23 fixed point (as the forward kernels form them),
+    //      written as blocks of eight for kx = 0, 1, 2
+    constexpr int WWI = W >= 32 ? W / 32 : 1;            // words per row
+    constexpr int XBW = W >= 32 ? 4 : XB;                // blocks of 8 pixels per word
     const size_t fstride = (size_t)p.B * p.Cin * p.H * p.Wwi;
-    for (int e = tid; e < 32 * rows_in * XB; e += kThreads) {
-      const int xb = e % XB, cr = e / XB;
+    for (int e = tid; e < 32 * rows_in * WWI; e += kThreads) {
+      const int wi = e % WWI, cr = e / WWI;
       const int ci = cr & 31, r = cr >> 5;
       const int iy = y0 - 1 + r;
-      float a[10];
+      uint32_t q[34];
 #pragma unroll
-      for (int i = 0; i < 10; ++i) a[i] = 0.0f;
+      for (int i = 0; i < 34; ++i) q[i] = 0u;
       if (iy >= 0 && iy < p.H) {
-        const uint32_t* src = p.spikes + ((size_t)k * p.K * p.B + b) * p.Cin * p.H * p.Wwi + ((size_t)(ci0 + ci) * p.H + iy) * p.Wwi;
-        const int wi = xb >> 2, sh = (xb & 3) * 8;       // word and bit of pixel 8 xb
+        const uint32_t* src = p.spikes + ((size_t)k * p.K * p.B + b) * p.Cin * p.H * p.Wwi + ((size_t)(ci0 + ci) * p.H + iy) * p.Wwi + wi;
         for (int j = 0; j < Kg; ++j) {
           const uint32_t* sw = src + j * fstride;
-          const uint32_t cur = sw[wi];
-          const uint32_t left = (sh == 0 && wi > 0) ? sw[wi - 1] >> 31 : 0u;                  // pixel 8 xb - 1 in the word before
-          const uint32_t right = (sh == 24 && wi + 1 < p.Wwi) ? sw[wi + 1] & 1u : 0u;         // pixel 8 xb + 8 in the next word
-          // bits 0..9 = pixels 8 xb - 1 .. 8 xb + 8 (beyond the row: the zero pad bits of the packed format)
-          uint32_t bits = sh == 0 ? ((cur & 0x1ffu) << 1) | left : (cur >> (sh - 1)) & 0x3ffu;
-          if (sh == 24) bits |= right << 9;
+          const uint32_t cur = sw[0];
+          const uint32_t left = wi > 0 ? sw[-1] >> 31 : 0u;                 // pixel 32 wi - 1
+          const uint32_t right = wi + 1 < WWI ? sw[1] & 1u : 0u;            // pixel 32 wi + 32
+          const uint32_t wq = (uint32_t)(wj[j] * 8388608.0f + 0.5f);        // beta^(Kg-1-j) in 2^-23 units
+          q[0] = __umul24(left, wq) + q[0];
 #pragma unroll
-          for (int i = 0; i < 10; ++i) a[i] += ((bits >> i) & 1u) ? wj[j] : 0.0f;
+          for (int i = 0; i < 32; ++i) q[i + 1] = __umul24(__builtin_amdgcn_ubfe(cur, i, 1), wq) + q[i + 1];
+          q[33] = __umul24(right, wq) + q[33];
         }
       }
+      // beyond the row (x = -1, x = W) the sums are zero: no word there, or the zero pad bits of the format
 #pragma unroll
-      for (int kx = 0; kx < 3; ++kx) {
-        u32x4 v;
+      for (int xl = 0; xl < XBW; ++xl) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = pack_bf16(a[kx + 2 * q], a[kx + 2 * q + 1]);
-        *reinterpret_cast<u32x4*>(lds + kx * copy_bytes + ((r * XB + xb) * 32 + ci) * 16) = v;
+        for (int kx = 0; kx < 3; ++kx) {
+          u32x4 v;
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+            v[t] = pack_bf16((float)q[8 * xl + kx + 2 * t] * (1.0f / 8388608.0f), (float)q[8 * xl + kx + 2 * t + 1] * (1.0f / 8388608.0f));
+          *reinterpret_cast<u32x4*>(lds + kx * copy_bytes + ((r * XB + wi * XBW + xl) * 32 + ci) * 16) = v;
+        }
       }
     }
     __syncthreads();
@@ -277,12 +284,12 @@ bool backward_wgrad_mfma_supported(const BackwardParams& p) {
 
 // dW and dbias must have been cleared.
 hipError_t backward_wgrad_mfma_launch(const BackwardParams& p, hipStream_t s) {
-  const int R = p.W <= 64 ? 384 / p.W : 3;               // output rows per strip: (R + 2) W / 8 <= 80 blocks
+  const int R = p.W <= 64 ? 256 / p.W : 2;               // output rows per strip; two workgroups per compute unit fit the LDS
   const int n_strips = (p.Ho + R - 1) / R;
   const size_t lds = (size_t)3 * (R + 2) * (p.W / 8) * 512;
   const int ci_blocks = p.Cin / 32, co_blocks = p.Cout / 128;
   const long long items = (long long)p.G * p.B * n_strips;
-  long long split = (256 + ci_blocks * co_blocks - 1) / (ci_blocks * co_blocks);      // one workgroup per compute unit
+  long long split = (512 + ci_blocks * co_blocks - 1) / (ci_blocks * co_blocks);      // two workgroups per compute unit
   if (split > items) split = items;
   if (split > 65535) split = 65535;
   if (split < 1) split = 1;
