@@ -24,17 +24,21 @@ __device__ __forceinline__ int group_frames(const BackwardParams& p, int k) {
   return (k == p.G - 1 && p.K_last) ? p.K_last : p.K;
 }
 
-// XS = W / 16: MFMA steps per output row.
+// XS = W / 16: MFMA steps per output row; R = 16 / XS output rows per strip.
 template <int XS>
-__global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(const BackwardParams p, int R, int n_strips, int n_split) {
+__global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(const BackwardParams p, int n_strips, int n_split) {
+  constexpr int R = 16 / XS;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, h = lane >> 5;
-  const int ci0 = blockIdx.x * 32;
+  // grid: x = slice of the work list, y = block of 128 output channels, z = block of 32 input channels.  Workgroups
+  // go to the 8 XCDs round-robin in x-fastest order: with a slice count that is a multiple of 8, those that read the
+  // same dY (same slice, other input channels) share an XCD and its L2.
+  const int ci0 = blockIdx.z * 32;
   const int co_w = blockIdx.y * 128 + wave * 32;         // the wave's 32 output channels
   constexpr int W = XS * 16, XB = W >> 3;
-  const int rows_in = R + 2;
+  constexpr int rows_in = R + 2;
   const size_t plane = (size_t)p.Ho * p.Wo;
   const int copy_bytes = rows_in * XB * 512;             // one kx copy: [row][x / 8][32 ci][8] bf16
 
@@ -46,25 +50,21 @@ __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(c
   float bias_acc = 0.0f;
 
   const int items = p.G * p.B * n_strips;
-  for (int it = blockIdx.z; it < items; it += n_split) {
+  for (int it = blockIdx.x; it < items; it += n_split) {
     const int strip = it % n_strips, kb = it / n_strips;
     const int b = kb % p.B, k = kb / p.B;
     const int Kg = group_frames(p, k);
     const float* wj = Kg == p.K ? p.wj : p.wj_last;
     const int y0 = strip * R;
-    // the wave's dY of the strip's first row is requested now and arrives while the aggregates are built;
-    // after that, row yl + 1 is requested before the MFMAs of row yl
+    // the wave's first 16 dY values of the strip are requested now and arrive while the aggregates are built
     const int rows = min(R, p.Ho - y0);
     const float* dy = p.grad_y + (((size_t)k * p.B + b) * p.Cout + co_w + n) * plane + (size_t)y0 * p.Wo + 8 * h;
-    f32x4 raw[XS][2];
-    auto request_row = [&](int yl) {
-#pragma unroll
-      for (int xs = 0; xs < XS; ++xs) {
-        raw[xs][0] = *reinterpret_cast<const f32x4*>(dy + (size_t)yl * p.Wo + xs * 16);
-        raw[xs][1] = *reinterpret_cast<const f32x4*>(dy + (size_t)yl * p.Wo + xs * 16 + 4);
-      }
+    f32x4 raw[2];
+    auto request = [&](int yl, int xs) {
+      raw[0] = *reinterpret_cast<const f32x4*>(dy + (size_t)yl * p.Wo + xs * 16);
+      raw[1] = *reinterpret_cast<const f32x4*>(dy + (size_t)yl * p.Wo + xs * 16 + 4);
     };
-    request_row(0);
+    request(0, 0);
     __syncthreads();                                     // the fragments of the strip before have been read
     // ---- aggregates of 32 channels x (R + 2) rows, a thread per (channel, row, word of 32 pixels): the
     //      34 sums x = 32 wi - 1 .. 32 wi + 32 in 2^-23 fixed point (as the forward kernels form them),
@@ -107,27 +107,40 @@ __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(c
       }
     }
     __syncthreads();
-    // ---- MFMAs: rows of the strip, 16 pixels at a time
-    for (int yl = 0; yl < rows; ++yl) {
-      bf16x8 gf[XS];
-#pragma unroll
-      for (int xs = 0; xs < XS; ++xs) {
-        const f32x4 g0 = raw[xs][0], g1 = raw[xs][1];
-        bias_acc += (g0[0] + g0[1]) + (g0[2] + g0[3]) + (g1[0] + g1[1]) + (g1[2] + g1[3]);
-        const u32x4 gp = {pack_bf16(g0[0], g0[1]), pack_bf16(g0[2], g0[3]), pack_bf16(g1[0], g1[1]), pack_bf16(g1[2], g1[3])};
-        gf[xs] = __builtin_bit_cast(bf16x8, gp);
-      }
-      if (yl + 1 < rows) request_row(yl + 1);
-#pragma unroll
-      for (int xs = 0; xs < XS; ++xs) {
-#pragma unroll
-        for (int t = 0; t < 9; ++t) {
-          const int ky = t / 3, kx = t % 3;
-          const bf16x8 af = *reinterpret_cast<const bf16x8*>(lds + kx * copy_bytes + (((yl + ky) * XB + 2 * xs + h) * 32 + n) * 16);
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[xs], af, acc[t], 0, 0, 0);
+    // ---- MFMAs, column of 16 pixels by column, down the aggregate rows r of the strip: a row's three fragments
+    //      (kx = 0, 1, 2) are read once and meet output rows r (ky = 0), r - 1 (ky = 1) and r - 2 (ky = 2), whose dY
+    //      fragments are kept in a window of three; the next 16 dY values are requested one step ahead
+    static_for<0, XS>([&](auto xs_) {
+      constexpr int xs = decltype(xs_)::value;
+      bf16x8 gf[3];
+      static_for<0, R + 2>([&](auto r_) {
+        constexpr int r = decltype(r_)::value;
+        if constexpr (r < R) {
+          if (r < rows) {
+            const f32x4 g0 = raw[0], g1 = raw[1];
+            bias_acc += (g0[0] + g0[1]) + (g0[2] + g0[3]) + (g1[0] + g1[1]) + (g1[2] + g1[3]);
+            const u32x4 gp = {pack_bf16(g0[0], g0[1]), pack_bf16(g0[2], g0[3]), pack_bf16(g1[0], g1[1]), pack_bf16(g1[2], g1[3])};
+            gf[r % 3] = __builtin_bit_cast(bf16x8, gp);
+            if (r + 1 < rows) request(r + 1, xs);
+            else if (xs + 1 < XS) request(0, xs + 1);
+          }
         }
-      }
-    }
+        bf16x8 af[3];
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx)
+          af[kx] = *reinterpret_cast<const bf16x8*>(lds + kx * copy_bytes + ((r * XB + 2 * xs + h) * 32 + n) * 16);
+        static_for<0, 3>([&](auto ky_) {
+          constexpr int ky = decltype(ky_)::value, yl = r - ky;
+          if constexpr (yl >= 0 && yl < R) {
+            if (yl < rows) {
+#pragma unroll
+              for (int kx = 0; kx < 3; ++kx)
+                acc[ky * 3 + kx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[yl % 3], af[kx], acc[ky * 3 + kx], 0, 0, 0);
+            }
+          }
+        });
+      });
+    });
   }
   // register r of acc[t] on lane (n, h): output channel 8 (r / 4) + 4 h + r % 4 of the wave, input channel n
 #pragma unroll
@@ -137,7 +150,7 @@ __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(c
       const int co = co_w + 8 * (r >> 2) + 4 * h + (r & 3);
       atomicAdd(p.grad_w + ((size_t)co * p.Cin + ci0 + n) * 9 + t, acc[t][r]);
     }
-  if (p.grad_bias && blockIdx.x == 0) {
+  if (p.grad_bias && blockIdx.z == 0) {
     bias_acc += __shfl_down(bias_acc, 32, 64);           // the two pixel halves of a channel
     if (h == 0) atomicAdd(p.grad_bias + co_w + n, bias_acc);
   }
@@ -161,7 +174,7 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, h = lane >> 5;
-  const int ci0 = blockIdx.x * 32;
+  const int ci0 = blockIdx.z * 32;                      // grid as in wgrad_mfma_kernel: x = slice, z = input-channel block
   const int n_steps16 = p.Cout >> 4;                     // contraction steps of 16 output channels
   uint8_t* const wl = lds + kTileBytes;                  // weight fragments [tap][step][lane][8]
   const size_t plane = (size_t)p.Ho * p.Wo;              // = H * W (stride 1)
@@ -182,7 +195,7 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
   }
 
   const int items = p.G * p.B * n_strips;
-  for (int it = blockIdx.z; it < items; it += n_split) {
+  for (int it = blockIdx.x; it < items; it += n_split) {
     const int strip = it % n_strips, kb = it / n_strips;
     const int b = kb % p.B, k = kb / p.B;
     const int y0 = strip * R;
@@ -261,13 +274,13 @@ hipError_t backward_dgrad_mfma_launch(const BackwardParams& p, hipStream_t s) {
   const int ci_blocks = p.Cin / 32;
   const long long items = (long long)p.G * p.B * n_strips;
   long long split = (256 + ci_blocks - 1) / ci_blocks;
+  split = (split + 7) / 8 * 8;                           // a multiple of the XCD count
   if (split > items) split = items;
-  if (split > 65535) split = 65535;
   if (split < 1) split = 1;
   auto launch = [&](auto kern) -> hipError_t {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(ci_blocks, 1, (unsigned)split), dim3(kThreads), lds, s, p, n_strips, (int)split);
+    hipLaunchKernelGGL(kern, dim3((unsigned)split, 1, ci_blocks), dim3(kThreads), lds, s, p, n_strips, (int)split);
     return hipGetLastError();
   };
   switch (p.W) {
@@ -284,19 +297,19 @@ bool backward_wgrad_mfma_supported(const BackwardParams& p) {
 
 // dW and dbias must have been cleared.
 hipError_t backward_wgrad_mfma_launch(const BackwardParams& p, hipStream_t s) {
-  const int R = p.W <= 64 ? 256 / p.W : 2;               // output rows per strip; two workgroups per compute unit fit the LDS
+  const int R = 256 / p.W;                               // output rows per strip (16 MFMA steps); two workgroups per compute unit fit the LDS
   const int n_strips = (p.Ho + R - 1) / R;
   const size_t lds = (size_t)3 * (R + 2) * (p.W / 8) * 512;
   const int ci_blocks = p.Cin / 32, co_blocks = p.Cout / 128;
   const long long items = (long long)p.G * p.B * n_strips;
   long long split = (512 + ci_blocks * co_blocks - 1) / (ci_blocks * co_blocks);      // two workgroups per compute unit
+  split = (split + 7) / 8 * 8;                           // a multiple of the XCD count
   if (split > items) split = items;
-  if (split > 65535) split = 65535;
   if (split < 1) split = 1;
   auto launch = [&](auto kern) -> hipError_t {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(ci_blocks, co_blocks, (unsigned)split), dim3(kThreads), lds, s, p, R, n_strips, (int)split);
+    hipLaunchKernelGGL(kern, dim3((unsigned)split, co_blocks, ci_blocks), dim3(kThreads), lds, s, p, n_strips, (int)split);
     return hipGetLastError();
   };
   switch (p.W) {
