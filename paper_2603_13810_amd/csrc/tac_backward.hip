@@ -38,6 +38,38 @@ __global__ __launch_bounds__(kThreads) void lif_backward_kernel(const BackwardPa
   if (i >= n_out) return;
   float c = 0.0f;
   size_t n = (size_t)p.n_steps;
+  if (p.mode != TAC_PRESERVE) {
+    // one step per group: the loads of four groups are issued together, only the chain through c is serial
+    int k = p.G - 1;
+    for (; k >= 3; k -= 4) {
+      float v[4], g[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        v[u] = p.v_trace[(n - 1 - u) * n_out + i];
+        g[u] = p.grad_out[(n - 1 - u) * n_out + i];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int Kg = group_frames(p, k - u);
+        const float decay = p.mode == TAC_COLLAPSE ? (Kg == p.K ? p.decay_full : p.decay_last) : p.beta;
+        const float sg = surrogate(p.surrogate, p.alpha, v[u] - p.theta);
+        const float gv = g[u] * sg + c * (p.detach_reset ? 1.0f : 1.0f - p.theta * sg);
+        p.grad_y[(size_t)(k - u) * n_out + i] = gv;
+        c = decay * gv;
+      }
+      n -= 4;
+    }
+    for (; k >= 0; --k) {
+      --n;
+      const int Kg = group_frames(p, k);
+      const float decay = p.mode == TAC_COLLAPSE ? (Kg == p.K ? p.decay_full : p.decay_last) : p.beta;
+      const float sg = surrogate(p.surrogate, p.alpha, p.v_trace[n * n_out + i] - p.theta);
+      const float gv = p.grad_out[n * n_out + i] * sg + c * (p.detach_reset ? 1.0f : 1.0f - p.theta * sg);
+      p.grad_y[(size_t)k * n_out + i] = gv;
+      c = decay * gv;
+    }
+    return;
+  }
   for (int k = p.G - 1; k >= 0; --k) {
     const int Kg = group_frames(p, k);
     const int nlif = p.mode == TAC_PRESERVE ? Kg : 1;

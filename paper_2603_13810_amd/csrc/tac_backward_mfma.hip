@@ -59,10 +59,24 @@ __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(c
     // the wave's first 16 dY values of the strip are requested now and arrive while the aggregates are built
     const int rows = min(R, p.Ho - y0);
     const float* dy = p.grad_y + (((size_t)k * p.B + b) * p.Cout + co_w + n) * plane + (size_t)y0 * p.Wo + 8 * h;
-    f32x4 raw[2];
+    // dY is fetched a column of 16 pixels x CR rows at a time (the whole column of the strip when it has at most 4
+    // rows), one column ahead of the MFMAs that use it
+    constexpr int CR = R <= 4 ? R : 1;
+    f32x4 raw[CR][2];
     auto request = [&](int yl, int xs) {
-      raw[0] = *reinterpret_cast<const f32x4*>(dy + (size_t)yl * p.Wo + xs * 16);
-      raw[1] = *reinterpret_cast<const f32x4*>(dy + (size_t)yl * p.Wo + xs * 16 + 4);
+#pragma unroll
+      for (int c = 0; c < CR; ++c) {
+        if (yl + c < rows) {
+          raw[c][0] = *reinterpret_cast<const f32x4*>(dy + (size_t)(yl + c) * p.Wo + xs * 16);
+          raw[c][1] = *reinterpret_cast<const f32x4*>(dy + (size_t)(yl + c) * p.Wo + xs * 16 + 4);
+        }
+      }
+    };
+    auto to_fragment = [&](int c) {
+      const f32x4 g0 = raw[c][0], g1 = raw[c][1];
+      bias_acc += (g0[0] + g0[1]) + (g0[2] + g0[3]) + (g1[0] + g1[1]) + (g1[2] + g1[3]);
+      const u32x4 gp = {pack_bf16(g0[0], g0[1]), pack_bf16(g0[2], g0[3]), pack_bf16(g1[0], g1[1]), pack_bf16(g1[2], g1[3])};
+      return __builtin_bit_cast(bf16x8, gp);
     };
     request(0, 0);
     __syncthreads();                                     // the fragments of the strip before have been read
@@ -112,15 +126,19 @@ __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(c
     //      fragments are kept in a window of three; the next 16 dY values are requested one step ahead
     static_for<0, XS>([&](auto xs_) {
       constexpr int xs = decltype(xs_)::value;
-      bf16x8 gf[3];
+      constexpr int NGF = CR > 1 ? R : 3;                // fragments kept: the whole column, or a window of three rows
+      bf16x8 gf[NGF];
+      if constexpr (CR > 1) {
+#pragma unroll
+        for (int c = 0; c < CR; ++c)
+          if (c < rows) gf[c] = to_fragment(c);
+        if (xs + 1 < XS) request(0, xs + 1);
+      }
       static_for<0, R + 2>([&](auto r_) {
         constexpr int r = decltype(r_)::value;
-        if constexpr (r < R) {
+        if constexpr (CR == 1 && r < R) {
           if (r < rows) {
-            const f32x4 g0 = raw[0], g1 = raw[1];
-            bias_acc += (g0[0] + g0[1]) + (g0[2] + g0[3]) + (g1[0] + g1[1]) + (g1[2] + g1[3]);
-            const u32x4 gp = {pack_bf16(g0[0], g0[1]), pack_bf16(g0[2], g0[3]), pack_bf16(g1[0], g1[1]), pack_bf16(g1[2], g1[3])};
-            gf[r % 3] = __builtin_bit_cast(bf16x8, gp);
+            gf[r % 3] = to_fragment(0);
             if (r + 1 < rows) request(r + 1, xs);
             else if (xs + 1 < XS) request(0, xs + 1);
           }
@@ -135,7 +153,7 @@ __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(c
             if (yl < rows) {
 #pragma unroll
               for (int kx = 0; kx < 3; ++kx)
-                acc[ky * 3 + kx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[yl % 3], af[kx], acc[ky * 3 + kx], 0, 0, 0);
+                acc[ky * 3 + kx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[yl % NGF], af[kx], acc[ky * 3 + kx], 0, 0, 0);
             }
           }
         });
