@@ -212,69 +212,100 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
     *reinterpret_cast<u32x4*>(lds + (orow * WP + (side ? W + 1 : 0)) * 16) = u32x4{0, 0, 0, 0};
   }
 
+  // The workgroup's work is a list of steps (strip of its slice, block of 64 output channels).  The dY values of
+  // step s + 1 are requested from global memory before the MFMAs of step s and go to LDS after them, so that
+  // their latency hides behind the MFMAs.
   const int items = p.G * p.B * n_strips;
-  for (int it = blockIdx.x; it < items; it += n_split) {
+  const int n_chunks = p.Cout >> 6;
+  const int my_items = blockIdx.x < items ? (items - 1 - blockIdx.x) / n_split + 1 : 0;
+  const int total = my_items * n_chunks;
+  constexpr int NI = (8 * RI * (W / 4) + kThreads - 1) / kThreads;       // (8 channels, row, 4 pixels) items per thread
+  f32x4 g[NI][8];
+  struct Where { int k, b, y0, c0; };
+  auto locate = [&](int s) {
+    const int it = blockIdx.x + (s / n_chunks) * n_split;
     const int strip = it % n_strips, kb = it / n_strips;
-    const int b = kb % p.B, k = kb / p.B;
-    const int y0 = strip * R;
-    f32x16 acc[NBW];
+    return Where{kb / p.B, kb % p.B, strip * R, (s % n_chunks) * 64};
+  };
+  auto request = [&](const Where& w) {
+    const float* dy = p.grad_y + (((size_t)w.k * p.B + w.b) * p.Cout + w.c0) * plane;
 #pragma unroll
-    for (int q = 0; q < NBW; ++q)
+    for (int q = 0; q < NI; ++q) {
+      const int e = tid + q * kThreads;
+      const int x4 = e % (W / 4), orow = e / (W / 4);
+      const int r = orow % RI, o = orow / RI;
+      const int y = w.y0 - 1 + r;
+      const bool ok = e < 8 * RI * (W / 4) && y >= 0 && y < p.Ho;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[q][r] = 0.0f;
-    for (int c0 = 0; c0 < p.Cout; c0 += 64) {
-      __syncthreads();                                   // the tile before has been read (and the weights are there)
-      // ---- dY rows y0 - 1 .. y0 + R of 64 output channels: a thread per (8 channels, row, 4 pixels)
-      const float* dy = p.grad_y + (((size_t)k * p.B + b) * p.Cout + c0) * plane;
-      for (int e = tid; e < 8 * RI * (W / 4); e += kThreads) {
+      for (int i = 0; i < 8; ++i)
+        g[q][i] = ok ? *reinterpret_cast<const f32x4*>(dy + (size_t)(8 * o + i) * plane + (size_t)y * W + 4 * x4) : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+  };
+  auto to_lds = [&]() {
+#pragma unroll
+    for (int q = 0; q < NI; ++q) {
+      const int e = tid + q * kThreads;
+      if (e < 8 * RI * (W / 4)) {
         const int x4 = e % (W / 4), orow = e / (W / 4);
-        const int r = orow % RI, o = orow / RI;
-        const int y = y0 - 1 + r;
-        f32x4 g[8];
-        if (y >= 0 && y < p.Ho) {
 #pragma unroll
-          for (int i = 0; i < 8; ++i) g[i] = *reinterpret_cast<const f32x4*>(dy + (size_t)(8 * o + i) * plane + (size_t)y * W + 4 * x4);
-        } else {
-#pragma unroll
-          for (int i = 0; i < 8; ++i) g[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          *reinterpret_cast<u32x4*>(lds + ((o * RI + r) * WP + 4 * x4 + q + 1) * 16) =
-              u32x4{pack_bf16(g[0][q], g[1][q]), pack_bf16(g[2][q], g[3][q]), pack_bf16(g[4][q], g[5][q]), pack_bf16(g[6][q], g[7][q])};
+        for (int t = 0; t < 4; ++t)
+          *reinterpret_cast<u32x4*>(lds + (orow * WP + 4 * x4 + t + 1) * 16) =
+              u32x4{pack_bf16(g[q][0][t], g[q][1][t]), pack_bf16(g[q][2][t], g[q][3][t]), pack_bf16(g[q][4][t], g[q][5][t]),
+                    pack_bf16(g[q][6][t], g[q][7][t])};
       }
-      __syncthreads();
-      // ---- MFMAs: 9 taps x 4 steps of 16 channels x the wave's pixel blocks
+    }
+  };
+  f32x16 acc[NBW];
 #pragma unroll
-      for (int tap = 0; tap < 9; ++tap) {
-        const int ky = tap / 3, kx = tap % 3;
+  for (int q = 0; q < NBW; ++q)
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-          const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wl + ((tap * n_steps16 + (c0 >> 4) + st) * 64 + lane) * 16);
+    for (int r = 0; r < 16; ++r) acc[q][r] = 0.0f;
+  if (total > 0) {
+    request(locate(0));
+    to_lds();
+  }
+  __syncthreads();                                       // weights, border and the first tile are in place
+  for (int s = 0; s < total; ++s) {
+    const Where w = locate(s);
+    if (s + 1 < total) request(locate(s + 1));
+    // ---- MFMAs: 9 taps x 4 steps of 16 channels x the wave's pixel blocks
 #pragma unroll
-          for (int q = 0; q < NBW; ++q) {
-            const int nb = wave * NBW + q, yl = nb / XS, x0 = (nb % XS) * 32;
-            const bf16x8 df = *reinterpret_cast<const bf16x8*>(
-                lds + (((2 * st + h) * RI + yl + 2 - ky) * WP + x0 + n + 2 - kx) * 16);
-            acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, df, acc[q], 0, 0, 0);
+    for (int tap = 0; tap < 9; ++tap) {
+      const int ky = tap / 3, kx = tap % 3;
+#pragma unroll
+      for (int st = 0; st < 4; ++st) {
+        const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wl + ((tap * n_steps16 + (w.c0 >> 4) + st) * 64 + lane) * 16);
+#pragma unroll
+        for (int q = 0; q < NBW; ++q) {
+          const int nb = wave * NBW + q, yl = nb / XS, x0 = (nb % XS) * 32;
+          const bf16x8 df = *reinterpret_cast<const bf16x8*>(
+              lds + (((2 * st + h) * RI + yl + 2 - ky) * WP + x0 + n + 2 - kx) * 16);
+          acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, df, acc[q], 0, 0, 0);
+        }
+      }
+    }
+    if (w.c0 + 64 >= p.Cout) {
+      // ---- the strip is complete: dL/dS of the group's frames.  Register r on lane (n, h) is channel
+      //      ci0 + 8 (r / 4) + 4 h + r % 4, pixel n of the block
+      const int Kg = group_frames(p, w.k);
+      const float* wj = Kg == p.K ? p.wj : p.wj_last;
+#pragma unroll
+      for (int q = 0; q < NBW; ++q) {
+        const int nb = wave * NBW + q, iy = w.y0 + nb / XS, ix = (nb % XS) * 32 + n;
+        if (iy < p.H) {
+          for (int j = 0; j < Kg; ++j) {
+            float* dst = p.grad_in + (((size_t)(w.k * p.K + j) * p.B + w.b) * p.Cin + ci0) * plane + (size_t)iy * W + ix;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dst[(size_t)(8 * (r >> 2) + 4 * h + (r & 3)) * plane] = wj[j] * acc[q][r];
           }
         }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[q][r] = 0.0f;
       }
     }
-    // ---- dL/dS of the group's frames: register r on lane (n, h) is channel ci0 + 8 (r / 4) + 4 h + r % 4, pixel n of the block
-    const int Kg = group_frames(p, k);
-    const float* wj = Kg == p.K ? p.wj : p.wj_last;
-#pragma unroll
-    for (int q = 0; q < NBW; ++q) {
-      const int nb = wave * NBW + q, iy = y0 + nb / XS, ix = (nb % XS) * 32 + n;
-      if (iy < p.H) {
-        for (int j = 0; j < Kg; ++j) {
-          float* dst = p.grad_in + (((size_t)(k * p.K + j) * p.B + b) * p.Cin + ci0) * plane + (size_t)iy * W + ix;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) dst[(size_t)(8 * (r >> 2) + 4 * h + (r & 3)) * plane] = wj[j] * acc[q][r];
-        }
-      }
-    }
+    __syncthreads();                                     // every wave has read the tile
+    if (s + 1 < total) to_lds();
+    __syncthreads();
   }
 }
 
