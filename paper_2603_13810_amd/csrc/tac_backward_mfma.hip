@@ -188,7 +188,11 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
   static_assert(R * XS == 4 * NBW, "the strip's pixel blocks are dealt out evenly over the four waves");
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   constexpr int W = XS * 32, WP = W + 2, RI = R + 2;
-  constexpr int kTileBytes = 8 * RI * WP * 16;          // 64 output channels of dY
+  // one plane of 8 channels: [row][column][8] bf16, padded so that consecutive planes start 32 banks apart (the two
+  // halves of a wave read neighbouring planes at once)
+  constexpr int kPlane = RI * WP * 16 + 4 * ((32 + 64 - (RI * WP * 4) % 64) % 64);
+  static_assert((kPlane / 4) % 64 == 32, "plane stride: half the banks");
+  constexpr int kTileBytes = 8 * kPlane;                // 64 output channels of dY
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, h = lane >> 5;
@@ -209,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
   // zero border columns of the dY tile (never written again)
   for (int e = tid; e < 8 * RI * 2; e += kThreads) {
     const int side = e & 1, orow = e >> 1;
-    *reinterpret_cast<u32x4*>(lds + (orow * WP + (side ? W + 1 : 0)) * 16) = u32x4{0, 0, 0, 0};
+    *reinterpret_cast<u32x4*>(lds + (orow / RI) * kPlane + ((orow % RI) * WP + (side ? W + 1 : 0)) * 16) = u32x4{0, 0, 0, 0};
   }
 
   // The workgroup's work is a list of steps (strip of its slice, block of 64 output channels).  The dY values of
@@ -249,7 +253,7 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
         const int x4 = e % (W / 4), orow = e / (W / 4);
 #pragma unroll
         for (int t = 0; t < 4; ++t)
-          *reinterpret_cast<u32x4*>(lds + (orow * WP + 4 * x4 + t + 1) * 16) =
+          *reinterpret_cast<u32x4*>(lds + (orow / RI) * kPlane + ((orow % RI) * WP + 4 * x4 + t + 1) * 16) =
               u32x4{pack_bf16(g[q][0][t], g[q][1][t]), pack_bf16(g[q][2][t], g[q][3][t]), pack_bf16(g[q][4][t], g[q][5][t]),
                     pack_bf16(g[q][6][t], g[q][7][t])};
       }
@@ -279,7 +283,7 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
         for (int q = 0; q < NBW; ++q) {
           const int nb = wave * NBW + q, yl = nb / XS, x0 = (nb % XS) * 32;
           const bf16x8 df = *reinterpret_cast<const bf16x8*>(
-              lds + (((2 * st + h) * RI + yl + 2 - ky) * WP + x0 + n + 2 - kx) * 16);
+              lds + (2 * st + h) * kPlane + ((yl + 2 - ky) * WP + x0 + n + 2 - kx) * 16);
           acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, df, acc[q], 0, 0, 0);
         }
       }
@@ -319,7 +323,8 @@ bool backward_dgrad_mfma_supported(const BackwardParams& p) {
 hipError_t backward_dgrad_mfma_launch(const BackwardParams& p, hipStream_t s) {
   const int R = p.W == 32 ? 12 : (p.W == 64 ? 6 : 2);
   const int n_strips = (p.H + R - 1) / R;
-  const size_t lds = (size_t)8 * (R + 2) * (p.W + 2) * 16 + (size_t)9 * (p.Cout / 16) * 1024;
+  const int cells = (R + 2) * (p.W + 2);                 // the kernel's padded plane of 8 channels
+  const size_t lds = (size_t)8 * (cells * 16 + 4 * ((32 + 64 - (cells * 4) % 64) % 64)) + (size_t)9 * (p.Cout / 16) * 1024;
   const int ci_blocks = p.Cin / 32;
   const long long items = (long long)p.G * p.B * n_strips;
   long long split = (256 + ci_blocks - 1) / ci_blocks;
