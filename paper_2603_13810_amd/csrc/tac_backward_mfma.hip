@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(c
 // 32 consecutive x of one row per MFMA.  Workgroup = 32 input channels x a slice of the (group,
 // sample, row strip) list; its weights (all output channels, 9 taps) are turned into MFMA
 // fragments in LDS once, the dY rows of a strip (with a zero border) go to LDS as bf16
-// [co / 8][row][column][8 co], 64 output channels at a time; a wave owns NBW blocks of 32 pixels.
+// [co / 8][row][column][8 co], 64 output channels at a time; a wave owns NBW blocks of 32 pixels, one below the other.
 // XS = W / 32; R = rows per strip; NBW = R * XS / 4.
 template <int XS, int R, int NBW>
 __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardParams p, int n_strips, int n_split) {
@@ -259,6 +259,7 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
       }
     }
   };
+  const int x0 = (wave % XS) * 32, yl0 = (wave / XS) * NBW;     // the wave's column block and first row in the strip
   f32x16 acc[NBW];
 #pragma unroll
   for (int q = 0; q < NBW; ++q)
@@ -272,20 +273,25 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
   for (int s = 0; s < total; ++s) {
     const Where w = locate(s);
     if (s + 1 < total) request(locate(s + 1));
-    // ---- MFMAs: 9 taps x 4 steps of 16 channels x the wave's pixel blocks
+    // ---- MFMAs.  The wave's NBW blocks of 32 pixels sit one below the other (rows yl0 .. yl0 + NBW - 1 of column
+    //      block x0), so a dY fragment of tile row yl0 + rr serves the output rows rr - 2 + ky for ky = 0, 1, 2:
+    //      per 16 channels and kx, 3 weight fragments and NBW + 2 dY fragments feed 3 NBW MFMAs
 #pragma unroll
-    for (int tap = 0; tap < 9; ++tap) {
-      const int ky = tap / 3, kx = tap % 3;
+    for (int st = 0; st < 4; ++st) {
 #pragma unroll
-      for (int st = 0; st < 4; ++st) {
-        const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wl + ((tap * n_steps16 + (w.c0 >> 4) + st) * 64 + lane) * 16);
+      for (int kx = 0; kx < 3; ++kx) {
+        bf16x8 wf[3];
 #pragma unroll
-        for (int q = 0; q < NBW; ++q) {
-          const int nb = wave * NBW + q, yl = nb / XS, x0 = (nb % XS) * 32;
-          const bf16x8 df = *reinterpret_cast<const bf16x8*>(
-              lds + (2 * st + h) * kPlane + ((yl + 2 - ky) * WP + x0 + n + 2 - kx) * 16);
-          acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, df, acc[q], 0, 0, 0);
-        }
+        for (int ky = 0; ky < 3; ++ky)
+          wf[ky] = *reinterpret_cast<const bf16x8*>(wl + (((ky * 3 + kx) * n_steps16 + (w.c0 >> 4) + st) * 64 + lane) * 16);
+        static_for<0, NBW + 2>([&](auto rr_) {
+          constexpr int rr = decltype(rr_)::value;
+          const bf16x8 df = *reinterpret_cast<const bf16x8*>(lds + (2 * st + h) * kPlane + ((yl0 + rr) * WP + x0 + n + 2 - kx) * 16);
+          static_for<0, 3>([&](auto ky_) {
+            constexpr int ky = decltype(ky_)::value, q = rr - 2 + ky;
+            if constexpr (q >= 0 && q < NBW) acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ky], df, acc[q], 0, 0, 0);
+          });
+        });
       }
     }
     if (w.c0 + 64 >= p.Cout) {
@@ -295,7 +301,7 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
       const float* wj = Kg == p.K ? p.wj : p.wj_last;
 #pragma unroll
       for (int q = 0; q < NBW; ++q) {
-        const int nb = wave * NBW + q, iy = w.y0 + nb / XS, ix = (nb % XS) * 32 + n;
+        const int iy = w.y0 + yl0 + q, ix = x0 + n;
         if (iy < p.H) {
           for (int j = 0; j < Kg; ++j) {
             float* dst = p.grad_in + (((size_t)(w.k * p.K + j) * p.B + w.b) * p.Cin + ci0) * plane + (size_t)iy * W + ix;
