@@ -215,10 +215,17 @@ def main():
             return dict(mode=api.MODE_NAMES[mode], K=Kg, ms=round(a.elapsed_time(b), 3), conv_gradient_stages=T // Kg,
                         tflops=round(fl / (a.elapsed_time(b) * 1e-3) / 1e12, 2))
         backward = [time_backward(api.TAC_PER_STEP, 1)]
-        if args.mode != "per_step":
-            backward.append(time_backward(MODE[args.mode], args.K))
+        for K in wl.Ks:
+            if K > 1:
+                backward.append(time_backward(api.TAC_COLLAPSE, K))
+        fwd = {(r["mode"], r["K"]): r["ms"] for r in table}
+        fwd[("per_step", 1)] = fwd.get(("per_step", 1), head["kernel_ms"] if args.mode == "per_step" else None)
         for r in backward:
             r["speedup"] = round(backward[0]["ms"] / r["ms"], 3)
+            f, f0 = fwd.get((r["mode"], r["K"])), fwd.get(("per_step", 1))
+            if f is not None and f0 is not None:      # forward + backward of the layer: one training step without the optimiser
+                r["forward_plus_backward_ms"] = round(f + r["ms"], 3)
+                r["training_step_speedup"] = round((f0 + backward[0]["ms"]) / (f + r["ms"]), 3)
 
     is_mfma = head["kernel"] == "mfma"
     peak = PEAK_BF16_TFLOPS if is_mfma else PEAK_FP32_TFLOPS
