@@ -231,6 +231,29 @@ int tac_conv_lif_backward(const tac_layer_desc_t* desc, const tac_backward_desc_
                           const float* w_oihw, const float* v_trace, const float* grad_out, float* grad_y,
                           float* grad_w, float* grad_bias, float* grad_in, void* stream);
 
+/* Backward pass through a stack run by tac_stack_forward with every layer's v_trace given: layer by
+ * layer from the last to the first, the input-frame gradient of layer l being the output-spike
+ * gradient of layer l-1 (their shapes agree by tac_stack_check: T of layer l = T_out of layer l-1,
+ * so gradients flow through TAC cascades and TAC-TP layers alike).  One entry per layer: */
+typedef struct tac_stack_grads {
+  const float* w_oihw;   /* DEVICE, read-only, the layer's plain weights [Cout][Cin][3][3]            */
+  float* grad_y;         /* DEVICE, written, [G][B][Cout][Ho][Wo]                                      */
+  float* grad_w;         /* DEVICE, written, [Cout][Cin][3][3]                                         */
+  float* grad_bias;      /* DEVICE, written, [Cout], or NULL                                           */
+  float* grad_in;        /* DEVICE, written, [T][B][Cin][H][W]; required for l >= 1, may be NULL for l = 0 */
+} tac_stack_grads_t;
+
+/*   layers, n_layers   the stack as given to tac_stack_forward (descriptions, v_trace and the packed
+ *                      outputs it wrote; every layer TAC_IN_BITS: no pool on load in the backward pass)
+ *   grads              n_layers entries, see above
+ *   bwd                surrogate, alpha, detach_reset for every layer
+ *   input              DEVICE: the packed frames layer 0 read
+ *   grad_out_last      DEVICE, float32 [T_out][B][Cout][Ho][Wo] of the last layer: dL/d(its spikes)
+ * Enqueued on `stream` in order; allocates and synchronises nothing.  Errors as tac_stack_check and
+ * tac_conv_lif_backward; TAC_ERR_NULL when a layer lacks v_trace or a layer >= 1 lacks grad_in. */
+int tac_stack_backward(const tac_stack_layer_t* layers, const tac_stack_grads_t* grads, const tac_backward_desc_t* bwd,
+                       int32_t n_layers, const void* input, const float* grad_out_last, void* stream);
+
 int tac_pack_spikes(const uint8_t* dense01, uint32_t* packed, int64_t rows, int32_t W, void* stream);
 int tac_unpack_spikes(const uint32_t* packed, uint8_t* dense01, int64_t rows, int32_t W, void* stream);
 

@@ -25,7 +25,7 @@ MODE_NAMES = {TAC_PER_STEP: "per_step", TAC_COLLAPSE: "TAC", TAC_PRESERVE: "TAC_
 
 EXPORTS = ("tac_out_shape", "tac_packed_bytes", "tac_select_kernel", "tac_prepared_weight_bytes",
            "tac_prepare_weights", "tac_conv_lif", "tac_pack_spikes", "tac_unpack_spikes", "tac_fold_batchnorm",
-           "tac_stack_check", "tac_stack_forward", "tac_conv_lif_backward", "tac_get_counters", "tac_reset_counters", "tac_status_string",
+           "tac_stack_check", "tac_stack_forward", "tac_conv_lif_backward", "tac_stack_backward", "tac_get_counters", "tac_reset_counters", "tac_status_string",
            "tac_last_error")
 
 
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.tac_stack_forward.restype = ctypes.c_int
         L.tac_conv_lif_backward.argtypes = [dp, ctypes.POINTER(tac_backward_desc_t)] + [vp] * 9
         L.tac_conv_lif_backward.restype = ctypes.c_int
+        L.tac_stack_backward.argtypes = [vp, vp, ctypes.POINTER(tac_backward_desc_t), ctypes.c_int32, vp, vp, vp]
+        L.tac_stack_backward.restype = ctypes.c_int
         L.tac_reset_counters.argtypes = []
         L.tac_reset_counters.restype = ctypes.c_int
         L.tac_status_string.argtypes = [ctypes.c_int]
@@ -296,6 +298,42 @@ def tac_stack_forward(stack, input, stream=None) -> None:
     if input.numel() * input.element_size() != need:
         raise ValueError("input has %d bytes, layer 0 needs %d" % (input.numel() * input.element_size(), need))
     _check(lib().tac_stack_forward(stack, len(stack), _dev_ptr(input, None, "input"), _stream(stream)))
+
+
+class tac_stack_grads_t(ctypes.Structure):
+    _fields_ = [("w_oihw", ctypes.c_void_p), ("grad_y", ctypes.c_void_p), ("grad_w", ctypes.c_void_p),
+                ("grad_bias", ctypes.c_void_p), ("grad_in", ctypes.c_void_p)]
+
+
+def tac_stack_backward(stack, weights, input, grad_out_last, *, surrogate=TAC_SG_FAST_SIGMOID, alpha=25.0, detach_reset=False,
+                       first_layer_input_grad=False, stream=None):
+    """Backward pass through a stack that tac_stack_forward has run with v_trace buffers.  weights: the layers'
+    plain float32 weights (device tensors).  Returns a list of dicts (grad_y, grad_w, grad_bias, grad_in) per layer."""
+    import torch
+    n = len(stack)
+    arr = (tac_stack_grads_t * n)()
+    out = []
+    for l in range(n):
+        d = stack[l].desc
+        T_out, Ho, Wo = tac_out_shape(d)
+        K = 1 if d.mode == TAC_PER_STEP else min(d.K, d.T)
+        dev = weights[l].device
+        g = dict(grad_y=torch.empty((-(-d.T // K), d.B, d.Cout, Ho, Wo), dtype=torch.float32, device=dev),
+                 grad_w=torch.empty((d.Cout, d.Cin, 3, 3), dtype=torch.float32, device=dev),
+                 grad_bias=torch.empty((d.Cout,), dtype=torch.float32, device=dev),
+                 grad_in=torch.empty((d.T, d.B, d.Cin, d.H, d.W), dtype=torch.float32, device=dev)
+                 if (l > 0 or first_layer_input_grad) else None)
+        if tuple(weights[l].shape) != (d.Cout, d.Cin, 3, 3):
+            raise ValueError("layer %d: weights must be [Cout,Cin,3,3]" % l)
+        val = lambda p: None if p is None else p.value
+        arr[l].w_oihw = val(_dev_ptr(weights[l], torch.float32, "weights"))
+        for k in ("grad_y", "grad_w", "grad_bias", "grad_in"):
+            setattr(arr[l], k, val(_dev_ptr(g[k])))
+        out.append(g)
+    bwd = tac_backward_desc_t(surrogate=surrogate, detach_reset=int(bool(detach_reset)), alpha=alpha)
+    _check(lib().tac_stack_backward(stack, arr, ctypes.byref(bwd), n, _dev_ptr(input, None, "input"),
+                                    _dev_ptr(grad_out_last, torch.float32, "grad_out_last"), _stream(stream)))
+    return out
 
 
 def tac_pack_spikes(dense01, packed=None, stream=None):

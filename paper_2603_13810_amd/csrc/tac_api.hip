@@ -273,6 +273,22 @@ int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* 
   return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_conv_lif_backward");
 }
 
+int tac_stack_backward(const tac_stack_layer_t* layers, const tac_stack_grads_t* grads, const tac_backward_desc_t* bwd,
+                       int32_t n_layers, const void* input, const float* grad_out_last, void* stream) {
+  if (!grads || !bwd || !input || !grad_out_last) return TAC_ERR_NULL;
+  int rc = tac_stack_check(layers, n_layers, nullptr);
+  if (rc) return rc;
+  for (int32_t l = 0; l < n_layers; ++l)
+    if (!layers[l].v_trace || (l > 0 && !grads[l].grad_in)) return TAC_ERR_NULL;
+  for (int32_t l = n_layers - 1; l >= 0; --l) {
+    rc = tac_conv_lif_backward(&layers[l].desc, bwd, l == 0 ? input : layers[l - 1].out_spikes_packed, grads[l].w_oihw,
+                               layers[l].v_trace, l == n_layers - 1 ? grad_out_last : grads[l + 1].grad_in, grads[l].grad_y,
+                               grads[l].grad_w, grads[l].grad_bias, grads[l].grad_in, stream);
+    if (rc) return rc;
+  }
+  return TAC_OK;
+}
+
 int tac_pack_spikes(const uint8_t* dense01, uint32_t* packed, int64_t rows, int32_t W, void* stream) {
   if (!dense01 || !packed) return TAC_ERR_NULL;
   if (rows < 1 || W < 1) return TAC_ERR_BAD_SHAPE;

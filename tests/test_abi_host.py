@@ -193,3 +193,23 @@ def test_backward_rejects_bad_requests_before_any_launch():
     assert call(d, api.tac_backward_desc_t(surrogate=0, detach_reset=0, alpha=0.0), *nine) == api.TAC_ERR_BAD_PARAM
     assert call(_desc(in_format=api.TAC_IN_BITS_MAXPOOL2), ok, *nine) == api.TAC_ERR_UNSUPPORTED
     assert call(_desc(K=0), ok, *nine) == api.TAC_ERR_BAD_K
+
+
+def test_stack_backward_needs_membranes_and_input_gradients():
+    L = api.lib()
+    mk = lambda T, Cin, Cout, **kw: api.make_desc(T, 2, Cin, 8, 8, Cout, beta=0.9, theta=1.0, **kw)
+    stack = _stack([mk(8, 2, 4, K=2, mode=api.TAC_COLLAPSE), mk(4, 4, 4, mode=api.TAC_PER_STEP)])
+    grads = (api.tac_stack_grads_t * 2)()
+    for g in grads:
+        g.w_oihw = g.grad_y = g.grad_w = 0x3000
+    bwd = api.tac_backward_desc_t(surrogate=api.TAC_SG_ARCTAN, detach_reset=1, alpha=2.0)
+    fake = ctypes.c_void_p(0x1000)
+    call = lambda: L.tac_stack_backward(stack, grads, ctypes.byref(bwd), 2, fake, fake, None)
+    assert call() == api.TAC_ERR_NULL                      # no v_trace recorded
+    for l in stack:
+        l.v_trace = 0x4000
+    assert call() == api.TAC_ERR_NULL                      # layer 1 has no grad_in to hand to layer 0
+    assert L.tac_stack_backward(stack, None, ctypes.byref(bwd), 2, fake, fake, None) == api.TAC_ERR_NULL
+    stack[1].desc.T = 5
+    grads[1].grad_in = 0x5000
+    assert call() == api.TAC_ERR_BAD_SHAPE                 # the stack itself does not chain

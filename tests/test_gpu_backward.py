@@ -129,3 +129,51 @@ def test_backward_bf16_layer_weight_gradient_on_the_matrix_cores(shape, mode, K,
     e = [err("dL/dY", got["grad_y"].cpu().numpy(), ref["dY"], 1e-3), err("dW", got["grad_w"].cpu().numpy(), ref["dW"], TOL_BF16),
          err("dbias", got["grad_bias"].cpu().numpy(), ref["dbias"], 1e-3), err("dL/dS", got["grad_in"].cpu().numpy(), ref["g_in"], TOL_BF16)]
     print("backward bf16", shape, api.MODE_NAMES[mode], "K=%d T=%d" % (K, T), "errors dY %.1e dW %.1e dbias %.1e dS %.1e" % tuple(e))
+
+
+@pytest.mark.parametrize("modes", [[(api.TAC_COLLAPSE, 2), (api.TAC_COLLAPSE, 2), (api.TAC_COLLAPSE, 2)],
+                                   [(api.TAC_PRESERVE, 4), (api.TAC_COLLAPSE, 3), (api.TAC_PER_STEP, 1)]])
+def test_backward_through_a_stack(modes):
+    # forward through the stack call, backward through tac_stack_backward; the oracle runs the same chain layer by
+    # layer (forward on its own spikes, backward handing dL/dS of a layer to the layer before as dL/ds)
+    r = _rng(1500 + len(modes) + modes[0][1])
+    T, B, H, W = 8, 2, 10, 12
+    chans = [3, 6, 8, 5]
+    s = (r.random((T, B, chans[0], H, W)) < 0.4).astype(np.uint8)
+    layers, ws, host = [], [], []
+    Tl = T
+    for l, (mode, K) in enumerate(modes):
+        desc = api.make_desc(Tl, B, chans[l], H, W, chans[l + 1], K=K, beta=0.9, theta=1.0, mode=mode)
+        w = (synth.kaiming_normal(50 + l, chans[l + 1], chans[l]) * np.float32(2.0)).astype(np.float32)
+        wd = torch.from_numpy(w).to(DEV)
+        T_out, Ho, Wo = api.tac_out_shape(desc)
+        layers.append(dict(desc=desc, w_prepared=api.tac_prepare_weights(desc, wd),
+                           v_inout=torch.zeros((B, chans[l + 1], Ho, Wo), dtype=torch.float32, device=DEV),
+                           v_trace=torch.empty((T_out, B, chans[l + 1], Ho, Wo), dtype=torch.float32, device=DEV)))
+        ws.append(wd)
+        host.append((w, mode, K))
+        Tl = T_out
+    stack, outs = api.make_stack(layers)
+    sp = torch.from_numpy(np_pack(s)).to(DEV)
+    api.tac_stack_forward(stack, sp)
+    g_last = r.standard_normal(tuple(layers[-1]["v_trace"].shape)).astype(np.float32)
+    got = api.tac_stack_backward(stack, ws, sp, torch.from_numpy(g_last).to(DEV), surrogate=api.TAC_SG_ARCTAN, alpha=2.0,
+                                 detach_reset=True, first_layer_input_grad=True)
+    torch.cuda.synchronize()
+    # oracle chain
+    x, fwd = s, []
+    for (w, mode, K) in host:
+        out, v_pre, _ = oracle.conv_lif(x, w.astype(np.float64), K=K, beta=float(np.float32(0.9)), theta=1.0, mode=ORACLE_MODE[mode])
+        fwd.append((x, v_pre))
+        x = out
+    from parity_util import np_unpack
+    assert np.array_equal(np_unpack(outs[-1].cpu().numpy(), W), x) and x.sum() > 0      # same spikes on both sides
+    g = g_last.astype(np.float64)
+    for l in range(len(host) - 1, -1, -1):
+        w, mode, K = host[l]
+        ref = oracle.conv_lif_backward(fwd[l][0], w.astype(np.float64), fwd[l][1], g, K=K, beta=float(np.float32(0.9)), theta=1.0,
+                                       mode=ORACLE_MODE[mode], surrogate=oracle.ARCTAN, alpha=2.0, detach_reset=True)
+        _close("layer %d dW" % l, got[l]["grad_w"].cpu().numpy(), ref["dW"])
+        _close("layer %d dbias" % l, got[l]["grad_bias"].cpu().numpy(), ref["dbias"])
+        _close("layer %d dL/dS" % l, got[l]["grad_in"].cpu().numpy(), ref["g_in"])
+        g = ref["g_in"]
