@@ -62,11 +62,15 @@ constexpr int kLdsLimit = 160 * 1024;          // LDS of one compute unit
 // integers (frames 0..7, frames 8..15) that are added before the one rounding to bf16.
 __host__ __device__ constexpr int lut_bytes(int K) { return K == 16 ? 2048 : (K >= 2 && K <= 8 ? ((2 << K) + 15) / 16 * 16 : 0); }
 
-// Compile-time geometry of a tile: input width WIN (32 or 64 pixels = 1 or 2 words), stride S.
-template <int WIN, int S>
+// Compile-time geometry of a tile: input width WIN (32 or 64 pixels = 1 or 2 words), stride S,
+// NP blocks of 32 output pixels per wave (2; 1 gives half as high a tile, for layers whose grid
+// would otherwise leave compute units idle; output rows of at most 32 pixels only).
+template <int WIN, int S, int NP = 2>
 struct Geo {
   static constexpr int kWo = WIN / S;                        // output width: 64, 32 or 16
-  static constexpr int kWaveRows = 64 / kWo;                 // output rows per wave
+  static constexpr int kNP = NP;
+  static_assert(NP == 2 || (NP == 1 && kWo <= 32), "half tiles: whole rows per wave");
+  static constexpr int kWaveRows = NP * 32 / kWo;            // output rows per wave
   static constexpr int kTileRows = kWaves * kWaveRows;       // output rows per workgroup
   static constexpr int kInRows = (kTileRows - 1) * S + 3;    // input rows with the 3x3 halo
   static constexpr int kWW = WIN / 32;                       // words per input row
@@ -100,7 +104,7 @@ __device__ __forceinline__ LaneGeom lane_geom(int lane, int oy_wave, int Ho, siz
   LaneGeom lg;
   const int n = lane & 31, h = lane >> 5;
 #pragma unroll
-  for (int np = 0; np < 2; ++np) {
+  for (int np = 0; np < G::kNP; ++np) {
     const int pix = np * 32 + n;
     // one row per wave: the row test below is wave-uniform and the threshold stays scalar
     const int lr = G::kWaveRows == 1 ? 0 : pix / G::kWo, ox = G::kWaveRows == 1 ? pix : pix % G::kWo;
@@ -393,9 +397,9 @@ __device__ __forceinline__ void lds_barrier() {
 // stores and their addresses do not weigh on the register allocation of the plain one).
 // MP: the input buffer holds the unpooled spikes of the layer before and a 2 x 2 max pool is
 // applied while staging (the staged words are pooled bits; everything after them is unchanged).
-template <int KT, int WIN, int S, bool TRACE, bool MP, int MC>
+template <int KT, int WIN, int S, bool TRACE, bool MP, int MC, int NP>
 __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
-  using G = Geo<WIN, S>;
+  using G = Geo<WIN, S, NP>;
   // MC = 32-channel blocks per workgroup and wave: 4 (128 output channels), or 2 (64) for layers
   // whose grid would otherwise leave compute units idle.  The prepared weights are laid out
   // for 128-channel tiles either way; a 64-channel workgroup copies its half of each tap.
@@ -448,7 +452,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   const size_t plane = (size_t)Ho * G::kWo;                    // elements per (b, cout)
   int a_frag_off[2];                                           // byte offset of the lane's B fragments, tap (0, 0)
 #pragma unroll
-  for (int np = 0; np < 2; ++np) {
+  for (int np = 0; np < NP; ++np) {
     const int pix = np * 32 + n;
     const int lr = pix / G::kWo, ox = pix % G::kWo;
     a_frag_off[np] = h * G::kAHalf + (((wave * G::kWaveRows + lr) * S) * G::kXP + G::col(ox * S)) * 16;
@@ -457,18 +461,18 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   const size_t v_wave = ((size_t)b * p.Cout + co_wave) * plane + (size_t)oy_wave * G::kWo;
 
   // membrane, MFMA result layout: register r of tile (mc, np), lane -> cout = 32 mc + 8 (r/4) + 4 h + r%4
-  float V[MC][2][16];
-  f32x16 acc[MC][2];
+  float V[MC][NP][16];
+  f32x16 acc[MC][NP];
 #pragma unroll
   for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
-    for (int np = 0; np < 2; ++np)
+    for (int np = 0; np < NP; ++np)
 #pragma unroll
       for (int r = 0; r < 16; ++r) V[mc][np][r] = 0.f;
   if (p.v_inout) {
     const LaneGeom lg = lane_geom<G>(lane, oy_wave, Ho, plane, p.theta);
     const char* vb = reinterpret_cast<const char*>(p.v_inout + v_wave);
-    static_for<0, 2>([&](auto np_) {
+    static_for<0, NP>([&](auto np_) {
       constexpr int np = decltype(np_)::value;
       if (lg.ok[np]) {
         static_for<0, MC>([&](auto mc_) { static_for<0, 16>([&](auto r_) {
@@ -576,7 +580,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   // MFMA operand fragments, two slots: tap t multiplies slot t & 1 while slot (t+1) & 1 is
   // being fetched; tap 8 fetches the next chunk's tap-0 fragments into slot 1, which the next
   // chunk starts by moving to slot 0
-  bf16x8 wf[2][MC], af[2][2];
+  bf16x8 wf[2][MC], af[2][NP];
   auto fetch = [&](const uint8_t* a_buf, const uint8_t* w_buf, int tap, int slot) {
     const int ky = tap / 3, kx = tap % 3;
     const int tap_off = (ky * G::kXP + G::col(kx)) * 16;            // col(ox S + kx) = col(ox S) + col(kx)
@@ -584,7 +588,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     for (int mc = 0; mc < MC; ++mc)
       wf[slot][mc] = *reinterpret_cast<const bf16x8*>(w_buf + tap * kWTapL + mc * 1024 + w_frag_off);
 #pragma unroll
-    for (int np = 0; np < 2; ++np)
+    for (int np = 0; np < NP; ++np)
       af[slot][np] = *reinterpret_cast<const bf16x8*>(a_buf + a_frag_off[np] + tap_off);
   };
   fetch(lds + G::kLdsA, lds + G::kLdsW, 0, 1);
@@ -607,7 +611,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
 #pragma unroll
     for (int mc = 0; mc < MC; ++mc) wf[0][mc] = wf[1][mc];
 #pragma unroll
-    for (int np = 0; np < 2; ++np) af[0][np] = af[1][np];
+    for (int np = 0; np < NP; ++np) af[0][np] = af[1][np];
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) {
       const int slot = tap & 1;
@@ -639,7 +643,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
 #pragma unroll
       for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
-        for (int np = 0; np < 2; ++np)
+        for (int np = 0; np < NP; ++np)
           acc[mc][np] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][mc], af[slot][np], acc[mc][np], 0, 0, 0);
       // loader: pipeline slot i writes step i-2, looks up step i-1 and reads the words of step i
       // (one frame: no table, the write follows the read by one slot)
@@ -661,7 +665,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
         constexpr int kValuPerMfma = (KT == 16 ? 4 : 2) * G::kSlotsPerTap;
         constexpr int kDsPerMfma = (G::kSlotsPerTap == 1 && KT != 16) ? 2 : 3;
 #pragma unroll
-        for (int i = 0; i < 2 * MC; ++i) {
+        for (int i = 0; i < NP * MC; ++i) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
           __builtin_amdgcn_sched_group_barrier(0x100, kDsPerMfma, 0);
           __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);
@@ -697,7 +701,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     out_row = lane & 3;
     out_off = (uint32_t)(8 * (r >> 2) + 4 * hi + (r & 3)) * out_plane + out_row;
   }
-  const bool out_ok = oy_wave + out_row < Ho;
+  const bool out_ok = oy_wave + out_row < Ho && out_row < G::kWaveRows;      // half tiles: the lanes of the absent block store nothing
 
   int s = 0;
   for (int g = 0; g < p.G; ++g) {
@@ -709,7 +713,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
 #pragma unroll
     for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
-      for (int np = 0; np < 2; ++np)
+      for (int np = 0; np < NP; ++np)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mc][np][r] = 0.f;
 
@@ -723,8 +727,8 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const float bv = bias_lds[mc * 32 + 8 * (r >> 2) + 4 * h + (r & 3)];
-          acc[mc][0][r] += bv;
-          acc[mc][1][r] += bv;
+#pragma unroll
+          for (int np = 0; np < NP; ++np) acc[mc][np][r] += bv;
         }
     }
     // epilogue geometry, recomputed per group: nothing of it lives across the MFMA loop
@@ -738,9 +742,9 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
         float* tl = p.v_trace + step * ((size_t)p.B * p.Cout * plane) + v_wave;
         size_t plane_l = plane;
         asm volatile("" : "+s"(plane_l));       // keep the trace addresses out of the loop preheader
-        lif_step<MC, G::kWo, true>(V, acc, p.decay, p.theta, lg, word, tl, plane_l);
+        lif_step<MC, G::kWo, true, NP>(V, acc, p.decay, p.theta, lg, word, tl, plane_l);
       } else {
-        lif_step<MC, G::kWo, false>(V, acc, p.decay, p.theta, lg, word, nullptr, plane);
+        lif_step<MC, G::kWo, false, NP>(V, acc, p.decay, p.theta, lg, word, nullptr, plane);
       }
       if (out_ok) {
         uint32_t* const o = out_wave + step * out_step;
@@ -758,7 +762,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     asm volatile("" : "+s"(plane_l));         // not before the time loop (they would not fit in registers)
     const LaneGeom lg = lane_geom<G>(lane, oy_wave, Ho, plane_l, p.theta);
     char* vb = reinterpret_cast<char*>(p.v_inout + v_wave);
-    static_for<0, 2>([&](auto np_) {
+    static_for<0, NP>([&](auto np_) {
       constexpr int np = decltype(np_)::value;
       if (lg.ok[np]) {
         static_for<0, MC>([&](auto mc_) { static_for<0, 16>([&](auto r_) {
@@ -793,14 +797,14 @@ __global__ void mfma_prepare_kernel(const float* __restrict__ w, uint32_t* __res
   out[i] = pack_bf16(a, bb);
 }
 
-template <int KT, int WIN, int S, bool TRACE, bool MP, int MC>
+template <int KT, int WIN, int S, bool TRACE, bool MP, int MC, int NP = 2>
 hipError_t launch_tile(const MfmaParams& mp, hipStream_t s) {
-  using G = Geo<WIN, S>;
+  using G = Geo<WIN, S, NP>;
   constexpr int lds = G::lds_bytes(KT > 0 ? KT : TAC_MAX_K, MC);
   static_assert(lds <= kLdsLimit, "tile does not fit the LDS");
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<KT, WIN, S, TRACE, MP, MC>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<KT, WIN, S, TRACE, MP, MC, NP>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_done = true;
@@ -808,7 +812,7 @@ hipError_t launch_tile(const MfmaParams& mp, hipStream_t s) {
   MfmaParams q = mp;
   q.row_tiles = (mp.Ho + G::kTileRows - 1) / G::kTileRows;
   const dim3 grid(q.row_tiles * (mp.Cout / (MC * 32)) * mp.B);
-  hipLaunchKernelGGL((mfma_kernel<KT, WIN, S, TRACE, MP, MC>), grid, dim3(kThreads), lds, s, q);
+  hipLaunchKernelGGL((mfma_kernel<KT, WIN, S, TRACE, MP, MC, NP>), grid, dim3(kThreads), lds, s, q);
   return hipGetLastError();
 }
 
@@ -819,7 +823,13 @@ template <int KT, int WIN, int S, bool TRACE, bool MP>
 hipError_t launch_traced(const MfmaParams& mp, hipStream_t s) {
   if constexpr (!MP) {
     const int row_tiles = (mp.Ho + Geo<WIN, S>::kTileRows - 1) / Geo<WIN, S>::kTileRows;
-    if ((long long)row_tiles * (mp.Cout / kCoutTile) * mp.B < kComputeUnits) return launch_tile<KT, WIN, S, TRACE, MP, 2>(mp, s);
+    if ((long long)row_tiles * (mp.Cout / kCoutTile) * mp.B < kComputeUnits) {
+      // still fewer workgroups than compute units with 64-channel tiles: half as high a tile as well
+      if constexpr (Geo<WIN, S>::kWo <= 32) {
+        if ((long long)row_tiles * (mp.Cout / 64) * mp.B < kComputeUnits) return launch_tile<KT, WIN, S, TRACE, MP, 2, 1>(mp, s);
+      }
+      return launch_tile<KT, WIN, S, TRACE, MP, 2>(mp, s);
+    }
   }
   return launch_tile<KT, WIN, S, TRACE, MP, 4>(mp, s);
 }

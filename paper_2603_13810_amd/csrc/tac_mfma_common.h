@@ -76,7 +76,7 @@ struct LaneGeom {
   int co_lim;            // channels (counted from the wave's first) that exist for this lane's half
 };
 
-// One LIF step on a wave's NMC x 2 MFMA tiles: V <- decay V + Y, spike iff V >= theta,
+// One LIF step on a wave's NMC x NP MFMA tiles (NP = 2; 1: the lanes of pixel block 1 stay zero and are not stored): V <- decay V + Y, spike iff V >= theta,
 // subtractive reset.  Register r of tile (mc, np) on lane (n, h) is channel
 // 32 mc + 8 (r/4) + 4 h + r%4 at the wave's pixel 32 np + n.  The ballot of a register is two
 // 32-bit halves (h = 0, 1), each the packed spikes of 32 consecutive output pixels of one
@@ -85,13 +85,13 @@ struct LaneGeom {
 //   output width 16:       a half is two rows of 16 pixels; lane
 //                          ((r & 7) << 3) | (h << 2) | (np << 1) | sub of word[mc][r >> 3] holds
 //                          row 2 np + sub.
-template <int NMC, int WO, bool TRACE>
-__device__ __forceinline__ void lif_step(float (&V)[NMC][2][16], const f32x16 (&acc)[NMC][2], float decay, float theta,
+template <int NMC, int WO, bool TRACE, int NP = 2>
+__device__ __forceinline__ void lif_step(float (&V)[NMC][NP][16], const f32x16 (&acc)[NMC][NP], float decay, float theta,
                                          const LaneGeom& lg, uint32_t (&word)[NMC][2], float* __restrict__ trace_wave,
                                          size_t plane) {
   static_for<0, NMC>([&](auto mc_) {
     constexpr int mc = decltype(mc_)::value;
-    static_for<0, 2>([&](auto np_) {
+    static_for<0, NP>([&](auto np_) {
       constexpr int np = decltype(np_)::value;
       // four registers at a time: all four membranes and compares first, then the four ballot
       // hand-overs, then the four resets, so that no instruction waits on the one before it
