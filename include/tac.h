@@ -214,7 +214,8 @@ typedef struct tac_backward_desc {
   float alpha;            /* surrogate sharpness, > 0                                           */
 } tac_backward_desc_t;
 
-/*   input      DEVICE, read-only: the packed frames the forward pass read (TAC_IN_BITS only)
+/*   input      DEVICE, read-only: what the forward pass read, packed frames (TAC_IN_BITS) or float32 frames
+ *              (TAC_IN_F32, first layers); the formats with a pool on load are not differentiated
  *   w_oihw     DEVICE, read-only, float32 [Cout][Cin][3][3] (the plain weights, not the prepared ones)
  *   v_trace    DEVICE, read-only, float32 [T_out][B][Cout][Ho][Wo]: what the forward pass wrote
  *   grad_out   DEVICE, read-only, float32 [T_out][B][Cout][Ho][Wo]: dL/d(output spikes)
@@ -225,7 +226,7 @@ typedef struct tac_backward_desc {
  *              layer before; NULL for a first layer (skips that stage)
  * Enqueued on `stream`; nothing is allocated or synchronised; sums over pixels use float atomics,
  * so the last bits of grad_w and grad_bias depend on the order of arrival.
- * Errors: as tac_conv_lif; TAC_ERR_UNSUPPORTED for other input formats than TAC_IN_BITS, W > 1024 or
+ * Errors: as tac_conv_lif; TAC_ERR_UNSUPPORTED for the input formats with a pool on load, W > 1024 or
  * more than 65535 (group, sample) pairs; TAC_ERR_BAD_PARAM for a bad surrogate or alpha <= 0. */
 int tac_conv_lif_backward(const tac_layer_desc_t* desc, const tac_backward_desc_t* bwd, const void* input,
                           const float* w_oihw, const float* v_trace, const float* grad_out, float* grad_y,

@@ -224,8 +224,10 @@ def tac_conv_lif_backward(desc, spikes_packed, w_oihw, v_trace, grad_out, *, sur
     K = 1 if desc.mode == TAC_PER_STEP else min(desc.K, desc.T)
     G = -(-desc.T // K)
     dev = spikes_packed.device
-    if spikes_packed.numel() * spikes_packed.element_size() != tac_packed_bytes(desc.T, desc.B, desc.Cin, desc.H, desc.W):
-        raise ValueError("spikes_packed does not match the description")
+    need = (desc.T * desc.B * desc.Cin * desc.H * desc.W * 4 if desc.in_format == TAC_IN_F32
+            else tac_packed_bytes(desc.T, desc.B, desc.Cin, desc.H, desc.W))
+    if spikes_packed.numel() * spikes_packed.element_size() != need:
+        raise ValueError("the input tensor does not match the description")
     if tuple(w_oihw.shape) != (desc.Cout, desc.Cin, 3, 3):
         raise ValueError("w_oihw must be [Cout,Cin,3,3]")
     for name, t in (("v_trace", v_trace), ("grad_out", grad_out)):

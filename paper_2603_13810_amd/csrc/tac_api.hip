@@ -243,7 +243,7 @@ int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* 
   if (((uintptr_t)input | (uintptr_t)w_oihw | (uintptr_t)v_trace | (uintptr_t)grad_out | (uintptr_t)grad_y |
        (uintptr_t)grad_w | (uintptr_t)grad_bias | (uintptr_t)grad_in) & 3u)
     return TAC_ERR_ALIGN;
-  if (eff.in_format != TAC_IN_BITS || eff.W > 1024) return TAC_ERR_UNSUPPORTED;
+  if ((eff.in_format != TAC_IN_BITS && eff.in_format != TAC_IN_F32) || eff.W > 1024) return TAC_ERR_UNSUPPORTED;
 
   tac::BackwardParams p;
   std::memset(&p, 0, sizeof(p));
@@ -260,6 +260,7 @@ int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* 
   p.n_steps = eff.mode == TAC_COLLAPSE ? p.G : eff.T;
   p.mode = eff.mode; p.surrogate = bwd->surrogate; p.detach_reset = bwd->detach_reset != 0;
   p.bf16 = eff.precision == TAC_BF16;
+  p.dense = eff.in_format == TAC_IN_F32;
   p.beta = eff.beta; p.theta = eff.theta; p.alpha = bwd->alpha;
   // powers of beta in double from the fp32 beta, rounded once (as in the forward pass)
   const double beta = (double)eff.beta;

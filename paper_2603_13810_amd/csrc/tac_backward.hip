@@ -95,6 +95,15 @@ __global__ __launch_bounds__(kThreads) void zero_kernel(float* __restrict__ a, s
 __device__ __forceinline__ float aggregate_at(const BackwardParams& p, int k, int Kg, int b, int ci, int iy, int ix) {
   if (iy < 0 || iy >= p.H || ix < 0 || ix >= p.W) return 0.0f;
   const float* wj = Kg == p.K ? p.wj : p.wj_last;
+  if (p.dense) {
+    // real-valued frames [T][B][Cin][H][W] (the continuous-valued first layer, Sec. 4.2)
+    const size_t fs = (size_t)p.B * p.Cin * p.H * p.W;
+    const float* x = reinterpret_cast<const float*>(p.spikes) + ((size_t)k * p.K * p.B + b) * p.Cin * p.H * p.W +
+                     ((size_t)ci * p.H + iy) * p.W + ix;
+    float a = 0.0f;
+    for (int j = 0; j < Kg; ++j) a = fmaf(wj[j], x[j * fs], a);
+    return a;
+  }
   const size_t fstride = (size_t)p.B * p.Cin * p.H * p.Wwi;
   const uint32_t* src = p.spikes + ((size_t)k * p.K * p.B + b) * p.Cin * p.H * p.Wwi + ((size_t)ci * p.H + iy) * p.Wwi + (ix >> 5);
   float a = 0.0f;
@@ -234,7 +243,7 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
   if (p.grad_bias)
     hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((p.Cout + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, p.grad_bias,
                        (size_t)p.Cout);
-  if (p.bf16 && backward_wgrad_mfma_supported(p)) {
+  if (p.bf16 && !p.dense && backward_wgrad_mfma_supported(p)) {
     e = backward_wgrad_mfma_launch(p, s);
     if (e != hipSuccess) return e;
   } else {

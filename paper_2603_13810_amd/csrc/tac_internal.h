@@ -70,6 +70,7 @@ struct BackwardParams {
   int n_steps;              // LIF steps = output steps of the forward pass
   int mode, surrogate, detach_reset;
   int bf16;                 // bf16 operands on the matrix cores where the shape allows
+  int dense;                // `spikes` points to float32 frames [T][B][Cin][H][W] (weight gradient by the vector kernel)
   float beta, theta, alpha;
   float decay_full, decay_last;          // beta^K, beta^K_last (TAC)
   float wj[TAC_MAX_K], wj_last[TAC_MAX_K];   // beta^(Kg-1-j) for a whole group and for the shorter last one

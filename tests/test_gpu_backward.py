@@ -177,3 +177,34 @@ def test_backward_through_a_stack(modes):
         _close("layer %d dbias" % l, got[l]["grad_bias"].cpu().numpy(), ref["dbias"])
         _close("layer %d dL/dS" % l, got[l]["grad_in"].cpu().numpy(), ref["g_in"])
         g = ref["g_in"]
+
+
+@pytest.mark.parametrize("mode,K,T", [(api.TAC_PER_STEP, 1, 4), (api.TAC_COLLAPSE, 4, 8), (api.TAC_PRESERVE, 2, 7)])
+@pytest.mark.parametrize("precision", [api.TAC_FP32, api.TAC_BF16])
+def test_backward_of_a_first_layer_on_real_valued_frames(mode, K, T, precision):
+    # the continuous-valued first layer (Sec. 4.2): A_k is a weighted sum of real frames; its weight gradient uses them
+    from gpu_util import bf16_round_np
+    r = _rng(1600 + K + T)
+    B, Cin, Cout, H, W, stride = 3, 2, 24, 12, 40, 2
+    x = (r.random((T, B, Cin, H, W)) * (r.random((T, B, Cin, H, W)) < 0.4)).astype(np.float32)
+    w = synth.kaiming_normal(60, Cout, Cin) * np.float32(2.0)
+    desc = api.make_desc(T, B, Cin, H, W, Cout, K=K, beta=0.5, theta=1.0, mode=mode, stride=stride, precision=precision,
+                         in_format=api.TAC_IN_F32)
+    T_out, Ho, Wo = api.tac_out_shape(desc)
+    g_out = r.standard_normal((T_out, B, Cout, Ho, Wo)).astype(np.float32)
+    xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    v = torch.zeros((B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    vt = torch.empty((T_out, B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    api.tac_conv_lif(desc, xd, api.tac_prepare_weights(desc, wd), None, v, None, vt)
+    got = api.tac_conv_lif_backward(desc, xd, wd, vt, torch.from_numpy(g_out).to(DEV), surrogate=api.TAC_SG_ARCTAN, alpha=2.0,
+                                    detach_reset=True)
+    torch.cuda.synchronize()
+    q = precision == api.TAC_BF16
+    kw = dict(K=K, beta=0.5, theta=1.0, mode=ORACLE_MODE[mode], stride=stride)
+    out, v_pre, _ = oracle.conv_lif(x.astype(np.float64), (bf16_round_np(w) if q else w).astype(np.float64), round_a_bf16=q, **kw)
+    ref = oracle.conv_lif_backward(x.astype(np.float64), w.astype(np.float64), v_pre, g_out.astype(np.float64), surrogate=oracle.ARCTAN,
+                                   alpha=2.0, detach_reset=True, **kw)
+    assert out.sum() > 0
+    _close("dL/dY", got["grad_y"].cpu().numpy(), ref["dY"])
+    _close("dW", got["grad_w"].cpu().numpy(), ref["dW"])
+    _close("dL/dx", got["grad_in"].cpu().numpy(), ref["g_in"])
