@@ -239,18 +239,18 @@ def conv_lif_neurons(spikes, weight, bias=None, *, idx, K=1, beta, theta, mode, 
 
 
 def conv_lif_backward(spikes, weight, v_pre, g_out, *, K=1, beta, theta, mode, stride=1, pad=1,
-                      surrogate=FAST_SIGMOID, alpha=25.0, detach_reset=False, want_input_grad=True, round_a_bf16=False):
+                      surrogate=FAST_SIGMOID, alpha=25.0, detach_reset=False, want_input_grad=True, round_a_bf16=False, pool2=False):
     """Backward pass of one conv-LIF layer with a surrogate gradient (Sec. 5.1, Training).
 
     spikes as in conv_lif (no pooled input); v_pre [T_out,B,Cout,Ho,Wo] is the membrane before the
     reset that conv_lif returned; g_out, same shape, is dL/d(output spikes).  Returns a dict with
     dY [G,B,Cout,Ho,Wo] (dL/dY_k), dW [Cout,Cin,kh,kw], dbias [Cout] and g_in [T,B,Cin,H,W]
     (dL/d(input frames); None when not wanted).  round_a_bf16: the aggregates A_k enter dW rounded to bfloat16,
-    as they entered a bf16 forward pass."""
+    as they entered a bf16 forward pass.  pool2 as in conv_lif: g_in is then the gradient of the unpooled frames."""
     lib = _load()
     spikes = _as_input(spikes)
     weight = np.ascontiguousarray(weight, dtype=np.float64)
-    d, Ho, Wo = _desc(spikes, weight, K, beta, theta, stride, pad, False, round_a_bf16, 1)
+    d, Ho, Wo = _desc(spikes, weight, K, beta, theta, stride, pad, pool2, round_a_bf16, 1)
     Kg = 1 if mode == PER_STEP else K
     G = -(-d.T // Kg)
     T_out = d.T if mode != TAC else G

@@ -438,7 +438,12 @@ int oracle_neurons(const oracle_desc_t* d, int mode, const uint8_t* S, const dou
  *   v_pre [N][n_out]   membrane before the reset at every LIF step (the forward pass returns it)
  *   g_out [N][n_out]   dL/ds
  *   dY    [G][n_out]   out;  dW [Cout][Cin][kh][kw] out;  dbias [Cout] out or NULL;
- *   g_in  [T][B][Cin][H][W] out or NULL.   mode: 0 per-step, 1 TAC, 2 TAC-TP.  No pooled input. */
+ *   g_in  [T][B][Cin][H][W] out or NULL ([T][B][Cin][2H][2W], the gradient of the unpooled frames, with pool2).
+ * mode: 0 per-step, 1 TAC, 2 TAC-TP.
+ * A 2x2 pool in front of the layer (pool2) is differentiated too: the mean pool hands a quarter of the
+ * pooled pixel's gradient to each of its four inputs; the max pool hands all of it to the first maximal
+ * input of the window in row-major order (the convention of the common frameworks; with binary spikes the
+ * four inputs are often equal, and then this is a convention and nothing more) and zero to the others. */
 static double surrogate(int kind, double alpha, double x) {
   if (kind == 0) {
     const double t = 1.0 + alpha * fabs(x);
@@ -456,7 +461,7 @@ int oracle_backward(const oracle_desc_t* d0, int mode, int kind, double alpha, i
   const oracle_desc_t* d = &dd;
   int rc = check_desc(d, 1);
   if (rc) return rc;
-  if (mode < 0 || mode > 2 || kind < 0 || kind > 1 || d->pool2) return -4;
+  if (mode < 0 || mode > 2 || kind < 0 || kind > 1) return -4;
   const int Ho = oracle_out_h(d), Wo = oracle_out_w(d);
   const int64_t n_out = (int64_t)d->B * d->Cout * Ho * Wo;
   const int64_t n_in = (int64_t)d->B * d->Cin * d->H * d->W;
@@ -487,13 +492,14 @@ int oracle_backward(const oracle_desc_t* d0, int mode, int kind, double alpha, i
   double* A = (double*)malloc(sizeof(double) * (size_t)n_in);
   double* X = (double*)malloc(sizeof(double) * (size_t)n_in);
   double* dA = (double*)malloc(sizeof(double) * (size_t)n_in);
-  if (!A || !X || !dA) return -3;
+  double* tmp = (double*)malloc(sizeof(double) * (size_t)n_in * (d->pool2 ? 4 : 1));
+  if (!A || !X || !dA || !tmp) return -3;
   const int64_t n_w = (int64_t)d->Cout * d->Cin * d->kh * d->kw;
   for (int64_t i = 0; i < n_w; ++i) dW[i] = 0.0;
   if (dbias) for (int co = 0; co < d->Cout; ++co) dbias[co] = 0.0;
   for (int k = 0; k < G; ++k) {
     const double* dy = dY + (int64_t)k * n_out;
-    oracle_aggregate(d, S, k, A, X, X);
+    oracle_aggregate(d, S, k, A, X, tmp);
     for (int64_t i = 0; i < n_in; ++i) dA[i] = 0.0;
     for (int b = 0; b < d->B; ++b)
       for (int co = 0; co < d->Cout; ++co)
@@ -516,12 +522,33 @@ int oracle_backward(const oracle_desc_t* d0, int mode, int kind, double alpha, i
       const int Kg = group_frames(d, k);
       double* w = (double*)malloc(sizeof(double) * (size_t)Kg);
       oracle_decay_weights(d->beta, Kg, w);
-      for (int j = 0; j < Kg; ++j)
-        for (int64_t i = 0; i < n_in; ++i) g_in[((int64_t)k * d->K + j) * n_in + i] = w[j] * dA[i];
+      for (int j = 0; j < Kg; ++j) {
+        const int t = k * d->K + j;
+        if (!d->pool2) {
+          for (int64_t i = 0; i < n_in; ++i) g_in[(int64_t)t * n_in + i] = w[j] * dA[i];
+          continue;
+        }
+        const int H2 = 2 * d->H, W2 = 2 * d->W;
+        for (int64_t pc = 0; pc < (int64_t)d->B * d->Cin; ++pc)
+          for (int iy = 0; iy < d->H; ++iy)
+            for (int ix = 0; ix < d->W; ++ix) {
+              const double g = w[j] * dA[(pc * d->H + iy) * d->W + ix];
+              const int64_t base = (((int64_t)t * d->B * d->Cin + pc) * H2 + 2 * iy) * W2 + 2 * ix;
+              const int64_t at[4] = {base, base + 1, base + W2, base + W2 + 1};
+              if (d->pool2 == 1) {
+                for (int q = 0; q < 4; ++q) g_in[at[q]] = 0.25 * g;
+              } else {
+                int best = 0;
+                for (int q = 1; q < 4; ++q)
+                  if (in_value(d, S, at[q]) > in_value(d, S, at[best])) best = q;
+                for (int q = 0; q < 4; ++q) g_in[at[q]] = q == best ? g : 0.0;
+              }
+            }
+      }
       free(w);
     }
   }
-  free(A); free(X); free(dA);
+  free(A); free(X); free(dA); free(tmp);
   return 0;
 }
 

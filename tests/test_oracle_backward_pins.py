@@ -169,3 +169,38 @@ def test_backward_against_automatic_differentiation(mode, K, T, stride, kind, al
     for name, ref in (("dW", wt.grad), ("dbias", bt.grad), ("g_in", xt.grad)):
         ref = ref.numpy()
         assert np.allclose(got[name], ref, rtol=1e-9, atol=1e-10 * max(1.0, np.abs(ref).max())), name
+
+
+@pytest.mark.parametrize("pool", [True, "max"])
+@pytest.mark.parametrize("mode,K,T", [(PER_STEP, 1, 4), (TAC, 2, 6), (TAC_TP, 3, 7)])
+def test_backward_through_the_pool_in_front_of_the_layer_against_automatic_differentiation(pool, mode, K, T):
+    # mean pool: linear; max pool: the gradient goes to the first maximal input of the window in row-major order,
+    # which is what the library pooling routine differentiated here does as well
+    r = _rng(700 + 13 * K + T + (pool == "max"))
+    B, Cin, Cout, H, W = 2, 3, 4, 5, 4
+    s = (r.random((T, B, Cin, 2 * H, 2 * W)) < 0.4).astype(np.uint8)
+    w = r.standard_normal((Cout, Cin, 3, 3)) * 0.6
+    beta, theta = 0.9, 1.0
+    out, v_pre, _ = oracle.conv_lif(s, w, K=K, beta=beta, theta=theta, mode=mode, pool2=pool)
+    g_out = r.standard_normal(out.shape)
+    got = oracle.conv_lif_backward(s, w, v_pre, g_out, K=K, beta=beta, theta=theta, mode=mode, surrogate=ARCTAN, alpha=2.0,
+                                   detach_reset=True, pool2=pool)
+    xt = torch.tensor(s, dtype=torch.float64, requires_grad=True)
+    wt = torch.tensor(w, requires_grad=True)
+    Kq = 1 if mode == PER_STEP else K
+    V, spikes = torch.zeros(()), []
+    for t0, Kg in groups(T, Kq):
+        fr = [F.max_pool2d(xt[t0 + j], 2) if pool == "max" else F.avg_pool2d(xt[t0 + j], 2) for j in range(Kg)]
+        A = sum(beta ** (Kg - 1 - j) * fr[j] for j in range(Kg))
+        Y = F.conv2d(A, wt, None, padding=1)
+        for _ in range(Kg if mode == TAC_TP else 1):
+            V = (beta ** Kg if mode == TAC else beta) * V + Y
+            sp = _Spike.apply(V - theta, ARCTAN, 2.0)
+            spikes.append(sp)
+            V = V - theta * sp.detach()
+    st = torch.stack(spikes)
+    assert np.array_equal(st.detach().numpy().astype(np.uint8), out) and out.sum() > 0
+    (st * torch.tensor(g_out)).sum().backward()
+    assert np.allclose(got["dW"], wt.grad.numpy(), rtol=1e-9, atol=1e-10)
+    assert np.allclose(got["g_in"], xt.grad.numpy(), rtol=1e-9, atol=1e-12)
+    assert got["g_in"].shape == s.shape
