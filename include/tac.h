@@ -204,7 +204,8 @@ int tac_stack_forward(const tac_stack_layer_t* layers, int32_t n_layers, const v
  * Sec. 4 applies to the backward pass as well).  With desc->precision = TAC_BF16 the two
  * convolution gradients run on the matrix cores where the shape allows (stride 1; Cin a multiple of
  * 32; width 16, 32, 64 or 128 and Cout a multiple of 128 for dW; width 32, 64 or 128 and Cout = 64
- * or 128 for dL/dS; grad_y 16-byte aligned): dY_k, A_k and W enter them rounded to bfloat16, sums
+ * or 128 for dL/dS; packed input without a pool on load; grad_y 16-byte aligned): dY_k, A_k and W
+ * enter them rounded to bfloat16, sums
  * are fp32.  Everything else, and TAC_FP32, is fp32 vector arithmetic.  The rounding inside a bf16
  * forward pass is differentiated as if it were not there. */
 enum { TAC_SG_FAST_SIGMOID = 0, TAC_SG_ARCTAN = 1 };
@@ -214,8 +215,7 @@ typedef struct tac_backward_desc {
   float alpha;            /* surrogate sharpness, > 0                                           */
 } tac_backward_desc_t;
 
-/*   input      DEVICE, read-only: what the forward pass read, packed frames (TAC_IN_BITS) or float32 frames
- *              (TAC_IN_F32, first layers); the formats with a pool on load are not differentiated
+/*   input      DEVICE, read-only: what the forward pass read, in desc->in_format
  *   w_oihw     DEVICE, read-only, float32 [Cout][Cin][3][3] (the plain weights, not the prepared ones)
  *   v_trace    DEVICE, read-only, float32 [T_out][B][Cout][Ho][Wo]: what the forward pass wrote
  *   grad_out   DEVICE, read-only, float32 [T_out][B][Cout][Ho][Wo]: dL/d(output spikes)
@@ -223,10 +223,13 @@ typedef struct tac_backward_desc {
  *   grad_w     DEVICE, written (not accumulated), float32 [Cout][Cin][3][3]
  *   grad_bias  DEVICE, written, float32 [Cout], or NULL
  *   grad_in    DEVICE, written, float32 [T][B][Cin][H][W]: dL/d(input frames), the grad_out of the
- *              layer before; NULL for a first layer (skips that stage)
+ *              layer before; NULL for a first layer (skips that stage).  With a pool on load it is the
+ *              gradient of the unpooled frames, [T][B][Cin][2H][2W]: a quarter of the pooled pixel's
+ *              gradient to each input of the mean pool; all of it to the first maximal input of the
+ *              max pool's window in row-major order (the first set bit, else the first input)
  * Enqueued on `stream`; nothing is allocated or synchronised; sums over pixels use float atomics,
  * so the last bits of grad_w and grad_bias depend on the order of arrival.
- * Errors: as tac_conv_lif; TAC_ERR_UNSUPPORTED for the input formats with a pool on load, W > 1024 or
+ * Errors: as tac_conv_lif; TAC_ERR_UNSUPPORTED for W > 1024 or
  * more than 65535 (group, sample) pairs; TAC_ERR_BAD_PARAM for a bad surrogate or alpha <= 0. */
 int tac_conv_lif_backward(const tac_layer_desc_t* desc, const tac_backward_desc_t* bwd, const void* input,
                           const float* w_oihw, const float* v_trace, const float* grad_out, float* grad_y,
@@ -245,7 +248,7 @@ typedef struct tac_stack_grads {
 } tac_stack_grads_t;
 
 /*   layers, n_layers   the stack as given to tac_stack_forward (descriptions, v_trace and the packed
- *                      outputs it wrote; every layer TAC_IN_BITS: no pool on load in the backward pass)
+ *                      outputs it wrote)
  *   grads              n_layers entries, see above
  *   bwd                surrogate, alpha, detach_reset for every layer
  *   input              DEVICE: the packed frames layer 0 read

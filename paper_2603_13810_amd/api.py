@@ -224,8 +224,9 @@ def tac_conv_lif_backward(desc, spikes_packed, w_oihw, v_trace, grad_out, *, sur
     K = 1 if desc.mode == TAC_PER_STEP else min(desc.K, desc.T)
     G = -(-desc.T // K)
     dev = spikes_packed.device
+    f = 2 if desc.in_format in (TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2) else 1
     need = (desc.T * desc.B * desc.Cin * desc.H * desc.W * 4 if desc.in_format == TAC_IN_F32
-            else tac_packed_bytes(desc.T, desc.B, desc.Cin, desc.H, desc.W))
+            else tac_packed_bytes(desc.T, desc.B, desc.Cin, desc.H * f, desc.W * f))
     if spikes_packed.numel() * spikes_packed.element_size() != need:
         raise ValueError("the input tensor does not match the description")
     if tuple(w_oihw.shape) != (desc.Cout, desc.Cin, 3, 3):
@@ -236,7 +237,7 @@ def tac_conv_lif_backward(desc, spikes_packed, w_oihw, v_trace, grad_out, *, sur
     grad_y = torch.empty((G, desc.B, desc.Cout, Ho, Wo), dtype=torch.float32, device=dev)
     grad_w = torch.empty((desc.Cout, desc.Cin, 3, 3), dtype=torch.float32, device=dev)
     grad_bias = torch.empty((desc.Cout,), dtype=torch.float32, device=dev)
-    grad_in = torch.empty((desc.T, desc.B, desc.Cin, desc.H, desc.W), dtype=torch.float32, device=dev) if want_input_grad else None
+    grad_in = torch.empty((desc.T, desc.B, desc.Cin, desc.H * f, desc.W * f), dtype=torch.float32, device=dev) if want_input_grad else None
     bwd = tac_backward_desc_t(surrogate=surrogate, detach_reset=int(bool(detach_reset)), alpha=alpha)
     _check(lib().tac_conv_lif_backward(ctypes.byref(desc), ctypes.byref(bwd), _dev_ptr(spikes_packed, None, "spikes_packed"),
                                        _dev_ptr(w_oihw, torch.float32, "w_oihw"), _dev_ptr(v_trace, torch.float32, "v_trace"),
@@ -323,7 +324,9 @@ def tac_stack_backward(stack, weights, input, grad_out_last, *, surrogate=TAC_SG
         g = dict(grad_y=torch.empty((-(-d.T // K), d.B, d.Cout, Ho, Wo), dtype=torch.float32, device=dev),
                  grad_w=torch.empty((d.Cout, d.Cin, 3, 3), dtype=torch.float32, device=dev),
                  grad_bias=torch.empty((d.Cout,), dtype=torch.float32, device=dev),
-                 grad_in=torch.empty((d.T, d.B, d.Cin, d.H, d.W), dtype=torch.float32, device=dev)
+                 grad_in=torch.empty((d.T, d.B, d.Cin, d.H * (2 if d.in_format in (TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2) else 1),
+                                      d.W * (2 if d.in_format in (TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2) else 1)),
+                                     dtype=torch.float32, device=dev)
                  if (l > 0 or first_layer_input_grad) else None)
         if tuple(weights[l].shape) != (d.Cout, d.Cin, 3, 3):
             raise ValueError("layer %d: weights must be [Cout,Cin,3,3]" % l)

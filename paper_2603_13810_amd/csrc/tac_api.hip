@@ -243,7 +243,7 @@ int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* 
   if (((uintptr_t)input | (uintptr_t)w_oihw | (uintptr_t)v_trace | (uintptr_t)grad_out | (uintptr_t)grad_y |
        (uintptr_t)grad_w | (uintptr_t)grad_bias | (uintptr_t)grad_in) & 3u)
     return TAC_ERR_ALIGN;
-  if ((eff.in_format != TAC_IN_BITS && eff.in_format != TAC_IN_F32) || eff.W > 1024) return TAC_ERR_UNSUPPORTED;
+  if (eff.W > 1024) return TAC_ERR_UNSUPPORTED;
 
   tac::BackwardParams p;
   std::memset(&p, 0, sizeof(p));
@@ -252,7 +252,8 @@ int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* 
   p.T = eff.T; p.B = eff.B; p.Cin = eff.Cin; p.H = eff.H; p.W = eff.W; p.Cout = eff.Cout; p.stride = eff.stride;
   p.Ho = (eff.H + 2 - 3) / eff.stride + 1;
   p.Wo = (eff.W + 2 - 3) / eff.stride + 1;
-  p.Wwi = (eff.W + 31) / 32;
+  p.pool2 = eff.in_format == TAC_IN_BITS_POOL2 ? 1 : (eff.in_format == TAC_IN_BITS_MAXPOOL2 ? 2 : 0);
+  p.Wwi = ((p.pool2 ? 2 * eff.W : eff.W) + 31) / 32;
   p.K = eff.K;
   p.K_last = eff.T % eff.K;
   p.G = (eff.T + eff.K - 1) / eff.K;

@@ -104,6 +104,17 @@ __device__ __forceinline__ float aggregate_at(const BackwardParams& p, int k, in
     for (int j = 0; j < Kg; ++j) a = fmaf(wj[j], x[j * fs], a);
     return a;
   }
+  if (p.pool2) {
+    // the stored frames are unpooled, [2H][2W]: mean of the four bits, or their OR (max pool)
+    const size_t fs = (size_t)p.B * p.Cin * 2 * p.H * p.Wwi;
+    const uint32_t* src = p.spikes + ((size_t)k * p.K * p.B + b) * p.Cin * 2 * p.H * p.Wwi + ((size_t)ci * 2 * p.H + 2 * iy) * p.Wwi + (ix >> 4);
+    float a = 0.0f;
+    for (int j = 0; j < Kg; ++j) {
+      const uint32_t two = ((src[j * fs] >> (2 * ix & 31)) & 3u) | (((src[j * fs + p.Wwi] >> (2 * ix & 31)) & 3u) << 2);
+      a += p.pool2 == 2 ? (two ? wj[j] : 0.0f) : (0.25f * (float)__popc(two)) * wj[j];
+    }
+    return a;
+  }
   const size_t fstride = (size_t)p.B * p.Cin * p.H * p.Wwi;
   const uint32_t* src = p.spikes + ((size_t)k * p.K * p.B + b) * p.Cin * p.H * p.Wwi + ((size_t)ci * p.H + iy) * p.Wwi + (ix >> 5);
   float a = 0.0f;
@@ -221,6 +232,30 @@ __global__ __launch_bounds__(kThreads) void dgrad_kernel(const BackwardParams p)
   const int Kg = group_frames(p, k);
   const float* wj = Kg == p.K ? p.wj : p.wj_last;
   const size_t in_plane = (size_t)p.H * p.W;
+  if (p.pool2) {
+    // gradient of the unpooled frames [2H][2W]: a quarter to each input of the mean pool; all of it to the first
+    // maximal input of the max pool's window in row-major order (the first set bit, or the first input when none is set)
+    const int W2 = 2 * p.W;
+    const size_t fs = (size_t)p.B * p.Cin * 2 * p.H * p.Wwi;
+    for (int j = 0; j < Kg; ++j)
+#pragma unroll
+      for (int c = 0; c < kCiTile; ++c)
+        if (ci0 + c < p.Cin) {
+          const size_t chan = ((size_t)(k * p.K + j) * p.B + b) * p.Cin + ci0 + c;
+          float* dst = p.grad_in + chan * 4 * in_plane + (size_t)(2 * iy) * W2 + 2 * ix;
+          const float g = wj[j] * dA[c];
+          float q[4] = {0.25f * g, 0.25f * g, 0.25f * g, 0.25f * g};
+          if (p.pool2 == 2) {
+            const uint32_t* src = p.spikes + chan * 2 * p.H * p.Wwi + (size_t)(2 * iy) * p.Wwi + (ix >> 4);
+            const uint32_t two = ((src[0] >> (2 * ix & 31)) & 3u) | (((src[p.Wwi] >> (2 * ix & 31)) & 3u) << 2);
+            const int best = two ? __ffs(two) - 1 : 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) q[e] = e == best ? g : 0.0f;
+          }
+          dst[0] = q[0]; dst[1] = q[1]; dst[W2] = q[2]; dst[W2 + 1] = q[3];
+        }
+    return;
+  }
   for (int j = 0; j < Kg; ++j)
 #pragma unroll
     for (int c = 0; c < kCiTile; ++c)
@@ -243,7 +278,7 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
   if (p.grad_bias)
     hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((p.Cout + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, p.grad_bias,
                        (size_t)p.Cout);
-  if (p.bf16 && !p.dense && backward_wgrad_mfma_supported(p)) {
+  if (p.bf16 && !p.dense && !p.pool2 && backward_wgrad_mfma_supported(p)) {
     e = backward_wgrad_mfma_launch(p, s);
     if (e != hipSuccess) return e;
   } else {
@@ -266,7 +301,7 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
   if (e != hipSuccess) return e;
   }
 
-  if (p.grad_in && p.bf16 && backward_dgrad_mfma_supported(p)) {
+  if (p.grad_in && p.bf16 && !p.pool2 && backward_dgrad_mfma_supported(p)) {
     e = backward_dgrad_mfma_launch(p, s);
   } else if (p.grad_in) {
     const dim3 grid((p.H * p.W + kThreads - 1) / kThreads, (p.Cin + kCiTile - 1) / kCiTile, p.G * p.B);

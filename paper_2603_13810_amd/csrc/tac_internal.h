@@ -71,6 +71,7 @@ struct BackwardParams {
   int mode, surrogate, detach_reset;
   int bf16;                 // bf16 operands on the matrix cores where the shape allows
   int dense;                // `spikes` points to float32 frames [T][B][Cin][H][W] (weight gradient by the vector kernel)
+  int pool2;                // the stored frames are unpooled [2H][2W] (Wwi = their words per row): 1 mean pool, 2 max pool
   float beta, theta, alpha;
   float decay_full, decay_last;          // beta^K, beta^K_last (TAC)
   float wj[TAC_MAX_K], wj_last[TAC_MAX_K];   // beta^(Kg-1-j) for a whole group and for the shorter last one

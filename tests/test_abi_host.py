@@ -191,7 +191,7 @@ def test_backward_rejects_bad_requests_before_any_launch():
     assert call(d, ok, *ptrs) == api.TAC_ERR_ALIGN
     assert call(d, api.tac_backward_desc_t(surrogate=2, detach_reset=0, alpha=2.0), *nine) == api.TAC_ERR_BAD_PARAM
     assert call(d, api.tac_backward_desc_t(surrogate=0, detach_reset=0, alpha=0.0), *nine) == api.TAC_ERR_BAD_PARAM
-    assert call(_desc(in_format=api.TAC_IN_BITS_MAXPOOL2), ok, *nine) == api.TAC_ERR_UNSUPPORTED
+    assert call(_desc(W=2048, in_format=api.TAC_IN_BITS), ok, *nine) == api.TAC_ERR_UNSUPPORTED
     assert call(_desc(K=0), ok, *nine) == api.TAC_ERR_BAD_K
 
 

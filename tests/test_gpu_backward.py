@@ -208,3 +208,76 @@ def test_backward_of_a_first_layer_on_real_valued_frames(mode, K, T, precision):
     _close("dL/dY", got["grad_y"].cpu().numpy(), ref["dY"])
     _close("dW", got["grad_w"].cpu().numpy(), ref["dW"])
     _close("dL/dx", got["grad_in"].cpu().numpy(), ref["g_in"])
+
+
+@pytest.mark.parametrize("pool", [True, "max"])
+@pytest.mark.parametrize("mode,K,T", [(api.TAC_PER_STEP, 1, 4), (api.TAC_COLLAPSE, 4, 8), (api.TAC_PRESERVE, 2, 7)])
+@pytest.mark.parametrize("precision", [api.TAC_FP32, api.TAC_BF16])
+def test_backward_through_the_pool_on_load(pool, mode, K, T, precision):
+    # Pool(2) between the convolutions of the rate-coded network, MaxPool(2) behind every LIF layer of the event-data
+    # network (Sec. 5.1): the gradient of the unpooled frames
+    from gpu_util import bf16_round_np
+    r = _rng(1700 + K + T + (pool == "max"))
+    B, Cin, Cout, H, W = 2, 8, 16, 7, 20
+    s = (r.random((T, B, Cin, 2 * H, 2 * W)) < 0.25).astype(np.uint8)
+    w = synth.kaiming_normal(61, Cout, Cin) * np.float32(1.5)
+    fmt = api.TAC_IN_BITS_MAXPOOL2 if pool == "max" else api.TAC_IN_BITS_POOL2
+    desc = api.make_desc(T, B, Cin, H, W, Cout, K=K, beta=0.9, theta=1.0, mode=mode, precision=precision, in_format=fmt)
+    T_out, Ho, Wo = api.tac_out_shape(desc)
+    g_out = r.standard_normal((T_out, B, Cout, Ho, Wo)).astype(np.float32)
+    sp, wd = torch.from_numpy(np_pack(s)).to(DEV), torch.from_numpy(w).to(DEV)
+    v = torch.zeros((B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    vt = torch.empty((T_out, B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    api.tac_conv_lif(desc, sp, api.tac_prepare_weights(desc, wd), None, v, None, vt)
+    got = api.tac_conv_lif_backward(desc, sp, wd, vt, torch.from_numpy(g_out).to(DEV), surrogate=api.TAC_SG_FAST_SIGMOID, alpha=25.0)
+    torch.cuda.synchronize()
+    q = precision == api.TAC_BF16
+    kw = dict(K=K, beta=float(np.float32(0.9)), theta=1.0, mode=ORACLE_MODE[mode], pool2=pool)
+    out, v_pre, _ = oracle.conv_lif(s, (bf16_round_np(w) if q else w).astype(np.float64), round_a_bf16=q, **kw)
+    ref = oracle.conv_lif_backward(s, w.astype(np.float64), v_pre, g_out.astype(np.float64), surrogate=oracle.FAST_SIGMOID, alpha=25.0, **kw)
+    assert out.sum() > 0 and got["grad_in"].shape == s.shape
+    _close("dL/dY", got["grad_y"].cpu().numpy(), ref["dY"])
+    _close("dW", got["grad_w"].cpu().numpy(), ref["dW"])
+    _close("dL/dS", got["grad_in"].cpu().numpy(), ref["g_in"])
+
+
+@pytest.mark.parametrize("pool", [True, "max"])
+def test_backward_through_a_stack_with_a_pool_between_the_layers(pool):
+    r = _rng(1800 + (pool == "max"))
+    T, B, H, W = 8, 2, 12, 16
+    s = (r.random((T, B, 3, H, W)) < 0.4).astype(np.uint8)
+    fmt = api.TAC_IN_BITS_MAXPOOL2 if pool == "max" else api.TAC_IN_BITS_POOL2
+    spec = [(3, 6, H, W, api.TAC_IN_BITS, api.TAC_PRESERVE, 2, False), (6, 8, H // 2, W // 2, fmt, api.TAC_COLLAPSE, 4, pool)]
+    layers, ws, host = [], [], []
+    for l, (ci, co, h, w_, f, mode, K, pl) in enumerate(spec):
+        desc = api.make_desc(T, B, ci, h, w_, co, K=K, beta=0.9, theta=1.0, mode=mode, in_format=f)
+        w = (synth.kaiming_normal(70 + l, co, ci) * np.float32(2.0)).astype(np.float32)
+        wd = torch.from_numpy(w).to(DEV)
+        T_out, Ho, Wo = api.tac_out_shape(desc)
+        layers.append(dict(desc=desc, w_prepared=api.tac_prepare_weights(desc, wd),
+                           v_inout=torch.zeros((B, co, Ho, Wo), dtype=torch.float32, device=DEV),
+                           v_trace=torch.empty((T_out, B, co, Ho, Wo), dtype=torch.float32, device=DEV)))
+        ws.append(wd)
+        host.append((w, mode, K, pl))
+    stack, outs = api.make_stack(layers)
+    assert api.tac_stack_check(stack) == (api.TAC_OK, -1)
+    sp = torch.from_numpy(np_pack(s)).to(DEV)
+    api.tac_stack_forward(stack, sp)
+    g_last = r.standard_normal(tuple(layers[-1]["v_trace"].shape)).astype(np.float32)
+    got = api.tac_stack_backward(stack, ws, sp, torch.from_numpy(g_last).to(DEV), surrogate=api.TAC_SG_ARCTAN, alpha=2.0, detach_reset=True)
+    torch.cuda.synchronize()
+    x, fwd = s, []
+    for (w, mode, K, pl) in host:
+        out, v_pre, _ = oracle.conv_lif(x, w.astype(np.float64), K=K, beta=float(np.float32(0.9)), theta=1.0, mode=ORACLE_MODE[mode], pool2=pl)
+        fwd.append((x, v_pre))
+        x = out
+    assert x.sum() > 0
+    g = g_last.astype(np.float64)
+    for l in (1, 0):
+        w, mode, K, pl = host[l]
+        ref = oracle.conv_lif_backward(fwd[l][0], w.astype(np.float64), fwd[l][1], g, K=K, beta=float(np.float32(0.9)), theta=1.0,
+                                       mode=ORACLE_MODE[mode], surrogate=oracle.ARCTAN, alpha=2.0, detach_reset=True, pool2=pl)
+        _close("layer %d dW" % l, got[l]["grad_w"].cpu().numpy(), ref["dW"])
+        if l > 0:
+            _close("layer %d dL/dS" % l, got[l]["grad_in"].cpu().numpy(), ref["g_in"])
+        g = ref["g_in"]
