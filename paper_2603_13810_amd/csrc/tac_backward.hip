@@ -278,7 +278,7 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
   if (p.grad_bias)
     hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((p.Cout + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, p.grad_bias,
                        (size_t)p.Cout);
-  if (p.bf16 && !p.dense && !p.pool2 && backward_wgrad_mfma_supported(p)) {
+  if (p.bf16 && !p.dense && p.pool2 != 1 && backward_wgrad_mfma_supported(p)) {
     e = backward_wgrad_mfma_launch(p, s);
     if (e != hipSuccess) return e;
   } else {
@@ -301,7 +301,7 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
   if (e != hipSuccess) return e;
   }
 
-  if (p.grad_in && p.bf16 && !p.pool2 && backward_dgrad_mfma_supported(p)) {
+  if (p.grad_in && p.bf16 && p.pool2 != 1 && backward_dgrad_mfma_supported(p)) {
     e = backward_dgrad_mfma_launch(p, s);
   } else if (p.grad_in) {
     const dim3 grid((p.H * p.W + kThreads - 1) / kThreads, (p.Cin + kCiTile - 1) / kCiTile, p.G * p.B);

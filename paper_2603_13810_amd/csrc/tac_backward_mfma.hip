@@ -20,12 +20,23 @@ namespace {
 constexpr int kThreads = 256;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
+// 2 x 2 max pool of bits: v = OR of the two rows' words; OR of horizontal neighbours, even bits gathered into
+// the low half: 32 stored pixels -> 16 pooled pixels
+__device__ __forceinline__ uint32_t pool_pairs(uint32_t v) {
+  v = (v | (v >> 1)) & 0x55555555u;
+  v = (v | (v >> 1)) & 0x33333333u;
+  v = (v | (v >> 2)) & 0x0f0f0f0fu;
+  v = (v | (v >> 4)) & 0x00ff00ffu;
+  return (v | (v >> 8)) & 0x0000ffffu;
+}
+
 __device__ __forceinline__ int group_frames(const BackwardParams& p, int k) {
   return (k == p.G - 1 && p.K_last) ? p.K_last : p.K;
 }
 
 // XS = W / 16: MFMA steps per output row; R = 16 / XS output rows per strip.
-template <int XS>
+// POOL: max pool on load (the stored frames are unpooled).
+template <int XS, bool POOL>
 __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(const BackwardParams p, int n_strips, int n_split) {
   constexpr int R = 16 / XS;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -94,12 +105,26 @@ __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(c
 #pragma unroll
       for (int i = 0; i < 34; ++i) q[i] = 0u;
       if (iy >= 0 && iy < p.H) {
-        const uint32_t* src = p.spikes + ((size_t)k * p.K * p.B + b) * p.Cin * p.H * p.Wwi + ((size_t)(ci0 + ci) * p.H + iy) * p.Wwi + wi;
+        // max pool on load: the stored frames are [2H][2W], Wwi words per stored row; pooled word wi comes from
+        // the stored words 2 wi and 2 wi + 1 of the rows 2 iy and 2 iy + 1
+        const size_t rows_st = POOL ? 2 * (size_t)p.H : (size_t)p.H;
+        const uint32_t* src = p.spikes + ((size_t)k * p.K * p.B + b) * p.Cin * rows_st * p.Wwi +
+                              ((size_t)(ci0 + ci) * rows_st + (POOL ? 2 * iy : iy)) * p.Wwi + (POOL ? 2 * wi : wi);
+        const size_t fstride_st = POOL ? 2 * fstride : fstride;
         for (int j = 0; j < Kg; ++j) {
-          const uint32_t* sw = src + j * fstride;
-          const uint32_t cur = sw[0];
-          const uint32_t left = wi > 0 ? sw[-1] >> 31 : 0u;                 // pixel 32 wi - 1
-          const uint32_t right = wi + 1 < WWI ? sw[1] & 1u : 0u;            // pixel 32 wi + 32
+          const uint32_t* sw = src + j * fstride_st;
+          uint32_t cur, left, right;
+          if constexpr (POOL) {
+            const uint32_t* s1 = sw + p.Wwi;             // the row below
+            const bool second = 2 * wi + 1 < p.Wwi;
+            cur = pool_pairs(sw[0] | s1[0]) | (second ? pool_pairs(sw[1] | s1[1]) << 16 : 0u);
+            left = wi > 0 ? (uint32_t)(((sw[-1] | s1[-1]) >> 30) != 0u) : 0u;
+            right = 2 * wi + 2 < p.Wwi ? (uint32_t)(((sw[2] | s1[2]) & 3u) != 0u) : 0u;
+          } else {
+            cur = sw[0];
+            left = wi > 0 ? sw[-1] >> 31 : 0u;           // pixel 32 wi - 1
+            right = wi + 1 < WWI ? sw[1] & 1u : 0u;      // pixel 32 wi + 32
+          }
           const uint32_t wq = (uint32_t)(wj[j] * 8388608.0f + 0.5f);        // beta^(Kg-1-j) in 2^-23 units
           q[0] = __umul24(left, wq) + q[0];
 #pragma unroll
@@ -302,7 +327,25 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
 #pragma unroll
       for (int q = 0; q < NBW; ++q) {
         const int iy = w.y0 + yl0 + q, ix = x0 + n;
-        if (iy < p.H) {
+        if (iy < p.H && p.pool2) {
+          // max pool on load: the gradient of the stored frames [2H][2W]; all of it to the first set bit of the
+          // window in row-major order (the first input when none is set), zero to the other three
+          for (int j = 0; j < Kg; ++j) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const size_t chan = ((size_t)(w.k * p.K + j) * p.B + w.b) * p.Cin + ci0 + 8 * (r >> 2) + 4 * h + (r & 3);
+              const uint32_t* src = p.spikes + chan * 2 * p.H * p.Wwi + (size_t)(2 * iy) * p.Wwi + (ix >> 4);
+              const uint32_t two = ((src[0] >> (2 * ix & 31)) & 3u) | (((src[p.Wwi] >> (2 * ix & 31)) & 3u) << 2);
+              const int best = two ? __ffs(two) - 1 : 0;
+              const float g = wj[j] * acc[q][r];
+              float* dst = p.grad_in + chan * 4 * plane + (size_t)(2 * iy) * (2 * W) + 2 * ix;
+              dst[0] = best == 0 ? g : 0.0f;
+              dst[1] = best == 1 ? g : 0.0f;
+              dst[2 * W] = best == 2 ? g : 0.0f;
+              dst[2 * W + 1] = best == 3 ? g : 0.0f;
+            }
+          }
+        } else if (iy < p.H) {
           for (int j = 0; j < Kg; ++j) {
             float* dst = p.grad_in + (((size_t)(w.k * p.K + j) * p.B + w.b) * p.Cin + ci0) * plane + (size_t)iy * W + ix;
 #pragma unroll
@@ -372,11 +415,19 @@ hipError_t backward_wgrad_mfma_launch(const BackwardParams& p, hipStream_t s) {
     hipLaunchKernelGGL(kern, dim3((unsigned)split, co_blocks, ci_blocks), dim3(kThreads), lds, s, p, n_strips, (int)split);
     return hipGetLastError();
   };
+  if (p.pool2) {
+    switch (p.W) {
+      case 16: return launch(&wgrad_mfma_kernel<1, true>);
+      case 32: return launch(&wgrad_mfma_kernel<2, true>);
+      case 64: return launch(&wgrad_mfma_kernel<4, true>);
+      default: return launch(&wgrad_mfma_kernel<8, true>);
+    }
+  }
   switch (p.W) {
-    case 16: return launch(&wgrad_mfma_kernel<1>);
-    case 32: return launch(&wgrad_mfma_kernel<2>);
-    case 64: return launch(&wgrad_mfma_kernel<4>);
-    default: return launch(&wgrad_mfma_kernel<8>);
+    case 16: return launch(&wgrad_mfma_kernel<1, false>);
+    case 32: return launch(&wgrad_mfma_kernel<2, false>);
+    case 64: return launch(&wgrad_mfma_kernel<4, false>);
+    default: return launch(&wgrad_mfma_kernel<8, false>);
   }
 }
 

@@ -281,3 +281,36 @@ def test_backward_through_a_stack_with_a_pool_between_the_layers(pool):
         if l > 0:
             _close("layer %d dL/dS" % l, got[l]["grad_in"].cpu().numpy(), ref["g_in"])
         g = ref["g_in"]
+
+
+@pytest.mark.parametrize("shape", [(32, 128, 6, 32), (32, 128, 5, 64), (64, 128, 9, 16)])
+@pytest.mark.parametrize("mode,K,T", [(api.TAC_PER_STEP, 1, 3), (api.TAC_COLLAPSE, 4, 8), (api.TAC_PRESERVE, 2, 5)])
+def test_backward_max_pool_on_load_on_the_matrix_cores(shape, mode, K, T):
+    # the hidden layers of the event-data network (Conv-BN-LIF-MaxPool blocks, Sec. 5.1) at shapes the MFMA gradient
+    # kernels take: the aggregates are pooled while they are rebuilt, the input gradient is routed to the stored frames
+    from gpu_util import bf16_round_np
+    Cin, Cout, H, W = shape
+    B = 2
+    r = _rng(1900 + Cin + H + W + K + T)
+    s = (r.random((T, B, Cin, 2 * H, 2 * W)) < 0.08).astype(np.uint8)
+    w = synth.kaiming_normal(62, Cout, Cin) * np.float32(1.5)
+    desc = api.make_desc(T, B, Cin, H, W, Cout, K=K, beta=0.9, theta=1.0, mode=mode, precision=api.TAC_BF16,
+                         in_format=api.TAC_IN_BITS_MAXPOOL2)
+    T_out, Ho, Wo = api.tac_out_shape(desc)
+    g_out = r.standard_normal((T_out, B, Cout, Ho, Wo)).astype(np.float32)
+    sp, wd = torch.from_numpy(np_pack(s)).to(DEV), torch.from_numpy(w).to(DEV)
+    v = torch.zeros((B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    vt = torch.empty((T_out, B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    api.tac_conv_lif(desc, sp, api.tac_prepare_weights(desc, wd), None, v, None, vt)
+    got = api.tac_conv_lif_backward(desc, sp, wd, vt, torch.from_numpy(g_out).to(DEV), surrogate=api.TAC_SG_ARCTAN, alpha=2.0,
+                                    detach_reset=True)
+    torch.cuda.synchronize()
+    kw = dict(K=K, beta=float(np.float32(0.9)), theta=1.0, mode=ORACLE_MODE[mode], pool2="max")
+    out, v_pre, _ = oracle.conv_lif(s, bf16_round_np(w).astype(np.float64), round_a_bf16=True, **kw)
+    ref = oracle.conv_lif_backward(s, w.astype(np.float64), v_pre, g_out.astype(np.float64), surrogate=oracle.ARCTAN, alpha=2.0,
+                                   detach_reset=True, round_a_bf16=True, **kw)
+    assert out.sum() > 0
+    for name, a, b, tol in (("dL/dY", got["grad_y"], ref["dY"], 1e-3), ("dW", got["grad_w"], ref["dW"], TOL_BF16),
+                            ("dL/dS", got["grad_in"], ref["g_in"], TOL_BF16)):
+        e = np.abs(a.cpu().numpy() - b).max() / np.abs(b).max()
+        assert e <= tol, "%s: %.3g" % (name, e)
