@@ -204,10 +204,10 @@ int tac_stack_forward(const tac_stack_layer_t* layers, int32_t n_layers, const v
  * Sec. 4 applies to the backward pass as well).  With desc->precision = TAC_BF16 the two
  * convolution gradients run on the matrix cores where the shape allows (stride 1; Cin a multiple of
  * 32; width 16, 32, 64 or 128 and Cout a multiple of 128 for dW; width 32, 64 or 128 and Cout = 64
- * or 128 for dL/dS; packed input without a pool on load; grad_y 16-byte aligned): dY_k, A_k and W
- * enter them rounded to bfloat16, sums
- * are fp32.  Everything else, and TAC_FP32, is fp32 vector arithmetic.  The rounding inside a bf16
- * forward pass is differentiated as if it were not there. */
+ * or 128 for dL/dS; packed input, as it is or with the max pool on load; grad_y 16-byte aligned):
+ * dY_k, A_k and W enter them rounded to bfloat16, sums are fp32.  Everything else, and TAC_FP32, is
+ * fp32 vector arithmetic.  The rounding inside a bf16 forward pass is differentiated as if it were
+ * not there. */
 enum { TAC_SG_FAST_SIGMOID = 0, TAC_SG_ARCTAN = 1 };
 typedef struct tac_backward_desc {
   int32_t surrogate;      /* TAC_SG_FAST_SIGMOID / TAC_SG_ARCTAN                                */
