@@ -155,3 +155,106 @@ def test_cfg5_full_size_sampled_neurons(cfg5_inputs, rate, mode, K):
     assert ref[0].mean() > 0.01
     print("cfg5 rate %.1f %s K=%d: %s final-V err %.2e output rate %.3f" %
           (rate, api.MODE_NAMES[mode], K, par, err[clean].max(), ref[0].mean()))
+
+
+# ---------------------------------------------------------------- cfg5 backward: full size, sampled windows
+
+_CENTRES = [0, 5, 11, 17, 23, 29, 35, 41, 47, 53, 58, 63]            # 5 x 5 input windows around them do not overlap
+
+
+@pytest.mark.parametrize("mode,K", [(api.TAC_COLLAPSE, 4), (api.TAC_PER_STEP, 1), (api.TAC_PRESERVE, 8)])
+def test_cfg5_full_size_backward_sampled_windows(cfg5_inputs, mode, K):
+    """Backward pass in the launch configuration `bench.py --backward` times.  dL/d(output spikes) is zero except on
+    sampled 3 x 3 windows of output pixels (all channels, all steps; image corners and edges among them), so every
+    gradient is a sum over those windows only and the oracle can form it from 5 x 5 crops of the input: dW and dbias
+    are compared whole, dL/dS on the crops, and dL/dS must be exactly zero everywhere else."""
+    wl = synth.WORKLOADS["cfg5"]
+    dev = torch.device("cuda:0")
+    packed, dense = cfg5_inputs[0.1]
+    w = wl.make_weights(0)
+    beta = float(np.float32(wl.beta))
+    d = api.make_desc(wl.T, wl.B, 128, 64, 64, 128, K=K, beta=wl.beta, theta=wl.theta, mode=mode, precision=api.TAC_BF16)
+    wd = torch.from_numpy(w).to(dev)
+    T_out = api.tac_out_shape(d)[0]
+    v = torch.zeros((wl.B, 128, 64, 64), dtype=torch.float32, device=dev)
+    vt = torch.empty((T_out, wl.B, 128, 64, 64), dtype=torch.float32, device=dev)
+    api.tac_conv_lif(d, packed, api.tac_prepare_weights(d, wd), None, v, None, vt)
+    torch.cuda.synchronize()
+    del v
+
+    r = _rng(5000 + 7 * K + mode)
+    cells = [(s, y, x) for s in (0, 1) for y in _CENTRES for x in _CENTRES]
+    corners = [c for c in cells if c[1] in (0, 63) or c[2] in (0, 63)]
+    pick = [corners[i] for i in r.choice(len(corners), 24, replace=False)]
+    inner = [c for c in cells if c not in corners]
+    pick += [inner[i] for i in r.choice(len(inner), 40, replace=False)]
+    n = len(pick)
+    # crops: input rows/columns y-2 .. y+2 (zero outside the image, which is the layer's own padding), output
+    # pixels of the crop = the same 5 x 5 positions, of which the inner 3 x 3 see their whole receptive field
+    crop = np.zeros((wl.T, n, 128, 5, 5), dtype=np.uint8)
+    inside = np.zeros((n, 5, 5), dtype=bool)
+    for i, (s, y, x) in enumerate(pick):
+        for dy in range(5):
+            for dx in range(5):
+                yy, xx = y - 2 + dy, x - 2 + dx
+                if 0 <= yy < 64 and 0 <= xx < 64:
+                    crop[:, i, :, dy, dx] = dense[:, s, :, yy, xx]
+                    inside[i, dy, dx] = True
+    kw = dict(K=K, beta=beta, theta=1.0, mode=ORACLE_MODE[mode])
+    spk_ref, v_ref, _ = oracle.conv_lif(crop, bf16_round_np(w).astype(np.float64), None, round_a_bf16=True, **kw)
+    win = inside.copy()                                                  # the 3 x 3 window, where it lies in the image
+    win[:, 0, :] = win[:, 4, :] = False
+    win[:, :, 0] = win[:, :, 4] = False
+    # the library's recorded membranes on the windows; windows with a spike that differs from the oracle's (a
+    # membrane within rounding of the threshold) are left out of the loss, on both sides
+    keep = np.ones(n, dtype=bool)
+    v_err = 0.0
+    for i, (s, y, x) in enumerate(pick):
+        b = 0 if s == 0 else wl.B - 1
+        for dy in range(1, 4):
+            for dx in range(1, 4):
+                if not win[i, dy, dx]:
+                    continue
+                vg = vt[:, b, :, y - 2 + dy, x - 2 + dx].cpu().numpy().astype(np.float64)
+                vr = v_ref[:, i, :, dy, dx]
+                if ((vg >= 1.0) != (vr >= 1.0)).any():
+                    keep[i] = False
+                else:
+                    v_err = max(v_err, (np.abs(vg - vr) / np.maximum(np.abs(vr), 1.0)).max())
+    assert keep.sum() >= n - 4, "too many windows with a threshold flip: %d of %d" % (n - keep.sum(), n)
+    assert v_err < 1e-3
+    g_crop = r.standard_normal((T_out, n, 128, 5, 5)) * (win & keep[:, None, None])[None, :, None]
+    g_crop = g_crop.astype(np.float32)
+    g_out = torch.zeros((T_out, wl.B, 128, 64, 64), dtype=torch.float32, device=dev)
+    for i, (s, y, x) in enumerate(pick):
+        b = 0 if s == 0 else wl.B - 1
+        for dy in range(1, 4):
+            for dx in range(1, 4):
+                if win[i, dy, dx]:
+                    g_out[:, b, :, y - 2 + dy, x - 2 + dx] = torch.from_numpy(g_crop[:, i, :, dy, dx]).to(dev)
+    got = api.tac_conv_lif_backward(d, packed, wd, vt, g_out, surrogate=api.TAC_SG_ARCTAN, alpha=2.0, detach_reset=True)
+    torch.cuda.synchronize()
+    ref = oracle.conv_lif_backward(crop, w.astype(np.float64), v_ref, g_crop.astype(np.float64), surrogate=oracle.ARCTAN,
+                                   alpha=2.0, detach_reset=True, round_a_bf16=True, **kw)
+
+    def err(name, a, b, tol):
+        e = np.abs(a - b).max() / np.abs(b).max()
+        assert e <= tol, "%s: %.3g" % (name, e)
+        return e
+    e_w = err("dW", got["grad_w"].cpu().numpy(), ref["dW"], 2e-2)
+    e_b = err("dbias", got["grad_bias"].cpu().numpy(), ref["dbias"], 1e-3)
+    gi = got["grad_in"]
+    scale = np.abs(ref["g_in"]).max()
+    e_s = 0.0
+    for i, (s, y, x) in enumerate(pick):
+        b = 0 if s == 0 else wl.B - 1
+        y0, y1, x0, x1 = max(y - 2, 0), min(y + 3, 64), max(x - 2, 0), min(x + 3, 64)
+        g = gi[:, b, :, y0:y1, x0:x1].cpu().numpy()
+        rr = ref["g_in"][:, i, :, y0 - (y - 2):y1 - (y - 2), x0 - (x - 2):x1 - (x - 2)]
+        e_s = max(e_s, np.abs(g - rr).max() / scale)
+        gi[:, b, :, y0:y1, x0:x1] = 0
+    assert e_s <= 2e-2, "dL/dS: %.3g" % e_s
+    assert scale > 0 and np.abs(ref["dW"]).max() > 0
+    assert float(gi.abs().max()) == 0.0, "input gradient outside the windows"
+    print("cfg5 backward %s K=%d: %d windows (%d left out), membrane err %.1e, dW %.1e dbias %.1e dS %.1e" %
+          (api.MODE_NAMES[mode], K, n, n - keep.sum(), v_err, e_w, e_b, e_s))
