@@ -82,13 +82,17 @@ struct Geo {
   static constexpr int kAHalf = kInRows * kXP * 16;          // bytes: one k-half plane
   static constexpr int kABuf = 2 * kAHalf;
   static constexpr int kWordsPerFrame = kChunk * kRowWords;  // staged dwords per chunk and frame
+  // bytes of one staging buffer: [row word][class word][cin], each row word's K x kChunk dwords followed by
+  // stage_pad(K) unused ones (see StagePlan; the stride-2 tiles have LDS to spare for it up to K = 2 only)
+  __host__ __device__ static constexpr int stage_pad(int K) { return (S == 1 || K <= 2) ? 4 : 0; }
+  __host__ __device__ static constexpr int words_bytes(int K) { return kRowWords * (K * kChunk + stage_pad(K)) * 4; }
   static constexpr int kOutWords = (kWo + 31) / 32;          // packed words per output row
   static constexpr int kLdsA = 0;
   static constexpr int kLdsW = kLdsA + 2 * kABuf;
   // two weight buffers of 9 taps x MC blocks of one KiB, bias, aggregate table, two staging buffers
   __host__ __device__ static constexpr int lds_bias(int MC) { return kLdsW + 2 * 9 * MC * 1024; }
   __host__ __device__ static constexpr int lds_lut(int MC) { return lds_bias(MC) + kCoutTile * 4; }
-  static constexpr int lds_bytes(int K, int MC = kMC) { return lds_lut(MC) + lut_bytes(K) + 2 * kWordsPerFrame * K * 4; }
+  static constexpr int lds_bytes(int K, int MC = kMC) { return lds_lut(MC) + lut_bytes(K) + 2 * words_bytes(K); }
   // LDS column (in 16-byte units) of padded pixel xp
   __host__ __device__ static constexpr int col(int xp) { return S == 1 ? xp : (xp & 1) * kXH + (xp >> 1); }
   // the loader pipeline has kSteps + 2 slots (slot i reads the words of step i, looks up step
@@ -125,6 +129,10 @@ __device__ __forceinline__ LaneGeom lane_geom(int lane, int oy_wave, int Ho, siz
 // pixel p as the K-bit field [bit j = frame j] at bit position p - c.  A loader lane then gets
 // all K bits of its pixel with one bit-field extract, and the aggregate from a table.  K = 16
 // is staged as two such halves of 8 frames.  In LDS the order is [row word][class word][cin].
+// The threads of a wave hold consecutive row words of one channel, which K x kChunk dwords apart would all
+// fall into the same LDS bank (K >= 4; a few banks for smaller K): every store of class words would take as
+// many cycles as the wave has row words of that channel.  Four dwords of padding per row word spread 16
+// consecutive row words over all 64 banks and keep the loader's 16-byte reads aligned.
 template <int NG>
 struct StagePlan {
   uint32_t goff[NG];     // dword offset of the group's frame-0 word from the chunk base (always valid)
@@ -146,7 +154,7 @@ __device__ __forceinline__ void stage_plan(StagePlan<NG>& sp, const MfmaParams& 
       const int row = rw / G::kWW, word = rw - row * G::kWW;
       const int iy = iy0 + row;
       const int iyc = min(max(iy, 0), p.H - 1);
-      sp.lofs[l] = (uint32_t)((rw * K * kChunk + cin) * 4);
+      sp.lofs[l] = (uint32_t)((rw * (K * kChunk + G::stage_pad(K)) + cin) * 4);
       // max pool on load: the stored image has twice the rows and words; the group starts at its
       // upper left word
       sp.goff[l] = MP ? (uint32_t)((cin * 2 * p.H + 2 * iyc) * (2 * G::kWW) + 2 * word)
@@ -302,11 +310,11 @@ __device__ __forceinline__ void read_words(StepRegs<KT>& sr, const uint8_t* word
   static_assert(KT > 0, "compile-time K only");
   const int lw = lane_word<G>(lane, step);
   if constexpr (KT == 16) {
-    const uint8_t* src = words_buf + (((lw * 16 + (lane & 7)) * kChunk + q * 4) * 4);
+    const uint8_t* src = words_buf + ((lw * (16 * kChunk + G::stage_pad(16)) + (lane & 7) * kChunk + q * 4) * 4);
     sr.cw = *reinterpret_cast<const u32x4*>(src);
     sr.cw_hi = *reinterpret_cast<const u32x4*>(src + 8 * kChunk * 4);
   } else {
-    sr.cw = *reinterpret_cast<const u32x4*>(words_buf + (((lw * KT + (lane & (KT - 1))) * kChunk + q * 4) * 4));
+    sr.cw = *reinterpret_cast<const u32x4*>(words_buf + ((lw * (KT * kChunk + G::stage_pad(KT)) + (lane & (KT - 1)) * kChunk + q * 4) * 4));
   }
 }
 
@@ -372,7 +380,7 @@ __device__ __forceinline__ void expand_step(const MfmaParams& p, const uint8_t* 
     lookup<KT>(sr, lut, lane);
     write_a<G, KT>(sr, a_next, lane, q, step);
   } else {
-    const uint32_t* src = reinterpret_cast<const uint32_t*>(words_buf) + (lane_word<G>(lane, step) * K * kChunk + q * 4);
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(words_buf) + (lane_word<G>(lane, step) * (K * kChunk + G::stage_pad(K)) + q * 4);
     const uint32_t bitpos = lane & 31;
     uint32_t acc[4] = {0, 0, 0, 0};
     for (int j = 0; j < K; ++j) {
@@ -435,7 +443,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   const int total = p.G * NC;
   uint8_t* const lut = lds + kLdsLut;
   uint8_t* const words0 = lut + lut_bytes(KT);
-  const int words_bytes = G::kWordsPerFrame * K * 4;
+  const int words_bytes = G::words_bytes(K);
   const int oy_wave = y0 + wave * G::kWaveRows;                // first output row of this wave
 
   // zero padding columns (left of pixel 0, right of the last pixel) of both A buffers; they
