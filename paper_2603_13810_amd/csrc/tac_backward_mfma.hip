@@ -36,18 +36,24 @@ __device__ __forceinline__ int group_frames(const BackwardParams& p, int k) {
 
 // XS = W / 16: MFMA steps per output row; R = 16 / XS output rows per strip.
 // POOL: max pool on load (the stored frames are unpooled).
-template <int XS, bool POOL>
-__global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(const BackwardParams p, int n_strips, int n_split) {
+// NCB: blocks of 32 input channels per workgroup.  1: four waves, two such workgroups per compute unit.  2: eight
+// waves, wave w and wave w + 4 take the same output channels and one block of input channels each, so that the dY
+// values both need are asked for by the same compute unit at about the same time and come from HBM once for the two.
+template <int XS, bool POOL, int NCB>
+__global__ __launch_bounds__(kThreads * NCB, (NCB == 1 && XS <= 4) ? 2 : 1) void wgrad_mfma_kernel(const BackwardParams p, int n_strips,
+                                                                                                   int n_split) {
   constexpr int R = 16 / XS;
+  constexpr int NT = kThreads * NCB;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int cib = wave >> 2;                             // the wave's block of input channels within the workgroup
   const int n = lane & 31, h = lane >> 5;
-  // grid: x = slice of the work list, y = block of 128 output channels, z = block of 32 input channels.  Workgroups
+  // grid: x = slice of the work list, y = block of 128 output channels, z = block of 32 NCB input channels.  Workgroups
   // go to the 8 XCDs round-robin in x-fastest order: with a slice count that is a multiple of 8, those that read the
   // same dY (same slice, other input channels) share an XCD and its L2.
-  const int ci0 = blockIdx.z * 32;
-  const int co_w = blockIdx.y * 128 + wave * 32;         // the wave's 32 output channels
+  const int ci0 = blockIdx.z * (32 * NCB);
+  const int co_w = blockIdx.y * 128 + (wave & 3) * 32;   // the wave's 32 output channels
   constexpr int W = XS * 16, XB = W >> 3;
   constexpr int rows_in = R + 2;
   const size_t plane = (size_t)p.Ho * p.Wo;
@@ -97,9 +103,9 @@ __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(c
     constexpr int WWI = W >= 32 ? W / 32 : 1;            // words per row
     constexpr int XBW = W >= 32 ? 4 : XB;                // blocks of 8 pixels per word
     const size_t fstride = (size_t)p.B * p.Cin * p.H * p.Wwi;
-    for (int e = tid; e < 32 * rows_in * WWI; e += kThreads) {
+    for (int e = tid; e < 32 * NCB * rows_in * WWI; e += NT) {
       const int wi = e % WWI, cr = e / WWI;
-      const int ci = cr & 31, r = cr >> 5;
+      const int ci = cr % (32 * NCB), r = cr / (32 * NCB);            // channel within the workgroup's NCB blocks
       const int iy = y0 - 1 + r;
       uint32_t q[34];
 #pragma unroll
@@ -141,7 +147,7 @@ __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(c
 #pragma unroll
           for (int t = 0; t < 4; ++t)
             v[t] = pack_bf16((float)q[8 * xl + kx + 2 * t] * (1.0f / 8388608.0f), (float)q[8 * xl + kx + 2 * t + 1] * (1.0f / 8388608.0f));
-          *reinterpret_cast<u32x4*>(lds + kx * copy_bytes + ((r * XB + wi * XBW + xl) * 32 + ci) * 16) = v;
+          *reinterpret_cast<u32x4*>(lds + ((ci >> 5) * 3 + kx) * copy_bytes + ((r * XB + wi * XBW + xl) * 32 + (ci & 31)) * 16) = v;
         }
       }
     }
@@ -171,7 +177,7 @@ __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(c
         bf16x8 af[3];
 #pragma unroll
         for (int kx = 0; kx < 3; ++kx)
-          af[kx] = *reinterpret_cast<const bf16x8*>(lds + kx * copy_bytes + ((r * XB + 2 * xs + h) * 32 + n) * 16);
+          af[kx] = *reinterpret_cast<const bf16x8*>(lds + (cib * 3 + kx) * copy_bytes + ((r * XB + 2 * xs + h) * 32 + n) * 16);
         static_for<0, 3>([&](auto ky_) {
           constexpr int ky = decltype(ky_)::value, yl = r - ky;
           if constexpr (yl >= 0 && yl < R) {
@@ -191,9 +197,9 @@ __global__ __launch_bounds__(kThreads, XS <= 4 ? 2 : 1) void wgrad_mfma_kernel(c
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int co = co_w + 8 * (r >> 2) + 4 * h + (r & 3);
-      atomicAdd(p.grad_w + ((size_t)co * p.Cin + ci0 + n) * 9 + t, acc[t][r]);
+      atomicAdd(p.grad_w + ((size_t)co * p.Cin + ci0 + 32 * cib + n) * 9 + t, acc[t][r]);
     }
-  if (p.grad_bias && blockIdx.z == 0) {
+  if (p.grad_bias && blockIdx.z == 0 && cib == 0) {
     bias_acc += __shfl_down(bias_acc, 32, 64);           // the two pixel halves of a channel
     if (h == 0) atomicAdd(p.grad_bias + co_w + n, bias_acc);
   }
@@ -402,32 +408,49 @@ bool backward_wgrad_mfma_supported(const BackwardParams& p) {
 hipError_t backward_wgrad_mfma_launch(const BackwardParams& p, hipStream_t s) {
   const int R = 256 / p.W;                               // output rows per strip (16 MFMA steps); two workgroups per compute unit fit the LDS
   const int n_strips = (p.Ho + R - 1) / R;
-  const size_t lds = (size_t)3 * (R + 2) * (p.W / 8) * 512;
-  const int ci_blocks = p.Cin / 32, co_blocks = p.Cout / 128;
+  // two blocks of input channels per workgroup (eight waves) where the channel count and the LDS allow it
+  const int ncb = (p.Cin % 64 == 0 && p.W <= 64) ? 2 : 1;
+  const size_t lds = (size_t)ncb * 3 * (R + 2) * (p.W / 8) * 512;
+  const int ci_blocks = p.Cin / (32 * ncb), co_blocks = p.Cout / 128;
   const long long items = (long long)p.G * p.B * n_strips;
-  long long split = (512 + ci_blocks * co_blocks - 1) / (ci_blocks * co_blocks);      // two workgroups per compute unit
+  const int resident = ncb == 2 ? 256 : 512;             // eight waves per compute unit either way
+  long long split = (resident + ci_blocks * co_blocks - 1) / (ci_blocks * co_blocks);
   split = (split + 7) / 8 * 8;                           // a multiple of the XCD count
   if (split > items) split = items;
   if (split < 1) split = 1;
   auto launch = [&](auto kern) -> hipError_t {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)split, co_blocks, ci_blocks), dim3(kThreads), lds, s, p, n_strips, (int)split);
+    hipLaunchKernelGGL(kern, dim3((unsigned)split, co_blocks, ci_blocks), dim3(kThreads * ncb), lds, s, p, n_strips, (int)split);
     return hipGetLastError();
   };
+  if (ncb == 2) {
+    if (p.pool2) {
+      switch (p.W) {
+        case 16: return launch(&wgrad_mfma_kernel<1, true, 2>);
+        case 32: return launch(&wgrad_mfma_kernel<2, true, 2>);
+        default: return launch(&wgrad_mfma_kernel<4, true, 2>);
+      }
+    }
+    switch (p.W) {
+      case 16: return launch(&wgrad_mfma_kernel<1, false, 2>);
+      case 32: return launch(&wgrad_mfma_kernel<2, false, 2>);
+      default: return launch(&wgrad_mfma_kernel<4, false, 2>);
+    }
+  }
   if (p.pool2) {
     switch (p.W) {
-      case 16: return launch(&wgrad_mfma_kernel<1, true>);
-      case 32: return launch(&wgrad_mfma_kernel<2, true>);
-      case 64: return launch(&wgrad_mfma_kernel<4, true>);
-      default: return launch(&wgrad_mfma_kernel<8, true>);
+      case 16: return launch(&wgrad_mfma_kernel<1, true, 1>);
+      case 32: return launch(&wgrad_mfma_kernel<2, true, 1>);
+      case 64: return launch(&wgrad_mfma_kernel<4, true, 1>);
+      default: return launch(&wgrad_mfma_kernel<8, true, 1>);
     }
   }
   switch (p.W) {
-    case 16: return launch(&wgrad_mfma_kernel<1, false>);
-    case 32: return launch(&wgrad_mfma_kernel<2, false>);
-    case 64: return launch(&wgrad_mfma_kernel<4, false>);
-    default: return launch(&wgrad_mfma_kernel<8, false>);
+    case 16: return launch(&wgrad_mfma_kernel<1, false, 1>);
+    case 32: return launch(&wgrad_mfma_kernel<2, false, 1>);
+    case 64: return launch(&wgrad_mfma_kernel<4, false, 1>);
+    default: return launch(&wgrad_mfma_kernel<8, false, 1>);
   }
 }
 
