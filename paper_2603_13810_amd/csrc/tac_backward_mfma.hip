@@ -4,8 +4,9 @@
 // For one filter tap this is a GEMM with the pixels as the contraction: D[32 co x 32 ci] +=
 // dY^T[32 co x 16 px] . A[16 px x 32 ci], the 16 pixels being 16 consecutive x of one output row.
 //
-// Workgroup = 32 input channels x all of a 128-channel block of outputs (wave w: channels 32 w ..)
-// x a slice of the (group, sample, row strip) list.  Per strip the aggregates A_k of the 32 input
+// Workgroup = one or two blocks of 32 input channels x all of a 128-channel block of outputs (four
+// waves per block of input channels, wave w: output channels 32 (w % 4) ..) x a slice of the (group,
+// sample, row strip) list.  Per strip the aggregates A_k of the 32 input
 // channels are rebuilt from the packed frames (Eq. 2, rounded to bf16 like the forward pass rounds
 // them) into LDS, three copies shifted by the tap's kx so that every fragment read is an aligned,
 // conflict-free 16 bytes per lane: [kx][row][x / 8][ci][x % 8].  A wave reads its dY rows from
