@@ -308,23 +308,35 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
     // ---- MFMAs.  The wave's NBW blocks of 32 pixels sit one below the other (rows yl0 .. yl0 + NBW - 1 of column
     //      block x0), so a dY fragment of tile row yl0 + rr serves the output rows rr - 2 + ky for ky = 0, 1, 2:
     //      per 16 channels and kx, 3 weight fragments and NBW + 2 dY fragments feed 3 NBW MFMAs
-#pragma unroll
-    for (int st = 0; st < 4; ++st) {
-#pragma unroll
-      for (int kx = 0; kx < 3; ++kx) {
-        bf16x8 wf[3];
+    //      The 12 (16 channels, kx) phases are software-pipelined over two sets of fragment registers: the LDS reads
+    //      of phase i + 1 are issued in front of the MFMAs of phase i, so that no MFMA waits for a read just issued.
+    {
+      bf16x8 wf[2][3], df[2][NBW + 2];
+      const uint8_t* const w_lane = wl + (((w.c0 >> 4) * 64 + lane) * 16);
+      const uint8_t* const d_lane = lds + h * kPlane + ((yl0 * WP + x0 + n + 2) * 16);
+      auto fetch = [&](auto ph_) {
+        constexpr int ph = decltype(ph_)::value, st = ph / 3, kx = ph % 3, set = ph & 1;
 #pragma unroll
         for (int ky = 0; ky < 3; ++ky)
-          wf[ky] = *reinterpret_cast<const bf16x8*>(wl + (((ky * 3 + kx) * n_steps16 + (w.c0 >> 4) + st) * 64 + lane) * 16);
+          wf[set][ky] = *reinterpret_cast<const bf16x8*>(w_lane + ((ky * 3 + kx) * n_steps16 + st) * 1024);
+#pragma unroll
+        for (int rr = 0; rr < NBW + 2; ++rr)
+          df[set][rr] = *reinterpret_cast<const bf16x8*>(d_lane + 2 * st * kPlane + (rr * WP - kx) * 16);
+      };
+      fetch(std::integral_constant<int, 0>{});
+      static_for<0, 12>([&](auto ph_) {
+        constexpr int ph = decltype(ph_)::value, set = ph & 1;
+        if constexpr (ph + 1 < 12) fetch(std::integral_constant<int, ph + 1>{});
+        __builtin_amdgcn_sched_barrier(0);
         static_for<0, NBW + 2>([&](auto rr_) {
           constexpr int rr = decltype(rr_)::value;
-          const bf16x8 df = *reinterpret_cast<const bf16x8*>(lds + (2 * st + h) * kPlane + ((yl0 + rr) * WP + x0 + n + 2 - kx) * 16);
           static_for<0, 3>([&](auto ky_) {
             constexpr int ky = decltype(ky_)::value, q = rr - 2 + ky;
-            if constexpr (q >= 0 && q < NBW) acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ky], df, acc[q], 0, 0, 0);
+            if constexpr (q >= 0 && q < NBW) acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[set][ky], df[set][rr], acc[q], 0, 0, 0);
           });
         });
-      }
+        __builtin_amdgcn_sched_barrier(0);
+      });
     }
     if (w.c0 + 64 >= p.Cout) {
       // ---- the strip is complete: dL/dS of the group's frames.  Register r on lane (n, h) is channel
