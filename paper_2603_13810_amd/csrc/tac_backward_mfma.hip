@@ -350,11 +350,19 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
           // max pool on load: the gradient of the stored frames [2H][2W]; all of it to the first set bit of the
           // window in row-major order (the first input when none is set), zero to the other three
           for (int j = 0; j < Kg; ++j) {
+            // the 16 channels' window bits first, all loads in flight together (behind a store the compiler
+            // could not move them: it does not know that frames and gradients do not overlap)
+            uint32_t bits[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               const size_t chan = ((size_t)(w.k * p.K + j) * p.B + w.b) * p.Cin + ci0 + 8 * (r >> 2) + 4 * h + (r & 3);
               const uint32_t* src = p.spikes + chan * 2 * p.H * p.Wwi + (size_t)(2 * iy) * p.Wwi + (ix >> 4);
-              const uint32_t two = ((src[0] >> (2 * ix & 31)) & 3u) | (((src[p.Wwi] >> (2 * ix & 31)) & 3u) << 2);
+              bits[r] = ((src[0] >> (2 * ix & 31)) & 3u) | (((src[p.Wwi] >> (2 * ix & 31)) & 3u) << 2);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const size_t chan = ((size_t)(w.k * p.K + j) * p.B + w.b) * p.Cin + ci0 + 8 * (r >> 2) + 4 * h + (r & 3);
+              const uint32_t two = bits[r];
               const int best = two ? __ffs(two) - 1 : 0;
               const float g = wj[j] * acc[q][r];
               float* dst = p.grad_in + chan * 4 * plane + (size_t)(2 * iy) * (2 * W) + 2 * ix;
