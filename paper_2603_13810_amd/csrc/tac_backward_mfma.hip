@@ -104,14 +104,66 @@ __global__ __launch_bounds__(kThreads * NCB, (NCB == 1 && XS <= 4) ? 2 : 1) void
     constexpr int WWI = W >= 32 ? W / 32 : 1;            // words per row
     constexpr int XBW = W >= 32 ? 4 : XB;                // blocks of 8 pixels per word
     const size_t fstride = (size_t)p.B * p.Cin * p.H * p.Wwi;
-    for (int e = tid; e < 32 * NCB * rows_in * WWI; e += NT) {
+    // Without the pool the frame words travel global -> LDS without passing through registers, four frames of a
+    // group at a time (staging area behind the aggregates: [pass][frame][thread]): one wait for global memory per
+    // four frames instead of one per frame, and for groups of up to four frames one for all passes together.  A
+    // thread's left and right neighbour words are those of the threads next to it (same wave).
+    constexpr int kPasses = (32 * NCB * rows_in * WWI + NT - 1) / NT;
+    uint8_t* const stage = lds + NCB * 3 * copy_bytes;
+    auto stage_request = [&](int pass, int j0) {
+      const int e = tid + pass * NT;
+      const int wi = e % WWI, cr = e / WWI;
+      const int ci = cr % (32 * NCB), iy = y0 - 1 + cr / (32 * NCB);
+      if (e < 32 * NCB * rows_in * WWI && iy >= 0 && iy < p.H) {
+        const uint32_t* src = p.spikes + ((size_t)k * p.K * p.B + b) * p.Cin * p.H * p.Wwi + ((size_t)(ci0 + ci) * p.H + iy) * p.Wwi + wi;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (j0 + u < Kg)
+            __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (size_t)(j0 + u) * fstride),
+                                             (lds_void_ptr)(stage + ((pass * 4 + u) * NT + wave * 64) * 4), 4, 0, 0);
+      }
+    };
+    if constexpr (!POOL) {
+      if (Kg <= 4) {
+#pragma unroll
+        for (int pass = 0; pass < kPasses; ++pass) stage_request(pass, 0);
+      }
+    }
+    for (int pass = 0; pass < kPasses; ++pass) {
+      const int e = tid + pass * NT;
+      if (e >= 32 * NCB * rows_in * WWI) break;
       const int wi = e % WWI, cr = e / WWI;
       const int ci = cr % (32 * NCB), r = cr / (32 * NCB);            // channel within the workgroup's NCB blocks
       const int iy = y0 - 1 + r;
       uint32_t q[34];
 #pragma unroll
       for (int i = 0; i < 34; ++i) q[i] = 0u;
-      if (iy >= 0 && iy < p.H) {
+      if constexpr (!POOL) {
+        for (int j0 = 0; j0 < Kg; j0 += 4) {
+          if (Kg > 4) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the reads of the batch before are done
+            stage_request(pass, j0);
+          }
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          if (iy >= 0 && iy < p.H) {
+            const uint32_t* sw = reinterpret_cast<const uint32_t*>(stage) + (pass * 4) * NT + tid;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              if (j0 + u < Kg) {
+                const uint32_t cur = sw[u * NT];
+                const uint32_t left = wi > 0 ? sw[u * NT - 1] >> 31 : 0u;           // pixel 32 wi - 1
+                const uint32_t right = wi + 1 < WWI ? sw[u * NT + 1] & 1u : 0u;     // pixel 32 wi + 32
+                const uint32_t wq = (uint32_t)(wj[j0 + u] * 8388608.0f + 0.5f);     // beta^(Kg-1-j) in 2^-23 units
+                q[0] = __umul24(left, wq) + q[0];
+#pragma unroll
+                for (int i = 0; i < 32; ++i) q[i + 1] = __umul24(__builtin_amdgcn_ubfe(cur, i, 1), wq) + q[i + 1];
+                q[33] = __umul24(right, wq) + q[33];
+              }
+            }
+          }
+        }
+      }
+      if (POOL && iy >= 0 && iy < p.H) {
         // max pool on load: the stored frames are [2H][2W], Wwi words per stored row; pooled word wi comes from
         // the stored words 2 wi and 2 wi + 1 of the rows 2 iy and 2 iy + 1
         const size_t rows_st = POOL ? 2 * (size_t)p.H : (size_t)p.H;
@@ -431,7 +483,10 @@ hipError_t backward_wgrad_mfma_launch(const BackwardParams& p, hipStream_t s) {
   const int n_strips = (p.Ho + R - 1) / R;
   // two blocks of input channels per workgroup (eight waves) where the channel count and the LDS allow it
   const int ncb = (p.Cin % 64 == 0 && p.W <= 64) ? 2 : 1;
-  const size_t lds = (size_t)ncb * 3 * (R + 2) * (p.W / 8) * 512;
+  // aggregates, then the staging area of the frame words: [pass][4 frames][thread]
+  const int n_threads = kThreads * ncb, wwi = p.W >= 32 ? p.W / 32 : 1;
+  const int passes = (32 * ncb * (R + 2) * wwi + n_threads - 1) / n_threads;
+  const size_t lds = (size_t)ncb * 3 * (R + 2) * (p.W / 8) * 512 + (size_t)passes * 4 * n_threads * 4;
   const int ci_blocks = p.Cin / (32 * ncb), co_blocks = p.Cout / 128;
   const long long items = (long long)p.G * p.B * n_strips;
   const int resident = ncb == 2 ? 256 : 512;             // eight waves per compute unit either way
@@ -440,7 +495,7 @@ hipError_t backward_wgrad_mfma_launch(const BackwardParams& p, hipStream_t s) {
   if (split > items) split = items;
   if (split < 1) split = 1;
   auto launch = [&](auto kern) -> hipError_t {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)split, co_blocks, ci_blocks), dim3(kThreads * ncb), lds, s, p, n_strips, (int)split);
     return hipGetLastError();
