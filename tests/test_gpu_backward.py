@@ -94,7 +94,7 @@ TOL_BF16 = 2e-2     # the bar of the bf16 path; dY and A_k enter the matrix core
 
 @pytest.mark.parametrize("shape", MFMA_SHAPES)
 @pytest.mark.parametrize("mode,K,T", [(api.TAC_PER_STEP, 1, 4), (api.TAC_COLLAPSE, 4, 8), (api.TAC_COLLAPSE, 4, 7), (api.TAC_PRESERVE, 2, 6),
-                                      (api.TAC_COLLAPSE, 16, 16)])
+                                      (api.TAC_COLLAPSE, 16, 16), (api.TAC_COLLAPSE, 8, 19), (api.TAC_PRESERVE, 8, 13)])
 def test_backward_bf16_layer_weight_gradient_on_the_matrix_cores(shape, mode, K, T):
     from gpu_util import bf16_round_np
     Cin, Cout, H, W = shape
@@ -118,8 +118,15 @@ def test_backward_bf16_layer_weight_gradient_on_the_matrix_cores(shape, mode, K,
 
     kw = dict(K=K, beta=float(np.float32(beta)), theta=theta, mode=ORACLE_MODE[mode])
     out, v_pre, _ = oracle.conv_lif(s, bf16_round_np(w).astype(np.float64), bias.astype(np.float64), round_a_bf16=True, **kw)
-    ref = oracle.conv_lif_backward(s, w.astype(np.float64), v_pre, g_out.astype(np.float64), surrogate=oracle.ARCTAN, alpha=2.0,
-                                   detach_reset=True, round_a_bf16=True, **kw)
+    # a membrane within rounding of the threshold may spike on one side only, and every later membrane of that neuron then
+    # differs by theta: such a flip must be that close to the threshold, and the backward pass is then compared on the
+    # membranes the library recorded (the oracle's own otherwise)
+    v_gpu = vt.cpu().numpy().astype(np.float64)
+    flips = (v_gpu >= theta) != (v_pre >= theta)
+    first = flips & (np.cumsum(flips, axis=0) == 1)
+    assert flips.sum() <= 4 and (np.abs(v_pre[first] - theta) < 1e-3).all(), "spikes differ away from the threshold"
+    ref = oracle.conv_lif_backward(s, w.astype(np.float64), v_gpu if flips.any() else v_pre, g_out.astype(np.float64),
+                                   surrogate=oracle.ARCTAN, alpha=2.0, detach_reset=True, round_a_bf16=True, **kw)
     assert out.sum() > 0
 
     def err(name, a, b, tol):
