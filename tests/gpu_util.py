@@ -5,7 +5,7 @@ import torch
 import oracle
 from paper_2603_13810_amd import api
 
-from parity_util import np_pack, np_unpack, pad_bits_zero, compare, TOL_FP32, TOL_BF16
+from parity_util import np_pack, np_unpack, pad_bits_zero, compare, compare3, TOL_FP32, TOL_BF16
 
 ORACLE_MODE = {api.TAC_PER_STEP: oracle.PER_STEP, api.TAC_COLLAPSE: oracle.TAC, api.TAC_PRESERVE: oracle.TAC_TP}
 
@@ -49,50 +49,66 @@ def run_gpu(spikes, w32, *, K, beta, theta, mode, stride=1, bias=None, v0=None, 
 
 
 def run_oracle(spikes, w32, *, K, beta, theta, mode, stride=1, bias=None, v0=None, pool2=False,
-               quantised=False, nthreads=8):
+               quantised=False, nthreads=None):
     """Plain oracle (double arithmetic on the fp32 inputs the GPU received) or, with quantised=True,
     the same with W and A_k first rounded to bf16."""
     w = bf16_round_np(w32) if quantised else np.asarray(w32, dtype=np.float32)
     return oracle.conv_lif(spikes, w.astype(np.float64), None if bias is None else np.asarray(bias, np.float32).astype(np.float64),
                            K=K, beta=float(np.float32(beta)), theta=float(np.float32(theta)), mode=ORACLE_MODE[mode],
                            stride=stride, pad=1, v0=None if v0 is None else np.asarray(v0, np.float32).astype(np.float64),
-                           pool2=pool2, round_a_bf16=quantised, nthreads=nthreads)
+                           pool2=pool2, round_a_bf16=quantised, nthreads=nthreads or oracle.max_threads())
 
 
 TOL_BF16_SAME_OPERANDS = 1e-3
 
 
 def check_layer(spikes, w32, *, precision=api.TAC_FP32, kernel=api.TAC_KERNEL_AUTO, expect_kernel=None,
-                plain_stats=True, **kw):
+                oracle_samples=None, **kw):
     """Run both sides and assert parity.
 
+    oracle_samples: list of sample indices.  The library runs on the whole batch (the launch geometry
+    under test); the oracle runs on those samples only and the comparison covers all of their neurons
+    (samples are independent).  The returned oracle arrays then have len(oracle_samples) samples.
+
     fp32 path: against the plain double-precision oracle at 1e-5.
-    bf16 path: rounding W and A_k to bfloat16 is a quantisation decision, so both sides take
-    it the same way: the graded comparison is against the oracle run on bf16-rounded W and
-    A_k (its own rounding code), where the stated bar is 2e-2 and this test asserts 1e-3
-    (what is left is fp32-vs-double accumulation and, rarely, one bf16 ulp in an A_k whose
-    fp32 sum sits on a rounding tie).  The distance to the unrounded oracle is measured and
-    returned as `.plain` for reporting: operand rounding alone exceeds 2e-2 at some neurons
-    (see test_bf16_operand_rounding_alone_exceeds_the_bar in the CPU tests).
+    bf16 path: the oracle runs twice, plain and with W and every A_k rounded to bfloat16 (its own
+    rounding code).  Asserted: (i) the library against the rounded oracle at 1e-3 (what is left is
+    fp32-vs-double accumulation and, rarely, one bf16 ulp in an A_k whose fp32 sum sits on a rounding
+    tie); (ii) the library adds nothing to what the operand rounding does by itself on the CPU: its
+    distance to the plain oracle is at most the rounded oracle's plus 1e-3 of the scale, and a neuron
+    leaves the plain oracle's spike train only where the rounded oracle's does (Parity3.bounded).
+    The comparison against the plain oracle at the stated 2e-2 is computed, returned as `.plain`
+    (all three as `.p3`) and printed by the callers; it is not asserted to be clean, because the rounded
+    oracle itself is not (TAC-TP with K >= 4: see test_bf16_operand_rounding_alone_exceeds_the_bar in
+    the CPU tests).
     """
     g = run_gpu(spikes, w32, precision=precision, kernel=kernel, **kw)
     if expect_kernel is not None:
         assert g["kernel"] == expect_kernel
     assert g["pad_ok"], "pad bits of the packed output must be zero"
     theta = float(np.float32(kw["theta"]))
+    if oracle_samples is not None:
+        sel = list(oracle_samples)
+        spikes = np.ascontiguousarray(np.asarray(spikes)[:, sel])
+        if kw.get("v0") is not None:
+            kw = dict(kw, v0=np.asarray(kw["v0"])[sel])
+        g = dict(g, spikes=g["spikes"][:, sel], v_trace=None if g["v_trace"] is None else g["v_trace"][:, sel],
+                 v_final=None if g["v_final"] is None else g["v_final"][sel], spikes_all=g["spikes"])
     if precision == api.TAC_BF16:
-        plain = None
-        if plain_stats:
-            r = run_oracle(spikes, w32, **kw)
-            plain = compare(r[0], r[1], g["spikes"], g["v_trace"], theta, TOL_BF16)
+        rp = run_oracle(spikes, w32, **kw)
         r = run_oracle(spikes, w32, quantised=True, **kw)
         tol = TOL_BF16_SAME_OPERANDS
+        p3 = compare3(rp[:2], r[:2], g["spikes"], g["v_trace"], theta, tol, TOL_BF16)
+        par = p3.vs_rounded
+        par.plain, par.p3 = p3.vs_plain, p3
+        assert par.ok, "vs rounded oracle: %s" % par
+        assert p3.bounded, "beyond the operand rounding: %s" % p3
     else:
         r = run_oracle(spikes, w32, **kw)
-        plain, tol = None, TOL_FP32
-    par = compare(r[0], r[1], g["spikes"], g["v_trace"], theta, tol)
-    par.plain = plain
-    assert par.ok, "vs oracle: %s" % par
+        tol = TOL_FP32
+        par = compare(r[0], r[1], g["spikes"], g["v_trace"], theta, tol)
+        par.plain, par.p3 = None, None
+        assert par.ok, "vs oracle: %s" % par
     if par.flips == 0 and g["v_final"] is not None:
         err = np.abs(g["v_final"] - r[2]) / np.maximum(np.abs(r[2]), theta)
         assert err.max() <= tol, "final V err %.3g" % err.max()

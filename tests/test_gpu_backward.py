@@ -111,21 +111,26 @@ def test_backward_bf16_layer_weight_gradient_on_the_matrix_cores(shape, mode, K,
     v = torch.zeros((B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
     vt = torch.empty((T_out, B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
     api.tac_conv_lif(desc, sp, api.tac_prepare_weights(desc, wd), torch.from_numpy(bias).to(DEV), v, None, vt)
-    got = api.tac_conv_lif_backward(desc, sp, wd, vt, torch.from_numpy(g_out).to(DEV), surrogate=api.TAC_SG_ARCTAN, alpha=2.0,
-                                    detach_reset=True)
     torch.cuda.synchronize()
-    # oracle: the bf16 forward pass (W and A_k rounded), then the backward pass with the rounded A_k in dW and the
-
+    # oracle: the bf16 forward pass (W and A_k rounded), then the backward pass with the rounded A_k in dW
     kw = dict(K=K, beta=float(np.float32(beta)), theta=theta, mode=ORACLE_MODE[mode])
     out, v_pre, _ = oracle.conv_lif(s, bf16_round_np(w).astype(np.float64), bias.astype(np.float64), round_a_bf16=True, **kw)
-    # a membrane within rounding of the threshold may spike on one side only, and every later membrane of that neuron then
-    # differs by theta: such a flip must be that close to the threshold, and the backward pass is then compared on the
-    # membranes the library recorded (the oracle's own otherwise)
+    # forward check, on its own: a membrane within rounding of the threshold may spike on one side only (every later
+    # membrane of that neuron then differs by theta); such a flip must be that close to the threshold, and everywhere
+    # before it the recorded membranes are the oracle's
     v_gpu = vt.cpu().numpy().astype(np.float64)
     flips = (v_gpu >= theta) != (v_pre >= theta)
     first = flips & (np.cumsum(flips, axis=0) == 1)
     assert flips.sum() <= 4 and (np.abs(v_pre[first] - theta) < 1e-3).all(), "spikes differ away from the threshold"
-    ref = oracle.conv_lif_backward(s, w.astype(np.float64), v_gpu if flips.any() else v_pre, g_out.astype(np.float64),
+    clean = np.cumsum(flips, axis=0) == 0
+    assert (np.abs(v_gpu - v_pre)[clean] <= 1e-3 * np.maximum(np.abs(v_pre[clean]), theta)).all()
+    # backward check: both sides start from the ORACLE's membranes (uploaded as the v_trace argument), so that nothing
+    # the library computed enters the oracle and a forward flip cannot leak into the gradient comparison
+    vt_ref = torch.from_numpy(v_pre.astype(np.float32)).to(DEV)
+    got = api.tac_conv_lif_backward(desc, sp, wd, vt_ref, torch.from_numpy(g_out).to(DEV), surrogate=api.TAC_SG_ARCTAN, alpha=2.0,
+                                    detach_reset=True)
+    torch.cuda.synchronize()
+    ref = oracle.conv_lif_backward(s, w.astype(np.float64), v_pre, g_out.astype(np.float64),
                                    surrogate=oracle.ARCTAN, alpha=2.0, detach_reset=True, round_a_bf16=True, **kw)
     assert out.sum() > 0
 

@@ -3,10 +3,11 @@ rate-coded and event-camera workloads), layer by layer against the CPU oracle.
 
 Multi-layer configurations are checked with teacher forcing: every GPU layer is fed the
 ORACLE's input spikes, because one tolerated near-threshold flip legitimately changes all later
-layers.  The free-running end-to-end difference is printed next to it.  Batch sizes are cut
-where the oracle would otherwise take minutes (samples are independent); the full-size
-roofline configuration is checked on sampled neurons in the launch configuration the
-benchmark times.
+layers.  The free-running end-to-end difference is printed next to it.  Every configuration runs
+on the library at its full batch size, i.e. in the launch geometry the benchmark times; where the
+oracle would otherwise take minutes it follows a few of the samples (samples are independent: all
+neurons of those samples are compared), and the full-size roofline configuration is checked on
+sampled neurons of samples spread over the batch.
 """
 import numpy as np
 import pytest
@@ -16,7 +17,7 @@ import oracle
 from paper_2603_13810_amd import api, synth
 
 from gpu_util import check_layer, run_gpu, ORACLE_MODE, bf16_round_np
-from parity_util import np_unpack, compare
+from parity_util import np_unpack, compare, compare3
 
 pytestmark = pytest.mark.gpu
 
@@ -31,10 +32,10 @@ def _rng(seed):
 @pytest.mark.parametrize("K", [2, 4, 8])
 def test_cfg2_two_layer_rate_coded(K, precision):
     wl = synth.WORKLOADS["cfg2"]
-    B = 32
+    B = wl.B                                            # 128, as timed
     s = wl.make_spikes(B=B)
     w1, w2 = wl.make_weights(0), wl.make_weights(1)
-    kw = dict(beta=wl.beta, theta=wl.theta, precision=precision, plain_stats=False)
+    kw = dict(beta=wl.beta, theta=wl.theta, precision=precision)
     # layer 1: TAC with group size K, 28x28, 1 -> 32
     # bf16: the short-contraction MFMA kernel; fp32: the vector-FMA kernel
     first = api.TAC_KERNEL_MFMA if precision == api.TAC_BF16 else api.TAC_KERNEL_DIRECT
@@ -58,70 +59,97 @@ def test_cfg2_two_layer_rate_coded(K, precision):
 @pytest.mark.parametrize("mode,K", [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 2), (api.TAC_PRESERVE, 2)])
 def test_cfg3_event_camera_layer(mode, K):
     wl = synth.WORKLOADS["cfg3"]
-    s = wl.make_spikes(B=4)
+    s = wl.make_spikes(B=wl.B)                         # 32, as timed
     assert 0.02 < s.mean() < 0.05                      # sparse background plus the moving patch
     w = wl.make_weights(0)
     par, g, r = check_layer(s, w, K=K, mode=mode, stride=2, beta=wl.beta, theta=wl.theta, precision=api.TAC_BF16,
-                            expect_kernel=api.TAC_KERNEL_MFMA)
+                            expect_kernel=api.TAC_KERNEL_MFMA, oracle_samples=[0, 5, 13, 22, 31])
     assert g["spikes"].shape[-2:] == (64, 64) and r[0].sum() > 0
-    print("cfg3", api.MODE_NAMES[mode], K, par, "| vs unrounded oracle:", par.plain)
+    print("cfg3", api.MODE_NAMES[mode], K, par)
 
 
 # ---------------------------------------------------------------- cfg4: five-layer event stack
+
+def _cfg4_stack(mode, K, gain, B, osel):
+    """cfg4 through the library at batch size B, the oracle following the samples `osel`: every layer is fed the
+    oracle's spikes of the layer before on those samples (teacher forcing) and the library's own on the others."""
+    wl = synth.WORKLOADS["cfg4"]
+    x_gpu = wl.make_spikes(B=B)
+    x_free = None
+    report, rates = [], []
+    for li, L in enumerate(wl.layers):
+        w = wl.make_weights(li) * np.float32(gain)
+        kw = dict(K=K, mode=mode, stride=L.stride, beta=wl.beta, theta=wl.theta, precision=api.TAC_BF16)
+        par, g, r = check_layer(x_gpu, w, oracle_samples=osel, **kw)
+        assert r[0].shape[0] == wl.T                                         # TAC-TP keeps T at every layer
+        free_all = run_gpu(x_free, w, trace=False, **kw)["spikes"] if li else g["spikes_all"]     # free running
+        gf = free_all[:, osel]
+        report.append("L%d[%s] %s rate=%.3f free-diff=%.1e" %
+                      (li + 1, "mfma" if g["kernel"] == api.TAC_KERNEL_MFMA else "direct", par, r[0].mean(),
+                       float((gf != r[0]).mean())))
+        rates.append(float(r[0].mean()))
+        x_free = free_all
+        x_gpu = g["spikes_all"].copy()
+        x_gpu[:, osel] = r[0]
+    return report, rates, r[0]
+
 
 @pytest.mark.parametrize("gain", [1.0, 3.0])
 @pytest.mark.parametrize("mode,K,calls", [(api.TAC_PER_STEP, 1, 80), (api.TAC_PRESERVE, 2, 40), (api.TAC_PRESERVE, 4, 20)])
 def test_cfg4_five_layer_stack(mode, K, calls, gain):
     # gain 1 is the configuration as stated (Kaiming weights: with beta = 0.5 and theta = 1 the
-    # deep layers then hardly fire); gain 3 scales the weights so that all five layers are active
+    # deep layers then hardly fire); gain 3 scales the weights so that all five layers are active.
+    # B = 16 as timed (layer 2 then runs 128-channel tiles, layers 3-5 the smaller ones).
     wl = synth.WORKLOADS["cfg4"]
-    x_ref = wl.make_spikes(B=1)
-    x_gpu = x_ref
     api.tac_reset_counters()
-    report = []
-    for li, L in enumerate(wl.layers):
-        w = wl.make_weights(li) * np.float32(gain)
-        kw = dict(K=K, mode=mode, stride=L.stride, beta=wl.beta, theta=wl.theta, precision=api.TAC_BF16)
-        par, g, r = check_layer(x_ref, w, plain_stats=False, **kw)          # teacher forced
-        assert r[0].shape[0] == wl.T                                         # TAC-TP keeps T at every layer
-        gf = run_gpu(x_gpu, w, trace=False, **kw) if li else g               # free running
-        report.append("L%d[%s] flips=%d rate=%.3f free-diff=%.1e" %
-                      (li + 1, "mfma" if g["kernel"] == api.TAC_KERNEL_MFMA else "direct", par.flips,
-                       r[0].mean(), float((gf["spikes"] != r[0]).mean())))
-        x_ref, x_gpu = r[0], gf["spikes"]
-    assert x_ref.shape == (wl.T, 1, 256, 16, 16)
+    report, rates, last = _cfg4_stack(mode, K, gain, wl.B, [0, 9])
+    assert last.shape == (wl.T, 2, 256, 16, 16)
     if gain > 1:
-        assert x_ref.mean() > 0.01                                           # the last layer does fire
+        assert min(rates) > 0.01                                             # every layer fires
     stages, lif = api.tac_get_counters()
     # teacher-forced and free-running calls both count (layer 1 is shared): 9 layer calls
     assert stages == calls * 9 // 5 and lif == 16 * 9
-    print("cfg4 gain %g" % gain, api.MODE_NAMES[mode], K, " | ".join(report))
+    print("cfg4 B=%d gain %g" % (wl.B, gain), api.MODE_NAMES[mode], K, "\n   " + "\n   ".join(report))
+
+
+def test_cfg4_single_sample_takes_the_small_tiles():
+    # B = 1: every large-kernel layer gets 64-channel (and half-height) tiles
+    report, rates, last = _cfg4_stack(api.TAC_PRESERVE, 2, 3.0, 1, [0])
+    assert last.shape[1:] == (1, 256, 16, 16) and min(rates) > 0.01
+    print("cfg4 B=1 gain 3 TAC_TP 2", "\n   " + "\n   ".join(report))
 
 
 # ---------------------------------------------------------------- cfg5: full size, sampled neurons
+
+CFG5_SAMPLES = (0, 37, 130, 255)      # the samples whose dense frames are kept for the oracle: both ends and the interior
+                                      # of the batch (the kernel's tile order spreads the samples over the 8 XCDs)
+
 
 @pytest.fixture(scope="module")
 def cfg5_inputs():
     wl = synth.WORKLOADS["cfg5"]
     dev = torch.device("cuda:0")
     out = {}
-    for rate in (0.1, 0.3):
+    for rate in (0.05, 0.1, 0.2, 0.3):
         packed = torch.empty((wl.T, wl.B, wl.C, wl.H, 2), dtype=torch.int32, device=dev)
-        dense = np.empty((wl.T, 2, wl.C, wl.H, wl.W), dtype=np.uint8)        # samples 0 and B-1, before packing
+        dense = np.empty((wl.T, len(CFG5_SAMPLES), wl.C, wl.H, wl.W), dtype=np.uint8)        # before packing
         for t in range(wl.T):
-            fr = synth.bernoulli_device(wl.seed + 100 * int(rate * 10) + t, wl.B, wl.C, wl.H, wl.W, rate, dev)
+            fr = synth.bernoulli_device(wl.seed + 100 * int(round(rate * 20)) + t, wl.B, wl.C, wl.H, wl.W, rate, dev)
             api.tac_pack_spikes(fr, packed[t])
-            dense[t, 0] = fr[0].cpu().numpy()
-            dense[t, 1] = fr[wl.B - 1].cpu().numpy()
+            dense[t] = fr[list(CFG5_SAMPLES)].cpu().numpy()
             del fr
         out[rate] = (packed, dense)
     torch.cuda.synchronize()
     return out
 
 
-@pytest.mark.parametrize("rate,mode,K", [(0.1, api.TAC_PER_STEP, 1), (0.1, api.TAC_COLLAPSE, 4), (0.1, api.TAC_PRESERVE, 2),
-                                         (0.3, api.TAC_COLLAPSE, 16), (0.3, api.TAC_PRESERVE, 8), (0.1, api.TAC_COLLAPSE, 2),
-                                         (0.3, api.TAC_COLLAPSE, 8)])
+CFG5_CASES = [(0.1, api.TAC_PER_STEP, 1), (0.1, api.TAC_COLLAPSE, 4), (0.1, api.TAC_PRESERVE, 2),
+              (0.3, api.TAC_COLLAPSE, 16), (0.3, api.TAC_PRESERVE, 8), (0.1, api.TAC_COLLAPSE, 2), (0.3, api.TAC_COLLAPSE, 8),
+              (0.05, api.TAC_COLLAPSE, 4), (0.05, api.TAC_PRESERVE, 4), (0.2, api.TAC_PRESERVE, 4), (0.2, api.TAC_PRESERVE, 16),
+              (0.2, api.TAC_COLLAPSE, 8), (0.05, api.TAC_PRESERVE, 16), (0.2, api.TAC_PER_STEP, 1)]
+
+
+@pytest.mark.parametrize("rate,mode,K", CFG5_CASES)
 def test_cfg5_full_size_sampled_neurons(cfg5_inputs, rate, mode, K):
     wl = synth.WORKLOADS["cfg5"]
     dev = torch.device("cuda:0")
@@ -137,24 +165,34 @@ def test_cfg5_full_size_sampled_neurons(cfg5_inputs, rate, mode, K):
     torch.cuda.synchronize()
     r = _rng(int(rate * 100) + 7 * K + mode)
     n = 4000
-    idx = np.stack([r.integers(0, 2, n), r.integers(0, 128, n), r.integers(0, 64, n), r.integers(0, 64, n)], 1).astype(np.int32)
+    ns = len(CFG5_SAMPLES)
+    idx = np.stack([r.integers(0, ns, n), r.integers(0, 128, n), r.integers(0, 64, n), r.integers(0, 64, n)], 1).astype(np.int32)
     idx[:64, 2] = r.choice([0, 63], 64); idx[64:128, 3] = r.choice([0, 63], 64)      # image borders too
-    ref = oracle.conv_lif_neurons(dense, bf16_round_np(w).astype(np.float64), idx=idx, K=K, beta=float(np.float32(wl.beta)),
-                                  theta=1.0, mode=ORACLE_MODE[mode], round_a_bf16=True, nthreads=16)
-    bsel = np.where(idx[:, 0] == 0, 0, wl.B - 1)
+    okw = dict(idx=idx, K=K, beta=float(np.float32(wl.beta)), theta=1.0, mode=ORACLE_MODE[mode], nthreads=oracle.max_threads())
+    ref = oracle.conv_lif_neurons(dense, bf16_round_np(w).astype(np.float64), round_a_bf16=True, **okw)
+    plain = oracle.conv_lif_neurons(dense, w.astype(np.float64), **okw)
+    bsel = np.asarray(CFG5_SAMPLES)[idx[:, 0]]
     sel = out[:, torch.from_numpy(bsel).to(dev), torch.from_numpy(idx[:, 1]).to(dev).long(),
               torch.from_numpy(idx[:, 2]).to(dev).long()].cpu().numpy()            # [T_out, n, 2] packed words
-    gpu_spk = (sel[np.arange(T_out)[:, None], np.arange(n)[None, :], idx[:, 3] // 32] >> (idx[:, 3] % 32)) & 1
-    par = compare(ref[0], ref[1], gpu_spk.astype(np.uint8), None, 1.0, 1e-3)
-    assert par.mismatches == 0, str(par)
+    gpu_spk = ((sel[np.arange(T_out)[:, None], np.arange(n)[None, :], idx[:, 3] // 32] >> (idx[:, 3] % 32)) & 1).astype(np.uint8)
+    p3 = compare3(plain[:2], ref[:2], gpu_spk, None, 1.0, 1e-3)
+    par = p3.vs_rounded
+    assert par.mismatches == 0, str(p3)
+    assert p3.extra_mismatches == 0, str(p3)          # no neuron leaves the plain oracle unless the rounded oracle does
     v_gpu = v[torch.from_numpy(bsel).to(dev), torch.from_numpy(idx[:, 1]).to(dev).long(),
               torch.from_numpy(idx[:, 2]).to(dev).long(), torch.from_numpy(idx[:, 3]).to(dev).long()].cpu().numpy()
     clean = (ref[0] == gpu_spk).all(axis=0)
     err = np.abs(v_gpu - ref[2]) / np.maximum(np.abs(ref[2]), 1.0)
     assert err[clean].max() < 1e-3
+    # final membrane against the plain oracle, where all three spike trains agree: what the stated 2e-2 measures
+    same = clean & (plain[0] == ref[0]).all(axis=0)
+    err_p = np.abs(v_gpu - plain[2]) / np.maximum(np.abs(plain[2]), 1.0)
+    err_q = np.abs(ref[2] - plain[2]) / np.maximum(np.abs(plain[2]), 1.0)
+    assert (err_p[same] <= err_q[same] + 1e-3).all()
     assert ref[0].mean() > 0.01
-    print("cfg5 rate %.1f %s K=%d: %s final-V err %.2e output rate %.3f" %
-          (rate, api.MODE_NAMES[mode], K, par, err[clean].max(), ref[0].mean()))
+    print("cfg5 rate %.2f %s K=%d: %s | final V vs rounded %.2e, vs plain %.2e (rounding alone %.2e), over 2e-2 vs plain: %d of %d | output rate %.3f" %
+          (rate, api.MODE_NAMES[mode], K, p3, err[clean].max(), err_p[same].max(), err_q[same].max(),
+           int((err_p[same] > 2e-2).sum()), int(same.sum()), ref[0].mean()))
 
 
 # ---------------------------------------------------------------- cfg5 backward: full size, sampled windows
@@ -183,7 +221,7 @@ def test_cfg5_full_size_backward_sampled_windows(cfg5_inputs, mode, K):
     del v
 
     r = _rng(5000 + 7 * K + mode)
-    cells = [(s, y, x) for s in (0, 1) for y in _CENTRES for x in _CENTRES]
+    cells = [(s, y, x) for s in (0, 2) for y in _CENTRES for x in _CENTRES]      # samples 0 and 130
     corners = [c for c in cells if c[1] in (0, 63) or c[2] in (0, 63)]
     pick = [corners[i] for i in r.choice(len(corners), 24, replace=False)]
     inner = [c for c in cells if c not in corners]
@@ -210,7 +248,7 @@ def test_cfg5_full_size_backward_sampled_windows(cfg5_inputs, mode, K):
     keep = np.ones(n, dtype=bool)
     v_err = 0.0
     for i, (s, y, x) in enumerate(pick):
-        b = 0 if s == 0 else wl.B - 1
+        b = CFG5_SAMPLES[s]
         for dy in range(1, 4):
             for dx in range(1, 4):
                 if not win[i, dy, dx]:
@@ -227,7 +265,7 @@ def test_cfg5_full_size_backward_sampled_windows(cfg5_inputs, mode, K):
     g_crop = g_crop.astype(np.float32)
     g_out = torch.zeros((T_out, wl.B, 128, 64, 64), dtype=torch.float32, device=dev)
     for i, (s, y, x) in enumerate(pick):
-        b = 0 if s == 0 else wl.B - 1
+        b = CFG5_SAMPLES[s]
         for dy in range(1, 4):
             for dx in range(1, 4):
                 if win[i, dy, dx]:
@@ -247,7 +285,7 @@ def test_cfg5_full_size_backward_sampled_windows(cfg5_inputs, mode, K):
     scale = np.abs(ref["g_in"]).max()
     e_s = 0.0
     for i, (s, y, x) in enumerate(pick):
-        b = 0 if s == 0 else wl.B - 1
+        b = CFG5_SAMPLES[s]
         y0, y1, x0, x1 = max(y - 2, 0), min(y + 3, 64), max(x - 2, 0), min(x + 3, 64)
         g = gi[:, b, :, y0:y1, x0:x1].cpu().numpy()
         rr = ref["g_in"][:, i, :, y0 - (y - 2):y1 - (y - 2), x0 - (x - 2):x1 - (x - 2)]

@@ -45,7 +45,7 @@ def test_shorter_last_group(shape, T, K, mode):
     v0 = (r.standard_normal((2, Cout, Ho, Wo)) * 0.3).astype(np.float32)
     api.tac_reset_counters()
     par, g, ref = check_layer(s, w, K=K, beta=0.9, theta=1.0, mode=mode, stride=stride, pool2=pool, precision=precision,
-                              bias=bias, v0=v0, expect_kernel=family, plain_stats=False)
+                              bias=bias, v0=v0, expect_kernel=family)
     n_groups = -(-T // min(K, T))
     assert g["spikes"].shape[0] == (n_groups if mode == api.TAC_COLLAPSE else T)
     assert api.tac_get_counters() == (n_groups, n_groups if mode == api.TAC_COLLAPSE else T)
@@ -61,7 +61,7 @@ def test_shorter_last_group_real_valued_frames(T, K, mode):
     w = synth.kaiming_normal(18, 48, 2) * np.float32(1.5)
     for precision, family in ((B16, MFMA), (F32, DIRECT)):
         par, g, ref = check_layer(x, w, K=K, beta=0.9, theta=1.0, mode=mode, precision=precision, expect_kernel=family,
-                                  plain_stats=False)
+                                  )
         assert ref[0][-1].sum() > 0
         print("shorter last group, real-valued frames T=%d K=%d" % (T, K), api.MODE_NAMES[mode], par)
 
