@@ -235,6 +235,20 @@ int tac_conv_lif_backward(const tac_layer_desc_t* desc, const tac_backward_desc_
                           const float* w_oihw, const float* v_trace, const float* grad_out, float* grad_y,
                           float* grad_w, float* grad_bias, float* grad_in, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving or training
+ * loops, harnesses that forbid hipMalloc): tac_conv_lif_backward without the grad_y argument.  dL/dY_k, which
+ * only passes from the LIF recurrence to the two convolution gradients, lives in a static device array of
+ * TAC_STATIC_SCRATCH_BYTES that the library holds on every GPU it runs on until the process ends; the call
+ * allocates and frees nothing.  All other arguments, the results and the errors are those of
+ * tac_conv_lif_backward.  TAC_ERR_UNSUPPORTED (text via tac_last_error) when
+ * ceil(T/K) * B * Cout * Ho * Wo * 4 bytes (T groups for per-step) exceed the array.  Every call on a GPU uses
+ * that GPU's one array: calls that overlap in time on one GPU (two streams, two host threads) race on it; calls
+ * on one stream are safe. */
+#define TAC_STATIC_SCRATCH_BYTES (64u << 20)
+int tac_conv_lif_backward_static(const tac_layer_desc_t* desc, const tac_backward_desc_t* bwd, const void* input,
+                                 const float* w_oihw, const float* v_trace, const float* grad_out, float* grad_w,
+                                 float* grad_bias, float* grad_in, void* stream);
+
 /* Backward pass through a stack run by tac_stack_forward with every layer's v_trace given: layer by
  * layer from the last to the first, the input-frame gradient of layer l being the output-spike
  * gradient of layer l-1 (their shapes agree by tac_stack_check: T of layer l = T_out of layer l-1,

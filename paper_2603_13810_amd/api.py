@@ -25,7 +25,7 @@ MODE_NAMES = {TAC_PER_STEP: "per_step", TAC_COLLAPSE: "TAC", TAC_PRESERVE: "TAC_
 
 EXPORTS = ("tac_out_shape", "tac_packed_bytes", "tac_select_kernel", "tac_prepared_weight_bytes",
            "tac_prepare_weights", "tac_conv_lif", "tac_pack_spikes", "tac_unpack_spikes", "tac_fold_batchnorm",
-           "tac_stack_check", "tac_stack_forward", "tac_conv_lif_backward", "tac_stack_backward", "tac_get_counters", "tac_reset_counters", "tac_status_string",
+           "tac_stack_check", "tac_stack_forward", "tac_conv_lif_backward", "tac_conv_lif_backward_static", "tac_stack_backward", "tac_get_counters", "tac_reset_counters", "tac_status_string",
            "tac_last_error")
 
 
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.tac_stack_forward.restype = ctypes.c_int
         L.tac_conv_lif_backward.argtypes = [dp, ctypes.POINTER(tac_backward_desc_t)] + [vp] * 9
         L.tac_conv_lif_backward.restype = ctypes.c_int
+        L.tac_conv_lif_backward_static.argtypes = [dp, ctypes.POINTER(tac_backward_desc_t)] + [vp] * 8
+        L.tac_conv_lif_backward_static.restype = ctypes.c_int
         L.tac_stack_backward.argtypes = [vp, vp, ctypes.POINTER(tac_backward_desc_t), ctypes.c_int32, vp, vp, vp]
         L.tac_stack_backward.restype = ctypes.c_int
         L.tac_reset_counters.argtypes = []
@@ -244,6 +246,22 @@ def tac_conv_lif_backward(desc, spikes_packed, w_oihw, v_trace, grad_out, *, sur
                                        _dev_ptr(grad_out, torch.float32, "grad_out"), _dev_ptr(grad_y), _dev_ptr(grad_w),
                                        _dev_ptr(grad_bias), _dev_ptr(grad_in), _stream(stream)))
     return dict(grad_y=grad_y, grad_w=grad_w, grad_bias=grad_bias, grad_in=grad_in)
+
+
+TAC_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def tac_conv_lif_backward_static(desc, spikes_packed, w_oihw, v_trace, grad_out, grad_w, grad_bias, grad_in, *,
+                                 surrogate=TAC_SG_FAST_SIGMOID, alpha=25.0, detach_reset=False, stream=None):
+    """tac_conv_lif_backward with dL/dY_k in the library's static scratch: the caller passes every output
+    (grad_w, grad_bias or None, grad_in or None) and nothing is allocated here or in the library."""
+    import torch
+    bwd = tac_backward_desc_t(surrogate=surrogate, detach_reset=int(bool(detach_reset)), alpha=alpha)
+    _check(lib().tac_conv_lif_backward_static(ctypes.byref(desc), ctypes.byref(bwd), _dev_ptr(spikes_packed, None, "spikes_packed"),
+                                              _dev_ptr(w_oihw, torch.float32, "w_oihw"), _dev_ptr(v_trace, torch.float32, "v_trace"),
+                                              _dev_ptr(grad_out, torch.float32, "grad_out"), _dev_ptr(grad_w, torch.float32, "grad_w"),
+                                              _dev_ptr(grad_bias, torch.float32, "grad_bias"), _dev_ptr(grad_in, torch.float32, "grad_in"),
+                                              _stream(stream)))
 
 
 class tac_stack_layer_t(ctypes.Structure):

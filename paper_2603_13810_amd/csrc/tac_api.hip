@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "tac_internal.h"
 
@@ -13,6 +14,16 @@ namespace {
 
 thread_local char g_last_error[512] = "";
 std::atomic<uint64_t> g_conv_stages{0}, g_lif_steps{0};
+
+// Scratch of tac_conv_lif_backward_static: the dL/dY_k values that pass from the LIF recurrence to the two
+// convolution gradients.  Every GPU the library runs on holds its own copy of this array until the
+// process ends; host code reaches it only through the address hipGetSymbolAddress returns for the
+// current device (kept per device below), never through the array's name.
+constexpr size_t kScratchFloats = TAC_STATIC_SCRATCH_BYTES / sizeof(float);
+static __device__ __align__(256) float scratch[kScratchFloats];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};
 
 int hip_fail(hipError_t e, const char* where) {
   std::snprintf(g_last_error, sizeof(g_last_error), "%s: %s", where, hipGetErrorString(e));
@@ -273,6 +284,40 @@ int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* 
   p.decay_last = (float)pw;
   hipError_t e = tac::backward_launch(p, (hipStream_t)stream);
   return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_conv_lif_backward");
+}
+
+int tac_conv_lif_backward_static(const tac_layer_desc_t* d, const tac_backward_desc_t* bwd, const void* input,
+                                 const float* w_oihw, const float* v_trace, const float* grad_out, float* grad_w,
+                                 float* grad_bias, float* grad_in, void* stream) {
+  tac_layer_desc_t eff;
+  int rc = effective(d, &eff);
+  if (rc) return rc;
+  const int Ho = (eff.H + 2 - 3) / eff.stride + 1, Wo = (eff.W + 2 - 3) / eff.stride + 1;
+  const size_t need = (size_t)((eff.T + eff.K - 1) / eff.K) * eff.B * eff.Cout * Ho * Wo;    // floats of dL/dY_k
+  if (need > kScratchFloats) {
+    std::snprintf(g_last_error, sizeof(g_last_error),
+                  "tac_conv_lif_backward_static: dL/dY_k needs %zu bytes, the static scratch holds %zu", need * sizeof(float),
+                  (size_t)TAC_STATIC_SCRATCH_BYTES);
+    return TAC_ERR_UNSUPPORTED;
+  }
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "tac_conv_lif_backward_static (hipGetDevice)");
+  if (dev < 0 || dev >= kMaxDevices) return TAC_ERR_UNSUPPORTED;
+  float* ptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+      void* sym = nullptr;
+      e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));       // this device's copy of the array
+      if (e != hipSuccess || !sym) return hip_fail(e, "tac_conv_lif_backward_static (hipGetSymbolAddress)");
+      g_scratch_ptr[dev] = static_cast<float*>(sym);
+    }
+    ptr = g_scratch_ptr[dev];
+  }
+  // every element of dL/dY_k is written by the LIF recurrence before the convolution gradients read it:
+  // nothing has to start at zero
+  return tac_conv_lif_backward(d, bwd, input, w_oihw, v_trace, grad_out, ptr, grad_w, grad_bias, grad_in, stream);
 }
 
 int tac_stack_backward(const tac_stack_layer_t* layers, const tac_stack_grads_t* grads, const tac_backward_desc_t* bwd,
