@@ -146,9 +146,6 @@ int tac_conv_lif(const tac_layer_desc_t* desc, const void* input, const void* w_
                  const float* bias, float* v_inout, uint32_t* out_spikes_packed, float* v_trace,
                  void* stream);
 
-/* Dense 0/1 bytes <-> packed words, `rows` rows of W pixels each (rows = T*B*C*H).
- *   dense01  DEVICE uint8 [rows][W]; any non-zero byte packs as 1
- *   packed   DEVICE uint32 [rows][ceil(W/32)] */
 /* Inference-time batch normalisation after the convolution (the Conv -> BN -> LIF blocks of
  * Sec. 5.1) folded into the layer's weights and bias:
  *   w_out[co] = w[co] * gamma[co] / sqrt(var[co] + eps)
@@ -162,6 +159,24 @@ int tac_conv_lif(const tac_layer_desc_t* desc, const void* input, const void* w_
 int tac_fold_batchnorm(const float* w_oihw, const float* bias, const float* gamma, const float* beta_bn,
                        const float* mean, const float* var, float eps, int32_t Cout, int32_t per_cout,
                        float* w_out, float* bias_out, void* stream);
+
+/* The aggregation stage alone, for measuring it (Eq. 2; Sec. 6 names the fusion of aggregation and
+ * convolution as the step after this one): for every group of K frames the decay-weighted aggregate A_k of the
+ * packed input is formed tile by tile exactly as tac_conv_lif forms it on the matrix-core kernel (same spike
+ * loading, same staging, same bf16 tiles in LDS; never written to HBM), and nothing else runs: no weights, no
+ * convolution, no LIF.  So that the work is observable and checkable, every workgroup adds up the 32-bit words
+ * of the A tiles it formed (a word = the bf16 patterns of an even input channel, low half, and of the next odd
+ * one, high half, of one pixel; values in the kernel's fixed-point scale 2^23 * A_k), over the input rows
+ * that belong to its tile, and writes the sum:
+ *   input      DEVICE, read-only, packed uint32 [T][B][Cin][H][ceil(W/32)]
+ *   tile_sums  DEVICE, written, uint64 [tac_aggregate_tiles(desc)], 8-byte aligned.  Their total is
+ *              sum over (group, sample, cin, y, x) of pattern16(bf16(2^23 A_k)) * (cin odd ? 65536 : 1),
+ *              times Cout / 128 (every tile of 128 output channels forms the aggregates again), exactly.
+ * Supported where the layer would run on the large matrix-core kernel with stride 1, packed-bit input without
+ * a pool and K in {1, 2, 4, 8, 16} dividing T; otherwise TAC_ERR_UNSUPPORTED (tac_aggregate_tiles returns 0).
+ * Enqueued on `stream`; nothing is allocated or synchronised. */
+size_t tac_aggregate_tiles(const tac_layer_desc_t* desc);
+int tac_aggregate_sums(const tac_layer_desc_t* desc, const void* input, uint64_t* tile_sums, void* stream);
 
 /* A stack of conv-LIF layers, each with its own mode and group size (App. B: TAC layers cascade,
  * T -> T / K_1 -> T / (K_1 K_2) ...; TAC-TP layers keep T; Sec. 5.1's networks mix both with
@@ -272,6 +287,10 @@ typedef struct tac_stack_grads {
 int tac_stack_backward(const tac_stack_layer_t* layers, const tac_stack_grads_t* grads, const tac_backward_desc_t* bwd,
                        int32_t n_layers, const void* input, const float* grad_out_last, void* stream);
 
+/* Dense 0/1 bytes <-> packed words, `rows` rows of W pixels each (rows = T*B*C*H).
+ *   dense01  DEVICE uint8 [rows][W]; any non-zero byte packs as 1
+ *   packed   DEVICE uint32 [rows][ceil(W/32)]
+ * Errors: TAC_ERR_NULL, TAC_ERR_BAD_SHAPE (rows or W < 1), TAC_ERR_ALIGN, TAC_ERR_HIP. */
 int tac_pack_spikes(const uint8_t* dense01, uint32_t* packed, int64_t rows, int32_t W, void* stream);
 int tac_unpack_spikes(const uint32_t* packed, uint8_t* dense01, int64_t rows, int32_t W, void* stream);
 

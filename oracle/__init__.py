@@ -63,6 +63,8 @@ def _load():
         lib.oracle_round_bf16.restype = ctypes.c_double
         lib.oracle_decay_weights.argtypes = [ctypes.c_double, ctypes.c_int, vp]
         lib.oracle_decay_weights.restype = None
+        lib.oracle_aggregate.argtypes = [dp, vp, ctypes.c_int, vp, vp, vp]
+        lib.oracle_aggregate.restype = None
         lib.oracle_avgpool2.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int]
         lib.oracle_avgpool2.restype = None
         lib.oracle_maxpool2.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int]
@@ -96,6 +98,19 @@ def decay_weights(beta: float, K: int) -> np.ndarray:
     w = np.zeros(K, dtype=np.float64)
     _load().oracle_decay_weights(float(beta), int(K), _ptr(w))
     return w
+
+
+def aggregate(spikes, k: int, *, K: int, beta: float, round_a_bf16: bool = False) -> np.ndarray:
+    """A_k = sum_j beta^(Kg-1-j) S_{kK+j} (Eq. 2) of group k of spikes uint8 [T,B,Cin,H,W]; float64 [B,Cin,H,W]."""
+    spikes = np.ascontiguousarray(spikes, dtype=np.uint8)
+    T, B, Cin, H, W = spikes.shape
+    d = _Desc(T=T, B=B, Cin=Cin, H=H, W=W, Cout=1, kh=3, kw=3, stride=1, pad=1, K=K, pool2=0,
+              round_a_bf16=int(bool(round_a_bf16)), nthreads=1, dense=0, beta=float(beta), theta=1.0)
+    A = np.zeros((B, Cin, H, W), dtype=np.float64)
+    X = np.zeros_like(A)
+    tmp = np.zeros_like(A)
+    _load().oracle_aggregate(ctypes.byref(d), _ptr(spikes), int(k), _ptr(A), _ptr(X), _ptr(tmp))
+    return A
 
 
 def avgpool2(x: np.ndarray) -> np.ndarray:

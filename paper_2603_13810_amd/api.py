@@ -24,7 +24,7 @@ TAC_MAX_K = 32
 MODE_NAMES = {TAC_PER_STEP: "per_step", TAC_COLLAPSE: "TAC", TAC_PRESERVE: "TAC_TP"}
 
 EXPORTS = ("tac_out_shape", "tac_packed_bytes", "tac_select_kernel", "tac_prepared_weight_bytes",
-           "tac_prepare_weights", "tac_conv_lif", "tac_pack_spikes", "tac_unpack_spikes", "tac_fold_batchnorm",
+           "tac_prepare_weights", "tac_conv_lif", "tac_aggregate_tiles", "tac_aggregate_sums", "tac_pack_spikes", "tac_unpack_spikes", "tac_fold_batchnorm",
            "tac_stack_check", "tac_stack_forward", "tac_conv_lif_backward", "tac_conv_lif_backward_static", "tac_stack_backward", "tac_get_counters", "tac_reset_counters", "tac_status_string",
            "tac_last_error")
 
@@ -66,6 +66,10 @@ def lib() -> ctypes.CDLL:
         L.tac_prepare_weights.restype = ctypes.c_int
         L.tac_conv_lif.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
         L.tac_conv_lif.restype = ctypes.c_int
+        L.tac_aggregate_tiles.argtypes = [dp]
+        L.tac_aggregate_tiles.restype = ctypes.c_size_t
+        L.tac_aggregate_sums.argtypes = [dp, vp, vp, vp]
+        L.tac_aggregate_sums.restype = ctypes.c_int
         L.tac_pack_spikes.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp]
         L.tac_pack_spikes.restype = ctypes.c_int
         L.tac_unpack_spikes.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp]
@@ -209,6 +213,27 @@ def tac_conv_lif(desc, spikes_packed, w_prepared, bias=None, v_inout=None, out_s
                               _dev_ptr(out_spikes_packed, None, "out_spikes_packed"),
                               _dev_ptr(v_trace, torch.float32, "v_trace"), _stream(stream)))
     return out_spikes_packed
+
+
+def tac_aggregate_tiles(desc) -> int:
+    return int(lib().tac_aggregate_tiles(ctypes.byref(desc)))
+
+
+def tac_aggregate_sums(desc, spikes_packed, tile_sums=None, stream=None):
+    """The aggregation stage alone (see include/tac.h).  Returns tile_sums (int64 device tensor, one per workgroup)."""
+    import torch
+    n = tac_aggregate_tiles(desc)
+    if n == 0:
+        _check(TAC_ERR_UNSUPPORTED)
+    if spikes_packed.numel() * spikes_packed.element_size() != tac_packed_bytes(desc.T, desc.B, desc.Cin, desc.H, desc.W):
+        raise ValueError("spikes_packed does not match the description")
+    if tile_sums is None:
+        tile_sums = torch.empty((n,), dtype=torch.int64, device=spikes_packed.device)
+    elif tile_sums.numel() != n or tile_sums.element_size() != 8:
+        raise ValueError("tile_sums must hold %d 64-bit words" % n)
+    _check(lib().tac_aggregate_sums(ctypes.byref(desc), _dev_ptr(spikes_packed, None, "spikes_packed"),
+                                    _dev_ptr(tile_sums, None, "tile_sums"), _stream(stream)))
+    return tile_sums
 
 
 TAC_SG_FAST_SIGMOID, TAC_SG_ARCTAN = 0, 1

@@ -203,6 +203,32 @@ int tac_conv_lif(const tac_layer_desc_t* d, const void* input, const void* w_pre
   return TAC_OK;
 }
 
+size_t tac_aggregate_tiles(const tac_layer_desc_t* d) {
+  tac_layer_desc_t eff;
+  if (effective(d, &eff) || !tac::mfma_aggregate_supported(eff)) return 0;
+  return tac::mfma_aggregate_tiles(eff);
+}
+
+int tac_aggregate_sums(const tac_layer_desc_t* d, const void* input, uint64_t* tile_sums, void* stream) {
+  tac_layer_desc_t eff;
+  int rc = effective(d, &eff);
+  if (rc) return rc;
+  if (!input || !tile_sums) return TAC_ERR_NULL;
+  if (((uintptr_t)input & 3u) || ((uintptr_t)tile_sums & 7u)) return TAC_ERR_ALIGN;
+  if (!tac::mfma_aggregate_supported(eff)) return TAC_ERR_UNSUPPORTED;
+  tac::LayerParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.spikes = static_cast<const uint32_t*>(input);
+  p.T = eff.T; p.B = eff.B; p.Cin = eff.Cin; p.H = eff.H; p.W = eff.W; p.Cout = eff.Cout; p.stride = 1;
+  p.Ho = eff.H; p.Wo = eff.W; p.Hs = eff.H; p.Wwi = (eff.W + 31) / 32; p.Wwo = p.Wwi;
+  p.K = eff.K; p.G = eff.T / eff.K; p.n_lif = 1; p.mfma_kind = 1; p.bf16 = 1; p.theta = eff.theta;
+  double pw = 1.0;
+  for (int j = p.K - 1; j >= 0; --j) { p.wj[j] = (float)pw; p.wjd[j] = pw; pw *= (double)eff.beta; }
+  p.decay = eff.beta;
+  hipError_t e = tac::mfma_aggregate_launch(p, tile_sums, (hipStream_t)stream);
+  return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_aggregate_sums");
+}
+
 int tac_stack_check(const tac_stack_layer_t* layers, int32_t n_layers, int32_t* bad_layer) {
   if (!layers) return TAC_ERR_NULL;
   if (n_layers < 1) return TAC_ERR_BAD_SHAPE;

@@ -6,6 +6,7 @@
 //   lif_backward_kernel  dL/dY_k from dL/ds and the membranes the forward pass recorded
 //   wgrad_kernel         dW, dbias: A_k rebuilt from the packed frames, strip by strip, in LDS
 //   dgrad_kernel         dL/dS_{kK+j} = beta^(Kg-1-j) * (dY_k convolved back through W)
+#include <mutex>
 #include "tac_internal.h"
 
 namespace tac {
@@ -290,12 +291,12 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
   if (split > 65535) split = 65535;
   if (split < 1) split = 1;
   const size_t lds = backward_wgrad_lds_bytes(p.W, p.stride);
-  static bool attr_done = false;
-  if (!attr_done) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static std::once_flag once;               // one attribute call, also with several host threads
+  static hipError_t attr = hipSuccess;
+  std::call_once(once, [] {
+    attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+  });
+  if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL(wgrad_kernel, dim3(co_tiles, p.Cin, (unsigned)split), dim3(kThreads), lds, s, p, n_strips, (int)split);
   e = hipGetLastError();
   if (e != hipSuccess) return e;

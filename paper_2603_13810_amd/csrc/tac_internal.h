@@ -42,6 +42,10 @@ bool mfma_supported(const tac_layer_desc_t& d);
 size_t mfma_weight_bytes(const tac_layer_desc_t& d);
 hipError_t mfma_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s);
 hipError_t mfma_launch(const LayerParams& p, hipStream_t s);
+// the aggregation stage of the large MFMA kernel alone: one 64-bit sum of A-tile words per workgroup
+bool mfma_aggregate_supported(const tac_layer_desc_t& d);
+size_t mfma_aggregate_tiles(const tac_layer_desc_t& d);
+hipError_t mfma_aggregate_launch(const LayerParams& p, uint64_t* tile_sums, hipStream_t s);
 // its member for the shapes in between (Cin a multiple of 8 up to 64, widths up to 128, any pool on load)
 bool mfma_mid_supported(const tac_layer_desc_t& d);
 size_t mfma_mid_weight_bytes(const tac_layer_desc_t& d);

@@ -41,6 +41,8 @@
 // integer below 2^28, converted once to fp32 and rounded to bf16, and the prepared weights carry
 // the factor 2^-23 (a power of two, so the bf16 rounding of both operands is unchanged and the
 // products are the same).
+#include <mutex>
+
 #include "tac_mfma_common.h"
 
 namespace tac {
@@ -68,6 +70,7 @@ __host__ __device__ constexpr int lut_bytes(int K) { return K == 16 ? 2048 : (K 
 template <int WIN, int S, int NP = 2>
 struct Geo {
   static constexpr int kWo = WIN / S;                        // output width: 64, 32 or 16
+  static constexpr int kS = S;
   static constexpr int kNP = NP;
   static_assert(NP == 2 || (NP == 1 && kWo <= 32), "half tiles: whole rows per wave");
   static constexpr int kWaveRows = NP * 32 / kWo;            // output rows per wave
@@ -335,18 +338,22 @@ __device__ __forceinline__ void lookup(StepRegs<KT>& sr, const uint8_t* lut, int
   }
 }
 
+// `sum` (aggregation-only kernel): the two words just written are added to it when the lane's pixel lies in an
+// input row that belongs to this tile alone (local rows 1 .. kTileRows * S; the rows above and below are the
+// neighbouring tiles' as well), so that the sums of all tiles count every element of every A_k once.
 template <class G>
-__device__ __forceinline__ void a_write_packed(uint8_t* a_next, int lane, int q, int step, u32x2 pk) {
+__device__ __forceinline__ void a_write_packed(uint8_t* a_next, int lane, int q, int step, u32x2 pk, uint64_t* sum = nullptr) {
   u32x2* dst = reinterpret_cast<u32x2*>(a_next + (q >> 1) * G::kAHalf + a_write_off<G>(lane, step) + (q & 1) * 8);
-  if (G::kOddTail && step == G::kSteps - 1) {
-    if (lane < 32) *dst = pk;
-  } else {
-    *dst = pk;
+  const bool active = !(G::kOddTail && step == G::kSteps - 1) || lane < 32;
+  if (active) *dst = pk;
+  if (sum) {
+    const int row = G::kWW == 2 ? step : step * 2 + (lane >> 5);
+    if (active && row >= 1 && row <= G::kTileRows * G::kS) *sum += (uint64_t)pk[0] + (uint64_t)pk[1];
   }
 }
 
 template <class G, int KT>
-__device__ __forceinline__ void write_a(const StepRegs<KT>& sr, uint8_t* a_next, int lane, int q, int step) {
+__device__ __forceinline__ void write_a(const StepRegs<KT>& sr, uint8_t* a_next, int lane, int q, int step, uint64_t* sum = nullptr) {
   u32x2 pk;
   if constexpr (KT == 1) {
     // one frame: the aggregate is the bit itself, 2^23 in the fixed-point scale, whose bf16
@@ -366,19 +373,19 @@ __device__ __forceinline__ void write_a(const StepRegs<KT>& sr, uint8_t* a_next,
     pk[0] = (sr.lv[1] << 16) | sr.lv[0];
     pk[1] = (sr.lv[3] << 16) | sr.lv[2];
   }
-  a_write_packed<G>(a_next, lane, q, step, pk);
+  a_write_packed<G>(a_next, lane, q, step, pk, sum);
 }
 
 // Unpipelined form (prologue, and the run-time-K kernel, which reads the frames' words as
 // they are and adds the weights bit by bit).
 template <class G, int KT>
 __device__ __forceinline__ void expand_step(const MfmaParams& p, const uint8_t* words_buf, const uint8_t* lut,
-                                            uint8_t* a_next, int K, int lane, int q, int step) {
+                                            uint8_t* a_next, int K, int lane, int q, int step, uint64_t* sum = nullptr) {
   if constexpr (KT > 0) {
     StepRegs<KT> sr;
     read_words<G, KT>(sr, words_buf, lane, q, step);
     lookup<KT>(sr, lut, lane);
-    write_a<G, KT>(sr, a_next, lane, q, step);
+    write_a<G, KT>(sr, a_next, lane, q, step, sum);
   } else {
     const uint32_t* src = reinterpret_cast<const uint32_t*>(words_buf) + (lane_word<G>(lane, step) * (K * kChunk + G::stage_pad(K)) + q * 4);
     const uint32_t bitpos = lane & 31;
@@ -405,7 +412,10 @@ __device__ __forceinline__ void lds_barrier() {
 // stores and their addresses do not weigh on the register allocation of the plain one).
 // MP: the input buffer holds the unpooled spikes of the layer before and a 2 x 2 max pool is
 // applied while staging (the staged words are pooled bits; everything after them is unchanged).
-template <int KT, int WIN, int S, bool TRACE, bool MP, int MC, int NP>
+// AGG: the aggregation stage alone (a measurement aid): spike loading, staging and the A tiles of every chunk are
+// formed exactly as in the layer, the weight copies, the MFMAs and the LIF steps are left out, and the workgroup
+// writes one 64-bit sum of the A-tile words it formed (see a_write_packed) to p.out instead of spikes.
+template <int KT, int WIN, int S, bool TRACE, bool MP, int MC, int NP, bool AGG = false>
 __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   using G = Geo<WIN, S, NP>;
   // MC = 32-channel blocks per workgroup and wave: 4 (128 output channels), or 2 (64) for layers
@@ -471,13 +481,15 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   // membrane, MFMA result layout: register r of tile (mc, np), lane -> cout = 32 mc + 8 (r/4) + 4 h + r%4
   float V[MC][NP][16];
   f32x16 acc[MC][NP];
+  uint64_t agg_sum = 0;
+  uint64_t* const agg = AGG ? &agg_sum : nullptr;
 #pragma unroll
   for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
     for (int np = 0; np < NP; ++np)
 #pragma unroll
       for (int r = 0; r < 16; ++r) V[mc][np][r] = 0.f;
-  if (p.v_inout) {
+  if (!AGG && p.v_inout) {
     const LaneGeom lg = lane_geom<G>(lane, oy_wave, Ho, plane, p.theta);
     const char* vb = reinterpret_cast<const char*>(p.v_inout + v_wave);
     static_for<0, NP>([&](auto np_) {
@@ -524,7 +536,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   const uint32_t w_lane_off = (MC == 4 ? (uint32_t)(wave * (kWBlocks * 1024)) : 0u) + (uint32_t)lane * 16u;
   const uint32_t w_half_off = (uint32_t)(co_tile & 1) * 2048u;       // MC == 2: which half of the 128-channel tile
   auto weights_to_lds = [&](const uint8_t* src, uint8_t* w_dst, auto i0_, auto i1_) {
-    static_for<decltype(i0_)::value, decltype(i1_)::value>([&](auto i_) {
+    if constexpr (!AGG) static_for<decltype(i0_)::value, decltype(i1_)::value>([&](auto i_) {
       constexpr int i = decltype(i_)::value;
       if constexpr (MC == 4) {
         __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (i / 4) * 4096 + w_lane_off),
@@ -574,7 +586,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     stage_load<KMAX, NG, MP, G::kWW>(wd, plan, cur.spk, fstride, K);
     stage_store<KT, KMAX, NG, MP>(wd, plan, words0 + words_bytes, K);
     __syncthreads();
-    for (int st = 0; st < G::kSteps; ++st) expand_step<G, KT>(p, words0, lut, lds + G::kLdsA, K, lane, q, st);
+    for (int st = 0; st < G::kSteps; ++st) expand_step<G, KT>(p, words0, lut, lds + G::kLdsA, K, lane, q, st, agg);
     advance(cur);                               // chunk 2
     w_n2 = cur.w;
     spk_n2 = cur.spk;
@@ -590,6 +602,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   // chunk starts by moving to slot 0
   bf16x8 wf[2][MC], af[2][NP];
   auto fetch = [&](const uint8_t* a_buf, const uint8_t* w_buf, int tap, int slot) {
+    if constexpr (AGG) return;
     const int ky = tap / 3, kx = tap % 3;
     const int tap_off = (ky * G::kXP + G::col(kx)) * 16;            // col(ox S + kx) = col(ox S) + col(kx)
 #pragma unroll
@@ -648,26 +661,30 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
         }
         fetch(a_cur, w_cur, tap + 1, slot ^ 1);
       }
+      if constexpr (!AGG) {
 #pragma unroll
-      for (int mc = 0; mc < MC; ++mc)
+        for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
-        for (int np = 0; np < NP; ++np)
-          acc[mc][np] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][mc], af[slot][np], acc[mc][np], 0, 0, 0);
+          for (int np = 0; np < NP; ++np)
+            acc[mc][np] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][mc], af[slot][np], acc[mc][np], 0, 0, 0);
+      }
+      // the tile built during the last chunk repeats that chunk (nothing follows it) and is not counted
+      uint64_t* const agg_s = (AGG && s + 1 < total) ? agg : nullptr;
       // loader: pipeline slot i writes step i-2, looks up step i-1 and reads the words of step i
       // (one frame: no table, the write follows the read by one slot)
 #pragma unroll
       for (int i = tap * G::kSlotsPerTap; i < (tap + 1) * G::kSlotsPerTap; ++i) {
         if constexpr (KT > 0) {
           constexpr int kD = KT == 1 ? 1 : 2;
-          if (i >= kD && i - kD < G::kSteps) write_a<G, KT>(sr, a_next, lane, q, i - kD);
+          if (i >= kD && i - kD < G::kSteps) write_a<G, KT>(sr, a_next, lane, q, i - kD, agg_s);
           if (kD == 2 && i >= 1 && i - 1 < G::kSteps) lookup<KT>(sr, lut, lane);
           if (i < G::kSteps) read_words<G, KT>(sr, words_next, lane, q, i);
         } else {
-          if (i < G::kSteps) expand_step<G, KT>(p, words_next, lut, a_next, K, lane, q, i);
+          if (i < G::kSteps) expand_step<G, KT>(p, words_next, lut, a_next, K, lane, q, i, agg_s);
         }
       }
       if (tap == 7) stage_store<KT, KMAX, NG, MP>(wd, plan, words_nn, K);
-      if constexpr (KT > 0) {
+      if constexpr (KT > 0 && !AGG) {
         // issue order inside the tap: one MFMA, then a few LDS reads and vector ops that run
         // while the matrix pipe is busy, eight times over
         constexpr int kValuPerMfma = (KT == 16 ? 4 : 2) * G::kSlotsPerTap;
@@ -726,6 +743,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
         for (int r = 0; r < 16; ++r) acc[mc][np][r] = 0.f;
 
     for (int c = 0; c < NC; ++c, ++s) chunk_iteration(s);
+    if constexpr (AGG) continue;
 
     // ---- LIF epilogue on Y_k = acc + bias
     const float* bias_lds = reinterpret_cast<const float*>(lds + kLdsBias);
@@ -765,6 +783,16 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
   }
   __syncthreads();                            // drains the last direct-to-LDS loads before the waves end
 
+  if constexpr (AGG) {
+    // sum over the workgroup: lanes by shuffles, the four waves through LDS (everything else in LDS is dead now)
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) agg_sum += (uint64_t)__shfl_xor((unsigned long long)agg_sum, o, 64);
+    uint64_t* red = reinterpret_cast<uint64_t*>(lds);
+    if (lane == 0) red[wave] = agg_sum;
+    __syncthreads();
+    if (tid == 0) reinterpret_cast<uint64_t*>(p.out)[tile] = red[0] + red[1] + red[2] + red[3];
+    return;
+  }
   if (p.v_inout) {
     size_t plane_l = plane;                   // opaque copy: the 128 addresses below are formed here,
     asm volatile("" : "+s"(plane_l));         // not before the time loop (they would not fit in registers)
@@ -810,13 +838,13 @@ hipError_t launch_tile(const MfmaParams& mp, hipStream_t s) {
   using G = Geo<WIN, S, NP>;
   constexpr int lds = G::lds_bytes(KT > 0 ? KT : TAC_MAX_K, MC);
   static_assert(lds <= kLdsLimit, "tile does not fit the LDS");
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<KT, WIN, S, TRACE, MP, MC, NP>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static std::once_flag once;               // one attribute call per kernel, also with several host threads
+  static hipError_t attr = hipSuccess;
+  std::call_once(once, [] {
+    attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<KT, WIN, S, TRACE, MP, MC, NP>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  });
+  if (attr != hipSuccess) return attr;
   MfmaParams q = mp;
   q.row_tiles = (mp.Ho + G::kTileRows - 1) / G::kTileRows;
   const dim3 grid(q.row_tiles * (mp.Cout / (MC * 32)) * mp.B);
@@ -826,9 +854,21 @@ hipError_t launch_tile(const MfmaParams& mp, hipStream_t s) {
 
 // 64-channel tiles when 128-channel tiles would give fewer workgroups than the chip has compute
 // units (small batches, deep layers); not combined with the max pool on load.
-constexpr int kComputeUnits = 256;
+// Compute units of the current device, asked once (256 on an MI355X; that figure also where the query fails).
+inline int compute_units() {
+  static std::once_flag once;
+  static int n = 256;
+  std::call_once(once, [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n = v;
+  });
+  return n;
+}
 template <int KT, int WIN, int S, bool TRACE, bool MP>
 hipError_t launch_traced(const MfmaParams& mp, hipStream_t s) {
+  const int kComputeUnits = compute_units();
   if constexpr (!MP) {
     const int row_tiles = (mp.Ho + Geo<WIN, S>::kTileRows - 1) / Geo<WIN, S>::kTileRows;
     if ((long long)row_tiles * (mp.Cout / kCoutTile) * mp.B < kComputeUnits) {
@@ -921,10 +961,7 @@ hipError_t mfma_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_
   return hipGetLastError();
 }
 
-hipError_t mfma_launch(const LayerParams& p, hipStream_t s) {
-  if (p.mfma_kind == 2) return mfma_small_launch(p, s);
-  if (p.mfma_kind == 3) return mfma_mid_launch(p, s);
-  MfmaParams mp;
+static void fill_params(MfmaParams& mp, const LayerParams& p) {
   mp.spikes = p.spikes; mp.w = static_cast<const uint8_t*>(p.w); mp.bias = p.bias; mp.v_inout = p.v_inout;
   mp.out = p.out; mp.v_trace = p.v_trace;
   mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.W = p.W; mp.Ho = p.Ho; mp.Wo = p.Wo; mp.Cout = p.Cout; mp.stride = p.stride;
@@ -936,11 +973,69 @@ hipError_t mfma_launch(const LayerParams& p, hipStream_t s) {
     const double q = (double)p.wj[j] * (double)(1u << kFixShift);
     mp.wq[j] = j < p.K ? (uint32_t)(q + 0.5) : 0u;
   }
+}
+
+hipError_t mfma_launch(const LayerParams& p, hipStream_t s) {
+  if (p.mfma_kind == 2) return mfma_small_launch(p, s);
+  if (p.mfma_kind == 3) return mfma_mid_launch(p, s);
+  MfmaParams mp;
+  fill_params(mp, p);
   if (p.W == 64 && p.stride == 1) return launch_geo<64, 1>(mp, s);
   if (p.W == 32 && p.stride == 1) return launch_geo<32, 1>(mp, s);
   if (p.W == 64 && p.stride == 2) return launch_geo<64, 2>(mp, s);
   if (p.W == 32 && p.stride == 2) return launch_geo<32, 2>(mp, s);
   return hipErrorInvalidValue;
+}
+
+// ---- the aggregation stage alone (measurement aid) ----------------------------------------
+bool mfma_aggregate_supported(const tac_layer_desc_t& d) {
+  const int K = d.mode == TAC_PER_STEP ? 1 : d.K;
+  return large_supported(d) && d.in_format == TAC_IN_BITS && d.stride == 1 && d.T % K == 0 &&
+         (K == 1 || K == 2 || K == 4 || K == 8 || K == 16);
+}
+
+size_t mfma_aggregate_tiles(const tac_layer_desc_t& d) {
+  const int rows = d.W == 64 ? Geo<64, 1>::kTileRows : Geo<32, 1>::kTileRows;
+  return (size_t)((d.H + rows - 1) / rows) * (size_t)(d.Cout / kCoutTile) * (size_t)d.B;
+}
+
+namespace {
+template <int KT, int WIN>
+hipError_t launch_agg(const MfmaParams& mp, hipStream_t s) {
+  using G = Geo<WIN, 1, 2>;
+  constexpr int lds = G::lds_bytes(KT, kMC);
+  static std::once_flag once;
+  static hipError_t attr = hipSuccess;
+  std::call_once(once, [] {
+    attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<KT, WIN, 1, false, false, kMC, 2, true>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  });
+  if (attr != hipSuccess) return attr;
+  MfmaParams q = mp;
+  q.row_tiles = (mp.Ho + G::kTileRows - 1) / G::kTileRows;
+  const dim3 grid(q.row_tiles * (mp.Cout / kCoutTile) * mp.B);
+  hipLaunchKernelGGL((mfma_kernel<KT, WIN, 1, false, false, kMC, 2, true>), grid, dim3(kThreads), lds, s, q);
+  return hipGetLastError();
+}
+template <int WIN>
+hipError_t launch_agg_k(const MfmaParams& mp, hipStream_t s) {
+  switch (mp.K) {
+    case 1: return launch_agg<1, WIN>(mp, s);
+    case 2: return launch_agg<2, WIN>(mp, s);
+    case 4: return launch_agg<4, WIN>(mp, s);
+    case 8: return launch_agg<8, WIN>(mp, s);
+    case 16: return launch_agg<16, WIN>(mp, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+}  // namespace
+
+hipError_t mfma_aggregate_launch(const LayerParams& p, uint64_t* tile_sums, hipStream_t s) {
+  MfmaParams mp;
+  fill_params(mp, p);
+  mp.out = reinterpret_cast<uint32_t*>(tile_sums);
+  mp.bias = nullptr; mp.v_inout = nullptr; mp.v_trace = nullptr; mp.w = nullptr;
+  return p.W == 64 ? launch_agg_k<64>(mp, s) : launch_agg_k<32>(mp, s);
 }
 
 }  // namespace tac

@@ -509,3 +509,29 @@ def test_bf16_operand_rounding_alone_exceeds_the_bar():
     # ... while the typical error is small: the rounding is doing what it should
     err = np.abs(a[1] - q[1]) / np.maximum(np.abs(a[1]), 1.0)
     assert np.median(err) < 5e-3
+
+
+# ---- the aggregate alone (Eq. 2), as exposed for the check of the aggregation-only kernel
+
+def test_aggregate_closed_forms():
+    r = np.random.Generator(np.random.PCG64(4242))
+    beta = 0.9
+    for K in (1, 2, 4, 8):
+        T = 2 * K
+        ones = np.ones((T, 1, 2, 3, 5), dtype=np.uint8)
+        A = oracle.aggregate(ones, 1, K=K, beta=beta)
+        assert np.allclose(A, (1 - beta ** K) / (1 - beta), rtol=0, atol=1e-13)           # geometric sum
+        for j in range(K):                                                               # one spike in frame j of group 1
+            s = np.zeros((T, 1, 2, 3, 5), dtype=np.uint8)
+            s[K + j, 0, 1, 2, 3] = 1
+            A = oracle.aggregate(s, 1, K=K, beta=beta)
+            assert abs(A[0, 1, 2, 3] - beta ** (K - 1 - j)) < 1e-15 and np.count_nonzero(A) == 1
+            assert np.count_nonzero(oracle.aggregate(s, 0, K=K, beta=beta)) == 0          # the other group sees nothing
+    s = (r.random((6, 2, 3, 4, 7)) < 0.4).astype(np.uint8)
+    assert np.array_equal(oracle.aggregate(s, 4, K=1, beta=beta), s[4].astype(np.float64))    # K = 1: the frame itself
+    # against the definition written out with numpy, and the bf16 reading against the library cast
+    A = oracle.aggregate(s, 1, K=3, beta=beta)
+    want = beta ** 2 * s[3] + beta * s[4] + 1.0 * s[5]
+    assert np.allclose(A, want, rtol=0, atol=1e-15)
+    Aq = oracle.aggregate(s, 1, K=3, beta=beta, round_a_bf16=True)
+    assert np.array_equal(Aq, torch.from_numpy(want).to(torch.bfloat16).to(torch.float64).numpy())
