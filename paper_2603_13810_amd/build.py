@@ -9,7 +9,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libtac.so")
-SOURCES = ["tac_api.hip", "tac_pack.hip", "tac_direct.hip", "tac_mfma.hip", "tac_mfma_small.hip", "tac_mfma_mid.hip", "tac_backward.hip", "tac_backward_mfma.hip"]
+# the large matrix-core kernel is compiled in one translation unit per geometry (input width, stride) and trace variant,
+# so that its many instantiations build side by side; the slowest files come first
+SOURCES = ["tac_mfma_w64s1.hip", "tac_mfma_w64s1_trace.hip", "tac_mfma_w32s1.hip", "tac_mfma_w32s1_trace.hip",
+           "tac_mfma_small.hip", "tac_mfma_w64s2.hip", "tac_mfma_w64s2_trace.hip", "tac_mfma_w32s2.hip",
+           "tac_mfma_w32s2_trace.hip", "tac_backward_mfma.hip", "tac_mfma_mid.hip", "tac_mfma.hip", "tac_api.hip",
+           "tac_pack.hip", "tac_direct.hip", "tac_backward.hip"]
+MAX_JOBS = min(16, os.cpu_count() or 4)
 
 
 def hipcc() -> str:
@@ -25,21 +31,23 @@ def build(verbose: bool = True) -> str:
     flags = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-I", INCLUDE, "-I", CSRC,
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
              "-Wall", "-Wno-unused-command-line-argument"]
-    procs = []
-    for src in SOURCES:
+    from concurrent.futures import ThreadPoolExecutor
+
+    def compile_one(src):
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
         cmd = [hipcc()] + flags + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
-        procs.append((subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True), src))
-        objs.append(obj)
-    failed = False
-    for p, src in procs:
-        out, _ = p.communicate()
-        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+        p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        out = "\n".join(l for l in p.stdout.splitlines() if "packed-fp32-ops" not in l)
         if out.strip() and (verbose or p.returncode):
             print(out, flush=True)
-        failed |= p.returncode != 0
+        return obj, p.returncode
+    failed = False
+    with ThreadPoolExecutor(max_workers=MAX_JOBS) as pool:
+        for obj, rc in pool.map(compile_one, SOURCES):
+            objs.append(obj)
+            failed |= rc != 0
     if failed:
         raise RuntimeError("hipcc failed")
     tmp = LIB + ".tmp%d" % os.getpid()

@@ -42,6 +42,17 @@ bool mfma_supported(const tac_layer_desc_t& d);
 size_t mfma_weight_bytes(const tac_layer_desc_t& d);
 hipError_t mfma_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s);
 hipError_t mfma_launch(const LayerParams& p, hipStream_t s);
+// the large member's kernels, one translation unit per geometry (input width, stride) and trace variant
+hipError_t mfma_large_w64s1(const LayerParams& p, hipStream_t s);
+hipError_t mfma_large_w64s1_trace(const LayerParams& p, hipStream_t s);
+hipError_t mfma_large_w32s1(const LayerParams& p, hipStream_t s);
+hipError_t mfma_large_w32s1_trace(const LayerParams& p, hipStream_t s);
+hipError_t mfma_large_w64s2(const LayerParams& p, hipStream_t s);
+hipError_t mfma_large_w64s2_trace(const LayerParams& p, hipStream_t s);
+hipError_t mfma_large_w32s2(const LayerParams& p, hipStream_t s);
+hipError_t mfma_large_w32s2_trace(const LayerParams& p, hipStream_t s);
+hipError_t mfma_aggregate_w64(const LayerParams& p, uint64_t* tile_sums, hipStream_t s);
+hipError_t mfma_aggregate_w32(const LayerParams& p, uint64_t* tile_sums, hipStream_t s);
 // the aggregation stage of the large MFMA kernel alone: one 64-bit sum of A-tile words per workgroup
 bool mfma_aggregate_supported(const tac_layer_desc_t& d);
 size_t mfma_aggregate_tiles(const tac_layer_desc_t& d);
