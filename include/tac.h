@@ -51,6 +51,16 @@ enum { TAC_FP32 = 0, TAC_BF16 = 1 };
  * first layer of Sec. 4.2, e.g. normalised event counts); aggregation, convolution and LIF are
  * the same, the aggregate A_k is a weighted sum of real frames. */
 enum { TAC_IN_BITS = 0, TAC_IN_BITS_POOL2 = 1, TAC_IN_BITS_MAXPOOL2 = 2, TAC_IN_F32 = 3 };
+/* Output format.  TAC_OUT_BITS: packed spikes [T_out][B][Cout][Ho][ceil(Wo/32)].  TAC_OUT_BITS_MAXPOOL2: the
+ * MaxPool(2) that follows every LIF layer of the event-data network (Conv -> BN -> LIF -> MaxPool(2), Sec. 5.1)
+ * is applied by the layer that writes the spikes: on 0/1 spikes the maximum of a 2 x 2 window is the OR of its
+ * four bits, and the stored tensor is [T_out][B][Cout][Ho/2][ceil(Wo/2/32)], a quarter of the bytes, which the
+ * next layer reads as plain TAC_IN_BITS of size Ho/2 x Wo/2.  Ho and Wo must be even.  The membrane (v_inout,
+ * v_trace) keeps the size Ho x Wo.  Supported by the MFMA kernels (tac_select_kernel: the large-shape member
+ * takes it with stride 1 only, other shapes go to the in-between member where it takes them);
+ * TAC_ERR_UNSUPPORTED otherwise (fp32 layers, the vector kernel), also for the backward pass (train with TAC_IN_BITS_MAXPOOL2 in the next
+ * layer instead, which pools the same bits while loading). */
+enum { TAC_OUT_BITS = 0, TAC_OUT_BITS_MAXPOOL2 = 1 };
 /* Kernel family.  AUTO picks MFMA when the shape qualifies (see
  * tac_select_kernel), else DIRECT.  Forcing MFMA on a shape it does not
  * support is TAC_ERR_UNSUPPORTED. */
@@ -83,6 +93,7 @@ typedef struct tac_layer_desc {
   int32_t precision;         /* TAC_FP32 / TAC_BF16                                       */
   int32_t in_format;         /* TAC_IN_BITS / _POOL2 / _MAXPOOL2 / TAC_IN_F32             */
   int32_t kernel;            /* TAC_KERNEL_AUTO / _DIRECT / _MFMA                         */
+  int32_t out_format;        /* TAC_OUT_BITS / TAC_OUT_BITS_MAXPOOL2                      */
   float beta;                /* membrane decay, in [0, 1]                                 */
   float theta;               /* threshold V_th, > 0                                       */
 } tac_layer_desc_t;
@@ -138,6 +149,7 @@ int tac_prepare_weights(const tac_layer_desc_t* desc, const float* w_oihw, void*
  *                      sequence can be fed in chunks of T.  NULL: V_0 = 0 (Alg. 1/2
  *                      line 1) and the final V is dropped
  *   out_spikes_packed  DEVICE, written, packed [T_out][B][Cout][Ho][ceil(Wo/32)]
+ *                      ([T_out][B][Cout][Ho/2][ceil(Wo/2/32)] with TAC_OUT_BITS_MAXPOOL2)
  *   v_trace            DEVICE, optional debug output, float32 [T_out][B][Cout][Ho][Wo]:
  *                      membrane BEFORE the reset at every LIF step; NULL in timed runs
  * Buffers must not overlap.  All pointers need 4-byte alignment (input 8-byte with
@@ -192,8 +204,9 @@ typedef struct tac_stack_layer {
 } tac_stack_layer_t;
 
 /* Host only: every description valid, and for l >= 1: B equal, Cin = Cout of layer l-1,
- * T = T_out of layer l-1, packed-bit input, and (H, W) = layer l-1's (Ho, Wo), or half of them
- * (both even) with TAC_IN_BITS_POOL2 / _MAXPOOL2.  TAC_OK, the failing layer's validation
+ * T = T_out of layer l-1, packed-bit input, and (H, W) = layer l-1's stored output size ((Ho, Wo), or
+ * (Ho/2, Wo/2) when layer l-1 has TAC_OUT_BITS_MAXPOOL2), or half of that (both even) with
+ * TAC_IN_BITS_POOL2 / _MAXPOOL2.  TAC_OK, the failing layer's validation
  * error, or TAC_ERR_BAD_SHAPE with *bad_layer (may be NULL) = index of the layer that does not
  * continue the one before. */
 int tac_stack_check(const tac_stack_layer_t* layers, int32_t n_layers, int32_t* bad_layer);

@@ -17,6 +17,7 @@ TAC_PER_STEP, TAC_COLLAPSE, TAC_PRESERVE = 0, 1, 2
 TAC_FP32, TAC_BF16 = 0, 1
 TAC_IN_BITS, TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2, TAC_IN_F32 = 0, 1, 2, 3
 TAC_KERNEL_AUTO, TAC_KERNEL_DIRECT, TAC_KERNEL_MFMA = 0, 1, 2
+TAC_OUT_BITS, TAC_OUT_BITS_MAXPOOL2 = 0, 1
 TAC_OK, TAC_ERR_NULL, TAC_ERR_BAD_SHAPE, TAC_ERR_BAD_K = 0, -1, -2, -3
 TAC_ERR_BAD_PARAM, TAC_ERR_UNSUPPORTED, TAC_ERR_HIP, TAC_ERR_ALIGN, TAC_ERR_NEED_STATE = -4, -5, -6, -7, -8
 TAC_MAX_K = 32
@@ -32,7 +33,7 @@ EXPORTS = ("tac_out_shape", "tac_packed_bytes", "tac_select_kernel", "tac_prepar
 class tac_layer_desc_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("T", "B", "Cin", "H", "W", "Cout", "kh", "kw", "stride", "pad", "K",
-                 "mode", "precision", "in_format", "kernel")] + \
+                 "mode", "precision", "in_format", "kernel", "out_format")] + \
                [("beta", ctypes.c_float), ("theta", ctypes.c_float)]
 
 
@@ -116,10 +117,16 @@ def _check(status: int) -> None:
 
 
 def make_desc(T, B, Cin, H, W, Cout, *, K=1, beta, theta, mode, stride=1, pad=1, kh=3, kw=3,
-              precision=TAC_FP32, in_format=TAC_IN_BITS, kernel=TAC_KERNEL_AUTO) -> tac_layer_desc_t:
+              precision=TAC_FP32, in_format=TAC_IN_BITS, kernel=TAC_KERNEL_AUTO, out_format=TAC_OUT_BITS) -> tac_layer_desc_t:
     return tac_layer_desc_t(T=T, B=B, Cin=Cin, H=H, W=W, Cout=Cout, kh=kh, kw=kw, stride=stride, pad=pad,
                             K=K, mode=mode, precision=precision, in_format=in_format, kernel=kernel,
-                            beta=beta, theta=theta)
+                            out_format=out_format, beta=beta, theta=theta)
+
+
+def stored_out_shape(desc: tac_layer_desc_t) -> Tuple[int, int, int]:
+    """(T_out, rows, pixels per row) of the packed output tensor: tac_out_shape, halved by the pool in the writer."""
+    T_out, Ho, Wo = tac_out_shape(desc)
+    return (T_out, Ho // 2, Wo // 2) if desc.out_format == TAC_OUT_BITS_MAXPOOL2 else (T_out, Ho, Wo)
 
 
 def tac_out_shape(desc: tac_layer_desc_t) -> Tuple[int, int, int]:
@@ -196,10 +203,11 @@ def tac_conv_lif(desc, spikes_packed, w_prepared, bias=None, v_inout=None, out_s
                          (spikes_packed.numel() * spikes_packed.element_size(), need_in))
     if w_prepared.numel() * w_prepared.element_size() < tac_prepared_weight_bytes(desc):
         raise ValueError("prepared-weight buffer too small for this description")
+    _, Hs, Ws = stored_out_shape(desc)
     if out_spikes_packed is None:
-        out_spikes_packed = torch.empty((T_out, desc.B, desc.Cout, Ho, (Wo + 31) // 32), dtype=torch.int32,
+        out_spikes_packed = torch.empty((T_out, desc.B, desc.Cout, Hs, (Ws + 31) // 32), dtype=torch.int32,
                                         device=spikes_packed.device)
-    elif out_spikes_packed.numel() * out_spikes_packed.element_size() != tac_packed_bytes(T_out, desc.B, desc.Cout, Ho, Wo):
+    elif out_spikes_packed.numel() * out_spikes_packed.element_size() != tac_packed_bytes(T_out, desc.B, desc.Cout, Hs, Ws):
         raise ValueError("out_spikes_packed has the wrong size")
     if bias is not None and tuple(bias.shape) != (desc.Cout,):
         raise ValueError("bias must be [Cout]")
@@ -304,10 +312,11 @@ def make_stack(layers):
     for i, L in enumerate(layers):
         desc = L["desc"]
         T_out, Ho, Wo = tac_out_shape(desc)
+        _, Hs, Ws = stored_out_shape(desc)
         if L.get("out_spikes_packed") is None:
-            L["out_spikes_packed"] = torch.empty((T_out, desc.B, desc.Cout, Ho, (Wo + 31) // 32), dtype=torch.int32,
+            L["out_spikes_packed"] = torch.empty((T_out, desc.B, desc.Cout, Hs, (Ws + 31) // 32), dtype=torch.int32,
                                                  device=L["w_prepared"].device)
-        elif L["out_spikes_packed"].numel() * L["out_spikes_packed"].element_size() != tac_packed_bytes(T_out, desc.B, desc.Cout, Ho, Wo):
+        elif L["out_spikes_packed"].numel() * L["out_spikes_packed"].element_size() != tac_packed_bytes(T_out, desc.B, desc.Cout, Hs, Ws):
             raise ValueError("layer %d: out_spikes_packed has the wrong size" % i)
         if L["w_prepared"].numel() * L["w_prepared"].element_size() < tac_prepared_weight_bytes(desc):
             raise ValueError("layer %d: prepared-weight buffer too small for this description" % i)

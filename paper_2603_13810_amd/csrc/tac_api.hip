@@ -41,6 +41,7 @@ int validate(const tac_layer_desc_t* d) {
   if (d->in_format < TAC_IN_BITS || d->in_format > TAC_IN_F32) return TAC_ERR_BAD_PARAM;
   if (d->kernel != TAC_KERNEL_AUTO && d->kernel != TAC_KERNEL_DIRECT && d->kernel != TAC_KERNEL_MFMA)
     return TAC_ERR_BAD_PARAM;
+  if (d->out_format != TAC_OUT_BITS && d->out_format != TAC_OUT_BITS_MAXPOOL2) return TAC_ERR_BAD_PARAM;
   if (!(d->beta >= 0.0f && d->beta <= 1.0f)) return TAC_ERR_BAD_PARAM;
   if (!(d->theta > 0.0f) || !std::isfinite(d->theta)) return TAC_ERR_BAD_PARAM;
   if (d->mode != TAC_PER_STEP) {
@@ -49,6 +50,7 @@ int validate(const tac_layer_desc_t* d) {
   // kernels index words and membrane elements with 32-bit offsets inside one (t) slab and
   // 64-bit offsets across slabs; keep each slab below 2^31 elements
   const int Ho = (d->H + 2 - 3) / d->stride + 1, Wo = (d->W + 2 - 3) / d->stride + 1;
+  if (d->out_format == TAC_OUT_BITS_MAXPOOL2 && ((Ho | Wo) & 1)) return TAC_ERR_BAD_SHAPE;
   const int64_t out_slab = (int64_t)d->B * d->Cout * Ho * Wo;
   const int f = (d->in_format == TAC_IN_BITS_POOL2 || d->in_format == TAC_IN_BITS_MAXPOOL2) ? 2 : 1;
   const int64_t in_slab = d->in_format == TAC_IN_F32 ? (int64_t)d->B * d->Cin * d->H * d->W
@@ -71,6 +73,8 @@ int effective(const tac_layer_desc_t* d, tac_layer_desc_t* e) {
 
 int select_kernel(const tac_layer_desc_t* d) {
   const bool ok = tac::mfma_supported(*d);
+  if (d->out_format == TAC_OUT_BITS_MAXPOOL2)      // pooled output: the MFMA kernels only
+    return (ok && d->kernel != TAC_KERNEL_DIRECT) ? (int)TAC_KERNEL_MFMA : (int)TAC_ERR_UNSUPPORTED;
   if (d->kernel == TAC_KERNEL_DIRECT) return TAC_KERNEL_DIRECT;
   if (d->kernel == TAC_KERNEL_MFMA) return ok ? (int)TAC_KERNEL_MFMA : (int)TAC_ERR_UNSUPPORTED;
   return ok ? (int)TAC_KERNEL_MFMA : (int)TAC_KERNEL_DIRECT;
@@ -154,6 +158,7 @@ int tac_conv_lif(const tac_layer_desc_t* d, const void* input, const void* w_pre
   p.Wo = (desc->W + 2 - 3) / desc->stride + 1;
   p.pool2 = desc->in_format == TAC_IN_BITS_POOL2 ? 1 : (desc->in_format == TAC_IN_BITS_MAXPOOL2 ? 2 : 0);
   p.dense = desc->in_format == TAC_IN_F32;
+  p.out_pool = desc->out_format == TAC_OUT_BITS_MAXPOOL2;
   p.mfma_kind = kern == TAC_KERNEL_MFMA ? tac::mfma_kind(*desc) : 0;
   p.Hs = p.pool2 ? 2 * desc->H : desc->H;
   p.Wwi = ((p.pool2 ? 2 * desc->W : desc->W) + 31) / 32;
@@ -186,7 +191,8 @@ int tac_conv_lif(const tac_layer_desc_t* d, const void* input, const void* w_pre
     const int skip = p.K - K_last;
     for (int j = 0; j < skip; ++j) { q.wj[j] = 0.0f; q.wjd[j] = 0.0; }
     const size_t in_slab = (size_t)p.B * p.Cin * p.Hs * (p.dense ? (size_t)p.W : (size_t)p.Wwi);   // 4-byte elements per frame
-    const size_t out_slab = (size_t)p.B * p.Cout * p.Ho * p.Wwo;
+    const size_t out_slab = p.out_pool ? (size_t)p.B * p.Cout * (p.Ho / 2) * ((p.Wo / 2 + 31) / 32)
+                                       : (size_t)p.B * p.Cout * p.Ho * p.Wwo;
     const size_t v_slab = (size_t)p.B * p.Cout * p.Ho * p.Wo;
     const size_t steps = (size_t)p.G * p.n_lif;  // LIF steps of the whole groups
     q.spikes = p.spikes + (size_t)(desc->T - p.K) * in_slab;
@@ -252,6 +258,7 @@ int tac_stack_check(const tac_stack_layer_t* layers, int32_t n_layers, int32_t* 
       if (bad_layer) *bad_layer = l;
       return rc;
     }
+    if (d.out_format == TAC_OUT_BITS_MAXPOOL2) { Ho /= 2; Wo /= 2; }      // what the next layer finds in memory
   }
   return TAC_OK;
 }
@@ -280,7 +287,7 @@ int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* 
   if (((uintptr_t)input | (uintptr_t)w_oihw | (uintptr_t)v_trace | (uintptr_t)grad_out | (uintptr_t)grad_y |
        (uintptr_t)grad_w | (uintptr_t)grad_bias | (uintptr_t)grad_in) & 3u)
     return TAC_ERR_ALIGN;
-  if (eff.W > 1024) return TAC_ERR_UNSUPPORTED;
+  if (eff.W > 1024 || eff.out_format != TAC_OUT_BITS) return TAC_ERR_UNSUPPORTED;
 
   tac::BackwardParams p;
   std::memset(&p, 0, sizeof(p));

@@ -21,16 +21,6 @@ namespace {
 constexpr int kThreads = 256;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-// 2 x 2 max pool of bits: v = OR of the two rows' words; OR of horizontal neighbours, even bits gathered into
-// the low half: 32 stored pixels -> 16 pooled pixels
-__device__ __forceinline__ uint32_t pool_pairs(uint32_t v) {
-  v = (v | (v >> 1)) & 0x55555555u;
-  v = (v | (v >> 1)) & 0x33333333u;
-  v = (v | (v >> 2)) & 0x0f0f0f0fu;
-  v = (v | (v >> 4)) & 0x00ff00ffu;
-  return (v | (v >> 8)) & 0x0000ffffu;
-}
-
 __device__ __forceinline__ int group_frames(const BackwardParams& p, int k) {
   return (k == p.G - 1 && p.K_last) ? p.K_last : p.K;
 }

@@ -23,6 +23,7 @@ struct LayerParams {
   int G;                    // groups = T / K = convolution stages
   int n_lif;                // LIF steps per group: K for TAC-TP, else 1
   int pool2;                // input is unpooled: 1 = 2x2 mean pool while loading, 2 = 2x2 max pool
+  int out_pool;             // the output spikes go through a 2x2 max pool before they are stored (Ho, Wo even)
   int mfma_kind;            // which MFMA kernel (see mfma_kind), 0 for the direct kernel
   int dense;                // input is float32 frames [T][B][Cin][H][W], not packed bits
   int bf16;                 // round A_k to bf16

@@ -43,6 +43,7 @@ static bool large_supported(const tac_layer_desc_t& d) {
   }
   if (d.Cin % kChunk != 0 || d.Cout % kCoutTile != 0) return false;
   if (d.W != 64 && d.W != 32) return false;
+  if (d.out_format == TAC_OUT_BITS_MAXPOOL2 && d.stride != 1) return false;     // pooled output: rows of 32 or 64 pixels
   if (d.stride == 1) return true;
   const int K = d.mode == TAC_PER_STEP ? 1 : d.K;
   return d.stride == 2 && (K == 1 || K == 2 || K == 4);     // LDS room of the stride-2 tiles

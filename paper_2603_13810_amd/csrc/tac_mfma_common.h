@@ -30,6 +30,7 @@ struct MfmaParams {
   int B, Cin, H, W, Ho, Wo, Cout, stride, K, G, n_lif, row_tiles, maxpool;
   float decay, theta;
   uint32_t wq[TAC_MAX_K];              // round(beta^(K-1-j) * 2^23)
+  int out_pool;                        // 2 x 2 max pool of the output spikes before they are stored
   int dense;                           // short-contraction kernel: the input is float32 frames
   int pool;                            // mid kernel: 2 x 2 pool on load, 1 mean, 2 max
   double wjd[TAC_MAX_K];               // beta^(K-1-j) in double, for real-valued frames
@@ -58,6 +59,16 @@ __device__ __forceinline__ uint32_t write_lanes(uint32_t old, const uint32_t (&x
         "s"(x[3][1]), "n"(L0), "n"(L0 + HALF), "n"(L0 + STEP), "n"(L0 + STEP + HALF), "n"(L0 + 2 * STEP),
         "n"(L0 + 2 * STEP + HALF), "n"(L0 + 3 * STEP), "n"(L0 + 3 * STEP + HALF), "0"(old));
   return r;
+}
+
+// 2 x 2 max pool of bits, horizontal part: OR of neighbouring bit pairs, even bits gathered into the low half;
+// 32 pixels -> 16 pooled pixels.
+__device__ __forceinline__ uint32_t pool_pairs(uint32_t v) {
+  v = (v | (v >> 1)) & 0x55555555u;
+  v = (v | (v >> 1)) & 0x33333333u;
+  v = (v | (v >> 2)) & 0x0f0f0f0fu;
+  v = (v | (v >> 4)) & 0x00ff00ffu;
+  return (v | (v >> 8)) & 0x0000ffffu;
 }
 
 template <int I, int N, class F>
@@ -151,6 +162,49 @@ __device__ __forceinline__ void lif_step(float (&V)[NMC][NP][16], const f32x16 (
     });
   });
 }
+
+// MaxPool(2) of the output spikes in the layer that writes them (the Conv -> BN -> LIF -> MaxPool(2) blocks of
+// Sec. 5.1): on 0/1 spikes the maximum of a 2 x 2 window is the OR of its four bits, so the packed words of one
+// LIF step are pooled before they are stored and the tensor crosses HBM at a quarter of its bytes.
+// `word` holds the step's packed output as lif_step leaves it for output rows of 32 pixels and more (lane
+// (r << 2) | (hi << 1) | np: channel 8 (r / 4) + 4 hi + r % 4 of 32-channel block mc, 32-pixel block np of the
+// wave).  A lane pools its 32 pixels horizontally to 16 bits and puts them into the exchange area in LDS
+//     ex: uint32 [rows][ctile][nseg],  low half = pooled block 0, high half = pooled block 1 of 64-pixel segment seg,
+// the workgroup meets at a barrier, and the threads then OR the two rows of every pooled row and store the words:
+// pooled row pr of channel c = ex[2 pr][c][..] | ex[2 pr + 1][c][..], nseg words of 32 pooled pixels each.
+//   two_rows   the wave's two blocks are two rows of 32 pixels (np = row) instead of two halves of one row
+//   row0       first row of the wave within the tile;  seg: its 64-pixel segment of the row
+//   out_tile   address of (this step, sample, first channel of the tile, pooled row y0 / 2, word 0)
+//   plane_p    words per channel of the pooled tensor, Wwp words per pooled row
+//   rows_p     pooled rows of the tile inside the image,  c_valid: channels of the tile that exist
+// Called by all threads of the workgroup (it contains a barrier); consecutive steps alternate between two areas.
+template <int NMC>
+__device__ __forceinline__ void pooled_store(const uint32_t (&word)[NMC][2], uint32_t* ex, int tid, int nthreads, int rows,
+                                             int nseg, bool two_rows, int row0, int seg, uint32_t* out_tile, size_t plane_p,
+                                             int Wwp, int rows_p, int c_valid) {
+  constexpr int ctile = NMC * 32;
+  const int lane = tid & 63;
+  const int r = lane >> 2, hi = (lane >> 1) & 1, np = lane & 1;
+  const int c_lane = 8 * (r >> 2) + 4 * hi + (r & 3);
+#pragma unroll
+  for (int mc = 0; mc < NMC; ++mc) {
+    const uint32_t hp = pool_pairs(word[mc][0]);
+    const int c = mc * 32 + c_lane;
+    if (two_rows)
+      ex[((row0 + np) * ctile + c) * nseg + seg] = hp;
+    else
+      reinterpret_cast<uint16_t*>(ex)[(((row0 * ctile + c) * nseg + seg) << 1) + np] = (uint16_t)hp;
+  }
+  __syncthreads();
+  const int items = (rows >> 1) * ctile * nseg;
+  for (int i = tid; i < items; i += nthreads) {
+    const int sg = i % nseg, c = (i / nseg) % ctile, pr = i / (nseg * ctile);
+    const uint32_t v = ex[((2 * pr) * ctile + c) * nseg + sg] | ex[((2 * pr + 1) * ctile + c) * nseg + sg];
+    if (pr < rows_p && c < c_valid && sg < Wwp) out_tile[(size_t)c * plane_p + (size_t)pr * Wwp + sg] = v;
+  }
+}
+
+__host__ __device__ constexpr int pool_exchange_bytes(int rows, int ctile, int nseg) { return 2 * rows * ctile * nseg * 4; }
 
 }  // namespace
 

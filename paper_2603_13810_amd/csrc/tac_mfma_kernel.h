@@ -97,6 +97,10 @@ struct Geo {
   __host__ __device__ static constexpr int lds_bias(int MC) { return kLdsW + 2 * 9 * MC * 1024; }
   __host__ __device__ static constexpr int lds_lut(int MC) { return lds_bias(MC) + kCoutTile * 4; }
   static constexpr int lds_bytes(int K, int MC = kMC) { return lds_lut(MC) + lut_bytes(K) + 2 * words_bytes(K); }
+  // behind it, when the output spikes are pooled before they are stored: the exchange area of pooled_store
+  // (output rows of 32 or 64 pixels only)
+  static constexpr bool kCanPoolOut = S == 1 && kWo >= 32;
+  static constexpr int pool_bytes(int MC) { return kCanPoolOut ? pool_exchange_bytes(kTileRows, MC * 32, 1) : 0; }
   // LDS column (in 16-byte units) of padded pixel xp
   __host__ __device__ static constexpr int col(int xp) { return S == 1 ? xp : (xp & 1) * kXH + (xp >> 1); }
   // the loader pipeline has kSteps + 2 slots (slot i reads the words of step i, looks up step
@@ -194,16 +198,6 @@ __device__ __forceinline__ void stage_load(uint32_t (&wd)[NG][KM * (MP ? 4 : 1)]
         }
       }
     }
-}
-
-// 2 x 2 max pool of bits: OR of the two rows, OR of horizontal neighbours, even bits gathered
-// into the low half; 64 stored pixels (a, b = the OR-ed rows' two words) -> 32 pooled pixels.
-__device__ __forceinline__ uint32_t pool_pairs(uint32_t v) {
-  v = (v | (v >> 1)) & 0x55555555u;
-  v = (v | (v >> 1)) & 0x33333333u;
-  v = (v | (v >> 2)) & 0x0f0f0f0fu;
-  v = (v | (v >> 4)) & 0x00ff00ffu;
-  return (v | (v >> 8)) & 0x0000ffffu;
 }
 
 // (a & m) | (b & ~m): one v_bfi_b32
@@ -773,7 +767,15 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
       } else {
         lif_step<MC, G::kWo, false, NP>(V, acc, p.decay, p.theta, lg, word, nullptr, plane);
       }
-      if (out_ok) {
+      if (G::kCanPoolOut && p.out_pool) {
+        if constexpr (G::kCanPoolOut) {
+          const uint32_t plane_p = (uint32_t)(Ho >> 1);                      // one word per pooled row
+          uint32_t* ex = reinterpret_cast<uint32_t*>(lds + G::lds_bytes(K, MC)) + (step & 1) * (G::kTileRows * kCT);
+          pooled_store<MC>(word, ex, tid, kThreads, G::kTileRows, 1, G::kWaveRows == 2, wave * G::kWaveRows, 0,
+                           p.out + (step * p.B * p.Cout + (size_t)b * p.Cout + co_wave) * plane_p + (y0 >> 1), plane_p, 1,
+                           min(G::kTileRows >> 1, (Ho - y0) >> 1), kCT);
+        }
+      } else if (out_ok) {
         uint32_t* const o = out_wave + step * out_step;
 #pragma unroll
         for (int sr = 0; sr < kStoreRegs; ++sr)
@@ -814,15 +816,18 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
 template <int KT, int WIN, int S, bool TRACE, bool MP, int MC, int NP = 2>
 hipError_t launch_tile(const MfmaParams& mp, hipStream_t s) {
   using G = Geo<WIN, S, NP>;
-  constexpr int lds = G::lds_bytes(KT > 0 ? KT : TAC_MAX_K, MC);
-  static_assert(lds <= kLdsLimit, "tile does not fit the LDS");
+  constexpr int lds_layer = G::lds_bytes(KT > 0 ? KT : TAC_MAX_K, MC);
+  constexpr int lds_max = lds_layer + G::pool_bytes(MC);
+  static_assert(lds_max <= kLdsLimit, "tile does not fit the LDS");
   static std::once_flag once;               // one attribute call per kernel, also with several host threads
   static hipError_t attr = hipSuccess;
   std::call_once(once, [] {
     attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_kernel<KT, WIN, S, TRACE, MP, MC, NP>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds_max);
   });
   if (attr != hipSuccess) return attr;
+  if (mp.out_pool && !G::kCanPoolOut) return hipErrorInvalidValue;
+  const int lds = mp.out_pool ? lds_max : lds_layer;
   MfmaParams q = mp;
   q.row_tiles = (mp.Ho + G::kTileRows - 1) / G::kTileRows;
   const dim3 grid(q.row_tiles * (mp.Cout / (MC * 32)) * mp.B);
@@ -906,7 +911,7 @@ inline void fill_params(MfmaParams& mp, const LayerParams& p) {
   mp.spikes = p.spikes; mp.w = static_cast<const uint8_t*>(p.w); mp.bias = p.bias; mp.v_inout = p.v_inout;
   mp.out = p.out; mp.v_trace = p.v_trace;
   mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.W = p.W; mp.Ho = p.Ho; mp.Wo = p.Wo; mp.Cout = p.Cout; mp.stride = p.stride;
-  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.maxpool = p.pool2 == 2; mp.dense = 0;
+  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.maxpool = p.pool2 == 2; mp.dense = 0; mp.out_pool = p.out_pool;
   mp.row_tiles = 0;
   mp.decay = p.decay; mp.theta = p.theta;
   for (int j = 0; j < TAC_MAX_K; ++j) {

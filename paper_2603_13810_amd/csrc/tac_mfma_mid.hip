@@ -69,6 +69,7 @@ __global__ __launch_bounds__(kMidThreads, TRACE ? 1 : 2) void mid_kernel(const M
   uint8_t* const w_lds = lds + m.a_bytes;
   int32_t* const tab = reinterpret_cast<int32_t*>(w_lds + m.w_bytes);
   float* const bias_lds = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(tab) + m.tab_bytes);
+  uint32_t* const pool_ex = reinterpret_cast<uint32_t*>(lds + m.total);        // only there when the output is pooled
   const int n_a = m.rows_in * m.WP * Cin;
 
   for (int i = tid; i < n_a + 8; i += kMidThreads) a_tile[i] = 0;          // padding columns, empty-slot zeros
@@ -121,6 +122,10 @@ __global__ __launch_bounds__(kMidThreads, TRACE ? 1 : 2) void mid_kernel(const M
   const size_t out_lane = ((size_t)b * p.Cout + co0 + st_co) * out_plane + (size_t)oy * Wwo + st_np;
   const bool out_ok = oy < p.Ho && st_np < Wwo;
   const size_t out_step = (size_t)p.B * p.Cout * out_plane;
+  // pooled output (2 x 2 max pool in the writer): [step][b][cout][Ho / 2][one word]
+  const size_t plane_p = (size_t)(p.Ho >> 1);
+  const size_t out_step_p = (size_t)p.B * p.Cout * plane_p;
+  uint32_t* const out_tile_p = p.out + ((size_t)b * p.Cout + co0) * plane_p + (y0 >> 1);
 
   const size_t in_chan = (size_t)Hs * WWs;                         // stored words per (t, b, cin)
   const size_t t_stride = (size_t)p.B * Cin * in_chan;
@@ -197,7 +202,10 @@ __global__ __launch_bounds__(kMidThreads, TRACE ? 1 : 2) void mid_kernel(const M
       for (int mc = 0; mc < NMC; ++mc) word[mc][0] = word[mc][1] = 0u;
       float* tl = TRACE ? p.v_trace + step * ((size_t)p.B * p.Cout * plane) + v_wave : nullptr;
       lif_step<NMC, 64, TRACE>(V, acc, p.decay, p.theta, lg, word, tl, plane);
-      if (out_ok) {
+      if (p.out_pool) {
+        pooled_store<NMC>(word, pool_ex + (step & 1) * (kMidRows * NMC * 32), tid, kMidThreads, kMidRows, 1, false, wave, 0,
+                          out_tile_p + step * out_step_p, plane_p, 1, min(kMidRows >> 1, (p.Ho - y0) >> 1), p.Cout - co0);
+      } else if (out_ok) {
 #pragma unroll
         for (int mc = 0; mc < NMC; ++mc)
           if (co0 + mc * 32 + st_co < p.Cout) p.out[step * out_step + out_lane + (size_t)mc * 32 * out_plane] = word[mc][0];
@@ -254,12 +262,13 @@ hipError_t mid_launch_t(const MfmaParams& mp, hipStream_t s) {
   const int co_tiles = (mp.Cout + NMC * 32 - 1) / (NMC * 32);
   const dim3 grid(((mp.Ho + kMidRows - 1) / kMidRows) * co_tiles * mp.B);
   auto kern = mp.v_trace ? &mid_kernel<S, NMC, true> : &mid_kernel<S, NMC, false>;
-  if (m.total > 64 * 1024) {
+  const int lds = m.total + (mp.out_pool ? pool_exchange_bytes(kMidRows, NMC * 32, 1) : 0);
+  if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kMidLdsLimit);
+                                       kMidLdsLimit + pool_exchange_bytes(kMidRows, 64, 1));
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(kMidThreads), m.total, s, mp);
+  hipLaunchKernelGGL(kern, grid, dim3(kMidThreads), lds, s, mp);
   return hipGetLastError();
 }
 
@@ -293,7 +302,7 @@ hipError_t mfma_mid_launch(const LayerParams& p, hipStream_t s) {
   mp.spikes = p.spikes; mp.w = static_cast<const uint8_t*>(p.w); mp.bias = p.bias; mp.v_inout = p.v_inout;
   mp.out = p.out; mp.v_trace = p.v_trace;
   mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.W = p.W; mp.Ho = p.Ho; mp.Wo = p.Wo; mp.Cout = p.Cout; mp.stride = p.stride;
-  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.row_tiles = 0; mp.maxpool = 0; mp.dense = 0; mp.pool = p.pool2;
+  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.row_tiles = 0; mp.maxpool = 0; mp.dense = 0; mp.pool = p.pool2; mp.out_pool = p.out_pool;
   mp.decay = p.decay; mp.theta = p.theta;
   for (int j = 0; j < TAC_MAX_K; ++j) {
     const double q = (double)p.wj[j] * (double)(1u << kFixShift);

@@ -64,6 +64,7 @@ __global__ __launch_bounds__(kSmallThreads, TRACE ? 1 : 2) void small_kernel(con
   uint16_t* const a_tile = reinterpret_cast<uint16_t*>(lds + ((n_words * 4 + 15) & ~15));
   const int n_a = CIN * kRowsIn * WP;
   float* const bias_lds = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(a_tile) + (((n_a + 1) * 2 + 15) & ~15));
+  uint32_t* const pool_ex = reinterpret_cast<uint32_t*>(bias_lds + NMC * 32);     // only there when the output is pooled
 
   for (int i = tid; i <= n_a; i += kSmallThreads) a_tile[i] = 0;       // padding columns and the zero element
   if (tid < NMC * 32) bias_lds[tid] = (p.bias && co0 + tid < p.Cout) ? p.bias[co0 + tid] : 0.f;
@@ -185,6 +186,11 @@ __global__ __launch_bounds__(kSmallThreads, TRACE ? 1 : 2) void small_kernel(con
   const size_t out_lane = ((size_t)b * p.Cout + co0 + st_co) * out_plane + (size_t)oy * Wwo + 2 * seg + st_np;
   const bool out_ok = oy < p.Ho && 2 * seg + st_np < Wwo;
   const size_t out_step = (size_t)p.B * p.Cout * out_plane;
+  // pooled output (2 x 2 max pool in the writer): [step][b][cout][Ho / 2][words of Wo / 2 pixels]
+  const int Wwp = ((p.Wo >> 1) + 31) >> 5;
+  const size_t plane_p = (size_t)(p.Ho >> 1) * Wwp;
+  const size_t out_step_p = (size_t)p.B * p.Cout * plane_p;
+  uint32_t* const out_tile_p = p.out + ((size_t)b * p.Cout + co0) * plane_p + (size_t)(y0 >> 1) * Wwp;
 
   for (int g = 0; g < p.G; ++g) {
     // ---- 1. words of this group -> LDS (item order: [frame][cin][row][word]); next group's requested
@@ -267,7 +273,10 @@ __global__ __launch_bounds__(kSmallThreads, TRACE ? 1 : 2) void small_kernel(con
       for (int mc = 0; mc < NMC; ++mc) word[mc][0] = word[mc][1] = 0u;
       float* tl = TRACE ? p.v_trace + step * ((size_t)p.B * p.Cout * plane) + v_wave : nullptr;
       lif_step<NMC, 64, TRACE>(V, acc, p.decay, p.theta, lg, word, tl, plane);
-      if (out_ok) {
+      if (p.out_pool) {
+        pooled_store<NMC>(word, pool_ex + (step & 1) * (kRows * NMC * 32 * SEG), tid, kSmallThreads, kRows, SEG, false, wrow, seg,
+                          out_tile_p + step * out_step_p, plane_p, Wwp, min(kRows >> 1, (p.Ho - y0) >> 1), p.Cout - co0);
+      } else if (out_ok) {
 #pragma unroll
         for (int mc = 0; mc < NMC; ++mc)
           if (co0 + mc * 32 + st_co < p.Cout) p.out[step * out_step + out_lane + (size_t)mc * 32 * out_plane] = word[mc][0];
@@ -318,7 +327,8 @@ template <int CIN, int S, int NMC, int SEG>
 hipError_t small_launch_t(const MfmaParams& mp, hipStream_t s) {
   const int co_tiles = (mp.Cout + NMC * 32 - 1) / (NMC * 32);
   const dim3 grid(((mp.Ho + kSmallRows / SEG - 1) / (kSmallRows / SEG)) * co_tiles * mp.B);
-  const size_t lds = small_lds_bytes(CIN, S, mp.W, mp.K, NMC, SEG);
+  const size_t lds = small_lds_bytes(CIN, S, mp.W, mp.K, NMC, SEG) +
+                     (mp.out_pool ? pool_exchange_bytes(kSmallRows / SEG, NMC * 32, SEG) : 0);
   if (mp.dense) {
     if (mp.v_trace)
       hipLaunchKernelGGL((small_kernel<CIN, S, NMC, true, true, SEG>), grid, dim3(kSmallThreads), lds, s, mp);
@@ -372,7 +382,7 @@ hipError_t mfma_small_launch(const LayerParams& p, hipStream_t s) {
   mp.spikes = p.spikes; mp.w = static_cast<const uint8_t*>(p.w); mp.bias = p.bias; mp.v_inout = p.v_inout;
   mp.out = p.out; mp.v_trace = p.v_trace;
   mp.B = p.B; mp.Cin = p.Cin; mp.H = p.H; mp.W = p.W; mp.Ho = p.Ho; mp.Wo = p.Wo; mp.Cout = p.Cout; mp.stride = p.stride;
-  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.row_tiles = 0; mp.maxpool = 0; mp.dense = p.dense;
+  mp.K = p.K; mp.G = p.G; mp.n_lif = p.n_lif; mp.row_tiles = 0; mp.maxpool = 0; mp.dense = p.dense; mp.out_pool = p.out_pool;
   for (int j = 0; j < TAC_MAX_K; ++j) mp.wjd[j] = p.wjd[j];
   mp.decay = p.decay; mp.theta = p.theta;
   for (int j = 0; j < TAC_MAX_K; ++j) {

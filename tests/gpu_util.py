@@ -16,9 +16,10 @@ def bf16_round_np(w32: np.ndarray) -> np.ndarray:
 
 
 def run_gpu(spikes, w32, *, K, beta, theta, mode, stride=1, bias=None, v0=None, pool2=False,
-            precision=api.TAC_FP32, kernel=api.TAC_KERNEL_AUTO, trace=True):
+            precision=api.TAC_FP32, kernel=api.TAC_KERNEL_AUTO, trace=True, out_pool=False):
     """spikes uint8 [T,B,Cin,Hs,Ws] host array (float32: real-valued frames, TAC_IN_F32).
-    Returns dict with unpacked spikes, v_trace, v_final, kernel id."""
+    Returns dict with unpacked spikes, v_trace, v_final, kernel id.  out_pool: the layer max-pools its output
+    spikes 2 x 2 before it stores them; `spikes` is then the pooled tensor [T_out,B,Cout,Ho/2,Wo/2]."""
     dev = torch.device("cuda:0")
     dense = np.issubdtype(np.asarray(spikes).dtype, np.floating)
     T, B, Cin, Hs, Ws = spikes.shape
@@ -26,6 +27,7 @@ def run_gpu(spikes, w32, *, K, beta, theta, mode, stride=1, bias=None, v0=None, 
     Cout = w32.shape[0]
     desc = api.make_desc(T, B, Cin, H, W, Cout, K=K, beta=beta, theta=theta, mode=mode, stride=stride,
                          precision=precision, kernel=kernel,
+                         out_format=api.TAC_OUT_BITS_MAXPOOL2 if out_pool else api.TAC_OUT_BITS,
                          in_format=api.TAC_IN_F32 if dense else
                          (api.TAC_IN_BITS_MAXPOOL2 if pool2 == "max" else api.TAC_IN_BITS_POOL2) if pool2 else api.TAC_IN_BITS)
     T_out, Ho, Wo = api.tac_out_shape(desc)
@@ -39,11 +41,12 @@ def run_gpu(spikes, w32, *, K, beta, theta, mode, stride=1, bias=None, v0=None, 
             v.copy_(torch.from_numpy(np.asarray(v0, dtype=np.float32)))
     vt = torch.full((T_out, B, Cout, Ho, Wo), float("nan"), dtype=torch.float32, device=dev) if trace else None
     # poison the output so unwritten words show up
-    out = torch.full((T_out, B, Cout, Ho, (Wo + 31) // 32), -1, dtype=torch.int32, device=dev)
+    _, Hst, Wst = api.stored_out_shape(desc)
+    out = torch.full((T_out, B, Cout, Hst, (Wst + 31) // 32), -1, dtype=torch.int32, device=dev)
     api.tac_conv_lif(desc, sp, wp, bias_d, v, out, vt)
     torch.cuda.synchronize()
     out_h = out.cpu().numpy()
-    return dict(spikes=np_unpack(out_h, Wo), pad_ok=pad_bits_zero(out_h, Wo), packed=out_h,
+    return dict(spikes=np_unpack(out_h, Wst), pad_ok=pad_bits_zero(out_h, Wst), packed=out_h,
                 v_trace=None if vt is None else vt.cpu().numpy(), v_final=None if v is None else v.cpu().numpy(),
                 kernel=api.tac_select_kernel(desc), desc=desc)
 
@@ -87,6 +90,19 @@ def check_layer(spikes, w32, *, precision=api.TAC_FP32, kernel=api.TAC_KERNEL_AU
         assert g["kernel"] == expect_kernel
     assert g["pad_ok"], "pad bits of the packed output must be zero"
     theta = float(np.float32(kw["theta"]))
+    if kw.get("out_pool"):
+        # The stored spikes are pooled.  The library's unpooled spikes follow from the membranes it recorded
+        # (spike iff V >= theta, the comparison the kernel makes, in fp32): (i) they and the membranes are held
+        # against the oracle below like any other layer's; (ii) the stored tensor must be their 2 x 2 maximum,
+        # bit for bit; (iii) the kernel without the membrane trace (the timed one) stores the same bits.
+        kw = {k: v for k, v in kw.items() if k != "out_pool"}
+        unpooled = (g["v_trace"] >= np.float32(theta)).astype(np.uint8)
+        T_, B_, C_, Ho_, Wo_ = unpooled.shape
+        want = unpooled.reshape(T_, B_, C_, Ho_ // 2, 2, Wo_ // 2, 2).max(axis=(4, 6))
+        assert np.array_equal(g["spikes"], want), "stored spikes are not the 2 x 2 maximum of the layer's spikes"
+        g2 = run_gpu(spikes, w32, precision=precision, kernel=kernel, trace=False, out_pool=True, **kw)
+        assert np.array_equal(g2["packed"], g["packed"]), "kernels with and without the membrane trace differ"
+        g = dict(g, pooled=g["spikes"], spikes=unpooled)
     if oracle_samples is not None:
         sel = list(oracle_samples)
         spikes = np.ascontiguousarray(np.asarray(spikes)[:, sel])

@@ -29,7 +29,13 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_desc_struct_layout_matches_header():
-    assert ctypes.sizeof(api.tac_layer_desc_t) == 15 * 4 + 2 * 4
+    # sixteen int32 fields in the header's order, then beta and theta
+    assert ctypes.sizeof(api.tac_layer_desc_t) == 16 * 4 + 2 * 4
+    header = open(os.path.join(ROOT, "include", "tac.h")).read()
+    body = header[header.index("typedef struct tac_layer_desc {"):header.index("} tac_layer_desc_t;")]
+    names = [n.strip() for decl in re.findall(r"(?:int32_t|float)\s+([^;]+);", body) for n in decl.split(",")]
+    assert names == [f[0] for f in api.tac_layer_desc_t._fields_]
+    assert api.tac_layer_desc_t.out_format.offset == 15 * 4 and api.tac_layer_desc_t.beta.offset == 16 * 4
 
 
 @pytest.mark.parametrize("mode,K,T_out", [(api.TAC_PER_STEP, 4, 8), (api.TAC_COLLAPSE, 4, 2),
@@ -213,3 +219,25 @@ def test_stack_backward_needs_membranes_and_input_gradients():
     stack[1].desc.T = 5
     grads[1].grad_in = 0x5000
     assert call() == api.TAC_ERR_BAD_SHAPE                 # the stack itself does not chain
+
+
+def test_pooled_output_validation_and_stack_chaining():
+    # MaxPool(2) in the writer (Sec. 5.1 blocks): even output sizes, matrix-core kernels only, no backward pass
+    ok = _desc(H=16, W=32, Cin=32, Cout=64, precision=api.TAC_BF16, out_format=api.TAC_OUT_BITS_MAXPOOL2)
+    assert api.tac_select_kernel(ok) == api.TAC_KERNEL_MFMA
+    assert api.tac_out_shape(ok)[1:] == (16, 32) and api.stored_out_shape(ok)[1:] == (8, 16)
+    L = api.lib()
+    odd = _desc(H=15, W=32, Cin=32, Cout=64, precision=api.TAC_BF16, out_format=api.TAC_OUT_BITS_MAXPOOL2)
+    assert L.tac_select_kernel(ctypes.byref(odd)) == api.TAC_ERR_BAD_SHAPE
+    fp32 = _desc(H=16, W=32, Cin=32, Cout=64, out_format=api.TAC_OUT_BITS_MAXPOOL2)
+    assert L.tac_select_kernel(ctypes.byref(fp32)) == api.TAC_ERR_UNSUPPORTED
+    bad = _desc(H=16, W=32, out_format=7)
+    assert L.tac_select_kernel(ctypes.byref(bad)) == api.TAC_ERR_BAD_PARAM
+    # a stack: the layer behind a pooling writer sees half the size, as plain bits
+    a = api.tac_stack_layer_t(desc=ok)
+    nxt = _desc(T=api.tac_out_shape(ok)[0], H=8, W=16, Cin=64, Cout=32, precision=api.TAC_BF16)
+    arr = (api.tac_stack_layer_t * 2)(a, api.tac_stack_layer_t(desc=nxt))
+    assert api.tac_stack_check(arr) == (api.TAC_OK, -1)
+    wrong = _desc(T=api.tac_out_shape(ok)[0], H=16, W=32, Cin=64, Cout=32, precision=api.TAC_BF16)
+    arr = (api.tac_stack_layer_t * 2)(a, api.tac_stack_layer_t(desc=wrong))
+    assert api.tac_stack_check(arr) == (api.TAC_ERR_BAD_SHAPE, 1)

@@ -1,5 +1,7 @@
 """The allocation-free backward entry point (dL/dY_k in the library's static device array) against
 tac_conv_lif_backward, through the C ABI, on two calls in a row, the second with a smaller input."""
+import gc
+
 import numpy as np
 import pytest
 import torch
@@ -28,10 +30,11 @@ def _case(seed, T, B, Cin, Cout, H, W, mode, K, precision):
     gb = torch.full_like(ref["grad_bias"], float("nan"))
     gi = torch.full_like(ref["grad_in"], float("nan"))
     torch.cuda.synchronize()
+    gc.collect()                               # tensors of earlier tests must not be freed in between
     before = torch.cuda.memory_allocated()
     api.tac_conv_lif_backward_static(desc, sp, wd, vt, g_out, gw, gb, gi, **kw)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_allocated() <= before           # the binding allocated no tensor either
     # dL/dS has no sums over pixels: identical; dW and dbias are float atomics in both calls: equal up to the order of arrival
     assert torch.equal(gi, ref["grad_in"])
     for got, want in ((gw, ref["grad_w"]), (gb, ref["grad_bias"])):
