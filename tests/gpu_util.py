@@ -90,6 +90,12 @@ def check_layer(spikes, w32, *, precision=api.TAC_FP32, kernel=api.TAC_KERNEL_AU
         assert g["kernel"] == expect_kernel
     assert g["pad_ok"], "pad bits of the packed output must be zero"
     theta = float(np.float32(kw["theta"]))
+    if not kw.get("out_pool"):
+        # the kernel without the membrane trace is the one that is timed (on the large matrix-core kernel it is a
+        # variant of its own, with the LIF step under the MFMAs): same spikes and same final membrane, bit for bit
+        g2 = run_gpu(spikes, w32, precision=precision, kernel=kernel, **dict(kw, trace=False, v0=kw.get("v0") if kw.get("v0") is not None else np.zeros_like(g["v_final"])))
+        assert np.array_equal(g2["packed"], g["packed"]), "kernels with and without the membrane trace store different spikes"
+        assert np.array_equal(g2["v_final"], g["v_final"]), "kernels with and without the membrane trace leave different membranes"
     if kw.get("out_pool"):
         # The stored spikes are pooled.  The library's unpooled spikes follow from the membranes it recorded
         # (spike iff V >= theta, the comparison the kernel makes, in fp32): (i) they and the membranes are held

@@ -107,8 +107,8 @@ def test_cfg4_five_layer_stack(mode, K, calls, gain):
     if gain > 1:
         assert min(rates) > 0.01                                             # every layer fires
     stages, lif = api.tac_get_counters()
-    # teacher-forced and free-running calls both count (layer 1 is shared): 9 layer calls
-    assert stages == calls * 9 // 5 and lif == 16 * 9
+    # every call counts: each layer teacher-forced twice (with and without the membrane trace), layers 2-5 free running
+    assert stages == calls * 14 // 5 and lif == 16 * 14
     print("cfg4 B=%d gain %g" % (wl.B, gain), api.MODE_NAMES[mode], K, "\n   " + "\n   ".join(report))
 
 
