@@ -108,12 +108,15 @@ size_t tac_packed_bytes(int32_t T, int32_t B, int32_t C, int32_t H, int32_t W);
 
 /* Which kernel family tac_prepare_weights / tac_conv_lif will use for this
  * layer: TAC_KERNEL_DIRECT or TAC_KERNEL_MFMA, or a negative error.  Host only.
- * MFMA (bf16 implicit GEMM on the matrix cores) needs precision = TAC_BF16 and one of
+ * MFMA (implicit GEMM on the matrix cores) needs precision = TAC_BF16 (but see the last member) and one of
  *   - Cin a multiple of 16, Cout a multiple of 128, W = 32 or 64, packed-bit input (as it is or
  *     with the max pool on load; stride 2 and the max pool only for groups of 1, 2 or 4 frames);
  *   - Cin = 1 or 2, any Cout, W <= 128, packed-bit or float32 input (first layers);
  *   - Cin a multiple of 8 up to 128 (tile of weights and aggregate tile within the LDS), W <= 128
  *     and at most 64 output pixels per row, packed-bit input as it is or with either pool on load;
+ *     this member also takes precision = TAC_FP32 (float32 operands, v_mfma_f32_32x32x2_f32) while the
+ *     float32 weights of a tile of output channels and the aggregate tile fit the LDS (up to about 64 input
+ *     channels);
  * everything else runs on the DIRECT kernel (fp32 vector FMAs, any shape, every input format). */
 int tac_select_kernel(const tac_layer_desc_t* desc);
 

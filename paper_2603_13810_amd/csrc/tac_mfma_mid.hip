@@ -16,6 +16,9 @@
 //   2. the contraction runs over slots kk = tap * Cin + cin in steps of 16: a lane's B fragment is
 //      8 consecutive input channels of one pixel of the window, one 16-byte LDS read;
 //   3. bias, LIF steps (1, or K for TAC-TP), ballot, packed stores.
+// F32: the fp32 layers of these shapes (the second convolution of the rate-coded network in fp32) on the same
+// structure with v_mfma_f32_32x32x2_f32: aggregate tile and weights in LDS as float32, two contraction slots per
+// MFMA (a lane supplies one weight and one aggregate value), products and sums in fp32.
 #include "tac_mfma_common.h"
 
 namespace tac {
@@ -31,26 +34,28 @@ struct MidLayout {
   int rows_in, WP, nks, a_bytes, w_bytes, tab_bytes, total;
 };
 
-__host__ __device__ inline MidLayout mid_layout(int Cin, int S, int W, int nmc) {
+// f32: float32 operands, k-steps of 2 contraction slots (one per lane half) instead of 16 (8 per lane half)
+__host__ __device__ inline MidLayout mid_layout(int Cin, int S, int W, int nmc, bool f32 = false) {
   MidLayout m;
   m.rows_in = (kMidRows - 1) * S + 3;
   m.WP = W + 2;
-  m.nks = (9 * Cin + 15) / 16;
-  m.a_bytes = ((m.rows_in * m.WP * Cin + 8) * 2 + 15) & ~15;       // + 8 zero elements for empty slots
-  m.w_bytes = m.nks * nmc * 64 * 16;
+  m.nks = f32 ? (9 * Cin + 1) / 2 : (9 * Cin + 15) / 16;
+  m.a_bytes = ((m.rows_in * m.WP * Cin + 8) * (f32 ? 4 : 2) + 15) & ~15;       // + 8 zero elements for empty slots
+  m.w_bytes = m.nks * nmc * 64 * (f32 ? 4 : 16);
   m.tab_bytes = (m.nks * 2 * 4 + 15) & ~15;
   m.total = m.a_bytes + m.w_bytes + m.tab_bytes + nmc * 32 * 4;
   return m;
 }
 
-template <int S, int NMC, bool TRACE>
+template <int S, int NMC, bool TRACE, bool F32 = false>
 __global__ __launch_bounds__(kMidThreads, TRACE ? 1 : 2) void mid_kernel(const MfmaParams p) {
+  constexpr int kEl = F32 ? 4 : 2;             // bytes of an operand element
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, h = lane >> 5;
   const int Cin = p.Cin, K = p.K;
-  const MidLayout m = mid_layout(Cin, S, p.W, NMC);
+  const MidLayout m = mid_layout(Cin, S, p.W, NMC, F32);
   const int row_tiles = (p.Ho + kMidRows - 1) / kMidRows;
   const int co_tiles = (p.Cout + NMC * 32 - 1) / (NMC * 32);
   int t = blockIdx.x;
@@ -65,14 +70,14 @@ __global__ __launch_bounds__(kMidThreads, TRACE ? 1 : 2) void mid_kernel(const M
   const int Hs = pool ? 2 * p.H : p.H;
   const int WWs = ((pool ? 2 * p.W : p.W) + 31) >> 5;
 
-  uint16_t* const a_tile = reinterpret_cast<uint16_t*>(lds);
+  uint8_t* const a_tile = lds;
   uint8_t* const w_lds = lds + m.a_bytes;
   int32_t* const tab = reinterpret_cast<int32_t*>(w_lds + m.w_bytes);
   float* const bias_lds = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(tab) + m.tab_bytes);
   uint32_t* const pool_ex = reinterpret_cast<uint32_t*>(lds + m.total);        // only there when the output is pooled
   const int n_a = m.rows_in * m.WP * Cin;
 
-  for (int i = tid; i < n_a + 8; i += kMidThreads) a_tile[i] = 0;          // padding columns, empty-slot zeros
+  for (int i = tid; i < (n_a + 8) * kEl / 4; i += kMidThreads) reinterpret_cast<uint32_t*>(a_tile)[i] = 0u;   // padding columns, empty-slot zeros
   {
     // the tile's weights: [k-step][mc][lane][8] bf16 in global memory, copied as they are
     const u32x4* src = reinterpret_cast<const u32x4*>(p.w + (size_t)co_tile * m.w_bytes);
@@ -81,10 +86,10 @@ __global__ __launch_bounds__(kMidThreads, TRACE ? 1 : 2) void mid_kernel(const M
   // slot table: k-step ks, lane half hh -> byte offset of the 8 channels (tap, cin0) relative to the
   // window's first element, or the zero elements behind the tile for slots beyond 9 Cin
   for (int i = tid; i < m.nks * 2; i += kMidThreads) {
-    const int kk0 = 16 * (i >> 1) + 8 * (i & 1);
+    const int kk0 = F32 ? i : 16 * (i >> 1) + 8 * (i & 1);         // fp32: k-step i / 2, lane half i % 2 -> slot i
     const int tap = kk0 / Cin, cin0 = kk0 - tap * Cin;
     const int ky = tap / 3, kx = tap - ky * 3;
-    tab[i] = tap < 9 ? ((ky * m.WP + kx) * Cin + cin0) * 2 : -1;
+    tab[i] = tap < 9 ? ((ky * m.WP + kx) * Cin + cin0) * kEl : -1;
   }
   if (tid < NMC * 32) bias_lds[tid] = (p.bias && co0 + tid < p.Cout) ? p.bias[co0 + tid] : 0.f;
 
@@ -97,7 +102,7 @@ __global__ __launch_bounds__(kMidThreads, TRACE ? 1 : 2) void mid_kernel(const M
     lg.ok[np] = oy < p.Ho && ox < p.Wo;
     lg.theta[np] = lg.ok[np] ? p.theta : __builtin_inff();
     lg.v_off[np] = (uint32_t)((4 * h * plane + ox) * 4);
-    pix_base[np] = (uint32_t)((((wave * S) * m.WP + (lg.ok[np] ? ox : 0) * S) * Cin) * 2);
+    pix_base[np] = (uint32_t)((((wave * S) * m.WP + (lg.ok[np] ? ox : 0) * S) * Cin) * kEl);
   }
   lg.co_lim = p.Cout - co0 - 4 * h;
   const size_t v_wave = ((size_t)b * p.Cout + co0) * plane + (size_t)oy * p.Wo;
@@ -164,10 +169,19 @@ __global__ __launch_bounds__(kMidThreads, TRACE ? 1 : 2) void mid_kernel(const M
         }
       }
       const float sc = pool ? 0.25f / (float)(1u << kFixShift) : 1.0f / (float)(1u << kFixShift);
-      u32x4 pk;
+      uint8_t* const dst = a_tile + (size_t)((row * m.WP + x + 1) * Cin + c8 * 8) * kEl;
+      if constexpr (F32) {
+        // the fixed-point sum is exact; one rounding to fp32
+        f32x4v lo = {(float)acc[0] * sc, (float)acc[1] * sc, (float)acc[2] * sc, (float)acc[3] * sc};
+        f32x4v hi = {(float)acc[4] * sc, (float)acc[5] * sc, (float)acc[6] * sc, (float)acc[7] * sc};
+        reinterpret_cast<f32x4v*>(dst)[0] = lo;
+        reinterpret_cast<f32x4v*>(dst)[1] = hi;
+      } else {
+        u32x4 pk;
 #pragma unroll
-      for (int c2 = 0; c2 < 4; ++c2) pk[c2] = pack_bf16((float)acc[2 * c2] * sc, (float)acc[2 * c2 + 1] * sc);
-      *reinterpret_cast<u32x4*>(a_tile + ((row * m.WP + x + 1) * Cin + c8 * 8)) = pk;
+        for (int c2 = 0; c2 < 4; ++c2) pk[c2] = pack_bf16((float)acc[2 * c2] * sc, (float)acc[2 * c2 + 1] * sc);
+        *reinterpret_cast<u32x4*>(dst) = pk;
+      }
     }
     __syncthreads();
     // ---- 2. contraction
@@ -178,6 +192,43 @@ __global__ __launch_bounds__(kMidThreads, TRACE ? 1 : 2) void mid_kernel(const M
       for (int np = 0; np < 2; ++np)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mc][np][r] = bias_lds[mc * 32 + 8 * (r >> 2) + 4 * h + (r & 3)];
+    if constexpr (F32) {
+      // Four partial sums per output (k-steps ks % 4), added at the end: the rounding error of a long fp32 sum grows
+      // with its length, and a quarter of the length keeps the membrane within the fp32 bar where one chain of
+      // 9 Cin terms does not.  Rows of at most 32 pixels leave the wave's second pixel block empty: its MFMAs are
+      // skipped (wave-uniform).
+      static_assert(NMC == 1, "fp32: 32-channel tiles (the partial sums take the registers of a second block)");
+      const int nblk = p.Wo > 32 ? 2 : 1;
+      f32x16 part[3][2];
+#pragma unroll
+      for (int i = 0; i < 3; ++i)
+#pragma unroll
+        for (int np = 0; np < 2; ++np)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) part[i][np][r] = 0.f;
+      auto step = [&](int ks, f32x16 (&dst)[2]) {
+        const int off = tab[ks * 2 + h];
+        const float wf = *reinterpret_cast<const float*>(w_lds + (ks * 64 + lane) * 4);
+        const float a0 = *reinterpret_cast<const float*>(a_tile + (off < 0 ? (uint32_t)(n_a * 4) : pix_base[0] + (uint32_t)off));
+        dst[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf, a0, dst[0], 0, 0, 0);
+        if (nblk == 2) {
+          const float a1 = *reinterpret_cast<const float*>(a_tile + (off < 0 ? (uint32_t)(n_a * 4) : pix_base[1] + (uint32_t)off));
+          dst[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf, a1, dst[1], 0, 0, 0);
+        }
+      };
+      int ks = 0;
+      for (; ks + 3 < m.nks; ks += 4) {
+        step(ks, acc[0]);
+        step(ks + 1, part[0]);
+        step(ks + 2, part[1]);
+        step(ks + 3, part[2]);
+      }
+      for (; ks < m.nks; ++ks) step(ks, acc[0]);
+#pragma unroll
+      for (int np = 0; np < 2; ++np)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[0][np][r] = (acc[0][np][r] + part[0][np][r]) + (part[1][np][r] + part[2][np][r]);
+    } else {
     for (int ks = 0; ks < m.nks; ++ks) {
       const int off = tab[ks * 2 + h];
       bf16x8 af[2], wf[NMC];
@@ -193,6 +244,7 @@ __global__ __launch_bounds__(kMidThreads, TRACE ? 1 : 2) void mid_kernel(const M
 #pragma unroll
         for (int np = 0; np < 2; ++np)
           acc[mc][np] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[mc], af[np], acc[mc][np], 0, 0, 0);
+    }
     }
     // ---- 3. LIF steps on Y_k = acc (bias included)
     for (int j = 0; j < p.n_lif; ++j) {
@@ -251,17 +303,34 @@ __global__ void mid_prepare_kernel(const float* __restrict__ w, uint32_t* __rest
   out[i] = pack_bf16(v[0], v[1]);
 }
 
-// 64-channel tiles when the tile's weights and the aggregate tile fit the LDS together, else 32
-int mid_nmc(int Cin, int S, int W, int Cout) {
-  return (Cout > 32 && mid_layout(Cin, S, W, 2).total <= kMidLdsLimit) ? 2 : 1;
+// fp32: OIHW -> [cout tile][k-step][mc][lane] float32: lane l of block mc holds cout 32 (tile nmc + mc) + l % 32 and
+// the contraction slot kk = 2 ks + l / 32 = tap * Cin + cin; slots beyond 9 Cin and channels beyond Cout are zero.
+__global__ void mid_prepare_f32_kernel(const float* __restrict__ w, float* __restrict__ out, int Cin, int Cout, int nmc, int nks,
+                                       int total) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  int t = i;
+  const int l = t & 63; t >>= 6;
+  const int mc = t % nmc; t /= nmc;
+  const int ks = t % nks;
+  const int tile = t / nks;
+  const int co = (tile * nmc + mc) * 32 + (l & 31);
+  const int kk = 2 * ks + (l >> 5);
+  const int tap = kk / Cin, cin = kk - tap * Cin;
+  out[i] = (tap < 9 && co < Cout) ? w[((size_t)co * Cin + cin) * 9 + tap] : 0.f;
 }
 
-template <int S, int NMC>
+// 64-channel tiles when the tile's weights and the aggregate tile fit the LDS together, else 32
+int mid_nmc(int Cin, int S, int W, int Cout, bool f32) {
+  return (!f32 && Cout > 32 && mid_layout(Cin, S, W, 2, f32).total <= kMidLdsLimit) ? 2 : 1;
+}
+
+template <int S, int NMC, bool F32>
 hipError_t mid_launch_t(const MfmaParams& mp, hipStream_t s) {
-  const MidLayout m = mid_layout(mp.Cin, S, mp.W, NMC);
+  const MidLayout m = mid_layout(mp.Cin, S, mp.W, NMC, F32);
   const int co_tiles = (mp.Cout + NMC * 32 - 1) / (NMC * 32);
   const dim3 grid(((mp.Ho + kMidRows - 1) / kMidRows) * co_tiles * mp.B);
-  auto kern = mp.v_trace ? &mid_kernel<S, NMC, true> : &mid_kernel<S, NMC, false>;
+  auto kern = mp.v_trace ? &mid_kernel<S, NMC, true, F32> : &mid_kernel<S, NMC, false, F32>;
   const int lds = m.total + (mp.out_pool ? pool_exchange_bytes(kMidRows, NMC * 32, 1) : 0);
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -275,22 +344,32 @@ hipError_t mid_launch_t(const MfmaParams& mp, hipStream_t s) {
 }  // namespace
 
 bool mfma_mid_supported(const tac_layer_desc_t& d) {
-  if (d.precision != TAC_BF16 || d.in_format == TAC_IN_F32) return false;
+  if (d.in_format == TAC_IN_F32) return false;
+  const bool f32 = d.precision == TAC_FP32;
   if (d.Cin % 8 != 0 || d.Cin > kMidMaxCin) return false;
   if (d.W > kMidMaxW || (d.W + 2 - 3) / d.stride + 1 > kMidMaxWo) return false;
-  return mid_layout(d.Cin, d.stride, d.W, mid_nmc(d.Cin, d.stride, d.W, d.Cout)).total <= kMidLdsLimit;
+  return mid_layout(d.Cin, d.stride, d.W, mid_nmc(d.Cin, d.stride, d.W, d.Cout, f32), f32).total <= kMidLdsLimit;
 }
 
 size_t mfma_mid_weight_bytes(const tac_layer_desc_t& d) {
-  const int nmc = mid_nmc(d.Cin, d.stride, d.W, d.Cout);
+  const bool f32 = d.precision == TAC_FP32;
+  const int nmc = mid_nmc(d.Cin, d.stride, d.W, d.Cout, f32);
   const int tiles = (d.Cout + nmc * 32 - 1) / (nmc * 32);
-  return (size_t)tiles * mid_layout(d.Cin, d.stride, d.W, nmc).w_bytes;
+  return (size_t)tiles * mid_layout(d.Cin, d.stride, d.W, nmc, f32).w_bytes;
 }
 
 hipError_t mfma_mid_prepare(const tac_layer_desc_t& d, const float* w_oihw, void* w_prepared, hipStream_t s) {
-  const int nmc = mid_nmc(d.Cin, d.stride, d.W, d.Cout);
-  const int nks = (9 * d.Cin + 15) / 16;
+  const bool f32 = d.precision == TAC_FP32;
+  const int nmc = mid_nmc(d.Cin, d.stride, d.W, d.Cout, f32);
   const int tiles = (d.Cout + nmc * 32 - 1) / (nmc * 32);
+  if (f32) {
+    const int nks2 = (9 * d.Cin + 1) / 2;
+    const int total = tiles * nks2 * nmc * 64;
+    hipLaunchKernelGGL(mid_prepare_f32_kernel, dim3((total + 255) / 256), dim3(256), 0, s, w_oihw,
+                       static_cast<float*>(w_prepared), d.Cin, d.Cout, nmc, nks2, total);
+    return hipGetLastError();
+  }
+  const int nks = (9 * d.Cin + 15) / 16;
   const int total = tiles * nks * nmc * 64 * 4;
   hipLaunchKernelGGL(mid_prepare_kernel, dim3((total + 255) / 256), dim3(256), 0, s, w_oihw,
                      static_cast<uint32_t*>(w_prepared), d.Cin, d.Cout, nmc, nks, total);
@@ -309,9 +388,10 @@ hipError_t mfma_mid_launch(const LayerParams& p, hipStream_t s) {
     mp.wq[j] = j < p.K ? (uint32_t)(q + 0.5) : 0u;
     mp.wjd[j] = p.wjd[j];
   }
-  const int nmc = mid_nmc(p.Cin, p.stride, p.W, p.Cout);
-  if (p.stride == 1) return nmc == 1 ? mid_launch_t<1, 1>(mp, s) : mid_launch_t<1, 2>(mp, s);
-  return nmc == 1 ? mid_launch_t<2, 1>(mp, s) : mid_launch_t<2, 2>(mp, s);
+  const int nmc = mid_nmc(p.Cin, p.stride, p.W, p.Cout, !p.bf16);
+  if (!p.bf16) return p.stride == 1 ? mid_launch_t<1, 1, true>(mp, s) : mid_launch_t<2, 1, true>(mp, s);
+  if (p.stride == 1) return nmc == 1 ? mid_launch_t<1, 1, false>(mp, s) : mid_launch_t<1, 2, false>(mp, s);
+  return nmc == 1 ? mid_launch_t<2, 1, false>(mp, s) : mid_launch_t<2, 2, false>(mp, s);
 }
 
 }  // namespace tac

@@ -229,7 +229,7 @@ def test_pooled_output_validation_and_stack_chaining():
     L = api.lib()
     odd = _desc(H=15, W=32, Cin=32, Cout=64, precision=api.TAC_BF16, out_format=api.TAC_OUT_BITS_MAXPOOL2)
     assert L.tac_select_kernel(ctypes.byref(odd)) == api.TAC_ERR_BAD_SHAPE
-    fp32 = _desc(H=16, W=32, Cin=32, Cout=64, out_format=api.TAC_OUT_BITS_MAXPOOL2)
+    fp32 = _desc(H=16, W=32, Cin=3, Cout=64, out_format=api.TAC_OUT_BITS_MAXPOOL2)      # vector kernel: no pooled output
     assert L.tac_select_kernel(ctypes.byref(fp32)) == api.TAC_ERR_UNSUPPORTED
     bad = _desc(H=16, W=32, out_format=7)
     assert L.tac_select_kernel(ctypes.byref(bad)) == api.TAC_ERR_BAD_PARAM

@@ -41,8 +41,9 @@ def test_cfg2_two_layer_rate_coded(K, precision):
     first = api.TAC_KERNEL_MFMA if precision == api.TAC_BF16 else api.TAC_KERNEL_DIRECT
     p1, g1, r1 = check_layer(s, w1, K=K, mode=api.TAC_COLLAPSE, expect_kernel=first, **kw)
     assert r1[0].shape == (wl.T // K, B, 32, 28, 28) and r1[0].sum() > 0
-    # layer 2 on the collapsed sequence: 2x2 mean pool while loading, 32 -> 64 at 14x14, K2 = 1
-    p2, g2, r2 = check_layer(r1[0], w2, K=1, mode=api.TAC_COLLAPSE, pool2=True, expect_kernel=first, **kw)
+    # layer 2 on the collapsed sequence: 2x2 mean pool while loading, 32 -> 64 at 14x14, K2 = 1: on the matrix cores
+    # in both precisions (fp32: v_mfma_f32_32x32x2_f32)
+    p2, g2, r2 = check_layer(r1[0], w2, K=1, mode=api.TAC_COLLAPSE, pool2=True, expect_kernel=api.TAC_KERNEL_MFMA, **kw)
     assert r2[0].shape == (wl.T // K, B, 64, 14, 14) and r2[0].sum() > 0
     # free running: the GPU's own layer-1 spikes into layer 2
     g2f = run_gpu(g1["spikes"], w2, K=1, mode=api.TAC_COLLAPSE, pool2=True, beta=wl.beta, theta=wl.theta,

@@ -306,3 +306,36 @@ def test_in_between_kernel(shape, mode, K):
                               bias=bias, v0=v0, expect_kernel=api.TAC_KERNEL_MFMA)
     assert ref[0].sum() > 0
     print("in-between kernel", shape, api.MODE_NAMES[mode], K, par)
+
+
+# ---- the in-between kernel in fp32 (float32 operands on the matrix cores), held to the fp32 bar of 1e-5
+# (Cin, Cout, H, W, stride, pool)
+MID_F32_SHAPES = [(32, 64, 14, 14, 1, True), (8, 32, 9, 50, 1, False), (16, 96, 11, 64, 2, False), (24, 20, 7, 20, 1, "max"),
+                  (40, 64, 6, 33, 1, True), (32, 64, 10, 40, 1, False)]
+
+
+@pytest.mark.parametrize("shape", MID_F32_SHAPES)
+@pytest.mark.parametrize("mode,K", [(api.TAC_PER_STEP, 1), (api.TAC_COLLAPSE, 2), (api.TAC_PRESERVE, 4), (api.TAC_COLLAPSE, 3), (api.TAC_COLLAPSE, 8)])
+def test_in_between_kernel_fp32(shape, mode, K):
+    Cin, Cout, H, W, stride, pool = shape
+    r = _rng(6500 + Cin + Cout + H + W + stride + K)
+    f = 2 if pool else 1
+    s = (r.random((16, 2, Cin, f * H, f * W)) < 0.15).astype(np.uint8)
+    w = synth.kaiming_normal(92, Cout, Cin) * np.float32(1.5)
+    bias = (r.standard_normal(Cout) * 0.1).astype(np.float32)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    v0 = (r.standard_normal((2, Cout, Ho, Wo)) * 0.3).astype(np.float32)
+    par, g, ref = check_layer(s, w, K=K, beta=0.9, theta=1.0, mode=mode, stride=stride, pool2=pool, precision=api.TAC_FP32,
+                              bias=bias, v0=v0, expect_kernel=api.TAC_KERNEL_MFMA)
+    assert ref[0].sum() > 0 and par.max_err < 1e-5
+    print("in-between kernel fp32", shape, api.MODE_NAMES[mode], K, par)
+
+
+def test_fp32_layers_outside_the_in_between_shapes_stay_on_the_vector_kernel():
+    mk = lambda **kw: api.make_desc(8, 2, kw.pop("Cin", 32), 16, kw.pop("W", 16), kw.pop("Cout", 64), K=2, beta=0.9, theta=1.0,
+                                    mode=api.TAC_COLLAPSE, precision=api.TAC_FP32, **kw)
+    assert api.tac_select_kernel(mk()) == api.TAC_KERNEL_MFMA
+    assert api.tac_select_kernel(mk(Cin=1)) == api.TAC_KERNEL_DIRECT            # first layers
+    assert api.tac_select_kernel(mk(Cin=12)) == api.TAC_KERNEL_DIRECT           # not a multiple of 8
+    assert api.tac_select_kernel(mk(Cin=128, Cout=128)) == api.TAC_KERNEL_DIRECT   # float32 weights of the tile exceed the LDS
+    assert api.tac_select_kernel(mk(kernel=api.TAC_KERNEL_DIRECT)) == api.TAC_KERNEL_DIRECT
