@@ -410,8 +410,11 @@ __device__ __forceinline__ void lds_barrier() {
 // AGG: the aggregation stage alone (a measurement aid): spike loading, staging and the A tiles of every chunk are
 // formed exactly as in the layer, the weight copies, the MFMAs and the LIF steps are left out, and the workgroup
 // writes one 64-bit sum of the A-tile words it formed (see a_write_packed) to p.out instead of spikes.
+// The 64-channel tiles ask for two waves per SIMD (256 registers each, which they fit without scratch): where
+// their LDS allows it two workgroups share a compute unit, and with the wave priorities below (high while a wave
+// feeds the matrix cores, low during its LIF steps) one workgroup's LIF steps run under the other's MFMAs.
 template <int KT, int WIN, int S, bool TRACE, bool MP, int MC, int NP, bool AGG = false>
-__global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
+__global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_kernel(const MfmaParams p) {
   using G = Geo<WIN, S, NP>;
   // MC = 32-channel blocks per workgroup and wave: 4 (128 output channels), or 2 (64) for layers
   // whose grid would otherwise leave compute units idle.  The prepared weights are laid out
@@ -730,6 +733,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
     // at its first use, in every iteration, and that wait would also cover the loads the loop
     // itself keeps in flight.
     __builtin_amdgcn_s_waitcnt(0x0f70);         // vmcnt(0), other counters untouched
+    __builtin_amdgcn_s_setprio(3);              // MFMA phase: ahead of a co-resident workgroup's LIF steps
 #pragma unroll
     for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
@@ -738,6 +742,7 @@ __global__ __launch_bounds__(kThreads) void mfma_kernel(const MfmaParams p) {
         for (int r = 0; r < 16; ++r) acc[mc][np][r] = 0.f;
 
     for (int c = 0; c < NC; ++c, ++s) chunk_iteration(s);
+    __builtin_amdgcn_s_setprio(0);
     if constexpr (AGG) continue;
 
     // ---- LIF epilogue on Y_k = acc + bias
@@ -852,6 +857,11 @@ inline int compute_units() {
 template <int KT, int WIN, int S, bool TRACE, bool MP>
 hipError_t launch_traced(const MfmaParams& mp, hipStream_t s) {
   const int kComputeUnits = compute_units();
+  // TAC-TP with groups of 4 or 8 frames: K LIF steps of pure vector work follow every group's MFMAs, so two
+  // workgroups of 64-channel tiles per compute unit (where two of them fit the LDS) beat one of 128 channels
+  if constexpr (!MP && (KT == 4 || KT == 8) && 2 * Geo<WIN, S>::lds_bytes(KT, 2) <= kLdsLimit) {
+    if (mp.n_lif >= 4 && !mp.out_pool) return launch_tile<KT, WIN, S, TRACE, MP, 2>(mp, s);
+  }
   if constexpr (!MP) {
     const int row_tiles = (mp.Ho + Geo<WIN, S>::kTileRows - 1) / Geo<WIN, S>::kTileRows;
     if ((long long)row_tiles * (mp.Cout / kCoutTile) * mp.B < kComputeUnits) {
