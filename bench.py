@@ -52,6 +52,14 @@ CPU_SAMPLES_ROUNDED = 4        # of those, the samples the bf16-rounded oracle r
 PAPER_CONTEXT = "TAC training speed-ups 13.8x (Apple M3 Max) and 11.0x (NVIDIA V100), other hardware"
 
 
+def kernel_source_sha256():
+    """Hash of the sources the headline kernel is compiled from."""
+    h = hashlib.sha256()
+    for f in ("tac_mfma_kernel.h", "tac_mfma_common.h"):
+        h.update(open(os.path.join(ROOT, "paper_2603_13810_amd", "csrc", f), "rb").read())
+    return h.hexdigest()
+
+
 def measured_traffic(workload, mode, K):
     """HBM bytes of one launch of the headline kernel from the rocprofv3 --pmc summary under profiles/
     (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size).  The figures belong to one version of
@@ -64,10 +72,9 @@ def measured_traffic(workload, mode, K):
     m = re.search(r"bench-traffic:\s*fetch_bytes=(\d+)\s+write_bytes=(\d+)\s+kernel_source_sha256=([0-9a-f]{64})", text)
     if not m:
         return None
-    src = os.path.join(ROOT, "paper_2603_13810_amd", "csrc", "tac_mfma.hip")
-    sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    sha = kernel_source_sha256()
     if sha != m.group(3):
-        print("bench.py: csrc/tac_mfma.hip has changed since the counters in %s were taken: roofline.traffic is null"
+        print("bench.py: the kernel source has changed since the counters in %s were taken: roofline.traffic is null"
               % os.path.relpath(path, ROOT), file=sys.stderr)
         return None
     return int(m.group(1)) + int(m.group(2))
