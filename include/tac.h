@@ -73,7 +73,8 @@ enum {
                                or a tensor too large for 32-bit word indexing           */
   TAC_ERR_BAD_K = -3,       /* K < 1 or K > TAC_MAX_K                                    */
   TAC_ERR_BAD_PARAM = -4,   /* beta outside [0,1], theta <= 0 or not finite, bad enum   */
-  TAC_ERR_UNSUPPORTED = -5, /* valid request that the chosen kernel family cannot run   */
+  TAC_ERR_UNSUPPORTED = -5, /* valid request that the chosen kernel family cannot run, or
+                               stored input rows wider than 2048 pixels                 */
   TAC_ERR_HIP = -6,         /* a HIP call failed; text via tac_last_error()             */
   TAC_ERR_ALIGN = -7,       /* a device pointer is not aligned as documented            */
   TAC_ERR_NEED_STATE = -8   /* K does not divide T and v_inout is NULL (see tac_conv_lif) */

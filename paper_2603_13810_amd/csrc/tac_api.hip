@@ -30,6 +30,8 @@ int hip_fail(hipError_t e, const char* where) {
   return TAC_ERR_HIP;
 }
 
+constexpr int kMaxRowPixels = 2048;
+
 // Shape / parameter checks shared by every entry point.  Returns TAC_OK or the error.
 int validate(const tac_layer_desc_t* d) {
   if (!d) return TAC_ERR_NULL;
@@ -57,6 +59,8 @@ int validate(const tac_layer_desc_t* d) {
                                                       : (int64_t)d->B * d->Cin * (d->H * f) * ((d->W * f + 31) / 32);
   if (out_slab >= (1LL << 31) || in_slab >= (1LL << 31)) return TAC_ERR_BAD_SHAPE;
   if (d->B > 65535) return TAC_ERR_BAD_SHAPE;
+  // the input rows under one strip of output words of one channel have to fit the vector kernel's LDS tile
+  if (d->W * f > kMaxRowPixels) return TAC_ERR_UNSUPPORTED;
   return TAC_OK;
 }
 

@@ -75,6 +75,7 @@ def test_packed_bytes():
     (dict(mode=7), api.TAC_ERR_BAD_PARAM), (dict(precision=3), api.TAC_ERR_BAD_PARAM),
     (dict(in_format=4), api.TAC_ERR_BAD_PARAM), (dict(kernel=9), api.TAC_ERR_BAD_PARAM),
     (dict(B=70000), api.TAC_ERR_BAD_SHAPE),
+    (dict(W=2049), api.TAC_ERR_UNSUPPORTED), (dict(W=1025, in_format=api.TAC_IN_BITS_POOL2), api.TAC_ERR_UNSUPPORTED),
 ])
 def test_invalid_descriptions_are_rejected_before_any_launch(kw, status):
     L = api.lib()
