@@ -395,6 +395,30 @@ __device__ __forceinline__ void expand_step(const MfmaParams& p, const uint8_t* 
   }
 }
 
+// N (1 or 2) direct-to-LDS loads of 16 bytes per lane from one global address to one LDS base address, the n-th
+// with the immediate offset OFF0 + 1024 n added to both.  Written as an assembly statement on purpose: while a
+// direct-to-LDS load that the compiler knows of is pending, it turns every wait on the LDS counter into a wait for
+// zero, and in the chunk loop one always is, so each tap would wait for the LDS reads and writes it has only just
+// issued.  The compiler therefore does not know of these loads at all: the reader of what they write waits for
+// vmcnt(0) (lds_dma_wait) in front of the workgroup barrier that separates writer and reader, and the kernel waits
+// once more before it ends.  The waits the compiler places for its own loads count these loads too, which only
+// makes them stricter.  M0 holds the LDS address; one wait state between its write and the load.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+template <int N, int OFF0>
+__device__ __forceinline__ void lds_dma16(const void* gsrc, uint32_t lds_base) {
+  static_assert(N == 1 || N == 2, "one or two loads");
+  if constexpr (N == 1)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2"
+                 :: "v"(gsrc), "s"(lds_base), "n"(OFF0) : "m0", "memory");
+  else
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2\n\t"
+                 "global_load_lds_dwordx4 %0, off offset:%3"
+                 :: "v"(gsrc), "s"(lds_base), "n"(OFF0), "n"(OFF0 + 1024) : "m0", "memory");
+}
+#pragma clang diagnostic pop
+__device__ __forceinline__ void lds_dma_wait() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0), other counters untouched
+
 // Workgroup barrier that orders LDS traffic only: the compiler waits for this wave's LDS
 // accesses and for its direct-to-LDS loads, but leaves ordinary global loads in flight.
 __device__ __forceinline__ void lds_barrier() {
@@ -534,20 +558,32 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
   const uint32_t w_lane_off = (MC == 4 ? (uint32_t)(wave * (kWBlocks * 1024)) : 0u) + (uint32_t)lane * 16u;
   const uint32_t w_half_off = (uint32_t)(co_tile & 1) * 2048u;       // MC == 2: which half of the 128-channel tile
   auto weights_to_lds = [&](const uint8_t* src, uint8_t* w_dst, auto i0_, auto i1_) {
-    if constexpr (!AGG) static_for<decltype(i0_)::value, decltype(i1_)::value>([&](auto i_) {
-      constexpr int i = decltype(i_)::value;
-      if constexpr (MC == 4) {
-        __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (i / 4) * 4096 + w_lane_off),
-                                         (lds_void_ptr)(w_dst + wave * (kWBlocks * 1024) + (i / 4) * 4096), 16,
-                                         (i % 4) * 1024, 0);
-      } else if constexpr (i < 5) {
-        const int blk = wave + 4 * i;              // 0 .. 17 (the fifth round only for waves 0 and 1)
-        if (i < 4 || wave < 2)
-          __builtin_amdgcn_global_load_lds(
-              (global_void_ptr)(src + (uint32_t)((blk >> 1) * 4096 + (blk & 1) * 1024) + w_half_off + w_lane_off),
-              (lds_void_ptr)(w_dst + blk * 1024), 16, 0, 0);
+    constexpr int i0 = decltype(i0_)::value, i1 = decltype(i1_)::value;
+    if constexpr (AGG) return;
+    const uint32_t dst = (uint32_t)(uintptr_t)(lds_void_ptr)w_dst;
+    if constexpr (MC == 4) {
+      // blocks i0 .. i1-1 of the wave's nine; blocks 4 g .. 4 g + 3 share the addresses of group g
+      static_assert(i1 - i0 <= 2 || (i0 == 0 && i1 == 9), "one or two blocks per call, or all nine");
+      if constexpr (i1 - i0 > 2) {
+        static_for<0, 4>([&](auto h_) {
+          constexpr int h = decltype(h_)::value;
+          lds_dma16<2, (2 * h % 4) * 1024>(src + (2 * h / 4) * 4096 + w_lane_off, dst + wave * (kWBlocks * 1024) + (2 * h / 4) * 4096);
+        });
+        lds_dma16<1, 0>(src + 2 * 4096 + w_lane_off, dst + wave * (kWBlocks * 1024) + 2 * 4096);
+      } else {
+        static_assert(i0 / 4 == (i1 - 1) / 4, "both blocks in one group");
+        lds_dma16<i1 - i0, (i0 % 4) * 1024>(src + (i0 / 4) * 4096 + w_lane_off, dst + wave * (kWBlocks * 1024) + (i0 / 4) * 4096);
       }
-    });
+    } else {
+      static_for<i0, i1>([&](auto i_) {
+        constexpr int i = decltype(i_)::value;
+        if constexpr (i < 5) {
+          const int blk = wave + 4 * i;              // 0 .. 17 (the fifth round only for waves 0 and 1)
+          if (i < 4 || wave < 2)
+            lds_dma16<1, 0>(src + (uint32_t)((blk >> 1) * 4096 + (blk & 1) * 1024) + w_half_off + w_lane_off, dst + blk * 1024);
+        }
+      });
+    }
   };
   constexpr std::integral_constant<int, 0> c0;
   constexpr std::integral_constant<int, 2> c2;
@@ -591,6 +627,7 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
     stage_load<KMAX, NG, MP, G::kWW>(wd, plan, cur.spk, fstride, K);
     advance(cur);                               // chunk 3
   }
+  lds_dma_wait();                               // the weights of chunks 0 and 1
   __syncthreads();
 
   const int w_frag_off = lane * 16;                                  // + tap*kWTap + mc*1024
@@ -626,11 +663,23 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
     uint8_t* w_next = lds + G::kLdsW + (PAR ^ 1) * kWBufL;
     const uint8_t* words_next = words0 + (PAR ^ 1) * words_bytes;    // words of chunk s+1 (read now)
     uint8_t* words_nn = words0 + PAR * words_bytes;                  // words of chunk s+2 (written at tap 7)
-    StepRegs<KT> sr;
+    StepRegs<(KT > 0 ? KT : 1)> sr[2];      // loader step i uses set i & 1
 #pragma unroll
     for (int mc = 0; mc < MC; ++mc) wf[0][mc] = wf[1][mc];
 #pragma unroll
     for (int np = 0; np < NP; ++np) af[0][np] = af[1][np];
+    // Loader pipeline: slot i reads the words of step i into register set i & 1, looks up the table entries of step
+    // i-1 in the other set and writes step i-2 (one frame: no table, the write follows the read by one slot).  With
+    // one slot per tap the slot's LDS reads come first in the tap's instruction stream and its write last, so that
+    // what a tap reads from LDS has returned long before the next tap uses it; with several slots per tap they run
+    // one after the other (a slot's look-up must not overtake the write of the slot before).
+    auto loader_reads = [&](int i) {
+      if constexpr (KT > 0) {
+        constexpr int kD = KT == 1 ? 1 : 2;
+        if (i < G::kSteps) read_words<G, KT>(sr[i & 1], words_next, lane, q, i);
+        if (kD == 2 && i >= 1 && i - 1 < G::kSteps) lookup<KT>(sr[(i - 1) & 1], lut, lane);
+      }
+    };
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) {
       const int slot = tap & 1;
@@ -644,6 +693,7 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
         weights_to_lds(w_n2, const_cast<uint8_t*>(w_cur), c0, c2);
         __builtin_amdgcn_sched_barrier(0);
         stage_load<KMAX, NG, MP, G::kWW>(wd, plan, cur.spk, fstride, K, 0, kLPT);
+        if constexpr (G::kSlotsPerTap == 1) loader_reads(tap);
         fetch(a_next, w_next, 0, slot ^ 1);
       } else {
         if (tap <= 5) {
@@ -657,6 +707,7 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
           }
           if (tap <= 4) stage_load<KMAX, NG, MP, G::kWW>(wd, plan, spk_n2, fstride, K, (tap + 1) * kLPT, (tap + 2) * kLPT);
         }
+        if constexpr (G::kSlotsPerTap == 1) loader_reads(tap);
         fetch(a_cur, w_cur, tap + 1, slot ^ 1);
       }
       if constexpr (!AGG) {
@@ -668,15 +719,12 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
       }
       // the tile built during the last chunk repeats that chunk (nothing follows it) and is not counted
       uint64_t* const agg_s = (AGG && s + 1 < total) ? agg : nullptr;
-      // loader: pipeline slot i writes step i-2, looks up step i-1 and reads the words of step i
-      // (one frame: no table, the write follows the read by one slot)
 #pragma unroll
       for (int i = tap * G::kSlotsPerTap; i < (tap + 1) * G::kSlotsPerTap; ++i) {
         if constexpr (KT > 0) {
           constexpr int kD = KT == 1 ? 1 : 2;
-          if (i >= kD && i - kD < G::kSteps) write_a<G, KT>(sr, a_next, lane, q, i - kD, agg_s);
-          if (kD == 2 && i >= 1 && i - 1 < G::kSteps) lookup<KT>(sr, lut, lane);
-          if (i < G::kSteps) read_words<G, KT>(sr, words_next, lane, q, i);
+          if constexpr (G::kSlotsPerTap > 1) loader_reads(i);
+          if (i >= kD && i - kD < G::kSteps) write_a<G, KT>(sr[(i - kD) & 1], a_next, lane, q, i - kD, agg_s);
         } else {
           if (i < G::kSteps) expand_step<G, KT>(p, words_next, lut, a_next, K, lane, q, i, agg_s);
         }
@@ -696,6 +744,7 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
       }
       __builtin_amdgcn_sched_barrier(0);
       if (tap == 7) {
+        lds_dma_wait();                         // this wave's part of the next chunk's weights
         lds_barrier();
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -789,7 +838,8 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
       }
     }
   }
-  __syncthreads();                            // drains the last direct-to-LDS loads before the waves end
+  lds_dma_wait();
+  __syncthreads();                            // the last direct-to-LDS loads have landed before the waves end
 
   if constexpr (AGG) {
     // sum over the workgroup: lanes by shuffles, the four waves through LDS (everything else in LDS is dead now)
