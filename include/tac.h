@@ -245,6 +245,19 @@ typedef struct tac_backward_desc {
   int32_t surrogate;      /* TAC_SG_FAST_SIGMOID / TAC_SG_ARCTAN                                */
   int32_t detach_reset;   /* != 0: no gradient through the spike in the reset term              */
   float alpha;            /* surrogate sharpness, > 0                                           */
+  /* The K input frames of a group receive the same gradient up to the factor beta^(Kg-1-j)
+   * (dL/dS_{kK+j} = beta^(Kg-1-j) dL/dA_k, Eq. 2), so between two layers of a stack it can cross
+   * memory once per group instead of once per frame (1/K of the bytes written by this layer and
+   * read by the layer before).  Both fields 0: gradients per frame / per step, as documented below. */
+  int32_t grad_in_per_group;    /* != 0: grad_in holds dL/dA_k, float32 [G][B][Cin][H][W], G = ceil(T/K) (T for
+                                   per-step), without the factor.  Not with a pool on load (the route through a
+                                   max pool differs from frame to frame): TAC_ERR_UNSUPPORTED.               */
+  int32_t grad_out_group_K;     /* Kc >= 2: grad_out holds the dL/dA_k of the layer AFTER this one, which groups
+                                   this layer's T_out output steps by Kc: float32 [ceil(T_out/Kc)][B][Cout][Ho][Wo];
+                                   dL/ds_n = beta_c^(Kg-1-j) grad_out[n / Kc], j = n % Kc, Kg = Kc or, in a
+                                   shorter last group, T_out % Kc.  0 or 1: grad_out per output step.
+                                   Above TAC_MAX_K: TAC_ERR_BAD_K.                                           */
+  float grad_out_group_beta;    /* beta_c, the leak of that next layer, in [0, 1]                            */
 } tac_backward_desc_t;
 
 /*   input      DEVICE, read-only: what the forward pass read, in desc->in_format
@@ -255,7 +268,8 @@ typedef struct tac_backward_desc {
  *   grad_w     DEVICE, written (not accumulated), float32 [Cout][Cin][3][3]
  *   grad_bias  DEVICE, written, float32 [Cout], or NULL
  *   grad_in    DEVICE, written, float32 [T][B][Cin][H][W]: dL/d(input frames), the grad_out of the
- *              layer before; NULL for a first layer (skips that stage).  With a pool on load it is the
+ *              layer before ([G][B][Cin][H][W] with bwd->grad_in_per_group); NULL for a first layer
+ *              (skips that stage).  With a pool on load it is the
  *              gradient of the unpooled frames, [T][B][Cin][2H][2W]: a quarter of the pooled pixel's
  *              gradient to each input of the mean pool; all of it to the first maximal input of the
  *              max pool's window in row-major order (the first set bit, else the first input)
@@ -296,7 +310,11 @@ typedef struct tac_stack_grads {
 /*   layers, n_layers   the stack as given to tac_stack_forward (descriptions, v_trace and the packed
  *                      outputs it wrote)
  *   grads              n_layers entries, see above
- *   bwd                surrogate, alpha, detach_reset for every layer
+ *   bwd                surrogate, alpha, detach_reset for every layer; grad_in_per_group != 0: every layer l >= 1
+ *                      that groups frames (TAC or TAC-TP with K > 1) and has no pool on load writes its input
+ *                      gradient once per group (grads[l].grad_in is then [G_l][B][Cin][H][W]) and layer l-1
+ *                      reads it that way; the other layers exchange gradients per frame as before.  The
+ *                      grad_out_group_* fields are ignored (the stack sets them per layer).
  *   input              DEVICE: the packed frames layer 0 read
  *   grad_out_last      DEVICE, float32 [T_out][B][Cout][Ho][Wo] of the last layer: dL/d(its spikes)
  * Enqueued on `stream` in order; allocates and synchronises nothing.  Errors as tac_stack_check and

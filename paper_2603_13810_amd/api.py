@@ -248,12 +248,16 @@ TAC_SG_FAST_SIGMOID, TAC_SG_ARCTAN = 0, 1
 
 
 class tac_backward_desc_t(ctypes.Structure):
-    _fields_ = [("surrogate", ctypes.c_int32), ("detach_reset", ctypes.c_int32), ("alpha", ctypes.c_float)]
+    _fields_ = [("surrogate", ctypes.c_int32), ("detach_reset", ctypes.c_int32), ("alpha", ctypes.c_float),
+                ("grad_in_per_group", ctypes.c_int32), ("grad_out_group_K", ctypes.c_int32), ("grad_out_group_beta", ctypes.c_float)]
 
 
 def tac_conv_lif_backward(desc, spikes_packed, w_oihw, v_trace, grad_out, *, surrogate=TAC_SG_FAST_SIGMOID, alpha=25.0,
-                          detach_reset=False, want_input_grad=True, stream=None):
-    """Backward pass of one layer.  Device tensors; returns dict(grad_y, grad_w, grad_bias, grad_in)."""
+                          detach_reset=False, want_input_grad=True, grad_in_per_group=False, grad_out_group_K=0,
+                          grad_out_group_beta=0.0, stream=None):
+    """Backward pass of one layer.  Device tensors; returns dict(grad_y, grad_w, grad_bias, grad_in).
+    grad_in_per_group: grad_in is dL/dA_k [G,B,Cin,H,W]; grad_out_group_K = Kc >= 2: grad_out is the next layer's
+    dL/dA_k [ceil(T_out/Kc),B,Cout,Ho,Wo] and grad_out_group_beta that layer's beta."""
     import torch
     T_out, Ho, Wo = tac_out_shape(desc)
     K = 1 if desc.mode == TAC_PER_STEP else min(desc.K, desc.T)
@@ -266,14 +270,18 @@ def tac_conv_lif_backward(desc, spikes_packed, w_oihw, v_trace, grad_out, *, sur
         raise ValueError("the input tensor does not match the description")
     if tuple(w_oihw.shape) != (desc.Cout, desc.Cin, 3, 3):
         raise ValueError("w_oihw must be [Cout,Cin,3,3]")
-    for name, t in (("v_trace", v_trace), ("grad_out", grad_out)):
-        if tuple(t.shape) != (T_out, desc.B, desc.Cout, Ho, Wo):
-            raise ValueError("%s must be [T_out,B,Cout,Ho,Wo]" % name)
+    steps_go = -(-T_out // grad_out_group_K) if grad_out_group_K > 1 else T_out
+    for name, t, n in (("v_trace", v_trace, T_out), ("grad_out", grad_out, steps_go)):
+        if tuple(t.shape) != (n, desc.B, desc.Cout, Ho, Wo):
+            raise ValueError("%s must be [%d,B,Cout,Ho,Wo]" % (name, n))
     grad_y = torch.empty((G, desc.B, desc.Cout, Ho, Wo), dtype=torch.float32, device=dev)
     grad_w = torch.empty((desc.Cout, desc.Cin, 3, 3), dtype=torch.float32, device=dev)
     grad_bias = torch.empty((desc.Cout,), dtype=torch.float32, device=dev)
-    grad_in = torch.empty((desc.T, desc.B, desc.Cin, desc.H * f, desc.W * f), dtype=torch.float32, device=dev) if want_input_grad else None
-    bwd = tac_backward_desc_t(surrogate=surrogate, detach_reset=int(bool(detach_reset)), alpha=alpha)
+    grad_in = (torch.empty((G if grad_in_per_group else desc.T, desc.B, desc.Cin, desc.H * f, desc.W * f), dtype=torch.float32, device=dev)
+               if want_input_grad else None)
+    bwd = tac_backward_desc_t(surrogate=surrogate, detach_reset=int(bool(detach_reset)), alpha=alpha,
+                              grad_in_per_group=int(bool(grad_in_per_group)), grad_out_group_K=int(grad_out_group_K),
+                              grad_out_group_beta=float(grad_out_group_beta))
     _check(lib().tac_conv_lif_backward(ctypes.byref(desc), ctypes.byref(bwd), _dev_ptr(spikes_packed, None, "spikes_packed"),
                                        _dev_ptr(w_oihw, torch.float32, "w_oihw"), _dev_ptr(v_trace, torch.float32, "v_trace"),
                                        _dev_ptr(grad_out, torch.float32, "grad_out"), _dev_ptr(grad_y), _dev_ptr(grad_w),
@@ -361,10 +369,12 @@ class tac_stack_grads_t(ctypes.Structure):
 
 
 def tac_stack_backward(stack, weights, input, grad_out_last, *, surrogate=TAC_SG_FAST_SIGMOID, alpha=25.0, detach_reset=False,
-                       first_layer_input_grad=False, stream=None):
+                       first_layer_input_grad=False, grad_in_per_group=False, stream=None):
     """Backward pass through a stack that tac_stack_forward has run with v_trace buffers.  weights: the layers'
-    plain float32 weights (device tensors).  Returns a list of dicts (grad_y, grad_w, grad_bias, grad_in) per layer."""
+    plain float32 weights (device tensors).  Returns a list of dicts (grad_y, grad_w, grad_bias, grad_in) per layer.
+    grad_in_per_group: layers l >= 1 that group frames and have no pool on load hand dL/dA_k [G,..] to the layer before."""
     import torch
+    pools = (TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2)
     n = len(stack)
     arr = (tac_stack_grads_t * n)()
     out = []
@@ -376,8 +386,8 @@ def tac_stack_backward(stack, weights, input, grad_out_last, *, surrogate=TAC_SG
         g = dict(grad_y=torch.empty((-(-d.T // K), d.B, d.Cout, Ho, Wo), dtype=torch.float32, device=dev),
                  grad_w=torch.empty((d.Cout, d.Cin, 3, 3), dtype=torch.float32, device=dev),
                  grad_bias=torch.empty((d.Cout,), dtype=torch.float32, device=dev),
-                 grad_in=torch.empty((d.T, d.B, d.Cin, d.H * (2 if d.in_format in (TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2) else 1),
-                                      d.W * (2 if d.in_format in (TAC_IN_BITS_POOL2, TAC_IN_BITS_MAXPOOL2) else 1)),
+                 grad_in=torch.empty((-(-d.T // K) if (grad_in_per_group and l > 0 and d.in_format not in pools) else d.T,
+                                      d.B, d.Cin, d.H * (2 if d.in_format in pools else 1), d.W * (2 if d.in_format in pools else 1)),
                                      dtype=torch.float32, device=dev)
                  if (l > 0 or first_layer_input_grad) else None)
         if tuple(weights[l].shape) != (d.Cout, d.Cin, 3, 3):
@@ -387,7 +397,8 @@ def tac_stack_backward(stack, weights, input, grad_out_last, *, surrogate=TAC_SG
         for k in ("grad_y", "grad_w", "grad_bias", "grad_in"):
             setattr(arr[l], k, val(_dev_ptr(g[k])))
         out.append(g)
-    bwd = tac_backward_desc_t(surrogate=surrogate, detach_reset=int(bool(detach_reset)), alpha=alpha)
+    bwd = tac_backward_desc_t(surrogate=surrogate, detach_reset=int(bool(detach_reset)), alpha=alpha,
+                              grad_in_per_group=int(bool(grad_in_per_group)))
     _check(lib().tac_stack_backward(stack, arr, ctypes.byref(bwd), n, _dev_ptr(input, None, "input"),
                                     _dev_ptr(grad_out_last, torch.float32, "grad_out_last"), _stream(stream)))
     return out

@@ -292,6 +292,10 @@ int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* 
        (uintptr_t)grad_w | (uintptr_t)grad_bias | (uintptr_t)grad_in) & 3u)
     return TAC_ERR_ALIGN;
   if (eff.W > 1024 || eff.out_format != TAC_OUT_BITS) return TAC_ERR_UNSUPPORTED;
+  const bool pool_on_load = eff.in_format == TAC_IN_BITS_POOL2 || eff.in_format == TAC_IN_BITS_MAXPOOL2;
+  if (bwd->grad_in_per_group && grad_in && pool_on_load) return TAC_ERR_UNSUPPORTED;
+  if (bwd->grad_out_group_K < 0 || bwd->grad_out_group_K > TAC_MAX_K) return TAC_ERR_BAD_K;
+  if (bwd->grad_out_group_K > 1 && !(bwd->grad_out_group_beta >= 0.0f && bwd->grad_out_group_beta <= 1.0f)) return TAC_ERR_BAD_PARAM;
 
   tac::BackwardParams p;
   std::memset(&p, 0, sizeof(p));
@@ -319,6 +323,18 @@ int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* 
   pw = 1.0;
   for (int j = p.K_last - 1; j >= 0; --j) { p.wj_last[j] = (float)pw; pw *= beta; }
   p.decay_last = (float)pw;
+  p.grad_in_group = bwd->grad_in_per_group != 0;
+  if (bwd->grad_out_group_K > 1) {
+    // the next layer's factors, formed as that layer forms its own
+    p.go_K = bwd->grad_out_group_K;
+    p.go_G = (p.n_steps + p.go_K - 1) / p.go_K;
+    p.go_last = p.n_steps % p.go_K;
+    const double bc = (double)bwd->grad_out_group_beta;
+    pw = 1.0;
+    for (int j = p.go_K - 1; j >= 0; --j) { p.go_w[j] = (float)pw; pw *= bc; }
+    pw = 1.0;
+    for (int j = p.go_last - 1; j >= 0; --j) { p.go_w_last[j] = (float)pw; pw *= bc; }
+  }
   hipError_t e = tac::backward_launch(p, (hipStream_t)stream);
   return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_conv_lif_backward");
 }
@@ -364,8 +380,23 @@ int tac_stack_backward(const tac_stack_layer_t* layers, const tac_stack_grads_t*
   if (rc) return rc;
   for (int32_t l = 0; l < n_layers; ++l)
     if (!layers[l].v_trace || (l > 0 && !grads[l].grad_in)) return TAC_ERR_NULL;
+  // which layers hand their input gradient to the layer before once per group of frames
+  auto per_group = [&](int32_t l) {
+    if (!bwd->grad_in_per_group || l < 1 || l >= n_layers) return false;
+    const tac_layer_desc_t& d = layers[l].desc;
+    return d.mode != TAC_PER_STEP && d.K > 1 && d.in_format != TAC_IN_BITS_POOL2 && d.in_format != TAC_IN_BITS_MAXPOOL2;
+  };
   for (int32_t l = n_layers - 1; l >= 0; --l) {
-    rc = tac_conv_lif_backward(&layers[l].desc, bwd, l == 0 ? input : layers[l - 1].out_spikes_packed, grads[l].w_oihw,
+    tac_backward_desc_t b = *bwd;
+    b.grad_in_per_group = per_group(l) ? 1 : 0;
+    b.grad_out_group_K = 0;
+    b.grad_out_group_beta = 0.0f;
+    if (per_group(l + 1)) {
+      const tac_layer_desc_t& nx = layers[l + 1].desc;
+      b.grad_out_group_K = nx.K > nx.T ? nx.T : nx.K;       // a sequence shorter than one group is one group
+      b.grad_out_group_beta = nx.beta;
+    }
+    rc = tac_conv_lif_backward(&layers[l].desc, &b, l == 0 ? input : layers[l - 1].out_spikes_packed, grads[l].w_oihw,
                                layers[l].v_trace, l == n_layers - 1 ? grad_out_last : grads[l + 1].grad_in, grads[l].grad_y,
                                grads[l].grad_w, grads[l].grad_bias, grads[l].grad_in, stream);
     if (rc) return rc;

@@ -32,6 +32,15 @@ __device__ __forceinline__ int group_frames(const BackwardParams& p, int k) {
   return (k == p.G - 1 && p.K_last) ? p.K_last : p.K;
 }
 
+// dL/ds of output step n at neuron i: stored per step, or once per group of the next layer's frames
+// (dL/dS_{kK+j} = beta^(Kg-1-j) dL/dA_k, Eq. 2) and multiplied by that layer's factor here
+__device__ __forceinline__ float grad_out_at(const BackwardParams& p, size_t n, size_t n_out, size_t i) {
+  if (p.go_K <= 1) return p.grad_out[n * n_out + i];
+  const int kc = (int)n / p.go_K, j = (int)n - kc * p.go_K;
+  const float f = (p.go_last && kc == p.go_G - 1) ? p.go_w_last[j] : p.go_w[j];
+  return f * p.grad_out[(size_t)kc * n_out + i];
+}
+
 // One thread per output neuron; groups and their LIF steps backwards, c = dL/dV' carried.
 __global__ __launch_bounds__(kThreads) void lif_backward_kernel(const BackwardParams p) {
   const size_t n_out = (size_t)p.B * p.Cout * p.Ho * p.Wo;
@@ -47,7 +56,7 @@ __global__ __launch_bounds__(kThreads) void lif_backward_kernel(const BackwardPa
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         v[u] = p.v_trace[(n - 1 - u) * n_out + i];
-        g[u] = p.grad_out[(n - 1 - u) * n_out + i];
+        g[u] = grad_out_at(p, n - 1 - u, n_out, i);
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -65,7 +74,7 @@ __global__ __launch_bounds__(kThreads) void lif_backward_kernel(const BackwardPa
       const int Kg = group_frames(p, k);
       const float decay = p.mode == TAC_COLLAPSE ? (Kg == p.K ? p.decay_full : p.decay_last) : p.beta;
       const float sg = surrogate(p.surrogate, p.alpha, p.v_trace[n * n_out + i] - p.theta);
-      const float gv = p.grad_out[n * n_out + i] * sg + c * (p.detach_reset ? 1.0f : 1.0f - p.theta * sg);
+      const float gv = grad_out_at(p, n, n_out, i) * sg + c * (p.detach_reset ? 1.0f : 1.0f - p.theta * sg);
       p.grad_y[(size_t)k * n_out + i] = gv;
       c = decay * gv;
     }
@@ -79,7 +88,7 @@ __global__ __launch_bounds__(kThreads) void lif_backward_kernel(const BackwardPa
     for (int j = nlif - 1; j >= 0; --j) {
       --n;
       const float sg = surrogate(p.surrogate, p.alpha, p.v_trace[n * n_out + i] - p.theta);
-      const float gv = p.grad_out[n * n_out + i] * sg + c * (p.detach_reset ? 1.0f : 1.0f - p.theta * sg);
+      const float gv = grad_out_at(p, n, n_out, i) * sg + c * (p.detach_reset ? 1.0f : 1.0f - p.theta * sg);
       acc += gv;
       c = decay * gv;
     }
@@ -255,6 +264,12 @@ __global__ __launch_bounds__(kThreads) void dgrad_kernel(const BackwardParams p)
           }
           dst[0] = q[0]; dst[1] = q[1]; dst[W2] = q[2]; dst[W2 + 1] = q[3];
         }
+    return;
+  }
+  if (p.grad_in_group) {
+#pragma unroll
+    for (int c = 0; c < kCiTile; ++c)
+      if (ci0 + c < p.Cin) p.grad_in[(((size_t)k * p.B + b) * p.Cin + ci0 + c) * in_plane + px] = dA[c];
     return;
   }
   for (int j = 0; j < Kg; ++j)

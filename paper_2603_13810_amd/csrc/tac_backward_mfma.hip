@@ -414,6 +414,10 @@ __global__ __launch_bounds__(kThreads) void dgrad_mfma_kernel(const BackwardPara
               dst[2 * W + 1] = best == 3 ? g : 0.0f;
             }
           }
+        } else if (iy < p.H && p.grad_in_group) {
+          float* dst = p.grad_in + (((size_t)w.k * p.B + w.b) * p.Cin + ci0) * plane + (size_t)iy * W + ix;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) dst[(size_t)(8 * (r >> 2) + 4 * h + (r & 3)) * plane] = acc[q][r];
         } else if (iy < p.H) {
           for (int j = 0; j < Kg; ++j) {
             float* dst = p.grad_in + (((size_t)(w.k * p.K + j) * p.B + w.b) * p.Cin + ci0) * plane + (size_t)iy * W + ix;

@@ -80,7 +80,7 @@ struct BackwardParams {
   float* grad_y;            // [G][B][Cout][Ho][Wo] dL/dY_k, written
   float* grad_w;            // [Cout][Cin][3][3], written
   float* grad_bias;         // [Cout] or nullptr
-  float* grad_in;           // [T][B][Cin][H][W] or nullptr
+  float* grad_in;           // [T][B][Cin][H][W] ([G].. with grad_in_group) or nullptr
   int T, B, Cin, H, W, Cout, stride, Ho, Wo, Wwi;
   int K, K_last, G;         // frames per group, frames of a shorter last group (0: none), groups
   int n_steps;              // LIF steps = output steps of the forward pass
@@ -91,6 +91,9 @@ struct BackwardParams {
   float beta, theta, alpha;
   float decay_full, decay_last;          // beta^K, beta^K_last (TAC)
   float wj[TAC_MAX_K], wj_last[TAC_MAX_K];   // beta^(Kg-1-j) for a whole group and for the shorter last one
+  int grad_in_group;        // grad_in is [G][B][Cin][H][W]: dL/dA_k once per group, without the factor
+  int go_K, go_G, go_last;  // grad_out comes per group of go_K output steps (0: per step): groups, steps of a shorter last group
+  float go_w[TAC_MAX_K], go_w_last[TAC_MAX_K];   // the next layer's beta^(Kg-1-j)
 };
 hipError_t backward_launch(const BackwardParams& p, hipStream_t s);
 size_t backward_wgrad_lds_bytes(int W, int stride);

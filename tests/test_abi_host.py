@@ -200,6 +200,14 @@ def test_backward_rejects_bad_requests_before_any_launch():
     assert call(d, api.tac_backward_desc_t(surrogate=0, detach_reset=0, alpha=0.0), *nine) == api.TAC_ERR_BAD_PARAM
     assert call(_desc(W=2048, in_format=api.TAC_IN_BITS), ok, *nine) == api.TAC_ERR_UNSUPPORTED
     assert call(_desc(K=0), ok, *nine) == api.TAC_ERR_BAD_K
+    # gradients once per group of frames: the struct of include/tac.h, and what is refused
+    assert ctypes.sizeof(api.tac_backward_desc_t) == 24
+    mk = lambda **kw: api.tac_backward_desc_t(surrogate=api.TAC_SG_ARCTAN, detach_reset=1, alpha=2.0, **kw)
+    for fmt in (api.TAC_IN_BITS_POOL2, api.TAC_IN_BITS_MAXPOOL2):
+        assert call(_desc(in_format=fmt), mk(grad_in_per_group=1), *nine) == api.TAC_ERR_UNSUPPORTED
+    assert call(d, mk(grad_out_group_K=api.TAC_MAX_K + 1, grad_out_group_beta=0.5), *nine) == api.TAC_ERR_BAD_K
+    assert call(d, mk(grad_out_group_K=-1), *nine) == api.TAC_ERR_BAD_K
+    assert call(d, mk(grad_out_group_K=4, grad_out_group_beta=1.5), *nine) == api.TAC_ERR_BAD_PARAM
 
 
 def test_stack_backward_needs_membranes_and_input_gradients():

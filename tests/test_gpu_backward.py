@@ -19,10 +19,10 @@ def _rng(seed):
     return np.random.Generator(np.random.PCG64(seed))
 
 
-def _close(name, got, ref):
+def _close(name, got, ref, tol=TOL):
     scale = max(np.abs(ref).max(), 1e-30)
     err = np.abs(got - ref).max() / scale
-    assert err <= TOL, "%s: max error %.3g of the largest magnitude %.3g" % (name, err, scale)
+    assert err <= tol, "%s: max error %.3g of the largest magnitude %.3g" % (name, err, scale)
     return err
 
 
@@ -189,6 +189,17 @@ def test_backward_through_a_stack(modes):
         _close("layer %d dbias" % l, got[l]["grad_bias"].cpu().numpy(), ref["dbias"])
         _close("layer %d dL/dS" % l, got[l]["grad_in"].cpu().numpy(), ref["g_in"])
         g = ref["g_in"]
+    # the same pass with the input gradients handed over once per group of frames where a layer groups them: the same
+    # products are formed on the reading side instead of the writing side, so dL/dY_k agrees bit for bit
+    grp = api.tac_stack_backward(stack, ws, sp, torch.from_numpy(g_last).to(DEV), surrogate=api.TAC_SG_ARCTAN, alpha=2.0,
+                                 detach_reset=True, first_layer_input_grad=True, grad_in_per_group=True)
+    torch.cuda.synchronize()
+    for l, (w, mode, K) in enumerate(host):
+        d = layers[l]["desc"]
+        grouped = l > 0 and mode != api.TAC_PER_STEP and K > 1
+        assert grp[l]["grad_in"].shape[0] == (-(-d.T // min(K, d.T)) if grouped else d.T), l
+        assert torch.equal(grp[l]["grad_y"], got[l]["grad_y"]), l
+        assert torch.allclose(grp[l]["grad_w"], got[l]["grad_w"], rtol=1e-4, atol=1e-5 * float(got[l]["grad_w"].abs().max())), l
 
 
 @pytest.mark.parametrize("mode,K,T", [(api.TAC_PER_STEP, 1, 4), (api.TAC_COLLAPSE, 4, 8), (api.TAC_PRESERVE, 2, 7)])
@@ -326,3 +337,92 @@ def test_backward_max_pool_on_load_on_the_matrix_cores(shape, mode, K, T):
                             ("dL/dS", got["grad_in"], ref["g_in"], TOL_BF16)):
         e = np.abs(a.cpu().numpy() - b).max() / np.abs(b).max()
         assert e <= tol, "%s: %.3g" % (name, e)
+
+
+# ---- the input gradient once per group of frames (dL/dS_{kK+j} = beta^(Kg-1-j) dL/dA_k, Eq. 2) ----------------------
+def _group_factors(beta, K, T):
+    """beta^(Kg-1-j) per frame, formed as the library forms them (double powers of the fp32 beta, rounded once)."""
+    b = float(np.float32(beta))
+    f = np.empty(T, dtype=np.float32)
+    for t in range(T):
+        k = t // K
+        Kg = min(K, T - k * K)
+        f[t] = np.float32(b ** (Kg - 1 - (t - k * K)))
+    return f
+
+
+# (Cin, Cout, H, W, stride, precision): the vector kernels and the matrix-core input gradient
+GROUP_SHAPES = [(3, 5, 7, 9, 1, api.TAC_FP32), (16, 24, 12, 33, 2, api.TAC_FP32), (32, 128, 12, 32, 1, api.TAC_BF16),
+                (64, 64, 9, 64, 1, api.TAC_BF16)]
+
+
+@pytest.mark.parametrize("shape", GROUP_SHAPES)
+@pytest.mark.parametrize("mode,K,T", [(api.TAC_COLLAPSE, 4, 8), (api.TAC_COLLAPSE, 4, 7), (api.TAC_PRESERVE, 2, 6),
+                                      (api.TAC_PRESERVE, 8, 13), (api.TAC_COLLAPSE, 8, 3), (api.TAC_PER_STEP, 1, 4)])
+def test_input_gradient_once_per_group(shape, mode, K, T):
+    Cin, Cout, H, W, stride, precision = shape
+    B = 2
+    r = _rng(1700 + Cin + Cout + H + W + K + T)
+    s = (r.random((T, B, Cin, H, W)) < 0.2).astype(np.uint8)
+    w = synth.kaiming_normal(47, Cout, Cin) * np.float32(1.5)
+    beta, theta = 0.9, 1.0
+    desc = api.make_desc(T, B, Cin, H, W, Cout, K=K, beta=beta, theta=theta, mode=mode, stride=stride, precision=precision)
+    T_out, Ho, Wo = api.tac_out_shape(desc)
+    Ke = 1 if mode == api.TAC_PER_STEP else min(K, T)
+    G = -(-T // Ke)
+    sp, wd = torch.from_numpy(np_pack(s)).to(DEV), torch.from_numpy(w).to(DEV)
+    vt = torch.empty((T_out, B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    v0 = torch.zeros((B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    api.tac_conv_lif(desc, sp, api.tac_prepare_weights(desc, wd), None, v0, None, vt)
+    r_g = r.standard_normal((T_out, B, Cout, Ho, Wo)).astype(np.float32)
+    g = torch.from_numpy(r_g).to(DEV)
+    frames = api.tac_conv_lif_backward(desc, sp, wd, vt, g)
+    groups = api.tac_conv_lif_backward(desc, sp, wd, vt, g, grad_in_per_group=True)
+    torch.cuda.synchronize()
+    assert tuple(groups["grad_in"].shape) == (G, B, Cin, H, W)
+    assert torch.equal(frames["grad_y"], groups["grad_y"])
+    fr, gr = frames["grad_in"].cpu().numpy(), groups["grad_in"].cpu().numpy()
+    f = _group_factors(beta, Ke, T)
+    # the same fp32 product, formed by the library in one case and here in the other: identical bits
+    expect = f[:, None, None, None, None] * gr[np.arange(T) // Ke]
+    assert np.array_equal(fr, expect)
+    # and against the oracle: the last frame of a group carries the factor 1, so its gradient is dL/dA_k itself
+    kw = dict(K=K, beta=float(np.float32(beta)), theta=theta, mode=ORACLE_MODE[mode], stride=stride)
+    v_pre = oracle.conv_lif(s, w.astype(np.float64), None, **kw)[1]
+    ref = oracle.conv_lif_backward(s, w.astype(np.float64), v_pre, r_g.astype(np.float64), **kw)
+    last = np.array([min((k + 1) * Ke, T) - 1 for k in range(G)])
+    if precision == api.TAC_FP32:
+        _close("dL/dA", gr, ref["g_in"][last])
+
+
+@pytest.mark.parametrize("mode,K,T", [(api.TAC_COLLAPSE, 2, 6), (api.TAC_PRESERVE, 4, 10), (api.TAC_PER_STEP, 1, 9)])
+@pytest.mark.parametrize("Kc,beta_c", [(2, 0.5), (4, 0.9), (8, 0.9)])
+def test_output_gradient_read_once_per_group_of_the_next_layer(mode, K, T, Kc, beta_c):
+    Cin, Cout, H, W, B = 6, 10, 9, 20, 2
+    r = _rng(1800 + K + T + Kc)
+    s = (r.random((T, B, Cin, H, W)) < 0.3).astype(np.uint8)
+    w = synth.kaiming_normal(48, Cout, Cin) * np.float32(1.5)
+    desc = api.make_desc(T, B, Cin, H, W, Cout, K=K, beta=0.9, theta=1.0, mode=mode)
+    T_out, Ho, Wo = api.tac_out_shape(desc)
+    Gc = -(-T_out // Kc)
+    sp, wd = torch.from_numpy(np_pack(s)).to(DEV), torch.from_numpy(w).to(DEV)
+    vt = torch.empty((T_out, B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    v0 = torch.zeros((B, Cout, Ho, Wo), dtype=torch.float32, device=DEV)
+    api.tac_conv_lif(desc, sp, api.tac_prepare_weights(desc, wd), None, v0, None, vt)
+    dA = r.standard_normal((Gc, B, Cout, Ho, Wo)).astype(np.float32)
+    f = _group_factors(beta_c, Kc, T_out)
+    per_step = f[:, None, None, None, None] * dA[np.arange(T_out) // Kc]          # what the next layer would have written
+    a = api.tac_conv_lif_backward(desc, sp, wd, vt, torch.from_numpy(per_step).to(DEV))
+    b = api.tac_conv_lif_backward(desc, sp, wd, vt, torch.from_numpy(dA).to(DEV), grad_out_group_K=Kc, grad_out_group_beta=beta_c)
+    torch.cuda.synchronize()
+    assert torch.equal(a["grad_y"], b["grad_y"])
+    assert torch.equal(a["grad_in"], b["grad_in"])
+    assert torch.allclose(a["grad_w"], b["grad_w"], rtol=1e-4, atol=1e-5 * float(a["grad_w"].abs().max()))
+    # the per-step form against the oracle (a shorter last group of the next layer included)
+    kw = dict(K=K, beta=float(np.float32(0.9)), theta=1.0, mode=ORACLE_MODE[mode], stride=1)
+    v_pre = oracle.conv_lif(s, w.astype(np.float64), None, **kw)[1]
+    ref = oracle.conv_lif_backward(s, w.astype(np.float64), v_pre, per_step.astype(np.float64), **kw)
+    # (the fast sigmoid's slope changes by up to 2 alpha = 50 per unit of V around the threshold, and the library reads
+    # fp32 membranes of its own forward pass: a little more room than TOL over ten dependent steps)
+    _close("dL/dY", b["grad_y"].cpu().numpy(), ref["dY"], 3e-4)
+    _close("dW", b["grad_w"].cpu().numpy(), ref["dW"], 3e-4)

@@ -204,3 +204,24 @@ def test_backward_through_the_pool_in_front_of_the_layer_against_automatic_diffe
     assert np.allclose(got["dW"], wt.grad.numpy(), rtol=1e-9, atol=1e-10)
     assert np.allclose(got["g_in"], xt.grad.numpy(), rtol=1e-9, atol=1e-12)
     assert got["g_in"].shape == s.shape
+
+
+@pytest.mark.parametrize("mode,K,T", [(oracle.TAC, 4, 8), (oracle.TAC, 4, 7), (oracle.TAC_TP, 3, 8)])
+def test_the_frames_of_a_group_receive_one_gradient_times_their_aggregate_weights(mode, K, T):
+    # A_k = sum_j beta^(Kg-1-j) S_{kK+j} (Eq. 2) is the only place a frame enters, so dL/dS_{kK+j} = beta^(Kg-1-j) dL/dA_k:
+    # within a group the input gradients are multiples of the last frame's, whose factor is 1
+    r = np.random.Generator(np.random.PCG64(77 + K + T))
+    B, Cin, Cout, H, W = 2, 3, 4, 6, 7
+    s = (r.random((T, B, Cin, H, W)) < 0.4).astype(np.uint8)
+    w = r.standard_normal((Cout, Cin, 3, 3))
+    beta = 0.8
+    kw = dict(K=K, beta=beta, theta=1.0, mode=mode)
+    out, v_pre, _ = oracle.conv_lif(s, w, None, **kw)
+    g_out = r.standard_normal(v_pre.shape)
+    g_in = oracle.conv_lif_backward(s, w, v_pre, g_out, **kw)["g_in"]
+    assert np.abs(g_in).max() > 0
+    for k in range(-(-T // K)):
+        Kg = min(K, T - k * K)
+        last = g_in[k * K + Kg - 1]
+        for j in range(Kg):
+            np.testing.assert_allclose(g_in[k * K + j], beta ** (Kg - 1 - j) * last, rtol=1e-12, atol=1e-15)
