@@ -236,7 +236,8 @@ int tac_stack_forward(const tac_stack_layer_t* layers, int32_t n_layers, const v
  * Sec. 4 applies to the backward pass as well).  With desc->precision = TAC_BF16 the two
  * convolution gradients run on the matrix cores where the shape allows (stride 1; Cin a multiple of
  * 32; width 16, 32, 64 or 128 and Cout a multiple of 128 for dW; width 32, 64 or 128 and Cout = 64
- * or 128 for dL/dS; packed input, as it is or with the max pool on load; grad_y 16-byte aligned):
+ * or 128 for dL/dS, or, without a pool, width 32 or 64, Cin a multiple of 128 and Cout a multiple of 16 (tiles of
+ * 128 input channels); packed input, as it is or with the max pool on load; grad_y 16-byte aligned):
  * dY_k, A_k and W enter them rounded to bfloat16, sums are fp32.  Everything else, and TAC_FP32, is
  * fp32 vector arithmetic.  The rounding inside a bf16 forward pass is differentiated as if it were
  * not there. */
@@ -265,7 +266,8 @@ typedef struct tac_backward_desc {
  *   v_trace    DEVICE, read-only, float32 [T_out][B][Cout][Ho][Wo]: what the forward pass wrote
  *   grad_out   DEVICE, read-only, float32 [T_out][B][Cout][Ho][Wo]: dL/d(output spikes)
  *   grad_y     DEVICE, written, float32 [G][B][Cout][Ho][Wo], G = ceil(T/K) (T for per-step): dL/dY_k
- *   grad_w     DEVICE, written (not accumulated), float32 [Cout][Cin][3][3]
+ *   grad_w     DEVICE, written (not accumulated), float32 [Cout][Cin][3][3]; the call may use it as scratch before
+ *              it holds the result (the wide-tile input gradient keeps its prepared weights there)
  *   grad_bias  DEVICE, written, float32 [Cout], or NULL
  *   grad_in    DEVICE, written, float32 [T][B][Cin][H][W]: dL/d(input frames), the grad_out of the
  *              layer before ([G][B][Cin][H][W] with bwd->grad_in_per_group); NULL for a first layer

@@ -14,7 +14,7 @@ LIB = os.path.join(HERE, "libtac.so")
 SOURCES = ["tac_mfma_w64s1.hip", "tac_mfma_w64s1_trace.hip", "tac_mfma_w32s1.hip", "tac_mfma_w32s1_trace.hip",
            "tac_mfma_small.hip", "tac_mfma_w64s2.hip", "tac_mfma_w64s2_trace.hip", "tac_mfma_w32s2.hip",
            "tac_mfma_w32s2_trace.hip", "tac_backward_mfma.hip", "tac_mfma_mid.hip", "tac_mfma.hip", "tac_api.hip",
-           "tac_pack.hip", "tac_direct.hip", "tac_backward.hip"]
+           "tac_pack.hip", "tac_direct.hip", "tac_backward.hip", "tac_backward_dgrad_tile.hip"]
 MAX_JOBS = min(16, os.cpu_count() or 4)
 
 

@@ -289,6 +289,13 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 
+  // the wide-tile input gradient uses grad_w as scratch for its prepared weights: it runs before grad_w is cleared
+  const bool dgrad_tile = p.grad_in && backward_dgrad_tile_supported(p);
+  if (dgrad_tile) {
+    e = backward_dgrad_tile_launch(p, s);
+    if (e != hipSuccess) return e;
+  }
+
   const size_t n_w = (size_t)p.Cout * p.Cin * 9;
   hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((n_w + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, p.grad_w, n_w);
   if (p.grad_bias)
@@ -317,7 +324,9 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
   if (e != hipSuccess) return e;
   }
 
-  if (p.grad_in && p.bf16 && p.pool2 != 1 && backward_dgrad_mfma_supported(p)) {
+  if (dgrad_tile) {
+    // done above
+  } else if (p.grad_in && p.bf16 && p.pool2 != 1 && backward_dgrad_mfma_supported(p)) {
     e = backward_dgrad_mfma_launch(p, s);
   } else if (p.grad_in) {
     const dim3 grid((p.H * p.W + kThreads - 1) / kThreads, (p.Cin + kCiTile - 1) / kCiTile, p.G * p.B);

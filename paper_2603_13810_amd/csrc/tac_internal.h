@@ -99,6 +99,8 @@ hipError_t backward_launch(const BackwardParams& p, hipStream_t s);
 size_t backward_wgrad_lds_bytes(int W, int stride);
 bool backward_wgrad_mfma_supported(const BackwardParams& p);
 hipError_t backward_wgrad_mfma_launch(const BackwardParams& p, hipStream_t s);
+bool backward_dgrad_tile_supported(const BackwardParams& p);     // wide tiles (128 input channels), grad_w as scratch
+hipError_t backward_dgrad_tile_launch(const BackwardParams& p, hipStream_t s);
 bool backward_dgrad_mfma_supported(const BackwardParams& p);
 hipError_t backward_dgrad_mfma_launch(const BackwardParams& p, hipStream_t s);
 

@@ -72,6 +72,30 @@ __device__ __forceinline__ uint32_t pool_pairs(uint32_t v) {
   return (v | (v >> 8)) & 0x0000ffffu;
 }
 
+// N (1 or 2) direct-to-LDS loads of 16 bytes per lane from one global address to one LDS base address, the n-th
+// with the immediate offset OFF0 + 1024 n added to both.  Written as an assembly statement on purpose: while a
+// direct-to-LDS load that the compiler knows of is pending, it turns every wait on the LDS counter into a wait for
+// zero, and in the chunk loops that use it one always is, so each tap would wait for the LDS reads and writes it has only just
+// issued.  The compiler therefore does not know of these loads at all: the reader of what they write waits for
+// vmcnt(0) (lds_dma_wait) in front of the workgroup barrier that separates writer and reader, and the kernel waits
+// once more before it ends.  The waits the compiler places for its own loads count these loads too, which only
+// makes them stricter.  M0 holds the LDS address; one wait state between its write and the load.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+template <int N, int OFF0>
+__device__ __forceinline__ void lds_dma16(const void* gsrc, uint32_t lds_base) {
+  static_assert(N == 1 || N == 2, "one or two loads");
+  if constexpr (N == 1)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2"
+                 :: "v"(gsrc), "s"(lds_base), "n"(OFF0) : "m0", "memory");
+  else
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2\n\t"
+                 "global_load_lds_dwordx4 %0, off offset:%3"
+                 :: "v"(gsrc), "s"(lds_base), "n"(OFF0), "n"(OFF0 + 1024) : "m0", "memory");
+}
+#pragma clang diagnostic pop
+__device__ __forceinline__ void lds_dma_wait() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0), other counters untouched
+
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
   if constexpr (I < N) {

@@ -88,7 +88,10 @@ def test_backward_first_layer_skips_the_input_gradient_and_is_repeatable_up_to_r
 
 # weight gradients on the matrix cores (bf16 layers; Cin a multiple of 32, Cout of 128, width 16/32/64/128, stride 1)
 # (Cin, Cout, H, W)
-MFMA_SHAPES = [(32, 128, 12, 32), (64, 128, 9, 64), (32, 256, 20, 16), (32, 128, 5, 128), (32, 64, 15, 32)]
+MFMA_SHAPES = [(32, 128, 12, 32), (64, 128, 9, 64), (32, 256, 20, 16), (32, 128, 5, 128), (32, 64, 15, 32),
+               # input gradient on the wide tiles (Cin a multiple of 128): rows that do not fill the last tile, a Cout that is
+               # only a multiple of 16 (its weight gradient then runs on the vector kernel), two tiles of input channels
+               (128, 128, 9, 64), (128, 48, 11, 32), (256, 128, 5, 32)]
 TOL_BF16 = 2e-2     # the bar of the bf16 path; dY and A_k enter the matrix cores rounded to bf16
 
 
@@ -353,7 +356,7 @@ def _group_factors(beta, K, T):
 
 # (Cin, Cout, H, W, stride, precision): the vector kernels and the matrix-core input gradient
 GROUP_SHAPES = [(3, 5, 7, 9, 1, api.TAC_FP32), (16, 24, 12, 33, 2, api.TAC_FP32), (32, 128, 12, 32, 1, api.TAC_BF16),
-                (64, 64, 9, 64, 1, api.TAC_BF16)]
+                (64, 64, 9, 64, 1, api.TAC_BF16), (128, 32, 6, 64, 1, api.TAC_BF16)]
 
 
 @pytest.mark.parametrize("shape", GROUP_SHAPES)
