@@ -58,8 +58,8 @@ enum { TAC_IN_BITS = 0, TAC_IN_BITS_POOL2 = 1, TAC_IN_BITS_MAXPOOL2 = 2, TAC_IN_
  * next layer reads as plain TAC_IN_BITS of size Ho/2 x Wo/2.  Ho and Wo must be even.  The membrane (v_inout,
  * v_trace) keeps the size Ho x Wo.  Supported by the MFMA kernels (tac_select_kernel: the large-shape member
  * takes it with stride 1 only, other shapes go to the in-between member where it takes them);
- * TAC_ERR_UNSUPPORTED otherwise (fp32 layers, the vector kernel), also for the backward pass (train with TAC_IN_BITS_MAXPOOL2 in the next
- * layer instead, which pools the same bits while loading). */
+ * TAC_ERR_UNSUPPORTED otherwise (fp32 layers, the vector kernel).  The backward pass takes the gradient of the pooled
+ * spikes and routes it to the first maximal spike of each window (see tac_conv_lif_backward). */
 enum { TAC_OUT_BITS = 0, TAC_OUT_BITS_MAXPOOL2 = 1 };
 /* Kernel family.  AUTO picks MFMA when the shape qualifies (see
  * tac_select_kernel), else DIRECT.  Forcing MFMA on a shape it does not
@@ -264,7 +264,10 @@ typedef struct tac_backward_desc {
 /*   input      DEVICE, read-only: what the forward pass read, in desc->in_format
  *   w_oihw     DEVICE, read-only, float32 [Cout][Cin][3][3] (the plain weights, not the prepared ones)
  *   v_trace    DEVICE, read-only, float32 [T_out][B][Cout][Ho][Wo]: what the forward pass wrote
- *   grad_out   DEVICE, read-only, float32 [T_out][B][Cout][Ho][Wo]: dL/d(output spikes)
+ *   grad_out   DEVICE, read-only, float32 [T_out][B][Cout][Ho][Wo]: dL/d(output spikes); with desc->out_format =
+ *              TAC_OUT_BITS_MAXPOOL2 [T_out][B][Cout][Ho/2][Wo/2]: dL/d(the pooled spikes the layer stored), all of which
+ *              goes to the first maximal spike of the 2 x 2 window in row-major order (the first set bit, else the
+ *              first neuron), the spikes being V >= theta on v_trace
  *   grad_y     DEVICE, written, float32 [G][B][Cout][Ho][Wo], G = ceil(T/K) (T for per-step): dL/dY_k
  *   grad_w     DEVICE, written (not accumulated), float32 [Cout][Cin][3][3]; the call may use it as scratch before
  *              it holds the result (the wide-tile input gradient keeps its prepared weights there)

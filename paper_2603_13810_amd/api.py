@@ -271,9 +271,11 @@ def tac_conv_lif_backward(desc, spikes_packed, w_oihw, v_trace, grad_out, *, sur
     if tuple(w_oihw.shape) != (desc.Cout, desc.Cin, 3, 3):
         raise ValueError("w_oihw must be [Cout,Cin,3,3]")
     steps_go = -(-T_out // grad_out_group_K) if grad_out_group_K > 1 else T_out
-    for name, t, n in (("v_trace", v_trace, T_out), ("grad_out", grad_out, steps_go)):
-        if tuple(t.shape) != (n, desc.B, desc.Cout, Ho, Wo):
-            raise ValueError("%s must be [%d,B,Cout,Ho,Wo]" % (name, n))
+    pf = 2 if desc.out_format == TAC_OUT_BITS_MAXPOOL2 else 1          # grad_out is that of the pooled spikes the layer stored
+    for name, t, shape in (("v_trace", v_trace, (T_out, desc.B, desc.Cout, Ho, Wo)),
+                           ("grad_out", grad_out, (steps_go, desc.B, desc.Cout, Ho // pf, Wo // pf))):
+        if tuple(t.shape) != shape:
+            raise ValueError("%s must be %s" % (name, list(shape)))
     grad_y = torch.empty((G, desc.B, desc.Cout, Ho, Wo), dtype=torch.float32, device=dev)
     grad_w = torch.empty((desc.Cout, desc.Cin, 3, 3), dtype=torch.float32, device=dev)
     grad_bias = torch.empty((desc.Cout,), dtype=torch.float32, device=dev)

@@ -291,7 +291,7 @@ int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* 
   if (((uintptr_t)input | (uintptr_t)w_oihw | (uintptr_t)v_trace | (uintptr_t)grad_out | (uintptr_t)grad_y |
        (uintptr_t)grad_w | (uintptr_t)grad_bias | (uintptr_t)grad_in) & 3u)
     return TAC_ERR_ALIGN;
-  if (eff.W > 1024 || eff.out_format != TAC_OUT_BITS) return TAC_ERR_UNSUPPORTED;
+  if (eff.W > 1024) return TAC_ERR_UNSUPPORTED;
   const bool pool_on_load = eff.in_format == TAC_IN_BITS_POOL2 || eff.in_format == TAC_IN_BITS_MAXPOOL2;
   if (bwd->grad_in_per_group && grad_in && pool_on_load) return TAC_ERR_UNSUPPORTED;
   if (bwd->grad_out_group_K < 0 || bwd->grad_out_group_K > TAC_MAX_K) return TAC_ERR_BAD_K;
@@ -323,6 +323,7 @@ int tac_conv_lif_backward(const tac_layer_desc_t* d, const tac_backward_desc_t* 
   pw = 1.0;
   for (int j = p.K_last - 1; j >= 0; --j) { p.wj_last[j] = (float)pw; pw *= beta; }
   p.decay_last = (float)pw;
+  p.out_pool = eff.out_format == TAC_OUT_BITS_MAXPOOL2;
   p.grad_in_group = bwd->grad_in_per_group != 0;
   if (bwd->grad_out_group_K > 1) {
     // the next layer's factors, formed as that layer forms its own

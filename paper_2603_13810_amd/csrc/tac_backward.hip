@@ -35,10 +35,26 @@ __device__ __forceinline__ int group_frames(const BackwardParams& p, int k) {
 // dL/ds of output step n at neuron i: stored per step, or once per group of the next layer's frames
 // (dL/dS_{kK+j} = beta^(Kg-1-j) dL/dA_k, Eq. 2) and multiplied by that layer's factor here
 __device__ __forceinline__ float grad_out_at(const BackwardParams& p, size_t n, size_t n_out, size_t i) {
-  if (p.go_K <= 1) return p.grad_out[n * n_out + i];
-  const int kc = (int)n / p.go_K, j = (int)n - kc * p.go_K;
-  const float f = (p.go_last && kc == p.go_G - 1) ? p.go_w_last[j] : p.go_w[j];
-  return f * p.grad_out[(size_t)kc * n_out + i];
+  size_t step = n;
+  float f = 1.0f;
+  if (p.go_K > 1) {
+    const int kc = (int)n / p.go_K, j = (int)n - kc * p.go_K;
+    f = (p.go_last && kc == p.go_G - 1) ? p.go_w_last[j] : p.go_w[j];
+    step = (size_t)kc;
+  }
+  if (!p.out_pool) return p.go_K > 1 ? f * p.grad_out[step * n_out + i] : p.grad_out[step * n_out + i];
+  // The layer stored the 2 x 2 max pool of its spikes (the OR of the four bits): the gradient of a pooled spike
+  // goes to the first maximal spike of its window in row-major order (the first set bit, else the first neuron),
+  // the spikes being what the forward pass decided on the recorded membranes of output step n, V >= theta.
+  const int x = (int)(i % p.Wo), y = (int)((i / p.Wo) % p.Ho);
+  const size_t bc = i / ((size_t)p.Wo * p.Ho);
+  const float* v = p.v_trace + n * n_out + (bc * p.Ho + (y & ~1)) * p.Wo + (x & ~1);
+  const uint32_t bits = (v[0] >= p.theta ? 1u : 0u) | (v[1] >= p.theta ? 2u : 0u) | (v[p.Wo] >= p.theta ? 4u : 0u) |
+                        (v[p.Wo + 1] >= p.theta ? 8u : 0u);
+  const int first = bits ? __ffs(bits) - 1 : 0;
+  if (first != (y & 1) * 2 + (x & 1)) return 0.0f;
+  const size_t ip = (bc * (p.Ho >> 1) + (y >> 1)) * (p.Wo >> 1) + (x >> 1);
+  return f * p.grad_out[step * (n_out >> 2) + ip];
 }
 
 // One thread per output neuron; groups and their LIF steps backwards, c = dL/dV' carried.

@@ -91,6 +91,7 @@ struct BackwardParams {
   float beta, theta, alpha;
   float decay_full, decay_last;          // beta^K, beta^K_last (TAC)
   float wj[TAC_MAX_K], wj_last[TAC_MAX_K];   // beta^(Kg-1-j) for a whole group and for the shorter last one
+  int out_pool;             // grad_out is the gradient of the 2 x 2 max-pooled spikes the layer stored: [..][B][Cout][Ho/2][Wo/2]
   int grad_in_group;        // grad_in is [G][B][Cin][H][W]: dL/dA_k once per group, without the factor
   int go_K, go_G, go_last;  // grad_out comes per group of go_K output steps (0: per step): groups, steps of a shorter last group
   float go_w[TAC_MAX_K], go_w_last[TAC_MAX_K];   // the next layer's beta^(Kg-1-j)

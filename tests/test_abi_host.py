@@ -231,7 +231,7 @@ def test_stack_backward_needs_membranes_and_input_gradients():
 
 
 def test_pooled_output_validation_and_stack_chaining():
-    # MaxPool(2) in the writer (Sec. 5.1 blocks): even output sizes, matrix-core kernels only, no backward pass
+    # MaxPool(2) in the writer (Sec. 5.1 blocks): even output sizes, matrix-core kernels only
     ok = _desc(H=16, W=32, Cin=32, Cout=64, precision=api.TAC_BF16, out_format=api.TAC_OUT_BITS_MAXPOOL2)
     assert api.tac_select_kernel(ok) == api.TAC_KERNEL_MFMA
     assert api.tac_out_shape(ok)[1:] == (16, 32) and api.stored_out_shape(ok)[1:] == (8, 16)

@@ -429,3 +429,43 @@ def test_output_gradient_read_once_per_group_of_the_next_layer(mode, K, T, Kc, b
     # fp32 membranes of its own forward pass: a little more room than TOL over ten dependent steps)
     _close("dL/dY", b["grad_y"].cpu().numpy(), ref["dY"], 3e-4)
     _close("dW", b["grad_w"].cpu().numpy(), ref["dW"], 3e-4)
+
+
+# ---- training through the max pool that the writer applies (out_format = TAC_OUT_BITS_MAXPOOL2) ---------------------
+@pytest.mark.parametrize("mode,K,T", [(api.TAC_PER_STEP, 1, 4), (api.TAC_COLLAPSE, 2, 6), (api.TAC_PRESERVE, 2, 4)])
+def test_backward_through_the_max_pool_in_the_writer(mode, K, T):
+    # Layer A stores pooled spikes; the gradient it receives is that of the pooled tensor.  The oracle has no pooled
+    # output: it runs the layer AFTER A with the max pool on load, whose input gradient is dL/d(A's unpooled spikes),
+    # routed through the pool by the oracle's own rule, and the same layer on the pooled tensor, whose input gradient is
+    # what the library is given.
+    from gpu_util import bf16_round_np
+    B, Cin, Ca, Cb, H, W = 2, 8, 16, 6, 12, 32
+    r = _rng(1900 + K + T)
+    s = (r.random((T, B, Cin, H, W)) < 0.3).astype(np.uint8)
+    wA = bf16_round_np(synth.kaiming_normal(49, Ca, Cin) * np.float32(1.5))
+    beta, theta = 0.9, 1.0
+    desc = api.make_desc(T, B, Cin, H, W, Ca, K=K, beta=beta, theta=theta, mode=mode, precision=api.TAC_BF16,
+                         out_format=api.TAC_OUT_BITS_MAXPOOL2)
+    T_out, Ho, Wo = api.tac_out_shape(desc)
+    sp, wd = torch.from_numpy(np_pack(s)).to(DEV), torch.from_numpy(wA).to(DEV)
+    vt = torch.empty((T_out, B, Ca, Ho, Wo), dtype=torch.float32, device=DEV)
+    pooled = api.tac_conv_lif(desc, sp, api.tac_prepare_weights(desc, wd), None, None, None, vt)
+    kwA = dict(K=K, beta=float(np.float32(beta)), theta=theta, mode=ORACLE_MODE[mode])
+    outA, v_preA, _ = oracle.conv_lif(s, wA.astype(np.float64), None, round_a_bf16=True, **kwA)
+    assert np.array_equal(vt.cpu().numpy() >= np.float32(theta), outA.astype(bool)) and outA.sum() > 0     # same spikes on both sides
+    from parity_util import np_unpack
+    assert np.array_equal(np_unpack(pooled.cpu().numpy(), Wo // 2), oracle.maxpool2(outA).astype(np.uint8))
+    # the layer after A, in the oracle only
+    wB = r.standard_normal((Cb, Ca, 3, 3)) * 0.3
+    kwB = dict(K=1, beta=0.8, theta=1.0, mode=oracle.PER_STEP)
+    _, v_preB, _ = oracle.conv_lif(outA, wB, None, pool2="max", **kwB)
+    gB = r.standard_normal(v_preB.shape)
+    routed = oracle.conv_lif_backward(outA, wB, v_preB, gB, pool2="max", **kwB)["g_in"]                  # [T_out,B,Ca,Ho,Wo]
+    at_pooled = oracle.conv_lif_backward(oracle.maxpool2(outA).astype(np.uint8), wB, v_preB, gB, **kwB)["g_in"]   # [T_out,B,Ca,Ho/2,Wo/2]
+    assert np.allclose(routed.reshape(T_out, B, Ca, Ho // 2, 2, Wo // 2, 2).sum(axis=(4, 6)), at_pooled, rtol=1e-12, atol=1e-14)
+    ref = oracle.conv_lif_backward(s, wA.astype(np.float64), v_preA, routed, **kwA)
+    got = api.tac_conv_lif_backward(desc, sp, wd, vt, torch.from_numpy(at_pooled.astype(np.float32)).to(DEV))
+    torch.cuda.synchronize()
+    _close("dL/dY", got["grad_y"].cpu().numpy(), ref["dY"], 3e-4)
+    _close("dW", got["grad_w"].cpu().numpy(), ref["dW"], TOL_BF16)
+    _close("dL/dS", got["grad_in"].cpu().numpy(), ref["g_in"], TOL_BF16)
