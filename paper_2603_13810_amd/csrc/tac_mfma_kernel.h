@@ -105,7 +105,6 @@ struct Geo {
   __host__ __device__ static constexpr int col(int xp) { return S == 1 ? xp : (xp & 1) * kXH + (xp >> 1); }
   // the loader pipeline has kSteps + 2 slots (slot i reads the words of step i, looks up step
   // i-1 and writes step i-2), spread over the 8 filter taps in front of the workgroup barrier
-  static constexpr int kSlotsPerTap = (kSteps + 2 + 7) / 8;
 };
 
 // Computed afresh wherever it is needed (from an opaque copy of the lane id), so that it does
@@ -608,10 +607,24 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
 
   const int w_frag_off = lane * 16;                                  // + tap*kWTap + mc*1024
 
-  // MFMA operand fragments, two slots: tap t multiplies slot t & 1 while slot (t+1) & 1 is
-  // being fetched; tap 8 fetches the next chunk's tap-0 fragments into slot 1, which the next
-  // chunk starts by moving to slot 0
-  bf16x8 wf[2][MC], af[2][NP];
+  // MFMA operand fragments are fetched kAhead taps before the tap that multiplies them.  One tap ahead (tiles with at
+  // least four MFMAs per tap), two slots: tap t multiplies slot t & 1 while slot (t+1) & 1 is being fetched; tap 8
+  // fetches the next chunk's tap-0 fragments into slot 1, which the next chunk starts by moving to slot 0.  Two taps
+  // ahead (tiles with two MFMAs per tap, whose single tap is shorter than an LDS read takes), three slots: tap t
+  // multiplies slot t % 3 while slot (t+2) % 3 is being fetched; nine taps are three rounds of the ring, so the next
+  // chunk finds its taps 0 and 1 in slots 0 and 1.
+  constexpr int kAhead = (MC * NP <= 2 && !AGG) ? 2 : 1;
+  constexpr int kBarTap = 8 - kAhead;            // the workgroup barrier follows this tap
+  // Loader slots per tap and the distance, in slots, between the three stages of the loader's pipeline (read the
+  // words of a step, look its table entries up, write its aggregates): one tap, so that no stage waits for an LDS
+  // access issued in the same tap.  All writes are done by the barrier.
+  constexpr int kSPT = [] {
+    for (int n = 1;; ++n)
+      if ((kBarTap + 1) * n >= G::kSteps + (KT == 1 ? 1 : 2) * n) return n;
+  }();
+  constexpr int kLD = kSPT;                      // slots between the stages
+  constexpr int kSets = 2 * kLD + 1;             // register sets in flight
+  bf16x8 wf[kAhead + 1][MC], af[kAhead + 1][NP];
   auto fetch = [&](const uint8_t* a_buf, const uint8_t* w_buf, int tap, int slot) {
     if constexpr (AGG) return;
     const int ky = tap / 3, kx = tap % 3;
@@ -623,14 +636,19 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
     for (int np = 0; np < NP; ++np)
       af[slot][np] = *reinterpret_cast<const bf16x8*>(a_buf + a_frag_off[np] + tap_off);
   };
-  fetch(lds + G::kLdsA, lds + G::kLdsW, 0, 1);
+  if constexpr (kAhead == 1) {
+    fetch(lds + G::kLdsA, lds + G::kLdsW, 0, 1);
+  } else {
+    fetch(lds + G::kLdsA, lds + G::kLdsW, 0, 0);
+    fetch(lds + G::kLdsA, lds + G::kLdsW, 1, 1);
+  }
 
   // One chunk of 16 input channels: 9 taps of MFMAs on buffers PAR, while the A tile of the
-  // next chunk is built in buffers PAR^1.  The workgroup barrier sits between tap 7 and tap 8:
-  // by then every read of the PAR buffers has returned (tap 8's fragments are fetched during
-  // tap 7) and every write to the PAR^1 buffers is done, so tap 8 already fetches the first
-  // fragments of the next chunk and starts refilling the PAR weight buffer.
-  static_assert(8 * G::kSlotsPerTap >= G::kSteps + 2, "the loader must be done before the barrier");
+  // next chunk is built in buffers PAR^1.  The workgroup barrier sits behind tap kBarTap (7, or 6 with two taps of
+  // look-ahead): by then every read of the PAR buffers has returned (the last taps' fragments have been fetched)
+  // and every write to the PAR^1 buffers is done, so the taps behind it already fetch the first fragments of the
+  // next chunk and start refilling the PAR weight buffer.
+  static_assert((kBarTap + 1) * kSPT >= G::kSteps + 2 * kLD, "the loader must be done before the barrier");
   auto chunk_iteration = [&](int s) {
     const int PAR = s & 1;
     const uint8_t* a_cur = lds + G::kLdsA + PAR * G::kABuf;
@@ -638,53 +656,77 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
     uint8_t* a_next = lds + G::kLdsA + (PAR ^ 1) * G::kABuf;
     uint8_t* w_next = lds + G::kLdsW + (PAR ^ 1) * kWBufL;
     const uint8_t* words_next = words0 + (PAR ^ 1) * words_bytes;    // words of chunk s+1 (read now)
-    uint8_t* words_nn = words0 + PAR * words_bytes;                  // words of chunk s+2 (written at tap 7)
-    StepRegs<(KT > 0 ? KT : 1)> sr[2];      // loader step i uses set i & 1
+    uint8_t* words_nn = words0 + PAR * words_bytes;                  // words of chunk s+2 (written at tap kBarTap)
+    StepRegs<(KT > 0 ? KT : 1)> sr[kSets];  // loader step i uses set i % kSets
+    if constexpr (kAhead == 1) {
 #pragma unroll
-    for (int mc = 0; mc < MC; ++mc) wf[0][mc] = wf[1][mc];
+      for (int mc = 0; mc < MC; ++mc) wf[0][mc] = wf[1][mc];
 #pragma unroll
-    for (int np = 0; np < NP; ++np) af[0][np] = af[1][np];
-    // Loader pipeline: slot i reads the words of step i into register set i & 1, looks up the table entries of step
-    // i-1 in the other set and writes step i-2 (one frame: no table, the write follows the read by one slot).  With
-    // one slot per tap the slot's LDS reads come first in the tap's instruction stream and its write last, so that
-    // what a tap reads from LDS has returned long before the next tap uses it; with several slots per tap they run
-    // one after the other (a slot's look-up must not overtake the write of the slot before).
+      for (int np = 0; np < NP; ++np) af[0][np] = af[1][np];
+    }
+    // Loader pipeline: slot i reads the words of step i into register set i % kSets, looks up the table entries of
+    // step i - kLD and writes the aggregates of step i - 2 kLD (one frame: no table, the write follows the read by kLD
+    // slots).  With one slot per tap the slot's LDS reads come first in the tap's instruction stream and its write
+    // last; with several slots per tap they run one after the other.
     auto loader_reads = [&](int i) {
       if constexpr (KT > 0) {
-        constexpr int kD = KT == 1 ? 1 : 2;
-        if (i < G::kSteps) read_words<G, KT>(sr[i & 1], words_next, lane, q, i);
-        if (kD == 2 && i >= 1 && i - 1 < G::kSteps) lookup<KT>(sr[(i - 1) & 1], lut, lane);
+        if (i < G::kSteps) read_words<G, KT>(sr[i % kSets], words_next, lane, q, i);
+        if (KT != 1 && i >= kLD && i - kLD < G::kSteps) lookup<KT>(sr[(i - kLD) % kSets], lut, lane);
       }
     };
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) {
-      const int slot = tap & 1;
+      const int slot = kAhead == 1 ? (tap & 1) : tap % 3;
       // Global loads are dealt out over the taps, a few per tap, so that the wave never
       // stalls on a full memory-instruction queue.  The weight buffer of this chunk is free
-      // after the barrier: tap 8 starts refilling it for chunk s+2 (blocks 0,1) and taps 0..5
-      // of the next chunk finish that (blocks 2..8).  Staged words likewise: part 0 at tap 8
-      // (for chunk s+3), parts 1..5 at taps 0..4 (for chunk s+2, written to LDS at tap 7).
+      // after the barrier: the taps behind it start refilling it for chunk s+2 and the first taps
+      // of the next chunk finish that.  Staged words likewise: the first parts behind the barrier
+      // (for chunk s+3), the others in the first taps of the next chunk (for chunk s+2 then, written to LDS
+      // at tap kBarTap).
       constexpr int kLPT = (NG * KMAX + 5) / 6;  // staged words requested per part
-      if (tap == 8) {
-        weights_to_lds(w_n2, const_cast<uint8_t*>(w_cur), c0, c2);
-        __builtin_amdgcn_sched_barrier(0);
-        stage_load<KMAX, NG, MP, G::kWW>(wd, plan, cur.spk, fstride, K, 0, kLPT);
-        if constexpr (G::kSlotsPerTap == 1) loader_reads(tap);
-        fetch(a_next, w_next, 0, slot ^ 1);
-      } else {
-        if (tap <= 5) {
-          switch (tap) {
-            case 0: weights_to_lds(w_n1, w_next, c2, c4); break;
-            case 1: weights_to_lds(w_n1, w_next, c4, c5); break;
-            case 2: weights_to_lds(w_n1, w_next, c5, c6); break;
-            case 3: weights_to_lds(w_n1, w_next, c6, c7); break;
-            case 4: weights_to_lds(w_n1, w_next, c7, c8); break;
-            default: weights_to_lds(w_n1, w_next, c8, c9); break;
+      if constexpr (kAhead == 1) {
+        if (tap == 8) {
+          weights_to_lds(w_n2, const_cast<uint8_t*>(w_cur), c0, c2);
+          __builtin_amdgcn_sched_barrier(0);
+          stage_load<KMAX, NG, MP, G::kWW>(wd, plan, cur.spk, fstride, K, 0, kLPT);
+          if constexpr (kSPT == 1) loader_reads(tap);
+          fetch(a_next, w_next, 0, slot ^ 1);
+        } else {
+          if (tap <= 5) {
+            switch (tap) {
+              case 0: weights_to_lds(w_n1, w_next, c2, c4); break;
+              case 1: weights_to_lds(w_n1, w_next, c4, c5); break;
+              case 2: weights_to_lds(w_n1, w_next, c5, c6); break;
+              case 3: weights_to_lds(w_n1, w_next, c6, c7); break;
+              case 4: weights_to_lds(w_n1, w_next, c7, c8); break;
+              default: weights_to_lds(w_n1, w_next, c8, c9); break;
+            }
+            if (tap <= 4) stage_load<KMAX, NG, MP, G::kWW>(wd, plan, spk_n2, fstride, K, (tap + 1) * kLPT, (tap + 2) * kLPT);
           }
-          if (tap <= 4) stage_load<KMAX, NG, MP, G::kWW>(wd, plan, spk_n2, fstride, K, (tap + 1) * kLPT, (tap + 2) * kLPT);
+          if constexpr (kSPT == 1) loader_reads(tap);
+          fetch(a_cur, w_cur, tap + 1, slot ^ 1);
         }
-        if constexpr (G::kSlotsPerTap == 1) loader_reads(tap);
-        fetch(a_cur, w_cur, tap + 1, slot ^ 1);
+      } else {
+        // two taps of look-ahead: barrier behind tap 6; taps 7 and 8 belong to the next chunk's preparation
+        switch (tap) {
+          case 7: weights_to_lds(w_n2, const_cast<uint8_t*>(w_cur), c0, c2); break;
+          case 8: weights_to_lds(w_n2, const_cast<uint8_t*>(w_cur), c2, c4); break;
+          case 0: weights_to_lds(w_n1, w_next, c4, c5); break;
+          case 1: weights_to_lds(w_n1, w_next, c5, c6); break;
+          case 2: weights_to_lds(w_n1, w_next, c6, c7); break;
+          case 3: weights_to_lds(w_n1, w_next, c7, c8); break;
+          case 4: weights_to_lds(w_n1, w_next, c8, c9); break;
+          default: break;
+        }
+        // a chunk of these tiles is shorter than a trip to HBM: all staged words are requested right behind the
+        // barrier, a whole chunk before they are written to LDS
+        if (tap == 7) {
+          __builtin_amdgcn_sched_barrier(0);
+          stage_load<KMAX, NG, MP, G::kWW>(wd, plan, cur.spk, fstride, K);
+        }
+        if constexpr (kSPT == 1) loader_reads(tap);
+        if (tap + 2 <= 8) fetch(a_cur, w_cur, tap + 2, (tap + 2) % 3);
+        else fetch(a_next, w_next, tap + 2 - 9, (tap + 2) % 3);
       }
       if constexpr (!AGG) {
 #pragma unroll
@@ -696,21 +738,21 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
       // the tile built during the last chunk repeats that chunk (nothing follows it) and is not counted
       uint64_t* const agg_s = (AGG && s + 1 < total) ? agg : nullptr;
 #pragma unroll
-      for (int i = tap * G::kSlotsPerTap; i < (tap + 1) * G::kSlotsPerTap; ++i) {
+      for (int i = tap * kSPT; i < (tap + 1) * kSPT; ++i) {
         if constexpr (KT > 0) {
-          constexpr int kD = KT == 1 ? 1 : 2;
-          if constexpr (G::kSlotsPerTap > 1) loader_reads(i);
-          if (i >= kD && i - kD < G::kSteps) write_a<G, KT>(sr[(i - kD) & 1], a_next, lane, q, i - kD, agg_s);
+          constexpr int kD = (KT == 1 ? 1 : 2) * kLD;
+          if constexpr (kSPT > 1) loader_reads(i);
+          if (i >= kD && i - kD < G::kSteps) write_a<G, KT>(sr[(i - kD) % kSets], a_next, lane, q, i - kD, agg_s);
         } else {
           if (i < G::kSteps) expand_step<G, KT>(p, words_next, lut, a_next, K, lane, q, i, agg_s);
         }
       }
-      if (tap == 7) stage_store<KT, KMAX, NG, MP>(wd, plan, words_nn, K);
+      if (tap == kBarTap) stage_store<KT, KMAX, NG, MP>(wd, plan, words_nn, K);
       if constexpr (KT > 0 && !AGG) {
         // issue order inside the tap: one MFMA, then a few LDS reads and vector ops that run
         // while the matrix pipe is busy, eight times over
-        constexpr int kValuPerMfma = (KT == 16 ? 4 : 2) * G::kSlotsPerTap;
-        constexpr int kDsPerMfma = (G::kSlotsPerTap == 1 && KT != 16) ? 2 : 3;
+        constexpr int kValuPerMfma = (KT == 16 ? 4 : 2) * kSPT;
+        constexpr int kDsPerMfma = (kSPT == 1 && KT != 16) ? 2 : 3;
 #pragma unroll
         for (int i = 0; i < NP * MC; ++i) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -719,7 +761,7 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
         }
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (tap == 7) {
+      if (tap == kBarTap) {
         lds_dma_wait();                         // this wave's part of the next chunk's weights
         lds_barrier();
         __builtin_amdgcn_sched_barrier(0);
