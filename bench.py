@@ -119,6 +119,23 @@ def roofline_entry(bound, flops, bytes_, kern_ms, **extra):
     return d
 
 
+def measure_mfma_loop(iterations=2000, launches=8):
+    """TFLOP/s of tac_mfma_probe: a few launches to bring the clock where it settles, then timed ones."""
+    import torch
+    from paper_2603_13810_amd import api
+    sums, flop = api.tac_mfma_probe(iterations)
+    for _ in range(launches):
+        api.tac_mfma_probe(iterations, sums)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(launches):
+        api.tac_mfma_probe(iterations, sums)
+    b.record()
+    torch.cuda.synchronize()
+    return flop * launches / (a.elapsed_time(b) * 1e-3) / 1e12
+
+
 def time_calls(fn, steps, warmup):
     """fn() enqueues one step on torch's current stream (the stream the library is given).  Returns
     (wall ms per step, mean HIP-event ms per step)."""
@@ -348,6 +365,13 @@ def main():
                               if (B == wl.B and rate == wl.rate and PREC == api.TAC_BF16) else None,
                               kernel_ms=round(head["kernel_ms"], 4), algorithmic_bytes=alg_bytes,
                               conv_tflops=round(head["tflops"], 2))
+
+    if bound == "mfma":
+        # the matrix cores alone (nothing but MFMAs, one wave per SIMD, operands like this layer's): the rate the chip
+        # sustains at the clock it holds under that load, the practical ceiling of the convolution stage
+        loop = measure_mfma_loop()
+        roofline["mfma_loop_tflops"] = round(loop, 1)
+        roofline["frac_of_mfma_loop"] = round(head["tflops"] / loop, 4)
 
     cpu, parity = None, None
     if not args.no_cpu:

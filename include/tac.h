@@ -194,6 +194,18 @@ int tac_fold_batchnorm(const float* w_oihw, const float* bias, const float* gamm
 size_t tac_aggregate_tiles(const tac_layer_desc_t* desc);
 int tac_aggregate_sums(const tac_layer_desc_t* desc, const void* input, uint64_t* tile_sums, void* stream);
 
+/* The matrix cores alone, for measuring the ceiling of the convolution stage (Sec. 3.1: the convolution is a dense
+ * GEMM and dominates the layer): tac_mfma_probe_workgroups() workgroups of four waves, one wave per SIMD as in the
+ * layer kernels, each wave issuing `iterations` x 8 independent v_mfma_f32_32x32x16_bf16 and nothing else, on
+ * operands like the layer's (weight-like values against aggregates of four frames at rate 0.1, two thirds of them
+ * zero).  The launch executes workgroups x 4 x iterations x 8 x 32768 FLOP; the caller times it.
+ *   sums  DEVICE, written, float32 [tac_mfma_probe_workgroups() * 256]: per thread the sum of its accumulators (every
+ *         workgroup computes the same values)
+ * Enqueued on `stream`; nothing is allocated or synchronised.  Errors: TAC_ERR_NULL, TAC_ERR_BAD_PARAM
+ * (iterations < 1), TAC_ERR_ALIGN, TAC_ERR_HIP. */
+size_t tac_mfma_probe_workgroups(void);
+int tac_mfma_probe(int32_t iterations, float* sums, void* stream);
+
 /* A stack of conv-LIF layers, each with its own mode and group size (App. B: TAC layers cascade,
  * T -> T / K_1 -> T / (K_1 K_2) ...; TAC-TP layers keep T; Sec. 5.1's networks mix both with
  * pooling between the layers).  Layer l reads what layer l-1 wrote, still packed.  Plain data;

@@ -25,7 +25,7 @@ TAC_MAX_K = 32
 MODE_NAMES = {TAC_PER_STEP: "per_step", TAC_COLLAPSE: "TAC", TAC_PRESERVE: "TAC_TP"}
 
 EXPORTS = ("tac_out_shape", "tac_packed_bytes", "tac_select_kernel", "tac_prepared_weight_bytes",
-           "tac_prepare_weights", "tac_conv_lif", "tac_aggregate_tiles", "tac_aggregate_sums", "tac_pack_spikes", "tac_unpack_spikes", "tac_fold_batchnorm",
+           "tac_prepare_weights", "tac_conv_lif", "tac_aggregate_tiles", "tac_aggregate_sums", "tac_mfma_probe_workgroups", "tac_mfma_probe", "tac_pack_spikes", "tac_unpack_spikes", "tac_fold_batchnorm",
            "tac_stack_check", "tac_stack_forward", "tac_conv_lif_backward", "tac_conv_lif_backward_static", "tac_stack_backward", "tac_get_counters", "tac_reset_counters", "tac_status_string",
            "tac_last_error")
 
@@ -71,6 +71,10 @@ def lib() -> ctypes.CDLL:
         L.tac_aggregate_tiles.restype = ctypes.c_size_t
         L.tac_aggregate_sums.argtypes = [dp, vp, vp, vp]
         L.tac_aggregate_sums.restype = ctypes.c_int
+        L.tac_mfma_probe_workgroups.argtypes = []
+        L.tac_mfma_probe_workgroups.restype = ctypes.c_size_t
+        L.tac_mfma_probe.argtypes = [ctypes.c_int32, vp, vp]
+        L.tac_mfma_probe.restype = ctypes.c_int
         L.tac_pack_spikes.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp]
         L.tac_pack_spikes.restype = ctypes.c_int
         L.tac_unpack_spikes.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp]
@@ -404,6 +408,18 @@ def tac_stack_backward(stack, weights, input, grad_out_last, *, surrogate=TAC_SG
     _check(lib().tac_stack_backward(stack, arr, ctypes.byref(bwd), n, _dev_ptr(input, None, "input"),
                                     _dev_ptr(grad_out_last, torch.float32, "grad_out_last"), _stream(stream)))
     return out
+
+
+def tac_mfma_probe(iterations, sums=None, stream=None):
+    """The matrix cores alone (measurement aid).  Returns (sums, FLOP executed by the launch)."""
+    import torch
+    wg = int(lib().tac_mfma_probe_workgroups())
+    if sums is None:
+        sums = torch.empty((wg, 256), dtype=torch.float32, device="cuda")
+    elif sums.numel() != wg * 256:
+        raise ValueError("sums must have %d elements" % (wg * 256))
+    _check(lib().tac_mfma_probe(int(iterations), _dev_ptr(sums, torch.float32, "sums"), _stream(stream)))
+    return sums, wg * 4 * int(iterations) * 8 * 32768
 
 
 def tac_pack_spikes(dense01, packed=None, stream=None):

@@ -239,6 +239,16 @@ int tac_aggregate_sums(const tac_layer_desc_t* d, const void* input, uint64_t* t
   return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_aggregate_sums");
 }
 
+size_t tac_mfma_probe_workgroups(void) { return tac::mfma_probe_workgroups(); }
+
+int tac_mfma_probe(int32_t iterations, float* sums, void* stream) {
+  if (!sums) return TAC_ERR_NULL;
+  if (iterations < 1) return TAC_ERR_BAD_PARAM;
+  if ((uintptr_t)sums & 3u) return TAC_ERR_ALIGN;
+  hipError_t e = tac::mfma_probe_launch(iterations, sums, (hipStream_t)stream);
+  return e == hipSuccess ? TAC_OK : hip_fail(e, "tac_mfma_probe");
+}
+
 int tac_stack_check(const tac_stack_layer_t* layers, int32_t n_layers, int32_t* bad_layer) {
   if (!layers) return TAC_ERR_NULL;
   if (n_layers < 1) return TAC_ERR_BAD_SHAPE;

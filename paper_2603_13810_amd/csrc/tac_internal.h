@@ -58,6 +58,9 @@ hipError_t mfma_aggregate_w32(const LayerParams& p, uint64_t* tile_sums, hipStre
 bool mfma_aggregate_supported(const tac_layer_desc_t& d);
 size_t mfma_aggregate_tiles(const tac_layer_desc_t& d);
 hipError_t mfma_aggregate_launch(const LayerParams& p, uint64_t* tile_sums, hipStream_t s);
+// the matrix cores alone (measurement aid): 4 workgroups per compute unit, `iterations` x 8 MFMAs per wave
+size_t mfma_probe_workgroups();
+hipError_t mfma_probe_launch(int iterations, float* sums, hipStream_t s);
 // its member for the shapes in between (Cin a multiple of 8 up to 64, widths up to 128, any pool on load)
 bool mfma_mid_supported(const tac_layer_desc_t& d);
 size_t mfma_mid_weight_bytes(const tac_layer_desc_t& d);

@@ -1,5 +1,6 @@
 // Host side of the matrix-core kernel family: which member takes a layer, prepared weights, dispatch to the
 // translation unit that holds the kernels of the layer's geometry (tac_mfma_kernel.h has the kernel itself).
+#include <mutex>
 #include "tac_mfma_common.h"
 
 namespace tac {
@@ -98,6 +99,83 @@ size_t mfma_aggregate_tiles(const tac_layer_desc_t& d) {
 
 hipError_t mfma_aggregate_launch(const LayerParams& p, uint64_t* tile_sums, hipStream_t s) {
   return p.W == 64 ? mfma_aggregate_w64(p, tile_sums, s) : mfma_aggregate_w32(p, tile_sums, s);
+}
+
+// ---- the matrix cores alone (measurement aid) ----------------------------------------------
+// One wave per SIMD, as in the layer kernels, issuing nothing but v_mfma_f32_32x32x16_bf16: eight independent
+// accumulators, eight different operand pairs in turn (weight-like values on one side, aggregate-like values with
+// two thirds of zeros on the other), so that consecutive instructions toggle the multipliers the way the layer's do.
+namespace {
+
+constexpr int kProbeLds = 96 * 1024;            // requested only so that one workgroup owns a compute unit
+
+__device__ __forceinline__ uint32_t probe_hash(uint32_t& h) {
+  h = h * 1664525u + 1013904223u;
+  return h >> 8;
+}
+
+__global__ __launch_bounds__(256, 1) void mfma_probe_kernel(float* __restrict__ sums, int iterations) {
+  const uint32_t lane = threadIdx.x & 63u;
+  bf16x8 a[8], b[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    uint32_t h = lane * 2654435761u + (uint32_t)i * 40503u + 12345u;
+    u32x4 wa, wb;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      // two bf16 patterns per dword.  Weights: sign, exponent 98..101, any mantissa (about 0.01 .. 0.2 times 2^-23).
+      const uint32_t r0 = probe_hash(h), r1 = probe_hash(h);
+      wa[e] = (((r0 & 0x8000u) | 0x3100u | (r0 & 0x01ffu)) & 0xffffu) | ((((r1 & 0x8000u) | 0x3100u | (r1 & 0x01ffu)) & 0xffffu) << 16);
+      // aggregates of four frames at rate 0.1 in the 2^23 scale: zero two times out of three, else 0x4b00 .. 0x4b5f
+      const uint32_t s0 = probe_hash(h), s1 = probe_hash(h);
+      const uint32_t lo = (s0 & 0xffu) < 87u ? 0x4b00u + ((s0 >> 8) % 0x60u) : 0u;
+      const uint32_t hi = (s1 & 0xffu) < 87u ? 0x4b00u + ((s1 >> 8) % 0x60u) : 0u;
+      wb[e] = lo | (hi << 16);
+    }
+    a[i] = __builtin_bit_cast(bf16x8, wa);
+    b[i] = __builtin_bit_cast(bf16x8, wb);
+  }
+  f32x16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+  for (int it = 0; it < iterations; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[i], acc[i], 0, 0, 0);
+  }
+  float t = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t += acc[i][r];
+  sums[(size_t)blockIdx.x * 256 + threadIdx.x] = t;
+}
+
+int probe_compute_units() {
+  static std::once_flag once;
+  static int n = 256;
+  std::call_once(once, [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n = v;
+  });
+  return n;
+}
+
+}  // namespace
+
+size_t mfma_probe_workgroups() { return (size_t)4 * probe_compute_units(); }
+
+hipError_t mfma_probe_launch(int iterations, float* sums, hipStream_t s) {
+  static std::once_flag once;
+  static hipError_t attr = hipSuccess;
+  std::call_once(once, [] {
+    attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma_probe_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kProbeLds);
+  });
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)mfma_probe_workgroups()), dim3(256), kProbeLds, s, sums, iterations);
+  return hipGetLastError();
 }
 
 }  // namespace tac

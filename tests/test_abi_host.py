@@ -250,3 +250,12 @@ def test_pooled_output_validation_and_stack_chaining():
     wrong = _desc(T=api.tac_out_shape(ok)[0], H=16, W=32, Cin=64, Cout=32, precision=api.TAC_BF16)
     arr = (api.tac_stack_layer_t * 2)(a, api.tac_stack_layer_t(desc=wrong))
     assert api.tac_stack_check(arr) == (api.TAC_ERR_BAD_SHAPE, 1)
+
+
+def test_matrix_core_probe_rejects_bad_requests_before_any_launch():
+    L = api.lib()
+    fake = ctypes.c_void_p(0x1000)
+    assert L.tac_mfma_probe(10, None, None) == api.TAC_ERR_NULL
+    assert L.tac_mfma_probe(0, fake, None) == api.TAC_ERR_BAD_PARAM
+    assert L.tac_mfma_probe(10, ctypes.c_void_p(0x1002), None) == api.TAC_ERR_ALIGN
+    assert L.tac_mfma_probe_workgroups() % 4 == 0 and L.tac_mfma_probe_workgroups() > 0

@@ -50,3 +50,19 @@ def test_aggregate_sums_reject_what_the_large_kernel_does_not_take():
         with pytest.raises(api.TacError) as e:
             api.tac_aggregate_sums(d, torch.zeros(12 * 2 * 32 * 16 * 2 * (4 if kw.get("in_format") else 1), dtype=torch.int32, device=DEV))
         assert e.value.status == api.TAC_ERR_UNSUPPORTED
+
+
+def test_matrix_core_probe_runs_and_every_workgroup_computes_the_same():
+    # the measurement aid behind the bench line's "mfma_loop" figures: nothing but MFMAs on fixed operands
+    sums, flop = api.tac_mfma_probe(50)
+    sums2, _ = api.tac_mfma_probe(50)
+    torch.cuda.synchronize()
+    wg = sums.shape[0]
+    assert flop == wg * 4 * 50 * 8 * 32768
+    s = sums.cpu().numpy()
+    assert np.isfinite(s).all() and np.abs(s).max() > 0
+    assert (s == s[0]).all()                       # same operands in every workgroup
+    assert np.array_equal(s, sums2.cpu().numpy())  # and in every launch
+    more, _ = api.tac_mfma_probe(100)
+    torch.cuda.synchronize()
+    assert np.allclose(more.cpu().numpy(), 2 * s, rtol=1e-3)    # twice the iterations accumulate twice the products
