@@ -925,10 +925,12 @@ inline int compute_units() {
 template <int KT, int WIN, int S, bool TRACE, bool MP>
 hipError_t launch_traced(const MfmaParams& mp, hipStream_t s) {
   const int kComputeUnits = compute_units();
-  // TAC-TP with groups of 4 or 8 frames: K LIF steps of pure vector work follow every group's MFMAs, so two
-  // workgroups of 64-channel tiles per compute unit (where two of them fit the LDS) beat one of 128 channels
-  if constexpr (!MP && (KT == 4 || KT == 8) && 2 * Geo<WIN, S>::lds_bytes(KT, 2) <= kLdsLimit) {
-    if (mp.n_lif >= 4 && !mp.out_pool) return launch_tile<KT, WIN, S, TRACE, MP, 2>(mp, s);
+  // Where the LIF steps of a group weigh as much as half its chunks of MFMAs (at least one LIF step per two chunks
+  // of 16 input channels: TAC-TP with groups of 4 or 8 frames on 128 channels, groups of 2 on 64, ..), the steps are
+  // pure vector work that follows every group's MFMAs: two workgroups of 64-channel tiles per compute unit (where two
+  // of them fit the LDS) beat one of 128 channels, one's LIF steps running under the other's MFMAs
+  if constexpr (!MP && KT >= 1 && KT <= 8 && 2 * Geo<WIN, S>::lds_bytes(KT, 2) <= kLdsLimit) {
+    if (mp.n_lif * 32 >= mp.Cin && !mp.out_pool) return launch_tile<KT, WIN, S, TRACE, MP, 2>(mp, s);
   }
   if constexpr (!MP) {
     const int row_tiles = (mp.Ho + Geo<WIN, S>::kTileRows - 1) / Geo<WIN, S>::kTileRows;
