@@ -925,12 +925,15 @@ inline int compute_units() {
 template <int KT, int WIN, int S, bool TRACE, bool MP>
 hipError_t launch_traced(const MfmaParams& mp, hipStream_t s) {
   const int kComputeUnits = compute_units();
-  // Where the LIF steps of a group weigh as much as half its chunks of MFMAs (at least one LIF step per two chunks
-  // of 16 input channels: TAC-TP with groups of 4 or 8 frames on 128 channels, groups of 2 on 64, ..), the steps are
-  // pure vector work that follows every group's MFMAs: two workgroups of 64-channel tiles per compute unit (where two
-  // of them fit the LDS) beat one of 128 channels, one's LIF steps running under the other's MFMAs
+  // The LIF steps of a group are pure vector work that follows the group's MFMAs.  Two workgroups of 64-channel tiles
+  // per compute unit (where two of them fit the LDS) let one's LIF steps run under the other's MFMAs, at the price of
+  // building every aggregate tile twice.  That pays where the steps weigh enough against the chunks of 16 input
+  // channels and the loader is cheap enough: measured on 64 x 64 layers, from one LIF step per eight chunks with
+  // single frames (the per-step layer on 128 channels), per four chunks with groups of two frames, per two chunks with
+  // larger groups (TAC-TP with groups of 4 or 8 on 128 channels).
   if constexpr (!MP && KT >= 1 && KT <= 8 && 2 * Geo<WIN, S>::lds_bytes(KT, 2) <= kLdsLimit) {
-    if (mp.n_lif * 32 >= mp.Cin && !mp.out_pool) return launch_tile<KT, WIN, S, TRACE, MP, 2>(mp, s);
+    constexpr int kChannelsPerStep = KT == 1 ? 128 : (KT == 2 ? 64 : 32);
+    if (mp.n_lif * kChannelsPerStep >= mp.Cin && !mp.out_pool) return launch_tile<KT, WIN, S, TRACE, MP, 2>(mp, s);
   }
   if constexpr (!MP) {
     const int row_tiles = (mp.Ho + Geo<WIN, S>::kTileRows - 1) / Geo<WIN, S>::kTileRows;
