@@ -63,7 +63,12 @@ constexpr int kLdsLimit = 160 * 1024;          // LDS of one compute unit
 // Aggregate table: entry t = the aggregate (Eq. 2) of a pixel whose frames have the bits of t,
 // in the 2^23 fixed-point scale.  K <= 8: 2^K bf16 patterns.  K = 16: two tables of 256
 // integers (frames 0..7, frames 8..15) that are added before the one rounding to bf16.
-__host__ __device__ constexpr int lut_bytes(int K) { return K == 16 ? 2048 : (K >= 2 && K <= 8 ? ((2 << K) + 15) / 16 * 16 : 0); }
+// Pair table (K = 2, and K = 4 where the tile leaves room): entry (t1 << K | t0) holds the bf16 patterns of two
+// neighbouring channels, t0 in the low half: one 32-bit read per channel pair instead of two 16-bit reads and a pack.
+__host__ __device__ constexpr bool lut_pairs(int K, bool room) { return K == 2 || (K == 4 && room); }
+__host__ __device__ constexpr int lut_bytes(int K, bool room) {
+  return lut_pairs(K, room) ? (4 << (2 * K)) : (K == 16 ? 2048 : (K >= 2 && K <= 8 ? ((2 << K) + 15) / 16 * 16 : 0));
+}
 
 // Compile-time geometry of a tile: input width WIN (32 or 64 pixels = 1 or 2 words), stride S,
 // NP blocks of 32 output pixels per wave (2; 1 gives half as high a tile, for layers whose grid
@@ -96,7 +101,9 @@ struct Geo {
   // two weight buffers of 9 taps x MC blocks of one KiB, bias, aggregate table, two staging buffers
   __host__ __device__ static constexpr int lds_bias(int MC) { return kLdsW + 2 * 9 * MC * 1024; }
   __host__ __device__ static constexpr int lds_lut(int MC) { return lds_bias(MC) + kCoutTile * 4; }
-  static constexpr int lds_bytes(int K, int MC = kMC) { return lds_lut(MC) + lut_bytes(K) + 2 * words_bytes(K); }
+  // the pair table of K = 4 (1 KiB) where the largest tile of the geometry still fits with it
+  static constexpr bool kLutRoom = lds_lut(kMC) + 1024 + 2 * words_bytes(4) <= kLdsLimit;
+  static constexpr int lds_bytes(int K, int MC = kMC) { return lds_lut(MC) + lut_bytes(K, kLutRoom) + 2 * words_bytes(K); }
   // behind it, when the output spikes are pooled before they are stored: the exchange area of pooled_store
   // (output rows of 32 or 64 pixels only)
   static constexpr bool kCanPoolOut = S == 1 && kWo >= 32;
@@ -254,9 +261,19 @@ __device__ __forceinline__ void stage_store(const uint32_t (&wd)[NG][KM * (MP ? 
     }
 }
 
-template <int KT>
+template <int KT, bool PAIRS>
 __device__ __forceinline__ void lut_fill(uint8_t* lut, const MfmaParams& p, int tid) {
-  if constexpr (KT >= 2 && KT <= 8) {
+  if constexpr (PAIRS) {
+    for (int t = tid; t < (1 << (2 * KT)); t += kThreads) {
+      uint32_t a0 = 0, a1 = 0;
+#pragma unroll
+      for (int j = 0; j < KT; ++j) {
+        a0 += ((t >> j) & 1) * p.wq[j];
+        a1 += ((t >> (KT + j)) & 1) * p.wq[j];
+      }
+      reinterpret_cast<uint32_t*>(lut)[t] = pack_bf16((float)a0, (float)a1);
+    }
+  } else if constexpr (KT >= 2 && KT <= 8) {
     for (int t = tid; t < (1 << KT); t += kThreads) {
       uint32_t acc = 0;
 #pragma unroll
@@ -315,9 +332,16 @@ __device__ __forceinline__ void read_words(StepRegs<KT>& sr, const uint8_t* word
   }
 }
 
-template <int KT>
+template <int KT, bool PAIRS>
 __device__ __forceinline__ void lookup(StepRegs<KT>& sr, const uint8_t* lut, int lane) {
-  if constexpr (KT >= 2 && KT <= 8) {
+  if constexpr (PAIRS) {
+    const uint32_t pos = lane & 31 & ~(KT - 1);
+#pragma unroll
+    for (int e2 = 0; e2 < 2; ++e2) {
+      const uint32_t t = __builtin_amdgcn_ubfe(sr.cw[2 * e2], pos, KT) | (__builtin_amdgcn_ubfe(sr.cw[2 * e2 + 1], pos, KT) << KT);
+      sr.lv[e2] = reinterpret_cast<const uint32_t*>(lut)[t];
+    }
+  } else if constexpr (KT >= 2 && KT <= 8) {
     const uint32_t pos = lane & 31 & ~(KT - 1);
 #pragma unroll
     for (int e = 0; e < 4; ++e)
@@ -349,7 +373,10 @@ __device__ __forceinline__ void a_write_packed(uint8_t* a_next, int lane, int q,
 template <class G, int KT>
 __device__ __forceinline__ void write_a(const StepRegs<KT>& sr, uint8_t* a_next, int lane, int q, int step, uint64_t* sum = nullptr) {
   u32x2 pk;
-  if constexpr (KT == 1) {
+  if constexpr (lut_pairs(KT, G::kLutRoom)) {
+    pk[0] = sr.lv[0];
+    pk[1] = sr.lv[1];
+  } else if constexpr (KT == 1) {
     // one frame: the aggregate is the bit itself, 2^23 in the fixed-point scale, whose bf16
     // pattern is 0x4b00; two channels per multiplication
     static_assert(kFixShift == 23, "0x4b00 is bf16(2^23)");
@@ -378,7 +405,7 @@ __device__ __forceinline__ void expand_step(const MfmaParams& p, const uint8_t* 
   if constexpr (KT > 0) {
     StepRegs<KT> sr;
     read_words<G, KT>(sr, words_buf, lane, q, step);
-    lookup<KT>(sr, lut, lane);
+    lookup<KT, lut_pairs(KT, G::kLutRoom)>(sr, lut, lane);
     write_a<G, KT>(sr, a_next, lane, q, step, sum);
   } else {
     const uint32_t* src = reinterpret_cast<const uint32_t*>(words_buf) + (lane_word<G>(lane, step) * (K * kChunk + G::stage_pad(K)) + q * 4);
@@ -449,7 +476,7 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
   const int co_wave = co_tile * kCT;
   const int total = p.G * NC;
   uint8_t* const lut = lds + kLdsLut;
-  uint8_t* const words0 = lut + lut_bytes(KT);
+  uint8_t* const words0 = lut + lut_bytes(KT, G::kLutRoom);
   const int words_bytes = G::words_bytes(K);
   const int oy_wave = y0 + wave * G::kWaveRows;                // first output row of this wave
 
@@ -573,7 +600,7 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
   stage_plan<G, NG, MP>(plan, p, K, tid, y0 * S - 1);
   uint32_t wd[NG][KMAX * (MP ? 4 : 1)];         // staged words in flight
   const uint32_t fstride = (uint32_t)((size_t)p.B * p.Cin * in_plane);         // dwords between frames
-  lut_fill<KT>(lut, p, tid);
+  lut_fill<KT, lut_pairs(KT, G::kLutRoom)>(lut, p, tid);
 
   // ---- prologue: A tile of chunk 0, weights of chunks 0 and 1, staged words of chunk 1,
   //      words of chunk 2 in registers
@@ -671,7 +698,7 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
     auto loader_reads = [&](int i) {
       if constexpr (KT > 0) {
         if (i < G::kSteps) read_words<G, KT>(sr[i % kSets], words_next, lane, q, i);
-        if (KT != 1 && i >= kLD && i - kLD < G::kSteps) lookup<KT>(sr[(i - kLD) % kSets], lut, lane);
+        if (KT != 1 && i >= kLD && i - kLD < G::kSteps) lookup<KT, lut_pairs(KT, G::kLutRoom)>(sr[(i - kLD) % kSets], lut, lane);
       }
     };
 #pragma unroll
