@@ -98,12 +98,14 @@ struct Geo {
   static constexpr int kOutWords = (kWo + 31) / 32;          // packed words per output row
   static constexpr int kLdsA = 0;
   static constexpr int kLdsW = kLdsA + 2 * kABuf;
-  // two weight buffers of 9 taps x MC blocks of one KiB, bias, aggregate table, two staging buffers
+  // two weight buffers of 9 taps x MC blocks of one KiB, bias, aggregate table, one staging buffer: a wave stages
+  // the words of the four channels it aggregates itself, so its in-order LDS accesses are all the ordering the
+  // buffer needs (the words of chunk s+2 are written behind the wave's last read of chunk s+1's)
   __host__ __device__ static constexpr int lds_bias(int MC) { return kLdsW + 2 * 9 * MC * 1024; }
   __host__ __device__ static constexpr int lds_lut(int MC) { return lds_bias(MC) + kCoutTile * 4; }
   // the pair table of K = 4 (1 KiB) where the largest tile of the geometry still fits with it
-  static constexpr bool kLutRoom = lds_lut(kMC) + 1024 + 2 * words_bytes(4) <= kLdsLimit;
-  static constexpr int lds_bytes(int K, int MC = kMC) { return lds_lut(MC) + lut_bytes(K, kLutRoom) + 2 * words_bytes(K); }
+  static constexpr bool kLutRoom = lds_lut(kMC) + 1024 + words_bytes(4) <= kLdsLimit;
+  static constexpr int lds_bytes(int K, int MC = kMC) { return lds_lut(MC) + lut_bytes(K, kLutRoom) + words_bytes(K); }
   // behind it, when the output spikes are pooled before they are stored: the exchange area of pooled_store
   // (output rows of 32 or 64 pixels only)
   static constexpr bool kCanPoolOut = S == 1 && kWo >= 32;
@@ -159,12 +161,14 @@ __device__ __forceinline__ void stage_plan(StagePlan<NG>& sp, const MfmaParams& 
   sp.keep = 0;
 #pragma unroll
   for (int l = 0; l < NG; ++l) {
-    const int g = tid + l * kThreads;
+    // wave w stages the four channels it aggregates (cin quad w of the chunk): its staged words are its own
+    const int g = (tid & 63) + l * 64;
     sp.goff[l] = 0;
     sp.lofs[l] = 0xffffffffu;
-    if (g < G::kWordsPerFrame) {
-      const int cin = g / G::kRowWords;
-      const int rw = g - cin * G::kRowWords;                // row * wpr + word
+    if (g < 4 * G::kRowWords) {
+      const int cq = g / G::kRowWords;
+      const int cin = (tid >> 6) * 4 + cq;
+      const int rw = g - cq * G::kRowWords;                 // row * wpr + word
       const int row = rw / G::kWW, word = rw - row * G::kWW;
       const int iy = iy0 + row;
       const int iyc = min(max(iy, 0), p.H - 1);
@@ -477,7 +481,6 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
   const int total = p.G * NC;
   uint8_t* const lut = lds + kLdsLut;
   uint8_t* const words0 = lut + lut_bytes(KT, G::kLutRoom);
-  const int words_bytes = G::words_bytes(K);
   const int oy_wave = y0 + wave * G::kWaveRows;                // first output row of this wave
 
   // zero padding columns (left of pixel 0, right of the last pixel) of both A buffers; they
@@ -620,9 +623,9 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
     w_n1 = cur.w;
     weights_to_lds(cur.w, lds + G::kLdsW + kWBufL, c0, c9);
     stage_load<KMAX, NG, MP, G::kWW>(wd, plan, cur.spk, fstride, K);
-    stage_store<KT, KMAX, NG, MP>(wd, plan, words0 + words_bytes, K);
-    __syncthreads();
+    __syncthreads();                            // the aggregate table
     for (int st = 0; st < G::kSteps; ++st) expand_step<G, KT>(p, words0, lut, lds + G::kLdsA, K, lane, q, st, agg);
+    stage_store<KT, KMAX, NG, MP>(wd, plan, words0, K);
     advance(cur);                               // chunk 2
     w_n2 = cur.w;
     spk_n2 = cur.spk;
@@ -682,8 +685,8 @@ __global__ __launch_bounds__(kThreads, (MC == 2 && NP == 2) ? 2 : 1) void mfma_k
     const uint8_t* w_cur = lds + G::kLdsW + PAR * kWBufL;
     uint8_t* a_next = lds + G::kLdsA + (PAR ^ 1) * G::kABuf;
     uint8_t* w_next = lds + G::kLdsW + (PAR ^ 1) * kWBufL;
-    const uint8_t* words_next = words0 + (PAR ^ 1) * words_bytes;    // words of chunk s+1 (read now)
-    uint8_t* words_nn = words0 + PAR * words_bytes;                  // words of chunk s+2 (written at tap kBarTap)
+    const uint8_t* words_next = words0;          // words of chunk s+1 (read now)
+    uint8_t* words_nn = words0;                  // words of chunk s+2: written at tap kBarTap, behind this chunk's reads
     StepRegs<(KT > 0 ? KT : 1)> sr[kSets];  // loader step i uses set i % kSets
     if constexpr (kAhead == 1) {
 #pragma unroll
@@ -958,7 +961,7 @@ hipError_t launch_traced(const MfmaParams& mp, hipStream_t s) {
   // channels and the loader is cheap enough: measured on 64 x 64 layers, from one LIF step per eight chunks with
   // single frames (the per-step layer on 128 channels), per four chunks with groups of two frames, per two chunks with
   // larger groups (TAC-TP with groups of 4 or 8 on 128 channels).
-  if constexpr (!MP && KT >= 1 && KT <= 8 && 2 * Geo<WIN, S>::lds_bytes(KT, 2) <= kLdsLimit) {
+  if constexpr (!MP && KT >= 1 && 2 * Geo<WIN, S>::lds_bytes(KT, 2) <= kLdsLimit) {
     constexpr int kChannelsPerStep = KT == 1 ? 128 : (KT == 2 ? 64 : 32);
     if (mp.n_lif * kChannelsPerStep >= mp.Cin && !mp.out_pool) return launch_tile<KT, WIN, S, TRACE, MP, 2>(mp, s);
   }
