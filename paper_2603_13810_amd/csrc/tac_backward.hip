@@ -57,58 +57,112 @@ __device__ __forceinline__ float grad_out_at(const BackwardParams& p, size_t n, 
   return f * p.grad_out[step * (n_out >> 2) + ip];
 }
 
-// One thread per output neuron; groups and their LIF steps backwards, c = dL/dV' carried.
+// VEC consecutive neurons of one row as one load or store (VEC = 4: 16 bytes per lane)
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+template <int VEC>
+struct Lanes {
+  float v[VEC];
+};
+template <int VEC>
+__device__ __forceinline__ Lanes<VEC> load_lanes(const float* src) {
+  Lanes<VEC> r;
+  if constexpr (VEC == 4) {
+    const f32x4 t = *reinterpret_cast<const f32x4*>(src);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r.v[e] = t[e];
+  } else {
+    r.v[0] = *src;
+  }
+  return r;
+}
+template <int VEC>
+__device__ __forceinline__ void store_lanes(float* dst, const Lanes<VEC>& a) {
+  if constexpr (VEC == 4)
+    *reinterpret_cast<f32x4*>(dst) = f32x4{a.v[0], a.v[1], a.v[2], a.v[3]};
+  else
+    *dst = a.v[0];
+}
+
+// dL/ds of output step n at the VEC neurons from i on (VEC = 4: unpooled output only)
+template <int VEC>
+__device__ __forceinline__ Lanes<VEC> grad_out_lanes(const BackwardParams& p, size_t n, size_t n_out, size_t i) {
+  if constexpr (VEC == 1) {
+    return Lanes<1>{{grad_out_at(p, n, n_out, i)}};
+  } else {
+    size_t step = n;
+    float f = 1.0f;
+    if (p.go_K > 1) {
+      const int kc = (int)n / p.go_K, j = (int)n - kc * p.go_K;
+      f = (p.go_last && kc == p.go_G - 1) ? p.go_w_last[j] : p.go_w[j];
+      step = (size_t)kc;
+    }
+    Lanes<VEC> g = load_lanes<VEC>(p.grad_out + step * n_out + i);
+    if (p.go_K > 1) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) g.v[e] = f * g.v[e];
+    }
+    return g;
+  }
+}
+
+// One thread per VEC output neurons; the LIF steps backwards, c = dL/dV' carried.  The loads of U steps are issued
+// together, only the chain through c is serial.  dL/dY_k is the sum of dL/dV over the LIF steps of group k (one step,
+// or the group's frames with TAC-TP).
+template <int VEC, int U>
 __global__ __launch_bounds__(kThreads) void lif_backward_kernel(const BackwardParams p) {
   const size_t n_out = (size_t)p.B * p.Cout * p.Ho * p.Wo;
-  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  const size_t i = ((size_t)blockIdx.x * kThreads + threadIdx.x) * VEC;
   if (i >= n_out) return;
-  float c = 0.0f;
-  size_t n = (size_t)p.n_steps;
-  if (p.mode != TAC_PRESERVE) {
-    // one step per group: the loads of four groups are issued together, only the chain through c is serial
-    int k = p.G - 1;
-    for (; k >= 3; k -= 4) {
-      float v[4], g[4];
+  float c[VEC], acc[VEC];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        v[u] = p.v_trace[(n - 1 - u) * n_out + i];
-        g[u] = grad_out_at(p, n - 1 - u, n_out, i);
-      }
+  for (int e = 0; e < VEC; ++e) c[e] = acc[e] = 0.0f;
+  int n = p.n_steps;
+  int k = p.G - 1;
+  auto lif_steps = [&](int kk) { return p.mode == TAC_PRESERVE ? group_frames(p, kk) : 1; };
+  auto decay_of = [&](int kk) {
+    return p.mode == TAC_COLLAPSE ? (group_frames(p, kk) == p.K ? p.decay_full : p.decay_last) : p.beta;
+  };
+  int j = lif_steps(k) - 1;                     // LIF step within the group
+  float decay = decay_of(k);
+  bool first = true;                            // first step of the group (in this order)
+  while (n > 0) {
+    const int m = min(U, n);
+    Lanes<VEC> v[U], g[U];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int Kg = group_frames(p, k - u);
-        const float decay = p.mode == TAC_COLLAPSE ? (Kg == p.K ? p.decay_full : p.decay_last) : p.beta;
-        const float sg = surrogate(p.surrogate, p.alpha, v[u] - p.theta);
-        const float gv = g[u] * sg + c * (p.detach_reset ? 1.0f : 1.0f - p.theta * sg);
-        p.grad_y[(size_t)(k - u) * n_out + i] = gv;
-        c = decay * gv;
+    for (int u = 0; u < U; ++u) {
+      if (u < m) {
+        v[u] = load_lanes<VEC>(p.v_trace + (size_t)(n - 1 - u) * n_out + i);
+        g[u] = grad_out_lanes<VEC>(p, (size_t)(n - 1 - u), n_out, i);
       }
-      n -= 4;
     }
-    for (; k >= 0; --k) {
-      --n;
-      const int Kg = group_frames(p, k);
-      const float decay = p.mode == TAC_COLLAPSE ? (Kg == p.K ? p.decay_full : p.decay_last) : p.beta;
-      const float sg = surrogate(p.surrogate, p.alpha, p.v_trace[n * n_out + i] - p.theta);
-      const float gv = grad_out_at(p, n, n_out, i) * sg + c * (p.detach_reset ? 1.0f : 1.0f - p.theta * sg);
-      p.grad_y[(size_t)k * n_out + i] = gv;
-      c = decay * gv;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (u < m) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const float sg = surrogate(p.surrogate, p.alpha, v[u].v[e] - p.theta);
+          const float gv = g[u].v[e] * sg + c[e] * (p.detach_reset ? 1.0f : 1.0f - p.theta * sg);
+          acc[e] = first ? gv : acc[e] + gv;
+          c[e] = decay * gv;
+        }
+        first = false;
+        if (j == 0) {
+          Lanes<VEC> out;
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) out.v[e] = acc[e];
+          store_lanes<VEC>(p.grad_y + (size_t)k * n_out + i, out);
+          --k;
+          if (k >= 0) {
+            j = lif_steps(k) - 1;
+            decay = decay_of(k);
+          }
+          first = true;
+        } else {
+          --j;
+        }
+      }
     }
-    return;
-  }
-  for (int k = p.G - 1; k >= 0; --k) {
-    const int Kg = group_frames(p, k);
-    const int nlif = p.mode == TAC_PRESERVE ? Kg : 1;
-    const float decay = p.mode == TAC_COLLAPSE ? (Kg == p.K ? p.decay_full : p.decay_last) : p.beta;
-    float acc = 0.0f;
-    for (int j = nlif - 1; j >= 0; --j) {
-      --n;
-      const float sg = surrogate(p.surrogate, p.alpha, p.v_trace[n * n_out + i] - p.theta);
-      const float gv = grad_out_at(p, n, n_out, i) * sg + c * (p.detach_reset ? 1.0f : 1.0f - p.theta * sg);
-      acc += gv;
-      c = decay * gv;
-    }
-    p.grad_y[(size_t)k * n_out + i] = acc;
+    n -= m;
   }
 }
 
@@ -301,7 +355,14 @@ size_t backward_wgrad_lds_bytes(int W, int stride) { return (size_t)((kStripRows
 
 hipError_t backward_launch(const BackwardParams& p, hipStream_t s) {
   const size_t n_out = (size_t)p.B * p.Cout * p.Ho * p.Wo;
-  hipLaunchKernelGGL(lif_backward_kernel, dim3((unsigned)((n_out + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, p);
+  // four neurons per thread where rows allow 16-byte accesses (the route through a pooled output is per neuron); with
+  // 16 bytes per lane one step in flight per thread keeps the memory busy, the scalar form asks for four steps at once
+  const bool vec4 = !p.out_pool && n_out % 4 == 0 &&
+                    (((uintptr_t)p.v_trace | (uintptr_t)p.grad_out | (uintptr_t)p.grad_y) & 15) == 0;
+  if (vec4)
+    hipLaunchKernelGGL((lif_backward_kernel<4, 1>), dim3((unsigned)((n_out / 4 + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, p);
+  else
+    hipLaunchKernelGGL((lif_backward_kernel<1, 4>), dim3((unsigned)((n_out + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 
