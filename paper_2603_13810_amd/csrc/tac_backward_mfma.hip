@@ -71,33 +71,36 @@ __global__ __launch_bounds__(kThreads * NCB, (NCB == 1 && XS <= 4) ? 2 : 1) void
     // rows), one column ahead of the MFMAs that use it
     constexpr int CR = R <= 4 ? R : 1;
     f32x4 raw[CR][2];
+    // rows beyond the image (a last, shorter strip): the strip's last row is read in their place (an address inside
+    // the tensor) and the values are replaced by zeros, so that their MFMAs add nothing and no branch is needed
     auto request = [&](int yl, int xs) {
 #pragma unroll
       for (int c = 0; c < CR; ++c) {
-        if (yl + c < rows) {
-          raw[c][0] = *reinterpret_cast<const f32x4*>(dy + (size_t)(yl + c) * p.Wo + xs * 16);
-          raw[c][1] = *reinterpret_cast<const f32x4*>(dy + (size_t)(yl + c) * p.Wo + xs * 16 + 4);
-        }
+        const float* src = dy + (size_t)min(yl + c, rows - 1) * p.Wo + xs * 16;
+        raw[c][0] = *reinterpret_cast<const f32x4*>(src);
+        raw[c][1] = *reinterpret_cast<const f32x4*>(src + 4);
       }
     };
-    auto to_fragment = [&](int c) {
+    auto to_fragment = [&](int c, int yl) {
       const f32x4 g0 = raw[c][0], g1 = raw[c][1];
-      bias_acc += (g0[0] + g0[1]) + (g0[2] + g0[3]) + (g1[0] + g1[1]) + (g1[2] + g1[3]);
-      const u32x4 gp = {pack_bf16(g0[0], g0[1]), pack_bf16(g0[2], g0[3]), pack_bf16(g1[0], g1[1]), pack_bf16(g1[2], g1[3])};
+      const bool inside = yl < rows;
+      const float sum = (g0[0] + g0[1]) + (g0[2] + g0[3]) + (g1[0] + g1[1]) + (g1[2] + g1[3]);
+      bias_acc += inside ? sum : 0.0f;
+      u32x4 gp = {pack_bf16(g0[0], g0[1]), pack_bf16(g0[2], g0[3]), pack_bf16(g1[0], g1[1]), pack_bf16(g1[2], g1[3])};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) gp[e] = inside ? gp[e] : 0u;
       return __builtin_bit_cast(bf16x8, gp);
     };
-    request(0, 0);
-    __syncthreads();                                     // the fragments of the strip before have been read
-    // ---- aggregates of 32 channels x (R + 2) rows, a thread per (channel, row, word of 32 pixels): the
-    //      34 sums x = 32 wi - 1 .. 32 wi + 32 in 2^-23 fixed point (as the forward kernels form them),
-    //      written as blocks of eight for kx = 0, 1, 2
     constexpr int WWI = W >= 32 ? W / 32 : 1;            // words per row
     constexpr int XBW = W >= 32 ? 4 : XB;                // blocks of 8 pixels per word
     const size_t fstride = (size_t)p.B * p.Cin * p.H * p.Wwi;
     // Without the pool the frame words travel global -> LDS without passing through registers, four frames of a
     // group at a time (staging area behind the aggregates: [pass][frame][thread]): one wait for global memory per
-    // four frames instead of one per frame, and for groups of up to four frames one for all passes together.  A
-    // thread's left and right neighbour words are those of the threads next to it (same wave).
+    // four frames instead of one per frame.  The first four frames of all passes are asked for here, before the
+    // barrier (nobody reads the staging area during the MFMAs of the item before).  A thread's left and right
+    // neighbour words are those of the threads next to it (same wave).  The loads are lds_dma4 (assembly): with the
+    // compiler's own direct-to-LDS load it waits for every outstanding load, the dY values included, before each LDS
+    // read that follows.
     constexpr int kPasses = (32 * NCB * rows_in * WWI + NT - 1) / NT;
     uint8_t* const stage = lds + NCB * 3 * copy_bytes;
     auto stage_request = [&](int pass, int j0) {
@@ -105,20 +108,24 @@ __global__ __launch_bounds__(kThreads * NCB, (NCB == 1 && XS <= 4) ? 2 : 1) void
       const int wi = e % WWI, cr = e / WWI;
       const int ci = cr % (32 * NCB), iy = y0 - 1 + cr / (32 * NCB);
       if (e < 32 * NCB * rows_in * WWI && iy >= 0 && iy < p.H) {
-        const uint32_t* src = p.spikes + ((size_t)k * p.K * p.B + b) * p.Cin * p.H * p.Wwi + ((size_t)(ci0 + ci) * p.H + iy) * p.Wwi + wi;
+        // wave-uniform address of the (frame, sample) block + the lane's byte offset in it (32 bits: one register)
+        const uint32_t* sbase = p.spikes + ((size_t)k * p.K * p.B + b) * p.Cin * p.H * p.Wwi;
+        const uint32_t voff = (uint32_t)((((ci0 + ci) * p.H + iy) * p.Wwi + wi) * 4);
 #pragma unroll
         for (int u = 0; u < 4; ++u)
           if (j0 + u < Kg)
-            __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (size_t)(j0 + u) * fstride),
-                                             (lds_void_ptr)(stage + ((pass * 4 + u) * NT + wave * 64) * 4), 4, 0, 0);
+            lds_dma4(voff, sbase + (size_t)(j0 + u) * fstride, (uint32_t)(uintptr_t)(lds_void_ptr)(stage + ((pass * 4 + u) * NT + wave * 64) * 4));
       }
     };
     if constexpr (!POOL) {
-      if (Kg <= 4) {
 #pragma unroll
-        for (int pass = 0; pass < kPasses; ++pass) stage_request(pass, 0);
-      }
+      for (int pass = 0; pass < kPasses; ++pass) stage_request(pass, 0);
     }
+    request(0, 0);
+    __syncthreads();                                     // the fragments of the strip before have been read
+    // ---- aggregates of 32 channels x (R + 2) rows, a thread per (channel, row, word of 32 pixels): the
+    //      34 sums x = 32 wi - 1 .. 32 wi + 32 in 2^-23 fixed point (as the forward kernels form them),
+    //      written as blocks of eight for kx = 0, 1, 2
     for (int pass = 0; pass < kPasses; ++pass) {
       const int e = tid + pass * NT;
       if (e >= 32 * NCB * rows_in * WWI) break;
@@ -130,7 +137,7 @@ __global__ __launch_bounds__(kThreads * NCB, (NCB == 1 && XS <= 4) ? 2 : 1) void
       for (int i = 0; i < 34; ++i) q[i] = 0u;
       if constexpr (!POOL) {
         for (int j0 = 0; j0 < Kg; j0 += 4) {
-          if (Kg > 4) {
+          if (j0 > 0) {
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the reads of the batch before are done
             stage_request(pass, j0);
           }
@@ -198,38 +205,49 @@ __global__ __launch_bounds__(kThreads * NCB, (NCB == 1 && XS <= 4) ? 2 : 1) void
     // ---- MFMAs, column of 16 pixels by column, down the aggregate rows r of the strip: a row's three fragments
     //      (kx = 0, 1, 2) are read once and meet output rows r (ky = 0), r - 1 (ky = 1) and r - 2 (ky = 2), whose dY
     //      fragments are kept in a window of three; the next 16 dY values are requested one step ahead
+    // Straight-line code, no branch between the MFMAs.  A row's MFMAs go tap column by tap column (kx), and as soon
+    // as the last MFMA with a row's kx fragment is issued the next row's fragment of that kx is requested into its
+    // place: six MFMAs pass before it is needed.
+    constexpr int NGF = CR > 1 ? R : 3;                  // dY fragments kept: the whole column, or a window of three rows
+    bf16x8 gf[NGF];
+    bf16x8 af[3];
+    // one address register per kx copy (opaque to the compiler, which would otherwise keep one per row whose offset
+    // does not fit the instruction's 16 bits); row and column are immediate offsets
+    uint32_t a_lane[3];
+#pragma unroll
+    for (int kx = 0; kx < 3; ++kx) {
+      a_lane[kx] = (uint32_t)((cib * 3 + kx) * copy_bytes + (h * 32 + n) * 16);
+      asm volatile("" : "+v"(a_lane[kx]));
+    }
+    auto fetch_af = [&](int r, int xs, int kx) {
+      af[kx] = *reinterpret_cast<const bf16x8*>(lds + a_lane[kx] + (r * XB + 2 * xs) * 512);
+    };
+#pragma unroll
+    for (int kx = 0; kx < 3; ++kx) fetch_af(0, 0, kx);
     static_for<0, XS>([&](auto xs_) {
       constexpr int xs = decltype(xs_)::value;
-      constexpr int NGF = CR > 1 ? R : 3;                // fragments kept: the whole column, or a window of three rows
-      bf16x8 gf[NGF];
       if constexpr (CR > 1) {
 #pragma unroll
-        for (int c = 0; c < CR; ++c)
-          if (c < rows) gf[c] = to_fragment(c);
+        for (int c = 0; c < CR; ++c) gf[c] = to_fragment(c, c);
         if (xs + 1 < XS) request(0, xs + 1);
       }
       static_for<0, R + 2>([&](auto r_) {
         constexpr int r = decltype(r_)::value;
         if constexpr (CR == 1 && r < R) {
-          if (r < rows) {
-            gf[r % 3] = to_fragment(0);
-            if (r + 1 < rows) request(r + 1, xs);
-            else if (xs + 1 < XS) request(0, xs + 1);
-          }
+          gf[r % 3] = to_fragment(0, r);
+          if (r + 1 < R) request(r + 1, xs);
+          else if (xs + 1 < XS) request(0, xs + 1);
         }
-        bf16x8 af[3];
-#pragma unroll
-        for (int kx = 0; kx < 3; ++kx)
-          af[kx] = *reinterpret_cast<const bf16x8*>(lds + (cib * 3 + kx) * copy_bytes + ((r * XB + 2 * xs + h) * 32 + n) * 16);
-        static_for<0, 3>([&](auto ky_) {
-          constexpr int ky = decltype(ky_)::value, yl = r - ky;
-          if constexpr (yl >= 0 && yl < R) {
-            if (yl < rows) {
-#pragma unroll
-              for (int kx = 0; kx < 3; ++kx)
-                acc[ky * 3 + kx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[yl % NGF], af[kx], acc[ky * 3 + kx], 0, 0, 0);
-            }
-          }
+        static_for<0, 3>([&](auto kx_) {
+          constexpr int kx = decltype(kx_)::value;
+          static_for<0, 3>([&](auto ky_) {
+            constexpr int ky = decltype(ky_)::value, yl = r - ky;
+            if constexpr (yl >= 0 && yl < R)
+              acc[ky * 3 + kx] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[yl % NGF], af[kx], acc[ky * 3 + kx], 0, 0, 0);
+          });
+          if constexpr (r + 1 < R + 2) fetch_af(r + 1, xs, kx);
+          else if constexpr (xs + 1 < XS) fetch_af(0, xs + 1, kx);
+          __builtin_amdgcn_sched_barrier(0);             // keeps this order (and the registers it was written for)
         });
       });
     });
@@ -468,7 +486,8 @@ hipError_t backward_dgrad_mfma_launch(const BackwardParams& p, hipStream_t s) {
 
 bool backward_wgrad_mfma_supported(const BackwardParams& p) {
   return p.stride == 1 && (p.W == 16 || p.W == 32 || p.W == 64 || p.W == 128) && p.Cin % 32 == 0 && p.Cout % 128 == 0 &&
-         ((uintptr_t)p.grad_y & 15u) == 0;               // the gradient rows are read 16 bytes at a time
+         ((uintptr_t)p.grad_y & 15u) == 0 &&             // the gradient rows are read 16 bytes at a time
+         (long long)p.Cin * p.H * p.Wwi * 4 < (1ll << 31);  // a frame of one sample is addressed with 32-bit byte offsets
 }
 
 // dW and dbias must have been cleared.

@@ -93,6 +93,11 @@ __device__ __forceinline__ void lds_dma16(const void* gsrc, uint32_t lds_base) {
                  "global_load_lds_dwordx4 %0, off offset:%3"
                  :: "v"(gsrc), "s"(lds_base), "n"(OFF0), "n"(OFF0 + 1024) : "m0", "memory");
 }
+// one dword per lane, from the wave-uniform address sbase plus the lane's byte offset voff: lane l's word goes to
+// lds_base + 4 l
+__device__ __forceinline__ void lds_dma4(uint32_t voff, const void* sbase, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" :: "v"(voff), "s"(sbase), "s"(lds_base) : "m0", "memory");
+}
 #pragma clang diagnostic pop
 __device__ __forceinline__ void lds_dma_wait() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0), other counters untouched
 
