@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kThreads * NCB, (NCB == 1 && XS <= 4) ? 2 : 1) void
   for (int t = 0; t < 9; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-  float bias_acc = 0.0f;
+  float bias_acc[2] = {0.0f, 0.0f};                      // of the channels lane / 4 and 16 + lane / 4 (loading order)
 
   const int items = p.G * p.B * n_strips;
   for (int it = blockIdx.x; it < items; it += n_split) {
@@ -66,7 +66,14 @@ __global__ __launch_bounds__(kThreads * NCB, (NCB == 1 && XS <= 4) ? 2 : 1) void
     const int y0 = strip * R;
     // the wave's first 16 dY values of the strip are requested now and arrive while the aggregates are built
     const int rows = min(R, p.Ho - y0);
-    const float* dy = p.grad_y + (((size_t)k * p.B + b) * p.Cout + co_w + n) * plane + (size_t)y0 * p.Wo + 8 * h;
+    // dY is LOADED four lanes to a channel: lane s reads the 16 bytes s % 4 of the 64 bytes (16 pixels) of channel
+    // s / 4 (load 0) and channel 16 + s / 4 (load 1), so a load instruction touches 16 stretches of 64 bytes.  With
+    // one channel per lane (the MFMA operand's own order) it touches 64 cache lines for the same KiB, the vector
+    // L1 takes them one per cycle, and the kernel spent nearly all its time on that (measured: 98 against 15
+    // cycles per load instruction).  The rounded values are then handed to the lanes of the operand order
+    // (channel n, pixels 8 h .. 8 h + 7) with ds_bpermute, which moves registers between lanes through the LDS
+    // crossbar without touching LDS memory.
+    const float* dy = p.grad_y + (((size_t)k * p.B + b) * p.Cout + co_w + (lane >> 2)) * plane + (size_t)y0 * p.Wo + 4 * (lane & 3);
     // dY is fetched a column of 16 pixels x CR rows at a time (the whole column of the strip when it has at most 4
     // rows), one column ahead of the MFMAs that use it
     constexpr int CR = R <= 4 ? R : 1;
@@ -78,17 +85,31 @@ __global__ __launch_bounds__(kThreads * NCB, (NCB == 1 && XS <= 4) ? 2 : 1) void
       for (int c = 0; c < CR; ++c) {
         const float* src = dy + (size_t)min(yl + c, rows - 1) * p.Wo + xs * 16;
         raw[c][0] = *reinterpret_cast<const f32x4*>(src);
-        raw[c][1] = *reinterpret_cast<const f32x4*>(src + 4);
+        raw[c][1] = *reinterpret_cast<const f32x4*>(src + 16 * plane);
       }
     };
+    // operand lane (n, h) takes its words 0, 1 (pixels 8 h .. 8 h + 3) from loading lane 4 (n % 16) + 2 h and its
+    // words 2, 3 from the lane after it, of load n / 16
+    const int take[2] = {(4 * (n & 15) + 2 * h) * 4, (4 * (n & 15) + 2 * h + 1) * 4};     // byte addresses of ds_bpermute
+    const bool low_channels = n < 16;
     auto to_fragment = [&](int c, int yl) {
-      const f32x4 g0 = raw[c][0], g1 = raw[c][1];
       const bool inside = yl < rows;
-      const float sum = (g0[0] + g0[1]) + (g0[2] + g0[3]) + (g1[0] + g1[1]) + (g1[2] + g1[3]);
-      bias_acc += inside ? sum : 0.0f;
-      u32x4 gp = {pack_bf16(g0[0], g0[1]), pack_bf16(g0[2], g0[3]), pack_bf16(g1[0], g1[1]), pack_bf16(g1[2], g1[3])};
+      uint32_t pk[2][2];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) gp[e] = inside ? gp[e] : 0u;
+      for (int j = 0; j < 2; ++j) {
+        const f32x4 g = raw[c][j];
+        const float sum = (g[0] + g[1]) + (g[2] + g[3]);
+        bias_acc[j] += inside ? sum : 0.0f;
+        pk[j][0] = inside ? pack_bf16(g[0], g[1]) : 0u;
+        pk[j][1] = inside ? pack_bf16(g[2], g[3]) : 0u;
+      }
+      u32x4 gp;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute(take[w >> 1], (int)pk[0][w & 1]);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute(take[w >> 1], (int)pk[1][w & 1]);
+        gp[w] = low_channels ? lo : hi;
+      }
       return __builtin_bit_cast(bf16x8, gp);
     };
     constexpr int WWI = W >= 32 ? W / 32 : 1;            // words per row
@@ -261,8 +282,13 @@ __global__ __launch_bounds__(kThreads * NCB, (NCB == 1 && XS <= 4) ? 2 : 1) void
       atomicAdd(p.grad_w + ((size_t)co * p.Cin + ci0 + 32 * cib + n) * 9 + t, acc[t][r]);
     }
   if (p.grad_bias && blockIdx.z == 0 && cib == 0) {
-    bias_acc += __shfl_down(bias_acc, 32, 64);           // the two pixel halves of a channel
-    if (h == 0) atomicAdd(p.grad_bias + co_w + n, bias_acc);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      float t = bias_acc[j];                             // the four 4-pixel pieces of a channel sit in neighbouring lanes
+      t += __shfl_xor(t, 1, 64);
+      t += __shfl_xor(t, 2, 64);
+      if ((lane & 3) == 0) atomicAdd(p.grad_bias + co_w + 16 * j + (lane >> 2), t);
+    }
   }
 }
 
