@@ -959,10 +959,11 @@ hipError_t launch_traced(const MfmaParams& mp, hipStream_t s) {
   // per compute unit (where two of them fit the LDS) let one's LIF steps run under the other's MFMAs, at the price of
   // building every aggregate tile twice.  That pays where the steps weigh enough against the chunks of 16 input
   // channels and the loader is cheap enough: measured on 64 x 64 layers, from one LIF step per eight chunks with
-  // single frames (the per-step layer on 128 channels), per four chunks with groups of two frames, per two chunks with
-  // larger groups (TAC-TP with groups of 4 or 8 on 128 channels).
+  // single frames (the per-step layer on 128 channels) and with groups of two frames and one step per group (TAC K = 2,
+  // whose pair table makes the loader cheap: 3 % faster on 128 channels), per four chunks with two steps per group of
+  // two frames, per two chunks with larger groups (TAC-TP with groups of 4, 8 or 16 on 128 channels).
   if constexpr (!MP && KT >= 1 && 2 * Geo<WIN, S>::lds_bytes(KT, 2) <= kLdsLimit) {
-    constexpr int kChannelsPerStep = KT == 1 ? 128 : (KT == 2 ? 64 : 32);
+    const int kChannelsPerStep = KT == 1 ? 128 : (KT == 2 ? (mp.n_lif == 1 ? 128 : 64) : 32);
     if (mp.n_lif * kChannelsPerStep >= mp.Cin && !mp.out_pool) return launch_tile<KT, WIN, S, TRACE, MP, 2>(mp, s);
   }
   if constexpr (!MP) {
