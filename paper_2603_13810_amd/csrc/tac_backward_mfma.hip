@@ -10,8 +10,10 @@
 // channels are rebuilt from the packed frames (Eq. 2, rounded to bf16 like the forward pass rounds
 // them) into LDS, three copies shifted by the tap's kx so that every fragment read is an aligned,
 // conflict-free 16 bytes per lane: [kx][row][x / 8][ci][x % 8].  A wave reads its dY rows from
-// global memory, rounds them to bf16 and issues 9 MFMAs (one per tap, 144 accumulator registers)
-// per 16 pixels.  Sums over the slices are combined with float atomics into the cleared dW.
+// global memory (four lanes to a channel's 64 bytes, so that a load covers few cache lines), rounds
+// them to bf16, hands them to the lanes of the MFMA operand order and issues 9 MFMAs (one per tap,
+// 144 accumulator registers) per 16 pixels.  Sums over the slices are combined with float atomics
+// into the cleared dW.
 #include "tac_mfma_common.h"
 
 namespace tac {
