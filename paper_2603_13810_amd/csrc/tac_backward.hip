@@ -57,8 +57,9 @@ __device__ __forceinline__ float grad_out_at(const BackwardParams& p, size_t n, 
   return f * p.grad_out[step * (n_out >> 2) + ip];
 }
 
-// VEC consecutive neurons of one row as one load or store (VEC = 4: 16 bytes per lane)
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// VEC consecutive neurons of one row as one load or store (VEC = 4: 16 bytes per lane)
 template <int VEC>
 struct Lanes {
   float v[VEC];
