@@ -97,6 +97,26 @@ __global__ __launch_bounds__(kThreads) void direct_kernel(const LayerParams p, c
             double ad = 0.0;
             for (int j = 0; j < p.K; ++j) ad = __dadd_rn(ad, __dmul_rn(p.wjd[j], (double)xs[j * ts]));
             a = (float)ad;
+          } else if (p.bf16) {
+            // bf16 operands: the sum over the frames is formed exactly, in the 2^-23 fixed point of the matrix-core
+            // kernels (weights rounded to it once, quarter counts with the mean pool), and rounded once: all bf16
+            // kernels then hand the same A_k to the convolution, and a sum of up to 16 terms does not drift across a
+            // bf16 rounding boundary the way a chain of fp32 additions can
+            const int xs = p.pool2 ? 2 * x : x;       // pooled: both stored columns sit in one word
+            const size_t off = (size_t)(p.pool2 ? 2 * iy : iy) * p.Wwi + (xs >> 5);
+            uint32_t q = 0u;
+            for (int j = 0; j < p.K; ++j) {
+              const uint32_t wq = (uint32_t)(p.wj[j] * 8388608.0f + 0.5f);
+              const uint32_t w0 = src[j * t_stride + off];
+              if (!p.pool2) {
+                q += ((w0 >> (xs & 31)) & 1u) ? 4u * wq : 0u;
+              } else {
+                const uint32_t w1 = src[j * t_stride + off + p.Wwi];
+                if (p.pool2 == 2) q += (((w0 | w1) >> (xs & 31)) & 3u) ? 4u * wq : 0u;      // max pool of bits = OR
+                else q += (uint32_t)(__popc((w0 >> (xs & 31)) & 3u) + __popc((w1 >> (xs & 31)) & 3u)) * wq;
+              }
+            }
+            a = round_bf16((float)q * (1.0f / 33554432.0f));        // quarter units of 2^-23
           } else if (!p.pool2) {
             const size_t off = (size_t)iy * p.Wwi + (x >> 5);
             for (int j = 0; j < p.K; ++j) {
@@ -116,7 +136,7 @@ __global__ __launch_bounds__(kThreads) void direct_kernel(const LayerParams p, c
               }
             }
           }
-          if (p.bf16) a = round_bf16(a);
+          if (p.bf16 && p.dense) a = round_bf16(a);
         }
         a_lds[i] = a;
       }

@@ -201,3 +201,18 @@ def test_real_valued_input_frames(mode, K, precision):
     a = run_gpu(s, w, K=K, beta=0.9, theta=1.0, mode=mode, precision=precision, kernel=api.TAC_KERNEL_DIRECT)
     b = run_gpu(s.astype(np.float32), w, K=K, beta=0.9, theta=1.0, mode=mode, precision=precision, kernel=api.TAC_KERNEL_DIRECT)
     assert np.array_equal(a["packed"], b["packed"]) and np.abs(a["v_trace"] - b["v_trace"]).max() < 1e-5
+
+
+def test_bf16_aggregates_of_sixteen_frames_are_summed_exactly():
+    # With bf16 operands every A_k is rounded once, after the sum over the frames (Eq. 2).  A chain of fp32 additions
+    # over 16 frames can land on the other side of a bf16 rounding boundary than the exact sum does; the membranes
+    # of the 9 x Cout neurons around such an element are then off by one bf16 step of A_k times a weight (this very
+    # input did that: 1399 membranes of the first group off by up to 8e-3).  The kernel therefore sums in the 2^-23
+    # fixed point of the matrix-core kernels and rounds once.  128-pixel rows: the vector kernel takes this shape.
+    r = _rng(1400 + 32 + 128 + 14 + 128 + 16 + 23)
+    s = (r.random((23, 3, 32, 14, 128)) < 0.15).astype(np.uint8)[:16]
+    w = synth.kaiming_normal(43, 128, 32) * np.float32(1.5)
+    bias = (r.standard_normal(128) * 0.1).astype(np.float32)
+    par, g, ref = check_layer(s, w, K=16, beta=0.9, theta=1.0, mode=api.TAC_COLLAPSE, precision=api.TAC_BF16, bias=bias,
+                              v0=np.zeros((3, 128, 14, 128), np.float32), expect_kernel=api.TAC_KERNEL_DIRECT)
+    assert par.max_err < 1e-4, par
