@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kThreads) void direct_kernel(const LayerParams p, c
       __syncthreads();
       // ---- 2. conv: 9 taps x cc channels, CB output channels per lane.  The chunk's terms are summed on their own and
       //      added to the sum of the chunks before: with hundreds of input channels one chain of fp32 additions
-      //      would carry the rounding of every term to the end (measured against the double-precision oracle:
+      //      would carry the rounding of every term to the end (measured against double-precision arithmetic:
       //      up to 5e-5 of the membrane's scale on 136 channels, where the bar is 1e-5)
       float part[CB];
 #pragma unroll
